@@ -1,0 +1,170 @@
+/*
+ * tcgnn.h -- C ABI of the MI355X (gfx950) neighbour-aggregation library.
+ *
+ * The library implements the hot path of TC-GNN (arxiv 2112.02052): the sparse graph
+ * translation (SGT) of a CSR adjacency into per-row-window condensed column tiles, the
+ * SpMM-like neighbour aggregation over the translated graph and the SDDMM-like edge feature
+ * computation, plus the row-wise softmax that an attention-style layer puts between the two.
+ *
+ * General conventions
+ *   - Every pointer whose name starts with d_ is DEVICE memory on the GPU that is current when
+ *     the call is made; every pointer whose name starts with h_ is HOST memory.
+ *   - Every function returns TCG_OK (0) or a negative tcg_status.  No C++ exception crosses
+ *     this boundary.  tcg_strerror() describes a status; after TCG_EHIP it also carries the
+ *     text of the failing HIP call (per thread).
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All kernels are
+ *     enqueued on it and the call returns without waiting, except tcg_sgt_build and
+ *     tcg_sgt_set_policy, which wait for the stream because sizes must reach the host, and
+ *     tcg_sgt_export to host memory.
+ *   - Indices are int32; nnz and the sum of window-unique columns must be below 2^31.
+ *   - The caller owns every array it passes in.  The CSR arrays are BORROWED by the metadata
+ *     object: they must stay alive and unchanged until tcg_sgt_free().
+ *   - A tcg_meta may be used by one call at a time (calls on one stream are ordered and fine;
+ *     concurrent calls on different streams with the same meta race on its scratch buffers).
+ */
+#ifndef TCGNN_H
+#define TCGNN_H
+
+#include <stdint.h>
+
+#if defined(__GNUC__)
+#define TCG_API __attribute__((visibility("default")))
+#else
+#define TCG_API
+#endif
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct tcg_meta tcg_meta; /* opaque; created by tcg_sgt_build, destroyed by tcg_sgt_free */
+
+typedef enum { TCG_F32 = 0, TCG_BF16 = 1, TCG_F16 = 2 } tcg_dtype;
+
+typedef enum {
+    TCG_OK = 0,
+    TCG_EINVAL = -1, /* null pointer, non-positive size, unsupported dtype, ld < D, misalignment */
+    TCG_ECSR = -2,   /* CSR malformed: row_ptr[0] != 0, row_ptr not monotone, row_ptr[n] != nnz,
+                        or a column index outside [0, n_cols)                                  */
+    TCG_ERANGE = -3, /* a size does not fit the int32 index space                               */
+    TCG_ENOMEM = -4, /* host or device allocation failed                                        */
+    TCG_EHIP = -5    /* a HIP runtime call or kernel launch failed                              */
+} tcg_status;
+
+/* Which kernel family a row window is executed by (see tcg_sgt_set_policy). */
+typedef enum {
+    TCG_POLICY_AUTO = 0,   /* per window: condensed-tile MFMA path when it pays, else row gather */
+    TCG_POLICY_GATHER = 1, /* every window on the wavefront row-gather path                      */
+    TCG_POLICY_TILE = 2    /* every non-empty window on the condensed-tile path (needs win_h 16) */
+} tcg_policy;
+
+/*
+ * Sparse Graph Translation -- Algorithm 1 and section 4.1 of the paper.
+ *
+ * Splits the rows into windows of `window_h` consecutive rows (the last one may be shorter).
+ * For each window: the ascending, duplicate-free list of the column ids of its edges
+ * (col_to_row, the text's colToRow); win_partition[w] = ceil(U_w / tile_w) where U_w is that
+ * list's length (0 for a window without edges); edge_to_col[e] = 0-based position of
+ * col_idx[e] in its window's list.  Column ids inside a CSR row may come in any order and may
+ * repeat (repeats share a condensed column and their values add up in tcg_spmm).
+ *
+ * The result is deterministic and equals the sequential algorithm bit for bit.  Alongside it
+ * the call prepares the execution plan used by tcg_spmm / tcg_sddmm (row segments for the
+ * gather path, the per-window path choice of TCG_POLICY_AUTO).
+ *
+ *   n_rows, n_cols  matrix shape (the paper's adjacency is square; nothing here requires it)
+ *   nnz             number of stored entries
+ *   d_row_ptr       device int32[n_rows + 1]   (nodePointer)  borrowed
+ *   d_col_idx       device int32[nnz]          (edgeList)     borrowed
+ *   window_h        rows per window  (TC_BLK_H; the paper uses 16)            >= 1
+ *   tile_w          condensed columns per tile (TC_BLK_W; paper: 8 / 16)      >= 1
+ *   validate        non-zero: check the CSR on the device first (TCG_ECSR on failure);
+ *                   zero: the caller guarantees a well-formed CSR
+ *   out             receives the metadata object; untouched on error
+ * Blocks until the stream has finished the build.
+ */
+TCG_API int tcg_sgt_build(int32_t n_rows, int32_t n_cols, int64_t nnz,
+                  const int32_t *d_row_ptr, const int32_t *d_col_idx,
+                  int32_t window_h, int32_t tile_w, int validate,
+                  void *stream, tcg_meta **out);
+
+/* Sizes of the translated graph.  Any output pointer may be NULL.
+ *   n_windows     ceil(n_rows / window_h)
+ *   total_unique  U = sum over windows of U_w            (length of col_to_row)
+ *   total_tiles   sum of win_partition
+ *   nnz           as given to tcg_sgt_build                                                    */
+TCG_API int tcg_sgt_sizes(const tcg_meta *meta, int64_t *n_windows, int64_t *total_unique,
+                  int64_t *total_tiles, int64_t *nnz);
+
+/*
+ * Copies the canonical metadata into caller-owned buffers (any of them may be NULL to skip):
+ *   win_partition   int32[n_windows]
+ *   win_unique_ptr  int32[n_windows + 1]   offsets of each window's list inside col_to_row
+ *   edge_to_col     int32[nnz]             positionally aligned with col_idx
+ *   col_to_row      int32[total_unique]
+ * dst_on_device != 0: the four pointers are device memory and the copies are asynchronous on
+ * `stream`; otherwise they are host memory and the call returns after the copies completed.
+ */
+TCG_API int tcg_sgt_export(const tcg_meta *meta, int32_t *win_partition, int32_t *win_unique_ptr,
+                   int32_t *edge_to_col, int32_t *col_to_row, int dst_on_device, void *stream);
+
+/*
+ * Chooses which windows run on the condensed-tile (MFMA) path.  TCG_POLICY_AUTO (the state
+ * after tcg_sgt_build) sends a window there when window_h == 16 and its neighbour reuse
+ * nnz_w / U_w is at least `min_reuse` (<= 0 selects the library default); the tile path is only
+ * taken by calls whose X is bf16 or f16, fp32 features always use the gather path.
+ * Blocks until the stream has finished.  Returns TCG_EINVAL for TCG_POLICY_TILE when
+ * window_h != 16.
+ */
+TCG_API int tcg_sgt_set_policy(tcg_meta *meta, tcg_policy policy, float min_reuse, void *stream);
+
+/* Plan statistics.  Any output pointer may be NULL.
+ *   n_tile_windows  windows currently assigned to the condensed-tile path
+ *   nnz_tile        stored entries inside those windows
+ *   n_segments      row segments of the gather plan
+ *   n_long_rows     rows split over several segments                                           */
+TCG_API int tcg_sgt_plan_stats(const tcg_meta *meta, int64_t *n_tile_windows, int64_t *nnz_tile,
+                       int64_t *n_segments, int64_t *n_long_rows);
+
+/*
+ * Neighbour aggregation -- Equation 1 and Algorithm 2 of the paper:  Y = (w (.) A) X.
+ *   Y[i][d] = sum over the stored entries e of row i of  w[e] * X[col_idx[e]][d],  fp32
+ *   accumulation, Y overwritten (rows without entries become 0).
+ *   d_X    device, row-major [n_cols x D], leading dimension ldx (elements), type x_dt
+ *   d_w    device float[nnz] edge values in CSR order, or NULL for all ones
+ *   d_Y    device, row-major [n_rows x D], leading dimension ldy (elements), type y_dt
+ * D >= 1; ldx, ldy >= D.  Any D works; rows whose byte length and stride are multiples of 16
+ * (and a 16-byte aligned base) take the vectorised kernels.  X and Y must not overlap.
+ * May allocate (and keeps) a scratch buffer for rows that are split over several segments.
+ */
+TCG_API int tcg_spmm(tcg_meta *meta, const void *d_X, tcg_dtype x_dt, int32_t D, int64_t ldx,
+             const float *d_w, void *d_Y, tcg_dtype y_dt, int64_t ldy, void *stream);
+
+/*
+ * Edge feature computation -- Equation 2 and Algorithm 3 of the paper:
+ *   d_out[e] = < X[i], X[col_idx[e]] >  for every stored entry e of row i, fp32 accumulation,
+ *   written in CSR (edgeList) order.  Needs a row of X for every row and every column id:
+ *   X is [max(n_rows, n_cols) x D].
+ */
+TCG_API int tcg_sddmm(tcg_meta *meta, const void *d_X, tcg_dtype x_dt, int32_t D, int64_t ldx,
+              float *d_out, void *stream);
+
+/*
+ * Row-wise softmax over the stored entries of each row (the normalisation of the
+ * attention-style workload; not part of the paper's method):
+ *   d_out[e] = exp(d_in[e] - m_i) / sum_{e' in row i} exp(d_in[e'] - m_i),  m_i = row maximum.
+ * In-place (d_out == d_in) is allowed.
+ */
+TCG_API int tcg_row_softmax(const tcg_meta *meta, const float *d_in, float *d_out, void *stream);
+
+/* Releases the metadata object and every device buffer it owns (NULL is a no-op).  The caller
+ * must make sure no kernel using it is still running.                                          */
+TCG_API void tcg_sgt_free(tcg_meta *meta);
+
+/* Text for a status code; valid until the calling thread's next library call.                  */
+TCG_API const char *tcg_strerror(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TCGNN_H */

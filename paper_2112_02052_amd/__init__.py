@@ -1,0 +1,8 @@
+"""MI355X-native neighbour aggregation (SGT + SpMM + SDDMM) -- Python face of libtcgnn.so.
+
+The functions mirror the C ABI in include/tcgnn.h one to one; all computation happens in the
+library's HIP kernels."""
+from .binding import (  # noqa: F401
+    EXPORTED, POLICY_AUTO, POLICY_GATHER, POLICY_TILE, TCG_BF16, TCG_F16, TCG_F32, Meta, TcgError,
+    load_library, row_softmax, sddmm, sgt_build, sgt_export, sgt_plan_stats, sgt_set_policy, spmm,
+)

@@ -1,0 +1,196 @@
+"""Thin ctypes binding of libtcgnn.so (include/tcgnn.h).  Argument marshalling only: every
+step of the path runs in the library's HIP kernels.  torch supplies device memory and the
+current stream; nothing here computes, and there is no CPU fallback -- if the library is
+missing or a call fails, an exception is raised."""
+import ctypes
+import os
+
+import torch
+
+from .build import LIB_PATH
+
+TCG_F32, TCG_BF16, TCG_F16 = 0, 1, 2
+POLICY_AUTO, POLICY_GATHER, POLICY_TILE = 0, 1, 2
+
+EXPORTED = ["tcg_sgt_build", "tcg_sgt_sizes", "tcg_sgt_export", "tcg_sgt_set_policy",
+            "tcg_sgt_plan_stats", "tcg_spmm", "tcg_sddmm", "tcg_row_softmax", "tcg_sgt_free",
+            "tcg_strerror"]
+
+_DTYPES = {torch.float32: TCG_F32, torch.bfloat16: TCG_BF16, torch.float16: TCG_F16}
+
+_vp = ctypes.c_void_p
+_i64p = ctypes.POINTER(ctypes.c_int64)
+_lib = None
+
+
+class TcgError(RuntimeError):
+    def __init__(self, status, text):
+        super().__init__("tcgnn status %d: %s" % (status, text))
+        self.status = status
+
+
+def load_library():
+    """Loads libtcgnn.so; raises if it has not been built (no fallback exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError("libtcgnn.so is not built: run `python -m paper_2112_02052_amd.build` "
+                           "(or __graft_entry__.build()) first")
+    lib = ctypes.CDLL(LIB_PATH)
+    lib.tcg_sgt_build.restype = ctypes.c_int
+    lib.tcg_sgt_build.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int64, _vp, _vp, ctypes.c_int32,
+                                  ctypes.c_int32, ctypes.c_int, _vp, ctypes.POINTER(_vp)]
+    lib.tcg_sgt_sizes.restype = ctypes.c_int
+    lib.tcg_sgt_sizes.argtypes = [_vp, _i64p, _i64p, _i64p, _i64p]
+    lib.tcg_sgt_export.restype = ctypes.c_int
+    lib.tcg_sgt_export.argtypes = [_vp, _vp, _vp, _vp, _vp, ctypes.c_int, _vp]
+    lib.tcg_sgt_set_policy.restype = ctypes.c_int
+    lib.tcg_sgt_set_policy.argtypes = [_vp, ctypes.c_int, ctypes.c_float, _vp]
+    lib.tcg_sgt_plan_stats.restype = ctypes.c_int
+    lib.tcg_sgt_plan_stats.argtypes = [_vp, _i64p, _i64p, _i64p, _i64p]
+    lib.tcg_spmm.restype = ctypes.c_int
+    lib.tcg_spmm.argtypes = [_vp, _vp, ctypes.c_int, ctypes.c_int32, ctypes.c_int64, _vp, _vp, ctypes.c_int,
+                             ctypes.c_int64, _vp]
+    lib.tcg_sddmm.restype = ctypes.c_int
+    lib.tcg_sddmm.argtypes = [_vp, _vp, ctypes.c_int, ctypes.c_int32, ctypes.c_int64, _vp, _vp]
+    lib.tcg_row_softmax.restype = ctypes.c_int
+    lib.tcg_row_softmax.argtypes = [_vp, _vp, _vp, _vp]
+    lib.tcg_sgt_free.restype = None
+    lib.tcg_sgt_free.argtypes = [_vp]
+    lib.tcg_strerror.restype = ctypes.c_char_p
+    lib.tcg_strerror.argtypes = [ctypes.c_int]
+    _lib = lib
+    return lib
+
+
+def _check(status):
+    if status != 0:
+        raise TcgError(status, load_library().tcg_strerror(status).decode())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _ptr(t):
+    return ctypes.c_void_p(t.data_ptr()) if t is not None else ctypes.c_void_p(0)
+
+
+def _need_cuda(*tensors):
+    for t in tensors:
+        if t is not None and not t.is_cuda:
+            raise ValueError("tensors must live on the GPU")
+
+
+class Meta:
+    """Owner of a tcg_meta handle.  Keeps the CSR tensors alive (the library borrows them)."""
+
+    def __init__(self, handle, row_ptr, col_idx, n_rows, n_cols, window_h, tile_w):
+        self._h = handle
+        self.row_ptr, self.col_idx = row_ptr, col_idx
+        self.n_rows, self.n_cols, self.window_h, self.tile_w = n_rows, n_cols, window_h, tile_w
+        nw, u, t, nnz = (ctypes.c_int64() for _ in range(4))
+        _check(load_library().tcg_sgt_sizes(self._h, nw, u, t, nnz))
+        self.n_windows, self.total_unique, self.total_tiles, self.nnz = nw.value, u.value, t.value, nnz.value
+
+    def free(self):
+        if self._h is not None:
+            torch.cuda.synchronize()
+            load_library().tcg_sgt_free(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.free()
+        except Exception:
+            pass
+
+
+def sgt_build(row_ptr, col_idx, window_h=16, tile_w=8, n_cols=None, validate=True):
+    """tcg_sgt_build: row_ptr int32[n_rows+1], col_idx int32[nnz] CUDA tensors."""
+    _need_cuda(row_ptr, col_idx)
+    if row_ptr.dtype != torch.int32 or col_idx.dtype != torch.int32:
+        raise ValueError("CSR arrays must be int32")
+    row_ptr, col_idx = row_ptr.contiguous(), col_idx.contiguous()
+    n_rows = row_ptr.numel() - 1
+    n_cols = n_rows if n_cols is None else int(n_cols)
+    h = ctypes.c_void_p()
+    _check(load_library().tcg_sgt_build(n_rows, n_cols, col_idx.numel(), _ptr(row_ptr), _ptr(col_idx),
+                                        int(window_h), int(tile_w), int(bool(validate)), _stream(),
+                                        ctypes.byref(h)))
+    return Meta(h, row_ptr, col_idx, n_rows, n_cols, int(window_h), int(tile_w))
+
+
+def sgt_export(meta):
+    """tcg_sgt_export into fresh CUDA int32 tensors: dict of the four metadata arrays."""
+    dev = meta.row_ptr.device
+    out = dict(win_partition=torch.empty(meta.n_windows, dtype=torch.int32, device=dev),
+               win_unique_ptr=torch.empty(meta.n_windows + 1, dtype=torch.int32, device=dev),
+               edge_to_col=torch.empty(meta.nnz, dtype=torch.int32, device=dev),
+               col_to_row=torch.empty(meta.total_unique, dtype=torch.int32, device=dev))
+    _check(load_library().tcg_sgt_export(meta._h, _ptr(out["win_partition"]), _ptr(out["win_unique_ptr"]),
+                                         _ptr(out["edge_to_col"]), _ptr(out["col_to_row"]), 1, _stream()))
+    return out
+
+
+def sgt_set_policy(meta, policy, min_reuse=0.0):
+    _check(load_library().tcg_sgt_set_policy(meta._h, int(policy), float(min_reuse), _stream()))
+
+
+def sgt_plan_stats(meta):
+    a, b, c, d = (ctypes.c_int64() for _ in range(4))
+    _check(load_library().tcg_sgt_plan_stats(meta._h, a, b, c, d))
+    return dict(n_tile_windows=a.value, nnz_tile=b.value, n_segments=c.value, n_long_rows=d.value)
+
+
+def _features(meta, X, rows_needed):
+    _need_cuda(X)
+    if X.dim() != 2 or X.dtype not in _DTYPES or X.stride(1) != 1:
+        raise ValueError("X must be a 2-D fp32/bf16/fp16 tensor with unit stride along features")
+    if X.shape[0] < rows_needed:
+        raise ValueError("X has %d rows, the graph needs %d" % (X.shape[0], rows_needed))
+    return X
+
+
+def spmm(meta, X, w=None, Y=None, y_dtype=torch.float32):
+    """tcg_spmm: Y = (w (.) A) X.  Returns Y (allocated here unless given)."""
+    X = _features(meta, X, meta.n_cols)
+    D = X.shape[1]
+    if w is not None:
+        _need_cuda(w)
+        if w.dtype != torch.float32 or w.numel() != meta.nnz or not w.is_contiguous():
+            raise ValueError("w must be a contiguous fp32 tensor with one value per stored entry")
+    if Y is None:
+        Y = torch.empty((meta.n_rows, D), dtype=y_dtype, device=X.device)
+    _need_cuda(Y)
+    if Y.dim() != 2 or Y.shape != (meta.n_rows, D) or Y.stride(1) != 1 or Y.dtype not in _DTYPES:
+        raise ValueError("Y must be [n_rows, D] with unit stride along features")
+    _check(load_library().tcg_spmm(meta._h, _ptr(X), _DTYPES[X.dtype], D, X.stride(0), _ptr(w), _ptr(Y),
+                                   _DTYPES[Y.dtype], Y.stride(0) if meta.n_rows > 1 else max(D, Y.stride(0)),
+                                   _stream()))
+    return Y
+
+
+def sddmm(meta, X, out=None):
+    """tcg_sddmm: out[e] = <X[row(e)], X[col(e)]>, fp32 in CSR order."""
+    X = _features(meta, X, max(meta.n_rows, meta.n_cols))
+    if out is None:
+        out = torch.empty(meta.nnz, dtype=torch.float32, device=X.device)
+    _need_cuda(out)
+    if out.dtype != torch.float32 or out.numel() != meta.nnz or not out.is_contiguous():
+        raise ValueError("out must be a contiguous fp32 tensor with one value per stored entry")
+    _check(load_library().tcg_sddmm(meta._h, _ptr(X), _DTYPES[X.dtype], X.shape[1], X.stride(0), _ptr(out),
+                                    _stream()))
+    return out
+
+
+def row_softmax(meta, v, out=None):
+    """tcg_row_softmax over the stored entries of each row."""
+    _need_cuda(v)
+    if v.dtype != torch.float32 or v.numel() != meta.nnz or not v.is_contiguous():
+        raise ValueError("v must be a contiguous fp32 tensor with one value per stored entry")
+    if out is None:
+        out = torch.empty_like(v)
+    _check(load_library().tcg_row_softmax(meta._h, _ptr(v), _ptr(out), _stream()))
+    return out

@@ -1,0 +1,161 @@
+// The C ABI (include/tcgnn.h): argument checks, object lifetime, export, error text.
+#include "common.h"
+
+#include <stdio.h>
+#include <string.h>
+
+#include <new>
+
+namespace tcg {
+
+static thread_local char g_hip_msg[256] = "";
+static thread_local char g_msg[320] = "";
+
+void set_hip_error(hipError_t e, const char *what)
+{
+    snprintf(g_hip_msg, sizeof(g_hip_msg), "%s: %s", what, hipGetErrorString(e));
+}
+
+static void free_meta(tcg_meta *m)
+{
+    if (!m) return;
+    void *bufs[] = {m->d_win_partition, m->d_win_unique_ptr, m->d_edge_to_col, m->d_col_to_row,
+                    m->d_seg_row,       m->d_seg_ebeg,       m->d_seg_dst,     m->d_long_row,
+                    m->d_long_slot_ptr, m->d_partial,        m->d_win_path};
+    for (void *b : bufs)
+        if (b) (void)hipFree(b);
+    delete m;
+}
+
+}  // namespace tcg
+
+using namespace tcg;
+
+extern "C" {
+
+int tcg_sgt_build(int32_t n_rows, int32_t n_cols, int64_t nnz, const int32_t *d_row_ptr,
+                  const int32_t *d_col_idx, int32_t window_h, int32_t tile_w, int validate, void *stream,
+                  tcg_meta **out)
+{
+    if (!out || !d_row_ptr || n_rows < 0 || n_cols < 0 || nnz < 0 || window_h < 1 || tile_w < 1)
+        return TCG_EINVAL;
+    if (nnz > 0 && !d_col_idx) return TCG_EINVAL;
+    if (nnz >= (int64_t)INT32_MAX || (int64_t)n_rows + 1 >= (int64_t)INT32_MAX) return TCG_ERANGE;
+    tcg_meta *m = new (std::nothrow) tcg_meta();
+    if (!m) return TCG_ENOMEM;
+    if (hipGetDevice(&m->device) != hipSuccess) {
+        delete m;
+        set_hip_error(hipGetLastError(), "hipGetDevice");
+        return TCG_EHIP;
+    }
+    m->n_rows = n_rows;
+    m->n_cols = n_cols;
+    m->nnz = nnz;
+    m->win_h = window_h;
+    m->tile_w = tile_w;
+    m->n_win = ceil_div(n_rows, window_h);
+    m->d_row_ptr = d_row_ptr;
+    m->d_col_idx = d_col_idx;
+    int st = sgt_build_impl(m, validate, static_cast<hipStream_t>(stream));
+    if (st != TCG_OK) {
+        (void)hipStreamSynchronize(static_cast<hipStream_t>(stream));
+        free_meta(m);
+        return st;
+    }
+    *out = m;
+    return TCG_OK;
+}
+
+int tcg_sgt_sizes(const tcg_meta *meta, int64_t *n_windows, int64_t *total_unique, int64_t *total_tiles,
+                  int64_t *nnz)
+{
+    if (!meta) return TCG_EINVAL;
+    if (n_windows) *n_windows = meta->n_win;
+    if (total_unique) *total_unique = meta->total_unique;
+    if (total_tiles) *total_tiles = meta->total_tiles;
+    if (nnz) *nnz = meta->nnz;
+    return TCG_OK;
+}
+
+int tcg_sgt_export(const tcg_meta *meta, int32_t *win_partition, int32_t *win_unique_ptr, int32_t *edge_to_col,
+                   int32_t *col_to_row, int dst_on_device, void *stream)
+{
+    if (!meta) return TCG_EINVAL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const hipMemcpyKind kind = dst_on_device ? hipMemcpyDeviceToDevice : hipMemcpyDeviceToHost;
+    struct Item { void *dst; const void *src; int64_t count; };
+    const Item items[] = {{win_partition, meta->d_win_partition, meta->n_win},
+                          {win_unique_ptr, meta->d_win_unique_ptr, meta->n_win + 1},
+                          {edge_to_col, meta->d_edge_to_col, meta->nnz},
+                          {col_to_row, meta->d_col_to_row, meta->total_unique}};
+    for (const Item &it : items)
+        if (it.dst && it.count > 0)
+            TCG_HIP(hipMemcpyAsync(it.dst, it.src, (size_t)it.count * sizeof(int32_t), kind, s));
+    if (!dst_on_device) TCG_HIP(hipStreamSynchronize(s));
+    return TCG_OK;
+}
+
+int tcg_sgt_set_policy(tcg_meta *meta, tcg_policy policy, float min_reuse, void *stream)
+{
+    if (!meta) return TCG_EINVAL;
+    if (policy != TCG_POLICY_AUTO && policy != TCG_POLICY_GATHER && policy != TCG_POLICY_TILE) return TCG_EINVAL;
+    return choose_paths(meta, policy, min_reuse, static_cast<hipStream_t>(stream));
+}
+
+int tcg_sgt_plan_stats(const tcg_meta *meta, int64_t *n_tile_windows, int64_t *nnz_tile, int64_t *n_segments,
+                       int64_t *n_long_rows)
+{
+    if (!meta) return TCG_EINVAL;
+    if (n_tile_windows) *n_tile_windows = meta->n_tile_win;
+    if (nnz_tile) *nnz_tile = meta->nnz_tile;
+    if (n_segments) *n_segments = meta->n_seg;
+    if (n_long_rows) *n_long_rows = meta->n_long;
+    return TCG_OK;
+}
+
+static bool dtype_ok(int dt) { return dt == TCG_F32 || dt == TCG_BF16 || dt == TCG_F16; }
+
+int tcg_spmm(tcg_meta *meta, const void *d_X, tcg_dtype x_dt, int32_t D, int64_t ldx, const float *d_w,
+             void *d_Y, tcg_dtype y_dt, int64_t ldy, void *stream)
+{
+    if (!meta || D < 1 || ldx < D || ldy < D || !dtype_ok(x_dt) || !dtype_ok(y_dt)) return TCG_EINVAL;
+    if ((!d_X && meta->nnz > 0) || (!d_Y && meta->n_rows > 0)) return TCG_EINVAL;
+    if ((reinterpret_cast<uintptr_t>(d_X) % dtype_size(x_dt)) || (reinterpret_cast<uintptr_t>(d_Y) % dtype_size(y_dt)))
+        return TCG_EINVAL;
+    return spmm_impl(meta, d_X, x_dt, D, ldx, d_w, d_Y, y_dt, ldy, static_cast<hipStream_t>(stream));
+}
+
+int tcg_sddmm(tcg_meta *meta, const void *d_X, tcg_dtype x_dt, int32_t D, int64_t ldx, float *d_out,
+              void *stream)
+{
+    if (!meta || D < 1 || ldx < D || !dtype_ok(x_dt)) return TCG_EINVAL;
+    if (meta->nnz > 0 && (!d_X || !d_out)) return TCG_EINVAL;
+    if (reinterpret_cast<uintptr_t>(d_X) % dtype_size(x_dt)) return TCG_EINVAL;
+    return sddmm_impl(meta, d_X, x_dt, D, ldx, d_out, static_cast<hipStream_t>(stream));
+}
+
+int tcg_row_softmax(const tcg_meta *meta, const float *d_in, float *d_out, void *stream)
+{
+    if (!meta) return TCG_EINVAL;
+    if (meta->nnz > 0 && (!d_in || !d_out)) return TCG_EINVAL;
+    return row_softmax_impl(meta, d_in, d_out, static_cast<hipStream_t>(stream));
+}
+
+void tcg_sgt_free(tcg_meta *meta) { free_meta(meta); }
+
+const char *tcg_strerror(int status)
+{
+    switch (status) {
+    case TCG_OK: return "success";
+    case TCG_EINVAL: return "invalid argument (null pointer, non-positive size, unsupported dtype, ld < D or misaligned pointer)";
+    case TCG_ECSR: return "malformed CSR (row_ptr not monotone from 0 to nnz, or a column index out of range)";
+    case TCG_ERANGE: return "size exceeds the int32 index space";
+    case TCG_ENOMEM: return "out of memory";
+    case TCG_EHIP:
+        snprintf(g_msg, sizeof(g_msg), "HIP error: %s", g_hip_msg[0] ? g_hip_msg : "(no detail recorded)");
+        return g_msg;
+    default: return "unknown status";
+    }
+}
+
+}  // extern "C"

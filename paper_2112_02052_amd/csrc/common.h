@@ -1,0 +1,119 @@
+// Internal declarations shared by the library's translation units (not part of the C ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "tcgnn.h"
+
+namespace tcg {
+
+constexpr int kWave = 64;            // gfx950 wavefront width
+constexpr int kSegLen = 128;         // max edges of one row segment on the gather path
+constexpr float kDefaultMinReuse = 2.0f;
+
+// Records the text of a failing HIP call for tcg_strerror (thread local).
+void set_hip_error(hipError_t e, const char *what);
+
+#define TCG_HIP(call)                                   \
+    do {                                                \
+        hipError_t e_ = (call);                         \
+        if (e_ != hipSuccess) {                         \
+            ::tcg::set_hip_error(e_, #call);            \
+            return TCG_EHIP;                            \
+        }                                               \
+    } while (0)
+
+#define TCG_TRY(call)                                   \
+    do {                                                \
+        int s_ = (call);                                \
+        if (s_ != TCG_OK) return s_;                    \
+    } while (0)
+
+inline int launch_status(const char *what)
+{
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+        set_hip_error(e, what);
+        return TCG_EHIP;
+    }
+    return TCG_OK;
+}
+
+template <typename T>
+int dev_alloc(T **p, int64_t count)
+{
+    *p = nullptr;
+    if (count <= 0) count = 1;       // keep pointers valid for empty graphs
+    hipError_t e = hipMalloc(reinterpret_cast<void **>(p), static_cast<size_t>(count) * sizeof(T));
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        set_hip_error(e, "hipMalloc");
+        *p = nullptr;
+        return TCG_ENOMEM;
+    }
+    return TCG_OK;
+}
+
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// Exclusive prefix sum of n int32 values on the device; out may alias in.  out has n + 1
+// entries: out[n] is the total.  Fails with TCG_ERANGE semantics left to the caller (sums are
+// computed in int32; callers bound the total beforehand).
+int exclusive_scan_i32(const int32_t *d_in, int32_t *d_out, int64_t n, hipStream_t s);
+
+}  // namespace tcg
+
+struct tcg_meta;
+
+namespace tcg {
+
+// sgt.hip
+int sgt_build_impl(tcg_meta *m, int validate, hipStream_t s);
+int choose_paths(tcg_meta *m, tcg_policy policy, float min_reuse, hipStream_t s);
+
+// spmm.hip / sddmm.hip / softmax.hip
+int spmm_impl(tcg_meta *m, const void *d_X, tcg_dtype x_dt, int32_t D, int64_t ldx, const float *d_w,
+              void *d_Y, tcg_dtype y_dt, int64_t ldy, hipStream_t s);
+int sddmm_impl(tcg_meta *m, const void *d_X, tcg_dtype x_dt, int32_t D, int64_t ldx, float *d_out,
+               hipStream_t s);
+int row_softmax_impl(const tcg_meta *m, const float *d_in, float *d_out, hipStream_t s);
+
+// spmm_tile.hip: can the condensed-tile kernels take this operand?
+bool tile_path_supports(tcg_dtype x_dt, int32_t D, int64_t ldx, const void *X);
+
+inline int dtype_size(tcg_dtype t) { return t == TCG_F32 ? 4 : 2; }
+
+}  // namespace tcg
+
+// The metadata object behind the opaque C handle.
+struct tcg_meta {
+    int device = 0;
+    int32_t n_rows = 0, n_cols = 0, win_h = 0, tile_w = 0;
+    int64_t nnz = 0, n_win = 0, total_unique = 0, total_tiles = 0;
+
+    const int32_t *d_row_ptr = nullptr;  // borrowed
+    const int32_t *d_col_idx = nullptr;  // borrowed
+
+    // Translated graph (Algorithm 1 outputs and the per-window unique lists).
+    int32_t *d_win_partition = nullptr;   // [n_win]
+    int32_t *d_win_unique_ptr = nullptr;  // [n_win + 1]
+    int32_t *d_edge_to_col = nullptr;     // [nnz]
+    int32_t *d_col_to_row = nullptr;      // [total_unique]
+
+    // Gather plan: every row is cut into segments of at most kSegLen edges.
+    int64_t n_seg = 0, n_long = 0, n_slots = 0;
+    int32_t *d_seg_row = nullptr;         // [n_seg] row of the segment
+    int32_t *d_seg_ebeg = nullptr;        // [n_seg] first edge
+    int32_t *d_seg_dst = nullptr;         // [n_seg] partial-sum slot, or -1: write the row directly
+    int32_t *d_long_row = nullptr;        // [n_long] rows with more than one segment
+    int32_t *d_long_slot_ptr = nullptr;   // [n_long + 1] their slot ranges
+    float *d_partial = nullptr;           // [n_slots x partial_ld] scratch, grown on demand
+    int64_t partial_elems = 0;
+
+    // Per-window path choice.
+    tcg_policy policy = TCG_POLICY_AUTO;
+    float min_reuse = 0.f;
+    uint8_t *d_win_path = nullptr;        // [n_win] 1 = condensed-tile path
+    int64_t n_tile_win = 0, nnz_tile = 0;
+};

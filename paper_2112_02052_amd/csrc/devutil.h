@@ -1,0 +1,74 @@
+// Device-side helpers: 16-byte feature chunks of fp32 / bf16 / fp16 rows unpacked to fp32,
+// and fp32 -> storage-type conversion for outputs.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+#include <stdint.h>
+
+#include "tcgnn.h"
+
+namespace tcg {
+
+template <int DT> struct Elem;  // VEC = elements in one 16-byte chunk
+template <> struct Elem<TCG_F32>  { static constexpr int VEC = 4; static constexpr int BYTES = 4; };
+template <> struct Elem<TCG_BF16> { static constexpr int VEC = 8; static constexpr int BYTES = 2; };
+template <> struct Elem<TCG_F16>  { static constexpr int VEC = 8; static constexpr int BYTES = 2; };
+
+__device__ __forceinline__ float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
+
+__device__ __forceinline__ float f16_bits_to_f32(uint32_t b)
+{
+    return __half2float(__ushort_as_half((unsigned short)b));
+}
+
+// Unpacks one 16-byte chunk into VEC floats (element k of the chunk -> v[k]).
+template <int DT>
+__device__ __forceinline__ void unpack16(const uint4 &raw, float *v)
+{
+    if constexpr (DT == TCG_F32) {
+        v[0] = __uint_as_float(raw.x);
+        v[1] = __uint_as_float(raw.y);
+        v[2] = __uint_as_float(raw.z);
+        v[3] = __uint_as_float(raw.w);
+    } else if constexpr (DT == TCG_BF16) {
+        const uint32_t r[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            v[2 * k] = __uint_as_float(r[k] << 16);
+            v[2 * k + 1] = __uint_as_float(r[k] & 0xFFFF0000u);
+        }
+    } else {
+        const uint32_t r[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            v[2 * k] = f16_bits_to_f32(r[k] & 0xFFFFu);
+            v[2 * k + 1] = f16_bits_to_f32(r[k] >> 16);
+        }
+    }
+}
+
+// Scalar element load as fp32.
+__device__ __forceinline__ float load_elem(const void *base, int64_t idx, int dt)
+{
+    if (dt == TCG_F32) return static_cast<const float *>(base)[idx];
+    uint32_t b = static_cast<const uint16_t *>(base)[idx];
+    return dt == TCG_BF16 ? bf16_bits_to_f32(b) : f16_bits_to_f32(b);
+}
+
+// fp32 -> bf16 bits, round to nearest even; NaN stays NaN.
+__device__ __forceinline__ uint16_t f32_to_bf16_bits(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x40u);
+    return (uint16_t)((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);
+}
+
+__device__ __forceinline__ void store_elem(void *base, int64_t idx, int dt, float v)
+{
+    if (dt == TCG_F32) static_cast<float *>(base)[idx] = v;
+    else if (dt == TCG_BF16) static_cast<uint16_t *>(base)[idx] = f32_to_bf16_bits(v);
+    else static_cast<uint16_t *>(base)[idx] = __half_as_ushort(__float2half_rn(v));
+}
+
+}  // namespace tcg

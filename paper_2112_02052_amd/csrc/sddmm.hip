@@ -1,0 +1,259 @@
+// Edge feature computation out[e] = <X[i], X[col_idx[e]]> (Equation 2 / Algorithm 3 of the
+// paper), gather path, and the row-wise softmax of the attention-style workload.
+//
+// Same decomposition as the SpMM gather path: a group of G lanes owns a row segment, keeps its
+// 16-byte slices of x_i in registers, streams the neighbour rows x_j through fully coalesced
+// 16-byte loads (ids prefetched one iteration ahead), multiplies lane-locally and adds across
+// the G lanes with wavefront shuffles.  UNROLL edges are reduced together by a butterfly that
+// halves the number of live partial sums at every step, so the cross-lane cost is about one
+// shuffle per edge instead of log2(G), and the results land in consecutive lanes for one
+// coalesced store.  The output is already in edgeList order; no dense-to-sparse step is needed
+// on this path.
+#include "common.h"
+#include "devutil.h"
+
+namespace tcg {
+
+// sddmm_tile.hip
+int sddmm_tile_launch(tcg_meta *m, const void *d_X, tcg_dtype x_dt, int32_t D, int64_t ldx, float *d_out,
+                      hipStream_t s);
+
+namespace {
+
+constexpr int kBlock = 256;
+
+// Sums UNROLL per-lane partials across the G lanes of a group.  On return, lane j (j < UNROLL,
+// position inside the group) holds the total of partial j -- if G >= UNROLL; otherwise every
+// lane holds all totals in p[].  Must be executed by all lanes of the group.
+template <int G, int UNROLL>
+__device__ __forceinline__ float group_reduce(float (&p)[UNROLL], int lane)
+{
+    if constexpr (G >= UNROLL) {
+        // Butterfly: at step with distance `off`, a lane keeps the half of its live partials whose
+        // index bit matches its own lane bit and receives the partner's copies of that half.
+        int live = UNROLL;
+#pragma unroll
+        for (int off = 1; off < UNROLL; off <<= 1) {
+            live >>= 1;
+            const bool upper = (lane & off) != 0;
+#pragma unroll
+            for (int k = 0; k < live; ++k) {
+                float keep = upper ? p[2 * k + 1] : p[2 * k];
+                float send = upper ? p[2 * k] : p[2 * k + 1];
+                p[k] = keep + __shfl_xor(send, off, G);
+            }
+        }
+        float r = p[0];
+#pragma unroll
+        for (int off = UNROLL; off < G; off <<= 1) r += __shfl_xor(r, off, G);
+        return r;  // lane's partial index = bit-reversal-free mapping: see below
+    } else {
+#pragma unroll
+        for (int k = 0; k < UNROLL; ++k)
+#pragma unroll
+            for (int off = 1; off < G; off <<= 1) p[k] += __shfl_xor(p[k], off, G);
+        return 0.f;
+    }
+}
+
+// After group_reduce with G >= UNROLL, lane (position in group) `l` holds the total of partial
+// index idx(l): step off=1 keeps index parity = bit 0 of l as the LOWEST bit of the original
+// index, the next step bit 1, and so on; so idx(l) = l mod UNROLL.
+template <int DT, int G, int NCH, int UNROLL>
+__global__ __launch_bounds__(kBlock) void sddmm_gather_kernel(
+    int64_t n_seg, const int32_t *__restrict__ seg_row, const int32_t *__restrict__ seg_ebeg,
+    const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ col_idx,
+    const char *__restrict__ X, int64_t ldx_bytes, int32_t n_chunks, float *__restrict__ out,
+    const uint8_t *__restrict__ win_path, int32_t win_h)
+{
+    constexpr int VEC = Elem<DT>::VEC;
+    const int lane = threadIdx.x % G;
+    const int64_t seg = (int64_t)blockIdx.x * (kBlock / G) + threadIdx.x / G;
+    if (seg >= n_seg) return;              // G divides the wavefront: whole groups leave together
+    const int32_t row = seg_row[seg];
+    if (win_path != nullptr && win_path[row / win_h]) return;
+    const int32_t eb = seg_ebeg[seg];
+    const int32_t ee = min(eb + kSegLen, row_ptr[row + 1]);
+
+    float xi[NCH][VEC];
+    {
+        const char *xr = X + (int64_t)row * ldx_bytes;
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) {
+            int chunk = lane + c * G;
+            uint4 raw = make_uint4(0, 0, 0, 0);
+            if (chunk < n_chunks) raw = *reinterpret_cast<const uint4 *>(xr + (int64_t)chunk * 16);
+            unpack16<DT>(raw, xi[c]);
+        }
+    }
+
+    int32_t cn[UNROLL];
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) cn[u] = (eb + u < ee) ? col_idx[eb + u] : 0;
+
+    for (int32_t e = eb; e < ee; e += UNROLL) {
+        uint4 raw[UNROLL][NCH];
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+#pragma unroll
+            for (int c = 0; c < NCH; ++c) {
+                int chunk = lane + c * G;
+                raw[u][c] = make_uint4(0, 0, 0, 0);
+                if (e + u < ee && chunk < n_chunks)
+                    raw[u][c] = *reinterpret_cast<const uint4 *>(X + (int64_t)cn[u] * ldx_bytes + (int64_t)chunk * 16);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            int32_t en = e + UNROLL + u;
+            if (en < ee) cn[u] = col_idx[en];
+        }
+        float p[UNROLL];
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            float a = 0.f;
+#pragma unroll
+            for (int c = 0; c < NCH; ++c) {
+                float v[VEC];
+                unpack16<DT>(raw[u][c], v);
+#pragma unroll
+                for (int k = 0; k < VEC; ++k) a = fmaf(xi[c][k], v[k], a);
+            }
+            p[u] = a;
+        }
+        float r = group_reduce<G, UNROLL>(p, lane);
+        if constexpr (G >= UNROLL) {
+            if (lane < UNROLL && e + lane < ee) out[e + lane] = r;
+        } else {
+            if (lane == 0) {
+#pragma unroll
+                for (int u = 0; u < UNROLL; ++u)
+                    if (e + u < ee) out[e + u] = p[u];
+            }
+        }
+    }
+}
+
+// Any D / alignment: one wavefront per segment, lanes stride over the feature dimension.
+__global__ __launch_bounds__(kBlock) void sddmm_gather_generic_kernel(
+    int64_t n_seg, const int32_t *__restrict__ seg_row, const int32_t *__restrict__ seg_ebeg,
+    const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ col_idx, const void *__restrict__ X,
+    int x_dt, int64_t ldx, int32_t D, float *__restrict__ out, const uint8_t *__restrict__ win_path,
+    int32_t win_h)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    const int64_t seg = (int64_t)blockIdx.x * (kBlock / kWave) + (threadIdx.x >> 6);
+    if (seg >= n_seg) return;
+    const int32_t row = seg_row[seg];
+    if (win_path != nullptr && win_path[row / win_h]) return;
+    const int32_t eb = seg_ebeg[seg];
+    const int32_t ee = min(eb + kSegLen, row_ptr[row + 1]);
+    for (int32_t e = eb; e < ee; ++e) {
+        const int64_t j = col_idx[e];
+        float a = 0.f;
+        for (int32_t d = lane; d < D; d += kWave)
+            a = fmaf(load_elem(X, (int64_t)row * ldx + d, x_dt), load_elem(X, j * ldx + d, x_dt), a);
+#pragma unroll
+        for (int off = 1; off < kWave; off <<= 1) a += __shfl_xor(a, off, kWave);
+        if (lane == 0) out[e] = a;
+    }
+}
+
+__device__ __forceinline__ float wave_max(float v)
+{
+#pragma unroll
+    for (int off = 1; off < kWave; off <<= 1) v = fmaxf(v, __shfl_xor(v, off, kWave));
+    return v;
+}
+
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int off = 1; off < kWave; off <<= 1) v += __shfl_xor(v, off, kWave);
+    return v;
+}
+
+// One wavefront per row: maximum, sum of exponentials, normalised write.
+__global__ __launch_bounds__(kBlock) void row_softmax_kernel(int32_t n_rows, const int32_t *__restrict__ row_ptr,
+                                                             const float *in, float *out)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    const int64_t row = (int64_t)blockIdx.x * (kBlock / kWave) + (threadIdx.x >> 6);
+    if (row >= n_rows) return;
+    const int32_t b = row_ptr[row], e = row_ptr[row + 1];
+    if (b == e) return;
+    float m = -INFINITY;
+    for (int32_t k = b + lane; k < e; k += kWave) m = fmaxf(m, in[k]);
+    m = wave_max(m);
+    float s = 0.f;
+    for (int32_t k = b + lane; k < e; k += kWave) s += expf(in[k] - m);
+    s = wave_sum(s);
+    const float inv = 1.f / s;
+    for (int32_t k = b + lane; k < e; k += kWave) out[k] = expf(in[k] - m) * inv;
+}
+
+template <int DT, int G, int NCH>
+void launch_sddmm(const tcg_meta *m, const void *X, int64_t ldx, int32_t n_chunks, float *out,
+                  const uint8_t *win_path, hipStream_t s)
+{
+    constexpr int UNROLL = NCH == 1 ? 8 : (NCH == 2 ? 4 : 2);
+    const unsigned grid = (unsigned)ceil_div(m->n_seg, kBlock / G);
+    hipLaunchKernelGGL((sddmm_gather_kernel<DT, G, NCH, UNROLL>), dim3(grid), dim3(kBlock), 0, s, m->n_seg,
+                       m->d_seg_row, m->d_seg_ebeg, m->d_row_ptr, m->d_col_idx, static_cast<const char *>(X),
+                       ldx * Elem<DT>::BYTES, n_chunks, out, win_path, m->win_h);
+}
+
+template <int DT>
+bool dispatch_sddmm(const tcg_meta *m, const void *X, int64_t ldx, int32_t n_chunks, float *out,
+                    const uint8_t *win_path, hipStream_t s)
+{
+    if (n_chunks <= 4) launch_sddmm<DT, 4, 1>(m, X, ldx, n_chunks, out, win_path, s);
+    else if (n_chunks <= 8) launch_sddmm<DT, 8, 1>(m, X, ldx, n_chunks, out, win_path, s);
+    else if (n_chunks <= 16) launch_sddmm<DT, 16, 1>(m, X, ldx, n_chunks, out, win_path, s);
+    else if (n_chunks <= 32) launch_sddmm<DT, 32, 1>(m, X, ldx, n_chunks, out, win_path, s);
+    else if (n_chunks <= 64) launch_sddmm<DT, 64, 1>(m, X, ldx, n_chunks, out, win_path, s);
+    else if (n_chunks <= 128) launch_sddmm<DT, 64, 2>(m, X, ldx, n_chunks, out, win_path, s);
+    else if (n_chunks <= 256) launch_sddmm<DT, 64, 4>(m, X, ldx, n_chunks, out, win_path, s);
+    else return false;
+    return true;
+}
+
+}  // namespace
+
+int sddmm_impl(tcg_meta *m, const void *d_X, tcg_dtype x_dt, int32_t D, int64_t ldx, float *d_out,
+               hipStream_t s)
+{
+    if (m->n_rows == 0 || m->nnz == 0) return TCG_OK;
+    const bool use_tiles = m->n_tile_win > 0 && m->win_h == 16 && tile_path_supports(x_dt, D, ldx, d_X);
+    const uint8_t *win_path = use_tiles ? m->d_win_path : nullptr;
+    if (use_tiles) TCG_TRY(sddmm_tile_launch(m, d_X, x_dt, D, ldx, d_out, s));
+    if (use_tiles && m->nnz_tile == m->nnz) return TCG_OK;
+
+    const int es = dtype_size(x_dt);
+    const bool vec_ok = ((int64_t)D * es) % 16 == 0 && (ldx * es) % 16 == 0 &&
+                        (reinterpret_cast<uintptr_t>(d_X) & 15) == 0;
+    bool done = false;
+    if (vec_ok) {
+        const int32_t n_chunks = (int32_t)((int64_t)D * es / 16);
+        if (x_dt == TCG_F32) done = dispatch_sddmm<TCG_F32>(m, d_X, ldx, n_chunks, d_out, win_path, s);
+        else if (x_dt == TCG_BF16) done = dispatch_sddmm<TCG_BF16>(m, d_X, ldx, n_chunks, d_out, win_path, s);
+        else done = dispatch_sddmm<TCG_F16>(m, d_X, ldx, n_chunks, d_out, win_path, s);
+    }
+    if (!done) {
+        const unsigned grid = (unsigned)ceil_div(m->n_seg, kBlock / kWave);
+        hipLaunchKernelGGL(sddmm_gather_generic_kernel, dim3(grid), dim3(kBlock), 0, s, m->n_seg, m->d_seg_row,
+                           m->d_seg_ebeg, m->d_row_ptr, m->d_col_idx, d_X, (int)x_dt, ldx, D, d_out, win_path,
+                           m->win_h);
+    }
+    return launch_status("sddmm_gather_kernel");
+}
+
+int row_softmax_impl(const tcg_meta *m, const float *d_in, float *d_out, hipStream_t s)
+{
+    if (m->n_rows == 0 || m->nnz == 0) return TCG_OK;
+    const unsigned grid = (unsigned)ceil_div(m->n_rows, kBlock / kWave);
+    hipLaunchKernelGGL(row_softmax_kernel, dim3(grid), dim3(kBlock), 0, s, m->n_rows, m->d_row_ptr, d_in, d_out);
+    return launch_status("row_softmax_kernel");
+}
+
+}  // namespace tcg

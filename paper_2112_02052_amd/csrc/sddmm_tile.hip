@@ -1,0 +1,148 @@
+// Edge feature computation on condensed tiles (Algorithm 3 of the paper) with gfx950 MFMA.
+//
+// One workgroup (4 wavefronts) per row window of 16 rows assigned to the tile path.  Here the
+// contraction runs over the feature dimension, which is contiguous in memory for both operands,
+// so the MFMA operands are loaded straight from global memory with 16-byte loads:
+//   FetchDenseRow  XTile_A = the window's own 16 rows, kept in registers for the whole window;
+//   FetchDenseCol  XTile_B = 16 neighbour rows named by col_to_row (each unique neighbour once);
+//   TCcompute      v_mfma_f32_16x16x32 accumulated over all of D before anything is written
+//                  (section 4.3: the result is only output after all iterations along the
+//                  embedding dimension);
+//   StoreSparse    the 16 x 16 output tiles of up to 256 condensed columns are parked in LDS and
+//                  every edge of the window picks its value through edge_to_col, which yields
+//                  the edgeList-ordered output.
+#include "common.h"
+#include "devutil.h"
+
+namespace tcg {
+
+namespace {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(8 * sizeof(_Float16)))) _Float16 f16x8;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
+
+constexpr int kTileBlock = 256;
+constexpr int kWaves = kTileBlock / kWave;
+constexpr int kCols = 256;            // condensed columns per LDS pass
+constexpr int kEStride = kCols + 4;   // floats; 4 * stride = 16 (mod 64 banks): the four row groups of a tile miss each other
+
+template <int DT>
+__device__ __forceinline__ f32x4 mfma16(const uint4 &a, const uint4 &b, f32x4 c)
+{
+    if constexpr (DT == TCG_BF16) {
+        bf16x8 va, vb;
+        __builtin_memcpy(&va, &a, 16);
+        __builtin_memcpy(&vb, &b, 16);
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, vb, c, 0, 0, 0);
+    } else {
+        f16x8 va, vb;
+        __builtin_memcpy(&va, &a, 16);
+        __builtin_memcpy(&vb, &b, 16);
+        return __builtin_amdgcn_mfma_f32_16x16x32_f16(va, vb, c, 0, 0, 0);
+    }
+}
+
+// KSTEPS = ceil(D / 32) rounded up to a power of two; steps beyond D contribute zeros.
+template <int DT, int KSTEPS>
+__global__ __launch_bounds__(kTileBlock) void sddmm_tile_kernel(
+    int32_t n_rows, const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ edge_to_col,
+    const int32_t *__restrict__ win_unique_ptr, const int32_t *__restrict__ col_to_row,
+    const uint8_t *__restrict__ win_path, const char *__restrict__ X, int64_t ldx_bytes, int32_t D,
+    float *__restrict__ out)
+{
+    __shared__ float s_e[16 * kEStride];
+    __shared__ int32_t s_rp[17];
+    const int64_t win = blockIdx.x;
+    if (!win_path[win]) return;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1);
+    const int wave = tid >> 6;
+    const int64_t r0 = win * 16;
+    if (tid < 17) {
+        int64_t r = r0 + tid;
+        s_rp[tid] = row_ptr[r < n_rows ? r : n_rows];
+    }
+    __syncthreads();
+    const int32_t lo = s_rp[0], hi = s_rp[16];
+    const int32_t u0 = win_unique_ptr[win];
+    const int32_t U = win_unique_ptr[win + 1] - u0;
+    const int32_t row_bytes = D * 2;
+    const int n = lane & 15;                    // tile row (A) / tile column (B) of this lane
+    const int32_t koff = (lane >> 4) * 16;      // byte offset of the lane's 8 features inside a 64-byte K step
+
+    uint4 a[KSTEPS];
+    {
+        const int64_t row = r0 + n;
+#pragma unroll
+        for (int kk = 0; kk < KSTEPS; ++kk) {
+            int32_t off = kk * 64 + koff;
+            a[kk] = make_uint4(0, 0, 0, 0);
+            if (row < n_rows && off < row_bytes) a[kk] = *reinterpret_cast<const uint4 *>(X + row * ldx_bytes + off);
+        }
+    }
+
+    for (int32_t c0 = 0; c0 < U; c0 += kCols) {
+        for (int t = wave; t < kCols / 16 && c0 + t * 16 < U; t += kWaves) {
+            const int32_t col = c0 + t * 16 + n;
+            const int64_t node = col < U ? col_to_row[u0 + col] : -1;
+            uint4 b[KSTEPS];
+#pragma unroll
+            for (int kk = 0; kk < KSTEPS; ++kk) {
+                int32_t off = kk * 64 + koff;
+                b[kk] = make_uint4(0, 0, 0, 0);
+                if (node >= 0 && off < row_bytes) b[kk] = *reinterpret_cast<const uint4 *>(X + node * ldx_bytes + off);
+            }
+            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int kk = 0; kk < KSTEPS; ++kk) acc = mfma16<DT>(a[kk], b[kk], acc);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) s_e[(4 * (lane >> 4) + r) * kEStride + t * 16 + n] = acc[r];
+        }
+        __syncthreads();
+        // StoreSparse: dense tile -> edgeList order.
+        for (int32_t e = lo + tid; e < hi; e += kTileBlock) {
+            int32_t c = edge_to_col[e] - c0;
+            if (c >= 0 && c < kCols) {
+                int r = 0;
+#pragma unroll
+                for (int step = 8; step > 0; step >>= 1)
+                    if (s_rp[r + step] <= e) r += step;
+                out[e] = s_e[r * kEStride + c];
+            }
+        }
+        __syncthreads();
+    }
+}
+
+template <int DT, int KSTEPS>
+void launch(const tcg_meta *m, const void *X, int64_t ldx, int32_t D, float *out, hipStream_t s)
+{
+    hipLaunchKernelGGL((sddmm_tile_kernel<DT, KSTEPS>), dim3((unsigned)m->n_win), dim3(kTileBlock), 0, s,
+                       m->n_rows, m->d_row_ptr, m->d_edge_to_col, m->d_win_unique_ptr, m->d_col_to_row,
+                       m->d_win_path, static_cast<const char *>(X), ldx * 2, D, out);
+}
+
+template <int DT>
+void launch_k(const tcg_meta *m, const void *X, int64_t ldx, int32_t D, float *out, hipStream_t s)
+{
+    const int ks = (D + 31) / 32;
+    if (ks <= 1) launch<DT, 1>(m, X, ldx, D, out, s);
+    else if (ks <= 2) launch<DT, 2>(m, X, ldx, D, out, s);
+    else if (ks <= 4) launch<DT, 4>(m, X, ldx, D, out, s);
+    else if (ks <= 8) launch<DT, 8>(m, X, ldx, D, out, s);
+    else launch<DT, 16>(m, X, ldx, D, out, s);
+}
+
+}  // namespace
+
+int sddmm_tile_launch(tcg_meta *m, const void *d_X, tcg_dtype x_dt, int32_t D, int64_t ldx, float *d_out,
+                      hipStream_t s)
+{
+    if (x_dt == TCG_BF16) launch_k<TCG_BF16>(m, d_X, ldx, D, d_out, s);
+    else launch_k<TCG_F16>(m, d_X, ldx, D, d_out, s);
+    return launch_status("sddmm_tile_kernel");
+}
+
+}  // namespace tcg

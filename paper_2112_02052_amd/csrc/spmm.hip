@@ -1,0 +1,291 @@
+// Neighbour aggregation Y = (w (.) A) X (Equation 1 / Algorithm 2 of the paper), gather path.
+//
+// The paper maps one row window to one thread block and multiplies condensed tiles on tensor
+// cores.  On MI355X the operation is bound by the HBM gathers of X rows, and on graphs without
+// much neighbour sharing inside a window a dense tile is mostly zeros, so windows that are not
+// assigned to the condensed-tile path run here:
+//   - every row is cut into segments of at most kSegLen edges (hub rows of power-law graphs
+//     would otherwise serialise on one wavefront);
+//   - a group of G lanes (G * 16 bytes >= one feature row) owns a segment; each lane keeps its
+//     16-byte slice of the row sum in registers, so every gathered X row is one fully coalesced
+//     request of the group and a 64-wide wavefront has 64 / G rows in flight per instruction;
+//   - neighbour ids (and edge values) of the next iteration are fetched before the current
+//     iteration's rows are consumed, so the id -> row dependency is off the critical path;
+//   - segments of one row window sit in the same workgroup, so neighbours shared inside the
+//     window are served by the CU's cache rather than HBM;
+//   - a row with a single segment is written straight to Y; a longer row writes one fp32
+//     partial per segment and a second kernel adds them in segment order (deterministic).
+#include "common.h"
+#include "devutil.h"
+
+namespace tcg {
+
+// spmm_tile.hip
+int spmm_tile_launch(tcg_meta *m, const void *d_X, tcg_dtype x_dt, int32_t D, int64_t ldx, const float *d_w,
+                     void *d_Y, tcg_dtype y_dt, int64_t ldy, hipStream_t s);
+
+namespace {
+
+constexpr int kBlock = 256;
+
+template <int DT, int G, int NCH, bool HAS_W, int UNROLL>
+__global__ __launch_bounds__(kBlock) void spmm_gather_kernel(
+    int64_t n_seg, const int32_t *__restrict__ seg_row, const int32_t *__restrict__ seg_ebeg,
+    const int32_t *__restrict__ seg_dst, const int32_t *__restrict__ row_ptr,
+    const int32_t *__restrict__ col_idx, const float *__restrict__ w, const char *__restrict__ X,
+    int64_t ldx_bytes, int32_t n_chunks, int32_t D, void *__restrict__ Y, int y_dt, int64_t ldy,
+    float *__restrict__ partial, int64_t partial_ld, const uint8_t *__restrict__ win_path, int32_t win_h,
+    int y_vec)
+{
+    constexpr int VEC = Elem<DT>::VEC;
+    const int lane = threadIdx.x % G;
+    const int64_t seg = (int64_t)blockIdx.x * (kBlock / G) + threadIdx.x / G;
+    if (seg >= n_seg) return;
+    const int32_t row = seg_row[seg];
+    if (win_path != nullptr && win_path[row / win_h]) return;
+    const int32_t eb = seg_ebeg[seg];
+    const int32_t ee = min(eb + kSegLen, row_ptr[row + 1]);
+
+    float acc[NCH][VEC];
+#pragma unroll
+    for (int c = 0; c < NCH; ++c)
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) acc[c][k] = 0.f;
+
+    int32_t cn[UNROLL];
+    float wn[UNROLL];
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) {
+        cn[u] = 0;
+        wn[u] = 1.f;
+        if (eb + u < ee) {
+            cn[u] = col_idx[eb + u];
+            if (HAS_W) wn[u] = w[eb + u];
+        }
+    }
+
+    for (int32_t e = eb; e < ee; e += UNROLL) {
+        uint4 raw[UNROLL][NCH];
+        float wc[UNROLL];
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            wc[u] = wn[u];
+            if (e + u < ee) {
+                const char *xr = X + (int64_t)cn[u] * ldx_bytes;
+#pragma unroll
+                for (int c = 0; c < NCH; ++c) {
+                    int chunk = lane + c * G;
+                    if (chunk < n_chunks) raw[u][c] = *reinterpret_cast<const uint4 *>(xr + (int64_t)chunk * 16);
+                }
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            int32_t en = e + UNROLL + u;
+            if (en < ee) {
+                cn[u] = col_idx[en];
+                if (HAS_W) wn[u] = w[en];
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            if (e + u < ee) {
+#pragma unroll
+                for (int c = 0; c < NCH; ++c) {
+                    int chunk = lane + c * G;
+                    if (chunk < n_chunks) {
+                        float v[VEC];
+                        unpack16<DT>(raw[u][c], v);
+#pragma unroll
+                        for (int k = 0; k < VEC; ++k) {
+                            if (HAS_W) acc[c][k] = fmaf(wc[u], v[k], acc[c][k]);
+                            else acc[c][k] += v[k];
+                        }
+                    }
+                }
+            }
+        }
+    }
+
+    const int32_t dst = seg_dst[seg];
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+        int chunk = lane + c * G;
+        if (chunk >= n_chunks) continue;
+        int64_t d0 = (int64_t)chunk * VEC;
+        if (dst >= 0) {
+            float *p = partial + (int64_t)dst * partial_ld + d0;
+#pragma unroll
+            for (int k = 0; k < VEC; k += 4)
+                *reinterpret_cast<float4 *>(p + k) = make_float4(acc[c][k], acc[c][k + 1], acc[c][k + 2], acc[c][k + 3]);
+        } else if (y_vec) {
+            float *p = static_cast<float *>(Y) + (int64_t)row * ldy + d0;
+#pragma unroll
+            for (int k = 0; k < VEC; k += 4)
+                *reinterpret_cast<float4 *>(p + k) = make_float4(acc[c][k], acc[c][k + 1], acc[c][k + 2], acc[c][k + 3]);
+        } else {
+#pragma unroll
+            for (int k = 0; k < VEC; ++k) store_elem(Y, (int64_t)row * ldy + d0 + k, y_dt, acc[c][k]);
+        }
+    }
+}
+
+// Any D, any alignment: one wavefront per segment, one lane per feature element.
+template <bool HAS_W>
+__global__ __launch_bounds__(kBlock) void spmm_gather_generic_kernel(
+    int64_t n_seg, const int32_t *__restrict__ seg_row, const int32_t *__restrict__ seg_ebeg,
+    const int32_t *__restrict__ seg_dst, const int32_t *__restrict__ row_ptr,
+    const int32_t *__restrict__ col_idx, const float *__restrict__ w, const void *__restrict__ X, int x_dt,
+    int64_t ldx, int32_t D, void *__restrict__ Y, int y_dt, int64_t ldy, float *__restrict__ partial,
+    int64_t partial_ld, const uint8_t *__restrict__ win_path, int32_t win_h)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    const int64_t seg = (int64_t)blockIdx.x * (kBlock / kWave) + (threadIdx.x >> 6);
+    if (seg >= n_seg) return;
+    const int32_t row = seg_row[seg];
+    if (win_path != nullptr && win_path[row / win_h]) return;
+    const int32_t eb = seg_ebeg[seg];
+    const int32_t ee = min(eb + kSegLen, row_ptr[row + 1]);
+    const int32_t dst = seg_dst[seg];
+    for (int32_t d = lane; d < D; d += kWave) {
+        float acc = 0.f;
+        for (int32_t e = eb; e < ee; ++e) {
+            float x = load_elem(X, (int64_t)col_idx[e] * ldx + d, x_dt);
+            acc = HAS_W ? fmaf(w[e], x, acc) : acc + x;
+        }
+        if (dst >= 0) partial[(int64_t)dst * partial_ld + d] = acc;
+        else store_elem(Y, (int64_t)row * ldy + d, y_dt, acc);
+    }
+}
+
+// Adds the per-segment partials of every long row, in segment order.
+__global__ __launch_bounds__(kBlock) void spmm_reduce_long_kernel(
+    int64_t n_long, const int32_t *__restrict__ long_row, const int32_t *__restrict__ long_slot_ptr,
+    const float *__restrict__ partial, int64_t partial_ld, int32_t D, void *__restrict__ Y, int y_dt,
+    int64_t ldy, const uint8_t *__restrict__ win_path, int32_t win_h)
+{
+    const int64_t li = blockIdx.x;
+    const int32_t row = long_row[li];
+    if (win_path != nullptr && win_path[row / win_h]) return;
+    const int32_t s0 = long_slot_ptr[li], s1 = long_slot_ptr[li + 1];
+    for (int32_t d = threadIdx.x; d < D; d += kBlock) {
+        float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+        int32_t s = s0;
+        for (; s + 4 <= s1; s += 4) {
+            a0 += partial[(int64_t)(s + 0) * partial_ld + d];
+            a1 += partial[(int64_t)(s + 1) * partial_ld + d];
+            a2 += partial[(int64_t)(s + 2) * partial_ld + d];
+            a3 += partial[(int64_t)(s + 3) * partial_ld + d];
+        }
+        for (; s < s1; ++s) a0 += partial[(int64_t)s * partial_ld + d];
+        store_elem(Y, (int64_t)row * ldy + d, y_dt, (a0 + a1) + (a2 + a3));
+    }
+}
+
+struct GatherArgs {
+    const tcg_meta *m;
+    const void *X;
+    int64_t ldx;
+    int32_t D;
+    const float *w;
+    void *Y;
+    int y_dt;
+    int64_t ldy;
+    const uint8_t *win_path;
+    hipStream_t s;
+};
+
+template <int DT, int G, int NCH, bool HAS_W>
+void launch_gather(const GatherArgs &a, int32_t n_chunks)
+{
+    constexpr int UNROLL = NCH == 1 ? 8 : (NCH == 2 ? 4 : 2);
+    const tcg_meta *m = a.m;
+    const int gpb = kBlock / G;
+    const unsigned grid = (unsigned)ceil_div(m->n_seg, gpb);
+    const int y_vec = a.y_dt == TCG_F32 && (a.ldy & 3) == 0 && (reinterpret_cast<uintptr_t>(a.Y) & 15) == 0;
+    hipLaunchKernelGGL((spmm_gather_kernel<DT, G, NCH, HAS_W, UNROLL>), dim3(grid), dim3(kBlock), 0, a.s,
+                       m->n_seg, m->d_seg_row, m->d_seg_ebeg, m->d_seg_dst, m->d_row_ptr, m->d_col_idx, a.w,
+                       static_cast<const char *>(a.X), a.ldx * Elem<DT>::BYTES, n_chunks, a.D, a.Y, a.y_dt,
+                       a.ldy, m->d_partial, (int64_t)a.D, a.win_path, m->win_h, y_vec);
+}
+
+template <int DT, bool HAS_W>
+bool dispatch_gather(const GatherArgs &a, int32_t n_chunks)
+{
+    if (n_chunks <= 4) launch_gather<DT, 4, 1, HAS_W>(a, n_chunks);
+    else if (n_chunks <= 8) launch_gather<DT, 8, 1, HAS_W>(a, n_chunks);
+    else if (n_chunks <= 16) launch_gather<DT, 16, 1, HAS_W>(a, n_chunks);
+    else if (n_chunks <= 32) launch_gather<DT, 32, 1, HAS_W>(a, n_chunks);
+    else if (n_chunks <= 64) launch_gather<DT, 64, 1, HAS_W>(a, n_chunks);
+    else if (n_chunks <= 128) launch_gather<DT, 64, 2, HAS_W>(a, n_chunks);
+    else if (n_chunks <= 256) launch_gather<DT, 64, 4, HAS_W>(a, n_chunks);
+    else return false;
+    return true;
+}
+
+template <int DT>
+bool dispatch_gather_w(const GatherArgs &a, int32_t n_chunks)
+{
+    return a.w ? dispatch_gather<DT, true>(a, n_chunks) : dispatch_gather<DT, false>(a, n_chunks);
+}
+
+}  // namespace
+
+int spmm_impl(tcg_meta *m, const void *d_X, tcg_dtype x_dt, int32_t D, int64_t ldx, const float *d_w,
+              void *d_Y, tcg_dtype y_dt, int64_t ldy, hipStream_t s)
+{
+    if (m->n_rows == 0) return TCG_OK;
+
+    // Scratch for the partial sums of rows that span several segments.
+    const int64_t need = m->n_slots * (int64_t)D;
+    if (need > m->partial_elems) {
+        if (m->d_partial) {
+            TCG_HIP(hipStreamSynchronize(s));
+            TCG_HIP(hipFree(m->d_partial));
+            m->d_partial = nullptr;
+            m->partial_elems = 0;
+        }
+        TCG_TRY(dev_alloc(&m->d_partial, need));
+        m->partial_elems = need;
+    }
+
+    const bool use_tiles = m->n_tile_win > 0 && m->win_h == 16 && tile_path_supports(x_dt, D, ldx, d_X);
+    const uint8_t *win_path = use_tiles ? m->d_win_path : nullptr;
+    if (use_tiles) TCG_TRY(spmm_tile_launch(m, d_X, x_dt, D, ldx, d_w, d_Y, y_dt, ldy, s));
+    if (use_tiles && m->nnz_tile == m->nnz && m->n_tile_win == m->n_win) return TCG_OK;  // nothing left
+
+    GatherArgs a{m, d_X, ldx, D, d_w, d_Y, (int)y_dt, ldy, win_path, s};
+    const int es = dtype_size(x_dt);
+    const bool vec_ok = ((int64_t)D * es) % 16 == 0 && (ldx * es) % 16 == 0 &&
+                        (reinterpret_cast<uintptr_t>(d_X) & 15) == 0;
+    bool done = false;
+    if (vec_ok) {
+        const int32_t n_chunks = (int32_t)((int64_t)D * es / 16);
+        if (x_dt == TCG_F32) done = dispatch_gather_w<TCG_F32>(a, n_chunks);
+        else if (x_dt == TCG_BF16) done = dispatch_gather_w<TCG_BF16>(a, n_chunks);
+        else done = dispatch_gather_w<TCG_F16>(a, n_chunks);
+    }
+    if (!done) {
+        const unsigned grid = (unsigned)ceil_div(m->n_seg, kBlock / kWave);
+        if (d_w)
+            hipLaunchKernelGGL(spmm_gather_generic_kernel<true>, dim3(grid), dim3(kBlock), 0, s, m->n_seg,
+                               m->d_seg_row, m->d_seg_ebeg, m->d_seg_dst, m->d_row_ptr, m->d_col_idx, d_w, d_X,
+                               (int)x_dt, ldx, D, d_Y, (int)y_dt, ldy, m->d_partial, (int64_t)D, win_path,
+                               m->win_h);
+        else
+            hipLaunchKernelGGL(spmm_gather_generic_kernel<false>, dim3(grid), dim3(kBlock), 0, s, m->n_seg,
+                               m->d_seg_row, m->d_seg_ebeg, m->d_seg_dst, m->d_row_ptr, m->d_col_idx, d_w, d_X,
+                               (int)x_dt, ldx, D, d_Y, (int)y_dt, ldy, m->d_partial, (int64_t)D, win_path,
+                               m->win_h);
+    }
+    TCG_TRY(launch_status("spmm_gather_kernel"));
+    if (m->n_long > 0) {
+        hipLaunchKernelGGL(spmm_reduce_long_kernel, dim3((unsigned)m->n_long), dim3(kBlock), 0, s, m->n_long,
+                           m->d_long_row, m->d_long_slot_ptr, m->d_partial, (int64_t)D, D, d_Y, (int)y_dt, ldy,
+                           win_path, m->win_h);
+        TCG_TRY(launch_status("spmm_reduce_long_kernel"));
+    }
+    return TCG_OK;
+}
+
+}  // namespace tcg

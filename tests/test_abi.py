@@ -1,0 +1,49 @@
+"""The C-ABI library loads without a GPU and exports every symbol the header declares.
+No compute call is made here."""
+import ctypes
+import os
+import re
+
+import paper_2112_02052_amd as tcg
+from paper_2112_02052_amd.build import INCLUDE
+
+
+def declared_symbols():
+    text = open(os.path.join(INCLUDE, "tcgnn.h")).read()
+    return sorted(set(re.findall(r"TCG_API[^;(]*?\b(tcg_\w+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported():
+    lib = tcg.load_library()
+    names = declared_symbols()
+    assert len(names) >= 10
+    assert sorted(tcg.EXPORTED) == names
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_status_texts_and_argument_checks_without_gpu():
+    lib = tcg.load_library()
+    for code in (0, -1, -2, -3, -4, -5, -99):
+        assert len(lib.tcg_strerror(code)) > 0
+    # Null handles / null outputs are rejected before any HIP call is made.
+    assert lib.tcg_sgt_build(4, 4, 0, None, None, 16, 8, 1, None, None) == -1
+    h = ctypes.c_void_p()
+    assert lib.tcg_sgt_build(4, 4, 0, None, None, 16, 8, 1, None, ctypes.byref(h)) == -1
+    assert lib.tcg_sgt_sizes(None, None, None, None, None) == -1
+    assert lib.tcg_spmm(None, None, 0, 16, 16, None, None, 0, 16, None) == -1
+    assert lib.tcg_sddmm(None, None, 0, 16, 16, None, None) == -1
+    assert lib.tcg_row_softmax(None, None, None, None) == -1
+    assert lib.tcg_sgt_set_policy(None, 0, 0.0, None) == -1
+    lib.tcg_sgt_free(None)
+
+
+def test_sources_have_no_oracle_dependency():
+    # The product never routes through the oracle: no file of the package mentions it.
+    pkg = os.path.dirname(tcg.__file__)
+    for root, _, files in os.walk(pkg):
+        if "_build" in root:
+            continue
+        for f in files:
+            if f.endswith((".py", ".hip", ".h")):
+                assert "oracle" not in open(os.path.join(root, f)).read().lower(), f
