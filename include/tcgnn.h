@@ -110,8 +110,9 @@ TCG_API int tcg_sgt_export(const tcg_meta *meta, int32_t *win_partition, int32_t
 
 /*
  * Chooses which windows run on the condensed-tile (MFMA) path.  TCG_POLICY_AUTO (the state
- * after tcg_sgt_build) sends a window there when window_h == 16 and its neighbour reuse
- * nnz_w / U_w is at least `min_reuse` (<= 0 selects the library default); the tile path is only
+ * after tcg_sgt_build) sends a window there when window_h == 16, it has at most 512 unique
+ * columns and its neighbour reuse nnz_w / U_w is at least `min_reuse` (<= 0 selects the library
+ * default, 2); the tile path is only
  * taken by calls whose X is bf16 or f16, fp32 features always use the gather path.
  * Blocks until the stream has finished.  Returns TCG_EINVAL for TCG_POLICY_TILE when
  * window_h != 16.

@@ -19,11 +19,9 @@ void set_hip_error(hipError_t e, const char *what)
 static void free_meta(tcg_meta *m)
 {
     if (!m) return;
-    void *bufs[] = {m->d_win_partition, m->d_win_unique_ptr, m->d_edge_to_col, m->d_col_to_row,
-                    m->d_seg_row,       m->d_seg_ebeg,       m->d_seg_dst,     m->d_long_row,
-                    m->d_long_slot_ptr, m->d_partial,        m->d_win_path};
-    for (void *b : bufs)
-        if (b) (void)hipFree(b);
+    for (int i = 0; i < m->n_owned; ++i)
+        if (m->owned[i]) (void)hipFree(m->owned[i]);
+    if (m->d_partial) (void)hipFree(m->d_partial);
     delete m;
 }
 

@@ -11,6 +11,7 @@ namespace tcg {
 constexpr int kWave = 64;            // gfx950 wavefront width
 constexpr int kSegLen = 128;         // max edges of one row segment on the gather path
 constexpr float kDefaultMinReuse = 2.0f;
+constexpr int kTileMaxUnique = 512;  // AUTO never sends a window with more unique columns to the tile path
 
 // Records the text of a failing HIP call for tcg_strerror (thread local).
 void set_hip_error(hipError_t e, const char *what);
@@ -58,9 +59,10 @@ int dev_alloc(T **p, int64_t count)
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
 // Exclusive prefix sum of n int32 values on the device; out may alias in.  out has n + 1
-// entries: out[n] is the total.  Fails with TCG_ERANGE semantics left to the caller (sums are
-// computed in int32; callers bound the total beforehand).
-int exclusive_scan_i32(const int32_t *d_in, int32_t *d_out, int64_t n, hipStream_t s);
+// entries: out[n] is the total (sums are computed in int32; callers bound the total beforehand).
+// d_work: device scratch of scan_workspace_elems(n) int32.
+int64_t scan_workspace_elems(int64_t n);
+int exclusive_scan_i32(const int32_t *d_in, int32_t *d_out, int64_t n, int32_t *d_work, hipStream_t s);
 
 }  // namespace tcg
 
@@ -110,6 +112,11 @@ struct tcg_meta {
     int32_t *d_long_slot_ptr = nullptr;   // [n_long + 1] their slot ranges
     float *d_partial = nullptr;           // [n_slots x partial_ld] scratch, grown on demand
     int64_t partial_elems = 0;
+
+    // Device allocations owned by this object (the pointers above and below are carved from them).
+    void *owned[8] = {nullptr};
+    int n_owned = 0;
+    unsigned long long *d_counters = nullptr;   // [0] tiles, [2] tile-path windows, [3] their edges
 
     // Per-window path choice.
     tcg_policy policy = TCG_POLICY_AUTO;

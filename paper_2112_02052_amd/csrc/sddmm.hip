@@ -46,7 +46,7 @@ __device__ __forceinline__ float group_reduce(float (&p)[UNROLL], int lane)
         float r = p[0];
 #pragma unroll
         for (int off = UNROLL; off < G; off <<= 1) r += __shfl_xor(r, off, G);
-        return r;  // lane's partial index = bit-reversal-free mapping: see below
+        return r;
     } else {
 #pragma unroll
         for (int k = 0; k < UNROLL; ++k)
@@ -87,27 +87,33 @@ __global__ __launch_bounds__(kBlock) void sddmm_gather_kernel(
         }
     }
 
+    if (eb >= ee) return;                  // empty row: nothing to write
+    // Ids are read from a clamped, valid position (no predicate, issued back to back) and the next
+    // iteration's ids go out before this iteration's row loads, so one wait covers both.
+    const int32_t last = ee - 1;
+    const uint32_t ldx32 = (uint32_t)ldx_bytes;
     int32_t cn[UNROLL];
 #pragma unroll
-    for (int u = 0; u < UNROLL; ++u) cn[u] = (eb + u < ee) ? col_idx[eb + u] : 0;
+    for (int u = 0; u < UNROLL; ++u) cn[u] = col_idx[min(eb + u, last)];
 
     for (int32_t e = eb; e < ee; e += UNROLL) {
+        int32_t cnext[UNROLL];
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) cnext[u] = col_idx[min(e + UNROLL + u, last)];
         uint4 raw[UNROLL][NCH];
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) {
+            const char *xr = X + (uint64_t)(uint32_t)cn[u] * ldx32;
 #pragma unroll
             for (int c = 0; c < NCH; ++c) {
                 int chunk = lane + c * G;
                 raw[u][c] = make_uint4(0, 0, 0, 0);
                 if (e + u < ee && chunk < n_chunks)
-                    raw[u][c] = *reinterpret_cast<const uint4 *>(X + (int64_t)cn[u] * ldx_bytes + (int64_t)chunk * 16);
+                    raw[u][c] = *reinterpret_cast<const uint4 *>(xr + (uint32_t)chunk * 16u);
             }
         }
 #pragma unroll
-        for (int u = 0; u < UNROLL; ++u) {
-            int32_t en = e + UNROLL + u;
-            if (en < ee) cn[u] = col_idx[en];
-        }
+        for (int u = 0; u < UNROLL; ++u) cn[u] = cnext[u];
         float p[UNROLL];
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) {
@@ -173,7 +179,10 @@ __device__ __forceinline__ float wave_sum(float v)
     return v;
 }
 
-// One wavefront per row: maximum, sum of exponentials, normalised write.
+static_assert(kSegLen == 2 * kWave, "row_softmax_kernel holds two entries per lane");
+
+// Rows of at most kSegLen entries: one wavefront per row (maximum, sum of exponentials,
+// normalised write).  Longer rows are left to row_softmax_long_kernel.
 __global__ __launch_bounds__(kBlock) void row_softmax_kernel(int32_t n_rows, const int32_t *__restrict__ row_ptr,
                                                              const float *in, float *out)
 {
@@ -181,15 +190,45 @@ __global__ __launch_bounds__(kBlock) void row_softmax_kernel(int32_t n_rows, con
     const int64_t row = (int64_t)blockIdx.x * (kBlock / kWave) + (threadIdx.x >> 6);
     if (row >= n_rows) return;
     const int32_t b = row_ptr[row], e = row_ptr[row + 1];
-    if (b == e) return;
+    if (b == e || e - b > kSegLen) return;
+    float v0 = (b + lane < e) ? in[b + lane] : -INFINITY;
+    float v1 = (b + kWave + lane < e) ? in[b + kWave + lane] : -INFINITY;
+    const float m = wave_max(fmaxf(v0, v1));
+    const float x0 = (b + lane < e) ? expf(v0 - m) : 0.f;
+    const float x1 = (b + kWave + lane < e) ? expf(v1 - m) : 0.f;
+    const float inv = 1.f / wave_sum(x0 + x1);
+    if (b + lane < e) out[b + lane] = x0 * inv;
+    if (b + kWave + lane < e) out[b + kWave + lane] = x1 * inv;
+}
+
+// Rows longer than kSegLen (the gather plan's list of split rows): one workgroup per row.
+__global__ __launch_bounds__(kBlock) void row_softmax_long_kernel(const int32_t *__restrict__ long_row,
+                                                                  const int32_t *__restrict__ row_ptr,
+                                                                  const float *in, float *out)
+{
+    __shared__ float s_red[kBlock / kWave];
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
+    const int32_t row = long_row[blockIdx.x];
+    const int32_t b = row_ptr[row], e = row_ptr[row + 1];
     float m = -INFINITY;
-    for (int32_t k = b + lane; k < e; k += kWave) m = fmaxf(m, in[k]);
+    for (int32_t k = b + threadIdx.x; k < e; k += kBlock) m = fmaxf(m, in[k]);
     m = wave_max(m);
+    if (lane == 0) s_red[wave] = m;
+    __syncthreads();
+    m = s_red[0];
+#pragma unroll
+    for (int i = 1; i < kBlock / kWave; ++i) m = fmaxf(m, s_red[i]);
+    __syncthreads();
     float s = 0.f;
-    for (int32_t k = b + lane; k < e; k += kWave) s += expf(in[k] - m);
+    for (int32_t k = b + threadIdx.x; k < e; k += kBlock) s += expf(in[k] - m);
     s = wave_sum(s);
+    if (lane == 0) s_red[wave] = s;
+    __syncthreads();
+    s = 0.f;
+#pragma unroll
+    for (int i = 0; i < kBlock / kWave; ++i) s += s_red[i];
     const float inv = 1.f / s;
-    for (int32_t k = b + lane; k < e; k += kWave) out[k] = expf(in[k] - m) * inv;
+    for (int32_t k = b + threadIdx.x; k < e; k += kBlock) out[k] = expf(in[k] - m) * inv;
 }
 
 template <int DT, int G, int NCH>
@@ -230,7 +269,7 @@ int sddmm_impl(tcg_meta *m, const void *d_X, tcg_dtype x_dt, int32_t D, int64_t 
     if (use_tiles && m->nnz_tile == m->nnz) return TCG_OK;
 
     const int es = dtype_size(x_dt);
-    const bool vec_ok = ((int64_t)D * es) % 16 == 0 && (ldx * es) % 16 == 0 &&
+    const bool vec_ok = ((int64_t)D * es) % 16 == 0 && (ldx * es) % 16 == 0 && ldx * es < (1ll << 32) &&
                         (reinterpret_cast<uintptr_t>(d_X) & 15) == 0;
     bool done = false;
     if (vec_ok) {
@@ -253,7 +292,13 @@ int row_softmax_impl(const tcg_meta *m, const float *d_in, float *d_out, hipStre
     if (m->n_rows == 0 || m->nnz == 0) return TCG_OK;
     const unsigned grid = (unsigned)ceil_div(m->n_rows, kBlock / kWave);
     hipLaunchKernelGGL(row_softmax_kernel, dim3(grid), dim3(kBlock), 0, s, m->n_rows, m->d_row_ptr, d_in, d_out);
-    return launch_status("row_softmax_kernel");
+    TCG_TRY(launch_status("row_softmax_kernel"));
+    if (m->n_long > 0) {
+        hipLaunchKernelGGL(row_softmax_long_kernel, dim3((unsigned)m->n_long), dim3(kBlock), 0, s, m->d_long_row,
+                           m->d_row_ptr, d_in, d_out);
+        TCG_TRY(launch_status("row_softmax_long_kernel"));
+    }
+    return TCG_OK;
 }
 
 }  // namespace tcg

@@ -2,10 +2,11 @@
 // execution plan derived from it.
 //
 // The paper notes that row windows are independent, so each window is translated by one
-// workgroup.  Three size classes, all producing the same canonical result (ascending unique
+// workgroup.  Four size classes, all producing the same canonical result (ascending unique
 // column list, rank of every edge's column in it):
-//   small  (<= 1024 edges)   sort in LDS with a bitonic network, 256 threads
-//   medium (<= 4096 edges)   same, 1024 threads, 32 KB of LDS
+//   tiny   (<= 128 edges)    bitonic network in LDS, one wavefront
+//   small  (<= 1024 edges)   same, 256 threads
+//   medium (<= 4096 edges)   same, 256 threads, 32 KB of LDS
 //   large  (>  4096 edges)   a bitmap over the column space in device scratch: set a bit per
 //                            edge, prefix-popcount the words, rank = prefix + popcount below.
 //                            Hub windows of power-law graphs land here; the cost is
@@ -13,6 +14,9 @@
 // Every window first writes its unique list at its own edge offset of a temporary array (the
 // list is never longer than the window's edge range); once all U_w are known a prefix sum gives
 // win_unique_ptr and the lists are packed into col_to_row.
+//
+// Host side: three stream synchronisations per build (class / plan sizes, U, final counters) and a
+// handful of arena allocations; everything else is enqueued back to back.
 #include "common.h"
 
 #include <limits.h>
@@ -23,6 +27,7 @@ namespace tcg {
 
 namespace {
 
+constexpr int kTinyCap = 128;
 constexpr int kSmallCap = 1024;
 constexpr int kMediumCap = 4096;   // 2 x 16 KB of static LDS
 
@@ -43,7 +48,7 @@ __device__ __forceinline__ int block_exclusive_scan(int v, int *tmp, int *total)
 {
     const int lane = threadIdx.x & (kWave - 1);
     const int wid = threadIdx.x >> 6;
-    const int nw = blockDim.x >> 6;
+    const int nw = (blockDim.x + kWave - 1) >> 6;
     int incl = wave_inclusive_scan(v);
     if (lane == kWave - 1) tmp[wid] = incl;
     __syncthreads();
@@ -60,26 +65,32 @@ __device__ __forceinline__ int block_exclusive_scan(int v, int *tmp, int *total)
     return res;
 }
 
-constexpr int kScanThreads = 1024;
-constexpr int kScanItems = 4;
+// ---- device-wide exclusive scan ------------------------------------------------------------------
+// Three steps: per-block sums of 4096-element blocks, a single-workgroup scan of those sums, and a
+// per-block rescan with the block's offset.  Inputs of up to 4096 elements take the single-workgroup
+// kernel alone.
 
-__global__ __launch_bounds__(kScanThreads) void scan_kernel(const int32_t *in, int32_t *out, int64_t n)
+constexpr int kScanThreads = 256;
+constexpr int kScanItems = 16;
+constexpr int kScanBlock = kScanThreads * kScanItems;
+
+__global__ __launch_bounds__(1024) void scan_single_kernel(const int32_t *in, int32_t *out, int64_t n)
 {
-    __shared__ int tmp[kScanThreads / kWave + 1];
+    __shared__ int tmp[1024 / kWave + 1];
     int carry = 0;
-    for (int64_t base = 0; base < n; base += (int64_t)kScanThreads * kScanItems) {
-        int64_t i0 = base + (int64_t)threadIdx.x * kScanItems;
-        int v[kScanItems];
+    for (int64_t base = 0; base < n; base += 1024 * 4) {
+        int64_t i0 = base + (int64_t)threadIdx.x * 4;
+        int v[4];
         int sum = 0;
 #pragma unroll
-        for (int k = 0; k < kScanItems; ++k) {
+        for (int k = 0; k < 4; ++k) {
             v[k] = (i0 + k < n) ? in[i0 + k] : 0;
             sum += v[k];
         }
         int total;
         int run = carry + block_exclusive_scan(sum, tmp, &total);
 #pragma unroll
-        for (int k = 0; k < kScanItems; ++k) {
+        for (int k = 0; k < 4; ++k) {
             if (i0 + k < n) out[i0 + k] = run;
             run += v[k];
         }
@@ -88,9 +99,44 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(const int32_t *in, i
     if (threadIdx.x == 0) out[n] = carry;
 }
 
-// CSR sanity check: flag bit 0 = row_ptr ends wrong, bit 1 = not monotone, bit 2 = column range.
-__global__ void validate_csr_kernel(int32_t n_rows, int32_t n_cols, int64_t nnz, const int32_t *rp,
-                                    const int32_t *ci, int *flag)
+__global__ __launch_bounds__(kScanThreads) void scan_block_sum_kernel(const int32_t *in, int64_t n,
+                                                                      int32_t *block_sums)
+{
+    __shared__ int tmp[kScanThreads / kWave + 1];
+    const int64_t i0 = (int64_t)blockIdx.x * kScanBlock + (int64_t)threadIdx.x * kScanItems;
+    int sum = 0;
+#pragma unroll
+    for (int k = 0; k < kScanItems; ++k) sum += (i0 + k < n) ? in[i0 + k] : 0;
+    int total;
+    (void)block_exclusive_scan(sum, tmp, &total);
+    if (threadIdx.x == 0) block_sums[blockIdx.x] = total;
+}
+
+__global__ __launch_bounds__(kScanThreads) void scan_apply_kernel(const int32_t *in, int32_t *out, int64_t n,
+                                                                  const int32_t *block_offs, int64_t n_blocks)
+{
+    __shared__ int tmp[kScanThreads / kWave + 1];
+    const int64_t i0 = (int64_t)blockIdx.x * kScanBlock + (int64_t)threadIdx.x * kScanItems;
+    int v[kScanItems];
+    int sum = 0;
+#pragma unroll
+    for (int k = 0; k < kScanItems; ++k) {
+        v[k] = (i0 + k < n) ? in[i0 + k] : 0;
+        sum += v[k];
+    }
+    int total;
+    int run = block_offs[blockIdx.x] + block_exclusive_scan(sum, tmp, &total);
+#pragma unroll
+    for (int k = 0; k < kScanItems; ++k) {
+        if (i0 + k < n) out[i0 + k] = run;
+        run += v[k];
+    }
+    if (blockIdx.x == 0 && threadIdx.x == 0) out[n] = block_offs[n_blocks];
+}
+
+// ---- CSR validation ------------------------------------------------------------------------------
+// flag bit 0 = row_ptr ends wrong, bit 1 = not monotone, bit 2 = column out of range.
+__global__ void validate_csr_kernel(int32_t n_rows, int64_t nnz, const int32_t *rp, int *flag)
 {
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     int64_t stride = (int64_t)gridDim.x * blockDim.x;
@@ -121,36 +167,41 @@ __device__ __forceinline__ void window_edge_range(const int32_t *rp, int32_t n_r
     *hi = rp[r1];
 }
 
-// Appends the windows of the large class to a list (order is irrelevant: each window's result
-// only depends on the window).
-__global__ void collect_large_kernel(int32_t n_rows, int32_t win_h, int64_t n_win, const int32_t *rp,
-                                     int32_t *large_list, int *n_large)
+// ---- window classification -----------------------------------------------------------------------
+// Appends every non-empty window to the list of its size class (order inside a list is irrelevant:
+// a window's result depends on the window only); empty windows get U_w = 0 here.
+// counts[0..3] = tiny, small, medium, large.
+__global__ void classify_windows_kernel(int32_t n_rows, int32_t win_h, int64_t n_win, const int32_t *rp,
+                                        int32_t *lists, int *counts, int32_t *win_unique)
 {
     int64_t w = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (w >= n_win) return;
     int32_t lo, hi;
     window_edge_range(rp, n_rows, win_h, w, &lo, &hi);
-    if (hi - lo > kMediumCap) large_list[atomicAdd(n_large, 1)] = (int32_t)w;
+    const int32_t cnt = hi - lo;
+    if (cnt == 0) {
+        win_unique[w] = 0;
+        return;
+    }
+    const int cls = cnt <= kTinyCap ? 0 : cnt <= kSmallCap ? 1 : cnt <= kMediumCap ? 2 : 3;
+    lists[(int64_t)cls * n_win + atomicAdd(&counts[cls], 1)] = (int32_t)w;
 }
 
-// Small and medium classes.  One workgroup per window; windows of another class return at once.
-template <int THREADS, int CAP, int MIN_EXCL>
+// Tiny, small and medium classes: one workgroup per listed window.
+template <int THREADS, int CAP>
 __global__ __launch_bounds__(THREADS) void sgt_window_lds_kernel(
-    int32_t n_rows, int32_t win_h, const int32_t *rp, const int32_t *ci, int32_t *edge_to_col,
-    int32_t *tmp_clean, int32_t *win_unique)
+    int32_t n_rows, int32_t win_h, const int32_t *__restrict__ win_list, const int32_t *__restrict__ rp,
+    const int32_t *__restrict__ ci, int32_t *__restrict__ edge_to_col, int32_t *__restrict__ tmp_clean,
+    int32_t *__restrict__ win_unique)
 {
     __shared__ int32_t s_key[CAP];
     __shared__ int32_t s_rank[CAP];
-    __shared__ int s_tmp[THREADS / kWave + 1];
+    __shared__ int s_tmp[(THREADS + kWave - 1) / kWave + 1];
 
-    const int64_t w = blockIdx.x;
+    const int64_t w = win_list[blockIdx.x];
     int32_t lo, hi;
     window_edge_range(rp, n_rows, win_h, w, &lo, &hi);
-    const int cnt = hi - lo;
-    if (cnt <= MIN_EXCL || cnt > CAP) {
-        if (cnt == 0 && MIN_EXCL == 0 && threadIdx.x == 0) win_unique[w] = 0;
-        return;
-    }
+    const int cnt = hi - lo;          // 1 <= cnt <= CAP by classification
     int n_pad = 2;
     while (n_pad < cnt) n_pad <<= 1;
 
@@ -211,72 +262,120 @@ __global__ __launch_bounds__(THREADS) void sgt_window_lds_kernel(
 }
 
 // Large class: bitmap over the column space, one workgroup per window.  `bitmap` must be zero on
-// entry; `prefix` is plain scratch; both hold n_words entries per workgroup.
+// entry; `prefix` is plain scratch; both hold n_words entries per workgroup.  The words are split
+// into one contiguous range per wavefront, so every pass over them is coalesced and only one
+// workgroup-wide scan (of the 16 wavefront totals) is needed.
 constexpr int kBitmapThreads = 1024;
+constexpr int kBitmapWaves = kBitmapThreads / kWave;
+constexpr int kEdgeUnroll = 4;
 
 __global__ __launch_bounds__(kBitmapThreads) void sgt_window_bitmap_kernel(
-    int32_t n_rows, int32_t win_h, int64_t n_words, const int32_t *large_list, const int32_t *rp,
-    const int32_t *ci, uint32_t *bitmap, int32_t *prefix, int32_t *edge_to_col, int32_t *tmp_clean,
-    int32_t *win_unique)
+    int32_t n_rows, int32_t win_h, int64_t n_words, const int32_t *__restrict__ large_list,
+    const int32_t *__restrict__ rp, const int32_t *__restrict__ ci, uint32_t *bitmap, int32_t *prefix,
+    int32_t *__restrict__ edge_to_col, int32_t *__restrict__ tmp_clean, int32_t *__restrict__ win_unique)
 {
-    __shared__ int s_tmp[kBitmapThreads / kWave + 1];
+    __shared__ int s_tmp[kBitmapWaves + 1];
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x >> 6;
     const int64_t w = large_list[blockIdx.x];
     uint32_t *bm = bitmap + (int64_t)blockIdx.x * n_words;
     int32_t *pf = prefix + (int64_t)blockIdx.x * n_words;
     int32_t lo, hi;
     window_edge_range(rp, n_rows, win_h, w, &lo, &hi);
 
-    for (int64_t e = lo + threadIdx.x; e < hi; e += kBitmapThreads) {
-        uint32_t c = (uint32_t)ci[e];
-        atomicOr(&bm[c >> 5], 1u << (c & 31));
+    // 1. one bit per edge
+    for (int64_t e0 = lo + threadIdx.x; e0 < hi; e0 += (int64_t)kBitmapThreads * kEdgeUnroll) {
+        uint32_t c[kEdgeUnroll];
+#pragma unroll
+        for (int u = 0; u < kEdgeUnroll; ++u) {
+            int64_t e = e0 + (int64_t)u * kBitmapThreads;
+            c[u] = e < hi ? (uint32_t)ci[e] : 0xFFFFFFFFu;
+        }
+#pragma unroll
+        for (int u = 0; u < kEdgeUnroll; ++u)
+            if (c[u] != 0xFFFFFFFFu) atomicOr(&bm[c[u] >> 5], 1u << (c[u] & 31));
     }
+    // All atomics of the workgroup are complete (fence + barrier) before any thread reads the bitmap;
+    // nobody read it earlier in this kernel, so no stale copy can sit in the CU's cache.
     __threadfence();
     __syncthreads();
+    __threadfence();
 
-    const int64_t wpt = (n_words + kBitmapThreads - 1) / kBitmapThreads;
-    const int64_t w0 = (int64_t)threadIdx.x * wpt;
-    int local = 0;
-    for (int64_t k = w0; k < w0 + wpt && k < n_words; ++k)
-        local += __popc(__hip_atomic_load(&bm[k], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+    // 2. per-wavefront popcount of its word range, then the offsets of the wavefronts
+    int64_t wpw = (n_words + kBitmapWaves - 1) / kBitmapWaves;
+    wpw = (wpw + kWave - 1) / kWave * kWave;
+    int64_t k_begin = (int64_t)wave * wpw;
+    if (k_begin > n_words) k_begin = n_words;
+    int64_t k_end = k_begin + wpw;
+    if (k_end > n_words) k_end = n_words;
+    int cnt = 0;
+    for (int64_t k = k_begin + lane; k < k_end; k += kWave) cnt += __popc(bm[k]);
+#pragma unroll
+    for (int off = 1; off < kWave; off <<= 1) cnt += __shfl_xor(cnt, off, kWave);
     int total;
-    int run = block_exclusive_scan(local, s_tmp, &total);
-    for (int64_t k = w0; k < w0 + wpt && k < n_words; ++k) {
-        uint32_t bits = __hip_atomic_load(&bm[k], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        pf[k] = run;
-        int pos = run;
+    int wave_off = block_exclusive_scan(lane == 0 ? cnt : 0, s_tmp, &total);
+    wave_off = __shfl(wave_off, 0, kWave);
+
+    // 3. prefix of every word, and the unique list itself (bit positions in ascending order)
+    int carry = wave_off;
+    for (int64_t k0 = k_begin; k0 < k_end; k0 += kWave) {
+        const int64_t k = k0 + lane;
+        uint32_t bits = k < k_end ? bm[k] : 0u;
+        const int p = __popc(bits);
+        const int incl = wave_inclusive_scan(p);
+        int pos = carry + incl - p;
+        if (k < k_end) pf[k] = pos;
         while (bits) {
             int b = __ffs(bits) - 1;
             bits &= bits - 1;
             tmp_clean[lo + pos] = (int32_t)(k * 32 + b);
             ++pos;
         }
-        run = pos;
+        carry += __shfl(incl, kWave - 1, kWave);
     }
     if (threadIdx.x == 0) win_unique[w] = total;
     __threadfence();
     __syncthreads();
+    __threadfence();
 
-    for (int64_t e = lo + threadIdx.x; e < hi; e += kBitmapThreads) {
-        uint32_t c = (uint32_t)ci[e];
-        uint32_t bits = __hip_atomic_load(&bm[c >> 5], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        int32_t base = __hip_atomic_load(&pf[c >> 5], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        edge_to_col[e] = base + __popc(bits & ((1u << (c & 31)) - 1u));
+    // 4. rank of every edge's column
+    for (int64_t e0 = lo + threadIdx.x; e0 < hi; e0 += (int64_t)kBitmapThreads * kEdgeUnroll) {
+        uint32_t c[kEdgeUnroll], bits[kEdgeUnroll];
+        int32_t base[kEdgeUnroll];
+#pragma unroll
+        for (int u = 0; u < kEdgeUnroll; ++u) {
+            int64_t e = e0 + (int64_t)u * kBitmapThreads;
+            c[u] = e < hi ? (uint32_t)ci[e] : 0u;
+        }
+#pragma unroll
+        for (int u = 0; u < kEdgeUnroll; ++u) {
+            bits[u] = bm[c[u] >> 5];
+            base[u] = pf[c[u] >> 5];
+        }
+#pragma unroll
+        for (int u = 0; u < kEdgeUnroll; ++u) {
+            int64_t e = e0 + (int64_t)u * kBitmapThreads;
+            if (e < hi) edge_to_col[e] = base[u] + __popc(bits[u] & ((1u << (c[u] & 31)) - 1u));
+        }
     }
 }
 
-// Packs the per-window lists into col_to_row and derives win_partition (ceil(U_w / tile_w)).
-__global__ __launch_bounds__(256) void sgt_pack_kernel(int32_t n_rows, int32_t win_h, int32_t tile_w,
-                                                       const int32_t *rp, const int32_t *tmp_clean,
-                                                       const int32_t *win_unique_ptr, int32_t *col_to_row,
-                                                       int32_t *win_partition,
-                                                       unsigned long long *total_tiles)
+// Packs the per-window lists into col_to_row, derives win_partition (ceil(U_w / tile_w)) and the
+// default per-window path, and counts tiles / tile-path windows / their edges.
+__global__ __launch_bounds__(kWave) void sgt_pack_kernel(int32_t n_rows, int32_t win_h, int32_t tile_w,
+                                                         const int32_t *__restrict__ rp,
+                                                         const int32_t *__restrict__ tmp_clean,
+                                                         const int32_t *__restrict__ win_unique_ptr,
+                                                         int32_t *__restrict__ col_to_row,
+                                                         int32_t *__restrict__ win_partition,
+                                                         unsigned long long *total_tiles)
 {
     const int64_t w = blockIdx.x;
     int32_t lo, hi;
     window_edge_range(rp, n_rows, win_h, w, &lo, &hi);
     const int32_t u0 = win_unique_ptr[w];
     const int32_t uw = win_unique_ptr[w + 1] - u0;
-    for (int k = threadIdx.x; k < uw; k += blockDim.x) col_to_row[u0 + k] = tmp_clean[lo + k];
+    for (int k = threadIdx.x; k < uw; k += kWave) col_to_row[u0 + k] = tmp_clean[lo + k];
     if (threadIdx.x == 0) {
         int32_t tiles = (int32_t)(((int64_t)uw + tile_w - 1) / tile_w);
         win_partition[w] = tiles;
@@ -304,9 +403,7 @@ __global__ void seg_fill_kernel(int32_t n_rows, const int32_t *rp, const int32_t
                                 int32_t *long_slot_ptr, int64_t n_long)
 {
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= n_rows) {
-        return;
-    }
+    if (i >= n_rows) return;
     int32_t s0 = seg_off[i], segs = seg_off[i + 1] - s0;
     int32_t e0 = rp[i];
     bool is_long = segs > 1;
@@ -336,7 +433,10 @@ __global__ void choose_path_kernel(int32_t n_rows, int32_t win_h, int64_t n_win,
     int32_t nnz_w = hi - lo;
     bool tile = false;
     if (policy == TCG_POLICY_TILE) tile = uw > 0;
-    else if (policy == TCG_POLICY_AUTO) tile = win_h == 16 && uw > 0 && (float)nnz_w >= min_reuse * (float)uw;
+    else if (policy == TCG_POLICY_AUTO)
+        // Windows with shared neighbours, but not hub windows: a tile kernel workgroup walks its
+        // window's edges once per 32-column chunk, which only pays for compact windows.
+        tile = win_h == 16 && uw > 0 && uw <= kTileMaxUnique && (float)nnz_w >= min_reuse * (float)uw;
     win_path[w] = tile ? 1 : 0;
     if (tile) {
         atomicAdd(&counts[0], 1ull);
@@ -344,74 +444,67 @@ __global__ void choose_path_kernel(int32_t n_rows, int32_t win_h, int64_t n_win,
     }
 }
 
-template <typename T>
-struct DevBuf {  // frees on scope exit unless released
-    T *p = nullptr;
-    ~DevBuf() { if (p) (void)hipFree(p); }
-    T *release() { T *q = p; p = nullptr; return q; }
+// One device allocation carved into 256-byte aligned pieces.
+struct Arena {
+    char *base = nullptr;
+    size_t size = 0, used = 0;
+    static size_t align(size_t b) { return (b + 255) & ~(size_t)255; }
+    void want(size_t bytes) { size += align(std::max<size_t>(bytes, 4)); }
+    int commit()
+    {
+        hipError_t e = hipMalloc(reinterpret_cast<void **>(&base), std::max<size_t>(size, 256));
+        if (e != hipSuccess) {
+            (void)hipGetLastError();
+            set_hip_error(e, "hipMalloc");
+            base = nullptr;
+            return TCG_ENOMEM;
+        }
+        return TCG_OK;
+    }
+    template <typename T> T *take(int64_t count)
+    {
+        T *p = reinterpret_cast<T *>(base + used);
+        used += align(std::max<size_t>((size_t)std::max<int64_t>(count, 0) * sizeof(T), 4));
+        return p;
+    }
+};
+
+struct ScopedFree {  // frees on scope exit
+    void *p = nullptr;
+    ~ScopedFree() { if (p) (void)hipFree(p); }
 };
 
 }  // namespace
 
-int exclusive_scan_i32(const int32_t *d_in, int32_t *d_out, int64_t n, hipStream_t s)
-{
-    hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(kScanThreads), 0, s, d_in, d_out, n);
-    return launch_status("scan_kernel");
-}
+int64_t scan_workspace_elems(int64_t n) { return ceil_div(std::max<int64_t>(n, 1), kScanBlock) + 2; }
 
-static int build_gather_plan(tcg_meta *m, hipStream_t s)
+int exclusive_scan_i32(const int32_t *d_in, int32_t *d_out, int64_t n, int32_t *d_work, hipStream_t s)
 {
-    const int32_t n = m->n_rows;
-    DevBuf<int32_t> seg_off, long_off, slot_off;
-    TCG_TRY(dev_alloc(&seg_off.p, (int64_t)n + 1));
-    TCG_TRY(dev_alloc(&long_off.p, (int64_t)n + 1));
-    TCG_TRY(dev_alloc(&slot_off.p, (int64_t)n + 1));
-    if (n > 0) {
-        hipLaunchKernelGGL(seg_count_kernel, dim3((unsigned)ceil_div(n, 256)), dim3(256), 0, s, n,
-                           m->d_row_ptr, seg_off.p, long_off.p, slot_off.p);
-        TCG_TRY(launch_status("seg_count_kernel"));
+    if (n <= kScanBlock) {
+        hipLaunchKernelGGL(scan_single_kernel, dim3(1), dim3(1024), 0, s, d_in, d_out, n);
+        return launch_status("scan_single_kernel");
     }
-    TCG_TRY(exclusive_scan_i32(seg_off.p, seg_off.p, n, s));
-    TCG_TRY(exclusive_scan_i32(long_off.p, long_off.p, n, s));
-    TCG_TRY(exclusive_scan_i32(slot_off.p, slot_off.p, n, s));
-    int32_t totals[3];
-    TCG_HIP(hipMemcpyAsync(&totals[0], seg_off.p + n, sizeof(int32_t), hipMemcpyDeviceToHost, s));
-    TCG_HIP(hipMemcpyAsync(&totals[1], long_off.p + n, sizeof(int32_t), hipMemcpyDeviceToHost, s));
-    TCG_HIP(hipMemcpyAsync(&totals[2], slot_off.p + n, sizeof(int32_t), hipMemcpyDeviceToHost, s));
-    TCG_HIP(hipStreamSynchronize(s));
-    m->n_seg = totals[0];
-    m->n_long = totals[1];
-    m->n_slots = totals[2];
-    TCG_TRY(dev_alloc(&m->d_seg_row, m->n_seg));
-    TCG_TRY(dev_alloc(&m->d_seg_ebeg, m->n_seg));
-    TCG_TRY(dev_alloc(&m->d_seg_dst, m->n_seg));
-    TCG_TRY(dev_alloc(&m->d_long_row, m->n_long));
-    TCG_TRY(dev_alloc(&m->d_long_slot_ptr, m->n_long + 1));
-    if (n > 0) {
-        hipLaunchKernelGGL(seg_fill_kernel, dim3((unsigned)ceil_div(n, 256)), dim3(256), 0, s, n,
-                           m->d_row_ptr, seg_off.p, long_off.p, slot_off.p, m->d_seg_row, m->d_seg_ebeg,
-                           m->d_seg_dst, m->d_long_row, m->d_long_slot_ptr, m->n_long);
-        TCG_TRY(launch_status("seg_fill_kernel"));
-    }
-    TCG_HIP(hipStreamSynchronize(s));  // temporaries are freed on return
-    return TCG_OK;
+    const int64_t nb = ceil_div(n, kScanBlock);
+    hipLaunchKernelGGL(scan_block_sum_kernel, dim3((unsigned)nb), dim3(kScanThreads), 0, s, d_in, n, d_work);
+    hipLaunchKernelGGL(scan_single_kernel, dim3(1), dim3(1024), 0, s, d_work, d_work, nb);
+    hipLaunchKernelGGL(scan_apply_kernel, dim3((unsigned)nb), dim3(kScanThreads), 0, s, d_in, d_out, n, d_work, nb);
+    return launch_status("scan kernels");
 }
 
 int choose_paths(tcg_meta *m, tcg_policy policy, float min_reuse, hipStream_t s)
 {
     if (policy == TCG_POLICY_TILE && m->win_h != 16) return TCG_EINVAL;
     if (min_reuse <= 0.f) min_reuse = kDefaultMinReuse;
-    DevBuf<unsigned long long> counts;
-    TCG_TRY(dev_alloc(&counts.p, 2));
-    TCG_HIP(hipMemsetAsync(counts.p, 0, 2 * sizeof(unsigned long long), s));
+    unsigned long long *counts = m->d_counters + 2;   // [2], [3]: tile windows, their edges
+    TCG_HIP(hipMemsetAsync(counts, 0, 2 * sizeof(unsigned long long), s));
     if (m->n_win > 0) {
         hipLaunchKernelGGL(choose_path_kernel, dim3((unsigned)ceil_div(m->n_win, 256)), dim3(256), 0, s,
                            m->n_rows, m->win_h, m->n_win, m->d_row_ptr, m->d_win_unique_ptr, (int)policy,
-                           min_reuse, m->d_win_path, counts.p);
+                           min_reuse, m->d_win_path, counts);
         TCG_TRY(launch_status("choose_path_kernel"));
     }
     unsigned long long h[2];
-    TCG_HIP(hipMemcpyAsync(h, counts.p, sizeof(h), hipMemcpyDeviceToHost, s));
+    TCG_HIP(hipMemcpyAsync(h, counts, sizeof(h), hipMemcpyDeviceToHost, s));
     TCG_HIP(hipStreamSynchronize(s));
     m->policy = policy;
     m->min_reuse = min_reuse;
@@ -425,100 +518,161 @@ int sgt_build_impl(tcg_meta *m, int validate, hipStream_t s)
     const int32_t n = m->n_rows;
     const int64_t nnz = m->nnz;
     const int64_t n_win = m->n_win;
+    const int64_t scan_elems = scan_workspace_elems(std::max<int64_t>(n, n_win));
+
+    // Arena 0 (kept): the translated graph except col_to_row, the path flags, a few counters.
+    Arena keep;
+    keep.want(n_win * 4);             // win_partition
+    keep.want((n_win + 1) * 4);       // win_unique_ptr
+    keep.want(nnz * 4);               // edge_to_col
+    keep.want(n_win);                 // win_path
+    keep.want(8 * 8);                 // counters
+    TCG_TRY(keep.commit());
+    m->owned[m->n_owned++] = keep.base;
+    m->d_win_partition = keep.take<int32_t>(n_win);
+    m->d_win_unique_ptr = keep.take<int32_t>(n_win + 1);
+    m->d_edge_to_col = keep.take<int32_t>(nnz);
+    m->d_win_path = keep.take<uint8_t>(n_win);
+    m->d_counters = keep.take<unsigned long long>(8);
+
+    // Temporaries of the build.
+    Arena tmp;
+    tmp.want(nnz * 4);                // tmp_clean
+    tmp.want((n_win + 1) * 4);        // win_unique
+    tmp.want(4 * n_win * 4);          // class lists
+    for (int i = 0; i < 3; ++i) tmp.want(((int64_t)n + 1) * 4);   // segment counts / offsets
+    tmp.want(scan_elems * 4);         // scan workspace
+    tmp.want(16 * 4);                 // class counts + validation flag
+    TCG_TRY(tmp.commit());
+    ScopedFree tmp_guard{tmp.base};
+    int32_t *tmp_clean = tmp.take<int32_t>(nnz);
+    int32_t *win_unique = tmp.take<int32_t>(n_win + 1);
+    int32_t *lists = tmp.take<int32_t>(4 * n_win);
+    int32_t *seg_off = tmp.take<int32_t>((int64_t)n + 1);
+    int32_t *long_off = tmp.take<int32_t>((int64_t)n + 1);
+    int32_t *slot_off = tmp.take<int32_t>((int64_t)n + 1);
+    int32_t *scan_work = tmp.take<int32_t>(scan_elems);
+    int *small_ints = tmp.take<int>(16);   // [0..3] class counts, [8] validation flag
+    TCG_HIP(hipMemsetAsync(small_ints, 0, 16 * sizeof(int), s));
+    TCG_HIP(hipMemsetAsync(m->d_counters, 0, 8 * sizeof(unsigned long long), s));
 
     if (validate) {
-        DevBuf<int> flag;
-        TCG_TRY(dev_alloc(&flag.p, 1));
-        TCG_HIP(hipMemsetAsync(flag.p, 0, sizeof(int), s));
-        hipLaunchKernelGGL(validate_csr_kernel, dim3((unsigned)std::min<int64_t>(ceil_div(n + 1, 256), 4096)),
-                           dim3(256), 0, s, n, m->n_cols, nnz, m->d_row_ptr, m->d_col_idx, flag.p);
+        int *flag = small_ints + 8;
+        hipLaunchKernelGGL(validate_csr_kernel, dim3((unsigned)std::min<int64_t>(ceil_div((int64_t)n + 1, 256), 4096)),
+                           dim3(256), 0, s, n, nnz, m->d_row_ptr, flag);
         TCG_TRY(launch_status("validate_csr_kernel"));
         int h = 0;
-        TCG_HIP(hipMemcpyAsync(&h, flag.p, sizeof(int), hipMemcpyDeviceToHost, s));
+        TCG_HIP(hipMemcpyAsync(&h, flag, sizeof(int), hipMemcpyDeviceToHost, s));
         TCG_HIP(hipStreamSynchronize(s));
         if (h) return TCG_ECSR;  // do not touch col_idx through a broken row_ptr
         if (nnz > 0) {
             hipLaunchKernelGGL(validate_cols_kernel, dim3((unsigned)std::min<int64_t>(ceil_div(nnz, 256), 8192)),
-                               dim3(256), 0, s, m->n_cols, nnz, m->d_col_idx, flag.p);
+                               dim3(256), 0, s, m->n_cols, nnz, m->d_col_idx, flag);
             TCG_TRY(launch_status("validate_cols_kernel"));
+            TCG_HIP(hipMemcpyAsync(&h, flag, sizeof(int), hipMemcpyDeviceToHost, s));
+            TCG_HIP(hipStreamSynchronize(s));
+            if (h) return TCG_ECSR;
         }
-        TCG_HIP(hipMemcpyAsync(&h, flag.p, sizeof(int), hipMemcpyDeviceToHost, s));
-        TCG_HIP(hipStreamSynchronize(s));
-        if (h) return TCG_ECSR;
     }
 
-    TCG_TRY(dev_alloc(&m->d_win_partition, n_win));
-    TCG_TRY(dev_alloc(&m->d_win_unique_ptr, n_win + 1));
-    TCG_TRY(dev_alloc(&m->d_edge_to_col, nnz));
-    TCG_TRY(dev_alloc(&m->d_win_path, n_win));
-
-    DevBuf<int32_t> tmp_clean, win_unique, large_list;
-    DevBuf<int> n_large_dev;
-    DevBuf<unsigned long long> tiles_dev;
-    TCG_TRY(dev_alloc(&tmp_clean.p, nnz));
-    TCG_TRY(dev_alloc(&win_unique.p, n_win + 1));
-    TCG_TRY(dev_alloc(&large_list.p, n_win));
-    TCG_TRY(dev_alloc(&n_large_dev.p, 1));
-    TCG_TRY(dev_alloc(&tiles_dev.p, 1));
-    TCG_HIP(hipMemsetAsync(n_large_dev.p, 0, sizeof(int), s));
-    TCG_HIP(hipMemsetAsync(tiles_dev.p, 0, sizeof(unsigned long long), s));
-
-    int n_large = 0;
+    // Window classes and segment counts (both depend on row_ptr only).
     if (n_win > 0) {
-        hipLaunchKernelGGL(collect_large_kernel, dim3((unsigned)ceil_div(n_win, 256)), dim3(256), 0, s, n,
-                           m->win_h, n_win, m->d_row_ptr, large_list.p, n_large_dev.p);
-        TCG_TRY(launch_status("collect_large_kernel"));
-        hipLaunchKernelGGL((sgt_window_lds_kernel<256, kSmallCap, 0>), dim3((unsigned)n_win), dim3(256), 0, s,
-                           n, m->win_h, m->d_row_ptr, m->d_col_idx, m->d_edge_to_col, tmp_clean.p,
-                           win_unique.p);
-        TCG_TRY(launch_status("sgt_window_lds_kernel<small>"));
-        hipLaunchKernelGGL((sgt_window_lds_kernel<1024, kMediumCap, kSmallCap>), dim3((unsigned)n_win),
-                           dim3(1024), 0, s, n, m->win_h, m->d_row_ptr, m->d_col_idx, m->d_edge_to_col,
-                           tmp_clean.p, win_unique.p);
-        TCG_TRY(launch_status("sgt_window_lds_kernel<medium>"));
-        TCG_HIP(hipMemcpyAsync(&n_large, n_large_dev.p, sizeof(int), hipMemcpyDeviceToHost, s));
-        TCG_HIP(hipStreamSynchronize(s));
+        hipLaunchKernelGGL(classify_windows_kernel, dim3((unsigned)ceil_div(n_win, 256)), dim3(256), 0, s, n,
+                           m->win_h, n_win, m->d_row_ptr, lists, small_ints, win_unique);
+        TCG_TRY(launch_status("classify_windows_kernel"));
     }
-    if (n_large > 0) {
+    if (n > 0) {
+        hipLaunchKernelGGL(seg_count_kernel, dim3((unsigned)ceil_div(n, 256)), dim3(256), 0, s, n, m->d_row_ptr,
+                           seg_off, long_off, slot_off);
+        TCG_TRY(launch_status("seg_count_kernel"));
+    }
+    TCG_TRY(exclusive_scan_i32(seg_off, seg_off, n, scan_work, s));
+    TCG_TRY(exclusive_scan_i32(long_off, long_off, n, scan_work, s));
+    TCG_TRY(exclusive_scan_i32(slot_off, slot_off, n, scan_work, s));
+    int h_cls[4] = {0, 0, 0, 0};
+    int32_t h_plan[3] = {0, 0, 0};
+    TCG_HIP(hipMemcpyAsync(h_cls, small_ints, sizeof(h_cls), hipMemcpyDeviceToHost, s));
+    TCG_HIP(hipMemcpyAsync(&h_plan[0], seg_off + n, sizeof(int32_t), hipMemcpyDeviceToHost, s));
+    TCG_HIP(hipMemcpyAsync(&h_plan[1], long_off + n, sizeof(int32_t), hipMemcpyDeviceToHost, s));
+    TCG_HIP(hipMemcpyAsync(&h_plan[2], slot_off + n, sizeof(int32_t), hipMemcpyDeviceToHost, s));
+    TCG_HIP(hipStreamSynchronize(s));                                           // sync 1
+    m->n_seg = h_plan[0];
+    m->n_long = h_plan[1];
+    m->n_slots = h_plan[2];
+
+    // Arena 1 (kept): the gather plan.
+    Arena plan;
+    plan.want(m->n_seg * 4);
+    plan.want(m->n_seg * 4);
+    plan.want(m->n_seg * 4);
+    plan.want(m->n_long * 4);
+    plan.want((m->n_long + 1) * 4);
+    TCG_TRY(plan.commit());
+    m->owned[m->n_owned++] = plan.base;
+    m->d_seg_row = plan.take<int32_t>(m->n_seg);
+    m->d_seg_ebeg = plan.take<int32_t>(m->n_seg);
+    m->d_seg_dst = plan.take<int32_t>(m->n_seg);
+    m->d_long_row = plan.take<int32_t>(m->n_long);
+    m->d_long_slot_ptr = plan.take<int32_t>(m->n_long + 1);
+    if (n > 0) {
+        hipLaunchKernelGGL(seg_fill_kernel, dim3((unsigned)ceil_div(n, 256)), dim3(256), 0, s, n, m->d_row_ptr,
+                           seg_off, long_off, slot_off, m->d_seg_row, m->d_seg_ebeg, m->d_seg_dst, m->d_long_row,
+                           m->d_long_slot_ptr, m->n_long);
+        TCG_TRY(launch_status("seg_fill_kernel"));
+    }
+
+    // Per-window translation, one launch per size class.
+    if (h_cls[0] > 0)
+        hipLaunchKernelGGL((sgt_window_lds_kernel<kWave, kTinyCap>), dim3((unsigned)h_cls[0]), dim3(kWave), 0, s, n,
+                           m->win_h, lists, m->d_row_ptr, m->d_col_idx, m->d_edge_to_col, tmp_clean, win_unique);
+    if (h_cls[1] > 0)
+        hipLaunchKernelGGL((sgt_window_lds_kernel<256, kSmallCap>), dim3((unsigned)h_cls[1]), dim3(256), 0, s, n,
+                           m->win_h, lists + n_win, m->d_row_ptr, m->d_col_idx, m->d_edge_to_col, tmp_clean,
+                           win_unique);
+    if (h_cls[2] > 0)
+        hipLaunchKernelGGL((sgt_window_lds_kernel<256, kMediumCap>), dim3((unsigned)h_cls[2]), dim3(256), 0, s, n,
+                           m->win_h, lists + 2 * n_win, m->d_row_ptr, m->d_col_idx, m->d_edge_to_col, tmp_clean,
+                           win_unique);
+    TCG_TRY(launch_status("sgt_window_lds_kernel"));
+    ScopedFree bitmap_guard;
+    if (h_cls[3] > 0) {
+        const int64_t n_large = h_cls[3];
         const int64_t n_words = ceil_div(m->n_cols, 32);
-        const int64_t budget_words = (int64_t)(64ll << 20) / 4;  // 64 MiB per scratch array
-        int64_t batch = std::max<int64_t>(1, std::min<int64_t>(n_large, budget_words / n_words));
-        DevBuf<uint32_t> bitmap;
-        DevBuf<int32_t> prefix;
-        TCG_TRY(dev_alloc(&bitmap.p, batch * n_words));
-        TCG_TRY(dev_alloc(&prefix.p, batch * n_words));
+        const int64_t budget_words = (int64_t)(128ll << 20) / 4;  // 128 MiB per scratch array
+        const int64_t batch = std::max<int64_t>(1, std::min<int64_t>(n_large, budget_words / n_words));
+        uint32_t *bitmap = nullptr;
+        TCG_TRY(dev_alloc(&bitmap, 2 * batch * n_words));
+        bitmap_guard.p = bitmap;
+        int32_t *prefix = reinterpret_cast<int32_t *>(bitmap + batch * n_words);
         for (int64_t b0 = 0; b0 < n_large; b0 += batch) {
-            int64_t nb = std::min<int64_t>(batch, n_large - b0);
-            TCG_HIP(hipMemsetAsync(bitmap.p, 0, (size_t)(nb * n_words) * sizeof(uint32_t), s));
+            const int64_t nb = std::min<int64_t>(batch, n_large - b0);
+            TCG_HIP(hipMemsetAsync(bitmap, 0, (size_t)(nb * n_words) * sizeof(uint32_t), s));
             hipLaunchKernelGGL(sgt_window_bitmap_kernel, dim3((unsigned)nb), dim3(kBitmapThreads), 0, s, n,
-                               m->win_h, n_words, large_list.p + b0, m->d_row_ptr, m->d_col_idx, bitmap.p,
-                               prefix.p, m->d_edge_to_col, tmp_clean.p, win_unique.p);
+                               m->win_h, n_words, lists + 3 * n_win + b0, m->d_row_ptr, m->d_col_idx, bitmap,
+                               prefix, m->d_edge_to_col, tmp_clean, win_unique);
             TCG_TRY(launch_status("sgt_window_bitmap_kernel"));
         }
-        TCG_HIP(hipStreamSynchronize(s));  // scratch is freed on scope exit
     }
 
-    TCG_TRY(exclusive_scan_i32(win_unique.p, m->d_win_unique_ptr, n_win, s));
+    TCG_TRY(exclusive_scan_i32(win_unique, m->d_win_unique_ptr, n_win, scan_work, s));
     int32_t total_unique = 0;
-    TCG_HIP(hipMemcpyAsync(&total_unique, m->d_win_unique_ptr + n_win, sizeof(int32_t),
-                           hipMemcpyDeviceToHost, s));
-    TCG_HIP(hipStreamSynchronize(s));
+    TCG_HIP(hipMemcpyAsync(&total_unique, m->d_win_unique_ptr + n_win, sizeof(int32_t), hipMemcpyDeviceToHost, s));
+    TCG_HIP(hipStreamSynchronize(s));                                           // sync 2
     m->total_unique = total_unique;
+
     TCG_TRY(dev_alloc(&m->d_col_to_row, m->total_unique));
+    m->owned[m->n_owned++] = m->d_col_to_row;
     if (n_win > 0) {
-        hipLaunchKernelGGL(sgt_pack_kernel, dim3((unsigned)n_win), dim3(256), 0, s, n, m->win_h, m->tile_w,
-                           m->d_row_ptr, tmp_clean.p, m->d_win_unique_ptr, m->d_col_to_row,
-                           m->d_win_partition, tiles_dev.p);
+        hipLaunchKernelGGL(sgt_pack_kernel, dim3((unsigned)n_win), dim3(kWave), 0, s, n, m->win_h, m->tile_w,
+                           m->d_row_ptr, tmp_clean, m->d_win_unique_ptr, m->d_col_to_row, m->d_win_partition,
+                           m->d_counters);
         TCG_TRY(launch_status("sgt_pack_kernel"));
     }
     unsigned long long tiles = 0;
-    TCG_HIP(hipMemcpyAsync(&tiles, tiles_dev.p, sizeof(tiles), hipMemcpyDeviceToHost, s));
-    TCG_HIP(hipStreamSynchronize(s));
+    TCG_HIP(hipMemcpyAsync(&tiles, m->d_counters, sizeof(tiles), hipMemcpyDeviceToHost, s));
+    TCG_TRY(choose_paths(m, TCG_POLICY_AUTO, 0.f, s));                          // sync 3 (also covers `tiles`)
     m->total_tiles = (int64_t)tiles;
-
-    TCG_TRY(build_gather_plan(m, s));
-    TCG_TRY(choose_paths(m, TCG_POLICY_AUTO, 0.f, s));
-    return TCG_OK;
+    return TCG_OK;   // temporaries are freed by the guards; the stream is idle here
 }
 
 }  // namespace tcg

@@ -52,55 +52,59 @@ __global__ __launch_bounds__(kBlock) void spmm_gather_kernel(
 #pragma unroll
         for (int k = 0; k < VEC; ++k) acc[c][k] = 0.f;
 
-    int32_t cn[UNROLL];
-    float wn[UNROLL];
-#pragma unroll
-    for (int u = 0; u < UNROLL; ++u) {
-        cn[u] = 0;
-        wn[u] = 1.f;
-        if (eb + u < ee) {
-            cn[u] = col_idx[eb + u];
-            if (HAS_W) wn[u] = w[eb + u];
-        }
-    }
-
-    for (int32_t e = eb; e < ee; e += UNROLL) {
-        uint4 raw[UNROLL][NCH];
-        float wc[UNROLL];
+    if (eb < ee) {
+        // Ids (and edge values) are always read from a clamped, valid position, so these loads carry
+        // no predicate and are issued back to back; only the row loads of a ragged tail are masked.
+        const int32_t last = ee - 1;
+        const uint32_t ldx32 = (uint32_t)ldx_bytes;
+        int32_t cn[UNROLL];
+        float wn[UNROLL];
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) {
-            wc[u] = wn[u];
-            if (e + u < ee) {
-                const char *xr = X + (int64_t)cn[u] * ldx_bytes;
+            const int32_t en = min(eb + u, last);
+            cn[u] = col_idx[en];
+            wn[u] = HAS_W ? w[en] : 1.f;
+        }
+        for (int32_t e = eb; e < ee; e += UNROLL) {
+            // Next iteration's ids go out first: they are older than the row loads below, so the
+            // one wait for the rows also covers them and their latency hides under the rows'.
+            int32_t cnext[UNROLL];
+            float wnext[UNROLL];
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) {
+                const int32_t en = min(e + UNROLL + u, last);
+                cnext[u] = col_idx[en];
+                wnext[u] = HAS_W ? w[en] : 1.f;
+            }
+            uint4 raw[UNROLL][NCH];
+            float wc[UNROLL];
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) {
+                wc[u] = (e + u < ee) ? wn[u] : 0.f;
+                const char *xr = X + (uint64_t)(uint32_t)cn[u] * ldx32;
 #pragma unroll
                 for (int c = 0; c < NCH; ++c) {
-                    int chunk = lane + c * G;
-                    if (chunk < n_chunks) raw[u][c] = *reinterpret_cast<const uint4 *>(xr + (int64_t)chunk * 16);
+                    const int chunk = lane + c * G;
+                    raw[u][c] = make_uint4(0, 0, 0, 0);
+                    if (e + u < ee && chunk < n_chunks)
+                        raw[u][c] = *reinterpret_cast<const uint4 *>(xr + (uint32_t)chunk * 16u);
                 }
             }
-        }
 #pragma unroll
-        for (int u = 0; u < UNROLL; ++u) {
-            int32_t en = e + UNROLL + u;
-            if (en < ee) {
-                cn[u] = col_idx[en];
-                if (HAS_W) wn[u] = w[en];
+            for (int u = 0; u < UNROLL; ++u) {
+                cn[u] = cnext[u];
+                wn[u] = wnext[u];
             }
-        }
 #pragma unroll
-        for (int u = 0; u < UNROLL; ++u) {
-            if (e + u < ee) {
+            for (int u = 0; u < UNROLL; ++u) {
 #pragma unroll
                 for (int c = 0; c < NCH; ++c) {
-                    int chunk = lane + c * G;
-                    if (chunk < n_chunks) {
-                        float v[VEC];
-                        unpack16<DT>(raw[u][c], v);
+                    float v[VEC];
+                    unpack16<DT>(raw[u][c], v);   // masked-off loads left zeros: they add nothing
 #pragma unroll
-                        for (int k = 0; k < VEC; ++k) {
-                            if (HAS_W) acc[c][k] = fmaf(wc[u], v[k], acc[c][k]);
-                            else acc[c][k] += v[k];
-                        }
+                    for (int k = 0; k < VEC; ++k) {
+                        if (HAS_W) acc[c][k] = fmaf(wc[u], v[k], acc[c][k]);
+                        else acc[c][k] += v[k];
                     }
                 }
             }
@@ -256,7 +260,7 @@ int spmm_impl(tcg_meta *m, const void *d_X, tcg_dtype x_dt, int32_t D, int64_t l
 
     GatherArgs a{m, d_X, ldx, D, d_w, d_Y, (int)y_dt, ldy, win_path, s};
     const int es = dtype_size(x_dt);
-    const bool vec_ok = ((int64_t)D * es) % 16 == 0 && (ldx * es) % 16 == 0 &&
+    const bool vec_ok = ((int64_t)D * es) % 16 == 0 && (ldx * es) % 16 == 0 && ldx * es < (1ll << 32) &&
                         (reinterpret_cast<uintptr_t>(d_X) & 15) == 0;
     bool done = false;
     if (vec_ok) {
