@@ -136,7 +136,8 @@ TCG_API int tcg_sgt_plan_stats(const tcg_meta *meta, int64_t *n_tile_windows, in
  *   d_Y    device, row-major [n_rows x D], leading dimension ldy (elements), type y_dt
  * D >= 1; ldx, ldy >= D.  Any D works; rows whose byte length and stride are multiples of 16
  * (and a 16-byte aligned base) take the vectorised kernels.  X and Y must not overlap.
- * May allocate (and keeps) a scratch buffer for rows that are split over several segments.
+ * The partial sums of rows split over several segments go to a scratch buffer reserved by
+ * tcg_sgt_build for D <= 128; the first call with a wider D reallocates (and keeps) it.
  */
 TCG_API int tcg_spmm(tcg_meta *meta, const void *d_X, tcg_dtype x_dt, int32_t D, int64_t ldx,
              const float *d_w, void *d_Y, tcg_dtype y_dt, int64_t ldy, void *stream);

@@ -21,7 +21,7 @@ static void free_meta(tcg_meta *m)
     if (!m) return;
     for (int i = 0; i < m->n_owned; ++i)
         if (m->owned[i]) (void)hipFree(m->owned[i]);
-    if (m->d_partial) (void)hipFree(m->d_partial);
+    if (m->partial_owned && m->d_partial) (void)hipFree(m->d_partial);
     delete m;
 }
 

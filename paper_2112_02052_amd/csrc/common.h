@@ -11,6 +11,7 @@ namespace tcg {
 constexpr int kWave = 64;            // gfx950 wavefront width
 constexpr int kSegLen = 128;         // max edges of one row segment on the gather path
 constexpr float kDefaultMinReuse = 2.0f;
+constexpr int kPartialInitD = 128;   // the build reserves partial-sum scratch for feature widths up to this
 constexpr int kTileMaxUnique = 512;  // AUTO never sends a window with more unique columns to the tile path
 
 // Records the text of a failing HIP call for tcg_strerror (thread local).
@@ -110,13 +111,14 @@ struct tcg_meta {
     int32_t *d_seg_dst = nullptr;         // [n_seg] partial-sum slot, or -1: write the row directly
     int32_t *d_long_row = nullptr;        // [n_long] rows with more than one segment
     int32_t *d_long_slot_ptr = nullptr;   // [n_long + 1] their slot ranges
-    float *d_partial = nullptr;           // [n_slots x partial_ld] scratch, grown on demand
+    float *d_partial = nullptr;           // [n_slots x D] scratch; reserved for D <= kPartialInitD, regrown on demand
     int64_t partial_elems = 0;
+    bool partial_owned = false;          // true once regrown by tcg_spmm for a wider D (separate allocation)
 
     // Device allocations owned by this object (the pointers above and below are carved from them).
     void *owned[8] = {nullptr};
     int n_owned = 0;
-    unsigned long long *d_counters = nullptr;   // [0] tiles, [2] tile-path windows, [3] their edges
+    unsigned long long *d_counters = nullptr;   // [0] tiles, [1] tile-path windows, [2] their edges
 
     // Per-window path choice.
     tcg_policy policy = TCG_POLICY_AUTO;

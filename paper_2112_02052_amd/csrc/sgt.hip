@@ -171,20 +171,31 @@ __device__ __forceinline__ void window_edge_range(const int32_t *rp, int32_t n_r
 // Appends every non-empty window to the list of its size class (order inside a list is irrelevant:
 // a window's result depends on the window only); empty windows get U_w = 0 here.
 // counts[0..3] = tiny, small, medium, large.
-__global__ void classify_windows_kernel(int32_t n_rows, int32_t win_h, int64_t n_win, const int32_t *rp,
-                                        int32_t *lists, int *counts, int32_t *win_unique)
+__global__ __launch_bounds__(256) void classify_windows_kernel(int32_t n_rows, int32_t win_h, int64_t n_win,
+                                                               const int32_t *rp, int32_t *lists, int *counts,
+                                                               int32_t *win_unique)
 {
-    int64_t w = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (w >= n_win) return;
-    int32_t lo, hi;
-    window_edge_range(rp, n_rows, win_h, w, &lo, &hi);
-    const int32_t cnt = hi - lo;
-    if (cnt == 0) {
-        win_unique[w] = 0;
-        return;
+    const int64_t w = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int lane = threadIdx.x & (kWave - 1);
+    int cls = -1;
+    if (w < n_win) {
+        int32_t lo, hi;
+        window_edge_range(rp, n_rows, win_h, w, &lo, &hi);
+        const int32_t cnt = hi - lo;
+        if (cnt == 0) win_unique[w] = 0;
+        else cls = cnt <= kTinyCap ? 0 : cnt <= kSmallCap ? 1 : cnt <= kMediumCap ? 2 : 3;
     }
-    const int cls = cnt <= kTinyCap ? 0 : cnt <= kSmallCap ? 1 : cnt <= kMediumCap ? 2 : 3;
-    lists[(int64_t)cls * n_win + atomicAdd(&counts[cls], 1)] = (int32_t)w;
+    // One atomic per wavefront and class instead of one per window.
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        const unsigned long long mask = __ballot(cls == c);
+        if (mask == 0) continue;
+        const int leader = __ffsll((long long)mask) - 1;
+        int base = 0;
+        if (lane == leader) base = atomicAdd(&counts[c], __popcll(mask));
+        base = __shfl(base, leader, kWave);
+        if (cls == c) lists[(int64_t)c * n_win + base + __popcll(mask & ((1ull << lane) - 1ull))] = (int32_t)w;
+    }
 }
 
 // Tiny, small and medium classes: one workgroup per listed window.
@@ -295,11 +306,11 @@ __global__ __launch_bounds__(kBitmapThreads) void sgt_window_bitmap_kernel(
         for (int u = 0; u < kEdgeUnroll; ++u)
             if (c[u] != 0xFFFFFFFFu) atomicOr(&bm[c[u] >> 5], 1u << (c[u] & 31));
     }
-    // All atomics of the workgroup are complete (fence + barrier) before any thread reads the bitmap;
-    // nobody read it earlier in this kernel, so no stale copy can sit in the CU's cache.
-    __threadfence();
+    // The barrier (with its workgroup-scope fence) orders the workgroup's atomics before the reads
+    // below; all waves of a workgroup share one CU cache and nobody read the bitmap earlier in this
+    // kernel, so no stale copy can exist.  Device-scope fences are not needed (and cost an L2
+    // write-back each).
     __syncthreads();
-    __threadfence();
 
     // 2. per-wavefront popcount of its word range, then the offsets of the wavefronts
     int64_t wpw = (n_words + kBitmapWaves - 1) / kBitmapWaves;
@@ -334,9 +345,7 @@ __global__ __launch_bounds__(kBitmapThreads) void sgt_window_bitmap_kernel(
         carry += __shfl(incl, kWave - 1, kWave);
     }
     if (threadIdx.x == 0) win_unique[w] = total;
-    __threadfence();
     __syncthreads();
-    __threadfence();
 
     // 4. rank of every edge's column
     for (int64_t e0 = lo + threadIdx.x; e0 < hi; e0 += (int64_t)kBitmapThreads * kEdgeUnroll) {
@@ -360,27 +369,41 @@ __global__ __launch_bounds__(kBitmapThreads) void sgt_window_bitmap_kernel(
     }
 }
 
-// Packs the per-window lists into col_to_row, derives win_partition (ceil(U_w / tile_w)) and the
-// default per-window path, and counts tiles / tile-path windows / their edges.
-__global__ __launch_bounds__(kWave) void sgt_pack_kernel(int32_t n_rows, int32_t win_h, int32_t tile_w,
+// Packs the per-window lists into col_to_row.  One wavefront per window; windows of the large
+// class are copied by sgt_pack_large_kernel with many workgroups each.
+__global__ __launch_bounds__(kWave) void sgt_pack_kernel(int32_t n_rows, int32_t win_h,
                                                          const int32_t *__restrict__ rp,
                                                          const int32_t *__restrict__ tmp_clean,
                                                          const int32_t *__restrict__ win_unique_ptr,
-                                                         int32_t *__restrict__ col_to_row,
-                                                         int32_t *__restrict__ win_partition,
-                                                         unsigned long long *total_tiles)
+                                                         int32_t *__restrict__ col_to_row)
 {
     const int64_t w = blockIdx.x;
     int32_t lo, hi;
     window_edge_range(rp, n_rows, win_h, w, &lo, &hi);
     const int32_t u0 = win_unique_ptr[w];
     const int32_t uw = win_unique_ptr[w + 1] - u0;
-    for (int k = threadIdx.x; k < uw; k += kWave) col_to_row[u0 + k] = tmp_clean[lo + k];
-    if (threadIdx.x == 0) {
-        int32_t tiles = (int32_t)(((int64_t)uw + tile_w - 1) / tile_w);
-        win_partition[w] = tiles;
-        if (tiles) atomicAdd(total_tiles, (unsigned long long)tiles);
-    }
+    if (hi - lo <= kMediumCap)
+        for (int k = threadIdx.x; k < uw; k += kWave) col_to_row[u0 + k] = tmp_clean[lo + k];
+}
+
+constexpr int kPackSplit = 16;   // workgroups per large window
+
+__global__ __launch_bounds__(256) void sgt_pack_large_kernel(int32_t n_rows, int32_t win_h,
+                                                             const int32_t *__restrict__ large_list,
+                                                             const int32_t *__restrict__ rp,
+                                                             const int32_t *__restrict__ tmp_clean,
+                                                             const int32_t *__restrict__ win_unique_ptr,
+                                                             int32_t *__restrict__ col_to_row)
+{
+    const int64_t w = large_list[blockIdx.x];
+    int32_t lo, hi;
+    window_edge_range(rp, n_rows, win_h, w, &lo, &hi);
+    const int32_t u0 = win_unique_ptr[w];
+    const int32_t uw = win_unique_ptr[w + 1] - u0;
+    const int32_t chunk = (uw + kPackSplit - 1) / kPackSplit;
+    const int32_t k0 = blockIdx.y * chunk;
+    const int32_t k1 = min(k0 + chunk, uw);
+    for (int32_t k = k0 + threadIdx.x; k < k1; k += 256) col_to_row[u0 + k] = tmp_clean[lo + k];
 }
 
 // ---- gather plan ------------------------------------------------------------------------------
@@ -421,26 +444,49 @@ __global__ void seg_fill_kernel(int32_t n_rows, const int32_t *rp, const int32_t
     }
 }
 
-__global__ void choose_path_kernel(int32_t n_rows, int32_t win_h, int64_t n_win, const int32_t *rp,
-                                   const int32_t *win_unique_ptr, int policy, float min_reuse,
-                                   uint8_t *win_path, unsigned long long *counts)
+__device__ __forceinline__ unsigned long long wave_sum_u64(unsigned long long v)
 {
-    int64_t w = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (w >= n_win) return;
-    int32_t lo, hi;
-    window_edge_range(rp, n_rows, win_h, w, &lo, &hi);
-    int32_t uw = win_unique_ptr[w + 1] - win_unique_ptr[w];
-    int32_t nnz_w = hi - lo;
-    bool tile = false;
-    if (policy == TCG_POLICY_TILE) tile = uw > 0;
-    else if (policy == TCG_POLICY_AUTO)
-        // Windows with shared neighbours, but not hub windows: a tile kernel workgroup walks its
-        // window's edges once per 32-column chunk, which only pays for compact windows.
-        tile = win_h == 16 && uw > 0 && uw <= kTileMaxUnique && (float)nnz_w >= min_reuse * (float)uw;
-    win_path[w] = tile ? 1 : 0;
-    if (tile) {
-        atomicAdd(&counts[0], 1ull);
-        atomicAdd(&counts[1], (unsigned long long)nnz_w);
+#pragma unroll
+    for (int off = 1; off < kWave; off <<= 1) v += __shfl_xor(v, off, kWave);
+    return v;
+}
+
+// Per window: win_partition = ceil(U_w / tile_w) (Algorithm 1), the path flag under the given policy,
+// and the totals (tiles, tile-path windows, their edges) with one atomic per wavefront.
+__global__ __launch_bounds__(256) void choose_path_kernel(int32_t n_rows, int32_t win_h, int32_t tile_w,
+                                                          int64_t n_win, const int32_t *rp,
+                                                          const int32_t *win_unique_ptr, int policy,
+                                                          float min_reuse, int32_t *win_partition,
+                                                          uint8_t *win_path, unsigned long long *counts)
+{
+    const int64_t w = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    unsigned long long tiles = 0, tile_win = 0, tile_nnz = 0;
+    if (w < n_win) {
+        int32_t lo, hi;
+        window_edge_range(rp, n_rows, win_h, w, &lo, &hi);
+        const int32_t uw = win_unique_ptr[w + 1] - win_unique_ptr[w];
+        const int32_t nnz_w = hi - lo;
+        tiles = (unsigned long long)(((int64_t)uw + tile_w - 1) / tile_w);
+        win_partition[w] = (int32_t)tiles;
+        bool tile = false;
+        if (policy == TCG_POLICY_TILE) tile = uw > 0;
+        else if (policy == TCG_POLICY_AUTO)
+            // Windows with shared neighbours, but not hub windows: a tile kernel workgroup walks its
+            // window's edges once per 32-column chunk, which only pays for compact windows.
+            tile = win_h == 16 && uw > 0 && uw <= kTileMaxUnique && (float)nnz_w >= min_reuse * (float)uw;
+        win_path[w] = tile ? 1 : 0;
+        if (tile) {
+            tile_win = 1;
+            tile_nnz = (unsigned long long)nnz_w;
+        }
+    }
+    tiles = wave_sum_u64(tiles);
+    tile_win = wave_sum_u64(tile_win);
+    tile_nnz = wave_sum_u64(tile_nnz);
+    if ((threadIdx.x & (kWave - 1)) == 0) {
+        if (tiles) atomicAdd(&counts[0], tiles);
+        if (tile_win) atomicAdd(&counts[1], tile_win);
+        if (tile_nnz) atomicAdd(&counts[2], tile_nnz);
     }
 }
 
@@ -495,21 +541,22 @@ int choose_paths(tcg_meta *m, tcg_policy policy, float min_reuse, hipStream_t s)
 {
     if (policy == TCG_POLICY_TILE && m->win_h != 16) return TCG_EINVAL;
     if (min_reuse <= 0.f) min_reuse = kDefaultMinReuse;
-    unsigned long long *counts = m->d_counters + 2;   // [2], [3]: tile windows, their edges
-    TCG_HIP(hipMemsetAsync(counts, 0, 2 * sizeof(unsigned long long), s));
+    unsigned long long *counts = m->d_counters;   // [0] tiles, [1] tile-path windows, [2] their edges
+    TCG_HIP(hipMemsetAsync(counts, 0, 3 * sizeof(unsigned long long), s));
     if (m->n_win > 0) {
         hipLaunchKernelGGL(choose_path_kernel, dim3((unsigned)ceil_div(m->n_win, 256)), dim3(256), 0, s,
-                           m->n_rows, m->win_h, m->n_win, m->d_row_ptr, m->d_win_unique_ptr, (int)policy,
-                           min_reuse, m->d_win_path, counts);
+                           m->n_rows, m->win_h, m->tile_w, m->n_win, m->d_row_ptr, m->d_win_unique_ptr,
+                           (int)policy, min_reuse, m->d_win_partition, m->d_win_path, counts);
         TCG_TRY(launch_status("choose_path_kernel"));
     }
-    unsigned long long h[2];
+    unsigned long long h[3];
     TCG_HIP(hipMemcpyAsync(h, counts, sizeof(h), hipMemcpyDeviceToHost, s));
     TCG_HIP(hipStreamSynchronize(s));
     m->policy = policy;
     m->min_reuse = min_reuse;
-    m->n_tile_win = (int64_t)h[0];
-    m->nnz_tile = (int64_t)h[1];
+    m->total_tiles = (int64_t)h[0];
+    m->n_tile_win = (int64_t)h[1];
+    m->nnz_tile = (int64_t)h[2];
     return TCG_OK;
 }
 
@@ -554,7 +601,6 @@ int sgt_build_impl(tcg_meta *m, int validate, hipStream_t s)
     int32_t *scan_work = tmp.take<int32_t>(scan_elems);
     int *small_ints = tmp.take<int>(16);   // [0..3] class counts, [8] validation flag
     TCG_HIP(hipMemsetAsync(small_ints, 0, 16 * sizeof(int), s));
-    TCG_HIP(hipMemsetAsync(m->d_counters, 0, 8 * sizeof(unsigned long long), s));
 
     if (validate) {
         int *flag = small_ints + 8;
@@ -607,6 +653,7 @@ int sgt_build_impl(tcg_meta *m, int validate, hipStream_t s)
     plan.want(m->n_seg * 4);
     plan.want(m->n_long * 4);
     plan.want((m->n_long + 1) * 4);
+    plan.want(m->n_slots * kPartialInitD * 4);   // partial sums of split rows for D <= kPartialInitD
     TCG_TRY(plan.commit());
     m->owned[m->n_owned++] = plan.base;
     m->d_seg_row = plan.take<int32_t>(m->n_seg);
@@ -614,6 +661,9 @@ int sgt_build_impl(tcg_meta *m, int validate, hipStream_t s)
     m->d_seg_dst = plan.take<int32_t>(m->n_seg);
     m->d_long_row = plan.take<int32_t>(m->n_long);
     m->d_long_slot_ptr = plan.take<int32_t>(m->n_long + 1);
+    m->d_partial = plan.take<float>(m->n_slots * kPartialInitD);
+    m->partial_elems = m->n_slots * kPartialInitD;
+    m->partial_owned = false;
     if (n > 0) {
         hipLaunchKernelGGL(seg_fill_kernel, dim3((unsigned)ceil_div(n, 256)), dim3(256), 0, s, n, m->d_row_ptr,
                            seg_off, long_off, slot_off, m->d_seg_row, m->d_seg_ebeg, m->d_seg_dst, m->d_long_row,
@@ -663,15 +713,17 @@ int sgt_build_impl(tcg_meta *m, int validate, hipStream_t s)
     TCG_TRY(dev_alloc(&m->d_col_to_row, m->total_unique));
     m->owned[m->n_owned++] = m->d_col_to_row;
     if (n_win > 0) {
-        hipLaunchKernelGGL(sgt_pack_kernel, dim3((unsigned)n_win), dim3(kWave), 0, s, n, m->win_h, m->tile_w,
-                           m->d_row_ptr, tmp_clean, m->d_win_unique_ptr, m->d_col_to_row, m->d_win_partition,
-                           m->d_counters);
+        hipLaunchKernelGGL(sgt_pack_kernel, dim3((unsigned)n_win), dim3(kWave), 0, s, n, m->win_h, m->d_row_ptr,
+                           tmp_clean, m->d_win_unique_ptr, m->d_col_to_row);
         TCG_TRY(launch_status("sgt_pack_kernel"));
+        if (h_cls[3] > 0) {
+            hipLaunchKernelGGL(sgt_pack_large_kernel, dim3((unsigned)h_cls[3], kPackSplit), dim3(256), 0, s, n,
+                               m->win_h, lists + 3 * n_win, m->d_row_ptr, tmp_clean, m->d_win_unique_ptr,
+                               m->d_col_to_row);
+            TCG_TRY(launch_status("sgt_pack_large_kernel"));
+        }
     }
-    unsigned long long tiles = 0;
-    TCG_HIP(hipMemcpyAsync(&tiles, m->d_counters, sizeof(tiles), hipMemcpyDeviceToHost, s));
-    TCG_TRY(choose_paths(m, TCG_POLICY_AUTO, 0.f, s));                          // sync 3 (also covers `tiles`)
-    m->total_tiles = (int64_t)tiles;
+    TCG_TRY(choose_paths(m, TCG_POLICY_AUTO, 0.f, s));                          // sync 3
     return TCG_OK;   // temporaries are freed by the guards; the stream is idle here
 }
 

@@ -243,14 +243,16 @@ int spmm_impl(tcg_meta *m, const void *d_X, tcg_dtype x_dt, int32_t D, int64_t l
     // Scratch for the partial sums of rows that span several segments.
     const int64_t need = m->n_slots * (int64_t)D;
     if (need > m->partial_elems) {
-        if (m->d_partial) {
+        if (m->partial_owned) {
             TCG_HIP(hipStreamSynchronize(s));
             TCG_HIP(hipFree(m->d_partial));
-            m->d_partial = nullptr;
-            m->partial_elems = 0;
         }
+        m->d_partial = nullptr;
+        m->partial_elems = 0;
+        m->partial_owned = false;
         TCG_TRY(dev_alloc(&m->d_partial, need));
         m->partial_elems = need;
+        m->partial_owned = true;
     }
 
     const bool use_tiles = m->n_tile_win > 0 && m->win_h == 16 && tile_path_supports(x_dt, D, ldx, d_X);
