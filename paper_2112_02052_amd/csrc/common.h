@@ -11,6 +11,7 @@ namespace tcg {
 constexpr int kWave = 64;            // gfx950 wavefront width
 constexpr int kSegLen = 128;         // max edges of one row segment on the gather path
 constexpr float kDefaultMinReuse = 2.0f;
+constexpr int kXcds = 8;              // accelerator dies of an MI355X; workgroup i is dispatched to die i % 8
 constexpr int kPartialInitD = 128;   // the build reserves partial-sum scratch for feature widths up to this
 constexpr int kTileMaxUnique = 512;  // AUTO never sends a window with more unique columns to the tile path
 
@@ -58,6 +59,54 @@ int dev_alloc(T **p, int64_t count)
 }
 
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// Gather-plan lookup: the segment that group `group` of workgroup blockIdx.x works on, or -1.
+// The segment list is ordered by column band (see sgt.hip).  Workgroup i belongs to dispatch lane
+// i % kXcds (the accelerator die it runs on).  lane_tab[kLaneTabStride * lane] holds {start, count} of
+// the lane's first band, {start, count} of its second band, and {start, count} of the whole unbanded
+// tail of the list (the same for all lanes).  A lane walks its two bands in workgroup-sized blocks,
+// one band after the other, then takes every kXcds-th run of the unbanded tail.
+constexpr int kLaneTabStride = 6;
+constexpr int kTailRun = 128;        // segments per contiguous run of the unbanded tail
+__device__ __forceinline__ int64_t plan_segment(const int32_t *__restrict__ lane_tab, int groups_per_block,
+                                                int group)
+{
+    const int lane = blockIdx.x % kXcds;
+    const int32_t *t = lane_tab + kLaneTabStride * lane;
+    int64_t blk = blockIdx.x / kXcds;
+    // One band after the other: interleaving them lets the rarely used columns evict the popular ones.
+#pragma unroll
+    for (int part = 0; part < 2; ++part) {
+        const int64_t nb = ((int64_t)t[2 * part + 1] + groups_per_block - 1) / groups_per_block;
+        if (blk < nb) {
+            const int64_t i = blk * groups_per_block + group;
+            return i < t[2 * part + 1] ? (int64_t)t[2 * part] + i : -1;
+        }
+        blk -= nb;
+    }
+    // Unbanded tail: runs of kTailRun consecutive segments (a few row windows, whose rows tend to share
+    // neighbours) stay on one die; the runs are dealt out round-robin.
+    const int run_blocks = kTailRun / groups_per_block > 0 ? kTailRun / groups_per_block : 1;
+    const int64_t tb = ((blk / run_blocks) * kXcds + lane) * run_blocks + blk % run_blocks;
+    const int64_t i = tb * groups_per_block + group;
+    return i < t[5] ? (int64_t)t[4] + i : -1;
+}
+
+// Host side of the same mapping: number of workgroups to launch for `groups_per_block`.
+inline int64_t plan_grid(const int32_t *h_lane_tab, int groups_per_block)
+{
+    int64_t band_blocks = 0;
+    for (int l = 0; l < kXcds; ++l) {
+        const int32_t *t = h_lane_tab + kLaneTabStride * l;
+        const int64_t nb = ((int64_t)t[1] + groups_per_block - 1) / groups_per_block +
+                           ((int64_t)t[3] + groups_per_block - 1) / groups_per_block;
+        band_blocks = nb > band_blocks ? nb : band_blocks;
+    }
+    const int64_t run_blocks = kTailRun / groups_per_block > 0 ? kTailRun / groups_per_block : 1;
+    const int64_t tail_blocks = ((int64_t)h_lane_tab[5] + groups_per_block - 1) / groups_per_block;
+    const int64_t tail_runs = (tail_blocks + run_blocks - 1) / run_blocks;
+    return kXcds * (band_blocks + (tail_runs + kXcds - 1) / kXcds * run_blocks);
+}
 
 // Exclusive prefix sum of n int32 values on the device; out may alias in.  out has n + 1
 // entries: out[n] is the total (sums are computed in int32; callers bound the total beforehand).
@@ -111,6 +160,8 @@ struct tcg_meta {
     int32_t *d_seg_dst = nullptr;         // [n_seg] partial-sum slot, or -1: write the row directly
     int32_t *d_long_row = nullptr;        // [n_long] rows with more than one segment
     int32_t *d_long_slot_ptr = nullptr;   // [n_long + 1] their slot ranges
+    int32_t *d_lane_tab = nullptr;        // [kXcds x kLaneTabStride] see plan_segment()
+    int32_t h_lane_tab[6 * 8] = {0};      // host copy (sizes the gather grids, see plan_grid())
     float *d_partial = nullptr;           // [n_slots x D] scratch; reserved for D <= kPartialInitD, regrown on demand
     int64_t partial_elems = 0;
     bool partial_owned = false;          // true once regrown by tcg_spmm for a wider D (separate allocation)

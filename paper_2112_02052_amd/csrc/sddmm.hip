@@ -61,15 +61,15 @@ __device__ __forceinline__ float group_reduce(float (&p)[UNROLL], int lane)
 // index, the next step bit 1, and so on; so idx(l) = l mod UNROLL.
 template <int DT, int G, int NCH, int UNROLL>
 __global__ __launch_bounds__(kBlock) void sddmm_gather_kernel(
-    int64_t n_seg, const int32_t *__restrict__ seg_row, const int32_t *__restrict__ seg_ebeg,
+    const int32_t *__restrict__ lane_tab, const int32_t *__restrict__ seg_row, const int32_t *__restrict__ seg_ebeg,
     const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ col_idx,
     const char *__restrict__ X, int64_t ldx_bytes, int32_t n_chunks, float *__restrict__ out,
     const uint8_t *__restrict__ win_path, int32_t win_h)
 {
     constexpr int VEC = Elem<DT>::VEC;
     const int lane = threadIdx.x % G;
-    const int64_t seg = (int64_t)blockIdx.x * (kBlock / G) + threadIdx.x / G;
-    if (seg >= n_seg) return;              // G divides the wavefront: whole groups leave together
+    const int64_t seg = plan_segment(lane_tab, kBlock / G, threadIdx.x / G);
+    if (seg < 0) return;              // G divides the wavefront: whole groups leave together
     const int32_t row = seg_row[seg];
     if (win_path != nullptr && win_path[row / win_h]) return;
     const int32_t eb = seg_ebeg[seg];
@@ -142,14 +142,14 @@ __global__ __launch_bounds__(kBlock) void sddmm_gather_kernel(
 
 // Any D / alignment: one wavefront per segment, lanes stride over the feature dimension.
 __global__ __launch_bounds__(kBlock) void sddmm_gather_generic_kernel(
-    int64_t n_seg, const int32_t *__restrict__ seg_row, const int32_t *__restrict__ seg_ebeg,
+    const int32_t *__restrict__ lane_tab, const int32_t *__restrict__ seg_row, const int32_t *__restrict__ seg_ebeg,
     const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ col_idx, const void *__restrict__ X,
     int x_dt, int64_t ldx, int32_t D, float *__restrict__ out, const uint8_t *__restrict__ win_path,
     int32_t win_h)
 {
     const int lane = threadIdx.x & (kWave - 1);
-    const int64_t seg = (int64_t)blockIdx.x * (kBlock / kWave) + (threadIdx.x >> 6);
-    if (seg >= n_seg) return;
+    const int64_t seg = plan_segment(lane_tab, kBlock / kWave, threadIdx.x >> 6);
+    if (seg < 0) return;
     const int32_t row = seg_row[seg];
     if (win_path != nullptr && win_path[row / win_h]) return;
     const int32_t eb = seg_ebeg[seg];
@@ -236,8 +236,8 @@ void launch_sddmm(const tcg_meta *m, const void *X, int64_t ldx, int32_t n_chunk
                   const uint8_t *win_path, hipStream_t s)
 {
     constexpr int UNROLL = NCH == 1 ? 8 : (NCH == 2 ? 4 : 2);
-    const unsigned grid = (unsigned)ceil_div(m->n_seg, kBlock / G);
-    hipLaunchKernelGGL((sddmm_gather_kernel<DT, G, NCH, UNROLL>), dim3(grid), dim3(kBlock), 0, s, m->n_seg,
+    const unsigned grid = (unsigned)plan_grid(m->h_lane_tab, kBlock / G);
+    hipLaunchKernelGGL((sddmm_gather_kernel<DT, G, NCH, UNROLL>), dim3(grid), dim3(kBlock), 0, s, m->d_lane_tab,
                        m->d_seg_row, m->d_seg_ebeg, m->d_row_ptr, m->d_col_idx, static_cast<const char *>(X),
                        ldx * Elem<DT>::BYTES, n_chunks, out, win_path, m->win_h);
 }
@@ -279,8 +279,8 @@ int sddmm_impl(tcg_meta *m, const void *d_X, tcg_dtype x_dt, int32_t D, int64_t 
         else done = dispatch_sddmm<TCG_F16>(m, d_X, ldx, n_chunks, d_out, win_path, s);
     }
     if (!done) {
-        const unsigned grid = (unsigned)ceil_div(m->n_seg, kBlock / kWave);
-        hipLaunchKernelGGL(sddmm_gather_generic_kernel, dim3(grid), dim3(kBlock), 0, s, m->n_seg, m->d_seg_row,
+        const unsigned grid = (unsigned)plan_grid(m->h_lane_tab, kBlock / kWave);
+        hipLaunchKernelGGL(sddmm_gather_generic_kernel, dim3(grid), dim3(kBlock), 0, s, m->d_lane_tab, m->d_seg_row,
                            m->d_seg_ebeg, m->d_row_ptr, m->d_col_idx, d_X, (int)x_dt, ldx, D, d_out, win_path,
                            m->win_h);
     }

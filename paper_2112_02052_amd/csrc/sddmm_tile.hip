@@ -46,15 +46,18 @@ __device__ __forceinline__ f32x4 mfma16(const uint4 &a, const uint4 &b, f32x4 c)
 // KSTEPS = ceil(D / 32) rounded up to a power of two; steps beyond D contribute zeros.
 template <int DT, int KSTEPS>
 __global__ __launch_bounds__(kTileBlock) void sddmm_tile_kernel(
-    int32_t n_rows, const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ edge_to_col,
+    int32_t n_rows, int64_t n_win, const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ edge_to_col,
     const int32_t *__restrict__ win_unique_ptr, const int32_t *__restrict__ col_to_row,
     const uint8_t *__restrict__ win_path, const char *__restrict__ X, int64_t ldx_bytes, int32_t D,
     float *__restrict__ out)
 {
     __shared__ float s_e[16 * kEStride];
     __shared__ int32_t s_rp[17];
-    const int64_t win = blockIdx.x;
-    if (!win_path[win]) return;
+    // Workgroup i runs on die i % kXcds: give every die a contiguous range of windows, so that
+    // neighbouring windows (which share neighbours on clustered graphs) meet in the same L2.
+    const int64_t per_die = (n_win + kXcds - 1) / kXcds;
+    const int64_t win = (int64_t)(blockIdx.x % kXcds) * per_die + blockIdx.x / kXcds;
+    if (win >= n_win || !win_path[win]) return;
 
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
@@ -119,8 +122,8 @@ __global__ __launch_bounds__(kTileBlock) void sddmm_tile_kernel(
 template <int DT, int KSTEPS>
 void launch(const tcg_meta *m, const void *X, int64_t ldx, int32_t D, float *out, hipStream_t s)
 {
-    hipLaunchKernelGGL((sddmm_tile_kernel<DT, KSTEPS>), dim3((unsigned)m->n_win), dim3(kTileBlock), 0, s,
-                       m->n_rows, m->d_row_ptr, m->d_edge_to_col, m->d_win_unique_ptr, m->d_col_to_row,
+    hipLaunchKernelGGL((sddmm_tile_kernel<DT, KSTEPS>), dim3((unsigned)(kXcds * ceil_div(m->n_win, kXcds))), dim3(kTileBlock), 0, s,
+                       m->n_rows, m->n_win, m->d_row_ptr, m->d_edge_to_col, m->d_win_unique_ptr, m->d_col_to_row,
                        m->d_win_path, static_cast<const char *>(X), ldx * 2, D, out);
 }
 

@@ -444,6 +444,82 @@ __global__ void seg_fill_kernel(int32_t n_rows, const int32_t *rp, const int32_t
     }
 }
 
+// ---- column bands: XCD-aware ordering of the segment list ---------------------------------------
+// Each accelerator die has its own L2.  Segments of split (long) rows cover a narrow range of the
+// row's columns, so sending all segments whose columns fall in the same band to the same die makes
+// that die's L2 hold only its bands' X rows: the hot rows are cached once per chip instead of once per
+// die.  The 2 * kXcds bands are chosen from a histogram of the split rows' segment start columns so
+// that every band gets about the same number of segments; die l takes bands l and 2 * kXcds - 1 - l,
+// which pairs a band of frequently used columns with a band of rarely used ones (on skewed graphs the
+// popular columns are a narrow id range), so that the L2 misses -- and with them the traffic on each
+// die's link to memory -- are spread evenly over the dies.  Single-segment rows are not banded; their
+// workgroup-sized blocks are dealt out to the dies round-robin.  Any grouping is correct: the order of the segment
+// list only changes where a segment runs.
+constexpr int kBands = 2 * kXcds;
+constexpr int kHistBins = 65536;
+
+__device__ __forceinline__ int column_bin(int32_t c, int32_t n_cols)
+{
+    return (int)(((int64_t)c * kHistBins) / (n_cols > 0 ? n_cols : 1));
+}
+
+__global__ void band_hist_kernel(int64_t n_seg, const int32_t *seg_dst, const int32_t *seg_ebeg,
+                                 const int32_t *ci, int32_t n_cols, int32_t *hist)
+{
+    int64_t sgi = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (sgi >= n_seg || seg_dst[sgi] < 0) return;
+    atomicAdd(&hist[column_bin(ci[seg_ebeg[sgi]], n_cols)], 1);
+}
+
+// flags[b * n_seg + s] = 1 iff segment s belongs to band b (b == kBands: unbanded).  `flags` is zeroed.
+__global__ void band_flag_kernel(int64_t n_seg, const int32_t *seg_dst, const int32_t *seg_ebeg,
+                                 const int32_t *ci, int32_t n_cols, const int32_t *hist_excl, uint8_t *seg_band,
+                                 int32_t *flags)
+{
+    int64_t sgi = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (sgi >= n_seg) return;
+    int b = kBands;
+    if (seg_dst[sgi] >= 0) {
+        const int64_t total = hist_excl[kHistBins];
+        const int64_t before = hist_excl[column_bin(ci[seg_ebeg[sgi]], n_cols)];
+        b = (int)((before * kBands) / (total > 0 ? total : 1));
+        if (b > kBands - 1) b = kBands - 1;
+    }
+    seg_band[sgi] = (uint8_t)b;
+    flags[(int64_t)b * n_seg + sgi] = 1;
+}
+
+__global__ void band_scatter_kernel(int64_t n_seg, const uint8_t *seg_band, const int32_t *pos,
+                                    const int32_t *in_row, const int32_t *in_ebeg, const int32_t *in_dst,
+                                    int32_t *out_row, int32_t *out_ebeg, int32_t *out_dst)
+{
+    int64_t sgi = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (sgi >= n_seg) return;
+    const int32_t p = pos[(int64_t)seg_band[sgi] * n_seg + sgi];
+    out_row[p] = in_row[sgi];
+    out_ebeg[p] = in_ebeg[sgi];
+    out_dst[p] = in_dst[sgi];
+}
+
+// lane_tab[kLaneTabStride * l] = {band l start, count, band (kBands-1-l) start, count, unbanded tail
+// start, count} (see plan_segment()).  pos == nullptr: no banding, the whole list is the tail.
+__global__ void lane_table_kernel(int64_t n_seg, const int32_t *pos, int32_t *lane_tab)
+{
+    if (threadIdx.x != 0 || blockIdx.x != 0) return;
+    const int32_t u_start = pos ? pos[(int64_t)kBands * n_seg] : 0;
+    const int32_t u_count = (int32_t)n_seg - u_start;
+    for (int l = 0; l < kXcds; ++l) {
+        const int b2 = kBands - 1 - l;
+        int32_t *t = lane_tab + kLaneTabStride * l;
+        t[0] = pos ? pos[(int64_t)l * n_seg] : 0;
+        t[1] = pos ? pos[(int64_t)(l + 1) * n_seg] - t[0] : 0;
+        t[2] = pos ? pos[(int64_t)b2 * n_seg] : 0;
+        t[3] = pos ? pos[(int64_t)(b2 + 1) * n_seg] - t[2] : 0;
+        t[4] = u_start;
+        t[5] = u_count;
+    }
+}
+
 __device__ __forceinline__ unsigned long long wave_sum_u64(unsigned long long v)
 {
 #pragma unroll
@@ -653,6 +729,7 @@ int sgt_build_impl(tcg_meta *m, int validate, hipStream_t s)
     plan.want(m->n_seg * 4);
     plan.want(m->n_long * 4);
     plan.want((m->n_long + 1) * 4);
+    plan.want(kLaneTabStride * kXcds * 4);
     plan.want(m->n_slots * kPartialInitD * 4);   // partial sums of split rows for D <= kPartialInitD
     TCG_TRY(plan.commit());
     m->owned[m->n_owned++] = plan.base;
@@ -661,14 +738,60 @@ int sgt_build_impl(tcg_meta *m, int validate, hipStream_t s)
     m->d_seg_dst = plan.take<int32_t>(m->n_seg);
     m->d_long_row = plan.take<int32_t>(m->n_long);
     m->d_long_slot_ptr = plan.take<int32_t>(m->n_long + 1);
+    m->d_lane_tab = plan.take<int32_t>(kLaneTabStride * kXcds);
     m->d_partial = plan.take<float>(m->n_slots * kPartialInitD);
     m->partial_elems = m->n_slots * kPartialInitD;
     m->partial_owned = false;
+
+    // Segment list in row order first, then reordered by column band (when there are split rows).
+    const bool banded = m->n_slots > 0 && (int64_t)(kBands + 1) * m->n_seg + 1 < (int64_t)INT32_MAX;
+    Arena ptmp;
+    const int64_t flag_elems = (int64_t)(kBands + 1) * m->n_seg + 1;
+    const int64_t pscan_elems = scan_workspace_elems(std::max<int64_t>(flag_elems, kHistBins));
+    if (banded) {
+        for (int i = 0; i < 3; ++i) ptmp.want(m->n_seg * 4);
+        ptmp.want(m->n_seg);
+        ptmp.want(flag_elems * 4);
+        ptmp.want((kHistBins + 1) * 4);
+        ptmp.want(pscan_elems * 4);
+        TCG_TRY(ptmp.commit());
+    }
+    ScopedFree ptmp_guard{ptmp.base};
     if (n > 0) {
+        int32_t *row_o = m->d_seg_row, *ebeg_o = m->d_seg_ebeg, *dst_o = m->d_seg_dst;
+        if (banded) {
+            row_o = ptmp.take<int32_t>(m->n_seg);
+            ebeg_o = ptmp.take<int32_t>(m->n_seg);
+            dst_o = ptmp.take<int32_t>(m->n_seg);
+        }
         hipLaunchKernelGGL(seg_fill_kernel, dim3((unsigned)ceil_div(n, 256)), dim3(256), 0, s, n, m->d_row_ptr,
-                           seg_off, long_off, slot_off, m->d_seg_row, m->d_seg_ebeg, m->d_seg_dst, m->d_long_row,
-                           m->d_long_slot_ptr, m->n_long);
+                           seg_off, long_off, slot_off, row_o, ebeg_o, dst_o, m->d_long_row, m->d_long_slot_ptr,
+                           m->n_long);
         TCG_TRY(launch_status("seg_fill_kernel"));
+        if (banded) {
+            uint8_t *seg_band = ptmp.take<uint8_t>(m->n_seg);
+            int32_t *flags = ptmp.take<int32_t>(flag_elems);
+            int32_t *hist = ptmp.take<int32_t>(kHistBins + 1);
+            int32_t *pscan = ptmp.take<int32_t>(pscan_elems);
+            const unsigned sgrid = (unsigned)ceil_div(m->n_seg, 256);
+            TCG_HIP(hipMemsetAsync(hist, 0, (kHistBins + 1) * sizeof(int32_t), s));
+            TCG_HIP(hipMemsetAsync(flags, 0, (size_t)flag_elems * sizeof(int32_t), s));
+            hipLaunchKernelGGL(band_hist_kernel, dim3(sgrid), dim3(256), 0, s, m->n_seg, dst_o, ebeg_o, m->d_col_idx,
+                               m->n_cols, hist);
+            TCG_TRY(exclusive_scan_i32(hist, hist, kHistBins, pscan, s));
+            hipLaunchKernelGGL(band_flag_kernel, dim3(sgrid), dim3(256), 0, s, m->n_seg, dst_o, ebeg_o, m->d_col_idx,
+                               m->n_cols, hist, seg_band, flags);
+            TCG_TRY(exclusive_scan_i32(flags, flags, flag_elems - 1, pscan, s));
+            hipLaunchKernelGGL(band_scatter_kernel, dim3(sgrid), dim3(256), 0, s, m->n_seg, seg_band, flags, row_o,
+                               ebeg_o, dst_o, m->d_seg_row, m->d_seg_ebeg, m->d_seg_dst);
+            hipLaunchKernelGGL(lane_table_kernel, dim3(1), dim3(64), 0, s, m->n_seg, flags, m->d_lane_tab);
+            TCG_TRY(launch_status("band kernels"));
+        }
+    }
+    if (!banded) {
+        hipLaunchKernelGGL(lane_table_kernel, dim3(1), dim3(64), 0, s, m->n_seg, (const int32_t *)nullptr,
+                           m->d_lane_tab);
+        TCG_TRY(launch_status("lane_table_kernel"));
     }
 
     // Per-window translation, one launch per size class.
@@ -707,6 +830,7 @@ int sgt_build_impl(tcg_meta *m, int validate, hipStream_t s)
     TCG_TRY(exclusive_scan_i32(win_unique, m->d_win_unique_ptr, n_win, scan_work, s));
     int32_t total_unique = 0;
     TCG_HIP(hipMemcpyAsync(&total_unique, m->d_win_unique_ptr + n_win, sizeof(int32_t), hipMemcpyDeviceToHost, s));
+    TCG_HIP(hipMemcpyAsync(m->h_lane_tab, m->d_lane_tab, sizeof(m->h_lane_tab), hipMemcpyDeviceToHost, s));
     TCG_HIP(hipStreamSynchronize(s));                                           // sync 2
     m->total_unique = total_unique;
 

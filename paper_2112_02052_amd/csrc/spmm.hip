@@ -30,7 +30,7 @@ constexpr int kBlock = 256;
 
 template <int DT, int G, int NCH, bool HAS_W, int UNROLL>
 __global__ __launch_bounds__(kBlock) void spmm_gather_kernel(
-    int64_t n_seg, const int32_t *__restrict__ seg_row, const int32_t *__restrict__ seg_ebeg,
+    const int32_t *__restrict__ lane_tab, const int32_t *__restrict__ seg_row, const int32_t *__restrict__ seg_ebeg,
     const int32_t *__restrict__ seg_dst, const int32_t *__restrict__ row_ptr,
     const int32_t *__restrict__ col_idx, const float *__restrict__ w, const char *__restrict__ X,
     int64_t ldx_bytes, int32_t n_chunks, int32_t D, void *__restrict__ Y, int y_dt, int64_t ldy,
@@ -39,8 +39,8 @@ __global__ __launch_bounds__(kBlock) void spmm_gather_kernel(
 {
     constexpr int VEC = Elem<DT>::VEC;
     const int lane = threadIdx.x % G;
-    const int64_t seg = (int64_t)blockIdx.x * (kBlock / G) + threadIdx.x / G;
-    if (seg >= n_seg) return;
+    const int64_t seg = plan_segment(lane_tab, kBlock / G, threadIdx.x / G);
+    if (seg < 0) return;
     const int32_t row = seg_row[seg];
     if (win_path != nullptr && win_path[row / win_h]) return;
     const int32_t eb = seg_ebeg[seg];
@@ -137,15 +137,15 @@ __global__ __launch_bounds__(kBlock) void spmm_gather_kernel(
 // Any D, any alignment: one wavefront per segment, one lane per feature element.
 template <bool HAS_W>
 __global__ __launch_bounds__(kBlock) void spmm_gather_generic_kernel(
-    int64_t n_seg, const int32_t *__restrict__ seg_row, const int32_t *__restrict__ seg_ebeg,
+    const int32_t *__restrict__ lane_tab, const int32_t *__restrict__ seg_row, const int32_t *__restrict__ seg_ebeg,
     const int32_t *__restrict__ seg_dst, const int32_t *__restrict__ row_ptr,
     const int32_t *__restrict__ col_idx, const float *__restrict__ w, const void *__restrict__ X, int x_dt,
     int64_t ldx, int32_t D, void *__restrict__ Y, int y_dt, int64_t ldy, float *__restrict__ partial,
     int64_t partial_ld, const uint8_t *__restrict__ win_path, int32_t win_h)
 {
     const int lane = threadIdx.x & (kWave - 1);
-    const int64_t seg = (int64_t)blockIdx.x * (kBlock / kWave) + (threadIdx.x >> 6);
-    if (seg >= n_seg) return;
+    const int64_t seg = plan_segment(lane_tab, kBlock / kWave, threadIdx.x >> 6);
+    if (seg < 0) return;
     const int32_t row = seg_row[seg];
     if (win_path != nullptr && win_path[row / win_h]) return;
     const int32_t eb = seg_ebeg[seg];
@@ -205,10 +205,10 @@ void launch_gather(const GatherArgs &a, int32_t n_chunks)
     constexpr int UNROLL = NCH == 1 ? 8 : (NCH == 2 ? 4 : 2);
     const tcg_meta *m = a.m;
     const int gpb = kBlock / G;
-    const unsigned grid = (unsigned)ceil_div(m->n_seg, gpb);
+    const unsigned grid = (unsigned)plan_grid(m->h_lane_tab, gpb);
     const int y_vec = a.y_dt == TCG_F32 && (a.ldy & 3) == 0 && (reinterpret_cast<uintptr_t>(a.Y) & 15) == 0;
     hipLaunchKernelGGL((spmm_gather_kernel<DT, G, NCH, HAS_W, UNROLL>), dim3(grid), dim3(kBlock), 0, a.s,
-                       m->n_seg, m->d_seg_row, m->d_seg_ebeg, m->d_seg_dst, m->d_row_ptr, m->d_col_idx, a.w,
+                       m->d_lane_tab, m->d_seg_row, m->d_seg_ebeg, m->d_seg_dst, m->d_row_ptr, m->d_col_idx, a.w,
                        static_cast<const char *>(a.X), a.ldx * Elem<DT>::BYTES, n_chunks, a.D, a.Y, a.y_dt,
                        a.ldy, m->d_partial, (int64_t)a.D, a.win_path, m->win_h, y_vec);
 }
@@ -272,14 +272,14 @@ int spmm_impl(tcg_meta *m, const void *d_X, tcg_dtype x_dt, int32_t D, int64_t l
         else done = dispatch_gather_w<TCG_F16>(a, n_chunks);
     }
     if (!done) {
-        const unsigned grid = (unsigned)ceil_div(m->n_seg, kBlock / kWave);
+        const unsigned grid = (unsigned)plan_grid(m->h_lane_tab, kBlock / kWave);
         if (d_w)
-            hipLaunchKernelGGL(spmm_gather_generic_kernel<true>, dim3(grid), dim3(kBlock), 0, s, m->n_seg,
+            hipLaunchKernelGGL(spmm_gather_generic_kernel<true>, dim3(grid), dim3(kBlock), 0, s, m->d_lane_tab,
                                m->d_seg_row, m->d_seg_ebeg, m->d_seg_dst, m->d_row_ptr, m->d_col_idx, d_w, d_X,
                                (int)x_dt, ldx, D, d_Y, (int)y_dt, ldy, m->d_partial, (int64_t)D, win_path,
                                m->win_h);
         else
-            hipLaunchKernelGGL(spmm_gather_generic_kernel<false>, dim3(grid), dim3(kBlock), 0, s, m->n_seg,
+            hipLaunchKernelGGL(spmm_gather_generic_kernel<false>, dim3(grid), dim3(kBlock), 0, s, m->d_lane_tab,
                                m->d_seg_row, m->d_seg_ebeg, m->d_seg_dst, m->d_row_ptr, m->d_col_idx, d_w, d_X,
                                (int)x_dt, ldx, D, d_Y, (int)y_dt, ldy, m->d_partial, (int64_t)D, win_path,
                                m->win_h);
