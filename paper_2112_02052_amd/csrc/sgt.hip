@@ -456,19 +456,28 @@ __global__ void seg_fill_kernel(int32_t n_rows, const int32_t *rp, const int32_t
 // workgroup-sized blocks are dealt out to the dies round-robin.  Any grouping is correct: the order of the segment
 // list only changes where a segment runs.
 constexpr int kBands = 2 * kXcds;
-constexpr int kHistBins = 65536;
+constexpr int kHistBins = 8192;    // 32 KB of LDS per workgroup in band_hist_kernel
 
 __device__ __forceinline__ int column_bin(int32_t c, int32_t n_cols)
 {
     return (int)(((int64_t)c * kHistBins) / (n_cols > 0 ? n_cols : 1));
 }
 
-__global__ void band_hist_kernel(int64_t n_seg, const int32_t *seg_dst, const int32_t *seg_ebeg,
-                                 const int32_t *ci, int32_t n_cols, int32_t *hist)
+// Histogram of the split rows' segment start columns.  Start columns of hub rows pile up in a few
+// bins, so every workgroup first counts in LDS and then adds its non-zero bins to the global array.
+__global__ __launch_bounds__(256) void band_hist_kernel(int64_t n_seg, const int32_t *seg_dst,
+                                                        const int32_t *seg_ebeg, const int32_t *ci,
+                                                        int32_t n_cols, int32_t *hist)
 {
-    int64_t sgi = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (sgi >= n_seg || seg_dst[sgi] < 0) return;
-    atomicAdd(&hist[column_bin(ci[seg_ebeg[sgi]], n_cols)], 1);
+    __shared__ int32_t s_hist[kHistBins];
+    for (int b = threadIdx.x; b < kHistBins; b += blockDim.x) s_hist[b] = 0;
+    __syncthreads();
+    for (int64_t sgi = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; sgi < n_seg;
+         sgi += (int64_t)gridDim.x * blockDim.x)
+        if (seg_dst[sgi] >= 0) atomicAdd(&s_hist[column_bin(ci[seg_ebeg[sgi]], n_cols)], 1);
+    __syncthreads();
+    for (int b = threadIdx.x; b < kHistBins; b += blockDim.x)
+        if (s_hist[b]) atomicAdd(&hist[b], s_hist[b]);
 }
 
 // flags[b * n_seg + s] = 1 iff segment s belongs to band b (b == kBands: unbanded).  `flags` is zeroed.
@@ -776,8 +785,8 @@ int sgt_build_impl(tcg_meta *m, int validate, hipStream_t s)
             const unsigned sgrid = (unsigned)ceil_div(m->n_seg, 256);
             TCG_HIP(hipMemsetAsync(hist, 0, (kHistBins + 1) * sizeof(int32_t), s));
             TCG_HIP(hipMemsetAsync(flags, 0, (size_t)flag_elems * sizeof(int32_t), s));
-            hipLaunchKernelGGL(band_hist_kernel, dim3(sgrid), dim3(256), 0, s, m->n_seg, dst_o, ebeg_o, m->d_col_idx,
-                               m->n_cols, hist);
+            hipLaunchKernelGGL(band_hist_kernel, dim3(std::min<unsigned>(sgrid, 512u)), dim3(256), 0, s, m->n_seg, dst_o,
+                               ebeg_o, m->d_col_idx, m->n_cols, hist);
             TCG_TRY(exclusive_scan_i32(hist, hist, kHistBins, pscan, s));
             hipLaunchKernelGGL(band_flag_kernel, dim3(sgrid), dim3(256), 0, s, m->n_seg, dst_o, ebeg_o, m->d_col_idx,
                                m->n_cols, hist, seg_band, flags);
