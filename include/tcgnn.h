@@ -160,8 +160,15 @@ TCG_API int tcg_sddmm(tcg_meta *meta, const void *d_X, tcg_dtype x_dt, int32_t D
 TCG_API int tcg_row_softmax(const tcg_meta *meta, const float *d_in, float *d_out, void *stream);
 
 /* Releases the metadata object and every device buffer it owns (NULL is a no-op).  The caller
- * must make sure no kernel using it is still running.                                          */
+ * must make sure no kernel using it is still running (its buffers go back to the library's cache
+ * and may be handed to the next tcg_sgt_build).                                         */
 TCG_API void tcg_sgt_free(tcg_meta *meta);
+
+/* The library keeps device blocks it no longer needs (temporaries of tcg_sgt_build, buffers of freed
+ * metadata objects) and reuses them for later calls, because allocating them costs more than the
+ * translation itself.  This call hands every cached block back to the driver; blocks of live
+ * metadata objects are not touched.                                                            */
+TCG_API void tcg_release_cached_memory(void);
 
 /* Text for a status code; valid until the calling thread's next library call.                  */
 TCG_API const char *tcg_strerror(int status);

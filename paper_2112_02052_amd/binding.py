@@ -14,7 +14,7 @@ POLICY_AUTO, POLICY_GATHER, POLICY_TILE = 0, 1, 2
 
 EXPORTED = ["tcg_sgt_build", "tcg_sgt_sizes", "tcg_sgt_export", "tcg_sgt_set_policy",
             "tcg_sgt_plan_stats", "tcg_spmm", "tcg_sddmm", "tcg_row_softmax", "tcg_sgt_free",
-            "tcg_strerror"]
+            "tcg_strerror", "tcg_release_cached_memory"]
 
 _DTYPES = {torch.float32: TCG_F32, torch.bfloat16: TCG_BF16, torch.float16: TCG_F16}
 
@@ -58,6 +58,8 @@ def load_library():
     lib.tcg_row_softmax.argtypes = [_vp, _vp, _vp, _vp]
     lib.tcg_sgt_free.restype = None
     lib.tcg_sgt_free.argtypes = [_vp]
+    lib.tcg_release_cached_memory.restype = None
+    lib.tcg_release_cached_memory.argtypes = []
     lib.tcg_strerror.restype = ctypes.c_char_p
     lib.tcg_strerror.argtypes = [ctypes.c_int]
     _lib = lib
@@ -183,6 +185,11 @@ def sddmm(meta, X, out=None):
     _check(load_library().tcg_sddmm(meta._h, _ptr(X), _DTYPES[X.dtype], X.shape[1], X.stride(0), _ptr(out),
                                     _stream()))
     return out
+
+
+def release_cached_memory():
+    """tcg_release_cached_memory: hand the library's cached device blocks back to the driver."""
+    load_library().tcg_release_cached_memory()
 
 
 def row_softmax(meta, v, out=None):

@@ -20,8 +20,8 @@ static void free_meta(tcg_meta *m)
 {
     if (!m) return;
     for (int i = 0; i < m->n_owned; ++i)
-        if (m->owned[i]) (void)hipFree(m->owned[i]);
-    if (m->partial_owned && m->d_partial) (void)hipFree(m->d_partial);
+        if (m->owned[i]) pool_free(m->owned[i]);
+    if (m->partial_owned && m->d_partial) pool_free(m->d_partial);
     delete m;
 }
 
@@ -140,6 +140,8 @@ int tcg_row_softmax(const tcg_meta *meta, const float *d_in, float *d_out, void 
 }
 
 void tcg_sgt_free(tcg_meta *meta) { free_meta(meta); }
+
+void tcg_release_cached_memory(void) { pool_release_all(); }
 
 const char *tcg_strerror(int status)
 {

@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <algorithm>
+
 #include "tcgnn.h"
 
 namespace tcg {
@@ -43,19 +45,19 @@ inline int launch_status(const char *what)
     return TCG_OK;
 }
 
+// pool.hip: caching device allocator (blocks are reused across graph translations).
+int pool_alloc(void **p, size_t bytes);
+void pool_free(void *p);
+void pool_release_all();
+
 template <typename T>
 int dev_alloc(T **p, int64_t count)
 {
-    *p = nullptr;
     if (count <= 0) count = 1;       // keep pointers valid for empty graphs
-    hipError_t e = hipMalloc(reinterpret_cast<void **>(p), static_cast<size_t>(count) * sizeof(T));
-    if (e != hipSuccess) {
-        (void)hipGetLastError();
-        set_hip_error(e, "hipMalloc");
-        *p = nullptr;
-        return TCG_ENOMEM;
-    }
-    return TCG_OK;
+    void *q = nullptr;
+    int st = pool_alloc(&q, static_cast<size_t>(count) * sizeof(T));
+    *p = static_cast<T *>(q);
+    return st;
 }
 
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }

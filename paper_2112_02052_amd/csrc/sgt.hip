@@ -583,14 +583,10 @@ struct Arena {
     void want(size_t bytes) { size += align(std::max<size_t>(bytes, 4)); }
     int commit()
     {
-        hipError_t e = hipMalloc(reinterpret_cast<void **>(&base), std::max<size_t>(size, 256));
-        if (e != hipSuccess) {
-            (void)hipGetLastError();
-            set_hip_error(e, "hipMalloc");
-            base = nullptr;
-            return TCG_ENOMEM;
-        }
-        return TCG_OK;
+        void *q = nullptr;
+        int st = pool_alloc(&q, std::max<size_t>(size, 256));
+        base = static_cast<char *>(q);
+        return st;
     }
     template <typename T> T *take(int64_t count)
     {
@@ -600,9 +596,9 @@ struct Arena {
     }
 };
 
-struct ScopedFree {  // frees on scope exit
+struct ScopedFree {  // returns the block to the pool on scope exit (the stream is idle by then)
     void *p = nullptr;
-    ~ScopedFree() { if (p) (void)hipFree(p); }
+    ~ScopedFree() { if (p) pool_free(p); }
 };
 
 }  // namespace

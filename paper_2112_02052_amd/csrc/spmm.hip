@@ -245,7 +245,7 @@ int spmm_impl(tcg_meta *m, const void *d_X, tcg_dtype x_dt, int32_t D, int64_t l
     if (need > m->partial_elems) {
         if (m->partial_owned) {
             TCG_HIP(hipStreamSynchronize(s));
-            TCG_HIP(hipFree(m->d_partial));
+            pool_free(m->d_partial);
         }
         m->d_partial = nullptr;
         m->partial_elems = 0;

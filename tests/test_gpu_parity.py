@@ -109,6 +109,21 @@ def test_sgt_rejects_malformed_csr():
     meta.free()
 
 
+def test_cached_memory_is_reused_and_can_be_released():
+    # Buffers of a freed translation go back to the library's cache; a later build (which may get
+    # them, stale contents included) must still be bit-exact, also after the cache was released.
+    g1 = W.make_config(4, n=20000, d=4)["csr"]
+    g2 = W.make_config(3, n=15000, d=4)["csr"]
+    for rnd in range(3):
+        for g in (g1, g2):
+            rp, ci = upload_csr(g)
+            meta = tcg.sgt_build(rp, ci, 16, 8)
+            check_sgt(meta, g, 16, 8)
+            meta.free()
+        if rnd == 1:
+            tcg.release_cached_memory()
+
+
 # ----------------------------------------------------------------------------------------------
 # SpMM
 # ----------------------------------------------------------------------------------------------
@@ -204,6 +219,18 @@ def test_spmm_integer_inputs_are_bit_exact_on_every_path():
         torch.cuda.synchronize()
         assert np.array_equal(Y.cpu().numpy().astype(np.float64), ref), (x_dtype, policy)
     meta.free()
+
+
+def test_spmm_rectangular_matrix():
+    # More columns than rows and the other way round: X has n_cols rows, Y has n_rows rows.
+    rng = np.random.default_rng(11)
+    for n_rows, n_cols in ((300, 5000), (5000, 300)):
+        rows = [rng.choice(n_cols, size=int(rng.integers(0, 60)), replace=False) for _ in range(n_rows)]
+        g = csr_from_rows(rows, n_cols)
+        X = W.features_normal(n_cols, 64, 2)
+        w = rng.standard_normal(g.nnz).astype(np.float32)
+        run_spmm_case(g, X, "f32", w, tcg.POLICY_AUTO, TOL_F32)
+        run_spmm_case(g, W.round_to_bf16(X), "bf16", None, tcg.POLICY_TILE, TOL_F32)
 
 
 def test_spmm_bf16_output():
