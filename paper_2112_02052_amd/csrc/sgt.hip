@@ -452,8 +452,8 @@ __global__ void seg_fill_kernel(int32_t n_rows, const int32_t *rp, const int32_t
 // that every band gets about the same number of segments; die l takes bands l and 2 * kXcds - 1 - l,
 // which pairs a band of frequently used columns with a band of rarely used ones (on skewed graphs the
 // popular columns are a narrow id range), so that the L2 misses -- and with them the traffic on each
-// die's link to memory -- are spread evenly over the dies.  Single-segment rows are not banded; their
-// workgroup-sized blocks are dealt out to the dies round-robin.  Any grouping is correct: the order of the segment
+// die's link to memory -- are spread evenly over the dies.  Single-segment rows are not banded; runs of
+// them are dealt out to the dies round-robin.  Any grouping is correct: the order of the segment
 // list only changes where a segment runs.
 constexpr int kBands = 2 * kXcds;
 constexpr int kHistBins = 8192;    // 32 KB of LDS per workgroup in band_hist_kernel
@@ -480,50 +480,92 @@ __global__ __launch_bounds__(256) void band_hist_kernel(int64_t n_seg, const int
         if (s_hist[b]) atomicAdd(&hist[b], s_hist[b]);
 }
 
-// flags[b * n_seg + s] = 1 iff segment s belongs to band b (b == kBands: unbanded).  `flags` is zeroed.
-__global__ void band_flag_kernel(int64_t n_seg, const int32_t *seg_dst, const int32_t *seg_ebeg,
-                                 const int32_t *ci, int32_t n_cols, const int32_t *hist_excl, uint8_t *seg_band,
-                                 int32_t *flags)
+// Category of a segment in the final order: 0 .. kBands-1 = column band of a split row's segment;
+// kBands + c = single-segment row of length class c.  With sort_tail the classes follow the number of
+// gather iterations a row needs (longest first), so that the lane groups of a wavefront get rows of
+// similar length; without it every single-segment row is class 0 and the tail stays in row order,
+// which keeps the rows of a window next to each other (that matters when they share neighbours).
+constexpr int kTailClasses = 8;
+constexpr int kCats = kBands + kTailClasses;
+constexpr int kPartThreads = 256;
+
+__device__ __forceinline__ int segment_category(int64_t sgi, const int32_t *seg_row, const int32_t *seg_dst,
+                                                const int32_t *seg_ebeg, const int32_t *rp, const int32_t *ci,
+                                                int32_t n_cols, const int32_t *hist_excl, int sort_tail)
 {
-    int64_t sgi = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (sgi >= n_seg) return;
-    int b = kBands;
     if (seg_dst[sgi] >= 0) {
         const int64_t total = hist_excl[kHistBins];
         const int64_t before = hist_excl[column_bin(ci[seg_ebeg[sgi]], n_cols)];
-        b = (int)((before * kBands) / (total > 0 ? total : 1));
-        if (b > kBands - 1) b = kBands - 1;
+        int b = (int)((before * kBands) / (total > 0 ? total : 1));
+        return b > kBands - 1 ? kBands - 1 : b;
     }
-    seg_band[sgi] = (uint8_t)b;
-    flags[(int64_t)b * n_seg + sgi] = 1;
+    if (!sort_tail) return kBands;
+    const int32_t r = seg_row[sgi];
+    const int32_t deg = rp[r + 1] - rp[r];
+    const int cls = deg > 96 ? 0 : deg > 64 ? 1 : deg > 48 ? 2 : deg > 32 ? 3 : deg > 24 ? 4 : deg > 16 ? 5 : deg > 8 ? 6 : 7;
+    return kBands + cls;
 }
 
-__global__ void band_scatter_kernel(int64_t n_seg, const uint8_t *seg_band, const int32_t *pos,
-                                    const int32_t *in_row, const int32_t *in_ebeg, const int32_t *in_dst,
-                                    int32_t *out_row, int32_t *out_ebeg, int32_t *out_dst)
+// Pass 1 of the stable partition: category of every segment and per-workgroup category counts
+// (block_cnt[cat * n_blocks + block]).
+__global__ __launch_bounds__(kPartThreads) void cat_count_kernel(
+    int64_t n_seg, const int32_t *seg_row, const int32_t *seg_dst, const int32_t *seg_ebeg, const int32_t *rp,
+    const int32_t *ci, int32_t n_cols, const int32_t *hist_excl, int sort_tail, uint8_t *seg_cat,
+    int32_t *block_cnt, int64_t n_blocks)
 {
-    int64_t sgi = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (sgi >= n_seg) return;
-    const int32_t p = pos[(int64_t)seg_band[sgi] * n_seg + sgi];
+    __shared__ int s_cnt[kCats];
+    if (threadIdx.x < kCats) s_cnt[threadIdx.x] = 0;
+    __syncthreads();
+    const int64_t sgi = (int64_t)blockIdx.x * kPartThreads + threadIdx.x;
+    if (sgi < n_seg) {
+        const int c = segment_category(sgi, seg_row, seg_dst, seg_ebeg, rp, ci, n_cols, hist_excl, sort_tail);
+        seg_cat[sgi] = (uint8_t)c;
+        atomicAdd(&s_cnt[c], 1);
+    }
+    __syncthreads();
+    if (threadIdx.x < kCats) block_cnt[(int64_t)threadIdx.x * n_blocks + blockIdx.x] = s_cnt[threadIdx.x];
+}
+
+// Pass 2: block_off = exclusive scan of block_cnt (category-major = the final order).  Inside a
+// workgroup a segment's rank among the segments of its category is found with wavefront ballots, so
+// the partition is stable (row order is kept inside every category) and deterministic.
+__global__ __launch_bounds__(kPartThreads) void cat_scatter_kernel(
+    int64_t n_seg, const uint8_t *seg_cat, const int32_t *block_off, int64_t n_blocks, const int32_t *in_row,
+    const int32_t *in_ebeg, const int32_t *in_dst, int32_t *out_row, int32_t *out_ebeg, int32_t *out_dst)
+{
+    __shared__ int s_wave_cnt[kPartThreads / kWave][kCats];
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
+    const int64_t sgi = (int64_t)blockIdx.x * kPartThreads + threadIdx.x;
+    const int cat = sgi < n_seg ? (int)seg_cat[sgi] : -1;
+    int rank_in_wave = 0;
+    for (int c = 0; c < kCats; ++c) {
+        const unsigned long long mask = __ballot(cat == c);
+        if (lane == 0) s_wave_cnt[wave][c] = __popcll(mask);
+        if (cat == c) rank_in_wave = __popcll(mask & ((1ull << lane) - 1ull));
+    }
+    __syncthreads();
+    if (cat < 0) return;
+    int32_t p = block_off[(int64_t)cat * n_blocks + blockIdx.x] + rank_in_wave;
+    for (int w2 = 0; w2 < wave; ++w2) p += s_wave_cnt[w2][cat];
     out_row[p] = in_row[sgi];
     out_ebeg[p] = in_ebeg[sgi];
     out_dst[p] = in_dst[sgi];
 }
 
-// lane_tab[kLaneTabStride * l] = {band l start, count, band (kBands-1-l) start, count, unbanded tail
-// start, count} (see plan_segment()).  pos == nullptr: no banding, the whole list is the tail.
-__global__ void lane_table_kernel(int64_t n_seg, const int32_t *pos, int32_t *lane_tab)
+// lane_tab[kLaneTabStride * l] = {band l start, count, band (kBands-1-l) start, count, tail start,
+// count} (see plan_segment()).  block_off == nullptr: no ordering, the whole list is the tail.
+__global__ void lane_table_kernel(int64_t n_seg, const int32_t *block_off, int64_t n_blocks, int32_t *lane_tab)
 {
     if (threadIdx.x != 0 || blockIdx.x != 0) return;
-    const int32_t u_start = pos ? pos[(int64_t)kBands * n_seg] : 0;
+    const int32_t u_start = block_off ? block_off[(int64_t)kBands * n_blocks] : 0;
     const int32_t u_count = (int32_t)n_seg - u_start;
     for (int l = 0; l < kXcds; ++l) {
         const int b2 = kBands - 1 - l;
         int32_t *t = lane_tab + kLaneTabStride * l;
-        t[0] = pos ? pos[(int64_t)l * n_seg] : 0;
-        t[1] = pos ? pos[(int64_t)(l + 1) * n_seg] - t[0] : 0;
-        t[2] = pos ? pos[(int64_t)b2 * n_seg] : 0;
-        t[3] = pos ? pos[(int64_t)(b2 + 1) * n_seg] - t[2] : 0;
+        t[0] = block_off ? block_off[(int64_t)l * n_blocks] : 0;
+        t[1] = block_off ? block_off[(int64_t)(l + 1) * n_blocks] - t[0] : 0;
+        t[2] = block_off ? block_off[(int64_t)b2 * n_blocks] : 0;
+        t[3] = block_off ? block_off[(int64_t)(b2 + 1) * n_blocks] - t[2] : 0;
         t[4] = u_start;
         t[5] = u_count;
     }
@@ -748,57 +790,6 @@ int sgt_build_impl(tcg_meta *m, int validate, hipStream_t s)
     m->partial_elems = m->n_slots * kPartialInitD;
     m->partial_owned = false;
 
-    // Segment list in row order first, then reordered by column band (when there are split rows).
-    const bool banded = m->n_slots > 0 && (int64_t)(kBands + 1) * m->n_seg + 1 < (int64_t)INT32_MAX;
-    Arena ptmp;
-    const int64_t flag_elems = (int64_t)(kBands + 1) * m->n_seg + 1;
-    const int64_t pscan_elems = scan_workspace_elems(std::max<int64_t>(flag_elems, kHistBins));
-    if (banded) {
-        for (int i = 0; i < 3; ++i) ptmp.want(m->n_seg * 4);
-        ptmp.want(m->n_seg);
-        ptmp.want(flag_elems * 4);
-        ptmp.want((kHistBins + 1) * 4);
-        ptmp.want(pscan_elems * 4);
-        TCG_TRY(ptmp.commit());
-    }
-    ScopedFree ptmp_guard{ptmp.base};
-    if (n > 0) {
-        int32_t *row_o = m->d_seg_row, *ebeg_o = m->d_seg_ebeg, *dst_o = m->d_seg_dst;
-        if (banded) {
-            row_o = ptmp.take<int32_t>(m->n_seg);
-            ebeg_o = ptmp.take<int32_t>(m->n_seg);
-            dst_o = ptmp.take<int32_t>(m->n_seg);
-        }
-        hipLaunchKernelGGL(seg_fill_kernel, dim3((unsigned)ceil_div(n, 256)), dim3(256), 0, s, n, m->d_row_ptr,
-                           seg_off, long_off, slot_off, row_o, ebeg_o, dst_o, m->d_long_row, m->d_long_slot_ptr,
-                           m->n_long);
-        TCG_TRY(launch_status("seg_fill_kernel"));
-        if (banded) {
-            uint8_t *seg_band = ptmp.take<uint8_t>(m->n_seg);
-            int32_t *flags = ptmp.take<int32_t>(flag_elems);
-            int32_t *hist = ptmp.take<int32_t>(kHistBins + 1);
-            int32_t *pscan = ptmp.take<int32_t>(pscan_elems);
-            const unsigned sgrid = (unsigned)ceil_div(m->n_seg, 256);
-            TCG_HIP(hipMemsetAsync(hist, 0, (kHistBins + 1) * sizeof(int32_t), s));
-            TCG_HIP(hipMemsetAsync(flags, 0, (size_t)flag_elems * sizeof(int32_t), s));
-            hipLaunchKernelGGL(band_hist_kernel, dim3(std::min<unsigned>(sgrid, 512u)), dim3(256), 0, s, m->n_seg, dst_o,
-                               ebeg_o, m->d_col_idx, m->n_cols, hist);
-            TCG_TRY(exclusive_scan_i32(hist, hist, kHistBins, pscan, s));
-            hipLaunchKernelGGL(band_flag_kernel, dim3(sgrid), dim3(256), 0, s, m->n_seg, dst_o, ebeg_o, m->d_col_idx,
-                               m->n_cols, hist, seg_band, flags);
-            TCG_TRY(exclusive_scan_i32(flags, flags, flag_elems - 1, pscan, s));
-            hipLaunchKernelGGL(band_scatter_kernel, dim3(sgrid), dim3(256), 0, s, m->n_seg, seg_band, flags, row_o,
-                               ebeg_o, dst_o, m->d_seg_row, m->d_seg_ebeg, m->d_seg_dst);
-            hipLaunchKernelGGL(lane_table_kernel, dim3(1), dim3(64), 0, s, m->n_seg, flags, m->d_lane_tab);
-            TCG_TRY(launch_status("band kernels"));
-        }
-    }
-    if (!banded) {
-        hipLaunchKernelGGL(lane_table_kernel, dim3(1), dim3(64), 0, s, m->n_seg, (const int32_t *)nullptr,
-                           m->d_lane_tab);
-        TCG_TRY(launch_status("lane_table_kernel"));
-    }
-
     // Per-window translation, one launch per size class.
     if (h_cls[0] > 0)
         hipLaunchKernelGGL((sgt_window_lds_kernel<kWave, kTinyCap>), dim3((unsigned)h_cls[0]), dim3(kWave), 0, s, n,
@@ -835,9 +826,63 @@ int sgt_build_impl(tcg_meta *m, int validate, hipStream_t s)
     TCG_TRY(exclusive_scan_i32(win_unique, m->d_win_unique_ptr, n_win, scan_work, s));
     int32_t total_unique = 0;
     TCG_HIP(hipMemcpyAsync(&total_unique, m->d_win_unique_ptr + n_win, sizeof(int32_t), hipMemcpyDeviceToHost, s));
-    TCG_HIP(hipMemcpyAsync(m->h_lane_tab, m->d_lane_tab, sizeof(m->h_lane_tab), hipMemcpyDeviceToHost, s));
     TCG_HIP(hipStreamSynchronize(s));                                           // sync 2
     m->total_unique = total_unique;
+
+    // Segment list: row order first, then a stable partition into column bands (split rows) and the
+    // tail of single-segment rows.  When the windows share few neighbours (U close to nnz) the tail is
+    // ordered by row length as well; otherwise it keeps the row order.
+    const int64_t n_pblocks = ceil_div(std::max<int64_t>(m->n_seg, 1), kPartThreads);
+    const int sort_tail = (double)m->total_unique > 0.75 * (double)std::max<int64_t>(nnz, 1) ? 1 : 0;
+    const bool ordered = (m->n_slots > 0 || sort_tail) && (int64_t)kCats * n_pblocks + 1 < (int64_t)INT32_MAX;
+    Arena ptmp;
+    const int64_t cnt_elems = (int64_t)kCats * n_pblocks + 1;
+    const int64_t pscan_elems = scan_workspace_elems(std::max<int64_t>(cnt_elems, kHistBins));
+    if (ordered) {
+        for (int i = 0; i < 3; ++i) ptmp.want(m->n_seg * 4);
+        ptmp.want(m->n_seg);
+        ptmp.want(cnt_elems * 4);
+        ptmp.want((kHistBins + 1) * 4);
+        ptmp.want(pscan_elems * 4);
+        TCG_TRY(ptmp.commit());
+    }
+    ScopedFree ptmp_guard{ptmp.base};
+    if (n > 0) {
+        int32_t *row_o = m->d_seg_row, *ebeg_o = m->d_seg_ebeg, *dst_o = m->d_seg_dst;
+        if (ordered) {
+            row_o = ptmp.take<int32_t>(m->n_seg);
+            ebeg_o = ptmp.take<int32_t>(m->n_seg);
+            dst_o = ptmp.take<int32_t>(m->n_seg);
+        }
+        hipLaunchKernelGGL(seg_fill_kernel, dim3((unsigned)ceil_div(n, 256)), dim3(256), 0, s, n, m->d_row_ptr,
+                           seg_off, long_off, slot_off, row_o, ebeg_o, dst_o, m->d_long_row, m->d_long_slot_ptr,
+                           m->n_long);
+        TCG_TRY(launch_status("seg_fill_kernel"));
+        if (ordered) {
+            uint8_t *seg_cat = ptmp.take<uint8_t>(m->n_seg);
+            int32_t *block_cnt = ptmp.take<int32_t>(cnt_elems);
+            int32_t *hist = ptmp.take<int32_t>(kHistBins + 1);
+            int32_t *pscan = ptmp.take<int32_t>(pscan_elems);
+            const unsigned sgrid = (unsigned)n_pblocks;
+            TCG_HIP(hipMemsetAsync(hist, 0, (kHistBins + 1) * sizeof(int32_t), s));
+            hipLaunchKernelGGL(band_hist_kernel, dim3(std::min<unsigned>(sgrid, 512u)), dim3(256), 0, s, m->n_seg, dst_o,
+                               ebeg_o, m->d_col_idx, m->n_cols, hist);
+            TCG_TRY(exclusive_scan_i32(hist, hist, kHistBins, pscan, s));
+            hipLaunchKernelGGL(cat_count_kernel, dim3(sgrid), dim3(kPartThreads), 0, s, m->n_seg, row_o, dst_o, ebeg_o,
+                               m->d_row_ptr, m->d_col_idx, m->n_cols, hist, sort_tail, seg_cat, block_cnt, n_pblocks);
+            TCG_TRY(exclusive_scan_i32(block_cnt, block_cnt, cnt_elems - 1, pscan, s));
+            hipLaunchKernelGGL(cat_scatter_kernel, dim3(sgrid), dim3(kPartThreads), 0, s, m->n_seg, seg_cat, block_cnt,
+                               n_pblocks, row_o, ebeg_o, dst_o, m->d_seg_row, m->d_seg_ebeg, m->d_seg_dst);
+            hipLaunchKernelGGL(lane_table_kernel, dim3(1), dim3(64), 0, s, m->n_seg, block_cnt, n_pblocks, m->d_lane_tab);
+            TCG_TRY(launch_status("segment ordering kernels"));
+        }
+    }
+    if (!ordered) {
+        hipLaunchKernelGGL(lane_table_kernel, dim3(1), dim3(64), 0, s, m->n_seg, (const int32_t *)nullptr, (int64_t)0,
+                           m->d_lane_tab);
+        TCG_TRY(launch_status("lane_table_kernel"));
+    }
+    TCG_HIP(hipMemcpyAsync(m->h_lane_tab, m->d_lane_tab, sizeof(m->h_lane_tab), hipMemcpyDeviceToHost, s));
 
     TCG_TRY(dev_alloc(&m->d_col_to_row, m->total_unique));
     m->owned[m->n_owned++] = m->d_col_to_row;
