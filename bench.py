@@ -1,18 +1,23 @@
 #!/usr/bin/env python3
 """Benchmark of the neighbour-aggregation hot path on one MI355X.
 
-Workload: the large-SpMM configuration (1,000,000-node R-MAT graph, ~10M sampled pairs
-deduplicated and symmetrised, unit edge values, X fp32 1M x 128, fp32 accumulation, Y fp32),
-synthetic and seeded.  One step = one pass of the whole path on inputs resident in HBM:
+Default workload ("4"): the large-SpMM configuration -- 1,000,000-node R-MAT graph (~10M sampled pairs,
+deduplicated and symmetrised), unit edge values, X fp32 1M x 128, fp32 accumulation, Y fp32; synthetic
+and seeded.  One step = one pass of the whole path on inputs resident in HBM:
     tcg_sgt_build (graph translation) -> tcg_spmm (neighbour aggregation) -> tcg_sddmm (edge features)
 Each part is bracketed by HIP events on the stream the library launches on.
 
 The printed JSON line reports
   value              useful SpMM GFLOP/s = 2 * nnz * D / (mean tcg_spmm time of the timed steps)
-  ms_per_step        wall time of one whole step (translation + SpMM + SDDMM)
+  ms_per_step        wall time of one whole step
   roofline           algorithmic SpMM bytes per call / mean tcg_spmm time, against 8 TB/s HBM
   cpu_baseline       the CPU oracle's SpMM timed on the host cores, same inputs
-plus the SDDMM edge rate, the bf16-feature SpMM numbers and the translation time.
+plus the SDDMM edge rate, steady-state numbers on a reused translation, and the translation time.
+
+--workload selects another of the five synthetic workloads (1, 2, 3, 5, or 5a = workload 5 without
+the random relabelling, the case where windows share neighbours and the MFMA tile path is chosen);
+their steps run the operations that workload lists (3: SDDMM -> row softmax -> SpMM).  --features
+overrides the feature type (f32 / bf16).
 """
 import argparse
 import json
@@ -26,6 +31,16 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0
 
+WORKLOADS = {
+    # name: (config number, permute, default feature type, operations after the translation)
+    "1": (1, True, "f32", ("spmm",)),
+    "2": (2, True, "f32", ("spmm",)),
+    "3": (3, True, "f32", ("sddmm", "row_softmax", "spmm_w")),
+    "4": (4, True, "f32", ("spmm", "sddmm")),
+    "5": (5, True, "bf16", ("sddmm", "spmm")),
+    "5a": (5, False, "bf16", ("sddmm", "spmm")),
+}
+
 
 def algorithmic_bytes_spmm(n_rows, nnz, U, n_win, D, s_x, s_y, weighted):
     """Bytes the method itself has to move for one SpMM: every window-unique neighbour row of X
@@ -38,9 +53,11 @@ def algorithmic_bytes_sddmm(n_rows, nnz, U, n_win, D, s_x):
     return U * D * s_x + n_rows * D * s_x + 4 * nnz + 4 * U + 4 * nnz + 4 * (n_rows + 1) + 8 * (n_win + 1)
 
 
-def read_traffic():
+def read_traffic(workload, features):
     """HBM bytes per tcg_spmm call measured with rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE runs),
-    as summarised under profiles/; None when no summary is present."""
+    as summarised under profiles/; None when no summary covers this workload."""
+    if workload != "4" or features != "f32":
+        return None
     path = os.path.join(ROOT, "profiles", "spmm_rmat1m_d128_f32_hbm_traffic.json")
     try:
         with open(path) as f:
@@ -54,8 +71,10 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--nodes", type=int, default=1000000, help="node count of the R-MAT workload")
-    ap.add_argument("--dim", type=int, default=128)
+    ap.add_argument("--workload", default="4", choices=sorted(WORKLOADS))
+    ap.add_argument("--features", default=None, choices=["f32", "bf16"])
+    ap.add_argument("--nodes", type=int, default=None, help="override the node count of the workload")
+    ap.add_argument("--dim", type=int, default=None, help="override the feature width of the workload")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 512 MiB device copy (reference dispatch for HBM counter scaling)")
@@ -76,31 +95,47 @@ def main():
     torch.cuda.set_device(0)
     dev = torch.device("cuda:0")
 
+    cfg, permute, feat, ops = WORKLOADS[args.workload]
+    feat = args.features or feat
     t0 = time.time()
-    c = W.make_config(4, n=args.nodes, d=args.dim)
+    c = W.make_config(cfg, n=args.nodes, d=args.dim, permute=permute, x_dtype=feat)
     g, X = c["csr"], c["X"]
-    N, nnz, D = g.n_rows, g.nnz, args.dim
+    N, nnz, D = g.n_rows, g.nnz, X.shape[1]
     gen_s = time.time() - t0
+    tdt = {"f32": torch.float32, "bf16": torch.bfloat16}
     rp = torch.from_numpy(g.row_ptr).to(dev)
     ci = torch.from_numpy(g.col_idx).to(dev)
-    Xf = torch.from_numpy(X).to(dev)
-    Xb = torch.from_numpy(W.round_to_bf16(X)).to(dev).to(torch.bfloat16)
+    Xd = {feat: torch.from_numpy(X).to(dev).to(tdt[feat])}
+    other = "bf16" if feat == "f32" else "f32"
+    Xd[other] = (torch.from_numpy(W.round_to_bf16(X)).to(dev).to(torch.bfloat16) if other == "bf16"
+                 else torch.from_numpy(X).to(dev))
+    w_given = torch.from_numpy(c["w"]).to(dev) if c["w"] is not None else None
     Y = torch.empty((N, D), dtype=torch.float32, device=dev)
     E = torch.empty(nnz, dtype=torch.float32, device=dev)
+    P = torch.empty(nnz, dtype=torch.float32, device=dev)
     H, TW = 16, 8
 
     def ev():
         return torch.cuda.Event(enable_timing=True)
 
+    def run_op(meta, op, x):
+        if op == "spmm":
+            tcg.spmm(meta, x, w_given, Y=Y)
+        elif op == "spmm_w":
+            tcg.spmm(meta, x, P, Y=Y)
+        elif op == "sddmm":
+            tcg.sddmm(meta, x, out=E)
+        elif op == "row_softmax":
+            tcg.row_softmax(meta, E, out=P)
+
     def one_step(record):
-        e = [ev() for _ in range(4)]
+        e = [ev() for _ in range(len(ops) + 2)]
         e[0].record()
         meta = tcg.sgt_build(rp, ci, H, TW, validate=False)
         e[1].record()
-        tcg.spmm(meta, Xf, None, Y=Y)
-        e[2].record()
-        tcg.sddmm(meta, Xf, out=E)
-        e[3].record()
+        for k, op in enumerate(ops):
+            run_op(meta, op, Xd[feat])
+            e[k + 2].record()
         if record is not None:
             record.append(e)
         return meta
@@ -120,14 +155,15 @@ def main():
     torch.cuda.synchronize()
     wall = time.perf_counter() - t_start
     ms_per_step = wall * 1e3 / args.steps
-    sgt_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in events]))
-    spmm_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in events]))
-    sddmm_ms = float(np.mean([e[2].elapsed_time(e[3]) for e in events]))
+    parts = {"sgt_build": float(np.mean([e[0].elapsed_time(e[1]) for e in events]))}
+    for k, op in enumerate(ops):
+        parts[op.replace("spmm_w", "spmm")] = float(np.mean([e[k + 1].elapsed_time(e[k + 2]) for e in events]))
+    spmm_ms, sddmm_ms, sgt_ms = parts["spmm"], parts.get("sddmm"), parts["sgt_build"]
 
     U, n_win, tiles = meta.total_unique, meta.n_windows, meta.total_tiles
     plan = tcg.sgt_plan_stats(meta)
 
-    # Steady state of the two kernels with the translated graph reused (how training uses it).
+    # Steady state of the kernels with the translated graph reused (how training uses it).
     def timed_loop(fn, reps):
         fn()
         torch.cuda.synchronize()
@@ -140,16 +176,29 @@ def main():
         return a.elapsed_time(b) / reps
 
     reps = max(5, args.steps)
-    spmm_f32_loop_ms = timed_loop(lambda: tcg.spmm(meta, Xf, None, Y=Y), reps)
-    spmm_bf16_loop_ms = timed_loop(lambda: tcg.spmm(meta, Xb, None, Y=Y), reps)
-    sddmm_f32_loop_ms = timed_loop(lambda: tcg.sddmm(meta, Xf, out=E), reps)
-    sddmm_bf16_loop_ms = timed_loop(lambda: tcg.sddmm(meta, Xb, out=E), reps)
-
-    b_f32 = algorithmic_bytes_spmm(N, nnz, U, n_win, D, 4, 4, False)
-    b_bf16 = algorithmic_bytes_spmm(N, nnz, U, n_win, D, 2, 4, False)
-    b_sddmm = algorithmic_bytes_sddmm(N, nnz, U, n_win, D, 4)
+    weighted = w_given is not None or "spmm_w" in ops
+    spmm_op = "spmm_w" if "spmm_w" in ops else "spmm"
     flops = 2.0 * nnz * D
-    achieved = b_f32 / (spmm_ms * 1e-3) / 1e9
+    sx = {"f32": 4, "bf16": 2}
+    steady = {}
+    for f in ("f32", "bf16"):
+        b_sp = algorithmic_bytes_spmm(N, nnz, U, n_win, D, sx[f], 4, weighted)
+        ms = timed_loop(lambda: run_op(meta, spmm_op, Xd[f]), reps)
+        steady["spmm_%s_ms" % f] = ms
+        steady["spmm_%s_gflops" % f] = flops / ms / 1e6
+        steady["spmm_%s_frac_hbm" % f] = b_sp / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS
+        b_sd = algorithmic_bytes_sddmm(N, nnz, U, n_win, D, sx[f])
+        ms = timed_loop(lambda: run_op(meta, "sddmm", Xd[f]), reps)
+        steady["sddmm_%s_ms" % f] = ms
+        steady["sddmm_%s_gedges" % f] = nnz / ms / 1e6
+        steady["sddmm_%s_frac_hbm" % f] = b_sd / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS
+
+    b_spmm = algorithmic_bytes_spmm(N, nnz, U, n_win, D, sx[feat], 4, weighted)
+    b_sddmm = algorithmic_bytes_sddmm(N, nnz, U, n_win, D, sx[feat])
+    achieved = b_spmm / (spmm_ms * 1e-3) / 1e9
+    tile_share = plan["nnz_tile"] / max(nnz, 1) if feat != "f32" else 0.0
+    kernel = ("tcg_spmm (spmm_tile_kernel)" if tile_share > 0.5
+              else "tcg_spmm (spmm_gather_kernel + spmm_reduce_long_kernel)")
 
     out = {
         "metric": "SpMM useful GFLOP/s + HBM GB/s (1M nodes, D=128); SDDMM Gedges/s",
@@ -164,44 +213,42 @@ def main():
         "vs_baseline": None,
         "dtype": "f32",
         "data": "synthetic",
-        "config": {"workload": "config 4: R-MAT N=%d, %d stored entries, unit edge values, X fp32 N x %d, "
-                               "window 16 x 8; step = sgt_build + spmm + sddmm" % (N, nnz, D),
-                   "nnz": nnz, "window_unique_total": U, "tiles": tiles, "windows": n_win,
-                   "tile_windows": plan["n_tile_windows"], "segments": plan["n_segments"],
-                   "long_rows": plan["n_long_rows"]},
-        "step_parts_ms": {"sgt_build": sgt_ms, "spmm": spmm_ms, "sddmm": sddmm_ms},
+        "config": {"workload": "config %s (%s): N=%d, %d stored entries, X %s N x %d, %s edge values, window 16 x 8; "
+                               "step = sgt_build + %s" % (args.workload, c["name"], N, nnz, feat, D,
+                                                          "given" if weighted else "unit", " + ".join(ops)),
+                   "features": feat, "nnz": nnz, "window_unique_total": U, "tiles": tiles, "windows": n_win,
+                   "tile_windows": plan["n_tile_windows"], "tile_edge_share": tile_share,
+                   "segments": plan["n_segments"], "long_rows": plan["n_long_rows"]},
+        "step_parts_ms": parts,
         "spmm_hbm_gbs_algorithmic": achieved,
-        "sddmm_gedges_per_s": nnz / (sddmm_ms * 1e-3) / 1e9,
-        "sddmm_hbm_gbs_algorithmic": b_sddmm / (sddmm_ms * 1e-3) / 1e9,
         "sgt_medges_per_s": nnz / (sgt_ms * 1e-3) / 1e6,
-        "steady_state": {
-            "spmm_f32_ms": spmm_f32_loop_ms, "spmm_f32_gflops": flops / spmm_f32_loop_ms / 1e6,
-            "spmm_f32_frac_hbm": b_f32 / (spmm_f32_loop_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
-            "spmm_bf16_ms": spmm_bf16_loop_ms, "spmm_bf16_gflops": flops / spmm_bf16_loop_ms / 1e6,
-            "spmm_bf16_frac_hbm": b_bf16 / (spmm_bf16_loop_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
-            "sddmm_f32_ms": sddmm_f32_loop_ms, "sddmm_f32_gedges": nnz / sddmm_f32_loop_ms / 1e6,
-            "sddmm_bf16_ms": sddmm_bf16_loop_ms, "sddmm_bf16_gedges": nnz / sddmm_bf16_loop_ms / 1e6,
-        },
-        "roofline": {"bound": "hbm", "kernel": "tcg_spmm (spmm_gather_kernel + spmm_reduce_long_kernel)",
-                     "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": read_traffic(),
-                     "algorithmic_bytes": b_f32},
+        "steady_state": steady,
+        "roofline": {"bound": "hbm", "kernel": kernel, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": read_traffic(args.workload, feat),
+                     "algorithmic_bytes": b_spmm},
         "generate_s": gen_s,
     }
+    if sddmm_ms is not None:
+        out["sddmm_gedges_per_s"] = nnz / (sddmm_ms * 1e-3) / 1e9
+        out["sddmm_hbm_gbs_algorithmic"] = b_sddmm / (sddmm_ms * 1e-3) / 1e9
 
     if not args.no_cpu_baseline:
         import oracle
-        oracle.spmm(g.row_ptr, g.col_idx, X)                      # warm-up
+        w_cpu = c["w"]
+        if "spmm_w" in ops:
+            w_cpu = P.cpu().numpy()
+        oracle.spmm(g.row_ptr, g.col_idx, X, w_cpu)                   # warm-up
         ts = []
-        for _ in range(9):
+        budget = time.perf_counter() + 2.0                            # about 2 s wall on all host cores
+        while len(ts) < 3 or (time.perf_counter() < budget and len(ts) < 50):
             t1 = time.perf_counter()
-            oracle.spmm(g.row_ptr, g.col_idx, X)
+            oracle.spmm(g.row_ptr, g.col_idx, X, w_cpu)
             ts.append(time.perf_counter() - t1)
         t_cpu = sorted(ts)[len(ts) // 2]
         out["cpu_baseline"] = {"value": flops / t_cpu / 1e9, "unit": "GFLOP/s (useful, SpMM)",
                                "cores": oracle.num_threads(), "kind": "oracle",
-                               "sample": "the full workload (all %d rows), fp64-accumulate CSR SpMM, median of 9 runs, "
-                                         "%.2f s each" % (N, t_cpu)}
+                               "sample": "the full workload (all %d rows), fp64-accumulate CSR SpMM, median of %d runs, "
+                                         "%.3f s each" % (N, len(ts), t_cpu)}
     if args.calibrate_copy:
         src = torch.empty(128 << 20, dtype=torch.float32, device=dev).normal_()
         dst = torch.empty_like(src)
