@@ -58,6 +58,13 @@ def _load():
         lib.oracle_sddmm_tiled.argtypes = [ctypes.c_int32, _i32p, _i32p, _i32p, ctypes.c_int32,
                                            ctypes.c_int32, _f32p, ctypes.c_int32, ctypes.c_int64,
                                            _f64p]
+        lib.oracle_csr_transpose.restype = None
+        lib.oracle_csr_transpose.argtypes = [ctypes.c_int32, ctypes.c_int32, _i32p, _i32p, _i32p, _i32p, _i32p]
+        lib.oracle_sddmm_pq.restype = None
+        lib.oracle_sddmm_pq.argtypes = [ctypes.c_int32, _i32p, _i32p, _f32p, ctypes.c_int64, _f32p,
+                                        ctypes.c_int64, ctypes.c_int32, _f64p]
+        lib.oracle_row_softmax_backward.restype = None
+        lib.oracle_row_softmax_backward.argtypes = [ctypes.c_int32, _i32p, _f64p, _f64p, _f64p]
         _lib = lib
     return _lib
 
@@ -178,3 +185,42 @@ def sddmm_tiled(row_ptr, col_idx, edge_to_col, win_h, tile_w, X):
     _load().oracle_sddmm_tiled(n_rows, _p(rp, _i32p), _p(ci, _i32p), _p(e2c, _i32p), win_h,
                                tile_w, _p(X, _f32p), X.shape[1], X.shape[1], _p(out, _f64p))
     return out
+
+
+def csr_transpose(row_ptr, col_idx, n_cols):
+    """CSR of the transpose: (row_ptr_t [n_cols+1], col_idx_t [nnz], perm [nnz]); entry k of the
+    transpose is entry perm[k] of the input."""
+    rp, ci = _csr(row_ptr, col_idx)
+    if ci.size and int(ci.max()) >= n_cols:
+        raise ValueError("column index out of range")
+    rpt = np.zeros(n_cols + 1, dtype=np.int32)
+    cit = np.zeros(ci.size, dtype=np.int32)
+    perm = np.zeros(ci.size, dtype=np.int32)
+    _load().oracle_csr_transpose(rp.size - 1, n_cols, _p(rp, _i32p), _p(ci, _i32p), _p(rpt, _i32p),
+                                 _p(cit, _i32p), _p(perm, _i32p))
+    return rpt, cit, perm
+
+
+def sddmm_pq(row_ptr, col_idx, P, Q):
+    """out[e] = <P[row(e)], Q[col(e)]> in double, CSR order."""
+    rp, ci = _csr(row_ptr, col_idx)
+    P = _features(P, rp.size - 1)
+    Q = _features(Q, int(ci.max()) + 1 if ci.size else 0)
+    if P.shape[1] != Q.shape[1]:
+        raise ValueError("P and Q must have the same width")
+    out = np.zeros(ci.size, dtype=np.float64)
+    _load().oracle_sddmm_pq(rp.size - 1, _p(rp, _i32p), _p(ci, _i32p), _p(P, _f32p), P.shape[1],
+                            _p(Q, _f32p), Q.shape[1], P.shape[1], _p(out, _f64p))
+    return out
+
+
+def row_softmax_backward(row_ptr, p, dp):
+    """dv[e] = p[e] * (dp[e] - sum over the row of p * dp), in double."""
+    rp = np.ascontiguousarray(row_ptr, dtype=np.int32)
+    p = np.ascontiguousarray(p, dtype=np.float64)
+    dp = np.ascontiguousarray(dp, dtype=np.float64)
+    if rp[-1] != p.size or p.shape != dp.shape:
+        raise ValueError("p and dp must have one value per stored entry")
+    dv = np.zeros_like(p)
+    _load().oracle_row_softmax_backward(rp.size - 1, _p(rp, _i32p), _p(p, _f64p), _p(dp, _f64p), _p(dv, _f64p))
+    return dv

@@ -14,6 +14,9 @@
  *                           eigenvector closed form, the hand-worked example.
  *   oracle_sddmm         -- dense brute force, one-hot features, self-loops, the example.
  *   oracle_row_softmax   -- rows sum to one, shift invariance, two-entry closed form.
+ *   oracle_csr_transpose -- dense transpose by numpy, double transpose = identity, perm validity.
+ *   oracle_sddmm_pq, oracle_row_softmax_backward and the gradient formulas built from these
+ *                        -- central finite differences of the forward oracles.
  *   oracle_spmm_tiled /
  *   oracle_sddmm_tiled   -- must reproduce oracle_spmm / oracle_sddmm (Algorithms 2 and 3 run
  *                           from the translated metadata alone).
@@ -267,4 +270,66 @@ int oracle_sddmm_tiled(int32_t n_rows, const int32_t *row_ptr, const int32_t *co
     }
     free(val_tile); free(col_to_nid);
     return 0;
+}
+
+/*
+ * ---- building blocks of the backward pass (the paper trains GNNs -- section 4 -- but does not spell
+ * the gradients out; they follow from Equations 1 and 2 by the chain rule) ------------------------
+ *
+ * With L a scalar loss and G = dL/dY for Y = (w (.) A) X:
+ *     dL/dX = (w (.) A)^T G            -> oracle_spmm on the transposed structure with permuted w
+ *     dL/dw[e] = < G[row(e)], X[col(e)] >   -> oracle_sddmm_pq(P = G, Q = X)
+ * With g = dL/dout for out[e] = < X[row(e)], X[col(e)] >:
+ *     dL/dX = (g (.) A) X + (g (.) A)^T X
+ * With dp = dL/dp for p = row_softmax(v):   dL/dv[e] = p[e] * (dp[e] - sum_{e' in row} p[e'] dp[e'])
+ */
+
+/*
+ * Transpose of a CSR structure.  Entry k of the result is entry perm[k] of the input; inside a row
+ * of the transpose the entries keep the order of the input (ascending input row, then input
+ * position), so the result is unique.  out_row_ptr has n_cols + 1 entries.
+ */
+void oracle_csr_transpose(int32_t n_rows, int32_t n_cols, const int32_t *row_ptr, const int32_t *col_idx,
+                          int32_t *out_row_ptr, int32_t *out_col_idx, int32_t *perm)
+{
+    int64_t nnz = row_ptr[n_rows];
+    int64_t *cursor = (int64_t *)calloc((size_t)n_cols + 1, sizeof(int64_t));
+    for (int64_t e = 0; e < nnz; ++e) cursor[col_idx[e] + 1] += 1;
+    for (int32_t c = 0; c < n_cols; ++c) cursor[c + 1] += cursor[c];
+    for (int32_t c = 0; c <= n_cols; ++c) out_row_ptr[c] = (int32_t)cursor[c];
+    for (int32_t i = 0; i < n_rows; ++i)
+        for (int64_t e = row_ptr[i]; e < row_ptr[i + 1]; ++e) {
+            int64_t k = cursor[col_idx[e]]++;
+            out_col_idx[k] = i;
+            perm[k] = (int32_t)e;
+        }
+    free(cursor);
+}
+
+/* out[e] = < P[row(e)], Q[col(e)] > -- Equation 2 with two different dense operands. */
+void oracle_sddmm_pq(int32_t n_rows, const int32_t *row_ptr, const int32_t *col_idx,
+                     const float *P, int64_t ldp, const float *Q, int64_t ldq, int32_t D, double *out)
+{
+#pragma omp parallel for schedule(dynamic, 256)
+    for (int32_t i = 0; i < n_rows; ++i) {
+        const float *pi = P + (int64_t)i * ldp;
+        for (int64_t e = row_ptr[i]; e < row_ptr[i + 1]; ++e) {
+            const float *qj = Q + (int64_t)col_idx[e] * ldq;
+            double acc = 0.0;
+            for (int32_t d = 0; d < D; ++d) acc += (double)pi[d] * (double)qj[d];
+            out[e] = acc;
+        }
+    }
+}
+
+/* Gradient of the row softmax: dv[e] = p[e] * (dp[e] - sum over the row of p * dp). */
+void oracle_row_softmax_backward(int32_t n_rows, const int32_t *row_ptr, const double *p, const double *dp,
+                                 double *dv)
+{
+#pragma omp parallel for schedule(dynamic, 256)
+    for (int32_t i = 0; i < n_rows; ++i) {
+        double dot = 0.0;
+        for (int64_t k = row_ptr[i]; k < row_ptr[i + 1]; ++k) dot += p[k] * dp[k];
+        for (int64_t k = row_ptr[i]; k < row_ptr[i + 1]; ++k) dv[k] = p[k] * (dp[k] - dot);
+    }
 }
