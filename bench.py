@@ -76,6 +76,8 @@ def main():
     ap.add_argument("--nodes", type=int, default=None, help="override the node count of the workload")
     ap.add_argument("--dim", type=int, default=None, help="override the feature width of the workload")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--backward", action="store_true",
+                    help="also time the backward-pass building blocks (transpose, dX = A^T dY, dw = SDDMM(dY, X))")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 512 MiB device copy (reference dispatch for HBM counter scaling)")
     args = ap.parse_args()
@@ -231,6 +233,28 @@ def main():
     if sddmm_ms is not None:
         out["sddmm_gedges_per_s"] = nnz / (sddmm_ms * 1e-3) / 1e9
         out["sddmm_hbm_gbs_algorithmic"] = b_sddmm / (sddmm_ms * 1e-3) / 1e9
+
+    if args.backward:
+        def once(fn):
+            a, b = ev(), ev()
+            a.record()
+            r = fn()
+            b.record()
+            torch.cuda.synchronize()
+            return r, a.elapsed_time(b)
+        tcg.csr_transpose(rp, ci, g.n_cols)                              # warm-up (fills the allocator cache)
+        (rpt, cit, perm), tr_ms = once(lambda: tcg.csr_transpose(rp, ci, g.n_cols))
+        meta_t, sgt_t_ms = once(lambda: tcg.sgt_build(rpt, cit, H, TW, n_cols=N, validate=False))
+        Gd = torch.randn((N, D), device=dev).to(tdt[feat])               # stands for dL/dY
+        w_fwd = w_given if w_given is not None else torch.ones(nnz, device=dev)
+        w_t = tcg.edge_gather(perm, w_fwd)
+        out["backward"] = {
+            "csr_transpose_ms": tr_ms, "sgt_build_transposed_ms": sgt_t_ms,
+            "edge_gather_ms": timed_loop(lambda: tcg.edge_gather(perm, w_fwd, out=w_t), reps),
+            "dX_spmm_transposed_ms": timed_loop(lambda: tcg.spmm(meta_t, Gd, w_t, Y=Y), reps),
+            "dw_sddmm_pq_ms": timed_loop(lambda: tcg.sddmm_pq(meta, Gd, Xd[feat], out=E), reps),
+        }
+        meta_t.free()
 
     if not args.no_cpu_baseline:
         import oracle

@@ -152,12 +152,46 @@ TCG_API int tcg_sddmm(tcg_meta *meta, const void *d_X, tcg_dtype x_dt, int32_t D
               float *d_out, void *stream);
 
 /*
+ * Equation 2 with two dense operands:  d_out[e] = < P[i], Q[col_idx[e]] >  for every stored entry e of
+ * row i.  tcg_sddmm is the case P = Q = X.  This is the edge-value gradient of tcg_spmm
+ * (dw = tcg_sddmm_pq(P = dY, Q = X)).  P is [n_rows x D] with leading dimension ldp, Q is [n_cols x D]
+ * with leading dimension ldq; both have type x_dt.
+ */
+TCG_API int tcg_sddmm_pq(tcg_meta *meta, const void *d_P, int64_t ldp, const void *d_Q, int64_t ldq,
+                 tcg_dtype x_dt, int32_t D, float *d_out, void *stream);
+
+/*
  * Row-wise softmax over the stored entries of each row (the normalisation of the
  * attention-style workload; not part of the paper's method):
  *   d_out[e] = exp(d_in[e] - m_i) / sum_{e' in row i} exp(d_in[e'] - m_i),  m_i = row maximum.
  * In-place (d_out == d_in) is allowed.
  */
 TCG_API int tcg_row_softmax(const tcg_meta *meta, const float *d_in, float *d_out, void *stream);
+
+/*
+ * Gradient of tcg_row_softmax:  d_dv[e] = d_p[e] * (d_dp[e] - sum over the row of d_p * d_dp), where d_p is
+ * the softmax output and d_dp the gradient with respect to it.  In-place (d_dv == d_dp) is allowed.
+ */
+TCG_API int tcg_row_softmax_backward(const tcg_meta *meta, const float *d_p, const float *d_dp, float *d_dv,
+                             void *stream);
+
+/*
+ * CSR structure of the transpose (needed for dX = (w (.) A)^T dY when A is not symmetric: translate the
+ * transpose with tcg_sgt_build and run tcg_spmm on it with the permuted edge values).
+ *   d_out_row_ptr  device int32[n_cols + 1]
+ *   d_out_col_idx  device int32[nnz]   ascending inside every row of the transpose when the input has no
+ *                                      repeated entries (entries keep the input's row-major order)
+ *   d_perm         device int32[nnz]   entry k of the transpose is entry d_perm[k] of the input
+ * The result is unique and deterministic (stable sort by column).  Needs a well-formed CSR.
+ * Blocks until the stream has finished (temporary buffers are released on return).
+ */
+TCG_API int tcg_csr_transpose(int32_t n_rows, int32_t n_cols, int64_t nnz, const int32_t *d_row_ptr,
+                      const int32_t *d_col_idx, int32_t *d_out_row_ptr, int32_t *d_out_col_idx,
+                      int32_t *d_perm, void *stream);
+
+/* d_out[k] = d_in[d_perm[k]] for k < n: edge values in the order of the transposed structure.
+ * d_out must not overlap d_in.                                                                        */
+TCG_API int tcg_edge_gather(int64_t n, const int32_t *d_perm, const float *d_in, float *d_out, void *stream);
 
 /* Releases the metadata object and every device buffer it owns (NULL is a no-op).  The caller
  * must make sure no kernel using it is still running (its buffers go back to the library's cache

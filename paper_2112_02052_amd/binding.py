@@ -14,7 +14,8 @@ POLICY_AUTO, POLICY_GATHER, POLICY_TILE = 0, 1, 2
 
 EXPORTED = ["tcg_sgt_build", "tcg_sgt_sizes", "tcg_sgt_export", "tcg_sgt_set_policy",
             "tcg_sgt_plan_stats", "tcg_spmm", "tcg_sddmm", "tcg_row_softmax", "tcg_sgt_free",
-            "tcg_strerror", "tcg_release_cached_memory"]
+            "tcg_strerror", "tcg_release_cached_memory", "tcg_sddmm_pq", "tcg_row_softmax_backward",
+            "tcg_csr_transpose", "tcg_edge_gather"]
 
 _DTYPES = {torch.float32: TCG_F32, torch.bfloat16: TCG_BF16, torch.float16: TCG_F16}
 
@@ -58,6 +59,14 @@ def load_library():
     lib.tcg_row_softmax.argtypes = [_vp, _vp, _vp, _vp]
     lib.tcg_sgt_free.restype = None
     lib.tcg_sgt_free.argtypes = [_vp]
+    lib.tcg_sddmm_pq.restype = ctypes.c_int
+    lib.tcg_sddmm_pq.argtypes = [_vp, _vp, ctypes.c_int64, _vp, ctypes.c_int64, ctypes.c_int, ctypes.c_int32, _vp, _vp]
+    lib.tcg_row_softmax_backward.restype = ctypes.c_int
+    lib.tcg_row_softmax_backward.argtypes = [_vp, _vp, _vp, _vp, _vp]
+    lib.tcg_csr_transpose.restype = ctypes.c_int
+    lib.tcg_csr_transpose.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int64, _vp, _vp, _vp, _vp, _vp, _vp]
+    lib.tcg_edge_gather.restype = ctypes.c_int
+    lib.tcg_edge_gather.argtypes = [ctypes.c_int64, _vp, _vp, _vp, _vp]
     lib.tcg_release_cached_memory.restype = None
     lib.tcg_release_cached_memory.argtypes = []
     lib.tcg_strerror.restype = ctypes.c_char_p
@@ -200,4 +209,61 @@ def row_softmax(meta, v, out=None):
     if out is None:
         out = torch.empty_like(v)
     _check(load_library().tcg_row_softmax(meta._h, _ptr(v), _ptr(out), _stream()))
+    return out
+
+
+def sddmm_pq(meta, P, Q, out=None):
+    """tcg_sddmm_pq: out[e] = <P[row(e)], Q[col(e)]>, fp32 in CSR order."""
+    P = _features(meta, P, meta.n_rows)
+    Q = _features(meta, Q, meta.n_cols)
+    if P.dtype != Q.dtype or P.shape[1] != Q.shape[1]:
+        raise ValueError("P and Q must have the same type and width")
+    if out is None:
+        out = torch.empty(meta.nnz, dtype=torch.float32, device=P.device)
+    _need_cuda(out)
+    if out.dtype != torch.float32 or out.numel() != meta.nnz or not out.is_contiguous():
+        raise ValueError("out must be a contiguous fp32 tensor with one value per stored entry")
+    _check(load_library().tcg_sddmm_pq(meta._h, _ptr(P), P.stride(0), _ptr(Q), Q.stride(0), _DTYPES[P.dtype],
+                                       P.shape[1], _ptr(out), _stream()))
+    return out
+
+
+def row_softmax_backward(meta, p, dp, out=None):
+    """tcg_row_softmax_backward: dv = p * (dp - rowsum(p * dp))."""
+    _need_cuda(p, dp)
+    for t in (p, dp):
+        if t.dtype != torch.float32 or t.numel() != meta.nnz or not t.is_contiguous():
+            raise ValueError("p and dp must be contiguous fp32 tensors with one value per stored entry")
+    if out is None:
+        out = torch.empty_like(dp)
+    _check(load_library().tcg_row_softmax_backward(meta._h, _ptr(p), _ptr(dp), _ptr(out), _stream()))
+    return out
+
+
+def csr_transpose(row_ptr, col_idx, n_cols=None):
+    """tcg_csr_transpose: (row_ptr_t, col_idx_t, perm) as CUDA int32 tensors."""
+    _need_cuda(row_ptr, col_idx)
+    if row_ptr.dtype != torch.int32 or col_idx.dtype != torch.int32:
+        raise ValueError("CSR arrays must be int32")
+    row_ptr, col_idx = row_ptr.contiguous(), col_idx.contiguous()
+    n_rows = row_ptr.numel() - 1
+    n_cols = n_rows if n_cols is None else int(n_cols)
+    nnz = col_idx.numel()
+    rpt = torch.empty(n_cols + 1, dtype=torch.int32, device=row_ptr.device)
+    cit = torch.empty(nnz, dtype=torch.int32, device=row_ptr.device)
+    perm = torch.empty(nnz, dtype=torch.int32, device=row_ptr.device)
+    _check(load_library().tcg_csr_transpose(n_rows, n_cols, nnz, _ptr(row_ptr), _ptr(col_idx), _ptr(rpt), _ptr(cit),
+                                            _ptr(perm), _stream()))
+    return rpt, cit, perm
+
+
+def edge_gather(perm, values, out=None):
+    """tcg_edge_gather: out[k] = values[perm[k]]."""
+    _need_cuda(perm, values)
+    if perm.dtype != torch.int32 or values.dtype != torch.float32 or perm.numel() != values.numel():
+        raise ValueError("perm must be int32 and values fp32, of equal length")
+    perm, values = perm.contiguous(), values.contiguous()
+    if out is None:
+        out = torch.empty_like(values)
+    _check(load_library().tcg_edge_gather(perm.numel(), _ptr(perm), _ptr(values), _ptr(out), _stream()))
     return out

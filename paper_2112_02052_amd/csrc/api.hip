@@ -129,7 +129,42 @@ int tcg_sddmm(tcg_meta *meta, const void *d_X, tcg_dtype x_dt, int32_t D, int64_
     if (!meta || D < 1 || ldx < D || !dtype_ok(x_dt)) return TCG_EINVAL;
     if (meta->nnz > 0 && (!d_X || !d_out)) return TCG_EINVAL;
     if (reinterpret_cast<uintptr_t>(d_X) % dtype_size(x_dt)) return TCG_EINVAL;
-    return sddmm_impl(meta, d_X, x_dt, D, ldx, d_out, static_cast<hipStream_t>(stream));
+    return sddmm_impl(meta, d_X, ldx, d_X, ldx, x_dt, D, d_out, static_cast<hipStream_t>(stream));
+}
+
+int tcg_sddmm_pq(tcg_meta *meta, const void *d_P, int64_t ldp, const void *d_Q, int64_t ldq, tcg_dtype x_dt,
+                 int32_t D, float *d_out, void *stream)
+{
+    if (!meta || D < 1 || ldp < D || ldq < D || !dtype_ok(x_dt)) return TCG_EINVAL;
+    if (meta->nnz > 0 && (!d_P || !d_Q || !d_out)) return TCG_EINVAL;
+    if ((reinterpret_cast<uintptr_t>(d_P) % dtype_size(x_dt)) || (reinterpret_cast<uintptr_t>(d_Q) % dtype_size(x_dt)))
+        return TCG_EINVAL;
+    return sddmm_impl(meta, d_P, ldp, d_Q, ldq, x_dt, D, d_out, static_cast<hipStream_t>(stream));
+}
+
+int tcg_row_softmax_backward(const tcg_meta *meta, const float *d_p, const float *d_dp, float *d_dv, void *stream)
+{
+    if (!meta) return TCG_EINVAL;
+    if (meta->nnz > 0 && (!d_p || !d_dp || !d_dv)) return TCG_EINVAL;
+    return row_softmax_backward_impl(meta, d_p, d_dp, d_dv, static_cast<hipStream_t>(stream));
+}
+
+int tcg_csr_transpose(int32_t n_rows, int32_t n_cols, int64_t nnz, const int32_t *d_row_ptr,
+                      const int32_t *d_col_idx, int32_t *d_out_row_ptr, int32_t *d_out_col_idx, int32_t *d_perm,
+                      void *stream)
+{
+    if (n_rows < 0 || n_cols < 0 || nnz < 0 || !d_row_ptr || !d_out_row_ptr) return TCG_EINVAL;
+    if (nnz > 0 && (!d_col_idx || !d_out_col_idx || !d_perm)) return TCG_EINVAL;
+    if (nnz >= (int64_t)INT32_MAX || (int64_t)n_cols + 1 >= (int64_t)INT32_MAX) return TCG_ERANGE;
+    return csr_transpose_impl(n_rows, n_cols, nnz, d_row_ptr, d_col_idx, d_out_row_ptr, d_out_col_idx, d_perm,
+                              static_cast<hipStream_t>(stream));
+}
+
+int tcg_edge_gather(int64_t n, const int32_t *d_perm, const float *d_in, float *d_out, void *stream)
+{
+    if (n < 0) return TCG_EINVAL;
+    if (n > 0 && (!d_perm || !d_in || !d_out)) return TCG_EINVAL;
+    return edge_gather_impl(n, d_perm, d_in, d_out, static_cast<hipStream_t>(stream));
 }
 
 int tcg_row_softmax(const tcg_meta *meta, const float *d_in, float *d_out, void *stream)

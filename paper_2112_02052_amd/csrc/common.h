@@ -129,8 +129,15 @@ int choose_paths(tcg_meta *m, tcg_policy policy, float min_reuse, hipStream_t s)
 // spmm.hip / sddmm.hip / softmax.hip
 int spmm_impl(tcg_meta *m, const void *d_X, tcg_dtype x_dt, int32_t D, int64_t ldx, const float *d_w,
               void *d_Y, tcg_dtype y_dt, int64_t ldy, hipStream_t s);
-int sddmm_impl(tcg_meta *m, const void *d_X, tcg_dtype x_dt, int32_t D, int64_t ldx, float *d_out,
-               hipStream_t s);
+int sddmm_impl(tcg_meta *m, const void *d_P, int64_t ldp, const void *d_X, int64_t ldx, tcg_dtype x_dt, int32_t D,
+               float *d_out, hipStream_t s);
+
+// backward.hip
+int row_softmax_backward_impl(const tcg_meta *m, const float *d_p, const float *d_dp, float *d_dv, hipStream_t s);
+int csr_transpose_impl(int32_t n_rows, int32_t n_cols, int64_t nnz, const int32_t *d_row_ptr,
+                       const int32_t *d_col_idx, int32_t *d_out_row_ptr, int32_t *d_out_col_idx, int32_t *d_perm,
+                       hipStream_t s);
+int edge_gather_impl(int64_t n, const int32_t *d_perm, const float *d_in, float *d_out, hipStream_t s);
 int row_softmax_impl(const tcg_meta *m, const float *d_in, float *d_out, hipStream_t s);
 
 // spmm_tile.hip: can the condensed-tile kernels take this operand?

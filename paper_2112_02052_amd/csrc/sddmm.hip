@@ -15,8 +15,8 @@
 namespace tcg {
 
 // sddmm_tile.hip
-int sddmm_tile_launch(tcg_meta *m, const void *d_X, tcg_dtype x_dt, int32_t D, int64_t ldx, float *d_out,
-                      hipStream_t s);
+int sddmm_tile_launch(tcg_meta *m, const void *d_P, int64_t ldp, const void *d_Q, int64_t ldq, tcg_dtype x_dt,
+                      int32_t D, float *d_out, hipStream_t s);
 
 namespace {
 
@@ -63,8 +63,8 @@ template <int DT, int G, int NCH, int UNROLL>
 __global__ __launch_bounds__(kBlock) void sddmm_gather_kernel(
     const int32_t *__restrict__ lane_tab, const int32_t *__restrict__ seg_row, const int32_t *__restrict__ seg_ebeg,
     const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ col_idx,
-    const char *__restrict__ X, int64_t ldx_bytes, int32_t n_chunks, float *__restrict__ out,
-    const uint8_t *__restrict__ win_path, int32_t win_h)
+    const char *__restrict__ P, int64_t ldp_bytes, const char *__restrict__ X, int64_t ldx_bytes, int32_t n_chunks,
+    float *__restrict__ out, const uint8_t *__restrict__ win_path, int32_t win_h)
 {
     constexpr int VEC = Elem<DT>::VEC;
     const int lane = threadIdx.x % G;
@@ -77,7 +77,7 @@ __global__ __launch_bounds__(kBlock) void sddmm_gather_kernel(
 
     float xi[NCH][VEC];
     {
-        const char *xr = X + (int64_t)row * ldx_bytes;
+        const char *xr = P + (int64_t)row * ldp_bytes;
 #pragma unroll
         for (int c = 0; c < NCH; ++c) {
             int chunk = lane + c * G;
@@ -143,9 +143,9 @@ __global__ __launch_bounds__(kBlock) void sddmm_gather_kernel(
 // Any D / alignment: one wavefront per segment, lanes stride over the feature dimension.
 __global__ __launch_bounds__(kBlock) void sddmm_gather_generic_kernel(
     const int32_t *__restrict__ lane_tab, const int32_t *__restrict__ seg_row, const int32_t *__restrict__ seg_ebeg,
-    const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ col_idx, const void *__restrict__ X,
-    int x_dt, int64_t ldx, int32_t D, float *__restrict__ out, const uint8_t *__restrict__ win_path,
-    int32_t win_h)
+    const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ col_idx, const void *__restrict__ P,
+    int64_t ldp, const void *__restrict__ X, int x_dt, int64_t ldx, int32_t D, float *__restrict__ out,
+    const uint8_t *__restrict__ win_path, int32_t win_h)
 {
     const int lane = threadIdx.x & (kWave - 1);
     const int64_t seg = plan_segment(lane_tab, kBlock / kWave, threadIdx.x >> 6);
@@ -158,7 +158,7 @@ __global__ __launch_bounds__(kBlock) void sddmm_gather_generic_kernel(
         const int64_t j = col_idx[e];
         float a = 0.f;
         for (int32_t d = lane; d < D; d += kWave)
-            a = fmaf(load_elem(X, (int64_t)row * ldx + d, x_dt), load_elem(X, j * ldx + d, x_dt), a);
+            a = fmaf(load_elem(P, (int64_t)row * ldp + d, x_dt), load_elem(X, j * ldx + d, x_dt), a);
 #pragma unroll
         for (int off = 1; off < kWave; off <<= 1) a += __shfl_xor(a, off, kWave);
         if (lane == 0) out[e] = a;
@@ -232,56 +232,59 @@ __global__ __launch_bounds__(kBlock) void row_softmax_long_kernel(const int32_t 
 }
 
 template <int DT, int G, int NCH>
-void launch_sddmm(const tcg_meta *m, const void *X, int64_t ldx, int32_t n_chunks, float *out,
-                  const uint8_t *win_path, hipStream_t s)
+void launch_sddmm(const tcg_meta *m, const void *P, int64_t ldp, const void *X, int64_t ldx, int32_t n_chunks,
+                  float *out, const uint8_t *win_path, hipStream_t s)
 {
     constexpr int UNROLL = NCH == 1 ? 8 : (NCH == 2 ? 4 : 2);
     const unsigned grid = (unsigned)plan_grid(m->h_lane_tab, kBlock / G);
     hipLaunchKernelGGL((sddmm_gather_kernel<DT, G, NCH, UNROLL>), dim3(grid), dim3(kBlock), 0, s, m->d_lane_tab,
-                       m->d_seg_row, m->d_seg_ebeg, m->d_row_ptr, m->d_col_idx, static_cast<const char *>(X),
-                       ldx * Elem<DT>::BYTES, n_chunks, out, win_path, m->win_h);
+                       m->d_seg_row, m->d_seg_ebeg, m->d_row_ptr, m->d_col_idx, static_cast<const char *>(P),
+                       ldp * Elem<DT>::BYTES, static_cast<const char *>(X), ldx * Elem<DT>::BYTES, n_chunks, out, win_path,
+                       m->win_h);
 }
 
 template <int DT>
-bool dispatch_sddmm(const tcg_meta *m, const void *X, int64_t ldx, int32_t n_chunks, float *out,
-                    const uint8_t *win_path, hipStream_t s)
+bool dispatch_sddmm(const tcg_meta *m, const void *P, int64_t ldp, const void *X, int64_t ldx, int32_t n_chunks,
+                    float *out, const uint8_t *win_path, hipStream_t s)
 {
-    if (n_chunks <= 4) launch_sddmm<DT, 4, 1>(m, X, ldx, n_chunks, out, win_path, s);
-    else if (n_chunks <= 8) launch_sddmm<DT, 8, 1>(m, X, ldx, n_chunks, out, win_path, s);
-    else if (n_chunks <= 16) launch_sddmm<DT, 16, 1>(m, X, ldx, n_chunks, out, win_path, s);
-    else if (n_chunks <= 32) launch_sddmm<DT, 32, 1>(m, X, ldx, n_chunks, out, win_path, s);
-    else if (n_chunks <= 64) launch_sddmm<DT, 64, 1>(m, X, ldx, n_chunks, out, win_path, s);
-    else if (n_chunks <= 128) launch_sddmm<DT, 64, 2>(m, X, ldx, n_chunks, out, win_path, s);
-    else if (n_chunks <= 256) launch_sddmm<DT, 64, 4>(m, X, ldx, n_chunks, out, win_path, s);
+    if (n_chunks <= 4) launch_sddmm<DT, 4, 1>(m, P, ldp, X, ldx, n_chunks, out, win_path, s);
+    else if (n_chunks <= 8) launch_sddmm<DT, 8, 1>(m, P, ldp, X, ldx, n_chunks, out, win_path, s);
+    else if (n_chunks <= 16) launch_sddmm<DT, 16, 1>(m, P, ldp, X, ldx, n_chunks, out, win_path, s);
+    else if (n_chunks <= 32) launch_sddmm<DT, 32, 1>(m, P, ldp, X, ldx, n_chunks, out, win_path, s);
+    else if (n_chunks <= 64) launch_sddmm<DT, 64, 1>(m, P, ldp, X, ldx, n_chunks, out, win_path, s);
+    else if (n_chunks <= 128) launch_sddmm<DT, 64, 2>(m, P, ldp, X, ldx, n_chunks, out, win_path, s);
+    else if (n_chunks <= 256) launch_sddmm<DT, 64, 4>(m, P, ldp, X, ldx, n_chunks, out, win_path, s);
     else return false;
     return true;
 }
 
 }  // namespace
 
-int sddmm_impl(tcg_meta *m, const void *d_X, tcg_dtype x_dt, int32_t D, int64_t ldx, float *d_out,
-               hipStream_t s)
+int sddmm_impl(tcg_meta *m, const void *d_P, int64_t ldp, const void *d_X, int64_t ldx, tcg_dtype x_dt, int32_t D,
+               float *d_out, hipStream_t s)
 {
     if (m->n_rows == 0 || m->nnz == 0) return TCG_OK;
-    const bool use_tiles = m->n_tile_win > 0 && m->win_h == 16 && tile_path_supports(x_dt, D, ldx, d_X);
+    const bool use_tiles = m->n_tile_win > 0 && m->win_h == 16 && tile_path_supports(x_dt, D, ldx, d_X) &&
+                           tile_path_supports(x_dt, D, ldp, d_P);
     const uint8_t *win_path = use_tiles ? m->d_win_path : nullptr;
-    if (use_tiles) TCG_TRY(sddmm_tile_launch(m, d_X, x_dt, D, ldx, d_out, s));
+    if (use_tiles) TCG_TRY(sddmm_tile_launch(m, d_P, ldp, d_X, ldx, x_dt, D, d_out, s));
     if (use_tiles && m->nnz_tile == m->nnz) return TCG_OK;
 
     const int es = dtype_size(x_dt);
     const bool vec_ok = ((int64_t)D * es) % 16 == 0 && (ldx * es) % 16 == 0 && ldx * es < (1ll << 32) &&
-                        (reinterpret_cast<uintptr_t>(d_X) & 15) == 0;
+                        (ldp * es) % 16 == 0 && (reinterpret_cast<uintptr_t>(d_X) & 15) == 0 &&
+                        (reinterpret_cast<uintptr_t>(d_P) & 15) == 0;
     bool done = false;
     if (vec_ok) {
         const int32_t n_chunks = (int32_t)((int64_t)D * es / 16);
-        if (x_dt == TCG_F32) done = dispatch_sddmm<TCG_F32>(m, d_X, ldx, n_chunks, d_out, win_path, s);
-        else if (x_dt == TCG_BF16) done = dispatch_sddmm<TCG_BF16>(m, d_X, ldx, n_chunks, d_out, win_path, s);
-        else done = dispatch_sddmm<TCG_F16>(m, d_X, ldx, n_chunks, d_out, win_path, s);
+        if (x_dt == TCG_F32) done = dispatch_sddmm<TCG_F32>(m, d_P, ldp, d_X, ldx, n_chunks, d_out, win_path, s);
+        else if (x_dt == TCG_BF16) done = dispatch_sddmm<TCG_BF16>(m, d_P, ldp, d_X, ldx, n_chunks, d_out, win_path, s);
+        else done = dispatch_sddmm<TCG_F16>(m, d_P, ldp, d_X, ldx, n_chunks, d_out, win_path, s);
     }
     if (!done) {
         const unsigned grid = (unsigned)plan_grid(m->h_lane_tab, kBlock / kWave);
         hipLaunchKernelGGL(sddmm_gather_generic_kernel, dim3(grid), dim3(kBlock), 0, s, m->d_lane_tab, m->d_seg_row,
-                           m->d_seg_ebeg, m->d_row_ptr, m->d_col_idx, d_X, (int)x_dt, ldx, D, d_out, win_path,
+                           m->d_seg_ebeg, m->d_row_ptr, m->d_col_idx, d_P, ldp, d_X, (int)x_dt, ldx, D, d_out, win_path,
                            m->win_h);
     }
     return launch_status("sddmm_gather_kernel");

@@ -3,7 +3,8 @@
 // One workgroup (4 wavefronts) per row window of 16 rows assigned to the tile path.  Here the
 // contraction runs over the feature dimension, which is contiguous in memory for both operands,
 // so the MFMA operands are loaded straight from global memory with 16-byte loads:
-//   FetchDenseRow  XTile_A = the window's own 16 rows, kept in registers for the whole window;
+//   FetchDenseRow  XTile_A = the window's own 16 rows (of P; P = X in the paper's operation), kept in
+//                  registers for the whole window;
 //   FetchDenseCol  XTile_B = 16 neighbour rows named by col_to_row (each unique neighbour once);
 //   TCcompute      v_mfma_f32_16x16x32 accumulated over all of D before anything is written
 //                  (section 4.3: the result is only output after all iterations along the
@@ -48,8 +49,8 @@ template <int DT, int KSTEPS>
 __global__ __launch_bounds__(kTileBlock) void sddmm_tile_kernel(
     int32_t n_rows, int64_t n_win, const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ edge_to_col,
     const int32_t *__restrict__ win_unique_ptr, const int32_t *__restrict__ col_to_row,
-    const uint8_t *__restrict__ win_path, const char *__restrict__ X, int64_t ldx_bytes, int32_t D,
-    float *__restrict__ out)
+    const uint8_t *__restrict__ win_path, const char *__restrict__ P, int64_t ldp_bytes,
+    const char *__restrict__ X, int64_t ldx_bytes, int32_t D, float *__restrict__ out)
 {
     __shared__ float s_e[16 * kEStride];
     __shared__ int32_t s_rp[17];
@@ -82,7 +83,7 @@ __global__ __launch_bounds__(kTileBlock) void sddmm_tile_kernel(
         for (int kk = 0; kk < KSTEPS; ++kk) {
             int32_t off = kk * 64 + koff;
             a[kk] = make_uint4(0, 0, 0, 0);
-            if (row < n_rows && off < row_bytes) a[kk] = *reinterpret_cast<const uint4 *>(X + row * ldx_bytes + off);
+            if (row < n_rows && off < row_bytes) a[kk] = *reinterpret_cast<const uint4 *>(P + row * ldp_bytes + off);
         }
     }
 
@@ -120,31 +121,33 @@ __global__ __launch_bounds__(kTileBlock) void sddmm_tile_kernel(
 }
 
 template <int DT, int KSTEPS>
-void launch(const tcg_meta *m, const void *X, int64_t ldx, int32_t D, float *out, hipStream_t s)
+void launch(const tcg_meta *m, const void *P, int64_t ldp, const void *X, int64_t ldx, int32_t D, float *out,
+            hipStream_t s)
 {
     hipLaunchKernelGGL((sddmm_tile_kernel<DT, KSTEPS>), dim3((unsigned)(kXcds * ceil_div(m->n_win, kXcds))), dim3(kTileBlock), 0, s,
                        m->n_rows, m->n_win, m->d_row_ptr, m->d_edge_to_col, m->d_win_unique_ptr, m->d_col_to_row,
-                       m->d_win_path, static_cast<const char *>(X), ldx * 2, D, out);
+                       m->d_win_path, static_cast<const char *>(P), ldp * 2, static_cast<const char *>(X), ldx * 2, D, out);
 }
 
 template <int DT>
-void launch_k(const tcg_meta *m, const void *X, int64_t ldx, int32_t D, float *out, hipStream_t s)
+void launch_k(const tcg_meta *m, const void *P, int64_t ldp, const void *X, int64_t ldx, int32_t D, float *out,
+              hipStream_t s)
 {
     const int ks = (D + 31) / 32;
-    if (ks <= 1) launch<DT, 1>(m, X, ldx, D, out, s);
-    else if (ks <= 2) launch<DT, 2>(m, X, ldx, D, out, s);
-    else if (ks <= 4) launch<DT, 4>(m, X, ldx, D, out, s);
-    else if (ks <= 8) launch<DT, 8>(m, X, ldx, D, out, s);
-    else launch<DT, 16>(m, X, ldx, D, out, s);
+    if (ks <= 1) launch<DT, 1>(m, P, ldp, X, ldx, D, out, s);
+    else if (ks <= 2) launch<DT, 2>(m, P, ldp, X, ldx, D, out, s);
+    else if (ks <= 4) launch<DT, 4>(m, P, ldp, X, ldx, D, out, s);
+    else if (ks <= 8) launch<DT, 8>(m, P, ldp, X, ldx, D, out, s);
+    else launch<DT, 16>(m, P, ldp, X, ldx, D, out, s);
 }
 
 }  // namespace
 
-int sddmm_tile_launch(tcg_meta *m, const void *d_X, tcg_dtype x_dt, int32_t D, int64_t ldx, float *d_out,
-                      hipStream_t s)
+int sddmm_tile_launch(tcg_meta *m, const void *d_P, int64_t ldp, const void *d_X, int64_t ldx, tcg_dtype x_dt,
+                      int32_t D, float *d_out, hipStream_t s)
 {
-    if (x_dt == TCG_BF16) launch_k<TCG_BF16>(m, d_X, ldx, D, d_out, s);
-    else launch_k<TCG_F16>(m, d_X, ldx, D, d_out, s);
+    if (x_dt == TCG_BF16) launch_k<TCG_BF16>(m, d_P, ldp, d_X, ldx, D, d_out, s);
+    else launch_k<TCG_F16>(m, d_P, ldp, d_X, ldx, D, d_out, s);
     return launch_status("sddmm_tile_kernel");
 }
 

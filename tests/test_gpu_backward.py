@@ -1,0 +1,126 @@
+"""GPU parity of the backward-pass building blocks against the oracle: CSR transpose (bit-exact),
+two-operand SDDMM, row-softmax gradient, and the composed gradients of SpMM and SDDMM."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2112_02052_amd as tcg
+import workloads as W
+
+from gpu_util import TOL_F32, TOL_MFMA, dev, norm_err, upload_csr, upload_x
+from test_gpu_parity import csr_from_rows, hub_graph
+
+pytestmark = pytest.mark.gpu
+
+
+def asymmetric_graph(n_rows, n_cols, seed, max_deg=40):
+    rng = np.random.default_rng(seed)
+    rows = [rng.choice(n_cols, size=int(rng.integers(0, max_deg)), replace=False) for _ in range(n_rows)]
+    rows[1] = rng.choice(n_cols, size=min(n_cols, 700), replace=False)       # one long row
+    return csr_from_rows(rows, n_cols)
+
+
+@pytest.mark.parametrize("make", [lambda: asymmetric_graph(300, 5000, 1), lambda: asymmetric_graph(5000, 300, 2),
+                                  lambda: hub_graph(3000), lambda: W.make_config(4, n=40000, d=2)["csr"],
+                                  lambda: W.make_config(3, n=17, d=2)["csr"],
+                                  lambda: csr_from_rows([[], [], []], 5), lambda: csr_from_rows([[2, 2, 0]], 3)])
+def test_csr_transpose_bit_exact(make):
+    g = make()
+    rp, ci = upload_csr(g)
+    rpt, cit, perm = tcg.csr_transpose(rp, ci, g.n_cols)
+    torch.cuda.synchronize()
+    ref = oracle.csr_transpose(g.row_ptr, g.col_idx, g.n_cols)
+    assert np.array_equal(rpt.cpu().numpy(), ref[0])
+    assert np.array_equal(cit.cpu().numpy(), ref[1])
+    assert np.array_equal(perm.cpu().numpy(), ref[2])
+
+
+def test_edge_gather_and_softmax_backward():
+    g = hub_graph(2500)
+    rp, ci = upload_csr(g)
+    meta = tcg.sgt_build(rp, ci, 16, 8)
+    rng = np.random.default_rng(0)
+    v = rng.standard_normal(g.nnz).astype(np.float32) * 3
+    dp = rng.standard_normal(g.nnz).astype(np.float32)
+    p = tcg.row_softmax(meta, torch.from_numpy(v).to(dev()))
+    dv = tcg.row_softmax_backward(meta, p, torch.from_numpy(dp).to(dev()))
+    torch.cuda.synchronize()
+    ref = oracle.row_softmax_backward(g.row_ptr, p.cpu().numpy().astype(np.float64), dp.astype(np.float64))
+    assert norm_err(dv.cpu().numpy(), ref) <= TOL_F32
+    perm = torch.from_numpy(rng.permutation(g.nnz).astype(np.int32)).to(dev())
+    out = tcg.edge_gather(perm, p)
+    torch.cuda.synchronize()
+    assert torch.equal(out, p[perm.long()])
+    meta.free()
+
+
+@pytest.mark.parametrize("x_dtype,policy,tol", [("f32", tcg.POLICY_AUTO, TOL_F32), ("bf16", tcg.POLICY_GATHER, TOL_F32),
+                                                ("bf16", tcg.POLICY_TILE, TOL_F32), ("f16", tcg.POLICY_TILE, TOL_F32)])
+def test_sddmm_pq(x_dtype, policy, tol):
+    rnd = {"f32": lambda a: a, "bf16": W.round_to_bf16, "f16": lambda a: a.astype(np.float16).astype(np.float32)}[x_dtype]
+    for g, D in ((asymmetric_graph(900, 2000, 3), 64), (asymmetric_graph(2000, 900, 4), 40),
+                 (W.make_config(5, n=64 * 20, d=2, permute=False)["csr"], 256)):
+        P = rnd(W.features_normal(g.n_rows, D, 1))
+        Q = rnd(W.features_normal(g.n_cols, D, 2, stream=7))
+        rp, ci = upload_csr(g)
+        meta = tcg.sgt_build(rp, ci, 16, 16, n_cols=g.n_cols)
+        tcg.sgt_set_policy(meta, policy)
+        out = tcg.sddmm_pq(meta, upload_x(P, x_dtype), upload_x(Q, x_dtype))
+        torch.cuda.synchronize()
+        assert norm_err(out.cpu().numpy(), oracle.sddmm_pq(g.row_ptr, g.col_idx, P, Q)) <= tol
+        meta.free()
+
+
+def test_spmm_backward_composition():
+    # Y = (w (.) A) X on an asymmetric rectangular A: dX through the transposed structure, dw by SDDMM.
+    g = asymmetric_graph(1500, 2600, 5)
+    D = 64
+    X = W.features_normal(g.n_cols, D, 3)
+    w = np.random.default_rng(1).standard_normal(g.nnz).astype(np.float32)
+    G = W.features_normal(g.n_rows, D, 4, stream=9)                     # dL/dY
+    rp, ci = upload_csr(g)
+    meta = tcg.sgt_build(rp, ci, 16, 8, n_cols=g.n_cols)
+    rpt, cit, perm = tcg.csr_transpose(rp, ci, g.n_cols)
+    meta_t = tcg.sgt_build(rpt, cit, 16, 8, n_cols=g.n_rows)
+    wd, Gd, Xd = torch.from_numpy(w).to(dev()), upload_x(G, "f32"), upload_x(X, "f32")
+    dX = tcg.spmm(meta_t, Gd, tcg.edge_gather(perm, wd))
+    dw = tcg.sddmm_pq(meta, Gd, Xd)
+    torch.cuda.synchronize()
+    rpt_o, cit_o, perm_o = oracle.csr_transpose(g.row_ptr, g.col_idx, g.n_cols)
+    assert norm_err(dX.cpu().numpy(), oracle.spmm(rpt_o, cit_o, G, w[perm_o])) <= TOL_F32
+    assert norm_err(dw.cpu().numpy(), oracle.sddmm_pq(g.row_ptr, g.col_idx, G, X)) <= TOL_F32
+    meta.free()
+    meta_t.free()
+
+
+def test_attention_layer_backward_composition():
+    # Y = (softmax(SDDMM(X)) (.) A) X, loss = sum(Y * G): every gradient step through the library,
+    # compared with the same chain evaluated by the oracle.
+    c = W.make_config(3, n=6000)
+    g, X = c["csr"], c["X"]
+    G = W.features_normal(g.n_rows, X.shape[1], 5, stream=11)
+    rp, ci = upload_csr(g)
+    meta = tcg.sgt_build(rp, ci, 16, 8)
+    rpt, cit, perm = tcg.csr_transpose(rp, ci, g.n_cols)
+    meta_t = tcg.sgt_build(rpt, cit, 16, 8)
+    Xd, Gd = upload_x(X, "f32"), upload_x(G, "f32")
+    e = tcg.sddmm(meta, Xd)
+    p = tcg.row_softmax(meta, e)
+    dp = tcg.sddmm_pq(meta, Gd, Xd)                                     # dL/dp
+    de = tcg.row_softmax_backward(meta, p, dp)                          # dL/de
+    dX = (tcg.spmm(meta_t, Gd, tcg.edge_gather(perm, p))                # through the aggregation
+          + tcg.spmm(meta, Xd, de) + tcg.spmm(meta_t, Xd, tcg.edge_gather(perm, de)))   # through the scores
+    torch.cuda.synchronize()
+    e_o = oracle.sddmm(g.row_ptr, g.col_idx, X)
+    p_o = oracle.row_softmax(g.row_ptr, e_o)
+    dp_o = oracle.sddmm_pq(g.row_ptr, g.col_idx, G, X)
+    de_o = oracle.row_softmax_backward(g.row_ptr, p_o, dp_o)
+    rpt_o, cit_o, perm_o = oracle.csr_transpose(g.row_ptr, g.col_idx, g.n_cols)
+    f32 = lambda a: a.astype(np.float32)
+    dX_o = (oracle.spmm(rpt_o, cit_o, G, f32(p_o[perm_o])) + oracle.spmm(g.row_ptr, g.col_idx, X, f32(de_o))
+            + oracle.spmm(rpt_o, cit_o, X, f32(de_o[perm_o])))
+    assert norm_err(de.cpu().numpy(), de_o) <= 1e-4       # the softmax amplifies the fp32 rounding of the scores
+    assert norm_err(dX.cpu().numpy(), dX_o) <= 1e-4
+    meta.free()
+    meta_t.free()
