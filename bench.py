@@ -195,6 +195,12 @@ def main():
         steady["sddmm_%s_gedges" % f] = nnz / ms / 1e6
         steady["sddmm_%s_frac_hbm" % f] = b_sd / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS
 
+    if "row_softmax" in ops:
+        # The same layer as one fused call (scores kept in registers, every neighbour row gathered once).
+        for f in ("f32", "bf16"):
+            steady["attention_fused_%s_ms" % f] = timed_loop(lambda: tcg.attention(meta, Xd[f], Y=Y), reps)
+        steady["attention_three_calls_%s_ms" % feat] = timed_loop(
+            lambda: [run_op(meta, op, Xd[feat]) for op in ops], reps)
     b_spmm = algorithmic_bytes_spmm(N, nnz, U, n_win, D, sx[feat], 4, weighted)
     b_sddmm = algorithmic_bytes_sddmm(N, nnz, U, n_win, D, sx[feat])
     achieved = b_spmm / (spmm_ms * 1e-3) / 1e9

@@ -169,6 +169,19 @@ TCG_API int tcg_sddmm_pq(tcg_meta *meta, const void *d_P, int64_t ldp, const voi
 TCG_API int tcg_row_softmax(const tcg_meta *meta, const float *d_in, float *d_out, void *stream);
 
 /*
+ * Fused attention-style aggregation (the SDDMM -> row softmax -> SpMM chain of the paper's AGNN
+ * workload in one pass over the graph):
+ *   Y[i] = sum over the stored entries e of row i of  softmax_i(< X[i], X[col_idx[.]] >)_e * X[col_idx[e]]
+ * Every neighbour row is gathered once; the scores stay in registers (online softmax).  Rows without
+ * entries give 0.  d_scores: NULL, or device float[nnz] that receives the raw scores <x_i, x_j> in CSR
+ * order (what tcg_sddmm would return; the backward pass needs them).  Needs rows of X whose byte
+ * length and stride are multiples of 16 bytes, a 16-byte aligned base and D * sizeof(element) <= 2048
+ * (TCG_EINVAL otherwise).  Always runs on the gather path.  X: [max(n_rows, n_cols) x D].
+ */
+TCG_API int tcg_attention(tcg_meta *meta, const void *d_X, tcg_dtype x_dt, int32_t D, int64_t ldx,
+                  float *d_scores, void *d_Y, tcg_dtype y_dt, int64_t ldy, void *stream);
+
+/*
  * Gradient of tcg_row_softmax:  d_dv[e] = d_p[e] * (d_dp[e] - sum over the row of d_p * d_dp), where d_p is
  * the softmax output and d_dp the gradient with respect to it.  In-place (d_dv == d_dp) is allowed.
  */

@@ -15,7 +15,7 @@ POLICY_AUTO, POLICY_GATHER, POLICY_TILE = 0, 1, 2
 EXPORTED = ["tcg_sgt_build", "tcg_sgt_sizes", "tcg_sgt_export", "tcg_sgt_set_policy",
             "tcg_sgt_plan_stats", "tcg_spmm", "tcg_sddmm", "tcg_row_softmax", "tcg_sgt_free",
             "tcg_strerror", "tcg_release_cached_memory", "tcg_sddmm_pq", "tcg_row_softmax_backward",
-            "tcg_csr_transpose", "tcg_edge_gather"]
+            "tcg_csr_transpose", "tcg_edge_gather", "tcg_attention"]
 
 _DTYPES = {torch.float32: TCG_F32, torch.bfloat16: TCG_BF16, torch.float16: TCG_F16}
 
@@ -67,6 +67,9 @@ def load_library():
     lib.tcg_csr_transpose.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int64, _vp, _vp, _vp, _vp, _vp, _vp]
     lib.tcg_edge_gather.restype = ctypes.c_int
     lib.tcg_edge_gather.argtypes = [ctypes.c_int64, _vp, _vp, _vp, _vp]
+    lib.tcg_attention.restype = ctypes.c_int
+    lib.tcg_attention.argtypes = [_vp, _vp, ctypes.c_int, ctypes.c_int32, ctypes.c_int64, _vp, _vp, ctypes.c_int,
+                                  ctypes.c_int64, _vp]
     lib.tcg_release_cached_memory.restype = None
     lib.tcg_release_cached_memory.argtypes = []
     lib.tcg_strerror.restype = ctypes.c_char_p
@@ -267,3 +270,21 @@ def edge_gather(perm, values, out=None):
         out = torch.empty_like(values)
     _check(load_library().tcg_edge_gather(perm.numel(), _ptr(perm), _ptr(values), _ptr(out), _stream()))
     return out
+
+
+def attention(meta, X, Y=None, scores=None, y_dtype=torch.float32):
+    """tcg_attention: Y[i] = sum_e softmax_i(<x_i, x_j>)_e x_j in one pass.  `scores` (optional fp32 [nnz])
+    receives the raw scores."""
+    X = _features(meta, X, max(meta.n_rows, meta.n_cols))
+    D = X.shape[1]
+    if Y is None:
+        Y = torch.empty((meta.n_rows, D), dtype=y_dtype, device=X.device)
+    _need_cuda(Y, scores)
+    if Y.dim() != 2 or Y.shape != (meta.n_rows, D) or Y.stride(1) != 1 or Y.dtype not in _DTYPES:
+        raise ValueError("Y must be [n_rows, D] with unit stride along features")
+    if scores is not None and (scores.dtype != torch.float32 or scores.numel() != meta.nnz or not scores.is_contiguous()):
+        raise ValueError("scores must be a contiguous fp32 tensor with one value per stored entry")
+    _check(load_library().tcg_attention(meta._h, _ptr(X), _DTYPES[X.dtype], D, X.stride(0), _ptr(scores), _ptr(Y),
+                                        _DTYPES[Y.dtype], Y.stride(0) if meta.n_rows > 1 else max(D, Y.stride(0)),
+                                        _stream()))
+    return Y

@@ -142,6 +142,15 @@ int tcg_sddmm_pq(tcg_meta *meta, const void *d_P, int64_t ldp, const void *d_Q, 
     return sddmm_impl(meta, d_P, ldp, d_Q, ldq, x_dt, D, d_out, static_cast<hipStream_t>(stream));
 }
 
+int tcg_attention(tcg_meta *meta, const void *d_X, tcg_dtype x_dt, int32_t D, int64_t ldx, float *d_scores, void *d_Y,
+                  tcg_dtype y_dt, int64_t ldy, void *stream)
+{
+    if (!meta || D < 1 || ldx < D || ldy < D || !dtype_ok(x_dt) || !dtype_ok(y_dt)) return TCG_EINVAL;
+    if ((!d_X && meta->nnz > 0) || (!d_Y && meta->n_rows > 0)) return TCG_EINVAL;
+    if ((reinterpret_cast<uintptr_t>(d_Y) % dtype_size(y_dt))) return TCG_EINVAL;
+    return attention_impl(meta, d_X, x_dt, D, ldx, d_scores, d_Y, y_dt, ldy, static_cast<hipStream_t>(stream));
+}
+
 int tcg_row_softmax_backward(const tcg_meta *meta, const float *d_p, const float *d_dp, float *d_dv, void *stream)
 {
     if (!meta) return TCG_EINVAL;

@@ -1,0 +1,246 @@
+// Fused attention-style aggregation: Y[i] = sum_e softmax_i(<x_i, x_j>)_e * x_j, i.e. the chain
+// SDDMM (Equation 2) -> row softmax -> SpMM (Equation 1) of the paper's AGNN workload in one pass.
+//
+// Run as three library calls the chain gathers every neighbour row twice (once for the score, once
+// for the aggregation) and moves the scores through HBM three times.  Here a group of G lanes walks a
+// row segment once: the 16-byte slices of a gathered row x_j sit in registers, the score is reduced
+// across the group with wavefront shuffles, and the row is added to the accumulator under an online
+// softmax (running maximum m and denominator l; the accumulator is rescaled whenever m grows), so the
+// scores never leave the registers.  Rows split over several segments write (accumulator, m, l) per
+// segment and a second kernel merges them in segment order: m = max m_s, l = sum l_s e^(m_s - m),
+// y = sum y_s e^(m_s - m), Y = y / l.  Deterministic; rows without entries give 0.
+#include "common.h"
+#include "devutil.h"
+
+namespace tcg {
+
+namespace {
+
+constexpr int kBlock = 256;
+
+template <int DT, int G, int NCH, int UNROLL>
+__global__ __launch_bounds__(kBlock) void attn_fused_kernel(
+    const int32_t *__restrict__ lane_tab, const int32_t *__restrict__ seg_row, const int32_t *__restrict__ seg_ebeg,
+    const int32_t *__restrict__ seg_dst, const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ col_idx,
+    const char *__restrict__ X, int64_t ldx_bytes, int32_t n_chunks, int32_t D, float *__restrict__ scores,
+    void *__restrict__ Y, int y_dt, int64_t ldy, float *__restrict__ partial, float *__restrict__ partial_ml)
+{
+    constexpr int VEC = Elem<DT>::VEC;
+    const int lane = threadIdx.x % G;
+    const int64_t seg = plan_segment(lane_tab, kBlock / G, threadIdx.x / G);
+    if (seg < 0) return;
+    const int32_t row = seg_row[seg];
+    const int32_t eb = seg_ebeg[seg];
+    const int32_t ee = min(eb + kSegLen, row_ptr[row + 1]);
+
+    float xi[NCH][VEC], acc[NCH][VEC];
+    {
+        const char *xr = X + (int64_t)row * ldx_bytes;
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) {
+            const int chunk = lane + c * G;
+            uint4 raw = make_uint4(0, 0, 0, 0);
+            if (chunk < n_chunks) raw = *reinterpret_cast<const uint4 *>(xr + (int64_t)chunk * 16);
+            unpack16<DT>(raw, xi[c]);
+#pragma unroll
+            for (int k = 0; k < VEC; ++k) acc[c][k] = 0.f;
+        }
+    }
+    float m_run = -INFINITY, l_run = 0.f;
+
+    if (eb < ee) {
+        const int32_t last = ee - 1;
+        const uint32_t ldx32 = (uint32_t)ldx_bytes;
+        int32_t cn[UNROLL];
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) cn[u] = col_idx[min(eb + u, last)];
+        for (int32_t e = eb; e < ee; e += UNROLL) {
+            int32_t cnext[UNROLL];
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) cnext[u] = col_idx[min(e + UNROLL + u, last)];
+            float v[UNROLL][NCH][VEC];
+            float p[UNROLL];
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) {
+                const char *xr = X + (uint64_t)(uint32_t)cn[u] * ldx32;
+                float a = 0.f;
+#pragma unroll
+                for (int c = 0; c < NCH; ++c) {
+                    const int chunk = lane + c * G;
+                    uint4 raw = make_uint4(0, 0, 0, 0);
+                    if (e + u < ee && chunk < n_chunks) raw = *reinterpret_cast<const uint4 *>(xr + (uint32_t)chunk * 16u);
+                    unpack16<DT>(raw, v[u][c]);
+#pragma unroll
+                    for (int k = 0; k < VEC; ++k) a = fmaf(xi[c][k], v[u][c][k], a);
+                }
+                p[u] = a;
+            }
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) cn[u] = cnext[u];
+
+            // Scores of the UNROLL edges, known to every lane of the group.
+            float s[UNROLL];
+            const float r = group_reduce<G, UNROLL>(p, lane);
+            if constexpr (G >= UNROLL) {
+                if (scores != nullptr && lane < UNROLL && e + lane < ee) scores[e + lane] = r;
+#pragma unroll
+                for (int u = 0; u < UNROLL; ++u) s[u] = __shfl(r, u, G);
+            } else {
+#pragma unroll
+                for (int u = 0; u < UNROLL; ++u) s[u] = p[u];
+                if (scores != nullptr && lane == 0) {
+#pragma unroll
+                    for (int u = 0; u < UNROLL; ++u)
+                        if (e + u < ee) scores[e + u] = s[u];
+                }
+            }
+            // Online softmax update (edge e itself is always valid, so the new maximum is finite).
+            float m_new = m_run;
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u)
+                if (e + u < ee) m_new = fmaxf(m_new, s[u]);
+            const float scale = expf(m_run - m_new);      // 0 for the first chunk (m_run = -inf)
+            l_run *= scale;
+#pragma unroll
+            for (int c = 0; c < NCH; ++c)
+#pragma unroll
+                for (int k = 0; k < VEC; ++k) acc[c][k] *= scale;
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) {
+                const float wgt = (e + u < ee) ? expf(s[u] - m_new) : 0.f;
+                l_run += wgt;
+#pragma unroll
+                for (int c = 0; c < NCH; ++c)
+#pragma unroll
+                    for (int k = 0; k < VEC; ++k) acc[c][k] = fmaf(wgt, v[u][c][k], acc[c][k]);
+            }
+            m_run = m_new;
+        }
+    }
+
+    const int32_t dst = seg_dst[seg];
+    const float inv = (dst < 0 && l_run > 0.f) ? 1.f / l_run : (dst < 0 ? 0.f : 1.f);
+    if (dst >= 0 && lane == 0) {
+        partial_ml[2 * (int64_t)dst] = m_run;
+        partial_ml[2 * (int64_t)dst + 1] = l_run;
+    }
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+        const int chunk = lane + c * G;
+        if (chunk >= n_chunks) continue;
+        const int64_t d0 = (int64_t)chunk * VEC;
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) {
+            const float val = acc[c][k] * inv;
+            if (dst >= 0) partial[(int64_t)dst * D + d0 + k] = val;
+            else store_elem(Y, (int64_t)row * ldy + d0 + k, y_dt, val);
+        }
+    }
+}
+
+// Merges the per-segment (accumulator, maximum, denominator) of every split row, in segment order.
+__global__ __launch_bounds__(kBlock) void attn_merge_long_kernel(
+    const int32_t *__restrict__ long_row, const int32_t *__restrict__ long_slot_ptr, const float *__restrict__ partial,
+    const float *__restrict__ partial_ml, int32_t D, void *__restrict__ Y, int y_dt, int64_t ldy)
+{
+    const int64_t li = blockIdx.x;
+    const int32_t row = long_row[li];
+    const int32_t s0 = long_slot_ptr[li], s1 = long_slot_ptr[li + 1];
+    float m = -INFINITY;
+    for (int32_t sgi = s0; sgi < s1; ++sgi) m = fmaxf(m, partial_ml[2 * (int64_t)sgi]);
+    float l = 0.f;
+    for (int32_t sgi = s0; sgi < s1; ++sgi) l += partial_ml[2 * (int64_t)sgi + 1] * expf(partial_ml[2 * (int64_t)sgi] - m);
+    const float inv = l > 0.f ? 1.f / l : 0.f;
+    for (int32_t d = threadIdx.x; d < D; d += kBlock) {
+        float y = 0.f;
+        for (int32_t sgi = s0; sgi < s1; ++sgi)
+            y = fmaf(partial[(int64_t)sgi * D + d], expf(partial_ml[2 * (int64_t)sgi] - m), y);
+        store_elem(Y, (int64_t)row * ldy + d, y_dt, y * inv);
+    }
+}
+
+struct Args {
+    tcg_meta *m;
+    const void *X;
+    int64_t ldx;
+    int32_t D;
+    float *scores;
+    void *Y;
+    int y_dt;
+    int64_t ldy;
+    float *partial_ml;
+    hipStream_t s;
+};
+
+template <int DT, int G, int NCH>
+void launch(const Args &a, int32_t n_chunks)
+{
+    constexpr int UNROLL = NCH == 1 ? 8 : (NCH == 2 ? 4 : 2);
+    const tcg_meta *m = a.m;
+    const unsigned grid = (unsigned)plan_grid(m->h_lane_tab, kBlock / G);
+    hipLaunchKernelGGL((attn_fused_kernel<DT, G, NCH, UNROLL>), dim3(grid), dim3(kBlock), 0, a.s, m->d_lane_tab,
+                       m->d_seg_row, m->d_seg_ebeg, m->d_seg_dst, m->d_row_ptr, m->d_col_idx,
+                       static_cast<const char *>(a.X), a.ldx * Elem<DT>::BYTES, n_chunks, a.D, a.scores, a.Y, a.y_dt, a.ldy,
+                       m->d_partial, a.partial_ml);
+}
+
+template <int DT>
+bool dispatch(const Args &a, int32_t n_chunks)
+{
+    if (n_chunks <= 4) launch<DT, 4, 1>(a, n_chunks);
+    else if (n_chunks <= 8) launch<DT, 8, 1>(a, n_chunks);
+    else if (n_chunks <= 16) launch<DT, 16, 1>(a, n_chunks);
+    else if (n_chunks <= 32) launch<DT, 32, 1>(a, n_chunks);
+    else if (n_chunks <= 64) launch<DT, 64, 1>(a, n_chunks);
+    else if (n_chunks <= 128) launch<DT, 64, 2>(a, n_chunks);
+    else return false;
+    return true;
+}
+
+}  // namespace
+
+int attention_impl(tcg_meta *m, const void *d_X, tcg_dtype x_dt, int32_t D, int64_t ldx, float *d_scores, void *d_Y,
+                   tcg_dtype y_dt, int64_t ldy, hipStream_t s)
+{
+    if (m->n_rows == 0) return TCG_OK;
+    const int es = dtype_size(x_dt);
+    const bool vec_ok = ((int64_t)D * es) % 16 == 0 && (ldx * es) % 16 == 0 && ldx * es < (1ll << 32) &&
+                        (reinterpret_cast<uintptr_t>(d_X) & 15) == 0 && (int64_t)D * es / 16 <= 128;
+    if (!vec_ok) return TCG_EINVAL;
+
+    // Scratch: fp32 accumulators of split rows (shared with tcg_spmm) and their (max, denominator).
+    const int64_t need = m->n_slots * (int64_t)D;
+    if (need > m->partial_elems) {
+        if (m->partial_owned) {
+            TCG_HIP(hipStreamSynchronize(s));
+            pool_free(m->d_partial);
+        }
+        m->d_partial = nullptr;
+        m->partial_elems = 0;
+        m->partial_owned = false;
+        TCG_TRY(dev_alloc(&m->d_partial, need));
+        m->partial_elems = need;
+        m->partial_owned = true;
+    }
+    if (m->n_slots > 0 && m->d_partial_ml == nullptr) {
+        TCG_TRY(dev_alloc(&m->d_partial_ml, 2 * m->n_slots));
+        m->owned[m->n_owned++] = m->d_partial_ml;
+    }
+
+    Args a{m, d_X, ldx, D, d_scores, d_Y, (int)y_dt, ldy, m->d_partial_ml, s};
+    const int32_t n_chunks = (int32_t)((int64_t)D * es / 16);
+    bool ok;
+    if (x_dt == TCG_F32) ok = dispatch<TCG_F32>(a, n_chunks);
+    else if (x_dt == TCG_BF16) ok = dispatch<TCG_BF16>(a, n_chunks);
+    else ok = dispatch<TCG_F16>(a, n_chunks);
+    if (!ok) return TCG_EINVAL;
+    TCG_TRY(launch_status("attn_fused_kernel"));
+    if (m->n_long > 0) {
+        hipLaunchKernelGGL(attn_merge_long_kernel, dim3((unsigned)m->n_long), dim3(kBlock), 0, s, m->d_long_row,
+                           m->d_long_slot_ptr, m->d_partial, m->d_partial_ml, D, d_Y, (int)y_dt, ldy);
+        TCG_TRY(launch_status("attn_merge_long_kernel"));
+    }
+    return TCG_OK;
+}
+
+}  // namespace tcg

@@ -132,6 +132,10 @@ int spmm_impl(tcg_meta *m, const void *d_X, tcg_dtype x_dt, int32_t D, int64_t l
 int sddmm_impl(tcg_meta *m, const void *d_P, int64_t ldp, const void *d_X, int64_t ldx, tcg_dtype x_dt, int32_t D,
                float *d_out, hipStream_t s);
 
+// attn.hip
+int attention_impl(tcg_meta *m, const void *d_X, tcg_dtype x_dt, int32_t D, int64_t ldx, float *d_scores, void *d_Y,
+                   tcg_dtype y_dt, int64_t ldy, hipStream_t s);
+
 // backward.hip
 int row_softmax_backward_impl(const tcg_meta *m, const float *d_p, const float *d_dp, float *d_dv, hipStream_t s);
 int csr_transpose_impl(int32_t n_rows, int32_t n_cols, int64_t nnz, const int32_t *d_row_ptr,
@@ -173,6 +177,7 @@ struct tcg_meta {
     int32_t h_lane_tab[6 * 8] = {0};      // host copy (sizes the gather grids, see plan_grid())
     float *d_partial = nullptr;           // [n_slots x D] scratch; reserved for D <= kPartialInitD, regrown on demand
     int64_t partial_elems = 0;
+    float *d_partial_ml = nullptr;        // [n_slots x 2] (maximum, denominator) per split-row segment (tcg_attention)
     bool partial_owned = false;          // true once regrown by tcg_spmm for a wider D (separate allocation)
 
     // Device allocations owned by this object (the pointers above and below are carved from them).

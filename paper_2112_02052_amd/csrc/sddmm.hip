@@ -22,40 +22,6 @@ namespace {
 
 constexpr int kBlock = 256;
 
-// Sums UNROLL per-lane partials across the G lanes of a group.  On return, lane j (j < UNROLL,
-// position inside the group) holds the total of partial j -- if G >= UNROLL; otherwise every
-// lane holds all totals in p[].  Must be executed by all lanes of the group.
-template <int G, int UNROLL>
-__device__ __forceinline__ float group_reduce(float (&p)[UNROLL], int lane)
-{
-    if constexpr (G >= UNROLL) {
-        // Butterfly: at step with distance `off`, a lane keeps the half of its live partials whose
-        // index bit matches its own lane bit and receives the partner's copies of that half.
-        int live = UNROLL;
-#pragma unroll
-        for (int off = 1; off < UNROLL; off <<= 1) {
-            live >>= 1;
-            const bool upper = (lane & off) != 0;
-#pragma unroll
-            for (int k = 0; k < live; ++k) {
-                float keep = upper ? p[2 * k + 1] : p[2 * k];
-                float send = upper ? p[2 * k] : p[2 * k + 1];
-                p[k] = keep + __shfl_xor(send, off, G);
-            }
-        }
-        float r = p[0];
-#pragma unroll
-        for (int off = UNROLL; off < G; off <<= 1) r += __shfl_xor(r, off, G);
-        return r;
-    } else {
-#pragma unroll
-        for (int k = 0; k < UNROLL; ++k)
-#pragma unroll
-            for (int off = 1; off < G; off <<= 1) p[k] += __shfl_xor(p[k], off, G);
-        return 0.f;
-    }
-}
-
 // After group_reduce with G >= UNROLL, lane (position in group) `l` holds the total of partial
 // index idx(l): step off=1 keeps index parity = bit 0 of l as the LOWEST bit of the original
 // index, the next step bit 1, and so on; so idx(l) = l mod UNROLL.

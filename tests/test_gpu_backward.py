@@ -124,3 +124,36 @@ def test_attention_layer_backward_composition():
     assert norm_err(dX.cpu().numpy(), dX_o) <= 1e-4
     meta.free()
     meta_t.free()
+
+
+@pytest.mark.parametrize("x_dtype", ["f32", "bf16", "f16"])
+def test_fused_attention_matches_the_three_call_chain(x_dtype):
+    rnd = {"f32": lambda a: a, "bf16": W.round_to_bf16, "f16": lambda a: a.astype(np.float16).astype(np.float32)}[x_dtype]
+    cases = [(W.make_config(3, n=20000), None), (W.make_config(4, n=6000, d=128), None),
+             (W.make_config(5, n=64 * 30, d=256, permute=False), None), (W.make_config(1, n=700, d=16), None)]
+    g_hub = hub_graph(2500)
+    cases.append((dict(csr=g_hub, X=W.features_normal(g_hub.n_cols, 64, 8)), None))
+    for c, _ in cases:
+        g = c["csr"]
+        X = rnd(c["X"] * (0.3 if x_dtype != "f32" else 1.0))         # keep 16-bit scores in a sane range
+        X = rnd(X)
+        rp, ci = upload_csr(g)
+        meta = tcg.sgt_build(rp, ci, 16, 8)
+        Xd = upload_x(X, x_dtype)
+        scores = torch.full((g.nnz,), float("nan"), device=dev())
+        Y = torch.full((g.n_rows, X.shape[1]), float("nan"), device=dev())
+        tcg.attention(meta, Xd, Y=Y, scores=scores)
+        torch.cuda.synchronize()
+        e_o = oracle.sddmm(g.row_ptr, g.col_idx, X)
+        p_o = oracle.row_softmax(g.row_ptr, e_o)
+        Y_o = oracle.spmm(g.row_ptr, g.col_idx, X, p_o.astype(np.float32))
+        assert norm_err(scores.cpu().numpy(), e_o) <= TOL_F32
+        assert norm_err(Y.cpu().numpy(), Y_o) <= 1e-4
+        deg = g.degrees()
+        assert np.all(Y.cpu().numpy()[deg == 0] == 0)
+        # the library's own three-call chain agrees (its SpMM may take the MFMA path for 16-bit features,
+        # which rounds the attention weights to the feature type)
+        Y3 = tcg.spmm(meta, Xd, tcg.row_softmax(meta, tcg.sddmm(meta, Xd)))
+        torch.cuda.synchronize()
+        assert norm_err(Y.cpu().numpy(), Y3.cpu().numpy().astype(np.float64)) <= (1e-4 if x_dtype == "f32" else TOL_MFMA)
+        meta.free()
