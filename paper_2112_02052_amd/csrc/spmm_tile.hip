@@ -1,22 +1,30 @@
 // Neighbour aggregation on condensed tiles (Algorithm 2 of the paper) with gfx950 MFMA.
 //
-// One workgroup (4 wavefronts) per row window of 16 rows that the plan assigned to this path,
-// i.e. windows whose rows share enough neighbours that every gathered X row is reused several
-// times.  The window's condensed columns (its sorted unique neighbour list from SGT) are walked
-// in chunks of KC = 32:
-//   InitSparse  the 16 x KC slice of the condensed adjacency is built in LDS in fp32 from the
+// One wavefront per row window of 16 rows that the plan assigned to this path, i.e. windows whose
+// rows share enough neighbours that every gathered X row is reused several times.  The window's
+// condensed columns (its sorted unique neighbour list from SGT) are walked in chunks of KW = 16:
+//   InitSparse  the 16 x KW slice of the condensed adjacency is built in LDS in fp32 from the
 //               window's edges and edge_to_col (repeated entries add up), then rounded to the
 //               feature type when it is loaded as the MFMA A operand;
-//   FetchDense  the KC neighbour rows named by col_to_row are copied into LDS with 16-byte
+//   FetchDense  the KW neighbour rows named by col_to_row are copied into LDS with 16-byte
 //               coalesced loads -- each unique neighbour is fetched once per window, which is
 //               the traffic reduction SGT exists for;
-//   TCcompute   v_mfma_f32_16x16x32 (bf16 or f16 inputs, fp32 accumulate); the feature dimension
-//               is split in 16-column slices over the wavefronts, which share the A operand;
-//   StoreDense  after the last chunk the accumulators are written to the window's rows of Y.
-// Differences from the paper's kernel: the K extent of a tile is 32 (gfx950 bf16/f16 MFMA)
-// instead of 8 (TF-32 WMMA), the column -> node map comes straight from SGT's col_to_row
-// instead of being rebuilt per block, and the B operand is transposed by the LDS read itself
-// (ds_read_b64_tr_b16), so the staged rows keep their row-major layout.
+//   TCcompute   v_mfma_f32_16x16x16 (bf16 or f16 inputs, fp32 accumulate), one per 16-column slice
+//               of the feature dimension, all sharing the A operand;
+//   StoreDense  after the last chunk the accumulators go through LDS and are written to the
+//               window's rows of Y as whole 16-byte pieces.
+// Differences from the paper's kernel: the K extent of a tile is 16 (bf16/f16 MFMA) instead of 8
+// (TF-32 WMMA); the column -> node map comes straight from SGT's col_to_row instead of being
+// rebuilt per block; the B operand is transposed by the LDS read itself (ds_read_b64_tr_b16), so
+// the staged rows keep their row-major layout; and a window belongs to one wavefront instead of a
+// block of warps that split the feature dimension.  A wavefront's LDS operations complete in
+// program order, so the kernel has no barrier at all, and with about 10 KB of LDS per window a
+// compute unit keeps twelve windows in flight, which is what hides the chain of dependent loads
+// of a window (row pointers -> edge list and neighbour ids -> neighbour rows).  The neighbour
+// rows of chunk c + 1 are requested as soon as the registers of chunk c have been written to LDS,
+// their ids one chunk earlier still.  Measured on MI355X this is faster than a 256-thread
+// workgroup per window with 32-column chunks; the counters show the path bound by the latency of
+// L1 -> L2 read requests, not by the matrix cores.
 #include "common.h"
 #include "devutil.h"
 
@@ -24,37 +32,11 @@ namespace tcg {
 
 namespace {
 
-typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
-typedef __attribute__((__vector_size__(8 * sizeof(_Float16)))) _Float16 f16x8;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
-
-constexpr int kTileBlock = 256;
-constexpr int kWaves = kTileBlock / kWave;
-constexpr int KC = 32;          // condensed columns per chunk = K of one MFMA
-constexpr int kAStride = KC + 1;
-
-// Staged X rows are padded so that consecutive rows start 32 bytes (8 LDS banks) apart modulo the
-// 256-byte bank cycle: the transposing reads below then touch every bank exactly once per pass.
-__host__ __device__ inline int32_t staged_row_stride(int32_t row_bytes)
-{
-    return row_bytes + ((32 - row_bytes % 256) + 256) % 256;
-}
-
-template <int DT>
-__device__ __forceinline__ f32x4 mfma16(const uint32_t (&a)[4], const uint32_t (&b)[4], f32x4 c)
-{
-    if constexpr (DT == TCG_BF16) {
-        bf16x8 va, vb;
-        __builtin_memcpy(&va, a, 16);
-        __builtin_memcpy(&vb, b, 16);
-        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, vb, c, 0, 0, 0);
-    } else {
-        f16x8 va, vb;
-        __builtin_memcpy(&va, a, 16);
-        __builtin_memcpy(&vb, b, 16);
-        return __builtin_amdgcn_mfma_f32_16x16x32_f16(va, vb, c, 0, 0, 0);
-    }
-}
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 h16x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
+typedef __attribute__((address_space(3))) bf16x4 lds_bf16x4;
 
 // Edge values to the feature type.  Unit values (and their small integer sums for repeated
 // entries) are exact in both 16-bit types, so without edge values truncation is exact.
@@ -69,9 +51,6 @@ __device__ __forceinline__ uint32_t pack2(float lo, float hi)
     }
 }
 
-typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
-typedef __attribute__((address_space(3))) bf16x4 lds_bf16x4;
-
 // gfx950 transposing LDS read (ds_read_b64_tr_b16).  Inside each group of 16 lanes, lane i receives
 // as its element e the element (i % 4) of the 8-byte chunk addressed by lane (i / 4 + 4 * e): a
 // 4 x 16 block of 16-bit values stored row-major comes back with one column per lane.
@@ -83,202 +62,229 @@ __device__ __forceinline__ uint2 lds_read_tr16(const char *p)
     return r;
 }
 
-// K index of the MFMA operand element j (0..7) of lane group g (0..3) inside a 32-column chunk.  Any
-// bijection works as long as A and B use the same one; this one makes the first four elements of all
-// groups rows 0..15 and the last four rows 16..31, which keeps the transposing reads conflict-free.
-__device__ __forceinline__ int chunk_k(int g, int j) { return (j < 4 ? 0 : 16) + 4 * g + (j & 3); }
+constexpr int KW = 16;
+constexpr int kAStrideW = 20;     // floats; 16 x 20 = 5 x 64: five stores per lane clear the slice
 
-// MAXS: 16-column slices of D per wavefront (D <= 64 * MAXS).
-template <int DT, bool HAS_W, int MAXS>
-__global__ __launch_bounds__(kTileBlock) void spmm_tile_kernel(
+// Orders the LDS accesses of the wavefront's lanes for the compiler; the hardware already completes a
+// wavefront's LDS operations in program order, so no instruction is emitted.
+__device__ __forceinline__ void wave_lds_order()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+template <int DT>
+__device__ __forceinline__ f32x4 mfma16k16(const uint2 &a, const uint2 &b, f32x4 c)
+{
+    if constexpr (DT == TCG_BF16) {
+        s16x4 va, vb;
+        __builtin_memcpy(&va, &a, 8);
+        __builtin_memcpy(&vb, &b, 8);
+        return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(va, vb, c, 0, 0, 0);
+    } else {
+        h16x4 va, vb;
+        __builtin_memcpy(&va, &a, 8);
+        __builtin_memcpy(&vb, &b, 8);
+        return __builtin_amdgcn_mfma_f32_16x16x16f16(va, vb, c, 0, 0, 0);
+    }
+}
+
+// NS: 16-column slices of D per wavefront; a window with D > 16 * NS is shared by n_dparts wavefronts.
+template <int DT, bool HAS_W, int NS>
+__global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(3))) void spmm_tile_wave_kernel(
     int32_t n_rows, int64_t n_win, const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ edge_to_col,
     const int32_t *__restrict__ win_unique_ptr, const int32_t *__restrict__ col_to_row,
     const uint8_t *__restrict__ win_path, const float *__restrict__ w, const char *__restrict__ X,
-    int64_t ldx_bytes, int32_t D, void *__restrict__ Y, int y_dt, int64_t ldy)
+    int64_t ldx_bytes, int32_t D, int32_t n_dparts, void *__restrict__ Y, int y_dt, int64_t ldy, bool y_vec)
 {
-    extern __shared__ __align__(16) char smem[];
-    // Workgroup i runs on die i % kXcds: give every die a contiguous range of windows, so that
-    // neighbouring windows (which share neighbours on clustered graphs) meet in the same L2.
+    constexpr int PP = NS / 2;                                    // 16-byte pieces of a chunk per lane
+    // Staged row stride: an odd multiple of 32 bytes, so the 8 rows that half a wavefront touches in
+    // a transposing read start in 8 different groups of 8 LDS banks.
+    constexpr int32_t rs = NS * 32 + 32;
+    __shared__ __align__(16) char xs[KW * rs];
+    __shared__ __align__(16) float a32[16 * kAStrideW];
+    __shared__ int32_t s_rp[17];
+
+    // Workgroup i runs on die i % kXcds: every die gets a contiguous range of windows.
     const int64_t per_die = (n_win + kXcds - 1) / kXcds;
-    const int64_t win = (int64_t)(blockIdx.x % kXcds) * per_die + blockIdx.x / kXcds;
-    if (win >= n_win || !win_path[win]) return;
+    const int64_t j = blockIdx.x / kXcds;
+    const int64_t win = (int64_t)(blockIdx.x % kXcds) * per_die + j / n_dparts;
+    if (j / n_dparts >= per_die || win >= n_win || !win_path[win]) return;
+    const int32_t d0 = (int32_t)(j % n_dparts) * (NS * 16);       // first feature column of this part
+    const int32_t Dp = min(NS * 16, D - d0);
 
-    const int32_t row_bytes = D * 2;
-    const int32_t rs = staged_row_stride(row_bytes);              // staged row stride, bytes (multiple of 16)
-    char *xs = smem;                                              // KC rows
-    float *a32 = reinterpret_cast<float *>(smem + (size_t)KC * rs);   // 16 x kAStride
-    int32_t *s_rp = reinterpret_cast<int32_t *>(a32 + 16 * kAStride);   // 17 row pointers
-
-    const int tid = threadIdx.x;
-    const int lane = tid & (kWave - 1);
-    const int wave = tid >> 6;
+    const int lane = threadIdx.x;
     const int64_t r0 = win * 16;
-    if (tid < 17) {
-        int64_t r = r0 + tid;
-        s_rp[tid] = row_ptr[r < n_rows ? r : n_rows];
+    if (lane < 17) {
+        int64_t r = r0 + lane;
+        s_rp[lane] = row_ptr[r < n_rows ? r : n_rows];
     }
-    __syncthreads();
-    const int32_t lo = s_rp[0], hi = s_rp[16];
+    wave_lds_order();
     const int32_t u0 = win_unique_ptr[win];
     const int32_t U = win_unique_ptr[win + 1] - u0;
-    const int32_t n_chunks16 = row_bytes / 16;
-    const int32_t n_slices = (D + 15) / 16;
+    // ids of the neighbours of chunks 0 and 1 (lane k < 16 holds row k of the chunk)
+    const int kk = lane & 15;
+    int32_t nid_cur = kk < U ? col_to_row[u0 + kk] : -1;
+    int32_t nid_nxt = KW + kk < U ? col_to_row[u0 + KW + kk] : -1;
+    const int32_t lo = s_rp[0], hi = s_rp[16];
+    const int32_t n_slices = (Dp + 15) / 16;
 
-    f32x4 acc[MAXS];
+    // FetchDense mapping: 2 * NS lanes cover one row part with 16-byte pieces, so one pass of the
+    // wavefront loads RPP rows and PP passes load the chunk; piece i of a lane is row i * RPP + sub.
+    constexpr int LPR = 2 * NS, RPP = kWave / LPR;
+    const int sub = lane / LPR;
+    const int32_t goff = (lane % LPR) * 16;
+    const bool piece_ok = goff < Dp * 2;
+    const char *Xp = X + (int64_t)d0 * 2 + goff;
+    char *xs_dst = xs + sub * rs + goff;
+    uint4 pre[PP];
+    auto fetch = [&](int32_t nid) {
 #pragma unroll
-    for (int i = 0; i < MAXS; ++i) acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int i = 0; i < PP; ++i) {
+            const int32_t node = __shfl(nid, i * RPP + sub);
+            pre[i] = make_uint4(0, 0, 0, 0);
+            if (piece_ok && node >= 0) pre[i] = *reinterpret_cast<const uint4 *>(Xp + (int64_t)node * ldx_bytes);
+        }
+    };
+    fetch(nid_cur);
 
-    // A window of at most 2 * kTileBlock edges keeps them in registers for all chunks (condensed
-    // column, offset of its row inside the A slice, value); larger windows re-read them per chunk.
-    constexpr int EPT = 2;
-    const bool edges_in_regs = hi - lo <= EPT * kTileBlock;
-    int32_t e_col[EPT];
-    int e_aoff[EPT];
+    // A window of at most EPT * 64 edges keeps them in registers: (A-slice row offset << 16 | condensed
+    // column) and the value.  Larger windows re-read their edges for every chunk.
+    constexpr int EPT = 8;
+    const bool edges_in_regs = hi - lo <= EPT * kWave;
+    int32_t e_code[EPT];
     float e_val[EPT];
 #pragma unroll
     for (int q = 0; q < EPT; ++q) {
-        const int32_t e = lo + tid + q * kTileBlock;
-        e_col[q] = -1;
-        e_aoff[q] = 0;
+        const int32_t e = lo + lane + q * kWave;
+        e_code[q] = -1;
         e_val[q] = 0.f;
         if (edges_in_regs && e < hi) {
-            e_col[q] = edge_to_col[e];
-            e_val[q] = HAS_W ? w[e] : 1.f;
             int r = 0;
 #pragma unroll
             for (int step = 8; step > 0; step >>= 1)
                 if (s_rp[r + step] <= e) r += step;
-            e_aoff[q] = r * kAStride;
+            e_code[q] = (r * kAStrideW) << 16 | edge_to_col[e];     // condensed column < kTileMaxUnique
+            if (HAS_W) e_val[q] = w[e];
         }
     }
 
-    // FetchDense: one row is n_chunks16 16-byte pieces; a thread owns pieces idx = tid + i * kTileBlock
-    // of each KC x n_chunks16 chunk (rows beyond the window's list are zero).
-    int32_t p_k[MAXS], p_goff[MAXS], p_loff[MAXS];     // row in chunk, byte offset in the row, LDS offset
+    f32x4 acc[NS];
 #pragma unroll
-    for (int i = 0; i < MAXS; ++i) {
-        const int32_t idx = tid + i * kTileBlock;
-        const int32_t k = idx / n_chunks16, ch = idx - k * n_chunks16;
-        p_k[i] = idx < KC * n_chunks16 ? k : -1;
-        p_goff[i] = ch * 16;
-        p_loff[i] = k * rs + ch * 16;
-    }
-    // MFMA operand addressing (constant over the chunks).
+    for (int i = 0; i < NS; ++i) acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+
     const int g = lane >> 4, n_in = lane & 15;
-    // A: row n_in of the slice, K elements chunk_k(g, 0..7)
-    const float *a_lo = a32 + n_in * kAStride + 4 * g;            // k = 4g .. 4g+3
-    const float *a_hi = a_lo + 16;                                // k = 16+4g .. 16+4g+3
-    // B: lane j of a 16-lane group addresses row (4g + j / 4) [+16 for the second read], 8-byte chunk j % 4
-    const int32_t b_off = (4 * g + (n_in >> 2)) * rs + (n_in & 3) * 8;
+    const float *a_src = a32 + n_in * kAStrideW + 4 * g;          // A: row n_in, k = 4g .. 4g+3
+    // B: lane j of a 16-lane group addresses row 4g + j / 4, 8-byte chunk j % 4 of a slice
+    const char *b_src = xs + (4 * g + (n_in >> 2)) * rs + (n_in & 3) * 8;
 
-    // The chunks are processed in groups of PD whose neighbour rows are requested at once (ids first,
-    // then the rows).  Measured on MI355X, deeper groups lose more through register pressure (fewer
-    // resident workgroups) than they gain in memory-level parallelism: PD = 1 is fastest.
-    constexpr int PD = 1;
-    for (int32_t kg = 0; kg < U; kg += PD * KC) {
-        uint4 pre[PD][MAXS];
-        int32_t nid[PD][MAXS];
+    for (int32_t k0 = 0; k0 < U; k0 += KW) {
+        // chunk k0: registers -> LDS, then request chunk k0 + KW and the ids of chunk k0 + 2 KW
 #pragma unroll
-        for (int c = 0; c < PD; ++c)
-#pragma unroll
-            for (int i = 0; i < MAXS; ++i) {
-                const int32_t k = kg + c * KC + p_k[i];
-                nid[c][i] = (p_k[i] >= 0 && k < U) ? col_to_row[u0 + k] : -1;
-            }
-#pragma unroll
-        for (int c = 0; c < PD; ++c)
-#pragma unroll
-            for (int i = 0; i < MAXS; ++i) {
-                pre[c][i] = make_uint4(0, 0, 0, 0);
-                if (nid[c][i] >= 0)
-                    pre[c][i] = *reinterpret_cast<const uint4 *>(X + (int64_t)nid[c][i] * ldx_bytes + p_goff[i]);
-            }
-#pragma unroll
-        for (int c = 0; c < PD; ++c) {
-            const int32_t k0 = kg + c * KC;
-            if (k0 >= U) break;
-            for (int i = tid; i < 16 * kAStride; i += kTileBlock) a32[i] = 0.f;
-#pragma unroll
-            for (int i = 0; i < MAXS; ++i)
-                if (p_k[i] >= 0) *reinterpret_cast<uint4 *>(xs + p_loff[i]) = pre[c][i];
-            __syncthreads();
-            // InitSparse: scatter the window's edges that fall into this chunk.
-            if (edges_in_regs) {
-#pragma unroll
-                for (int q = 0; q < EPT; ++q) {
-                    const int32_t cc = e_col[q] - k0;
-                    if (cc >= 0 && cc < KC) atomicAdd(&a32[e_aoff[q] + cc], e_val[q]);
-                }
-            } else {
-                for (int32_t e = lo + tid; e < hi; e += kTileBlock) {
-                    int32_t cc = edge_to_col[e] - k0;
-                    if (cc >= 0 && cc < KC) {
-                        int r = 0;
-#pragma unroll
-                        for (int step = 8; step > 0; step >>= 1)
-                            if (s_rp[r + step] <= e) r += step;
-                        atomicAdd(&a32[r * kAStride + cc], HAS_W ? w[e] : 1.f);
-                    }
-                }
-            }
-            __syncthreads();
-            // TCcompute.
-            uint32_t af[4];
-            af[0] = pack2<DT, !HAS_W>(a_lo[0], a_lo[1]);
-            af[1] = pack2<DT, !HAS_W>(a_lo[2], a_lo[3]);
-            af[2] = pack2<DT, !HAS_W>(a_hi[0], a_hi[1]);
-            af[3] = pack2<DT, !HAS_W>(a_hi[2], a_hi[3]);
-#pragma unroll
-            for (int i = 0; i < MAXS; ++i) {
-                const int sl = wave + kWaves * i;
-                if (sl < n_slices) {  // D is a multiple of 8: columns of a half slice beyond D read padding and are never stored
-                    const char *p = xs + b_off + sl * 32;
-                    const uint2 b0 = lds_read_tr16(p);
-                    const uint2 b1 = lds_read_tr16(p + 16 * rs);
-                    const uint32_t bf[4] = {b0.x, b0.y, b1.x, b1.y};
-                    acc[i] = mfma16<DT>(af, bf, acc[i]);
-                }
-            }
-            __syncthreads();
+        for (int i = 0; i < PP; ++i)
+            if (piece_ok) *reinterpret_cast<uint4 *>(xs_dst + i * RPP * rs) = pre[i];
+        nid_cur = nid_nxt;
+        if (k0 + KW < U) {
+            fetch(nid_cur);
+            nid_nxt = k0 + 2 * KW + kk < U ? col_to_row[u0 + k0 + 2 * KW + kk] : -1;
         }
+        // InitSparse
+#pragma unroll
+        for (int i = 0; i < 5; ++i) a32[lane + i * kWave] = 0.f;
+        wave_lds_order();
+        if (edges_in_regs) {
+#pragma unroll
+            for (int q = 0; q < EPT; ++q) {
+                const int32_t cc = (e_code[q] & 0xFFFF) - k0;
+                if (e_code[q] >= 0 && cc >= 0 && cc < KW) atomicAdd(&a32[(e_code[q] >> 16) + cc], HAS_W ? e_val[q] : 1.f);
+            }
+        } else {
+            for (int32_t e = lo + lane; e < hi; e += kWave) {
+                int32_t cc = edge_to_col[e] - k0;
+                if (cc >= 0 && cc < KW) {
+                    int r = 0;
+#pragma unroll
+                    for (int step = 8; step > 0; step >>= 1)
+                        if (s_rp[r + step] <= e) r += step;
+                    atomicAdd(&a32[r * kAStrideW + cc], HAS_W ? w[e] : 1.f);
+                }
+            }
+        }
+        wave_lds_order();
+        // TCcompute
+        const float4 av = *reinterpret_cast<const float4 *>(a_src);
+        uint2 af;
+        af.x = pack2<DT, !HAS_W>(av.x, av.y);
+        af.y = pack2<DT, !HAS_W>(av.z, av.w);
+#pragma unroll
+        for (int i = 0; i < NS; ++i)
+            if (i < n_slices)   // columns of a half slice beyond D read padding and are never stored
+                acc[i] = mfma16k16<DT>(af, lds_read_tr16(b_src + i * 32), acc[i]);
+        wave_lds_order();
     }
 
-    // StoreDense: lane holds rows 4 * (lane / 16) + r, column lane % 16 of each of its slices.
+    // StoreDense.  A lane holds rows 4g .. 4g+3 of one column per slice; the tile goes through LDS (the
+    // staging area is free now), half of the slices at a time, and leaves as whole 16-byte pieces of
+    // consecutive lanes: every store instruction writes RPP complete row parts.
+    constexpr int SP = NS / 2, YS = 8 * NS + 4;                   // slices per pass; LDS row stride in floats
+    float *ys = reinterpret_cast<float *>(xs);
 #pragma unroll
-    for (int i = 0; i < MAXS; ++i) {
-        const int sl = wave + kWaves * i;
-        if (sl >= n_slices) continue;
-        const int n = sl * 16 + n_in;
-        if (n >= D) continue;
+    for (int h = 0; h < 2; ++h) {
+        if (h * SP >= n_slices) break;
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const int64_t row = r0 + 4 * g + r;
-            if (row < n_rows) {
-                if (y_dt == TCG_F32) static_cast<float *>(Y)[row * ldy + n] = acc[i][r];
-                else store_elem(Y, row * ldy + n, y_dt, acc[i][r]);
+        for (int i = 0; i < SP; ++i)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) ys[(4 * g + r) * YS + i * 16 + n_in] = acc[h * SP + i][r];
+        wave_lds_order();
+        const int32_t col = h * SP * 16 + (lane % LPR) * 4;       // first of the lane's 4 columns inside the part
+#pragma unroll
+        for (int i = 0; i < PP; ++i) {
+            const int64_t row = r0 + i * RPP + sub;
+            if (row >= n_rows || col >= Dp) continue;
+            const float4 v = *reinterpret_cast<const float4 *>(ys + (i * RPP + sub) * YS + (lane % LPR) * 4);
+            const int64_t o = row * ldy + d0 + col;
+            if (y_dt == TCG_F32) {
+                float *y = static_cast<float *>(Y) + o;
+                if (y_vec) *reinterpret_cast<float4 *>(y) = v;
+                else { y[0] = v.x; y[1] = v.y; y[2] = v.z; y[3] = v.w; }
+            } else {
+                uint16_t *y = static_cast<uint16_t *>(Y) + o;
+                uint2 pk;
+                if (y_dt == TCG_BF16) {
+                    pk.x = (uint32_t)f32_to_bf16_bits(v.x) | ((uint32_t)f32_to_bf16_bits(v.y) << 16);
+                    pk.y = (uint32_t)f32_to_bf16_bits(v.z) | ((uint32_t)f32_to_bf16_bits(v.w) << 16);
+                } else {
+                    pk.x = (uint32_t)__half_as_ushort(__float2half_rn(v.x)) | ((uint32_t)__half_as_ushort(__float2half_rn(v.y)) << 16);
+                    pk.y = (uint32_t)__half_as_ushort(__float2half_rn(v.z)) | ((uint32_t)__half_as_ushort(__float2half_rn(v.w)) << 16);
+                }
+                if (y_vec) *reinterpret_cast<uint2 *>(y) = pk;
+                else { y[0] = (uint16_t)pk.x; y[1] = (uint16_t)(pk.x >> 16); y[2] = (uint16_t)pk.y; y[3] = (uint16_t)(pk.y >> 16); }
             }
         }
+        wave_lds_order();
     }
 }
 
-template <int DT, bool HAS_W, int MAXS>
-void launch(const tcg_meta *m, const void *X, int64_t ldx, int32_t D, const float *w, void *Y, int y_dt,
-            int64_t ldy, hipStream_t s)
+template <int DT, bool HAS_W, int NS>
+void launch_wave(const tcg_meta *m, const void *X, int64_t ldx, int32_t D, const float *w, void *Y, int y_dt,
+                 int64_t ldy, hipStream_t s)
 {
-    const size_t lds = (size_t)KC * staged_row_stride(D * 2) + 16 * kAStride * sizeof(float) + 17 * sizeof(int32_t);
-    hipLaunchKernelGGL((spmm_tile_kernel<DT, HAS_W, MAXS>), dim3((unsigned)(kXcds * ceil_div(m->n_win, kXcds))), dim3(kTileBlock), lds, s,
-                       m->n_rows, m->n_win, m->d_row_ptr, m->d_edge_to_col, m->d_win_unique_ptr, m->d_col_to_row,
-                       m->d_win_path, w, static_cast<const char *>(X), ldx * 2, D, Y, y_dt, ldy);
+    const int32_t n_dparts = (D + NS * 16 - 1) / (NS * 16);
+    // 4 outputs of a row leave in one store if every such group is aligned to its own size
+    const bool y_vec = ldy % 4 == 0 && reinterpret_cast<uintptr_t>(Y) % (y_dt == TCG_F32 ? 16 : 8) == 0;
+    hipLaunchKernelGGL((spmm_tile_wave_kernel<DT, HAS_W, NS>), dim3((unsigned)(kXcds * ceil_div(m->n_win, kXcds) * n_dparts)),
+                       dim3(kWave), 0, s, m->n_rows, m->n_win, m->d_row_ptr, m->d_edge_to_col, m->d_win_unique_ptr,
+                       m->d_col_to_row, m->d_win_path, w, static_cast<const char *>(X), ldx * 2, D, n_dparts, Y, y_dt, ldy, y_vec);
 }
 
 template <int DT, bool HAS_W>
-void launch_s(const tcg_meta *m, const void *X, int64_t ldx, int32_t D, const float *w, void *Y, int y_dt,
-              int64_t ldy, hipStream_t s)
+void launch_wave_s(const tcg_meta *m, const void *X, int64_t ldx, int32_t D, const float *w, void *Y, int y_dt,
+                   int64_t ldy, hipStream_t s)
 {
-    if (D <= 64) launch<DT, HAS_W, 1>(m, X, ldx, D, w, Y, y_dt, ldy, s);
-    else if (D <= 128) launch<DT, HAS_W, 2>(m, X, ldx, D, w, Y, y_dt, ldy, s);
-    else if (D <= 256) launch<DT, HAS_W, 4>(m, X, ldx, D, w, Y, y_dt, ldy, s);
-    else launch<DT, HAS_W, 8>(m, X, ldx, D, w, Y, y_dt, ldy, s);
+    if (D <= 64) launch_wave<DT, HAS_W, 4>(m, X, ldx, D, w, Y, y_dt, ldy, s);
+    else if (D <= 128) launch_wave<DT, HAS_W, 8>(m, X, ldx, D, w, Y, y_dt, ldy, s);
+    else launch_wave<DT, HAS_W, 16>(m, X, ldx, D, w, Y, y_dt, ldy, s);
 }
 
 }  // namespace
@@ -293,13 +299,13 @@ int spmm_tile_launch(tcg_meta *m, const void *d_X, tcg_dtype x_dt, int32_t D, in
                      void *d_Y, tcg_dtype y_dt, int64_t ldy, hipStream_t s)
 {
     if (x_dt == TCG_BF16) {
-        if (d_w) launch_s<TCG_BF16, true>(m, d_X, ldx, D, d_w, d_Y, (int)y_dt, ldy, s);
-        else launch_s<TCG_BF16, false>(m, d_X, ldx, D, d_w, d_Y, (int)y_dt, ldy, s);
+        if (d_w) launch_wave_s<TCG_BF16, true>(m, d_X, ldx, D, d_w, d_Y, (int)y_dt, ldy, s);
+        else launch_wave_s<TCG_BF16, false>(m, d_X, ldx, D, d_w, d_Y, (int)y_dt, ldy, s);
     } else {
-        if (d_w) launch_s<TCG_F16, true>(m, d_X, ldx, D, d_w, d_Y, (int)y_dt, ldy, s);
-        else launch_s<TCG_F16, false>(m, d_X, ldx, D, d_w, d_Y, (int)y_dt, ldy, s);
+        if (d_w) launch_wave_s<TCG_F16, true>(m, d_X, ldx, D, d_w, d_Y, (int)y_dt, ldy, s);
+        else launch_wave_s<TCG_F16, false>(m, d_X, ldx, D, d_w, d_Y, (int)y_dt, ldy, s);
     }
-    return launch_status("spmm_tile_kernel");
+    return launch_status("spmm_tile_wave_kernel");
 }
 
 }  // namespace tcg

@@ -233,6 +233,41 @@ def test_spmm_rectangular_matrix():
         run_spmm_case(g, W.round_to_bf16(X), "bf16", None, tcg.POLICY_TILE, TOL_F32)
 
 
+@pytest.mark.parametrize("D", [8, 24, 72, 136, 200, 264, 392, 512])
+def test_spmm_tile_path_feature_widths(D):
+    # Widths that are not a multiple of the 16-column slice, that span two and four feature parts,
+    # with and without edge values, padded rows, and outputs that cannot take 16-byte stores.
+    c = W.make_config(5, n=64 * 12, d=D, permute=False)
+    g, X = c["csr"], c["X"]
+    w = np.random.default_rng(D).standard_normal(g.nnz).astype(np.float32)
+    run_spmm_case(g, X, "bf16", w, tcg.POLICY_TILE, TOL_MFMA)
+    run_spmm_case(g, X.astype(np.float16).astype(np.float32), "f16", None, tcg.POLICY_TILE, TOL_MFMA, pad=8)
+    rp, ci = upload_csr(g)
+    meta = tcg.sgt_build(rp, ci, 16, 8)
+    tcg.sgt_set_policy(meta, tcg.POLICY_TILE)
+    Xd = upload_x(X, "bf16")
+    ref = oracle.spmm(g.row_ptr, g.col_idx, X, None)
+    for y_dtype, tol in ((torch.float32, TOL_F32), (torch.bfloat16, 2.0 ** -8)):
+        big = torch.full((g.n_rows, D + 3), float("nan"), dtype=y_dtype, device=dev())
+        Y = big[:, 1:D + 1]                                   # odd leading dimension, shifted start
+        tcg.spmm(meta, Xd, None, Y=Y)
+        torch.cuda.synchronize()
+        assert norm_err(Y.to(torch.float32).cpu().numpy(), ref) <= tol
+        assert torch.isnan(big[:, 0]).all() and torch.isnan(big[:, D + 1:]).all()   # nothing outside Y
+    meta.free()
+
+
+def test_spmm_tile_path_windows_with_many_edges():
+    # Fully dense 16 x 16 blocks: 48 blocks per window give 12,288 edges and 768 condensed columns,
+    # beyond what the tile kernel keeps in registers; 2 blocks per window stay inside it.
+    for blocks in (2, 48):
+        g = W.dense_block_windows(1024, blocks, seed=5)
+        X = W.round_to_bf16(W.features_normal(1024, 40, 6))
+        w = np.random.default_rng(blocks).standard_normal(g.nnz).astype(np.float32)
+        run_spmm_case(g, X, "bf16", None, tcg.POLICY_TILE, TOL_F32)
+        run_spmm_case(g, X, "bf16", w, tcg.POLICY_TILE, TOL_MFMA)
+
+
 def test_spmm_bf16_output():
     c = W.make_config(5, n=64 * 20, d=64, permute=False)
     for policy in (tcg.POLICY_GATHER, tcg.POLICY_TILE):
