@@ -1,0 +1,213 @@
+"""GPU parity of the layer module (paper_2112_02052_amd.nn: differentiable spmm / sddmm / row softmax /
+fused self-attention, GCNConv, AGNNConv and the paper's two benchmark models) against the dense fp64
+layer oracle, values and gradients.
+
+Tolerance: the graph kernels meet 1e-5 (normalised by the largest magnitude of the oracle's result) one
+by one; a layer chains a handful of them with fp32 GEMMs and element-wise fp32 steps, a model chains
+several layers, and rounding errors add up roughly linearly in that depth: 2e-5 for single
+operations and layers, 1e-4 for the multi-layer models."""
+import numpy as np
+import pytest
+import torch
+
+import oracle.layers as L
+import paper_2112_02052_amd as tcg
+import paper_2112_02052_amd.nn as tnn
+import workloads as W
+
+from gpu_util import dev, norm_err, upload_csr
+from test_gpu_backward import asymmetric_graph
+
+pytestmark = pytest.mark.gpu
+
+TOL_LAYER = 2e-5
+TOL_MODEL = 1e-4
+
+
+def t32(a, grad=False):
+    t = torch.tensor(np.asarray(a, dtype=np.float32), device=dev())
+    return t.requires_grad_(True) if grad else t
+
+
+def check(name, got, ref, tol):
+    err = norm_err(got.detach().to(torch.float32).cpu().numpy(), ref)
+    assert err <= tol, "%s: normalised error %.3g above %.1g" % (name, err, tol)
+
+
+def f32(a):
+    return np.asarray(a, dtype=np.float32)
+
+
+@pytest.fixture(scope="module")
+def cfg3():
+    c = W.make_config(3, n=1500, d=32)
+    g = c["csr"]
+    rp, ci = upload_csr(g)
+    graph = tnn.TiledGraph(rp, ci)
+    yield g, graph, f32(c["X"])
+    graph.free()
+
+
+def test_differentiable_spmm_square_and_rectangular(cfg3):
+    g, graph, X = cfg3
+    rng = np.random.default_rng(0)
+    w = f32(rng.standard_normal(g.nnz))
+    dY = f32(rng.standard_normal(X.shape))
+    Xd, wd = t32(X, True), t32(w, True)
+    Y = tnn.spmm(graph, Xd, wd)
+    Y.backward(t32(dY))
+    Yr, dXr, dwr = L.spmm_grads(g.row_ptr, g.col_idx, g.n_cols, w, X, dY)
+    check("Y", Y, Yr, TOL_LAYER)
+    check("dX", Xd.grad, dXr, TOL_LAYER)
+    check("dw", wd.grad, dwr, TOL_LAYER)
+    # unit edge values, no gradient for them
+    Xd = t32(X, True)
+    tnn.spmm(graph, Xd).backward(t32(dY))
+    check("dX unit", Xd.grad, L.spmm_grads(g.row_ptr, g.col_idx, g.n_cols, None, X, dY)[1], TOL_LAYER)
+    # rectangular pattern: X has n_cols rows, Y has n_rows rows
+    gr = asymmetric_graph(300, 900, 4)
+    rp, ci = upload_csr(gr)
+    rect = tnn.TiledGraph(rp, ci, n_cols=gr.n_cols)
+    Xr = f32(rng.standard_normal((900, 24)))
+    wr = f32(rng.standard_normal(gr.nnz))
+    dYr = f32(rng.standard_normal((300, 24)))
+    Xd, wd = t32(Xr, True), t32(wr, True)
+    Y = tnn.spmm(rect, Xd, wd)
+    Y.backward(t32(dYr))
+    ref = L.spmm_grads(gr.row_ptr, gr.col_idx, gr.n_cols, wr, Xr, dYr)
+    check("rect Y", Y, ref[0], TOL_LAYER)
+    check("rect dX", Xd.grad, ref[1], TOL_LAYER)
+    check("rect dw", wd.grad, ref[2], TOL_LAYER)
+    rect.free()
+
+
+def test_differentiable_sddmm_and_softmax(cfg3):
+    g, graph, X = cfg3
+    rng = np.random.default_rng(1)
+    ds = f32(rng.standard_normal(g.nnz))
+    Xd = t32(X, True)
+    s = tnn.sddmm(graph, Xd)
+    s.backward(t32(ds))
+    sr, dXr = L.sddmm_grads(g.row_ptr, g.col_idx, X, ds)
+    check("s", s, sr, TOL_LAYER)
+    check("dX", Xd.grad, dXr, TOL_LAYER)
+
+
+@pytest.mark.parametrize("policy", [tcg.POLICY_AUTO, tcg.POLICY_GATHER])
+def test_self_attention_fused_and_chained(cfg3, policy):
+    g, graph, X = cfg3
+    graph.set_policy(policy)
+    X = X * np.float32(0.3)                                    # keeps the softmax away from one-hot rows
+    dH = f32(np.random.default_rng(2).standard_normal(X.shape))
+    Hr, Pr, dXr = L.self_attention(g.row_ptr, g.col_idx, X, dH)
+    Xd = t32(X, True)
+    H = tnn.self_attention(graph, Xd)
+    H.backward(t32(dH))
+    check("fused H", H, Hr, TOL_LAYER)
+    check("fused dX", Xd.grad, dXr, TOL_LAYER)
+    Xd = t32(X, True)
+    P = tnn.row_softmax(graph, tnn.sddmm(graph, Xd))
+    H = tnn.spmm(graph, Xd, P)
+    H.backward(t32(dH))
+    check("chain P", P, Pr, TOL_LAYER)
+    check("chain H", H, Hr, TOL_LAYER)
+    check("chain dX", Xd.grad, dXr, TOL_LAYER)
+    graph.set_policy(tcg.POLICY_AUTO)
+
+
+@pytest.mark.parametrize("in_dim,out_dim", [(48, 16), (16, 40)])
+def test_gcn_conv(in_dim, out_dim):
+    c = W.make_config(2, n=1200, d=in_dim)
+    g, X, w = c["csr"], f32(c["X"]), c["w"]
+    rp, ci = upload_csr(g)
+    graph = tnn.TiledGraph(rp, ci)
+    torch.manual_seed(0)
+    layer = tnn.GCNConv(in_dim, out_dim).to(dev())
+    with torch.no_grad():
+        layer.bias.copy_(torch.randn(out_dim))
+    dH = f32(np.random.default_rng(3).standard_normal((g.n_rows, out_dim)))
+    Xd, wd = t32(X, True), t32(w, True)
+    H = layer(Xd, graph, wd)
+    H.backward(t32(dH))
+    Wn = layer.linear.weight.detach().cpu().numpy()
+    bn = layer.bias.detach().cpu().numpy()
+    Hr, dXr, dWr, dbr, dwr = L.gcn_conv(g.row_ptr, g.col_idx, g.n_cols, w, X, Wn, bn, dH)
+    check("H", H, Hr, TOL_LAYER)
+    check("dX", Xd.grad, dXr, TOL_LAYER)
+    check("dW", layer.linear.weight.grad, dWr, TOL_LAYER)
+    check("db", layer.bias.grad, dbr, TOL_LAYER)
+    check("dw", wd.grad, dwr, TOL_LAYER)
+    graph.free()
+
+
+def test_agnn_conv(cfg3):
+    g, graph, X = cfg3
+    beta = 1.3
+    layer = tnn.AGNNConv(init_beta=beta).to(dev())
+    dH = f32(np.random.default_rng(4).standard_normal(X.shape))
+    Xd = t32(X, True)
+    H = layer(Xd, graph)
+    H.backward(t32(dH))
+    Hr, Pr, dXr, dbr = L.agnn_conv(g.row_ptr, g.col_idx, X, beta, dH)
+    check("H", H, Hr, TOL_LAYER)
+    check("dX", Xd.grad, dXr, TOL_LAYER)
+    assert abs(layer.beta.grad.item() - dbr) <= TOL_MODEL * max(1.0, abs(dbr))   # a sum over all edges
+
+
+def test_gcn_model_training_step():
+    # the paper's GCN setting: two layers, 16 hidden features
+    c = W.make_config(2, n=1500, d=64)
+    g, X, w = c["csr"], f32(c["X"]), c["w"]
+    rp, ci = upload_csr(g)
+    graph = tnn.TiledGraph(rp, ci)
+    torch.manual_seed(1)
+    model = tnn.GCN(64, 16, 7).to(dev())
+    dOut = f32(np.random.default_rng(5).standard_normal((g.n_rows, 7)))
+    out = model(t32(X), graph, t32(w))
+    out.backward(t32(dOut))
+    params = [model.layer1.linear.weight, model.layer1.bias, model.layer2.linear.weight, model.layer2.bias]
+    ref_out, ref_grads = L.gcn_model(g.row_ptr, g.col_idx, w, X, [p.detach().cpu().numpy() for p in params], dOut)
+    check("out", out, ref_out, TOL_MODEL)
+    for name, p, r in zip(("dW1", "db1", "dW2", "db2"), params, ref_grads):
+        check(name, p.grad, r, TOL_MODEL)
+    graph.free()
+
+
+def test_agnn_model_training_step():
+    # the paper's AGNN setting: four propagation layers, 32 hidden features
+    c = W.make_config(3, n=1200, d=48)
+    g, X = c["csr"], f32(c["X"])
+    rp, ci = upload_csr(g)
+    graph = tnn.TiledGraph(rp, ci)
+    torch.manual_seed(2)
+    model = tnn.AGNN(48, 32, 5, n_layers=4).to(dev())
+    with torch.no_grad():
+        for k, prop in enumerate(model.props):
+            prop.beta.fill_(0.5 + 0.25 * k)
+    dOut = f32(np.random.default_rng(6).standard_normal((g.n_rows, 5)))
+    out = model(t32(X), graph)
+    out.backward(t32(dOut))
+    params = [model.embed.weight, model.embed.bias, model.readout.weight, model.readout.bias]
+    betas = [float(p.beta.detach()) for p in model.props]
+    ref_out, ref_grads = L.agnn_model(g.row_ptr, g.col_idx, X, [p.detach().cpu().numpy() for p in params], betas, dOut)
+    check("out", out, ref_out, TOL_MODEL)
+    for name, p, r in zip(("dWe", "dbe", "dWr", "dbr"), params, ref_grads[:4]):
+        check(name, p.grad, r, TOL_MODEL)
+    for k, prop in enumerate(model.props):
+        r = float(ref_grads[4 + k])
+        assert abs(prop.beta.grad.item() - r) <= TOL_MODEL * max(1.0, abs(r)), (k, prop.beta.grad.item(), r)
+    graph.free()
+
+
+def test_bf16_features_through_the_layers(cfg3):
+    # bf16 node features: the graph kernels take them as they are; gradients come back in bf16.
+    g, graph, X = cfg3
+    Xb = W.round_to_bf16(X * np.float32(0.3))
+    dH = W.round_to_bf16(f32(np.random.default_rng(7).standard_normal(X.shape)))
+    Xd = torch.tensor(Xb, device=dev()).to(torch.bfloat16).requires_grad_(True)
+    H = tnn.self_attention(graph, Xd)
+    H.backward(t32(dH))
+    Hr, _, dXr = L.self_attention(g.row_ptr, g.col_idx, Xb, dH)
+    check("H", H, Hr, 1e-2)
+    assert Xd.grad.dtype == torch.bfloat16
+    check("dX", Xd.grad, dXr, 2e-2)
