@@ -78,6 +78,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--backward", action="store_true",
                     help="also time the backward-pass building blocks (transpose, dX = A^T dY, dw = SDDMM(dY, X))")
+    ap.add_argument("--model", default=None, choices=["gcn", "agnn"],
+                    help="also time training epochs of the paper's GCN (2 layers, 16 hidden) or AGNN (4 layers, "
+                         "32 hidden) model built from the layer module on this workload's graph")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 512 MiB device copy (reference dispatch for HBM counter scaling)")
     args = ap.parse_args()
@@ -261,6 +264,41 @@ def main():
             "dw_sddmm_pq_ms": timed_loop(lambda: tcg.sddmm_pq(meta, Gd, Xd[feat], out=E), reps),
         }
         meta_t.free()
+
+    if args.model:
+        import paper_2112_02052_amd.nn as tnn
+        graph = tnn.TiledGraph(rp, ci, validate=False)
+        graph.transposed()                                                # built once, like the forward plan
+        torch.manual_seed(0)
+        n_classes = 10
+        Xf = Xd["f32"]
+        if args.model == "gcn":
+            model = tnn.GCN(D, 16, n_classes).to(dev)
+            wv = w_given if w_given is not None else None
+            fwd = lambda: model(Xf, graph, wv)                            # noqa: E731
+        else:
+            model = tnn.AGNN(D, 32, n_classes, n_layers=4).to(dev)
+            fwd = lambda: model(Xf, graph)                                # noqa: E731
+        labels = torch.randint(0, n_classes, (N,), device=dev)
+        opt = torch.optim.Adam(model.parameters(), lr=0.01)
+
+        def epoch():
+            opt.zero_grad(set_to_none=True)
+            loss = -fwd().gather(1, labels[:, None]).mean()               # negative log-likelihood of the labels
+            loss.backward()
+            opt.step()
+
+        def forward_only():
+            with torch.no_grad():
+                fwd()
+
+        for _ in range(3):
+            epoch()
+        out["model"] = {"name": args.model, "layers": 2 if args.model == "gcn" else 4,
+                        "hidden": 16 if args.model == "gcn" else 32, "in_dim": D, "classes": n_classes,
+                        "epoch_ms": timed_loop(epoch, reps), "forward_ms": timed_loop(forward_only, reps),
+                        "epoch": "forward + NLL loss + backward + Adam step, fp32, translated graph and its transpose reused"}
+        graph.free()
 
     if not args.no_cpu_baseline:
         import oracle

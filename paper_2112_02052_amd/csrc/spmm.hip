@@ -134,7 +134,92 @@ __global__ __launch_bounds__(kBlock) void spmm_gather_kernel(
     }
 }
 
-// Any D, any alignment: one wavefront per segment, one lane per feature element.
+// Rows that cannot be read in 16-byte pieces (width or leading dimension not a multiple of 16 bytes,
+// or a misaligned base): the same segment / group / prefetch structure with one element per lane and
+// pass, G lanes per segment, D <= G * NCH.  Narrow outputs of a layer (a handful of classes) land here.
+template <int DT, int G, int NCH, bool HAS_W, int UNROLL>
+__global__ __launch_bounds__(kBlock) void spmm_gather_elem_kernel(
+    const int32_t *__restrict__ lane_tab, const int32_t *__restrict__ seg_row, const int32_t *__restrict__ seg_ebeg,
+    const int32_t *__restrict__ seg_dst, const int32_t *__restrict__ row_ptr,
+    const int32_t *__restrict__ col_idx, const float *__restrict__ w, const char *__restrict__ X,
+    int64_t ldx_bytes, int32_t D, void *__restrict__ Y, int y_dt, int64_t ldy, float *__restrict__ partial,
+    int64_t partial_ld, const uint8_t *__restrict__ win_path, int32_t win_h)
+{
+    constexpr int ES = Elem<DT>::BYTES;
+    const int lane = threadIdx.x % G;
+    const int64_t seg = plan_segment(lane_tab, kBlock / G, threadIdx.x / G);
+    if (seg < 0) return;
+    const int32_t row = seg_row[seg];
+    if (win_path != nullptr && win_path[row / win_h]) return;
+    const int32_t eb = seg_ebeg[seg];
+    const int32_t ee = min(eb + kSegLen, row_ptr[row + 1]);
+
+    float acc[NCH];
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) acc[c] = 0.f;
+
+    if (eb < ee) {
+        const int32_t last = ee - 1;
+        int32_t cn[UNROLL];
+        float wn[UNROLL];
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            const int32_t en = min(eb + u, last);
+            cn[u] = col_idx[en];
+            wn[u] = HAS_W ? w[en] : 1.f;
+        }
+        for (int32_t e = eb; e < ee; e += UNROLL) {
+            int32_t cnext[UNROLL];
+            float wnext[UNROLL];
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) {
+                const int32_t en = min(e + UNROLL + u, last);
+                cnext[u] = col_idx[en];
+                wnext[u] = HAS_W ? w[en] : 1.f;
+            }
+            float v[UNROLL][NCH];
+            float wc[UNROLL];
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) {
+                wc[u] = (e + u < ee) ? wn[u] : 0.f;
+                const char *xr = X + (int64_t)cn[u] * ldx_bytes;
+#pragma unroll
+                for (int c = 0; c < NCH; ++c) {
+                    const int d = lane + c * G;
+                    v[u][c] = 0.f;
+                    if (e + u < ee && d < D) {
+                        if constexpr (DT == TCG_F32) v[u][c] = *reinterpret_cast<const float *>(xr + d * ES);
+                        else if constexpr (DT == TCG_BF16) v[u][c] = bf16_bits_to_f32(*reinterpret_cast<const uint16_t *>(xr + d * ES));
+                        else v[u][c] = f16_bits_to_f32(*reinterpret_cast<const uint16_t *>(xr + d * ES));
+                    }
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) {
+                cn[u] = cnext[u];
+                wn[u] = wnext[u];
+            }
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u)
+#pragma unroll
+                for (int c = 0; c < NCH; ++c) {
+                    if (HAS_W) acc[c] = fmaf(wc[u], v[u][c], acc[c]);
+                    else acc[c] += v[u][c];
+                }
+        }
+    }
+
+    const int32_t dst = seg_dst[seg];
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+        const int d = lane + c * G;
+        if (d >= D) continue;
+        if (dst >= 0) partial[(int64_t)dst * partial_ld + d] = acc[c];
+        else store_elem(Y, (int64_t)row * ldy + d, y_dt, acc[c]);
+    }
+}
+
+// Any D, any alignment: one wavefront per segment, one lane per feature element (D > 256 only).
 template <bool HAS_W>
 __global__ __launch_bounds__(kBlock) void spmm_gather_generic_kernel(
     const int32_t *__restrict__ lane_tab, const int32_t *__restrict__ seg_row, const int32_t *__restrict__ seg_ebeg,
@@ -233,6 +318,38 @@ bool dispatch_gather_w(const GatherArgs &a, int32_t n_chunks)
     return a.w ? dispatch_gather<DT, true>(a, n_chunks) : dispatch_gather<DT, false>(a, n_chunks);
 }
 
+template <int DT, int G, int NCH, bool HAS_W>
+void launch_elem(const GatherArgs &a)
+{
+    constexpr int UNROLL = NCH == 1 ? 8 : (NCH == 2 ? 4 : 2);
+    const tcg_meta *m = a.m;
+    const unsigned grid = (unsigned)plan_grid(m->h_lane_tab, kBlock / G);
+    hipLaunchKernelGGL((spmm_gather_elem_kernel<DT, G, NCH, HAS_W, UNROLL>), dim3(grid), dim3(kBlock), 0, a.s,
+                       m->d_lane_tab, m->d_seg_row, m->d_seg_ebeg, m->d_seg_dst, m->d_row_ptr, m->d_col_idx, a.w,
+                       static_cast<const char *>(a.X), a.ldx * Elem<DT>::BYTES, a.D, a.Y, a.y_dt, a.ldy,
+                       m->d_partial, (int64_t)a.D, a.win_path, m->win_h);
+}
+
+template <int DT, bool HAS_W>
+bool dispatch_elem(const GatherArgs &a)
+{
+    if (a.D <= 4) launch_elem<DT, 4, 1, HAS_W>(a);
+    else if (a.D <= 8) launch_elem<DT, 8, 1, HAS_W>(a);
+    else if (a.D <= 16) launch_elem<DT, 16, 1, HAS_W>(a);
+    else if (a.D <= 32) launch_elem<DT, 32, 1, HAS_W>(a);
+    else if (a.D <= 64) launch_elem<DT, 64, 1, HAS_W>(a);
+    else if (a.D <= 128) launch_elem<DT, 64, 2, HAS_W>(a);
+    else if (a.D <= 256) launch_elem<DT, 64, 4, HAS_W>(a);
+    else return false;
+    return true;
+}
+
+template <int DT>
+bool dispatch_elem_w(const GatherArgs &a)
+{
+    return a.w ? dispatch_elem<DT, true>(a) : dispatch_elem<DT, false>(a);
+}
+
 }  // namespace
 
 int spmm_impl(tcg_meta *m, const void *d_X, tcg_dtype x_dt, int32_t D, int64_t ldx, const float *d_w,
@@ -270,6 +387,11 @@ int spmm_impl(tcg_meta *m, const void *d_X, tcg_dtype x_dt, int32_t D, int64_t l
         if (x_dt == TCG_F32) done = dispatch_gather_w<TCG_F32>(a, n_chunks);
         else if (x_dt == TCG_BF16) done = dispatch_gather_w<TCG_BF16>(a, n_chunks);
         else done = dispatch_gather_w<TCG_F16>(a, n_chunks);
+    }
+    if (!done) {
+        if (x_dt == TCG_F32) done = dispatch_elem_w<TCG_F32>(a);
+        else if (x_dt == TCG_BF16) done = dispatch_elem_w<TCG_BF16>(a);
+        else done = dispatch_elem_w<TCG_F16>(a);
     }
     if (!done) {
         const unsigned grid = (unsigned)plan_grid(m->h_lane_tab, kBlock / kWave);

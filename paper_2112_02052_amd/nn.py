@@ -135,6 +135,54 @@ class _SelfAttention(torch.autograd.Function):
         return None, dX.to(Xc.dtype)
 
 
+def _tall_tn(A, B, chunk=4096):
+    """A^T B for tall A [N, p] and B [N, q]: the reduction over the N nodes is cut into chunks that run as
+    one batched GEMM and are then added, which gives the BLAS library parallel work when p and q are
+    small (a plain GEMM call reduces over all N inside a handful of workgroups)."""
+    N = A.shape[0]
+    S = N // chunk
+    if S < 2:
+        return A.t() @ B
+    head = S * chunk
+    A, B = A.contiguous(), B.contiguous()
+    out = torch.bmm(A[:head].view(S, chunk, -1).transpose(1, 2), B[:head].view(S, chunk, -1)).sum(dim=0)
+    if head < N:
+        out += A[head:].t() @ B[head:]
+    return out
+
+
+class _NodeLinear(torch.autograd.Function):
+    """Z = X W^T with one row of X per node (the update phase); only the weight gradient differs from
+    torch's own linear: it uses the chunked reduction above."""
+
+    @staticmethod
+    def forward(ctx, X, W):
+        ctx.save_for_backward(X, W)
+        return X @ W.t()
+
+    @staticmethod
+    def backward(ctx, dZ):
+        X, W = ctx.saved_tensors
+        dX = dZ @ W if ctx.needs_input_grad[0] else None
+        dW = _tall_tn(dZ, X) if ctx.needs_input_grad[1] else None
+        return dX, dW
+
+
+class NodeLinear(torch.nn.Module):
+    """Linear update of node features, Z = X W^T (+ b), initialised like torch.nn.Linear."""
+
+    def __init__(self, in_features, out_features, bias=True):
+        super().__init__()
+        ref = torch.nn.Linear(in_features, out_features, bias=bias)
+        self.in_features, self.out_features = in_features, out_features
+        self.weight = torch.nn.Parameter(ref.weight.detach().clone())
+        self.bias = torch.nn.Parameter(ref.bias.detach().clone()) if bias else None
+
+    def forward(self, X):
+        Z = _NodeLinear.apply(X, self.weight)
+        return Z if self.bias is None else Z + self.bias
+
+
 def spmm(graph, X, w=None):
     """Differentiable Y = (w . A) X (Eq. 1); w = None means unit edge values."""
     return _SpMM.apply(graph, X, w)
@@ -162,7 +210,7 @@ class GCNConv(torch.nn.Module):
 
     def __init__(self, in_dim, out_dim, bias=True):
         super().__init__()
-        self.linear = torch.nn.Linear(in_dim, out_dim, bias=False)
+        self.linear = NodeLinear(in_dim, out_dim, bias=False)
         self.bias = torch.nn.Parameter(torch.zeros(out_dim)) if bias else None
 
     def forward(self, X, graph, edge_values=None):
@@ -210,9 +258,9 @@ class AGNN(torch.nn.Module):
 
     def __init__(self, in_dim, hidden_dim, out_dim, n_layers=4):
         super().__init__()
-        self.embed = torch.nn.Linear(in_dim, hidden_dim)
+        self.embed = NodeLinear(in_dim, hidden_dim)
         self.props = torch.nn.ModuleList([AGNNConv() for _ in range(n_layers)])
-        self.readout = torch.nn.Linear(hidden_dim, out_dim)
+        self.readout = NodeLinear(hidden_dim, out_dim)
 
     def forward(self, X, graph):
         H = torch.relu(self.embed(X))
