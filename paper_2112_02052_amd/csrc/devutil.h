@@ -48,6 +48,48 @@ __device__ __forceinline__ void unpack16(const uint4 &raw, float *v)
     }
 }
 
+// The unit a lane reads from a feature row: PB bytes = VEC elements.  16-byte chunks are the normal case;
+// rows whose width, leading dimension or base address rule them out are read in 4-byte units (one fp32
+// or two 16-bit elements) or, failing that, element by element.
+template <int DT, int PB>
+struct Piece {
+    static constexpr int BYTES = PB;
+    static constexpr int VEC = PB / Elem<DT>::BYTES;
+    static_assert(PB == 16 || PB == 4 || PB == Elem<DT>::BYTES, "unsupported piece size");
+    // p must be valid and PB-aligned; v receives VEC floats
+    static __device__ __forceinline__ void load(const char *p, float *v)
+    {
+        if constexpr (PB == 16) {
+            unpack16<DT>(*reinterpret_cast<const uint4 *>(p), v);
+        } else if constexpr (DT == TCG_F32) {
+            v[0] = *reinterpret_cast<const float *>(p);
+        } else if constexpr (PB == 4) {
+            const uint32_t r = *reinterpret_cast<const uint32_t *>(p);
+            if constexpr (DT == TCG_BF16) {
+                v[0] = __uint_as_float(r << 16);
+                v[1] = __uint_as_float(r & 0xFFFF0000u);
+            } else {
+                v[0] = f16_bits_to_f32(r & 0xFFFFu);
+                v[1] = f16_bits_to_f32(r >> 16);
+            }
+        } else if constexpr (DT == TCG_BF16) {
+            v[0] = bf16_bits_to_f32(*reinterpret_cast<const uint16_t *>(p));
+        } else {
+            v[0] = f16_bits_to_f32(*reinterpret_cast<const uint16_t *>(p));
+        }
+    }
+};
+
+// Largest piece smaller than 16 bytes that rows of `width` elements with leading dimensions ld_a, ld_b
+// (elements) at base addresses a, b allow for element size es.
+inline int small_piece_bytes(int es, int64_t width, int64_t ld_a, int64_t ld_b, const void *a, const void *b)
+{
+    if (es == 4) return 4;
+    const bool pair = width % 2 == 0 && ld_a % 2 == 0 && ld_b % 2 == 0 &&
+                      (reinterpret_cast<uintptr_t>(a) & 3) == 0 && (reinterpret_cast<uintptr_t>(b) & 3) == 0;
+    return pair ? 4 : 2;
+}
+
 // Scalar element load as fp32.
 __device__ __forceinline__ float load_elem(const void *base, int64_t idx, int dt)
 {

@@ -25,14 +25,18 @@ constexpr int kBlock = 256;
 // After group_reduce with G >= UNROLL, lane (position in group) `l` holds the total of partial
 // index idx(l): step off=1 keeps index parity = bit 0 of l as the LOWEST bit of the original
 // index, the next step bit 1, and so on; so idx(l) = l mod UNROLL.
-template <int DT, int G, int NCH, int UNROLL>
+// PB: bytes a lane reads per piece; n_chunks = pieces per row.  16 is the normal case, smaller pieces
+// serve rows that cannot be read in 16-byte chunks.
+template <int DT, int G, int NCH, int UNROLL, int PB>
 __global__ __launch_bounds__(kBlock) void sddmm_gather_kernel(
     const int32_t *__restrict__ lane_tab, const int32_t *__restrict__ seg_row, const int32_t *__restrict__ seg_ebeg,
     const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ col_idx,
     const char *__restrict__ P, int64_t ldp_bytes, const char *__restrict__ X, int64_t ldx_bytes, int32_t n_chunks,
     float *__restrict__ out, const uint8_t *__restrict__ win_path, int32_t win_h)
 {
-    constexpr int VEC = Elem<DT>::VEC;
+    using Pc = Piece<DT, PB>;
+    constexpr bool ELEM = PB != 16;
+    constexpr int VEC = Pc::VEC;
     const int lane = threadIdx.x % G;
     const int64_t seg = plan_segment(lane_tab, kBlock / G, threadIdx.x / G);
     if (seg < 0) return;              // G divides the wavefront: whole groups leave together
@@ -47,9 +51,9 @@ __global__ __launch_bounds__(kBlock) void sddmm_gather_kernel(
 #pragma unroll
         for (int c = 0; c < NCH; ++c) {
             int chunk = lane + c * G;
-            uint4 raw = make_uint4(0, 0, 0, 0);
-            if (chunk < n_chunks) raw = *reinterpret_cast<const uint4 *>(xr + (int64_t)chunk * 16);
-            unpack16<DT>(raw, xi[c]);
+#pragma unroll
+            for (int k = 0; k < VEC; ++k) xi[c][k] = 0.f;
+            if (chunk < n_chunks) Pc::load(xr + (int64_t)chunk * Pc::BYTES, xi[c]);
         }
     }
 
@@ -66,32 +70,58 @@ __global__ __launch_bounds__(kBlock) void sddmm_gather_kernel(
         int32_t cnext[UNROLL];
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) cnext[u] = col_idx[min(e + UNROLL + u, last)];
-        uint4 raw[UNROLL][NCH];
-#pragma unroll
-        for (int u = 0; u < UNROLL; ++u) {
-            const char *xr = X + (uint64_t)(uint32_t)cn[u] * ldx32;
-#pragma unroll
-            for (int c = 0; c < NCH; ++c) {
-                int chunk = lane + c * G;
-                raw[u][c] = make_uint4(0, 0, 0, 0);
-                if (e + u < ee && chunk < n_chunks)
-                    raw[u][c] = *reinterpret_cast<const uint4 *>(xr + (uint32_t)chunk * 16u);
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < UNROLL; ++u) cn[u] = cnext[u];
         float p[UNROLL];
+        if constexpr (!ELEM) {
+            uint4 raw[UNROLL][NCH];
 #pragma unroll
-        for (int u = 0; u < UNROLL; ++u) {
-            float a = 0.f;
+            for (int u = 0; u < UNROLL; ++u) {
+                const char *xr = X + (uint64_t)(uint32_t)cn[u] * ldx32;
 #pragma unroll
-            for (int c = 0; c < NCH; ++c) {
-                float v[VEC];
-                unpack16<DT>(raw[u][c], v);
-#pragma unroll
-                for (int k = 0; k < VEC; ++k) a = fmaf(xi[c][k], v[k], a);
+                for (int c = 0; c < NCH; ++c) {
+                    int chunk = lane + c * G;
+                    raw[u][c] = make_uint4(0, 0, 0, 0);
+                    if (e + u < ee && chunk < n_chunks)
+                        raw[u][c] = *reinterpret_cast<const uint4 *>(xr + (uint32_t)chunk * 16u);
+                }
             }
-            p[u] = a;
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) cn[u] = cnext[u];
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) {
+                float a = 0.f;
+#pragma unroll
+                for (int c = 0; c < NCH; ++c) {
+                    float v[VEC];
+                    unpack16<DT>(raw[u][c], v);
+#pragma unroll
+                    for (int k = 0; k < VEC; ++k) a = fmaf(xi[c][k], v[k], a);
+                }
+                p[u] = a;
+            }
+        } else {
+            float v[UNROLL][NCH][VEC];
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) {
+                const char *xr = X + (int64_t)cn[u] * ldx_bytes;
+#pragma unroll
+                for (int c = 0; c < NCH; ++c) {
+                    int chunk = lane + c * G;
+#pragma unroll
+                    for (int k = 0; k < VEC; ++k) v[u][c][k] = 0.f;
+                    if (e + u < ee && chunk < n_chunks) Pc::load(xr + (int64_t)chunk * Pc::BYTES, v[u][c]);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) cn[u] = cnext[u];
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) {
+                float a = 0.f;
+#pragma unroll
+                for (int c = 0; c < NCH; ++c)
+#pragma unroll
+                    for (int k = 0; k < VEC; ++k) a = fmaf(xi[c][k], v[u][c][k], a);
+                p[u] = a;
+            }
         }
         float r = group_reduce<G, UNROLL>(p, lane);
         if constexpr (G >= UNROLL) {
@@ -197,13 +227,13 @@ __global__ __launch_bounds__(kBlock) void row_softmax_long_kernel(const int32_t 
     for (int32_t k = b + threadIdx.x; k < e; k += kBlock) out[k] = expf(in[k] - m) * inv;
 }
 
-template <int DT, int G, int NCH>
+template <int DT, int G, int NCH, int PB = 16>
 void launch_sddmm(const tcg_meta *m, const void *P, int64_t ldp, const void *X, int64_t ldx, int32_t n_chunks,
                   float *out, const uint8_t *win_path, hipStream_t s)
 {
     constexpr int UNROLL = NCH == 1 ? 8 : (NCH == 2 ? 4 : 2);
     const unsigned grid = (unsigned)plan_grid(m->h_lane_tab, kBlock / G);
-    hipLaunchKernelGGL((sddmm_gather_kernel<DT, G, NCH, UNROLL>), dim3(grid), dim3(kBlock), 0, s, m->d_lane_tab,
+    hipLaunchKernelGGL((sddmm_gather_kernel<DT, G, NCH, UNROLL, PB>), dim3(grid), dim3(kBlock), 0, s, m->d_lane_tab,
                        m->d_seg_row, m->d_seg_ebeg, m->d_row_ptr, m->d_col_idx, static_cast<const char *>(P),
                        ldp * Elem<DT>::BYTES, static_cast<const char *>(X), ldx * Elem<DT>::BYTES, n_chunks, out, win_path,
                        m->win_h);
@@ -222,6 +252,33 @@ bool dispatch_sddmm(const tcg_meta *m, const void *P, int64_t ldp, const void *X
     else if (n_chunks <= 256) launch_sddmm<DT, 64, 4>(m, P, ldp, X, ldx, n_chunks, out, win_path, s);
     else return false;
     return true;
+}
+
+// Rows read in pieces of PB < 16 bytes: up to 256 pieces per row.
+template <int DT, int PB>
+bool dispatch_sddmm_small(const tcg_meta *m, const void *P, int64_t ldp, const void *X, int64_t ldx, int32_t D,
+                          float *out, const uint8_t *win_path, hipStream_t s)
+{
+    const int32_t n = D / Piece<DT, PB>::VEC;
+    if (n <= 4) launch_sddmm<DT, 4, 1, PB>(m, P, ldp, X, ldx, n, out, win_path, s);
+    else if (n <= 8) launch_sddmm<DT, 8, 1, PB>(m, P, ldp, X, ldx, n, out, win_path, s);
+    else if (n <= 16) launch_sddmm<DT, 16, 1, PB>(m, P, ldp, X, ldx, n, out, win_path, s);
+    else if (n <= 32) launch_sddmm<DT, 32, 1, PB>(m, P, ldp, X, ldx, n, out, win_path, s);
+    else if (n <= 64) launch_sddmm<DT, 64, 1, PB>(m, P, ldp, X, ldx, n, out, win_path, s);
+    else if (n <= 128) launch_sddmm<DT, 64, 2, PB>(m, P, ldp, X, ldx, n, out, win_path, s);
+    else if (n <= 256) launch_sddmm<DT, 64, 4, PB>(m, P, ldp, X, ldx, n, out, win_path, s);
+    else return false;
+    return true;
+}
+
+template <int DT>
+bool dispatch_sddmm_elem(const tcg_meta *m, const void *P, int64_t ldp, const void *X, int64_t ldx, int32_t D,
+                         float *out, const uint8_t *win_path, hipStream_t s)
+{
+    if (small_piece_bytes(Elem<DT>::BYTES, D, ldp, ldx, P, X) == 4)
+        return dispatch_sddmm_small<DT, 4>(m, P, ldp, X, ldx, D, out, win_path, s);
+    if constexpr (DT != TCG_F32) return dispatch_sddmm_small<DT, 2>(m, P, ldp, X, ldx, D, out, win_path, s);
+    return false;
 }
 
 }  // namespace
@@ -246,6 +303,11 @@ int sddmm_impl(tcg_meta *m, const void *d_P, int64_t ldp, const void *d_X, int64
         if (x_dt == TCG_F32) done = dispatch_sddmm<TCG_F32>(m, d_P, ldp, d_X, ldx, n_chunks, d_out, win_path, s);
         else if (x_dt == TCG_BF16) done = dispatch_sddmm<TCG_BF16>(m, d_P, ldp, d_X, ldx, n_chunks, d_out, win_path, s);
         else done = dispatch_sddmm<TCG_F16>(m, d_P, ldp, d_X, ldx, n_chunks, d_out, win_path, s);
+    }
+    if (!done) {
+        if (x_dt == TCG_F32) done = dispatch_sddmm_elem<TCG_F32>(m, d_P, ldp, d_X, ldx, D, d_out, win_path, s);
+        else if (x_dt == TCG_BF16) done = dispatch_sddmm_elem<TCG_BF16>(m, d_P, ldp, d_X, ldx, D, d_out, win_path, s);
+        else done = dispatch_sddmm_elem<TCG_F16>(m, d_P, ldp, d_X, ldx, D, d_out, win_path, s);
     }
     if (!done) {
         const unsigned grid = (unsigned)plan_grid(m->h_lane_tab, kBlock / kWave);

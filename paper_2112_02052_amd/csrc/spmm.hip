@@ -135,17 +135,19 @@ __global__ __launch_bounds__(kBlock) void spmm_gather_kernel(
 }
 
 // Rows that cannot be read in 16-byte pieces (width or leading dimension not a multiple of 16 bytes,
-// or a misaligned base): the same segment / group / prefetch structure with one element per lane and
-// pass, G lanes per segment, D <= G * NCH.  Narrow outputs of a layer (a handful of classes) land here.
-template <int DT, int G, int NCH, bool HAS_W, int UNROLL>
-__global__ __launch_bounds__(kBlock) void spmm_gather_elem_kernel(
+// or a misaligned base): the same segment / group / prefetch structure with pieces of PB = 4 bytes (one
+// fp32, two 16-bit elements) or one 16-bit element per lane and pass; G lanes per segment, n_pieces <=
+// G * NCH.  Narrow outputs of a layer (a handful of classes) land here.
+template <int DT, int PB, int G, int NCH, bool HAS_W, int UNROLL>
+__global__ __launch_bounds__(kBlock) void spmm_gather_small_kernel(
     const int32_t *__restrict__ lane_tab, const int32_t *__restrict__ seg_row, const int32_t *__restrict__ seg_ebeg,
     const int32_t *__restrict__ seg_dst, const int32_t *__restrict__ row_ptr,
     const int32_t *__restrict__ col_idx, const float *__restrict__ w, const char *__restrict__ X,
-    int64_t ldx_bytes, int32_t D, void *__restrict__ Y, int y_dt, int64_t ldy, float *__restrict__ partial,
+    int64_t ldx_bytes, int32_t n_pieces, void *__restrict__ Y, int y_dt, int64_t ldy, float *__restrict__ partial,
     int64_t partial_ld, const uint8_t *__restrict__ win_path, int32_t win_h)
 {
-    constexpr int ES = Elem<DT>::BYTES;
+    using Pc = Piece<DT, PB>;
+    constexpr int VEC = Pc::VEC;
     const int lane = threadIdx.x % G;
     const int64_t seg = plan_segment(lane_tab, kBlock / G, threadIdx.x / G);
     if (seg < 0) return;
@@ -154,9 +156,11 @@ __global__ __launch_bounds__(kBlock) void spmm_gather_elem_kernel(
     const int32_t eb = seg_ebeg[seg];
     const int32_t ee = min(eb + kSegLen, row_ptr[row + 1]);
 
-    float acc[NCH];
+    float acc[NCH][VEC];
 #pragma unroll
-    for (int c = 0; c < NCH; ++c) acc[c] = 0.f;
+    for (int c = 0; c < NCH; ++c)
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) acc[c][k] = 0.f;
 
     if (eb < ee) {
         const int32_t last = ee - 1;
@@ -177,7 +181,7 @@ __global__ __launch_bounds__(kBlock) void spmm_gather_elem_kernel(
                 cnext[u] = col_idx[en];
                 wnext[u] = HAS_W ? w[en] : 1.f;
             }
-            float v[UNROLL][NCH];
+            float v[UNROLL][NCH][VEC];
             float wc[UNROLL];
 #pragma unroll
             for (int u = 0; u < UNROLL; ++u) {
@@ -185,13 +189,10 @@ __global__ __launch_bounds__(kBlock) void spmm_gather_elem_kernel(
                 const char *xr = X + (int64_t)cn[u] * ldx_bytes;
 #pragma unroll
                 for (int c = 0; c < NCH; ++c) {
-                    const int d = lane + c * G;
-                    v[u][c] = 0.f;
-                    if (e + u < ee && d < D) {
-                        if constexpr (DT == TCG_F32) v[u][c] = *reinterpret_cast<const float *>(xr + d * ES);
-                        else if constexpr (DT == TCG_BF16) v[u][c] = bf16_bits_to_f32(*reinterpret_cast<const uint16_t *>(xr + d * ES));
-                        else v[u][c] = f16_bits_to_f32(*reinterpret_cast<const uint16_t *>(xr + d * ES));
-                    }
+                    const int piece = lane + c * G;
+#pragma unroll
+                    for (int k = 0; k < VEC; ++k) v[u][c][k] = 0.f;
+                    if (e + u < ee && piece < n_pieces) Pc::load(xr + piece * PB, v[u][c]);
                 }
             }
 #pragma unroll
@@ -202,20 +203,26 @@ __global__ __launch_bounds__(kBlock) void spmm_gather_elem_kernel(
 #pragma unroll
             for (int u = 0; u < UNROLL; ++u)
 #pragma unroll
-                for (int c = 0; c < NCH; ++c) {
-                    if (HAS_W) acc[c] = fmaf(wc[u], v[u][c], acc[c]);
-                    else acc[c] += v[u][c];
-                }
+                for (int c = 0; c < NCH; ++c)
+#pragma unroll
+                    for (int k = 0; k < VEC; ++k) {
+                        if (HAS_W) acc[c][k] = fmaf(wc[u], v[u][c][k], acc[c][k]);
+                        else acc[c][k] += v[u][c][k];
+                    }
         }
     }
 
     const int32_t dst = seg_dst[seg];
 #pragma unroll
     for (int c = 0; c < NCH; ++c) {
-        const int d = lane + c * G;
-        if (d >= D) continue;
-        if (dst >= 0) partial[(int64_t)dst * partial_ld + d] = acc[c];
-        else store_elem(Y, (int64_t)row * ldy + d, y_dt, acc[c]);
+        const int piece = lane + c * G;
+        if (piece >= n_pieces) continue;
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) {
+            const int d = piece * VEC + k;
+            if (dst >= 0) partial[(int64_t)dst * partial_ld + d] = acc[c][k];
+            else store_elem(Y, (int64_t)row * ldy + d, y_dt, acc[c][k]);
+        }
     }
 }
 
@@ -318,28 +325,29 @@ bool dispatch_gather_w(const GatherArgs &a, int32_t n_chunks)
     return a.w ? dispatch_gather<DT, true>(a, n_chunks) : dispatch_gather<DT, false>(a, n_chunks);
 }
 
-template <int DT, int G, int NCH, bool HAS_W>
-void launch_elem(const GatherArgs &a)
+template <int DT, int PB, int G, int NCH, bool HAS_W>
+void launch_small(const GatherArgs &a, int32_t n_pieces)
 {
     constexpr int UNROLL = NCH == 1 ? 8 : (NCH == 2 ? 4 : 2);
     const tcg_meta *m = a.m;
     const unsigned grid = (unsigned)plan_grid(m->h_lane_tab, kBlock / G);
-    hipLaunchKernelGGL((spmm_gather_elem_kernel<DT, G, NCH, HAS_W, UNROLL>), dim3(grid), dim3(kBlock), 0, a.s,
+    hipLaunchKernelGGL((spmm_gather_small_kernel<DT, PB, G, NCH, HAS_W, UNROLL>), dim3(grid), dim3(kBlock), 0, a.s,
                        m->d_lane_tab, m->d_seg_row, m->d_seg_ebeg, m->d_seg_dst, m->d_row_ptr, m->d_col_idx, a.w,
-                       static_cast<const char *>(a.X), a.ldx * Elem<DT>::BYTES, a.D, a.Y, a.y_dt, a.ldy,
+                       static_cast<const char *>(a.X), a.ldx * Elem<DT>::BYTES, n_pieces, a.Y, a.y_dt, a.ldy,
                        m->d_partial, (int64_t)a.D, a.win_path, m->win_h);
 }
 
-template <int DT, bool HAS_W>
-bool dispatch_elem(const GatherArgs &a)
+template <int DT, int PB, bool HAS_W>
+bool dispatch_small(const GatherArgs &a)
 {
-    if (a.D <= 4) launch_elem<DT, 4, 1, HAS_W>(a);
-    else if (a.D <= 8) launch_elem<DT, 8, 1, HAS_W>(a);
-    else if (a.D <= 16) launch_elem<DT, 16, 1, HAS_W>(a);
-    else if (a.D <= 32) launch_elem<DT, 32, 1, HAS_W>(a);
-    else if (a.D <= 64) launch_elem<DT, 64, 1, HAS_W>(a);
-    else if (a.D <= 128) launch_elem<DT, 64, 2, HAS_W>(a);
-    else if (a.D <= 256) launch_elem<DT, 64, 4, HAS_W>(a);
+    const int32_t n = a.D / Piece<DT, PB>::VEC;
+    if (n <= 4) launch_small<DT, PB, 4, 1, HAS_W>(a, n);
+    else if (n <= 8) launch_small<DT, PB, 8, 1, HAS_W>(a, n);
+    else if (n <= 16) launch_small<DT, PB, 16, 1, HAS_W>(a, n);
+    else if (n <= 32) launch_small<DT, PB, 32, 1, HAS_W>(a, n);
+    else if (n <= 64) launch_small<DT, PB, 64, 1, HAS_W>(a, n);
+    else if (n <= 128) launch_small<DT, PB, 64, 2, HAS_W>(a, n);
+    else if (n <= 256) launch_small<DT, PB, 64, 4, HAS_W>(a, n);
     else return false;
     return true;
 }
@@ -347,7 +355,10 @@ bool dispatch_elem(const GatherArgs &a)
 template <int DT>
 bool dispatch_elem_w(const GatherArgs &a)
 {
-    return a.w ? dispatch_elem<DT, true>(a) : dispatch_elem<DT, false>(a);
+    if (small_piece_bytes(Elem<DT>::BYTES, a.D, a.ldx, a.ldx, a.X, a.X) == 4)
+        return a.w ? dispatch_small<DT, 4, true>(a) : dispatch_small<DT, 4, false>(a);
+    if constexpr (DT != TCG_F32) return a.w ? dispatch_small<DT, 2, true>(a) : dispatch_small<DT, 2, false>(a);
+    return false;
 }
 
 }  // namespace

@@ -10,7 +10,7 @@ import paper_2112_02052_amd as tcg
 import workloads as W
 from workloads.graphs import CSR
 
-from gpu_util import TOL_F32, TOL_MFMA, check_sgt, dev, norm_err, upload_csr, upload_x
+from gpu_util import TORCH_DT, TOL_F32, TOL_MFMA, check_sgt, dev, norm_err, upload_csr, upload_x
 
 pytestmark = pytest.mark.gpu
 
@@ -266,6 +266,31 @@ def test_spmm_tile_path_windows_with_many_edges():
         w = np.random.default_rng(blocks).standard_normal(g.nnz).astype(np.float32)
         run_spmm_case(g, X, "bf16", None, tcg.POLICY_TILE, TOL_F32)
         run_spmm_case(g, X, "bf16", w, tcg.POLICY_TILE, TOL_MFMA)
+
+
+@pytest.mark.parametrize("x_dtype", ["f32", "bf16", "f16"])
+@pytest.mark.parametrize("D", [1, 3, 10, 20, 50, 100, 150, 250])
+def test_rows_that_cannot_be_read_in_16_byte_pieces(x_dtype, D):
+    # Widths that are not a multiple of 16 bytes: fp32 rows go element by element, 16-bit rows in pairs
+    # when the width is even and element by element when it is odd or the rows start at odd elements.
+    c = W.make_config(3, n=2500, d=D)
+    g = c["csr"]
+    X = c["X"].astype(np.float16).astype(np.float32) if x_dtype == "f16" else W.round_to_bf16(c["X"])
+    w = np.random.default_rng(D).standard_normal(g.nnz).astype(np.float32)
+    run_spmm_case(g, X, x_dtype, w, tcg.POLICY_AUTO, TOL_F32)
+    run_spmm_case(g, X, x_dtype, None, tcg.POLICY_AUTO, TOL_F32, pad=1)       # odd leading dimension
+    run_sddmm_case(g, X, x_dtype, tcg.POLICY_AUTO, TOL_F32)
+    rp, ci = upload_csr(g)
+    meta = tcg.sgt_build(rp, ci, 16, 8)
+    big = torch.zeros((g.n_rows, D + 3), dtype=TORCH_DT[x_dtype], device=dev())
+    big[:, 1:D + 1] = upload_x(X, x_dtype)
+    Xs = big[:, 1:D + 1]                                                       # rows start at an odd element
+    out = tcg.sddmm(meta, Xs)
+    Y = tcg.spmm(meta, Xs)
+    torch.cuda.synchronize()
+    assert norm_err(out.cpu().numpy(), oracle.sddmm(g.row_ptr, g.col_idx, X)) <= TOL_F32
+    assert norm_err(Y.cpu().numpy(), oracle.spmm(g.row_ptr, g.col_idx, X, None)) <= TOL_F32
+    meta.free()
 
 
 def test_spmm_bf16_output():
