@@ -206,6 +206,35 @@ TCG_API int tcg_csr_transpose(int32_t n_rows, int32_t n_cols, int64_t nnz, const
  * d_out must not overlap d_in.                                                                        */
 TCG_API int tcg_edge_gather(int64_t n, const int32_t *d_perm, const float *d_in, float *d_out, void *stream);
 
+/* Row clustering before SGT.  The paper's related-work section calls row reordering orthogonal and
+ * complementary to SGT and names no algorithm; this is a cheap deterministic heuristic for graphs whose
+ * labelling scatters the members of a community (SGT only pays off when the rows of a window share
+ * neighbours).  For a square n x n pattern (nodes = rows = columns):
+ *   hash(v) = splitmix64 of (seed, v), nodes compared by (hash, id);
+ *   parent(v) = the smallest node of {v} + N(v);  root(v) = the fixed point of v -> parent(v);
+ *   label = root, then `refine` synchronous rounds of "most frequent label among the first 128 stored
+ *   neighbours" (ties to the smallest label id, rows without entries keep theirs);
+ *   d_perm[new] = old: the nodes sorted by (label, parent, id).
+ *   d_row_ptr   device int32[n + 1], d_col_idx device int32[nnz]   the pattern (borrowed)
+ *   refine      >= 0                   number of refinement rounds (2 is a good default)
+ *   d_perm      device int32[n]        result
+ * The result is deterministic.  Returns TCG_ECSR for a malformed pattern or a column outside [0, n).
+ * Blocks until the stream has finished (temporary buffers are released on return).                   */
+TCG_API int tcg_reorder_rows(int32_t n, int64_t nnz, const int32_t *d_row_ptr, const int32_t *d_col_idx,
+                     uint64_t seed, int32_t refine, int32_t *d_perm, void *stream);
+
+/* Symmetric permutation of a square CSR pattern: row i of the result is row d_perm[i] of the input and
+ * every column id c becomes the new position of node c.  Entries keep their order inside a row.
+ *   d_perm          device int32[n]       new -> old, a permutation of 0 .. n-1 (checked: TCG_EINVAL)
+ *   d_out_row_ptr   device int32[n + 1], d_out_col_idx device int32[nnz]   the result
+ *   d_edge_perm     device int32[nnz] or NULL   entry k of the result is entry d_edge_perm[k] of the input
+ *                                               (edge values follow with tcg_edge_gather)
+ * Features and outputs follow the same relabelling: X'[i] = X[d_perm[i]], Y'[i] = Y[d_perm[i]].
+ * Blocks until the stream has finished.                                                               */
+TCG_API int tcg_csr_permute(int32_t n, int64_t nnz, const int32_t *d_row_ptr, const int32_t *d_col_idx,
+                    const int32_t *d_perm, int32_t *d_out_row_ptr, int32_t *d_out_col_idx,
+                    int32_t *d_edge_perm, void *stream);
+
 /* Releases the metadata object and every device buffer it owns (NULL is a no-op).  The caller
  * must make sure no kernel using it is still running (its buffers go back to the library's cache
  * and may be handed to the next tcg_sgt_build).                                         */

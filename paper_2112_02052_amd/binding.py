@@ -15,7 +15,7 @@ POLICY_AUTO, POLICY_GATHER, POLICY_TILE = 0, 1, 2
 EXPORTED = ["tcg_sgt_build", "tcg_sgt_sizes", "tcg_sgt_export", "tcg_sgt_set_policy",
             "tcg_sgt_plan_stats", "tcg_spmm", "tcg_sddmm", "tcg_row_softmax", "tcg_sgt_free",
             "tcg_strerror", "tcg_release_cached_memory", "tcg_sddmm_pq", "tcg_row_softmax_backward",
-            "tcg_csr_transpose", "tcg_edge_gather", "tcg_attention"]
+            "tcg_csr_transpose", "tcg_edge_gather", "tcg_attention", "tcg_reorder_rows", "tcg_csr_permute"]
 
 _DTYPES = {torch.float32: TCG_F32, torch.bfloat16: TCG_BF16, torch.float16: TCG_F16}
 
@@ -65,6 +65,10 @@ def load_library():
     lib.tcg_row_softmax_backward.argtypes = [_vp, _vp, _vp, _vp, _vp]
     lib.tcg_csr_transpose.restype = ctypes.c_int
     lib.tcg_csr_transpose.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int64, _vp, _vp, _vp, _vp, _vp, _vp]
+    lib.tcg_reorder_rows.restype = ctypes.c_int
+    lib.tcg_reorder_rows.argtypes = [ctypes.c_int32, ctypes.c_int64, _vp, _vp, ctypes.c_uint64, ctypes.c_int32, _vp, _vp]
+    lib.tcg_csr_permute.restype = ctypes.c_int
+    lib.tcg_csr_permute.argtypes = [ctypes.c_int32, ctypes.c_int64, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
     lib.tcg_edge_gather.restype = ctypes.c_int
     lib.tcg_edge_gather.argtypes = [ctypes.c_int64, _vp, _vp, _vp, _vp]
     lib.tcg_attention.restype = ctypes.c_int
@@ -270,6 +274,41 @@ def edge_gather(perm, values, out=None):
         out = torch.empty_like(values)
     _check(load_library().tcg_edge_gather(perm.numel(), _ptr(perm), _ptr(values), _ptr(out), _stream()))
     return out
+
+
+def _square_csr(row_ptr, col_idx):
+    _need_cuda(row_ptr, col_idx)
+    if row_ptr.dtype != torch.int32 or col_idx.dtype != torch.int32:
+        raise ValueError("CSR arrays must be int32")
+    return row_ptr.contiguous(), col_idx.contiguous()
+
+
+def reorder_rows(row_ptr, col_idx, seed=0, refine=2):
+    """tcg_reorder_rows: perm (CUDA int32 [n], perm[new] = old) that puts rows with shared neighbours next
+    to each other."""
+    row_ptr, col_idx = _square_csr(row_ptr, col_idx)
+    n = row_ptr.numel() - 1
+    perm = torch.empty(n, dtype=torch.int32, device=row_ptr.device)
+    _check(load_library().tcg_reorder_rows(n, col_idx.numel(), _ptr(row_ptr), _ptr(col_idx), int(seed) & (2 ** 64 - 1),
+                                           int(refine), _ptr(perm), _stream()))
+    return perm
+
+
+def csr_permute(row_ptr, col_idx, perm, want_edge_perm=True):
+    """tcg_csr_permute: (row_ptr', col_idx', edge_perm or None) of the symmetrically relabelled pattern."""
+    row_ptr, col_idx = _square_csr(row_ptr, col_idx)
+    _need_cuda(perm)
+    n = row_ptr.numel() - 1
+    nnz = col_idx.numel()
+    if perm.dtype != torch.int32 or perm.numel() != n:
+        raise ValueError("perm must be int32 with one entry per node")
+    perm = perm.contiguous()
+    rp2 = torch.empty(n + 1, dtype=torch.int32, device=row_ptr.device)
+    ci2 = torch.empty(nnz, dtype=torch.int32, device=row_ptr.device)
+    ep = torch.empty(nnz, dtype=torch.int32, device=row_ptr.device) if want_edge_perm else None
+    _check(load_library().tcg_csr_permute(n, nnz, _ptr(row_ptr), _ptr(col_idx), _ptr(perm), _ptr(rp2), _ptr(ci2),
+                                          _ptr(ep), _stream()))
+    return rp2, ci2, ep
 
 
 def attention(meta, X, Y=None, scores=None, y_dtype=torch.float32):

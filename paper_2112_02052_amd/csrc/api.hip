@@ -169,6 +169,28 @@ int tcg_csr_transpose(int32_t n_rows, int32_t n_cols, int64_t nnz, const int32_t
                               static_cast<hipStream_t>(stream));
 }
 
+int tcg_reorder_rows(int32_t n, int64_t nnz, const int32_t *d_row_ptr, const int32_t *d_col_idx, uint64_t seed,
+                     int32_t refine, int32_t *d_perm, void *stream)
+{
+    if (n < 0 || nnz < 0 || refine < 0 || !d_row_ptr) return TCG_EINVAL;
+    if (n > 0 && !d_perm) return TCG_EINVAL;
+    if (nnz > 0 && !d_col_idx) return TCG_EINVAL;
+    if (nnz >= (int64_t)INT32_MAX || (int64_t)n + 1 >= (int64_t)INT32_MAX) return TCG_ERANGE;
+    return reorder_rows_impl(n, nnz, d_row_ptr, d_col_idx, seed, refine, d_perm, static_cast<hipStream_t>(stream));
+}
+
+int tcg_csr_permute(int32_t n, int64_t nnz, const int32_t *d_row_ptr, const int32_t *d_col_idx,
+                    const int32_t *d_perm, int32_t *d_out_row_ptr, int32_t *d_out_col_idx, int32_t *d_edge_perm,
+                    void *stream)
+{
+    if (n < 0 || nnz < 0 || !d_row_ptr || !d_out_row_ptr) return TCG_EINVAL;
+    if (n > 0 && !d_perm) return TCG_EINVAL;
+    if (nnz > 0 && (!d_col_idx || !d_out_col_idx)) return TCG_EINVAL;
+    if (nnz >= (int64_t)INT32_MAX || (int64_t)n + 1 >= (int64_t)INT32_MAX) return TCG_ERANGE;
+    return csr_permute_impl(n, nnz, d_row_ptr, d_col_idx, d_perm, d_out_row_ptr, d_out_col_idx, d_edge_perm,
+                            static_cast<hipStream_t>(stream));
+}
+
 int tcg_edge_gather(int64_t n, const int32_t *d_perm, const float *d_in, float *d_out, void *stream)
 {
     if (n < 0) return TCG_EINVAL;

@@ -137,11 +137,6 @@ __global__ __launch_bounds__(kThreads) void softmax_bwd_long_kernel(const int32_
     for (int32_t k = b + threadIdx.x; k < e; k += kThreads) dv[k] = p[k] * (dp[k] - dot);
 }
 
-struct PoolBuf {
-    void *p = nullptr;
-    ~PoolBuf() { if (p) pool_free(p); }
-};
-
 }  // namespace
 
 int row_softmax_backward_impl(const tcg_meta *m, const float *d_p, const float *d_dp, float *d_dv, hipStream_t s)
@@ -165,6 +160,50 @@ int edge_gather_impl(int64_t n, const int32_t *d_perm, const float *d_in, float 
     return launch_status("edge_gather_kernel");
 }
 
+size_t radix_sort_scratch_bytes(int64_t n)
+{
+    const int64_t n_blocks = ceil_div(n, kThreads);
+    const int64_t cnt_elems = (int64_t)kDigits * n_blocks + 1;
+    if (cnt_elems >= (int64_t)INT32_MAX) return 0;
+    const size_t arr = ((size_t)n * 4 + 255) & ~(size_t)255;
+    const size_t cnt_bytes = ((size_t)cnt_elems * 4 + 255) & ~(size_t)255;
+    return 2 * arr + cnt_bytes + (size_t)scan_workspace_elems(cnt_elems) * 4;
+}
+
+int radix_sort_pairs(const int32_t *d_keys_in, const int32_t *d_vals_in, int64_t n, int bits, int32_t *d_keys_out,
+                     int32_t *d_vals_out, void *d_scratch, hipStream_t s)
+{
+    if (n == 0) return TCG_OK;
+    const int passes = (bits + 3) / 4;
+    const int64_t n_blocks = ceil_div(n, kThreads);
+    const int64_t cnt_elems = (int64_t)kDigits * n_blocks + 1;
+    const size_t arr = ((size_t)n * 4 + 255) & ~(size_t)255;
+    const size_t cnt_bytes = ((size_t)cnt_elems * 4 + 255) & ~(size_t)255;
+    char *base = static_cast<char *>(d_scratch);
+    int32_t *keys_b = reinterpret_cast<int32_t *>(base);
+    int32_t *vals_b = reinterpret_cast<int32_t *>(base + arr);
+    int32_t *block_cnt = reinterpret_cast<int32_t *>(base + 2 * arr);
+    int32_t *scan_work = reinterpret_cast<int32_t *>(base + 2 * arr + cnt_bytes);
+
+    const int32_t *kin = d_keys_in;
+    const int32_t *vin = d_vals_in;
+    for (int pass = 0; pass < passes; ++pass) {
+        // Choose the outputs so that the last pass lands in the caller's arrays.
+        const bool to_out = ((passes - 1 - pass) % 2) == 0;
+        int32_t *kout = to_out ? d_keys_out : keys_b;
+        int32_t *vout = to_out ? d_vals_out : vals_b;
+        hipLaunchKernelGGL(radix_count_kernel, dim3((unsigned)n_blocks), dim3(kThreads), 0, s, kin, n, 4 * pass,
+                           block_cnt, n_blocks);
+        TCG_TRY(exclusive_scan_i32(block_cnt, block_cnt, cnt_elems - 1, scan_work, s));
+        hipLaunchKernelGGL(radix_scatter_kernel, dim3((unsigned)n_blocks), dim3(kThreads), 0, s, kin, vin, n, 4 * pass,
+                           block_cnt, n_blocks, kout, vout);
+        TCG_TRY(launch_status("radix kernels"));
+        kin = kout;
+        vin = vout;
+    }
+    return TCG_OK;
+}
+
 int csr_transpose_impl(int32_t n_rows, int32_t n_cols, int64_t nnz, const int32_t *d_row_ptr,
                        const int32_t *d_col_idx, int32_t *d_out_row_ptr, int32_t *d_out_col_idx, int32_t *d_perm,
                        hipStream_t s)
@@ -176,41 +215,17 @@ int csr_transpose_impl(int32_t n_rows, int32_t n_cols, int64_t nnz, const int32_
     }
     int bits = 1;
     while (bits < 31 && (1ll << bits) < (int64_t)n_cols) ++bits;
-    const int passes = (bits + 3) / 4;
     const int64_t n_blocks = ceil_div(nnz, kThreads);
-    const int64_t cnt_elems = (int64_t)kDigits * n_blocks + 1;
-    if (cnt_elems >= (int64_t)INT32_MAX) return TCG_ERANGE;
-    const int64_t scan_elems = scan_workspace_elems(cnt_elems);
+    if (radix_sort_scratch_bytes(nnz) == 0) return TCG_ERANGE;
 
-    // Scratch: two (key, value) ping-pong pairs, the digit counts and the scan workspace.
+    // Scratch: sorted keys plus the sort's own workspace; the caller's perm array receives the values.
     const size_t arr = ((size_t)nnz * 4 + 255) & ~(size_t)255;
-    const size_t cnt_bytes = ((size_t)cnt_elems * 4 + 255) & ~(size_t)255;
     PoolBuf buf;
-    TCG_TRY(pool_alloc(&buf.p, 3 * arr + cnt_bytes + (size_t)scan_elems * 4));
+    TCG_TRY(pool_alloc(&buf.p, arr + radix_sort_scratch_bytes(nnz)));
     char *base = static_cast<char *>(buf.p);
-    int32_t *keys_a = reinterpret_cast<int32_t *>(base);
-    int32_t *keys_b = reinterpret_cast<int32_t *>(base + arr);
-    int32_t *vals_b = reinterpret_cast<int32_t *>(base + 2 * arr);
-    int32_t *block_cnt = reinterpret_cast<int32_t *>(base + 3 * arr);
-    int32_t *scan_work = reinterpret_cast<int32_t *>(base + 3 * arr + cnt_bytes);
-    int32_t *vals_a = d_perm;             // the caller's perm array doubles as one value buffer
-
-    const int32_t *kin = d_col_idx;
-    const int32_t *vin = nullptr;
-    for (int pass = 0; pass < passes; ++pass) {
-        // Choose the outputs so that the last pass lands in (keys_a, d_perm).
-        const bool to_a = ((passes - 1 - pass) % 2) == 0;
-        int32_t *kout = to_a ? keys_a : keys_b;
-        int32_t *vout = to_a ? vals_a : vals_b;
-        hipLaunchKernelGGL(radix_count_kernel, dim3((unsigned)n_blocks), dim3(kThreads), 0, s, kin, nnz, 4 * pass,
-                           block_cnt, n_blocks);
-        TCG_TRY(exclusive_scan_i32(block_cnt, block_cnt, cnt_elems - 1, scan_work, s));
-        hipLaunchKernelGGL(radix_scatter_kernel, dim3((unsigned)n_blocks), dim3(kThreads), 0, s, kin, vin, nnz, 4 * pass,
-                           block_cnt, n_blocks, kout, vout);
-        TCG_TRY(launch_status("radix kernels"));
-        kin = kout;
-        vin = vout;
-    }
+    int32_t *keys_sorted = reinterpret_cast<int32_t *>(base);
+    TCG_TRY(radix_sort_pairs(d_col_idx, nullptr, nnz, bits, keys_sorted, d_perm, base + arr, s));
+    const int32_t *kin = keys_sorted;
     hipLaunchKernelGGL(transpose_finish_kernel, dim3((unsigned)n_blocks), dim3(kThreads), 0, s, n_rows, n_cols, nnz,
                        d_row_ptr, kin, d_perm, d_out_row_ptr, d_out_col_idx);
     TCG_TRY(launch_status("transpose_finish_kernel"));

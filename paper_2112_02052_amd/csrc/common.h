@@ -112,6 +112,12 @@ inline int64_t plan_grid(const int32_t *h_lane_tab, int groups_per_block)
 
 // Exclusive prefix sum of n int32 values on the device; out may alias in.  out has n + 1
 // entries: out[n] is the total (sums are computed in int32; callers bound the total beforehand).
+// A pooled device buffer that goes back to the pool when the scope ends (the stream must be idle by then).
+struct PoolBuf {
+    void *p = nullptr;
+    ~PoolBuf() { if (p) pool_free(p); }
+};
+
 // d_work: device scratch of scan_workspace_elems(n) int32.
 int64_t scan_workspace_elems(int64_t n);
 int exclusive_scan_i32(const int32_t *d_in, int32_t *d_out, int64_t n, int32_t *d_work, hipStream_t s);
@@ -142,6 +148,20 @@ int csr_transpose_impl(int32_t n_rows, int32_t n_cols, int64_t nnz, const int32_
                        const int32_t *d_col_idx, int32_t *d_out_row_ptr, int32_t *d_out_col_idx, int32_t *d_perm,
                        hipStream_t s);
 int edge_gather_impl(int64_t n, const int32_t *d_perm, const float *d_in, float *d_out, hipStream_t s);
+// Stable least-significant-digit radix sort (4 bits per pass) of n (key, value) pairs by key, keys in
+// [0, 2^bits).  d_vals_in == nullptr stands for the values 0 .. n-1.  The outputs must not overlap the
+// inputs.  d_scratch: device
+// memory of radix_sort_scratch_bytes(n) bytes (0 = n too large).  Asynchronous on s.
+size_t radix_sort_scratch_bytes(int64_t n);
+int radix_sort_pairs(const int32_t *d_keys_in, const int32_t *d_vals_in, int64_t n, int bits, int32_t *d_keys_out,
+                     int32_t *d_vals_out, void *d_scratch, hipStream_t s);
+
+// reorder.hip
+int reorder_rows_impl(int32_t n, int64_t nnz, const int32_t *d_row_ptr, const int32_t *d_col_idx, uint64_t seed,
+                      int32_t refine, int32_t *d_perm, hipStream_t s);
+int csr_permute_impl(int32_t n, int64_t nnz, const int32_t *d_row_ptr, const int32_t *d_col_idx,
+                     const int32_t *d_perm, int32_t *d_out_row_ptr, int32_t *d_out_col_idx, int32_t *d_edge_perm,
+                     hipStream_t s);
 int row_softmax_impl(const tcg_meta *m, const float *d_in, float *d_out, hipStream_t s);
 
 // spmm_tile.hip: can the condensed-tile kernels take this operand?
