@@ -16,6 +16,13 @@ constexpr float kDefaultMinReuse = 2.0f;
 constexpr int kXcds = 8;              // accelerator dies of an MI355X; workgroup i is dispatched to die i % 8
 constexpr int kPartialInitD = 128;   // the build reserves partial-sum scratch for feature widths up to this
 constexpr int kTileMaxUnique = 512;  // AUTO never sends a window with more unique columns to the tile path
+// Values of the per-window path flag: 0 = gather path; tile path with the window's edges kept in
+// registers (at most kTileFewEdges of them, or more unique columns than kTileMaxUnique under a forced
+// tile policy); tile path with the window's whole condensed adjacency built once in LDS.
+constexpr uint8_t kTileFew = 1, kTileMany = 2;
+constexpr int kTileFewEdges = 512;
+// SpMM sends a class to the MFMA kernels only from this feature width on (measured crossovers).
+constexpr int kTileMinWidthFew = 64, kTileMinWidthMany = 128;
 
 // Records the text of a failing HIP call for tcg_strerror (thread local).
 void set_hip_error(hipError_t e, const char *what);
@@ -209,5 +216,6 @@ struct tcg_meta {
     tcg_policy policy = TCG_POLICY_AUTO;
     float min_reuse = 0.f;
     uint8_t *d_win_path = nullptr;        // [n_win] 1 = condensed-tile path
-    int64_t n_tile_win = 0, nnz_tile = 0;
+    int64_t n_tile_win = 0, nnz_tile = 0;   // windows on the tile path (both classes) and their edges
+    int64_t n_tile_many = 0, max_unique_many = 0;   // class kTileMany: count, widest window
 };

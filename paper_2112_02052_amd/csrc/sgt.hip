@@ -587,7 +587,7 @@ __global__ __launch_bounds__(256) void choose_path_kernel(int32_t n_rows, int32_
                                                           uint8_t *win_path, unsigned long long *counts)
 {
     const int64_t w = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    unsigned long long tiles = 0, tile_win = 0, tile_nnz = 0;
+    unsigned long long tiles = 0, tile_win = 0, tile_nnz = 0, tile_many = 0;
     if (w < n_win) {
         int32_t lo, hi;
         window_edge_range(rp, n_rows, win_h, w, &lo, &hi);
@@ -598,22 +598,29 @@ __global__ __launch_bounds__(256) void choose_path_kernel(int32_t n_rows, int32_
         bool tile = false;
         if (policy == TCG_POLICY_TILE) tile = uw > 0;
         else if (policy == TCG_POLICY_AUTO)
-            // Windows with shared neighbours, but not hub windows: a tile kernel workgroup walks its
-            // window's edges once per 32-column chunk, which only pays for compact windows.
+            // Windows with shared neighbours, but not hub windows: the tile kernels keep a window's
+            // condensed columns (or its whole condensed adjacency) in LDS, which needs compact windows.
             tile = win_h == 16 && uw > 0 && uw <= kTileMaxUnique && (float)nnz_w >= min_reuse * (float)uw;
-        win_path[w] = tile ? 1 : 0;
+        const bool many = tile && nnz_w > kTileFewEdges && uw <= kTileMaxUnique;
+        win_path[w] = tile ? (many ? kTileMany : kTileFew) : 0;
         if (tile) {
             tile_win = 1;
             tile_nnz = (unsigned long long)nnz_w;
+        }
+        if (many) {
+            tile_many = 1;
+            atomicMax(&counts[4], (unsigned long long)uw);
         }
     }
     tiles = wave_sum_u64(tiles);
     tile_win = wave_sum_u64(tile_win);
     tile_nnz = wave_sum_u64(tile_nnz);
+    tile_many = wave_sum_u64(tile_many);
     if ((threadIdx.x & (kWave - 1)) == 0) {
         if (tiles) atomicAdd(&counts[0], tiles);
         if (tile_win) atomicAdd(&counts[1], tile_win);
         if (tile_nnz) atomicAdd(&counts[2], tile_nnz);
+        if (tile_many) atomicAdd(&counts[3], tile_many);
     }
 }
 
@@ -664,15 +671,16 @@ int choose_paths(tcg_meta *m, tcg_policy policy, float min_reuse, hipStream_t s)
 {
     if (policy == TCG_POLICY_TILE && m->win_h != 16) return TCG_EINVAL;
     if (min_reuse <= 0.f) min_reuse = kDefaultMinReuse;
-    unsigned long long *counts = m->d_counters;   // [0] tiles, [1] tile-path windows, [2] their edges
-    TCG_HIP(hipMemsetAsync(counts, 0, 3 * sizeof(unsigned long long), s));
+    // [0] tiles, [1] tile-path windows, [2] their edges, [3] windows of class kTileMany, [4] their widest
+    unsigned long long *counts = m->d_counters;
+    TCG_HIP(hipMemsetAsync(counts, 0, 5 * sizeof(unsigned long long), s));
     if (m->n_win > 0) {
         hipLaunchKernelGGL(choose_path_kernel, dim3((unsigned)ceil_div(m->n_win, 256)), dim3(256), 0, s,
                            m->n_rows, m->win_h, m->tile_w, m->n_win, m->d_row_ptr, m->d_win_unique_ptr,
                            (int)policy, min_reuse, m->d_win_partition, m->d_win_path, counts);
         TCG_TRY(launch_status("choose_path_kernel"));
     }
-    unsigned long long h[3];
+    unsigned long long h[5];
     TCG_HIP(hipMemcpyAsync(h, counts, sizeof(h), hipMemcpyDeviceToHost, s));
     TCG_HIP(hipStreamSynchronize(s));
     m->policy = policy;
@@ -680,6 +688,8 @@ int choose_paths(tcg_meta *m, tcg_policy policy, float min_reuse, hipStream_t s)
     m->total_tiles = (int64_t)h[0];
     m->n_tile_win = (int64_t)h[1];
     m->nnz_tile = (int64_t)h[2];
+    m->n_tile_many = (int64_t)h[3];
+    m->max_unique_many = (int64_t)h[4];
     return TCG_OK;
 }
 

@@ -22,7 +22,7 @@ namespace tcg {
 
 // spmm_tile.hip
 int spmm_tile_launch(tcg_meta *m, const void *d_X, tcg_dtype x_dt, int32_t D, int64_t ldx, const float *d_w,
-                     void *d_Y, tcg_dtype y_dt, int64_t ldy, hipStream_t s);
+                     void *d_Y, tcg_dtype y_dt, int64_t ldy, int tile_mask, hipStream_t s);
 
 namespace {
 
@@ -35,14 +35,14 @@ __global__ __launch_bounds__(kBlock) void spmm_gather_kernel(
     const int32_t *__restrict__ col_idx, const float *__restrict__ w, const char *__restrict__ X,
     int64_t ldx_bytes, int32_t n_chunks, int32_t D, void *__restrict__ Y, int y_dt, int64_t ldy,
     float *__restrict__ partial, int64_t partial_ld, const uint8_t *__restrict__ win_path, int32_t win_h,
-    int y_vec)
+    int tile_mask, int y_vec)
 {
     constexpr int VEC = Elem<DT>::VEC;
     const int lane = threadIdx.x % G;
     const int64_t seg = plan_segment(lane_tab, kBlock / G, threadIdx.x / G);
     if (seg < 0) return;
     const int32_t row = seg_row[seg];
-    if (win_path != nullptr && win_path[row / win_h]) return;
+    if (win_path != nullptr && ((tile_mask >> win_path[row / win_h]) & 1)) return;
     const int32_t eb = seg_ebeg[seg];
     const int32_t ee = min(eb + kSegLen, row_ptr[row + 1]);
 
@@ -144,7 +144,7 @@ __global__ __launch_bounds__(kBlock) void spmm_gather_small_kernel(
     const int32_t *__restrict__ seg_dst, const int32_t *__restrict__ row_ptr,
     const int32_t *__restrict__ col_idx, const float *__restrict__ w, const char *__restrict__ X,
     int64_t ldx_bytes, int32_t n_pieces, void *__restrict__ Y, int y_dt, int64_t ldy, float *__restrict__ partial,
-    int64_t partial_ld, const uint8_t *__restrict__ win_path, int32_t win_h)
+    int64_t partial_ld, const uint8_t *__restrict__ win_path, int32_t win_h, int tile_mask)
 {
     using Pc = Piece<DT, PB>;
     constexpr int VEC = Pc::VEC;
@@ -152,7 +152,7 @@ __global__ __launch_bounds__(kBlock) void spmm_gather_small_kernel(
     const int64_t seg = plan_segment(lane_tab, kBlock / G, threadIdx.x / G);
     if (seg < 0) return;
     const int32_t row = seg_row[seg];
-    if (win_path != nullptr && win_path[row / win_h]) return;
+    if (win_path != nullptr && ((tile_mask >> win_path[row / win_h]) & 1)) return;
     const int32_t eb = seg_ebeg[seg];
     const int32_t ee = min(eb + kSegLen, row_ptr[row + 1]);
 
@@ -233,13 +233,13 @@ __global__ __launch_bounds__(kBlock) void spmm_gather_generic_kernel(
     const int32_t *__restrict__ seg_dst, const int32_t *__restrict__ row_ptr,
     const int32_t *__restrict__ col_idx, const float *__restrict__ w, const void *__restrict__ X, int x_dt,
     int64_t ldx, int32_t D, void *__restrict__ Y, int y_dt, int64_t ldy, float *__restrict__ partial,
-    int64_t partial_ld, const uint8_t *__restrict__ win_path, int32_t win_h)
+    int64_t partial_ld, const uint8_t *__restrict__ win_path, int32_t win_h, int tile_mask)
 {
     const int lane = threadIdx.x & (kWave - 1);
     const int64_t seg = plan_segment(lane_tab, kBlock / kWave, threadIdx.x >> 6);
     if (seg < 0) return;
     const int32_t row = seg_row[seg];
-    if (win_path != nullptr && win_path[row / win_h]) return;
+    if (win_path != nullptr && ((tile_mask >> win_path[row / win_h]) & 1)) return;
     const int32_t eb = seg_ebeg[seg];
     const int32_t ee = min(eb + kSegLen, row_ptr[row + 1]);
     const int32_t dst = seg_dst[seg];
@@ -258,11 +258,11 @@ __global__ __launch_bounds__(kBlock) void spmm_gather_generic_kernel(
 __global__ __launch_bounds__(kBlock) void spmm_reduce_long_kernel(
     int64_t n_long, const int32_t *__restrict__ long_row, const int32_t *__restrict__ long_slot_ptr,
     const float *__restrict__ partial, int64_t partial_ld, int32_t D, void *__restrict__ Y, int y_dt,
-    int64_t ldy, const uint8_t *__restrict__ win_path, int32_t win_h)
+    int64_t ldy, const uint8_t *__restrict__ win_path, int32_t win_h, int tile_mask)
 {
     const int64_t li = blockIdx.x;
     const int32_t row = long_row[li];
-    if (win_path != nullptr && win_path[row / win_h]) return;
+    if (win_path != nullptr && ((tile_mask >> win_path[row / win_h]) & 1)) return;
     const int32_t s0 = long_slot_ptr[li], s1 = long_slot_ptr[li + 1];
     for (int32_t d = threadIdx.x; d < D; d += kBlock) {
         float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
@@ -288,6 +288,7 @@ struct GatherArgs {
     int y_dt;
     int64_t ldy;
     const uint8_t *win_path;
+    int tile_mask;      // bit c set: windows of path class c are handled by the tile kernels
     hipStream_t s;
 };
 
@@ -302,7 +303,7 @@ void launch_gather(const GatherArgs &a, int32_t n_chunks)
     hipLaunchKernelGGL((spmm_gather_kernel<DT, G, NCH, HAS_W, UNROLL>), dim3(grid), dim3(kBlock), 0, a.s,
                        m->d_lane_tab, m->d_seg_row, m->d_seg_ebeg, m->d_seg_dst, m->d_row_ptr, m->d_col_idx, a.w,
                        static_cast<const char *>(a.X), a.ldx * Elem<DT>::BYTES, n_chunks, a.D, a.Y, a.y_dt,
-                       a.ldy, m->d_partial, (int64_t)a.D, a.win_path, m->win_h, y_vec);
+                       a.ldy, m->d_partial, (int64_t)a.D, a.win_path, m->win_h, a.tile_mask, y_vec);
 }
 
 template <int DT, bool HAS_W>
@@ -334,7 +335,7 @@ void launch_small(const GatherArgs &a, int32_t n_pieces)
     hipLaunchKernelGGL((spmm_gather_small_kernel<DT, PB, G, NCH, HAS_W, UNROLL>), dim3(grid), dim3(kBlock), 0, a.s,
                        m->d_lane_tab, m->d_seg_row, m->d_seg_ebeg, m->d_seg_dst, m->d_row_ptr, m->d_col_idx, a.w,
                        static_cast<const char *>(a.X), a.ldx * Elem<DT>::BYTES, n_pieces, a.Y, a.y_dt, a.ldy,
-                       m->d_partial, (int64_t)a.D, a.win_path, m->win_h);
+                       m->d_partial, (int64_t)a.D, a.win_path, m->win_h, a.tile_mask);
 }
 
 template <int DT, int PB, bool HAS_W>
@@ -383,12 +384,27 @@ int spmm_impl(tcg_meta *m, const void *d_X, tcg_dtype x_dt, int32_t D, int64_t l
         m->partial_owned = true;
     }
 
-    const bool use_tiles = m->n_tile_win > 0 && m->win_h == 16 && tile_path_supports(x_dt, D, ldx, d_X);
+    // Which classes of tile-path windows really go to the MFMA kernels depends on the feature width, which
+    // the plan does not know: measured on MI355X (the calibration tool's sweeps), narrow rows are gathered
+    // faster than they are staged through LDS, and building a window's whole condensed adjacency in LDS
+    // pays only for wider rows still.  A forced tile policy is taken literally.
+    int tile_mask = 0;
+    if (m->n_tile_win > 0 && m->win_h == 16 && tile_path_supports(x_dt, D, ldx, d_X)) {
+        const bool forced = m->policy == TCG_POLICY_TILE;
+        if (forced || D >= kTileMinWidthFew) tile_mask |= 1 << kTileFew;
+        if (forced || D >= kTileMinWidthMany) tile_mask |= 1 << kTileMany;
+    }
+    const int64_t n_few = m->n_tile_win - m->n_tile_many;
+    const bool few = ((tile_mask >> kTileFew) & 1) || n_few == 0;            // class handled, or empty
+    const bool many = ((tile_mask >> kTileMany) & 1) || m->n_tile_many == 0;
+    if (n_few == 0) tile_mask &= ~(1 << kTileFew);
+    if (m->n_tile_many == 0) tile_mask &= ~(1 << kTileMany);
+    const bool use_tiles = tile_mask != 0;
     const uint8_t *win_path = use_tiles ? m->d_win_path : nullptr;
-    if (use_tiles) TCG_TRY(spmm_tile_launch(m, d_X, x_dt, D, ldx, d_w, d_Y, y_dt, ldy, s));
-    if (use_tiles && m->nnz_tile == m->nnz && m->n_tile_win == m->n_win) return TCG_OK;  // nothing left
+    if (use_tiles) TCG_TRY(spmm_tile_launch(m, d_X, x_dt, D, ldx, d_w, d_Y, y_dt, ldy, tile_mask, s));
+    if (few && many && m->nnz_tile == m->nnz && m->n_tile_win == m->n_win) return TCG_OK;  // nothing left
 
-    GatherArgs a{m, d_X, ldx, D, d_w, d_Y, (int)y_dt, ldy, win_path, s};
+    GatherArgs a{m, d_X, ldx, D, d_w, d_Y, (int)y_dt, ldy, win_path, tile_mask, s};
     const int es = dtype_size(x_dt);
     const bool vec_ok = ((int64_t)D * es) % 16 == 0 && (ldx * es) % 16 == 0 && ldx * es < (1ll << 32) &&
                         (reinterpret_cast<uintptr_t>(d_X) & 15) == 0;
@@ -410,18 +426,18 @@ int spmm_impl(tcg_meta *m, const void *d_X, tcg_dtype x_dt, int32_t D, int64_t l
             hipLaunchKernelGGL(spmm_gather_generic_kernel<true>, dim3(grid), dim3(kBlock), 0, s, m->d_lane_tab,
                                m->d_seg_row, m->d_seg_ebeg, m->d_seg_dst, m->d_row_ptr, m->d_col_idx, d_w, d_X,
                                (int)x_dt, ldx, D, d_Y, (int)y_dt, ldy, m->d_partial, (int64_t)D, win_path,
-                               m->win_h);
+                               m->win_h, tile_mask);
         else
             hipLaunchKernelGGL(spmm_gather_generic_kernel<false>, dim3(grid), dim3(kBlock), 0, s, m->d_lane_tab,
                                m->d_seg_row, m->d_seg_ebeg, m->d_seg_dst, m->d_row_ptr, m->d_col_idx, d_w, d_X,
                                (int)x_dt, ldx, D, d_Y, (int)y_dt, ldy, m->d_partial, (int64_t)D, win_path,
-                               m->win_h);
+                               m->win_h, tile_mask);
     }
     TCG_TRY(launch_status("spmm_gather_kernel"));
     if (m->n_long > 0) {
         hipLaunchKernelGGL(spmm_reduce_long_kernel, dim3((unsigned)m->n_long), dim3(kBlock), 0, s, m->n_long,
                            m->d_long_row, m->d_long_slot_ptr, m->d_partial, (int64_t)D, D, d_Y, (int)y_dt, ldy,
-                           win_path, m->win_h);
+                           win_path, m->win_h, tile_mask);
         TCG_TRY(launch_status("spmm_reduce_long_kernel"));
     }
     return TCG_OK;

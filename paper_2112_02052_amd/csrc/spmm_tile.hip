@@ -91,26 +91,35 @@ __device__ __forceinline__ f32x4 mfma16k16(const uint2 &a, const uint2 &b, f32x4
 }
 
 // NS: 16-column slices of D per wavefront; a window with D > 16 * NS is shared by n_dparts wavefronts.
-template <int DT, bool HAS_W, int NS>
+// FULL_A = false serves the windows of class kTileFew (at most kTileFewEdges edges, kept in registers;
+// the 16 x KW slice of the condensed adjacency is rebuilt for every chunk).  FULL_A = true serves class
+// kTileMany: the whole 16 x U_w condensed adjacency of the window is built once in (dynamic) LDS with a
+// single pass over the window's edges -- dense windows would otherwise walk thousands of edges per chunk --
+// and every chunk reads its slice from there; a_stride = its row stride in floats.
+template <int DT, bool HAS_W, int NS, bool FULL_A>
 __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(3))) void spmm_tile_wave_kernel(
     int32_t n_rows, int64_t n_win, const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ edge_to_col,
     const int32_t *__restrict__ win_unique_ptr, const int32_t *__restrict__ col_to_row,
     const uint8_t *__restrict__ win_path, const float *__restrict__ w, const char *__restrict__ X,
-    int64_t ldx_bytes, int32_t D, int32_t n_dparts, void *__restrict__ Y, int y_dt, int64_t ldy, bool y_vec)
+    int64_t ldx_bytes, int32_t D, int32_t n_dparts, void *__restrict__ Y, int y_dt, int64_t ldy, bool y_vec,
+    int32_t a_stride)
 {
+    extern __shared__ __align__(16) float a_full[];              // FULL_A: 16 x a_stride
     constexpr int PP = NS / 2;                                    // 16-byte pieces of a chunk per lane
     // Staged row stride: an odd multiple of 32 bytes, so the 8 rows that half a wavefront touches in
     // a transposing read start in 8 different groups of 8 LDS banks.
     constexpr int32_t rs = NS * 32 + 32;
     __shared__ __align__(16) char xs[KW * rs];
-    __shared__ __align__(16) float a32[16 * kAStrideW];
+    __shared__ __align__(16) float a_slice[FULL_A ? 4 : 16 * kAStrideW];
     __shared__ int32_t s_rp[17];
+    float *a32 = FULL_A ? a_full : a_slice;
+    const int32_t as = FULL_A ? a_stride : kAStrideW;
 
     // Workgroup i runs on die i % kXcds: every die gets a contiguous range of windows.
     const int64_t per_die = (n_win + kXcds - 1) / kXcds;
     const int64_t j = blockIdx.x / kXcds;
     const int64_t win = (int64_t)(blockIdx.x % kXcds) * per_die + j / n_dparts;
-    if (j / n_dparts >= per_die || win >= n_win || !win_path[win]) return;
+    if (j / n_dparts >= per_die || win >= n_win || win_path[win] != (FULL_A ? kTileMany : kTileFew)) return;
     const int32_t d0 = (int32_t)(j % n_dparts) * (NS * 16);       // first feature column of this part
     const int32_t Dp = min(NS * 16, D - d0);
 
@@ -149,25 +158,56 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(3))) void
     };
     fetch(nid_cur);
 
-    // A window of at most EPT * 64 edges keeps them in registers: (A-slice row offset << 16 | condensed
-    // column) and the value.  Larger windows re-read their edges for every chunk.
-    constexpr int EPT = 8;
+    // !FULL_A: a window of at most EPT * 64 edges keeps them in registers: (A-slice row offset << 16 |
+    // condensed column) and the value.  (Windows forced onto this path with more edges re-read them for
+    // every chunk.)
+    constexpr int EPT = FULL_A ? 1 : kTileFewEdges / kWave;
     const bool edges_in_regs = hi - lo <= EPT * kWave;
     int32_t e_code[EPT];
     float e_val[EPT];
+    if constexpr (!FULL_A) {
 #pragma unroll
-    for (int q = 0; q < EPT; ++q) {
-        const int32_t e = lo + lane + q * kWave;
-        e_code[q] = -1;
-        e_val[q] = 0.f;
-        if (edges_in_regs && e < hi) {
-            int r = 0;
+        for (int q = 0; q < EPT; ++q) {
+            const int32_t e = lo + lane + q * kWave;
+            e_code[q] = -1;
+            e_val[q] = 0.f;
+            if (edges_in_regs && e < hi) {
+                int r = 0;
 #pragma unroll
-            for (int step = 8; step > 0; step >>= 1)
-                if (s_rp[r + step] <= e) r += step;
-            e_code[q] = (r * kAStrideW) << 16 | edge_to_col[e];     // condensed column < kTileMaxUnique
-            if (HAS_W) e_val[q] = w[e];
+                for (int step = 8; step > 0; step >>= 1)
+                    if (s_rp[r + step] <= e) r += step;
+                e_code[q] = (r * kAStrideW) << 16 | edge_to_col[e];     // condensed column < kTileMaxUnique
+                if (HAS_W) e_val[q] = w[e];
+            }
         }
+    } else {
+        // InitSparse for the whole window: clear 16 x a_stride floats, then one pass over the edges.
+        for (int32_t i = lane * 4; i < 16 * as; i += kWave * 4)
+            *reinterpret_cast<float4 *>(a32 + i) = make_float4(0.f, 0.f, 0.f, 0.f);
+        wave_lds_order();
+        // batches of 8 edges per lane: the loads of a batch are issued together (clamped, always valid)
+        for (int32_t e0 = lo; e0 < hi; e0 += 8 * kWave) {
+            int32_t cc[8];
+            float vv[8];
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                const int32_t e = min(e0 + lane + q * kWave, hi - 1);
+                cc[q] = edge_to_col[e];
+                vv[q] = HAS_W ? w[e] : 1.f;
+            }
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                const int32_t e = e0 + lane + q * kWave;
+                if (e < hi) {
+                    int r = 0;
+#pragma unroll
+                    for (int step = 8; step > 0; step >>= 1)
+                        if (s_rp[r + step] <= e) r += step;
+                    atomicAdd(&a32[r * as + cc[q]], vv[q]);
+                }
+            }
+        }
+        wave_lds_order();
     }
 
     f32x4 acc[NS];
@@ -175,7 +215,7 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(3))) void
     for (int i = 0; i < NS; ++i) acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     const int g = lane >> 4, n_in = lane & 15;
-    const float *a_src = a32 + n_in * kAStrideW + 4 * g;          // A: row n_in, k = 4g .. 4g+3
+    const float *a_src = a32 + n_in * as + 4 * g;                 // A: row n_in, k = 4g .. 4g+3 (+ k0 if FULL_A)
     // B: lane j of a 16-lane group addresses row 4g + j / 4, 8-byte chunk j % 4 of a slice
     const char *b_src = xs + (4 * g + (n_in >> 2)) * rs + (n_in & 3) * 8;
 
@@ -189,31 +229,33 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(3))) void
             fetch(nid_cur);
             nid_nxt = k0 + 2 * KW + kk < U ? col_to_row[u0 + k0 + 2 * KW + kk] : -1;
         }
-        // InitSparse
+        if constexpr (!FULL_A) {
+            // InitSparse
 #pragma unroll
-        for (int i = 0; i < 5; ++i) a32[lane + i * kWave] = 0.f;
-        wave_lds_order();
-        if (edges_in_regs) {
+            for (int i = 0; i < 5; ++i) a32[lane + i * kWave] = 0.f;
+            wave_lds_order();
+            if (edges_in_regs) {
 #pragma unroll
-            for (int q = 0; q < EPT; ++q) {
-                const int32_t cc = (e_code[q] & 0xFFFF) - k0;
-                if (e_code[q] >= 0 && cc >= 0 && cc < KW) atomicAdd(&a32[(e_code[q] >> 16) + cc], HAS_W ? e_val[q] : 1.f);
-            }
-        } else {
-            for (int32_t e = lo + lane; e < hi; e += kWave) {
-                int32_t cc = edge_to_col[e] - k0;
-                if (cc >= 0 && cc < KW) {
-                    int r = 0;
+                for (int q = 0; q < EPT; ++q) {
+                    const int32_t cc = (e_code[q] & 0xFFFF) - k0;
+                    if (e_code[q] >= 0 && cc >= 0 && cc < KW) atomicAdd(&a32[(e_code[q] >> 16) + cc], HAS_W ? e_val[q] : 1.f);
+                }
+            } else {
+                for (int32_t e = lo + lane; e < hi; e += kWave) {
+                    int32_t cc = edge_to_col[e] - k0;
+                    if (cc >= 0 && cc < KW) {
+                        int r = 0;
 #pragma unroll
-                    for (int step = 8; step > 0; step >>= 1)
-                        if (s_rp[r + step] <= e) r += step;
-                    atomicAdd(&a32[r * kAStrideW + cc], HAS_W ? w[e] : 1.f);
+                        for (int step = 8; step > 0; step >>= 1)
+                            if (s_rp[r + step] <= e) r += step;
+                        atomicAdd(&a32[r * kAStrideW + cc], HAS_W ? w[e] : 1.f);
+                    }
                 }
             }
+            wave_lds_order();
         }
-        wave_lds_order();
         // TCcompute
-        const float4 av = *reinterpret_cast<const float4 *>(a_src);
+        const float4 av = *reinterpret_cast<const float4 *>(a_src + (FULL_A ? k0 : 0));
         uint2 af;
         af.x = pack2<DT, !HAS_W>(av.x, av.y);
         af.y = pack2<DT, !HAS_W>(av.z, av.w);
@@ -268,23 +310,34 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(3))) void
 
 template <int DT, bool HAS_W, int NS>
 void launch_wave(const tcg_meta *m, const void *X, int64_t ldx, int32_t D, const float *w, void *Y, int y_dt,
-                 int64_t ldy, hipStream_t s)
+                 int64_t ldy, int tile_mask, hipStream_t s)
 {
     const int32_t n_dparts = (D + NS * 16 - 1) / (NS * 16);
     // 4 outputs of a row leave in one store if every such group is aligned to its own size
     const bool y_vec = ldy % 4 == 0 && reinterpret_cast<uintptr_t>(Y) % (y_dt == TCG_F32 ? 16 : 8) == 0;
-    hipLaunchKernelGGL((spmm_tile_wave_kernel<DT, HAS_W, NS>), dim3((unsigned)(kXcds * ceil_div(m->n_win, kXcds) * n_dparts)),
-                       dim3(kWave), 0, s, m->n_rows, m->n_win, m->d_row_ptr, m->d_edge_to_col, m->d_win_unique_ptr,
-                       m->d_col_to_row, m->d_win_path, w, static_cast<const char *>(X), ldx * 2, D, n_dparts, Y, y_dt, ldy, y_vec);
+    const dim3 grid((unsigned)(kXcds * ceil_div(m->n_win, kXcds) * n_dparts));
+    if ((tile_mask >> kTileFew) & 1)
+        hipLaunchKernelGGL((spmm_tile_wave_kernel<DT, HAS_W, NS, false>), grid, dim3(kWave), 0, s, m->n_rows, m->n_win,
+                           m->d_row_ptr, m->d_edge_to_col, m->d_win_unique_ptr, m->d_col_to_row, m->d_win_path, w,
+                           static_cast<const char *>(X), ldx * 2, D, n_dparts, Y, y_dt, ldy, y_vec, 0);
+    if ((tile_mask >> kTileMany) & 1) {
+        // row stride of the window's condensed adjacency: its widest window rounded up to whole chunks,
+        // plus 4 floats so that consecutive rows start in different banks
+        const int32_t a_stride = (int32_t)((m->max_unique_many + KW - 1) / KW * KW + 4);
+        hipLaunchKernelGGL((spmm_tile_wave_kernel<DT, HAS_W, NS, true>), grid, dim3(kWave),
+                           (size_t)16 * a_stride * sizeof(float), s, m->n_rows, m->n_win, m->d_row_ptr,
+                           m->d_edge_to_col, m->d_win_unique_ptr, m->d_col_to_row, m->d_win_path, w,
+                           static_cast<const char *>(X), ldx * 2, D, n_dparts, Y, y_dt, ldy, y_vec, a_stride);
+    }
 }
 
 template <int DT, bool HAS_W>
 void launch_wave_s(const tcg_meta *m, const void *X, int64_t ldx, int32_t D, const float *w, void *Y, int y_dt,
-                   int64_t ldy, hipStream_t s)
+                   int64_t ldy, int tile_mask, hipStream_t s)
 {
-    if (D <= 64) launch_wave<DT, HAS_W, 4>(m, X, ldx, D, w, Y, y_dt, ldy, s);
-    else if (D <= 128) launch_wave<DT, HAS_W, 8>(m, X, ldx, D, w, Y, y_dt, ldy, s);
-    else launch_wave<DT, HAS_W, 16>(m, X, ldx, D, w, Y, y_dt, ldy, s);
+    if (D <= 64) launch_wave<DT, HAS_W, 4>(m, X, ldx, D, w, Y, y_dt, ldy, tile_mask, s);
+    else if (D <= 128) launch_wave<DT, HAS_W, 8>(m, X, ldx, D, w, Y, y_dt, ldy, tile_mask, s);
+    else launch_wave<DT, HAS_W, 16>(m, X, ldx, D, w, Y, y_dt, ldy, tile_mask, s);
 }
 
 }  // namespace
@@ -296,14 +349,14 @@ bool tile_path_supports(tcg_dtype x_dt, int32_t D, int64_t ldx, const void *X)
 }
 
 int spmm_tile_launch(tcg_meta *m, const void *d_X, tcg_dtype x_dt, int32_t D, int64_t ldx, const float *d_w,
-                     void *d_Y, tcg_dtype y_dt, int64_t ldy, hipStream_t s)
+                     void *d_Y, tcg_dtype y_dt, int64_t ldy, int tile_mask, hipStream_t s)
 {
     if (x_dt == TCG_BF16) {
-        if (d_w) launch_wave_s<TCG_BF16, true>(m, d_X, ldx, D, d_w, d_Y, (int)y_dt, ldy, s);
-        else launch_wave_s<TCG_BF16, false>(m, d_X, ldx, D, d_w, d_Y, (int)y_dt, ldy, s);
+        if (d_w) launch_wave_s<TCG_BF16, true>(m, d_X, ldx, D, d_w, d_Y, (int)y_dt, ldy, tile_mask, s);
+        else launch_wave_s<TCG_BF16, false>(m, d_X, ldx, D, d_w, d_Y, (int)y_dt, ldy, tile_mask, s);
     } else {
-        if (d_w) launch_wave_s<TCG_F16, true>(m, d_X, ldx, D, d_w, d_Y, (int)y_dt, ldy, s);
-        else launch_wave_s<TCG_F16, false>(m, d_X, ldx, D, d_w, d_Y, (int)y_dt, ldy, s);
+        if (d_w) launch_wave_s<TCG_F16, true>(m, d_X, ldx, D, d_w, d_Y, (int)y_dt, ldy, tile_mask, s);
+        else launch_wave_s<TCG_F16, false>(m, d_X, ldx, D, d_w, d_Y, (int)y_dt, ldy, tile_mask, s);
     }
     return launch_status("spmm_tile_wave_kernel");
 }

@@ -92,3 +92,15 @@ def test_bf16_rounding_matches_torch():
     assert np.array_equal(bits.view(np.int16), torch.from_numpy(x).to(torch.bfloat16).view(torch.int16).numpy())
     c = W.make_config(5, n=640)
     assert c["x_dtype"] == "bf16" and np.array_equal(W.round_to_bf16(c["X"]), c["X"])
+
+
+def test_window_fill_controls_the_sharing():
+    g = W.window_fill(2048, 48, 0.5, seed=3)
+    assert g.n_rows == 2048 and g.col_idx.max() < 2048
+    for w in (0, 17, 127):
+        cols = np.unique(g.col_idx[g.row_ptr[16 * w]:g.row_ptr[16 * w + 16]])
+        assert cols.size <= 48
+    reuse = g.nnz / sum(np.unique(g.col_idx[g.row_ptr[16 * w]:g.row_ptr[16 * w + 16]]).size for w in range(128))
+    assert 7.0 < reuse < 9.0                                    # about 16 * fill entries per distinct column
+    g2 = W.window_fill(2048, 48, 0.5, seed=3)
+    assert np.array_equal(g.col_idx, g2.col_idx)

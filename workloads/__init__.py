@@ -15,6 +15,7 @@ from .graphs import (
     rmat,
     clustered_communities,
     dense_block_windows,
+    window_fill,
     sym_norm_weights,
 )
 from .features import features_uniform, features_normal, round_to_bf16, bf16_bits
@@ -24,7 +25,7 @@ __all__ = [
     "splitmix64", "uniform01", "uniform_pm1", "normal01",
     "CSR", "csr_from_undirected_pairs", "csr_from_directed_pairs",
     "erdos_renyi_gnm", "chung_lu_powerlaw", "rmat", "clustered_communities",
-    "dense_block_windows", "sym_norm_weights",
+    "dense_block_windows", "window_fill", "sym_norm_weights",
     "features_uniform", "features_normal", "round_to_bf16", "bf16_bits",
     "CONFIGS", "make_config",
 ]

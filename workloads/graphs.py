@@ -201,6 +201,26 @@ def dense_block_windows(n, blocks_per_window, seed, block=16):
     return csr_from_directed_pairs(np.concatenate(src_parts), np.concatenate(dst_parts), n)
 
 
+def window_fill(n, unique_per_window, fill, seed, block=16):
+    """Windows with a chosen amount of neighbour sharing: every `block`-row window draws
+    `unique_per_window` distinct columns and every (row, column) pair of that window x column set is
+    stored with probability `fill`, so a window's entries per distinct column -- the reuse that decides
+    between the gather and the tile path -- is about block * fill."""
+    assert n % block == 0 and unique_per_window <= n
+    nb = n // block
+    src_parts, dst_parts = [], []
+    for w in range(nb):
+        draws = (splitmix64(seed, 61, w * 4 * unique_per_window, 4 * unique_per_window) % np.uint64(n)).astype(np.int64)
+        _, first = np.unique(draws, return_index=True)
+        cols = draws[np.sort(first)][:unique_per_window]           # distinct, in drawing order
+        assert cols.size == unique_per_window, "column space too small for this many distinct columns"
+        r = uniform01(seed, 62, w * block * unique_per_window, block * unique_per_window)
+        rr, cc = np.nonzero(r.reshape(block, unique_per_window) < fill)
+        src_parts.append(w * block + rr)
+        dst_parts.append(cols[cc])
+    return csr_from_directed_pairs(np.concatenate(src_parts), np.concatenate(dst_parts), n)
+
+
 def sym_norm_weights(csr):
     """Edge weights 1/sqrt(deg_i * deg_j) in CSR order (float32), deg = stored row length.
     Needs a square structure whose every referenced column has a non-empty row."""
