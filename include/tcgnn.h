@@ -112,8 +112,11 @@ TCG_API int tcg_sgt_export(const tcg_meta *meta, int32_t *win_partition, int32_t
  * Chooses which windows run on the condensed-tile (MFMA) path.  TCG_POLICY_AUTO (the state
  * after tcg_sgt_build) sends a window there when window_h == 16, it has at most 512 unique
  * columns and its neighbour reuse nnz_w / U_w is at least `min_reuse` (<= 0 selects the library
- * default, 2); the tile path is only
- * taken by calls whose X is bf16 or f16, fp32 features always use the gather path.
+ * default, 2).  The flag says where a window may go; a call takes the tile path only when its X is
+ * bf16 or f16 (fp32 features always use the gather path), and under TCG_POLICY_AUTO tcg_spmm
+ * additionally gathers narrow features: windows of at most 512 entries use the tile kernels from
+ * D >= 64, windows with more entries from D >= 128 (measured crossovers).  TCG_POLICY_TILE sends
+ * every non-empty window to the tile kernels at any width.
  * Blocks until the stream has finished.  Returns TCG_EINVAL for TCG_POLICY_TILE when
  * window_h != 16.
  */
