@@ -369,6 +369,106 @@ __global__ __launch_bounds__(kBitmapThreads) void sgt_window_bitmap_kernel(
     }
 }
 
+// Large class when the column space fits: the same bitmap, but in LDS (gfx950 gives a workgroup up to
+// 160 KB): one bit per column plus the running count in front of every group of kPfGroup words.
+// Setting the bits and looking the ranks up are LDS operations instead of L2 atomics and gathers, and
+// no device scratch has to be cleared.  Needs lds_bitmap_bytes(n_words) <= kLdsBitmapMax.
+constexpr int kPfGroup = 8;
+constexpr size_t kLdsBitmapMax = 160 * 1024 - 256;
+inline size_t lds_bitmap_bytes(int64_t n_words)
+{
+    return (size_t)(n_words + (n_words + kPfGroup - 1) / kPfGroup + 1) * 4;
+}
+
+__global__ __launch_bounds__(kBitmapThreads) void sgt_window_lds_bitmap_kernel(
+    int32_t n_rows, int32_t win_h, int32_t n_words, const int32_t *__restrict__ large_list,
+    const int32_t *__restrict__ rp, const int32_t *__restrict__ ci, int32_t *__restrict__ edge_to_col,
+    int32_t *__restrict__ tmp_clean, int32_t *__restrict__ win_unique)
+{
+    extern __shared__ uint32_t s_words[];          // bitmap, then the group prefixes
+    __shared__ int s_tmp[kBitmapWaves + 1];
+    uint32_t *bm = s_words;
+    int32_t *gpf = reinterpret_cast<int32_t *>(s_words + n_words);
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x >> 6;
+    const int64_t w = large_list[blockIdx.x];
+    int32_t lo, hi;
+    window_edge_range(rp, n_rows, win_h, w, &lo, &hi);
+
+    for (int32_t k = threadIdx.x; k < n_words; k += kBitmapThreads) bm[k] = 0u;
+    __syncthreads();
+
+    // 1. one bit per edge
+    for (int64_t e0 = lo + threadIdx.x; e0 < hi; e0 += (int64_t)kBitmapThreads * kEdgeUnroll) {
+        uint32_t c[kEdgeUnroll];
+#pragma unroll
+        for (int u = 0; u < kEdgeUnroll; ++u) {
+            int64_t e = e0 + (int64_t)u * kBitmapThreads;
+            c[u] = e < hi ? (uint32_t)ci[e] : 0xFFFFFFFFu;
+        }
+#pragma unroll
+        for (int u = 0; u < kEdgeUnroll; ++u)
+            if (c[u] != 0xFFFFFFFFu) atomicOr(&bm[c[u] >> 5], 1u << (c[u] & 31));
+    }
+    __syncthreads();
+
+    // 2. per-wavefront popcount of its word range (a multiple of the wavefront width, hence of the
+    //    prefix group), then the offsets of the wavefronts
+    int32_t wpw = (n_words + kBitmapWaves - 1) / kBitmapWaves;
+    wpw = (wpw + kWave - 1) / kWave * kWave;
+    const int32_t k_begin = min(wave * wpw, n_words);
+    const int32_t k_end = min(k_begin + wpw, n_words);
+    int cnt = 0;
+    for (int32_t k = k_begin + lane; k < k_end; k += kWave) cnt += __popc(bm[k]);
+#pragma unroll
+    for (int off = 1; off < kWave; off <<= 1) cnt += __shfl_xor(cnt, off, kWave);
+    int total;
+    int wave_off = block_exclusive_scan(lane == 0 ? cnt : 0, s_tmp, &total);
+    wave_off = __shfl(wave_off, 0, kWave);
+
+    // 3. the count in front of every group of words, and the unique list (bit positions ascending)
+    int carry = wave_off;
+    for (int32_t k0 = k_begin; k0 < k_end; k0 += kWave) {
+        const int32_t k = k0 + lane;
+        uint32_t bits = k < k_end ? bm[k] : 0u;
+        const int p = __popc(bits);
+        const int incl = wave_inclusive_scan(p);
+        int pos = carry + incl - p;
+        if (k < k_end && (k % kPfGroup) == 0) gpf[k / kPfGroup] = pos;
+        while (bits) {
+            int b = __ffs(bits) - 1;
+            bits &= bits - 1;
+            tmp_clean[lo + pos] = (int32_t)(k * 32 + b);
+            ++pos;
+        }
+        carry += __shfl(incl, kWave - 1, kWave);
+    }
+    if (threadIdx.x == 0) win_unique[w] = total;
+    __syncthreads();
+
+    // 4. rank of every edge's column: group prefix + the words of the group in front of it + the bits below
+    for (int64_t e0 = lo + threadIdx.x; e0 < hi; e0 += (int64_t)kBitmapThreads * kEdgeUnroll) {
+        uint32_t c[kEdgeUnroll];
+#pragma unroll
+        for (int u = 0; u < kEdgeUnroll; ++u) {
+            int64_t e = e0 + (int64_t)u * kBitmapThreads;
+            c[u] = e < hi ? (uint32_t)ci[e] : 0u;
+        }
+#pragma unroll
+        for (int u = 0; u < kEdgeUnroll; ++u) {
+            int64_t e = e0 + (int64_t)u * kBitmapThreads;
+            if (e >= hi) continue;
+            const int32_t wi = (int32_t)(c[u] >> 5);
+            const int32_t g0 = wi / kPfGroup * kPfGroup;
+            int r = gpf[wi / kPfGroup] + __popc(bm[wi] & ((1u << (c[u] & 31)) - 1u));
+#pragma unroll
+            for (int j = 0; j < kPfGroup - 1; ++j)
+                if (g0 + j < wi) r += __popc(bm[g0 + j]);
+            edge_to_col[e] = r;
+        }
+    }
+}
+
 // Packs the per-window lists into col_to_row.  One wavefront per window; windows of the large
 // class are copied by sgt_pack_large_kernel with many workgroups each.
 __global__ __launch_bounds__(kWave) void sgt_pack_kernel(int32_t n_rows, int32_t win_h,
@@ -814,9 +914,22 @@ int sgt_build_impl(tcg_meta *m, int validate, hipStream_t s)
                            win_unique);
     TCG_TRY(launch_status("sgt_window_lds_kernel"));
     ScopedFree bitmap_guard;
-    if (h_cls[3] > 0) {
+    const int64_t n_words_all = ceil_div(m->n_cols, 32);
+    if (h_cls[3] > 0 && lds_bitmap_bytes(n_words_all) <= kLdsBitmapMax) {
+        const size_t lds = lds_bitmap_bytes(n_words_all);
+        static bool raised = false;       // more than 64 KB of dynamic LDS has to be asked for once
+        if (!raised) {
+            TCG_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(sgt_window_lds_bitmap_kernel),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBitmapMax));
+            raised = true;
+        }
+        hipLaunchKernelGGL(sgt_window_lds_bitmap_kernel, dim3((unsigned)h_cls[3]), dim3(kBitmapThreads), lds, s, n,
+                           m->win_h, (int32_t)n_words_all, lists + 3 * n_win, m->d_row_ptr, m->d_col_idx,
+                           m->d_edge_to_col, tmp_clean, win_unique);
+        TCG_TRY(launch_status("sgt_window_lds_bitmap_kernel"));
+    } else if (h_cls[3] > 0) {
         const int64_t n_large = h_cls[3];
-        const int64_t n_words = ceil_div(m->n_cols, 32);
+        const int64_t n_words = n_words_all;
         const int64_t budget_words = (int64_t)(128ll << 20) / 4;  // 128 MiB per scratch array
         const int64_t batch = std::max<int64_t>(1, std::min<int64_t>(n_large, budget_words / n_words));
         uint32_t *bitmap = nullptr;

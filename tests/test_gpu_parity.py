@@ -70,6 +70,26 @@ def test_sgt_all_size_classes_and_unsorted_rows():
         meta.free()
 
 
+def test_sgt_large_windows_in_both_bitmap_variants():
+    # Windows above 4096 entries use a bitmap over the column space: in LDS when the column space fits
+    # (up to about 1.16 M columns), in device memory beyond.  Both with columns up to the last one, rows
+    # in shuffled order, repeated entries, and a window that is nearly full.
+    rng = np.random.default_rng(21)
+    for n_cols in (70000, 1160000 - 7, 1400003):
+        rows = []
+        for i in range(48):
+            k = 400 if i < 16 else (3 if i < 32 else 700)
+            r = rng.integers(0, n_cols, size=k)
+            if i == 0:
+                r[:3] = (0, n_cols - 1, n_cols - 1)
+            rows.append(r)
+        g = csr_from_rows(rows, n_cols)
+        rp, ci = upload_csr(g)
+        meta = tcg.sgt_build(rp, ci, 16, 8, n_cols=n_cols)
+        check_sgt(meta, g, 16, 8)
+        meta.free()
+
+
 def test_sgt_empty_and_degenerate():
     for g in (CSR(0, 0, np.zeros(1, np.int32), np.zeros(0, np.int32)),
               CSR(37, 37, np.zeros(38, np.int32), np.zeros(0, np.int32)),
