@@ -173,7 +173,7 @@ __device__ __forceinline__ void window_edge_range(const int32_t *rp, int32_t n_r
 // counts[0..3] = tiny, small, medium, large.
 __global__ __launch_bounds__(256) void classify_windows_kernel(int32_t n_rows, int32_t win_h, int64_t n_win,
                                                                const int32_t *rp, int32_t *lists, int *counts,
-                                                               int32_t *win_unique)
+                                                               int32_t *win_unique, int32_t medium_cap)
 {
     const int64_t w = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     const int lane = threadIdx.x & (kWave - 1);
@@ -183,7 +183,7 @@ __global__ __launch_bounds__(256) void classify_windows_kernel(int32_t n_rows, i
         window_edge_range(rp, n_rows, win_h, w, &lo, &hi);
         const int32_t cnt = hi - lo;
         if (cnt == 0) win_unique[w] = 0;
-        else cls = cnt <= kTinyCap ? 0 : cnt <= kSmallCap ? 1 : cnt <= kMediumCap ? 2 : 3;
+        else cls = cnt <= kTinyCap ? 0 : cnt <= kSmallCap ? 1 : cnt <= medium_cap ? 2 : 3;
     }
     // One atomic per wavefront and class instead of one per window.
 #pragma unroll
@@ -374,6 +374,7 @@ __global__ __launch_bounds__(kBitmapThreads) void sgt_window_bitmap_kernel(
 // Setting the bits and looking the ranks up are LDS operations instead of L2 atomics and gathers, and
 // no device scratch has to be cleared.  Needs lds_bitmap_bytes(n_words) <= kLdsBitmapMax.
 constexpr int kPfGroup = 8;
+constexpr int kLdsBitmapFrom = 1024;
 constexpr size_t kLdsBitmapMax = 160 * 1024 - 256;
 inline size_t lds_bitmap_bytes(int64_t n_words)
 {
@@ -475,14 +476,14 @@ __global__ __launch_bounds__(kWave) void sgt_pack_kernel(int32_t n_rows, int32_t
                                                          const int32_t *__restrict__ rp,
                                                          const int32_t *__restrict__ tmp_clean,
                                                          const int32_t *__restrict__ win_unique_ptr,
-                                                         int32_t *__restrict__ col_to_row)
+                                                         int32_t *__restrict__ col_to_row, int32_t medium_cap)
 {
     const int64_t w = blockIdx.x;
     int32_t lo, hi;
     window_edge_range(rp, n_rows, win_h, w, &lo, &hi);
     const int32_t u0 = win_unique_ptr[w];
     const int32_t uw = win_unique_ptr[w + 1] - u0;
-    if (hi - lo <= kMediumCap)
+    if (hi - lo <= medium_cap)
         for (int k = threadIdx.x; k < uw; k += kWave) col_to_row[u0 + k] = tmp_clean[lo + k];
 }
 
@@ -799,6 +800,10 @@ int sgt_build_impl(tcg_meta *m, int validate, hipStream_t s)
     const int64_t nnz = m->nnz;
     const int64_t n_win = m->n_win;
     const int64_t scan_elems = scan_workspace_elems(std::max<int64_t>(n, n_win));
+    // Windows above medium_cap entries form the large class (bitmap over the column space).  When that
+    // bitmap fits in LDS it is cheaper than sorting from kLdsBitmapFrom entries on, so the class starts there.
+    const bool lds_bitmap = lds_bitmap_bytes(ceil_div(m->n_cols, 32)) <= kLdsBitmapMax;
+    const int32_t medium_cap = lds_bitmap ? std::min(kLdsBitmapFrom, kMediumCap) : kMediumCap;
 
     // Arena 0 (kept): the translated graph except col_to_row, the path flags, a few counters.
     Arena keep;
@@ -857,7 +862,7 @@ int sgt_build_impl(tcg_meta *m, int validate, hipStream_t s)
     // Window classes and segment counts (both depend on row_ptr only).
     if (n_win > 0) {
         hipLaunchKernelGGL(classify_windows_kernel, dim3((unsigned)ceil_div(n_win, 256)), dim3(256), 0, s, n,
-                           m->win_h, n_win, m->d_row_ptr, lists, small_ints, win_unique);
+                           m->win_h, n_win, m->d_row_ptr, lists, small_ints, win_unique, medium_cap);
         TCG_TRY(launch_status("classify_windows_kernel"));
     }
     if (n > 0) {
@@ -1011,7 +1016,7 @@ int sgt_build_impl(tcg_meta *m, int validate, hipStream_t s)
     m->owned[m->n_owned++] = m->d_col_to_row;
     if (n_win > 0) {
         hipLaunchKernelGGL(sgt_pack_kernel, dim3((unsigned)n_win), dim3(kWave), 0, s, n, m->win_h, m->d_row_ptr,
-                           tmp_clean, m->d_win_unique_ptr, m->d_col_to_row);
+                           tmp_clean, m->d_win_unique_ptr, m->d_col_to_row, medium_cap);
         TCG_TRY(launch_status("sgt_pack_kernel"));
         if (h_cls[3] > 0) {
             hipLaunchKernelGGL(sgt_pack_large_kernel, dim3((unsigned)h_cls[3], kPackSplit), dim3(256), 0, s, n,
