@@ -390,17 +390,28 @@ __global__ __launch_bounds__(kBitmapThreads) void sgt_window_lds_bitmap_kernel(
     __shared__ int s_tmp[kBitmapWaves + 1];
     uint32_t *bm = s_words;
     int32_t *gpf = reinterpret_cast<int32_t *>(s_words + n_words);
-    const int lane = threadIdx.x & (kWave - 1);
-    const int wave = threadIdx.x >> 6;
     const int64_t w = large_list[blockIdx.x];
     int32_t lo, hi;
     window_edge_range(rp, n_rows, win_h, w, &lo, &hi);
 
+    // The first batch of columns is requested before the bitmap is cleared (its latency hides under the
+    // clearing) and kept for step 4: windows of up to kBitmapThreads * kEdgeUnroll entries read their
+    // columns once.
+    uint32_t c_first[kEdgeUnroll];
+#pragma unroll
+    for (int u = 0; u < kEdgeUnroll; ++u) {
+        const int64_t e = (int64_t)lo + threadIdx.x + (int64_t)u * kBitmapThreads;
+        c_first[u] = e < hi ? (uint32_t)ci[e] : 0xFFFFFFFFu;
+    }
     for (int32_t k = threadIdx.x; k < n_words; k += kBitmapThreads) bm[k] = 0u;
     __syncthreads();
 
     // 1. one bit per edge
-    for (int64_t e0 = lo + threadIdx.x; e0 < hi; e0 += (int64_t)kBitmapThreads * kEdgeUnroll) {
+#pragma unroll
+    for (int u = 0; u < kEdgeUnroll; ++u)
+        if (c_first[u] != 0xFFFFFFFFu) atomicOr(&bm[c_first[u] >> 5], 1u << (c_first[u] & 31));
+    for (int64_t e0 = (int64_t)lo + (int64_t)kBitmapThreads * kEdgeUnroll + threadIdx.x; e0 < hi;
+         e0 += (int64_t)kBitmapThreads * kEdgeUnroll) {
         uint32_t c[kEdgeUnroll];
 #pragma unroll
         for (int u = 0; u < kEdgeUnroll; ++u) {
@@ -413,42 +424,46 @@ __global__ __launch_bounds__(kBitmapThreads) void sgt_window_lds_bitmap_kernel(
     }
     __syncthreads();
 
-    // 2. per-wavefront popcount of its word range (a multiple of the wavefront width, hence of the
-    //    prefix group), then the offsets of the wavefronts
-    int32_t wpw = (n_words + kBitmapWaves - 1) / kBitmapWaves;
-    wpw = (wpw + kWave - 1) / kWave * kWave;
-    const int32_t k_begin = min(wave * wpw, n_words);
-    const int32_t k_end = min(k_begin + wpw, n_words);
+    // 2. every thread owns a contiguous run of R words (R odd: the lanes of a wavefront then read
+    //    different banks) and counts its bits; one workgroup-wide scan gives the count in front of
+    //    every run.  (A scan per 64 words instead costs a chain of cross-lane steps per row.)
+    const int32_t R = ((n_words + kBitmapThreads - 1) / kBitmapThreads) | 1;
+    const int32_t kb = min((int32_t)threadIdx.x * R, n_words), ke = min(kb + R, n_words);
     int cnt = 0;
-    for (int32_t k = k_begin + lane; k < k_end; k += kWave) cnt += __popc(bm[k]);
-#pragma unroll
-    for (int off = 1; off < kWave; off <<= 1) cnt += __shfl_xor(cnt, off, kWave);
+    for (int32_t k = kb; k < ke; ++k) cnt += __popc(bm[k]);
     int total;
-    int wave_off = block_exclusive_scan(lane == 0 ? cnt : 0, s_tmp, &total);
-    wave_off = __shfl(wave_off, 0, kWave);
+    int pos = block_exclusive_scan(cnt, s_tmp, &total);
 
     // 3. the count in front of every group of words, and the unique list (bit positions ascending)
-    int carry = wave_off;
-    for (int32_t k0 = k_begin; k0 < k_end; k0 += kWave) {
-        const int32_t k = k0 + lane;
-        uint32_t bits = k < k_end ? bm[k] : 0u;
-        const int p = __popc(bits);
-        const int incl = wave_inclusive_scan(p);
-        int pos = carry + incl - p;
-        if (k < k_end && (k % kPfGroup) == 0) gpf[k / kPfGroup] = pos;
+    for (int32_t k = kb; k < ke; ++k) {
+        uint32_t bits = bm[k];
+        if ((k % kPfGroup) == 0) gpf[k / kPfGroup] = pos;
         while (bits) {
-            int b = __ffs(bits) - 1;
+            const int b = __ffs(bits) - 1;
             bits &= bits - 1;
-            tmp_clean[lo + pos] = (int32_t)(k * 32 + b);
+            tmp_clean[lo + pos] = k * 32 + b;
             ++pos;
         }
-        carry += __shfl(incl, kWave - 1, kWave);
     }
     if (threadIdx.x == 0) win_unique[w] = total;
     __syncthreads();
 
     // 4. rank of every edge's column: group prefix + the words of the group in front of it + the bits below
-    for (int64_t e0 = lo + threadIdx.x; e0 < hi; e0 += (int64_t)kBitmapThreads * kEdgeUnroll) {
+    auto rank_of = [&](uint32_t c) {
+        const int32_t wi = (int32_t)(c >> 5);
+        const int32_t g0 = wi / kPfGroup * kPfGroup;
+        int r = gpf[wi / kPfGroup] + __popc(bm[wi] & ((1u << (c & 31)) - 1u));
+#pragma unroll
+        for (int j = 0; j < kPfGroup - 1; ++j)
+            if (g0 + j < wi) r += __popc(bm[g0 + j]);
+        return r;
+    };
+#pragma unroll
+    for (int u = 0; u < kEdgeUnroll; ++u)
+        if (c_first[u] != 0xFFFFFFFFu)
+            edge_to_col[(int64_t)lo + threadIdx.x + (int64_t)u * kBitmapThreads] = rank_of(c_first[u]);
+    for (int64_t e0 = (int64_t)lo + (int64_t)kBitmapThreads * kEdgeUnroll + threadIdx.x; e0 < hi;
+         e0 += (int64_t)kBitmapThreads * kEdgeUnroll) {
         uint32_t c[kEdgeUnroll];
 #pragma unroll
         for (int u = 0; u < kEdgeUnroll; ++u) {
@@ -458,14 +473,7 @@ __global__ __launch_bounds__(kBitmapThreads) void sgt_window_lds_bitmap_kernel(
 #pragma unroll
         for (int u = 0; u < kEdgeUnroll; ++u) {
             int64_t e = e0 + (int64_t)u * kBitmapThreads;
-            if (e >= hi) continue;
-            const int32_t wi = (int32_t)(c[u] >> 5);
-            const int32_t g0 = wi / kPfGroup * kPfGroup;
-            int r = gpf[wi / kPfGroup] + __popc(bm[wi] & ((1u << (c[u] & 31)) - 1u));
-#pragma unroll
-            for (int j = 0; j < kPfGroup - 1; ++j)
-                if (g0 + j < wi) r += __popc(bm[g0 + j]);
-            edge_to_col[e] = r;
+            if (e < hi) edge_to_col[e] = rank_of(c[u]);
         }
     }
 }
@@ -794,6 +802,15 @@ int choose_paths(tcg_meta *m, tcg_policy policy, float min_reuse, hipStream_t s)
     return TCG_OK;
 }
 
+__global__ void collect3_kernel(const int32_t *a, const int32_t *b, const int32_t *c, int *out)
+{
+    if (threadIdx.x == 0) {
+        out[0] = *a;
+        out[1] = *b;
+        out[2] = *c;
+    }
+}
+
 int sgt_build_impl(tcg_meta *m, int validate, hipStream_t s)
 {
     const int32_t n = m->n_rows;
@@ -837,7 +854,7 @@ int sgt_build_impl(tcg_meta *m, int validate, hipStream_t s)
     int32_t *long_off = tmp.take<int32_t>((int64_t)n + 1);
     int32_t *slot_off = tmp.take<int32_t>((int64_t)n + 1);
     int32_t *scan_work = tmp.take<int32_t>(scan_elems);
-    int *small_ints = tmp.take<int>(16);   // [0..3] class counts, [8] validation flag
+    int *small_ints = tmp.take<int>(16);   // [0..3] class counts, [4..6] plan totals, [8] validation flag
     TCG_HIP(hipMemsetAsync(small_ints, 0, 16 * sizeof(int), s));
 
     if (validate) {
@@ -873,13 +890,15 @@ int sgt_build_impl(tcg_meta *m, int validate, hipStream_t s)
     TCG_TRY(exclusive_scan_i32(seg_off, seg_off, n, scan_work, s));
     TCG_TRY(exclusive_scan_i32(long_off, long_off, n, scan_work, s));
     TCG_TRY(exclusive_scan_i32(slot_off, slot_off, n, scan_work, s));
-    int h_cls[4] = {0, 0, 0, 0};
-    int32_t h_plan[3] = {0, 0, 0};
-    TCG_HIP(hipMemcpyAsync(h_cls, small_ints, sizeof(h_cls), hipMemcpyDeviceToHost, s));
-    TCG_HIP(hipMemcpyAsync(&h_plan[0], seg_off + n, sizeof(int32_t), hipMemcpyDeviceToHost, s));
-    TCG_HIP(hipMemcpyAsync(&h_plan[1], long_off + n, sizeof(int32_t), hipMemcpyDeviceToHost, s));
-    TCG_HIP(hipMemcpyAsync(&h_plan[2], slot_off + n, sizeof(int32_t), hipMemcpyDeviceToHost, s));
+    // One copy for everything the host needs here (every separate small copy costs tens of microseconds):
+    // the three totals are collected next to the class counts first.
+    hipLaunchKernelGGL(collect3_kernel, dim3(1), dim3(64), 0, s, seg_off + n, long_off + n, slot_off + n,
+                       small_ints + 4);
+    int h_small[7] = {0, 0, 0, 0, 0, 0, 0};
+    TCG_HIP(hipMemcpyAsync(h_small, small_ints, sizeof(h_small), hipMemcpyDeviceToHost, s));
     TCG_HIP(hipStreamSynchronize(s));                                           // sync 1
+    const int h_cls[4] = {h_small[0], h_small[1], h_small[2], h_small[3]};
+    const int32_t h_plan[3] = {h_small[4], h_small[5], h_small[6]};
     m->n_seg = h_plan[0];
     m->n_long = h_plan[1];
     m->n_slots = h_plan[2];
