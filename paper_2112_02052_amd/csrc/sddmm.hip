@@ -231,7 +231,9 @@ template <int DT, int G, int NCH, int PB = 16>
 void launch_sddmm(const tcg_meta *m, const void *P, int64_t ldp, const void *X, int64_t ldx, int32_t n_chunks,
                   float *out, const uint8_t *win_path, hipStream_t s)
 {
-    constexpr int UNROLL = NCH == 1 ? 8 : (NCH == 2 ? 4 : 2);
+    // A group narrower than 8 lanes reduces 8 partial products with more shuffles and stores than
+    // loads; it takes as many edges per step as it has lanes.
+    constexpr int UNROLL = NCH == 1 ? (G < 8 ? G : 8) : (NCH == 2 ? 4 : 2);
     const unsigned grid = (unsigned)plan_grid(m->h_lane_tab, kBlock / G);
     hipLaunchKernelGGL((sddmm_gather_kernel<DT, G, NCH, UNROLL, PB>), dim3(grid), dim3(kBlock), 0, s, m->d_lane_tab,
                        m->d_seg_row, m->d_seg_ebeg, m->d_row_ptr, m->d_col_idx, static_cast<const char *>(P),
