@@ -78,6 +78,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--backward", action="store_true",
                     help="also time the backward-pass building blocks (transpose, dX = A^T dY, dw = SDDMM(dY, X))")
+    ap.add_argument("--window-height", type=int, default=16,
+                    help="rows per window of the translation (16 as in the paper; 32 halves the neighbour fetches "
+                         "of the MFMA tile path on clustered graphs)")
     ap.add_argument("--reorder", type=int, default=None, metavar="ROUNDS",
                     help="cluster the rows (tcg_reorder_rows with this many refinement rounds) and relabel the "
                          "graph and X before the timed steps; the one-off cost is reported under 'reorder'")
@@ -132,7 +135,7 @@ def main():
         (rp2, ci2, ep), t_csr = once_ms(lambda: tcg.csr_permute(rp, ci, perm))
         pl = perm.long()
         _, t_x = once_ms(lambda: Xd[feat][pl])
-        u_before = tcg.sgt_build(rp, ci, 16, 8, validate=False)
+        u_before = tcg.sgt_build(rp, ci, args.window_height, 8, validate=False)
         reorder_info = {"refine_rounds": args.reorder, "reorder_rows_ms": t_perm, "csr_permute_ms": t_csr,
                         "permute_X_ms": t_x, "window_unique_before": u_before.total_unique}
         u_before.free()
@@ -143,7 +146,7 @@ def main():
     Y = torch.empty((N, D), dtype=torch.float32, device=dev)
     E = torch.empty(nnz, dtype=torch.float32, device=dev)
     P = torch.empty(nnz, dtype=torch.float32, device=dev)
-    H, TW = 16, 8
+    H, TW = args.window_height, 8
 
     def ev():
         return torch.cuda.Event(enable_timing=True)
@@ -249,9 +252,9 @@ def main():
         "vs_baseline": None,
         "dtype": "f32",
         "data": "synthetic",
-        "config": {"workload": "config %s (%s): N=%d, %d stored entries, X %s N x %d, %s edge values, window 16 x 8; "
+        "config": {"workload": "config %s (%s): N=%d, %d stored entries, X %s N x %d, %s edge values, window %d x 8; "
                                "step = sgt_build + %s" % (args.workload, c["name"], N, nnz, feat, D,
-                                                          "given" if weighted else "unit", " + ".join(ops)),
+                                                          "given" if weighted else "unit", H, " + ".join(ops)),
                    "features": feat, "nnz": nnz, "window_unique_total": U, "tiles": tiles, "windows": n_win,
                    "tile_windows": plan["n_tile_windows"], "tile_edge_share": tile_share,
                    "segments": plan["n_segments"], "long_rows": plan["n_long_rows"]},
@@ -295,7 +298,7 @@ def main():
 
     if args.model:
         import paper_2112_02052_amd.nn as tnn
-        graph = tnn.TiledGraph(rp, ci, validate=False)
+        graph = tnn.TiledGraph(rp, ci, window_h=H, validate=False)
         graph.transposed()                                                # built once, like the forward plan
         torch.manual_seed(0)
         n_classes = 10

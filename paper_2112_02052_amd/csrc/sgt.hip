@@ -709,8 +709,10 @@ __global__ __launch_bounds__(256) void choose_path_kernel(int32_t n_rows, int32_
         else if (policy == TCG_POLICY_AUTO)
             // Windows with shared neighbours, but not hub windows: the tile kernels keep a window's
             // condensed columns (or its whole condensed adjacency) in LDS, which needs compact windows.
-            tile = win_h == 16 && uw > 0 && uw <= kTileMaxUnique && (float)nnz_w >= min_reuse * (float)uw;
-        const bool many = tile && nnz_w > kTileFewEdges && uw <= kTileMaxUnique;
+            tile = (win_h == 16 || win_h == 32) && uw > 0 && uw <= kTileMaxUnique && (float)nnz_w >= min_reuse * (float)uw;
+        // windows of 32 rows: class kTileFew only (twice the edges of a 16-row window fit in registers)
+        if (win_h == 32 && policy == TCG_POLICY_AUTO && nnz_w > 2 * kTileFewEdges) tile = false;
+        const bool many = tile && win_h == 16 && nnz_w > kTileFewEdges && uw <= kTileMaxUnique;
         win_path[w] = tile ? (many ? kTileMany : kTileFew) : 0;
         if (tile) {
             tile_win = 1;
@@ -778,7 +780,7 @@ int exclusive_scan_i32(const int32_t *d_in, int32_t *d_out, int64_t n, int32_t *
 
 int choose_paths(tcg_meta *m, tcg_policy policy, float min_reuse, hipStream_t s)
 {
-    if (policy == TCG_POLICY_TILE && m->win_h != 16) return TCG_EINVAL;
+    if (policy == TCG_POLICY_TILE && m->win_h != 16 && m->win_h != 32) return TCG_EINVAL;
     if (min_reuse <= 0.f) min_reuse = kDefaultMinReuse;
     // [0] tiles, [1] tile-path windows, [2] their edges, [3] windows of class kTileMany, [4] their widest
     unsigned long long *counts = m->d_counters;

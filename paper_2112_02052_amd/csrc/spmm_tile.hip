@@ -96,7 +96,10 @@ __device__ __forceinline__ f32x4 mfma16k16(const uint2 &a, const uint2 &b, f32x4
 // kTileMany: the whole 16 x U_w condensed adjacency of the window is built once in (dynamic) LDS with a
 // single pass over the window's edges -- dense windows would otherwise walk thousands of edges per chunk --
 // and every chunk reads its slice from there; a_stride = its row stride in floats.
-template <int DT, bool HAS_W, int NS, bool FULL_A>
+// HB: 16-row blocks per window (1: windows of 16 rows, 2: windows of 32 rows, class kTileFew only).  A taller
+// window fetches a neighbour shared by its rows once instead of once per 16 rows, and every B fragment read
+// from LDS feeds HB MFMAs.
+template <int DT, bool HAS_W, int NS, bool FULL_A, int HB>
 __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(3))) void spmm_tile_wave_kernel(
     int32_t n_rows, int64_t n_win, const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ edge_to_col,
     const int32_t *__restrict__ win_unique_ptr, const int32_t *__restrict__ col_to_row,
@@ -104,14 +107,16 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(3))) void
     int64_t ldx_bytes, int32_t D, int32_t n_dparts, void *__restrict__ Y, int y_dt, int64_t ldy, bool y_vec,
     int32_t a_stride)
 {
+    static_assert(!(FULL_A && HB != 1), "the whole-window adjacency variant handles 16-row windows");
+    constexpr int H = 16 * HB;
     extern __shared__ __align__(16) float a_full[];              // FULL_A: 16 x a_stride
     constexpr int PP = NS / 2;                                    // 16-byte pieces of a chunk per lane
     // Staged row stride: an odd multiple of 32 bytes, so the 8 rows that half a wavefront touches in
     // a transposing read start in 8 different groups of 8 LDS banks.
     constexpr int32_t rs = NS * 32 + 32;
     __shared__ __align__(16) char xs[KW * rs];
-    __shared__ __align__(16) float a_slice[FULL_A ? 4 : 16 * kAStrideW];
-    __shared__ int32_t s_rp[17];
+    __shared__ __align__(16) float a_slice[FULL_A ? 4 : H * kAStrideW];
+    __shared__ int32_t s_rp[H + 1];
     float *a32 = FULL_A ? a_full : a_slice;
     const int32_t as = FULL_A ? a_stride : kAStrideW;
 
@@ -124,8 +129,8 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(3))) void
     const int32_t Dp = min(NS * 16, D - d0);
 
     const int lane = threadIdx.x;
-    const int64_t r0 = win * 16;
-    if (lane < 17) {
+    const int64_t r0 = win * H;
+    if (lane < H + 1) {
         int64_t r = r0 + lane;
         s_rp[lane] = row_ptr[r < n_rows ? r : n_rows];
     }
@@ -136,7 +141,7 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(3))) void
     const int kk = lane & 15;
     int32_t nid_cur = kk < U ? col_to_row[u0 + kk] : -1;
     int32_t nid_nxt = KW + kk < U ? col_to_row[u0 + KW + kk] : -1;
-    const int32_t lo = s_rp[0], hi = s_rp[16];
+    const int32_t lo = s_rp[0], hi = s_rp[H];
     const int32_t n_slices = (Dp + 15) / 16;
 
     // FetchDense mapping: 2 * NS lanes cover one row part with 16-byte pieces, so one pass of the
@@ -161,7 +166,7 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(3))) void
     // !FULL_A: a window of at most EPT * 64 edges keeps them in registers: (A-slice row offset << 16 |
     // condensed column) and the value.  (Windows forced onto this path with more edges re-read them for
     // every chunk.)
-    constexpr int EPT = FULL_A ? 1 : kTileFewEdges / kWave;
+    constexpr int EPT = FULL_A ? 1 : HB * kTileFewEdges / kWave;
     const bool edges_in_regs = hi - lo <= EPT * kWave;
     int32_t e_code[EPT];
     float e_val[EPT];
@@ -174,7 +179,7 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(3))) void
             if (edges_in_regs && e < hi) {
                 int r = 0;
 #pragma unroll
-                for (int step = 8; step > 0; step >>= 1)
+                for (int step = H / 2; step > 0; step >>= 1)
                     if (s_rp[r + step] <= e) r += step;
                 e_code[q] = (r * kAStrideW) << 16 | edge_to_col[e];     // condensed column < kTileMaxUnique
                 if (HAS_W) e_val[q] = w[e];
@@ -201,7 +206,7 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(3))) void
                 if (e < hi) {
                     int r = 0;
 #pragma unroll
-                    for (int step = 8; step > 0; step >>= 1)
+                    for (int step = H / 2; step > 0; step >>= 1)
                         if (s_rp[r + step] <= e) r += step;
                     atomicAdd(&a32[r * as + cc[q]], vv[q]);
                 }
@@ -210,9 +215,11 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(3))) void
         wave_lds_order();
     }
 
-    f32x4 acc[NS];
+    f32x4 acc[HB][NS];
 #pragma unroll
-    for (int i = 0; i < NS; ++i) acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int hb = 0; hb < HB; ++hb)
+#pragma unroll
+        for (int i = 0; i < NS; ++i) acc[hb][i] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     const int g = lane >> 4, n_in = lane & 15;
     const float *a_src = a32 + n_in * as + 4 * g;                 // A: row n_in, k = 4g .. 4g+3 (+ k0 if FULL_A)
@@ -232,7 +239,7 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(3))) void
         if constexpr (!FULL_A) {
             // InitSparse
 #pragma unroll
-            for (int i = 0; i < 5; ++i) a32[lane + i * kWave] = 0.f;
+            for (int i = 0; i < 5 * HB; ++i) a32[lane + i * kWave] = 0.f;
             wave_lds_order();
             if (edges_in_regs) {
 #pragma unroll
@@ -246,7 +253,7 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(3))) void
                     if (cc >= 0 && cc < KW) {
                         int r = 0;
 #pragma unroll
-                        for (int step = 8; step > 0; step >>= 1)
+                        for (int step = H / 2; step > 0; step >>= 1)
                             if (s_rp[r + step] <= e) r += step;
                         atomicAdd(&a32[r * kAStrideW + cc], HAS_W ? w[e] : 1.f);
                     }
@@ -255,14 +262,20 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(3))) void
             wave_lds_order();
         }
         // TCcompute
-        const float4 av = *reinterpret_cast<const float4 *>(a_src + (FULL_A ? k0 : 0));
-        uint2 af;
-        af.x = pack2<DT, !HAS_W>(av.x, av.y);
-        af.y = pack2<DT, !HAS_W>(av.z, av.w);
+        uint2 af[HB];
+#pragma unroll
+        for (int hb = 0; hb < HB; ++hb) {
+            const float4 av = *reinterpret_cast<const float4 *>(a_src + hb * 16 * as + (FULL_A ? k0 : 0));
+            af[hb].x = pack2<DT, !HAS_W>(av.x, av.y);
+            af[hb].y = pack2<DT, !HAS_W>(av.z, av.w);
+        }
 #pragma unroll
         for (int i = 0; i < NS; ++i)
-            if (i < n_slices)   // columns of a half slice beyond D read padding and are never stored
-                acc[i] = mfma16k16<DT>(af, lds_read_tr16(b_src + i * 32), acc[i]);
+            if (i < n_slices) {   // columns of a half slice beyond D read padding and are never stored
+                const uint2 bf = lds_read_tr16(b_src + i * 32);
+#pragma unroll
+                for (int hb = 0; hb < HB; ++hb) acc[hb][i] = mfma16k16<DT>(af[hb], bf, acc[hb][i]);
+            }
         wave_lds_order();
     }
 
@@ -272,17 +285,18 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(3))) void
     constexpr int SP = NS / 2, YS = 8 * NS + 4;                   // slices per pass; LDS row stride in floats
     float *ys = reinterpret_cast<float *>(xs);
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
-        if (h * SP >= n_slices) break;
+    for (int hh = 0; hh < 2 * HB; ++hh) {
+        const int hb = hh / 2, h = hh % 2;
+        if (h * SP >= n_slices) continue;
 #pragma unroll
         for (int i = 0; i < SP; ++i)
 #pragma unroll
-            for (int r = 0; r < 4; ++r) ys[(4 * g + r) * YS + i * 16 + n_in] = acc[h * SP + i][r];
+            for (int r = 0; r < 4; ++r) ys[(4 * g + r) * YS + i * 16 + n_in] = acc[hb][h * SP + i][r];
         wave_lds_order();
         const int32_t col = h * SP * 16 + (lane % LPR) * 4;       // first of the lane's 4 columns inside the part
 #pragma unroll
         for (int i = 0; i < PP; ++i) {
-            const int64_t row = r0 + i * RPP + sub;
+            const int64_t row = r0 + hb * 16 + i * RPP + sub;
             if (row >= n_rows || col >= Dp) continue;
             const float4 v = *reinterpret_cast<const float4 *>(ys + (i * RPP + sub) * YS + (lane % LPR) * 4);
             const int64_t o = row * ldy + d0 + col;
@@ -308,7 +322,7 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(3))) void
     }
 }
 
-template <int DT, bool HAS_W, int NS>
+template <int DT, bool HAS_W, int NS, int HB>
 void launch_wave(const tcg_meta *m, const void *X, int64_t ldx, int32_t D, const float *w, void *Y, int y_dt,
                  int64_t ldy, int tile_mask, hipStream_t s)
 {
@@ -317,17 +331,19 @@ void launch_wave(const tcg_meta *m, const void *X, int64_t ldx, int32_t D, const
     const bool y_vec = ldy % 4 == 0 && reinterpret_cast<uintptr_t>(Y) % (y_dt == TCG_F32 ? 16 : 8) == 0;
     const dim3 grid((unsigned)(kXcds * ceil_div(m->n_win, kXcds) * n_dparts));
     if ((tile_mask >> kTileFew) & 1)
-        hipLaunchKernelGGL((spmm_tile_wave_kernel<DT, HAS_W, NS, false>), grid, dim3(kWave), 0, s, m->n_rows, m->n_win,
-                           m->d_row_ptr, m->d_edge_to_col, m->d_win_unique_ptr, m->d_col_to_row, m->d_win_path, w,
-                           static_cast<const char *>(X), ldx * 2, D, n_dparts, Y, y_dt, ldy, y_vec, 0);
-    if ((tile_mask >> kTileMany) & 1) {
-        // row stride of the window's condensed adjacency: its widest window rounded up to whole chunks,
-        // plus 4 floats so that consecutive rows start in different banks
-        const int32_t a_stride = (int32_t)((m->max_unique_many + KW - 1) / KW * KW + 4);
-        hipLaunchKernelGGL((spmm_tile_wave_kernel<DT, HAS_W, NS, true>), grid, dim3(kWave),
-                           (size_t)16 * a_stride * sizeof(float), s, m->n_rows, m->n_win, m->d_row_ptr,
-                           m->d_edge_to_col, m->d_win_unique_ptr, m->d_col_to_row, m->d_win_path, w,
-                           static_cast<const char *>(X), ldx * 2, D, n_dparts, Y, y_dt, ldy, y_vec, a_stride);
+        hipLaunchKernelGGL((spmm_tile_wave_kernel<DT, HAS_W, NS, false, HB>), grid, dim3(kWave), 0, s, m->n_rows,
+                           m->n_win, m->d_row_ptr, m->d_edge_to_col, m->d_win_unique_ptr, m->d_col_to_row,
+                           m->d_win_path, w, static_cast<const char *>(X), ldx * 2, D, n_dparts, Y, y_dt, ldy, y_vec, 0);
+    if constexpr (HB == 1) {
+        if ((tile_mask >> kTileMany) & 1) {
+            // row stride of the window's condensed adjacency: its widest window rounded up to whole chunks,
+            // plus 4 floats so that consecutive rows start in different banks
+            const int32_t a_stride = (int32_t)((m->max_unique_many + KW - 1) / KW * KW + 4);
+            hipLaunchKernelGGL((spmm_tile_wave_kernel<DT, HAS_W, NS, true, 1>), grid, dim3(kWave),
+                               (size_t)16 * a_stride * sizeof(float), s, m->n_rows, m->n_win, m->d_row_ptr,
+                               m->d_edge_to_col, m->d_win_unique_ptr, m->d_col_to_row, m->d_win_path, w,
+                               static_cast<const char *>(X), ldx * 2, D, n_dparts, Y, y_dt, ldy, y_vec, a_stride);
+        }
     }
 }
 
@@ -335,9 +351,12 @@ template <int DT, bool HAS_W>
 void launch_wave_s(const tcg_meta *m, const void *X, int64_t ldx, int32_t D, const float *w, void *Y, int y_dt,
                    int64_t ldy, int tile_mask, hipStream_t s)
 {
-    if (D <= 64) launch_wave<DT, HAS_W, 4>(m, X, ldx, D, w, Y, y_dt, ldy, tile_mask, s);
-    else if (D <= 128) launch_wave<DT, HAS_W, 8>(m, X, ldx, D, w, Y, y_dt, ldy, tile_mask, s);
-    else launch_wave<DT, HAS_W, 16>(m, X, ldx, D, w, Y, y_dt, ldy, tile_mask, s);
+    if (m->win_h == 32) {      // two row blocks per wavefront: half as many feature slices each
+        if (D <= 64) launch_wave<DT, HAS_W, 4, 2>(m, X, ldx, D, w, Y, y_dt, ldy, tile_mask, s);
+        else launch_wave<DT, HAS_W, 8, 2>(m, X, ldx, D, w, Y, y_dt, ldy, tile_mask, s);
+    } else if (D <= 64) launch_wave<DT, HAS_W, 4, 1>(m, X, ldx, D, w, Y, y_dt, ldy, tile_mask, s);
+    else if (D <= 128) launch_wave<DT, HAS_W, 8, 1>(m, X, ldx, D, w, Y, y_dt, ldy, tile_mask, s);
+    else launch_wave<DT, HAS_W, 16, 1>(m, X, ldx, D, w, Y, y_dt, ldy, tile_mask, s);
 }
 
 }  // namespace

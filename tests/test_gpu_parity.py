@@ -124,7 +124,7 @@ def test_sgt_rejects_malformed_csr():
     assert ei.value.status == -1
     meta = tcg.sgt_build(rp, torch.tensor([0, 1, 2], dtype=torch.int32, device=dev()), 8, 8)
     with pytest.raises(tcg.TcgError) as ei:
-        tcg.sgt_set_policy(meta, tcg.POLICY_TILE)                       # tile path needs window height 16
+        tcg.sgt_set_policy(meta, tcg.POLICY_TILE)                       # tile path needs window height 16 or 32
     assert ei.value.status == -1
     meta.free()
 
@@ -313,6 +313,30 @@ def test_rows_that_cannot_be_read_in_16_byte_pieces(x_dtype, D):
     meta.free()
 
 
+@pytest.mark.parametrize("D", [24, 72, 136, 264])
+def test_spmm_tile_path_with_32_row_windows(D):
+    # Windows of 32 rows: two MFMA row blocks per wavefront.  Clustered graph (windows share neighbours),
+    # forced and automatic policy, with and without edge values, ragged last window, bf16 output.
+    c = W.make_config(5, n=64 * 12, d=D, permute=False)
+    full, X = c["csr"], c["X"]
+    n_keep = 64 * 12 - 23                                       # last window has 9 rows
+    g = CSR(n_keep, full.n_cols, full.row_ptr[:n_keep + 1].copy(), full.col_idx[:full.row_ptr[n_keep]].copy())
+    w = np.random.default_rng(D).standard_normal(g.nnz).astype(np.float32)
+    for policy in (tcg.POLICY_TILE, tcg.POLICY_AUTO):
+        st = run_spmm_case(g, X, "bf16", w, policy, TOL_MFMA, H=32)
+        if policy == tcg.POLICY_TILE or D >= 64:
+            assert st["n_tile_windows"] > 0
+        run_spmm_case(g, X, "bf16", None, policy, TOL_F32, H=32)
+    run_spmm_case(g, X.astype(np.float16).astype(np.float32), "f16", None, tcg.POLICY_TILE, TOL_MFMA, H=32, pad=8)
+    run_spmm_case(g, X, "bf16", None, tcg.POLICY_TILE, 2.0 ** -8, H=32, y_dtype=torch.bfloat16)
+    run_sddmm_case(g, W.round_to_bf16(X), "bf16", tcg.POLICY_TILE, TOL_F32, H=32)      # SDDMM keeps to the gather path here
+    # a window with more edges than fit in registers under a forced policy, and a hub window
+    gd = W.dense_block_windows(1024, 5, seed=9)
+    Xd = W.round_to_bf16(W.features_normal(1024, D, 7))
+    run_spmm_case(gd, Xd, "bf16", None, tcg.POLICY_TILE, TOL_F32, H=32)
+    run_spmm_case(gd, Xd, "bf16", None, tcg.POLICY_AUTO, TOL_F32, H=32)
+
+
 def test_spmm_bf16_output():
     c = W.make_config(5, n=64 * 20, d=64, permute=False)
     for policy in (tcg.POLICY_GATHER, tcg.POLICY_TILE):
@@ -335,9 +359,9 @@ def test_spmm_is_deterministic():
 # SDDMM and row softmax
 # ----------------------------------------------------------------------------------------------
 
-def run_sddmm_case(g, X, x_dtype, policy, tol):
+def run_sddmm_case(g, X, x_dtype, policy, tol, H=16):
     rp, ci = upload_csr(g)
-    meta = tcg.sgt_build(rp, ci, 16, 16, n_cols=g.n_cols)
+    meta = tcg.sgt_build(rp, ci, H, 16, n_cols=g.n_cols)
     tcg.sgt_set_policy(meta, policy)
     out = torch.full((g.nnz,), float("nan"), device=dev())
     tcg.sddmm(meta, upload_x(X, x_dtype), out=out)

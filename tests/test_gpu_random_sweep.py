@@ -38,7 +38,7 @@ def random_case(rng):
     D = int(rng.choice([1, 4, 8, 16, 24, 32, 64, 100, 128, 256, 520]))
     x_dtype = str(rng.choice(["f32", "bf16", "f16"]))
     policy = int(rng.choice([tcg.POLICY_AUTO, tcg.POLICY_GATHER, tcg.POLICY_TILE]))
-    if policy == tcg.POLICY_TILE and H != 16:
+    if policy == tcg.POLICY_TILE and H not in (16, 32):
         policy = tcg.POLICY_AUTO
     weighted = bool(rng.random() < 0.5)
     return csr_from_rows(rows, n_cols), H, Wt, D, x_dtype, policy, weighted
