@@ -157,8 +157,8 @@ int csr_transpose_impl(int32_t n_rows, int32_t n_cols, int64_t nnz, const int32_
 int edge_gather_impl(int64_t n, const int32_t *d_perm, const float *d_in, float *d_out, hipStream_t s);
 // Stable least-significant-digit radix sort (4 bits per pass) of n (key, value) pairs by key, keys in
 // [0, 2^bits).  d_vals_in == nullptr stands for the values 0 .. n-1.  The outputs must not overlap the
-// inputs.  d_scratch: device
-// memory of radix_sort_scratch_bytes(n) bytes (0 = n too large).  Asynchronous on s.
+// inputs.  d_scratch: device memory of radix_sort_scratch_bytes(n) bytes (0 = n too large).
+// Asynchronous on s.
 size_t radix_sort_scratch_bytes(int64_t n);
 int radix_sort_pairs(const int32_t *d_keys_in, const int32_t *d_vals_in, int64_t n, int bits, int32_t *d_keys_out,
                      int32_t *d_vals_out, void *d_scratch, hipStream_t s);
