@@ -44,13 +44,22 @@ __device__ __forceinline__ f32x4 mfma16(const uint4 &a, const uint4 &b, f32x4 c)
     }
 }
 
+// Orders the LDS accesses of the wavefront's lanes for the compiler; the hardware already completes a
+// wavefront's LDS operations in program order, so no instruction is emitted.
+__device__ __forceinline__ void wave_lds_order()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
 // KSTEPS = ceil(D / 32) rounded up to a power of two; steps beyond D contribute zeros.
 template <int DT, int KSTEPS>
 __global__ __launch_bounds__(kTileBlock) void sddmm_tile_kernel(
     int32_t n_rows, int64_t n_win, const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ edge_to_col,
     const int32_t *__restrict__ win_unique_ptr, const int32_t *__restrict__ col_to_row,
     const uint8_t *__restrict__ win_path, const char *__restrict__ P, int64_t ldp_bytes,
-    const char *__restrict__ X, int64_t ldx_bytes, int32_t D, float *__restrict__ out)
+    const char *__restrict__ X, int64_t ldx_bytes, int32_t D, float *__restrict__ out, bool skip_few)
 {
     __shared__ float s_e[16 * kEStride];
     __shared__ int32_t s_rp[17];
@@ -58,7 +67,7 @@ __global__ __launch_bounds__(kTileBlock) void sddmm_tile_kernel(
     // neighbouring windows (which share neighbours on clustered graphs) meet in the same L2.
     const int64_t per_die = (n_win + kXcds - 1) / kXcds;
     const int64_t win = (int64_t)(blockIdx.x % kXcds) * per_die + blockIdx.x / kXcds;
-    if (win >= n_win || !win_path[win]) return;
+    if (win >= n_win || !win_path[win] || (skip_few && win_path[win] == kTileFew)) return;
 
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
@@ -120,13 +129,131 @@ __global__ __launch_bounds__(kTileBlock) void sddmm_tile_kernel(
     }
 }
 
+// ---- one wavefront per window (class kTileFew: at most kTileFewEdges edges, kept in registers) ----------
+// No barrier, 1 KB of LDS per window (one 16 x 16 score tile), the B operand of the next tile column is
+// requested before the current one is multiplied, and the window's edges (row, condensed column) wait in
+// registers for their tile column to come by: after each tile column every lane looks its edges up in
+// the tile and writes those that fall into it.
+constexpr int kScoreStride = 17;
+
+template <int DT, int KSTEPS>
+__global__ __launch_bounds__(kWave) void sddmm_tile_wave_kernel(
+    int32_t n_rows, int64_t n_win, const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ edge_to_col,
+    const int32_t *__restrict__ win_unique_ptr, const int32_t *__restrict__ col_to_row,
+    const uint8_t *__restrict__ win_path, const char *__restrict__ P, int64_t ldp_bytes,
+    const char *__restrict__ X, int64_t ldx_bytes, int32_t D, float *__restrict__ out)
+{
+    constexpr int EPT = kTileFewEdges / kWave;
+    __shared__ float s_e[16 * kScoreStride];
+    __shared__ int32_t s_rp[17];
+    const int64_t per_die = (n_win + kXcds - 1) / kXcds;
+    const int64_t win = (int64_t)(blockIdx.x % kXcds) * per_die + blockIdx.x / kXcds;
+    if (blockIdx.x / kXcds >= per_die || win >= n_win || win_path[win] != kTileFew) return;
+
+    const int lane = threadIdx.x;
+    const int n = lane & 15;                    // tile row (A) / tile column (B) of this lane
+    const int kg = lane >> 4;                   // which 16 bytes of every 64-byte K step
+    const int64_t r0 = win * 16;
+    if (lane < 17) {
+        int64_t r = r0 + lane;
+        s_rp[lane] = row_ptr[r < n_rows ? r : n_rows];
+    }
+    const int32_t u0 = win_unique_ptr[win];
+    const int32_t U = win_unique_ptr[win + 1] - u0;
+    const int32_t row_bytes = D * 2;
+    int32_t nid = n < U ? col_to_row[u0 + n] : -1;              // neighbour of tile column 0
+    int32_t nid_nxt = 16 + n < U ? col_to_row[u0 + 16 + n] : -1;
+
+    uint4 a[KSTEPS];
+    {
+        const int64_t row = r0 + n;
+#pragma unroll
+        for (int kk = 0; kk < KSTEPS; ++kk) {
+            const int32_t off = kk * 64 + kg * 16;
+            a[kk] = make_uint4(0, 0, 0, 0);
+            if (row < n_rows && off < row_bytes) a[kk] = *reinterpret_cast<const uint4 *>(P + row * ldp_bytes + off);
+        }
+    }
+    uint4 b[KSTEPS];
+    auto fetch = [&](int32_t node) {
+#pragma unroll
+        for (int kk = 0; kk < KSTEPS; ++kk) {
+            const int32_t off = kk * 64 + kg * 16;
+            b[kk] = make_uint4(0, 0, 0, 0);
+            if (node >= 0 && off < row_bytes) b[kk] = *reinterpret_cast<const uint4 *>(X + (int64_t)node * ldx_bytes + off);
+        }
+    };
+    fetch(nid);
+
+    wave_lds_order();
+    const int32_t lo = s_rp[0], hi = s_rp[16];
+    // the window's edges: (score-tile row offset << 16 | condensed column); larger windows (only a forced
+    // policy puts them here) re-read their edges for every tile column
+    const bool edges_in_regs = hi - lo <= EPT * kWave;
+    int32_t e_code[EPT];
+#pragma unroll
+    for (int q = 0; q < EPT; ++q) {
+        const int32_t e = lo + lane + q * kWave;
+        e_code[q] = -1;
+        if (edges_in_regs && e < hi) {
+            int r = 0;
+#pragma unroll
+            for (int step = 8; step > 0; step >>= 1)
+                if (s_rp[r + step] <= e) r += step;
+            e_code[q] = (r * kScoreStride) << 16 | edge_to_col[e];
+        }
+    }
+
+    for (int32_t c0 = 0; c0 < U; c0 += 16) {
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int kk = 0; kk < KSTEPS; ++kk) acc = mfma16<DT>(a[kk], b[kk], acc);
+        // next tile column: its rows go out now, its successor's ids with them
+        nid = nid_nxt;
+        if (c0 + 16 < U) {
+            fetch(nid);
+            nid_nxt = c0 + 32 + n < U ? col_to_row[u0 + c0 + 32 + n] : -1;
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r) s_e[(4 * kg + r) * kScoreStride + n] = acc[r];
+        wave_lds_order();
+        // StoreSparse
+        if (edges_in_regs) {
+#pragma unroll
+            for (int q = 0; q < EPT; ++q) {
+                const int32_t cc = (e_code[q] & 0xFFFF) - c0;
+                if (e_code[q] >= 0 && cc >= 0 && cc < 16) out[lo + lane + q * kWave] = s_e[(e_code[q] >> 16) + cc];
+            }
+        } else {
+            for (int32_t e = lo + lane; e < hi; e += kWave) {
+                const int32_t cc = edge_to_col[e] - c0;
+                if (cc >= 0 && cc < 16) {
+                    int r = 0;
+#pragma unroll
+                    for (int step = 8; step > 0; step >>= 1)
+                        if (s_rp[r + step] <= e) r += step;
+                    out[e] = s_e[r * kScoreStride + cc];
+                }
+            }
+        }
+        wave_lds_order();
+    }
+}
+
 template <int DT, int KSTEPS>
 void launch(const tcg_meta *m, const void *P, int64_t ldp, const void *X, int64_t ldx, int32_t D, float *out,
             hipStream_t s)
 {
-    hipLaunchKernelGGL((sddmm_tile_kernel<DT, KSTEPS>), dim3((unsigned)(kXcds * ceil_div(m->n_win, kXcds))), dim3(kTileBlock), 0, s,
-                       m->n_rows, m->n_win, m->d_row_ptr, m->d_edge_to_col, m->d_win_unique_ptr, m->d_col_to_row,
-                       m->d_win_path, static_cast<const char *>(P), ldp * 2, static_cast<const char *>(X), ldx * 2, D, out);
+    const dim3 grid((unsigned)(kXcds * ceil_div(m->n_win, kXcds)));
+    const bool few = m->n_tile_win > m->n_tile_many;
+    if (few)
+        hipLaunchKernelGGL((sddmm_tile_wave_kernel<DT, KSTEPS>), grid, dim3(kWave), 0, s, m->n_rows, m->n_win,
+                           m->d_row_ptr, m->d_edge_to_col, m->d_win_unique_ptr, m->d_col_to_row, m->d_win_path,
+                           static_cast<const char *>(P), ldp * 2, static_cast<const char *>(X), ldx * 2, D, out);
+    if (m->n_tile_many > 0)
+        hipLaunchKernelGGL((sddmm_tile_kernel<DT, KSTEPS>), grid, dim3(kTileBlock), 0, s, m->n_rows, m->n_win,
+                           m->d_row_ptr, m->d_edge_to_col, m->d_win_unique_ptr, m->d_col_to_row, m->d_win_path,
+                           static_cast<const char *>(P), ldp * 2, static_cast<const char *>(X), ldx * 2, D, out, true);
 }
 
 template <int DT>
