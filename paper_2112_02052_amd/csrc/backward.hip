@@ -221,6 +221,7 @@ int csr_transpose_impl(int32_t n_rows, int32_t n_cols, int64_t nnz, const int32_
     // Scratch: sorted keys plus the sort's own workspace; the caller's perm array receives the values.
     const size_t arr = ((size_t)nnz * 4 + 255) & ~(size_t)255;
     PoolBuf buf;
+    buf.s = s;
     TCG_TRY(pool_alloc(&buf.p, arr + radix_sort_scratch_bytes(nnz)));
     char *base = static_cast<char *>(buf.p);
     int32_t *keys_sorted = reinterpret_cast<int32_t *>(base);

@@ -119,10 +119,18 @@ inline int64_t plan_grid(const int32_t *h_lane_tab, int groups_per_block)
 
 // Exclusive prefix sum of n int32 values on the device; out may alias in.  out has n + 1
 // entries: out[n] is the total (sums are computed in int32; callers bound the total beforehand).
-// A pooled device buffer that goes back to the pool when the scope ends (the stream must be idle by then).
+// A pooled device buffer that goes back to the pool when the scope ends.  The stream that used it is
+// drained first (a no-op on the normal paths, which synchronise themselves; it matters when an error
+// return leaves kernels in flight).
 struct PoolBuf {
     void *p = nullptr;
-    ~PoolBuf() { if (p) pool_free(p); }
+    hipStream_t s = nullptr;
+    ~PoolBuf()
+    {
+        if (!p) return;
+        (void)hipStreamSynchronize(s);
+        pool_free(p);
+    }
 };
 
 // d_work: device scratch of scan_workspace_elems(n) int32.

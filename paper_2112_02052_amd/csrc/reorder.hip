@@ -234,6 +234,7 @@ int reorder_rows_impl(int32_t n, int64_t nnz, const int32_t *d_row_ptr, const in
     const size_t long_bytes = ((size_t)max_long * 4 + 255) & ~(size_t)255;
     // parent, label a/b, sorted keys, values of the first sort, long-row list, counters, sort scratch
     PoolBuf buf;
+    buf.s = s;
     TCG_TRY(pool_alloc(&buf.p, 6 * arr + long_bytes + 256 + radix_sort_scratch_bytes(n)));
     char *base = static_cast<char *>(buf.p);
     int32_t *parent = reinterpret_cast<int32_t *>(base);
@@ -288,6 +289,7 @@ int csr_permute_impl(int32_t n, int64_t nnz, const int32_t *d_row_ptr, const int
     const size_t arr = ((size_t)n * 4 + 255) & ~(size_t)255;
     const size_t scan_bytes = (size_t)scan_workspace_elems(n) * 4;
     PoolBuf buf;
+    buf.s = s;
     TCG_TRY(pool_alloc(&buf.p, 2 * arr + 256 + scan_bytes));
     char *base = static_cast<char *>(buf.p);
     int32_t *inv = reinterpret_cast<int32_t *>(base);

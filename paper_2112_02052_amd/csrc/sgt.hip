@@ -756,9 +756,17 @@ struct Arena {
     }
 };
 
-struct ScopedFree {  // returns the block to the pool on scope exit (the stream is idle by then)
+// Returns the block to the pool on scope exit.  On the normal path the stream is idle by then; an early
+// error return may leave kernels in flight that still use the block, so the stream is drained first.
+struct ScopedFree {
     void *p = nullptr;
-    ~ScopedFree() { if (p) pool_free(p); }
+    hipStream_t s = nullptr;
+    ~ScopedFree()
+    {
+        if (!p) return;
+        (void)hipStreamSynchronize(s);
+        pool_free(p);
+    }
 };
 
 }  // namespace
@@ -848,7 +856,7 @@ int sgt_build_impl(tcg_meta *m, int validate, hipStream_t s)
     tmp.want(scan_elems * 4);         // scan workspace
     tmp.want(16 * 4);                 // class counts + validation flag
     TCG_TRY(tmp.commit());
-    ScopedFree tmp_guard{tmp.base};
+    ScopedFree tmp_guard{tmp.base, s};
     int32_t *tmp_clean = tmp.take<int32_t>(nnz);
     int32_t *win_unique = tmp.take<int32_t>(n_win + 1);
     int32_t *lists = tmp.take<int32_t>(4 * n_win);
@@ -939,7 +947,7 @@ int sgt_build_impl(tcg_meta *m, int validate, hipStream_t s)
                            m->win_h, lists + 2 * n_win, m->d_row_ptr, m->d_col_idx, m->d_edge_to_col, tmp_clean,
                            win_unique);
     TCG_TRY(launch_status("sgt_window_lds_kernel"));
-    ScopedFree bitmap_guard;
+    ScopedFree bitmap_guard{nullptr, s};
     const int64_t n_words_all = ceil_div(m->n_cols, 32);
     if (h_cls[3] > 0 && lds_bitmap_bytes(n_words_all) <= kLdsBitmapMax) {
         const size_t lds = lds_bitmap_bytes(n_words_all);
@@ -995,7 +1003,7 @@ int sgt_build_impl(tcg_meta *m, int validate, hipStream_t s)
         ptmp.want(pscan_elems * 4);
         TCG_TRY(ptmp.commit());
     }
-    ScopedFree ptmp_guard{ptmp.base};
+    ScopedFree ptmp_guard{ptmp.base, s};
     if (n > 0) {
         int32_t *row_o = m->d_seg_row, *ebeg_o = m->d_seg_ebeg, *dst_o = m->d_seg_dst;
         if (ordered) {
