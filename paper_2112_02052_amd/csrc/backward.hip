@@ -118,23 +118,54 @@ __global__ __launch_bounds__(kThreads) void softmax_bwd_kernel(int32_t n_rows, c
     for (int32_t k = b + lane; k < e; k += kWave) dv[k] = p[k] * (dp[k] - dot);
 }
 
-__global__ __launch_bounds__(kThreads) void softmax_bwd_long_kernel(const int32_t *__restrict__ long_row,
-                                                                    const int32_t *__restrict__ row_ptr,
-                                                                    const float *p, const float *dp, float *dv)
+// Long rows: one workgroup per row, 256 of its threads for rows up to kLongRowWide entries and all 1024
+// beyond; four values per thread in flight.
+constexpr int kLongThreads = 1024;
+constexpr int kLongRowWide = 4096;
+
+__global__ __launch_bounds__(kLongThreads) void softmax_bwd_long_kernel(const int32_t *__restrict__ long_row,
+                                                                        const int32_t *__restrict__ row_ptr,
+                                                                        const float *p, const float *dp, float *dv)
 {
-    __shared__ float s_red[kThreads / kWave];
+    __shared__ float s_red[kLongThreads / kWave];
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
     const int32_t row = long_row[blockIdx.x];
     const int32_t b = row_ptr[row], e = row_ptr[row + 1];
+    const int nthr = e - b > kLongRowWide ? kLongThreads : kThreads;
     float dot = 0.f;
-    for (int32_t k = b + threadIdx.x; k < e; k += kThreads) dot = fmaf(p[k], dp[k], dot);
+    if ((int)threadIdx.x < nthr) {
+        for (int32_t k0 = b + threadIdx.x; k0 < e; k0 += 4 * nthr) {
+            float a[4], c[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const bool ok = k0 + u * nthr < e;
+                a[u] = ok ? p[k0 + u * nthr] : 0.f;
+                c[u] = ok ? dp[k0 + u * nthr] : 0.f;
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) dot = fmaf(a[u], c[u], dot);
+        }
+    }
     dot = wave_sum(dot);
     if (lane == 0) s_red[wave] = dot;
     __syncthreads();
     dot = 0.f;
 #pragma unroll
-    for (int i = 0; i < kThreads / kWave; ++i) dot += s_red[i];
-    for (int32_t k = b + threadIdx.x; k < e; k += kThreads) dv[k] = p[k] * (dp[k] - dot);
+    for (int i = 0; i < kLongThreads / kWave; ++i) dot += s_red[i];
+    if ((int)threadIdx.x < nthr) {
+        for (int32_t k0 = b + threadIdx.x; k0 < e; k0 += 4 * nthr) {
+            float a[4], c[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const bool ok = k0 + u * nthr < e;
+                a[u] = ok ? p[k0 + u * nthr] : 0.f;
+                c[u] = ok ? dp[k0 + u * nthr] : 0.f;
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                if (k0 + u * nthr < e) dv[k0 + u * nthr] = a[u] * (c[u] - dot);
+        }
+    }
 }
 
 }  // namespace
@@ -146,7 +177,7 @@ int row_softmax_backward_impl(const tcg_meta *m, const float *d_p, const float *
                        m->n_rows, m->d_row_ptr, d_p, d_dp, d_dv);
     TCG_TRY(launch_status("softmax_bwd_kernel"));
     if (m->n_long > 0) {
-        hipLaunchKernelGGL(softmax_bwd_long_kernel, dim3((unsigned)m->n_long), dim3(kThreads), 0, s, m->d_long_row,
+        hipLaunchKernelGGL(softmax_bwd_long_kernel, dim3((unsigned)m->n_long), dim3(kLongThreads), 0, s, m->d_long_row,
                            m->d_row_ptr, d_p, d_dp, d_dv);
         TCG_TRY(launch_status("softmax_bwd_long_kernel"));
     }

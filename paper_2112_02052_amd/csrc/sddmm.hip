@@ -197,34 +197,61 @@ __global__ __launch_bounds__(kBlock) void row_softmax_kernel(int32_t n_rows, con
     if (b + kWave + lane < e) out[b + kWave + lane] = x1 * inv;
 }
 
-// Rows longer than kSegLen (the gather plan's list of split rows): one workgroup per row.
-__global__ __launch_bounds__(kBlock) void row_softmax_long_kernel(const int32_t *__restrict__ long_row,
-                                                                  const int32_t *__restrict__ row_ptr,
-                                                                  const float *in, float *out)
+// Rows longer than kSegLen (the gather plan's list of split rows): one workgroup per row, 256 of its
+// threads for rows up to kLongRowWide entries and all 1024 beyond (hub rows of power-law graphs would
+// otherwise set the kernel's duration).  Two passes: running maximum and rescaled sum of exponentials
+// (four values per thread in flight), then the normalised values.
+constexpr int kLongThreads = 1024;
+constexpr int kLongRowWide = 4096;
+
+__global__ __launch_bounds__(kLongThreads) void row_softmax_long_kernel(const int32_t *__restrict__ long_row,
+                                                                        const int32_t *__restrict__ row_ptr,
+                                                                        const float *in, float *out)
 {
-    __shared__ float s_red[kBlock / kWave];
+    __shared__ float s_m[kLongThreads / kWave], s_s[kLongThreads / kWave];
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
     const int32_t row = long_row[blockIdx.x];
     const int32_t b = row_ptr[row], e = row_ptr[row + 1];
-    float m = -INFINITY;
-    for (int32_t k = b + threadIdx.x; k < e; k += kBlock) m = fmaxf(m, in[k]);
-    m = wave_max(m);
-    if (lane == 0) s_red[wave] = m;
-    __syncthreads();
-    m = s_red[0];
+    const int nthr = e - b > kLongRowWide ? kLongThreads : kBlock;
+    float m = -INFINITY, s = 0.f;
+    if ((int)threadIdx.x < nthr) {
+        for (int32_t k0 = b + threadIdx.x; k0 < e; k0 += 4 * nthr) {
+            float v[4];
 #pragma unroll
-    for (int i = 1; i < kBlock / kWave; ++i) m = fmaxf(m, s_red[i]);
-    __syncthreads();
-    float s = 0.f;
-    for (int32_t k = b + threadIdx.x; k < e; k += kBlock) s += expf(in[k] - m);
-    s = wave_sum(s);
-    if (lane == 0) s_red[wave] = s;
-    __syncthreads();
-    s = 0.f;
+            for (int u = 0; u < 4; ++u) v[u] = k0 + u * nthr < e ? in[k0 + u * nthr] : -INFINITY;
+            const float mb = fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3]));
+            if (mb > m) {
+                s *= expf(m - mb);          // exp(-inf) = 0 on the first batch
+                m = mb;
+            }
 #pragma unroll
-    for (int i = 0; i < kBlock / kWave; ++i) s += s_red[i];
-    const float inv = 1.f / s;
-    for (int32_t k = b + threadIdx.x; k < e; k += kBlock) out[k] = expf(in[k] - m) * inv;
+            for (int u = 0; u < 4; ++u) s += expf(v[u] - m);
+        }
+    }
+    const float wm = wave_max(m);
+    const float ws = wave_sum(m > -INFINITY ? s * expf(m - wm) : 0.f);
+    if (lane == 0) {
+        s_m[wave] = wm;
+        s_s[wave] = ws;
+    }
+    __syncthreads();
+    float M = -INFINITY;
+#pragma unroll
+    for (int i = 0; i < kLongThreads / kWave; ++i) M = fmaxf(M, s_m[i]);
+    float S = 0.f;
+#pragma unroll
+    for (int i = 0; i < kLongThreads / kWave; ++i) S += s_m[i] > -INFINITY ? s_s[i] * expf(s_m[i] - M) : 0.f;
+    const float inv = 1.f / S;
+    if ((int)threadIdx.x < nthr) {
+        for (int32_t k0 = b + threadIdx.x; k0 < e; k0 += 4 * nthr) {
+            float v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) v[u] = k0 + u * nthr < e ? in[k0 + u * nthr] : 0.f;
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                if (k0 + u * nthr < e) out[k0 + u * nthr] = expf(v[u] - M) * inv;
+        }
+    }
 }
 
 template <int DT, int G, int NCH, int PB = 16>
@@ -327,7 +354,7 @@ int row_softmax_impl(const tcg_meta *m, const float *d_in, float *d_out, hipStre
     hipLaunchKernelGGL(row_softmax_kernel, dim3(grid), dim3(kBlock), 0, s, m->n_rows, m->d_row_ptr, d_in, d_out);
     TCG_TRY(launch_status("row_softmax_kernel"));
     if (m->n_long > 0) {
-        hipLaunchKernelGGL(row_softmax_long_kernel, dim3((unsigned)m->n_long), dim3(kBlock), 0, s, m->d_long_row,
+        hipLaunchKernelGGL(row_softmax_long_kernel, dim3((unsigned)m->n_long), dim3(kLongThreads), 0, s, m->d_long_row,
                            m->d_row_ptr, d_in, d_out);
         TCG_TRY(launch_status("row_softmax_long_kernel"));
     }
