@@ -431,3 +431,33 @@ def test_row_softmax_and_attention_chain():
     torch.cuda.synchronize()
     assert torch.equal(q, p)
     meta.free()
+
+
+def test_calls_follow_the_current_stream():
+    # The binding passes torch's current stream: the whole path on a side stream must give the same bits
+    # as on the default stream, and the work must really be enqueued there (the side stream's event
+    # completes only after the library's kernels).
+    c = W.make_config(4, n=30000, d=64)
+    g, X = c["csr"], c["X"]
+    rp, ci = upload_csr(g)
+    Xd = upload_x(X, "f32")
+    meta0 = tcg.sgt_build(rp, ci, 16, 8)
+    Y0 = tcg.spmm(meta0, Xd)
+    e0 = tcg.sddmm(meta0, Xd)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        meta1 = tcg.sgt_build(rp, ci, 16, 8)
+        Y1 = tcg.spmm(meta1, Xd)
+        e1 = tcg.sddmm(meta1, Xd)
+        p1 = tcg.row_softmax(meta1, e1)
+        done = torch.cuda.Event()
+        done.record(side)
+    done.synchronize()
+    assert torch.equal(Y0, Y1) and torch.equal(e0, e1)
+    assert np.array_equal(tcg.sgt_export(meta0)["edge_to_col"].cpu().numpy(), tcg.sgt_export(meta1)["edge_to_col"].cpu().numpy())
+    S = oracle.row_softmax(g.row_ptr, e1.cpu().numpy().astype(np.float64))
+    assert norm_err(p1.cpu().numpy(), S) <= TOL_F32
+    meta0.free()
+    meta1.free()
