@@ -258,7 +258,7 @@ def main():
     b_sddmm = algorithmic_bytes_sddmm(N, nnz, U, n_win, D, sx[feat])
     achieved = b_spmm / (spmm_ms * 1e-3) / 1e9
     tile_share = plan["nnz_tile"] / max(nnz, 1) if feat != "f32" else 0.0
-    kernel = ("tcg_spmm (spmm_tile_kernel)" if tile_share > 0.5
+    kernel = ("tcg_spmm (spmm_tile_direct_kernel)" if tile_share > 0.5
               else "tcg_spmm (spmm_gather_kernel + spmm_reduce_long_kernel)")
 
     out = {
@@ -289,6 +289,10 @@ def main():
                      "algorithmic_bytes": b_spmm,
                      # brackets: every X row once (a lower bound for any method) / once per stored entry (no reuse)
                      "compulsory_bytes": b_spmm - U * D * sx[feat] + g.n_cols * D * sx[feat],
+                     # the same launch priced with the compulsory bytes: what the memory really has to deliver when
+                     # the window-unique rows of neighbouring windows are served by the cache
+                     "frac_compulsory": (b_spmm - U * D * sx[feat] + g.n_cols * D * sx[feat])
+                                        / (spmm_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                      "csr_gather_bytes": algorithmic_bytes_spmm(N, nnz, nnz, n_win, D, sx[feat], 4, weighted)},
         "generate_s": gen_s,
     }

@@ -113,6 +113,21 @@ __device__ __forceinline__ void store_elem(void *base, int64_t idx, int dt, floa
     else static_cast<uint16_t *>(base)[idx] = __half_as_ushort(__float2half_rn(v));
 }
 
+// Streaming stores for outputs that the kernel never reads back (the result matrix of an SpMM): marked
+// non-temporal, they do not claim L2 lines that the gathered neighbour rows would otherwise keep.
+__device__ __forceinline__ void stream_store(float *p, float a, float b, float c, float d)
+{
+    typedef float f32x4_t __attribute__((ext_vector_type(4)));
+    const f32x4_t v = {a, b, c, d};
+    __builtin_nontemporal_store(v, reinterpret_cast<f32x4_t *>(p));
+}
+__device__ __forceinline__ void stream_store(uint16_t *p, uint32_t lo, uint32_t hi)
+{
+    typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+    const u32x2_t v = {lo, hi};
+    __builtin_nontemporal_store(v, reinterpret_cast<u32x2_t *>(p));
+}
+
 // Sums UNROLL per-lane partials across the G lanes of a group.  On return, lane j (j < UNROLL,
 // position inside the group) holds the total of partial j -- if G >= UNROLL; otherwise every
 // lane holds all totals in p[].  Must be executed by all lanes of the group.

@@ -125,8 +125,7 @@ __global__ __launch_bounds__(kBlock) void spmm_gather_kernel(
         } else if (y_vec) {
             float *p = static_cast<float *>(Y) + (int64_t)row * ldy + d0;
 #pragma unroll
-            for (int k = 0; k < VEC; k += 4)
-                *reinterpret_cast<float4 *>(p + k) = make_float4(acc[c][k], acc[c][k + 1], acc[c][k + 2], acc[c][k + 3]);
+            for (int k = 0; k < VEC; k += 4) stream_store(p + k, acc[c][k], acc[c][k + 1], acc[c][k + 2], acc[c][k + 3]);
         } else {
 #pragma unroll
             for (int k = 0; k < VEC; ++k) store_elem(Y, (int64_t)row * ldy + d0 + k, y_dt, acc[c][k]);

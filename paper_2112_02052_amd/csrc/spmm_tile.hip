@@ -6,25 +6,25 @@
 //   InitSparse  the 16 x KW slice of the condensed adjacency is built in LDS in fp32 from the
 //               window's edges and edge_to_col (repeated entries add up), then rounded to the
 //               feature type when it is loaded as the MFMA A operand;
-//   FetchDense  the KW neighbour rows named by col_to_row are copied into LDS with 16-byte
-//               coalesced loads -- each unique neighbour is fetched once per window, which is
-//               the traffic reduction SGT exists for;
-//   TCcompute   v_mfma_f32_16x16x16 (bf16 or f16 inputs, fp32 accumulate), one per 16-column slice
-//               of the feature dimension, all sharing the A operand;
-//   StoreDense  after the last chunk the accumulators go through LDS and are written to the
-//               window's rows of Y as whole 16-byte pieces.
+//   FetchDense  the KW neighbour rows named by col_to_row are fetched with coalesced loads -- each
+//               unique neighbour once per window, which is the traffic reduction SGT exists for;
+//   TCcompute   v_mfma_f32_16x16x16 (bf16 or f16 inputs, fp32 accumulate), all sharing the A operand;
+//   StoreDense  after the last chunk the accumulators are written to the window's rows of Y in
+//               16-byte pieces, as streaming stores.
+// Two kernels implement this.  spmm_tile_direct_kernel (rows of more than 64 features) loads the
+// neighbour rows straight into the B operand registers and stores straight from the accumulators;
+// spmm_tile_wave_kernel (narrow rows, 32-row windows) stages the rows and the finished tile in LDS.
 // Differences from the paper's kernel: the K extent of a tile is 16 (bf16/f16 MFMA) instead of 8
 // (TF-32 WMMA); the column -> node map comes straight from SGT's col_to_row instead of being
-// rebuilt per block; the B operand is transposed by the LDS read itself (ds_read_b64_tr_b16), so
-// the staged rows keep their row-major layout; and a window belongs to one wavefront instead of a
-// block of warps that split the feature dimension.  A wavefront's LDS operations complete in
-// program order, so the kernel has no barrier at all, and with about 10 KB of LDS per window a
-// compute unit keeps twelve windows in flight, which is what hides the chain of dependent loads
-// of a window (row pointers -> edge list and neighbour ids -> neighbour rows).  The neighbour
-// rows of chunk c + 1 are requested as soon as the registers of chunk c have been written to LDS,
-// their ids one chunk earlier still.  Measured on MI355X this is faster than a 256-thread
-// workgroup per window with 32-column chunks; the counters show the path bound by the latency of
-// L1 -> L2 read requests, not by the matrix cores.
+// rebuilt per block; no transposition through shared memory is needed for the B operand (a permuted
+// assignment of features to MFMA columns in the direct kernel, the transposing LDS read
+// ds_read_b64_tr_b16 in the other); and a window belongs to one wavefront instead of a block of
+// warps that split the feature dimension.  A wavefront's LDS operations complete in program
+// order, so the kernels have no barrier at all, and a compute unit keeps twelve to sixteen windows
+// in flight, which is what hides the chain of dependent loads of a window (row pointers -> edge
+// list and neighbour ids -> neighbour rows).  The neighbour rows of chunk c + 1 are requested as
+// soon as chunk c has been consumed, their ids one chunk earlier still.  The counters show the path
+// bound by the memory side (row fetches through L2, result stores), not by the matrix cores.
 #include "common.h"
 #include "devutil.h"
 
@@ -90,6 +90,28 @@ __device__ __forceinline__ f32x4 mfma16k16(const uint2 &a, const uint2 &b, f32x4
     }
 }
 
+// Four consecutive outputs of a row: one 16-byte (fp32) or 8-byte (16-bit) store when aligned, else scalars.
+__device__ __forceinline__ void store4(void *Y, int y_dt, int64_t o, const float4 &v, bool y_vec)
+{
+    if (y_dt == TCG_F32) {
+        float *y = static_cast<float *>(Y) + o;
+        if (y_vec) stream_store(y, v.x, v.y, v.z, v.w);
+        else { y[0] = v.x; y[1] = v.y; y[2] = v.z; y[3] = v.w; }
+    } else {
+        uint16_t *y = static_cast<uint16_t *>(Y) + o;
+        uint2 pk;
+        if (y_dt == TCG_BF16) {
+            pk.x = (uint32_t)f32_to_bf16_bits(v.x) | ((uint32_t)f32_to_bf16_bits(v.y) << 16);
+            pk.y = (uint32_t)f32_to_bf16_bits(v.z) | ((uint32_t)f32_to_bf16_bits(v.w) << 16);
+        } else {
+            pk.x = (uint32_t)__half_as_ushort(__float2half_rn(v.x)) | ((uint32_t)__half_as_ushort(__float2half_rn(v.y)) << 16);
+            pk.y = (uint32_t)__half_as_ushort(__float2half_rn(v.z)) | ((uint32_t)__half_as_ushort(__float2half_rn(v.w)) << 16);
+        }
+        if (y_vec) stream_store(y, pk.x, pk.y);
+        else { y[0] = (uint16_t)pk.x; y[1] = (uint16_t)(pk.x >> 16); y[2] = (uint16_t)pk.y; y[3] = (uint16_t)(pk.y >> 16); }
+    }
+}
+
 // NS: 16-column slices of D per wavefront; a window with D > 16 * NS is shared by n_dparts wavefronts.
 // FULL_A = false serves the windows of class kTileFew (at most kTileFewEdges edges, kept in registers;
 // the 16 x KW slice of the condensed adjacency is rebuilt for every chunk).  FULL_A = true serves class
@@ -105,7 +127,7 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(3))) void
     const int32_t *__restrict__ win_unique_ptr, const int32_t *__restrict__ col_to_row,
     const uint8_t *__restrict__ win_path, const float *__restrict__ w, const char *__restrict__ X,
     int64_t ldx_bytes, int32_t D, int32_t n_dparts, void *__restrict__ Y, int y_dt, int64_t ldy, bool y_vec,
-    int32_t a_stride)
+    int32_t a_stride, bool skip_small)
 {
     static_assert(!(FULL_A && HB != 1), "the whole-window adjacency variant handles 16-row windows");
     constexpr int H = 16 * HB;
@@ -142,6 +164,7 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(3))) void
     int32_t nid_cur = kk < U ? col_to_row[u0 + kk] : -1;
     int32_t nid_nxt = KW + kk < U ? col_to_row[u0 + KW + kk] : -1;
     const int32_t lo = s_rp[0], hi = s_rp[H];
+    if (skip_small && hi - lo <= kTileFewEdges) return;        // taken by the direct kernel
     const int32_t n_slices = (Dp + 15) / 16;
 
     // FetchDense mapping: 2 * NS lanes cover one row part with 16-byte pieces, so one pass of the
@@ -302,7 +325,7 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(3))) void
             const int64_t o = row * ldy + d0 + col;
             if (y_dt == TCG_F32) {
                 float *y = static_cast<float *>(Y) + o;
-                if (y_vec) *reinterpret_cast<float4 *>(y) = v;
+                if (y_vec) stream_store(y, v.x, v.y, v.z, v.w);
                 else { y[0] = v.x; y[1] = v.y; y[2] = v.z; y[3] = v.w; }
             } else {
                 uint16_t *y = static_cast<uint16_t *>(Y) + o;
@@ -314,12 +337,205 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(3))) void
                     pk.x = (uint32_t)__half_as_ushort(__float2half_rn(v.x)) | ((uint32_t)__half_as_ushort(__float2half_rn(v.y)) << 16);
                     pk.y = (uint32_t)__half_as_ushort(__float2half_rn(v.z)) | ((uint32_t)__half_as_ushort(__float2half_rn(v.w)) << 16);
                 }
-                if (y_vec) *reinterpret_cast<uint2 *>(y) = pk;
+                if (y_vec) stream_store(y, pk.x, pk.y);
                 else { y[0] = (uint16_t)pk.x; y[1] = (uint16_t)(pk.x >> 16); y[2] = (uint16_t)pk.y; y[3] = (uint16_t)(pk.y >> 16); }
             }
         }
         wave_lds_order();
     }
+}
+
+// ---- neighbour rows straight into the MFMA operand registers (16-row windows of class kTileFew) --------
+// The B operand of v_mfma_f32_16x16x16 wants, per lane (n = lane % 16, q = lane / 16), the four values
+// B[4q .. 4q+3][n]: four NEIGHBOURS, one feature.  Memory has the features of a neighbour contiguous, which
+// is why the kernel above stages the rows in LDS and reads them back transposed.  But nothing says that
+// column n of the tile must be feature n: here lane (n, q) loads 8 bytes = the 4 features 4n .. 4n+3 of
+// each of its four neighbour rows 4q .. 4q+3 (16 lanes cover 128 contiguous bytes of a row) and issues four
+// MFMAs, the m-th of which takes element m of the four loaded pieces (two byte-permute instructions
+// assemble the operand).  MFMA m then computes, in its column n, feature 4n + m: across the four
+// accumulators a lane ends up with 4 CONSECUTIVE features of its four output rows, one 16-byte store per
+// row with 16 lanes writing 256 contiguous bytes -- no LDS staging on the way in, none on the way out,
+// no barrier.  A second set of pieces, 64 features further on, fills a block of 128 features.  LDS
+// only holds the 16 x 16 slice of the condensed adjacency (the A operand) and the row pointers.
+// NFB: blocks of 128 features per wavefront (a wider D is split over n_dparts wavefronts).
+template <int DT, bool HAS_W, int NFB, bool FULL_A>
+__global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(4))) void spmm_tile_direct_kernel(
+    int32_t n_rows, int64_t n_win, const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ edge_to_col,
+    const int32_t *__restrict__ win_unique_ptr, const int32_t *__restrict__ col_to_row,
+    const uint8_t *__restrict__ win_path, const float *__restrict__ w, const char *__restrict__ X,
+    int64_t ldx_bytes, int32_t D, int32_t n_dparts, void *__restrict__ Y, int y_dt, int64_t ldy, bool y_vec,
+    int32_t a_stride)
+{
+    constexpr int EPT = kTileFewEdges / kWave;
+    extern __shared__ __align__(16) float a_full[];                    // FULL_A: 16 x a_stride
+    __shared__ __align__(16) float a_slice[FULL_A ? 4 : 16 * kAStrideW];
+    __shared__ int32_t s_rp[17];
+    __shared__ int32_t s_code[FULL_A ? 1 : kTileFewEdges];             // per edge: slice row offset << 16 | condensed column
+    __shared__ float s_val[HAS_W && !FULL_A ? kTileFewEdges : 1];      // per edge: its value
+    float *a32 = FULL_A ? a_full : a_slice;
+    const int32_t as = FULL_A ? a_stride : kAStrideW;
+
+    const int64_t per_die = (n_win + kXcds - 1) / kXcds;
+    const int64_t j = blockIdx.x / kXcds;
+    const int64_t win = (int64_t)(blockIdx.x % kXcds) * per_die + j / n_dparts;
+    if (j / n_dparts >= per_die || win >= n_win || win_path[win] != (FULL_A ? kTileMany : kTileFew)) return;
+    const int32_t d0 = (int32_t)(j % n_dparts) * (NFB * 128);     // first feature column of this part
+    const int32_t Dp = min(NFB * 128, D - d0);
+
+    const int lane = threadIdx.x;
+    const int n = lane & 15, q = lane >> 4;
+    const int64_t r0 = win * 16;
+    if (lane < 17) {
+        int64_t r = r0 + lane;
+        s_rp[lane] = row_ptr[r < n_rows ? r : n_rows];
+    }
+    wave_lds_order();
+    const int32_t u0 = win_unique_ptr[win];
+    const int32_t U = win_unique_ptr[win + 1] - u0;
+    // ids of the neighbours of chunks 0 and 1 (lane k < 16 holds row k of the chunk)
+    int32_t nid_cur = n < U ? col_to_row[u0 + n] : -1;
+    int32_t nid_nxt = KW + n < U ? col_to_row[u0 + KW + n] : -1;
+    const int32_t lo = s_rp[0], hi = s_rp[16];
+    if (!FULL_A && hi - lo > kTileFewEdges) return;    // only a forced policy puts such a window into this class
+
+    // FetchDense: chunk rows 4q .. 4q+3; of every block of 128 features the two 8-byte pieces
+    // 4n .. 4n+3 and 64 + 4n .. 64 + 4n+3 (16 lanes cover 128 contiguous bytes of a row per load)
+    const char *Xp = X + (int64_t)d0 * 2 + n * 8;
+    uint2 xr[NFB][2][4];
+    auto fetch = [&](int32_t nid) {
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+            const int32_t node = __shfl(nid, 4 * q + jj);
+#pragma unroll
+            for (int fb = 0; fb < NFB; ++fb)
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    xr[fb][h][jj] = make_uint2(0, 0);
+                    if (node >= 0 && fb * 128 + h * 64 + 4 * n < Dp)
+                        xr[fb][h][jj] =
+                            *reinterpret_cast<const uint2 *>(Xp + (int64_t)node * ldx_bytes + fb * 256 + h * 128);
+                }
+        }
+    };
+    fetch(nid_cur);
+
+    if constexpr (!FULL_A) {
+        // the window's edges go to LDS (registers are the scarce resource here: they bound the wavefronts,
+        // and so the bytes in flight, per CU); each lane writes and later reads only its own slots
+#pragma unroll
+        for (int e_i = 0; e_i < EPT; ++e_i) {
+            const int32_t e = lo + lane + e_i * kWave;
+            int32_t code = -1;
+            if (e < hi) {
+                int r = 0;
+#pragma unroll
+                for (int step = 8; step > 0; step >>= 1)
+                    if (s_rp[r + step] <= e) r += step;
+                code = (r * kAStrideW) << 16 | edge_to_col[e];     // condensed column < kTileFewEdges
+                if (HAS_W) s_val[lane + e_i * kWave] = w[e];
+            }
+            s_code[lane + e_i * kWave] = code;
+        }
+    } else {
+        // InitSparse for the whole window: clear 16 x a_stride floats, then one pass over the edges in
+        // batches of 8 per lane whose loads are issued together (clamped, always valid)
+        for (int32_t i = lane * 4; i < 16 * as; i += kWave * 4)
+            *reinterpret_cast<float4 *>(a32 + i) = make_float4(0.f, 0.f, 0.f, 0.f);
+        wave_lds_order();
+        for (int32_t e0 = lo; e0 < hi; e0 += 8 * kWave) {
+            int32_t cc[8];
+            float vv[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int32_t e = min(e0 + lane + i * kWave, hi - 1);
+                cc[i] = edge_to_col[e];
+                vv[i] = HAS_W ? w[e] : 1.f;
+            }
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int32_t e = e0 + lane + i * kWave;
+                if (e < hi) {
+                    int r = 0;
+#pragma unroll
+                    for (int step = 8; step > 0; step >>= 1)
+                        if (s_rp[r + step] <= e) r += step;
+                    atomicAdd(&a32[r * as + cc[i]], vv[i]);
+                }
+            }
+        }
+        wave_lds_order();
+    }
+
+    f32x4 acc[NFB][8];
+#pragma unroll
+    for (int fb = 0; fb < NFB; ++fb)
+#pragma unroll
+        for (int m = 0; m < 8; ++m) acc[fb][m] = f32x4{0.f, 0.f, 0.f, 0.f};
+    const float *a_src = a32 + n * as + 4 * q;                    // A: row n, k = 4q .. 4q+3
+
+    for (int32_t k0 = 0; k0 < U; k0 += KW) {
+        if constexpr (!FULL_A) {
+            // InitSparse (the rows of this chunk are still on their way)
+#pragma unroll
+            for (int i = 0; i < 5; ++i) a32[lane + i * kWave] = 0.f;
+            wave_lds_order();
+#pragma unroll
+            for (int e_i = 0; e_i < EPT; ++e_i) {
+                const int32_t code = s_code[lane + e_i * kWave];
+                const int32_t cc = (code & 0xFFFF) - k0;
+                if (code >= 0 && cc >= 0 && cc < KW)
+                    atomicAdd(&a32[(code >> 16) + cc], HAS_W ? s_val[lane + e_i * kWave] : 1.f);
+            }
+            wave_lds_order();
+        }
+        const float4 av = *reinterpret_cast<const float4 *>(a_src + (FULL_A ? k0 : 0));
+        uint2 af;
+        af.x = pack2<DT, !HAS_W>(av.x, av.y);
+        af.y = pack2<DT, !HAS_W>(av.z, av.w);
+        wave_lds_order();
+        // TCcompute: element m of the four pieces -> B operand of MFMA (h, m)
+#pragma unroll
+        for (int fb = 0; fb < NFB; ++fb)
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const uint32_t wd[4][2] = {{xr[fb][h][0].x, xr[fb][h][0].y},
+                                           {xr[fb][h][1].x, xr[fb][h][1].y},
+                                           {xr[fb][h][2].x, xr[fb][h][2].y},
+                                           {xr[fb][h][3].x, xr[fb][h][3].y}};
+#pragma unroll
+                for (int m = 0; m < 4; ++m) {
+                    const uint32_t sel = (m & 1) ? 0x07060302u : 0x05040100u;   // high / low halves of two words
+                    uint2 bf;
+                    bf.x = __builtin_amdgcn_perm(wd[1][m >> 1], wd[0][m >> 1], sel);
+                    bf.y = __builtin_amdgcn_perm(wd[3][m >> 1], wd[2][m >> 1], sel);
+                    acc[fb][h * 4 + m] = mfma16k16<DT>(af, bf, acc[fb][h * 4 + m]);
+                }
+            }
+        // next chunk's rows into the registers just consumed; the ids of the one after
+        nid_cur = nid_nxt;
+        if (k0 + KW < U) {
+            fetch(nid_cur);
+            nid_nxt = k0 + 2 * KW + n < U ? col_to_row[u0 + k0 + 2 * KW + n] : -1;
+        }
+    }
+
+    // StoreDense: acc[fb][4h + m][r] = Y[r0 + 4q + r][d0 + 128 fb + 64 h + 4n + m]: 16 lanes write 256
+    // contiguous bytes of a row per store
+#pragma unroll
+    for (int fb = 0; fb < NFB; ++fb)
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int32_t col = fb * 128 + h * 64 + 4 * n;
+            if (col >= Dp) continue;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int64_t row = r0 + 4 * q + r;
+                if (row < n_rows)
+                    store4(Y, y_dt, row * ldy + d0 + col,
+                           make_float4(acc[fb][4 * h][r], acc[fb][4 * h + 1][r], acc[fb][4 * h + 2][r],
+                                       acc[fb][4 * h + 3][r]), y_vec);
+            }
+        }
 }
 
 template <int DT, bool HAS_W, int NS, int HB>
@@ -330,19 +546,43 @@ void launch_wave(const tcg_meta *m, const void *X, int64_t ldx, int32_t D, const
     // 4 outputs of a row leave in one store if every such group is aligned to its own size
     const bool y_vec = ldy % 4 == 0 && reinterpret_cast<uintptr_t>(Y) % (y_dt == TCG_F32 ? 16 : 8) == 0;
     const dim3 grid((unsigned)(kXcds * ceil_div(m->n_win, kXcds) * n_dparts));
-    if ((tile_mask >> kTileFew) & 1)
-        hipLaunchKernelGGL((spmm_tile_wave_kernel<DT, HAS_W, NS, false, HB>), grid, dim3(kWave), 0, s, m->n_rows,
-                           m->n_win, m->d_row_ptr, m->d_edge_to_col, m->d_win_unique_ptr, m->d_col_to_row,
-                           m->d_win_path, w, static_cast<const char *>(X), ldx * 2, D, n_dparts, Y, y_dt, ldy, y_vec, 0);
+    // Rows of more than 64 features in 16-row windows go to the kernel that loads them straight into the MFMA
+    // operands; narrower rows would leave most of its lanes without a piece to load.
+    constexpr bool kDirect = HB == 1 && NS >= 8;
+    constexpr int NFB = NS >= 16 ? 2 : 1;                          // 128-feature blocks per wavefront
+    const int32_t parts = (D + NFB * 128 - 1) / (NFB * 128);
+    const dim3 grid_direct((unsigned)(kXcds * ceil_div(m->n_win, kXcds) * parts));
+    if ((tile_mask >> kTileFew) & 1) {
+        bool rest = true;        // windows of the class left for the LDS-staging kernel
+        if constexpr (kDirect) {
+            hipLaunchKernelGGL((spmm_tile_direct_kernel<DT, HAS_W, NFB, false>), grid_direct, dim3(kWave), 0, s,
+                               m->n_rows, m->n_win, m->d_row_ptr, m->d_edge_to_col, m->d_win_unique_ptr,
+                               m->d_col_to_row, m->d_win_path, w, static_cast<const char *>(X), ldx * 2, D, parts, Y,
+                               y_dt, ldy, y_vec, 0);
+            rest = m->policy == TCG_POLICY_TILE;       // only a forced policy puts larger windows into this class
+        }
+        if (rest)
+            hipLaunchKernelGGL((spmm_tile_wave_kernel<DT, HAS_W, NS, false, HB>), grid, dim3(kWave), 0, s, m->n_rows,
+                               m->n_win, m->d_row_ptr, m->d_edge_to_col, m->d_win_unique_ptr, m->d_col_to_row,
+                               m->d_win_path, w, static_cast<const char *>(X), ldx * 2, D, n_dparts, Y, y_dt, ldy, y_vec,
+                               0, kDirect);
+    }
     if constexpr (HB == 1) {
         if ((tile_mask >> kTileMany) & 1) {
             // row stride of the window's condensed adjacency: its widest window rounded up to whole chunks,
             // plus 4 floats so that consecutive rows start in different banks
             const int32_t a_stride = (int32_t)((m->max_unique_many + KW - 1) / KW * KW + 4);
-            hipLaunchKernelGGL((spmm_tile_wave_kernel<DT, HAS_W, NS, true, 1>), grid, dim3(kWave),
-                               (size_t)16 * a_stride * sizeof(float), s, m->n_rows, m->n_win, m->d_row_ptr,
-                               m->d_edge_to_col, m->d_win_unique_ptr, m->d_col_to_row, m->d_win_path, w,
-                               static_cast<const char *>(X), ldx * 2, D, n_dparts, Y, y_dt, ldy, y_vec, a_stride);
+            const size_t a_bytes = (size_t)16 * a_stride * sizeof(float);
+            if constexpr (kDirect)
+                hipLaunchKernelGGL((spmm_tile_direct_kernel<DT, HAS_W, NFB, true>), grid_direct, dim3(kWave), a_bytes, s,
+                                   m->n_rows, m->n_win, m->d_row_ptr, m->d_edge_to_col, m->d_win_unique_ptr,
+                                   m->d_col_to_row, m->d_win_path, w, static_cast<const char *>(X), ldx * 2, D, parts,
+                                   Y, y_dt, ldy, y_vec, a_stride);
+            else
+                hipLaunchKernelGGL((spmm_tile_wave_kernel<DT, HAS_W, NS, true, 1>), grid, dim3(kWave), a_bytes, s,
+                                   m->n_rows, m->n_win, m->d_row_ptr, m->d_edge_to_col, m->d_win_unique_ptr,
+                                   m->d_col_to_row, m->d_win_path, w, static_cast<const char *>(X), ldx * 2, D,
+                                   n_dparts, Y, y_dt, ldy, y_vec, a_stride, false);
         }
     }
 }
@@ -377,7 +617,7 @@ int spmm_tile_launch(tcg_meta *m, const void *d_X, tcg_dtype x_dt, int32_t D, in
         if (d_w) launch_wave_s<TCG_F16, true>(m, d_X, ldx, D, d_w, d_Y, (int)y_dt, ldy, tile_mask, s);
         else launch_wave_s<TCG_F16, false>(m, d_X, ldx, D, d_w, d_Y, (int)y_dt, ldy, tile_mask, s);
     }
-    return launch_status("spmm_tile_wave_kernel");
+    return launch_status("spmm_tile kernels");
 }
 
 }  // namespace tcg
