@@ -56,9 +56,11 @@ def algorithmic_bytes_sddmm(n_rows, nnz, U, n_win, D, s_x):
 def read_traffic(workload, features):
     """HBM bytes per tcg_spmm call measured with rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE runs),
     as summarised under profiles/; None when no summary covers this workload."""
-    if workload != "4" or features != "f32":
+    name = {("4", "f32"): "spmm_rmat1m_d128_f32_hbm_traffic.json",
+            ("5a", "bf16"): "spmm_clustered5a_d256_bf16_hbm_traffic.json"}.get((workload, features))
+    if name is None:
         return None
-    path = os.path.join(ROOT, "profiles", "spmm_rmat1m_d128_f32_hbm_traffic.json")
+    path = os.path.join(ROOT, "profiles", name)
     try:
         with open(path) as f:
             return float(json.load(f)["hbm_bytes_per_spmm_call"])
