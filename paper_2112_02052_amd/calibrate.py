@@ -2,7 +2,7 @@
 """Measures on this GPU where the per-window choice between the gather path and the MFMA tile path
 should switch, and whether row clustering pays off on a given kind of graph.
 
-    python -m paper_2112_02052_amd.calibrate [--sweep density|reuse|reorder|all] [--nodes N]
+    python -m paper_2112_02052_amd.calibrate [--sweep density|reuse|reorder|all] [--nodes N] [--features bf16|f32]
 
 density  the paper's sparsity analysis (its table of dense blocks per row window): an N x N adjacency in
          which every 16-row window holds k fully dense 16 x 16 blocks, k = 1 .. 32, X bf16 N x 16; reports
@@ -32,6 +32,8 @@ def main():
     ap.add_argument("--sweep", default="all", choices=["density", "reuse", "reorder", "all"])
     ap.add_argument("--nodes", type=int, default=65536)
     ap.add_argument("--reps", type=int, default=20)
+    ap.add_argument("--features", default="bf16", choices=["bf16", "f32"],
+                    help="feature type of the density and reuse sweeps (fp32 rows take the bf16-triple MFMA kernel)")
     args = ap.parse_args()
 
     import numpy as np
@@ -59,7 +61,9 @@ def main():
             ts.append(a.elapsed_time(b) * 1e3)
         return sorted(ts)[len(ts) // 2]
 
-    def both_paths(g, D, dtype=torch.bfloat16):
+    feat_dtype = torch.bfloat16 if args.features == "bf16" else torch.float32
+
+    def both_paths(g, D, dtype=feat_dtype):
         rp = torch.from_numpy(g.row_ptr).to(dev)
         ci = torch.from_numpy(g.col_idx).to(dev)
         meta = tcg.sgt_build(rp, ci, 16, 8, validate=False)
@@ -79,7 +83,7 @@ def main():
 
     if args.sweep in ("density", "all"):
         n, D = args.nodes, 16
-        print("density sweep: N = %d, D = %d, bf16, k dense 16 x 16 blocks per window" % (n, D))
+        print("density sweep: N = %d, D = %d, %s, k dense 16 x 16 blocks per window" % (n, D, args.features))
         print("  k  sparsity%%  nnz        spmm gather/tile us   useful GFLOP/s gather/tile   dense-equiv GFLOP/s gather/tile")
         for k in (1, 2, 4, 8, 16, 32):
             g = W.dense_block_windows(n, k, seed=1)
@@ -89,11 +93,11 @@ def main():
             print("%3d  %8.2f  %9d  %9.1f /%8.1f   %12.0f /%8.0f   %16.0f /%10.0f" % (
                 k, 100.0 * (1 - g.nnz / (n * n)), g.nnz, r["spmm_gather_us"], r["spmm_tile_us"], useful[0], useful[1],
                 dense[0], dense[1]))
-            emit(dict(sweep="density", n=n, D=D, blocks_per_window=k, nnz=g.nnz, **r))
+            emit(dict(sweep="density", n=n, D=D, features=args.features, blocks_per_window=k, nnz=g.nnz, **r))
 
     if args.sweep in ("reuse", "all"):
         n = args.nodes
-        print("reuse sweep: N = %d, bf16; entries per distinct column of a window = 16 * fill" % n)
+        print("reuse sweep: N = %d, %s; entries per distinct column of a window = 16 * fill" % (n, args.features))
         print("  D    U_w  reuse   spmm gather/tile us    sddmm gather/tile us")
         for D in (32, 128, 256):
             for uw in (32, 128):
@@ -105,7 +109,7 @@ def main():
                     ratio = r["spmm_gather_us"] / r["spmm_tile_us"]
                     print("%4d  %4d  %5.2f  %9.1f /%8.1f    %9.1f /%8.1f" % (
                         D, uw, r["reuse"], r["spmm_gather_us"], r["spmm_tile_us"], r["sddmm_gather_us"], r["sddmm_tile_us"]))
-                    emit(dict(sweep="reuse", n=n, D=D, unique_per_window=uw, fill=fill, **r))
+                    emit(dict(sweep="reuse", n=n, D=D, features=args.features, unique_per_window=uw, fill=fill, **r))
                     if cross is None and ratio >= 1.0:
                         cross = r["reuse"] if prev is None else 0.5 * (prev + r["reuse"])
                     prev = r["reuse"]

@@ -388,7 +388,7 @@ int spmm_impl(tcg_meta *m, const void *d_X, tcg_dtype x_dt, int32_t D, int64_t l
     // faster than they are staged through LDS, and building a window's whole condensed adjacency in LDS
     // pays only for wider rows still.  A forced tile policy is taken literally.
     int tile_mask = 0;
-    if (m->n_tile_win > 0 && (m->win_h == 16 || m->win_h == 32) && tile_path_supports(x_dt, D, ldx, d_X)) {
+    if (m->n_tile_win > 0 && spmm_tile_supports(x_dt, D, ldx, d_X, m->win_h)) {
         const bool forced = m->policy == TCG_POLICY_TILE;
         if (forced || D >= kTileMinWidthFew) tile_mask |= 1 << kTileFew;
         if (forced || D >= kTileMinWidthMany) tile_mask |= 1 << kTileMany;

@@ -538,6 +538,260 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(4))) void
         }
 }
 
+// ---- fp32 features ---------------------------------------------------------------------------------------
+// gfx950 has no MFMA that takes fp32 inputs, and on the vector ALUs the dense 16 x U_w x D product of a window
+// (mostly zeros of the condensed adjacency) costs more than the memory traffic it saves.  An fp32 value is,
+// however, EXACTLY the sum of three bf16 values: its upper 16 bits, the upper 16 bits of what is left, and the
+// upper 16 bits of what is left after that (8 significant bits each, 24 in all; truncation, so nothing rounds
+// and nothing overflows).  So the kernel is the direct kernel above with every fp32 operand split in three:
+//     w x  =  (wh + wm + wl)(xh + xm + xl)  ~  wh xh + wh xm + wm xh + wh xl + wm xm + wl xh,
+// six bf16 MFMAs with fp32 accumulation; the three dropped terms are below 2^-23 |w x|, the size of the
+// rounding of the fp32 result itself.  With unit edge values the adjacency entries are small integers (the
+// multiplicity of an edge; exact in bf16 up to 256) and three MFMAs suffice.  Lane (n, q) loads the 16-byte
+// piece "features 4n .. 4n+3" of a block of 64 features from its four neighbour rows; MFMA m of the block takes
+// element m, so its column n is feature 4n + m and a lane ends up with four consecutive features of its four
+// output rows: one 16-byte streaming store per row.  NB blocks of 64 features per wavefront.
+// (A non-finite feature becomes NaN in every row of its window that has an edge to it or not -- inf - inf in
+// the split, NaN x 0 in the MFMA -- where the gather path propagates it only along edges.)
+__device__ __forceinline__ uint32_t upper_halves(float lo, float hi)
+{
+    return __builtin_amdgcn_perm(__float_as_uint(hi), __float_as_uint(lo), 0x07060302u);
+}
+__device__ __forceinline__ float below_upper_half(float v)
+{
+    return v - __uint_as_float(__float_as_uint(v) & 0xFFFF0000u);      // exact
+}
+
+template <bool HAS_W, int NB, bool FULL_A>
+__global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(NB >= 4 ? 2 : 4))) void spmm_tile_f32_kernel(
+    int32_t n_rows, int64_t n_win, const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ edge_to_col,
+    const int32_t *__restrict__ win_unique_ptr, const int32_t *__restrict__ col_to_row,
+    const uint8_t *__restrict__ win_path, const float *__restrict__ w, const float *__restrict__ X, int64_t ldx,
+    int32_t D, int32_t n_dparts, void *__restrict__ Y, int y_dt, int64_t ldy, bool y_vec, int32_t a_stride)
+{
+    constexpr int EPT = kTileFewEdges / kWave;
+    extern __shared__ __align__(16) float a_full[];                    // FULL_A: 16 x a_stride
+    __shared__ __align__(16) float a_slice[FULL_A ? 4 : 16 * kAStrideW];
+    __shared__ int32_t s_rp[17];
+    __shared__ int32_t s_code[FULL_A ? 1 : kTileFewEdges];             // per edge: slice row offset << 16 | condensed column
+    __shared__ float s_val[HAS_W && !FULL_A ? kTileFewEdges : 1];      // per edge: its value
+    float *a32 = FULL_A ? a_full : a_slice;
+    const int32_t as = FULL_A ? a_stride : kAStrideW;
+
+    const int64_t per_die = (n_win + kXcds - 1) / kXcds;
+    const int64_t j = blockIdx.x / kXcds;
+    const int64_t win = (int64_t)(blockIdx.x % kXcds) * per_die + j / n_dparts;
+    if (j / n_dparts >= per_die || win >= n_win || win_path[win] != (FULL_A ? kTileMany : kTileFew)) return;
+    const int32_t d0 = (int32_t)(j % n_dparts) * (NB * 64);       // first feature column of this part
+    const int32_t Dp = min(NB * 64, D - d0);
+
+    const int lane = threadIdx.x;
+    const int n = lane & 15, q = lane >> 4;
+    const int64_t r0 = win * 16;
+    if (lane < 17) {
+        int64_t r = r0 + lane;
+        s_rp[lane] = row_ptr[r < n_rows ? r : n_rows];
+    }
+    wave_lds_order();
+    const int32_t u0 = win_unique_ptr[win];
+    const int32_t U = win_unique_ptr[win + 1] - u0;
+    // ids of the neighbours of chunks 0 and 1 (lane k < 16 holds row k of the chunk)
+    int32_t nid_cur = n < U ? col_to_row[u0 + n] : -1;
+    int32_t nid_nxt = KW + n < U ? col_to_row[u0 + KW + n] : -1;
+    const int32_t lo = s_rp[0], hi = s_rp[16];
+    // only a forced policy puts a window with more edges into class kTileFew: its edges are then read from
+    // global memory for every chunk
+    const bool edges_in_lds = hi - lo <= kTileFewEdges;
+
+    // FetchDense: chunk rows 4q .. 4q+3, features 4n .. 4n+3 of every block of 64
+    const float *Xp = X + d0 + 4 * n;
+    f32x4 xr[NB][4];
+    auto fetch = [&](int32_t nid) {
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+            const int32_t node = __shfl(nid, 4 * q + jj);
+#pragma unroll
+            for (int fb = 0; fb < NB; ++fb) {
+                xr[fb][jj] = f32x4{0.f, 0.f, 0.f, 0.f};
+                if (node >= 0 && fb * 64 + 4 * n < Dp)
+                    xr[fb][jj] = *reinterpret_cast<const f32x4 *>(Xp + (int64_t)node * ldx + fb * 64);
+            }
+        }
+    };
+    fetch(nid_cur);
+
+    if constexpr (!FULL_A) {
+        // the window's edges go to LDS; each lane writes and later reads only its own slots
+#pragma unroll
+        for (int e_i = 0; e_i < EPT; ++e_i) {
+            const int32_t e = lo + lane + e_i * kWave;
+            int32_t code = -1;
+            if (edges_in_lds && e < hi) {
+                int r = 0;
+#pragma unroll
+                for (int step = 8; step > 0; step >>= 1)
+                    if (s_rp[r + step] <= e) r += step;
+                code = (r * kAStrideW) << 16 | edge_to_col[e];     // condensed column < kTileFewEdges
+                if (HAS_W) s_val[lane + e_i * kWave] = w[e];
+            }
+            s_code[lane + e_i * kWave] = code;
+        }
+    } else {
+        // InitSparse for the whole window
+        for (int32_t i = lane * 4; i < 16 * as; i += kWave * 4)
+            *reinterpret_cast<float4 *>(a32 + i) = make_float4(0.f, 0.f, 0.f, 0.f);
+        wave_lds_order();
+        for (int32_t e0 = lo; e0 < hi; e0 += 8 * kWave) {
+            int32_t cc[8];
+            float vv[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int32_t e = min(e0 + lane + i * kWave, hi - 1);
+                cc[i] = edge_to_col[e];
+                vv[i] = HAS_W ? w[e] : 1.f;
+            }
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int32_t e = e0 + lane + i * kWave;
+                if (e < hi) {
+                    int r = 0;
+#pragma unroll
+                    for (int step = 8; step > 0; step >>= 1)
+                        if (s_rp[r + step] <= e) r += step;
+                    atomicAdd(&a32[r * as + cc[i]], vv[i]);
+                }
+            }
+        }
+        wave_lds_order();
+    }
+
+    f32x4 acc[NB][4];
+#pragma unroll
+    for (int fb = 0; fb < NB; ++fb)
+#pragma unroll
+        for (int m = 0; m < 4; ++m) acc[fb][m] = f32x4{0.f, 0.f, 0.f, 0.f};
+    const float *a_src = a32 + n * as + 4 * q;                    // A: row n, k = 4q .. 4q+3
+
+    for (int32_t k0 = 0; k0 < U; k0 += KW) {
+        if constexpr (!FULL_A) {
+            // InitSparse (the rows of this chunk are still on their way)
+#pragma unroll
+            for (int i = 0; i < 5; ++i) a32[lane + i * kWave] = 0.f;
+            wave_lds_order();
+            if (edges_in_lds) {
+#pragma unroll
+                for (int e_i = 0; e_i < EPT; ++e_i) {
+                    const int32_t code = s_code[lane + e_i * kWave];
+                    const int32_t cc = (code & 0xFFFF) - k0;
+                    if (code >= 0 && cc >= 0 && cc < KW)
+                        atomicAdd(&a32[(code >> 16) + cc], HAS_W ? s_val[lane + e_i * kWave] : 1.f);
+                }
+            } else {
+                for (int32_t e = lo + lane; e < hi; e += kWave) {
+                    const int32_t cc = edge_to_col[e] - k0;
+                    if (cc >= 0 && cc < KW) {
+                        int r = 0;
+#pragma unroll
+                        for (int step = 8; step > 0; step >>= 1)
+                            if (s_rp[r + step] <= e) r += step;
+                        atomicAdd(&a32[r * kAStrideW + cc], HAS_W ? w[e] : 1.f);
+                    }
+                }
+            }
+            wave_lds_order();
+        }
+        const float4 av = *reinterpret_cast<const float4 *>(a_src + (FULL_A ? k0 : 0));
+        wave_lds_order();
+        // A operand: the upper halves; with edge values also the two remainders
+        uint2 ah, am, al;
+        ah.x = upper_halves(av.x, av.y);
+        ah.y = upper_halves(av.z, av.w);
+        if (HAS_W) {
+            const float r0x = below_upper_half(av.x), r0y = below_upper_half(av.y), r0z = below_upper_half(av.z),
+                        r0w = below_upper_half(av.w);
+            am.x = upper_halves(r0x, r0y);
+            am.y = upper_halves(r0z, r0w);
+            al.x = upper_halves(below_upper_half(r0x), below_upper_half(r0y));
+            al.y = upper_halves(below_upper_half(r0z), below_upper_half(r0w));
+        }
+        // TCcompute: element m of the four pieces, split in three -> B operands of the MFMAs of (fb, m)
+#pragma unroll
+        for (int fb = 0; fb < NB; ++fb)
+#pragma unroll
+            for (int m = 0; m < 4; ++m) {
+                const float v0 = xr[fb][0][m], v1 = xr[fb][1][m], v2 = xr[fb][2][m], v3 = xr[fb][3][m];
+                const float s0 = below_upper_half(v0), s1 = below_upper_half(v1), s2 = below_upper_half(v2),
+                            s3 = below_upper_half(v3);
+                uint2 bh, bm, bl;
+                bh.x = upper_halves(v0, v1);
+                bh.y = upper_halves(v2, v3);
+                bm.x = upper_halves(s0, s1);
+                bm.y = upper_halves(s2, s3);
+                bl.x = upper_halves(below_upper_half(s0), below_upper_half(s1));
+                bl.y = upper_halves(below_upper_half(s2), below_upper_half(s3));
+                f32x4 c = acc[fb][m];
+                c = mfma16k16<TCG_BF16>(ah, bl, c);             // smallest terms first
+                if (HAS_W) {
+                    c = mfma16k16<TCG_BF16>(al, bh, c);
+                    c = mfma16k16<TCG_BF16>(am, bm, c);
+                    c = mfma16k16<TCG_BF16>(am, bh, c);
+                }
+                c = mfma16k16<TCG_BF16>(ah, bm, c);
+                c = mfma16k16<TCG_BF16>(ah, bh, c);
+                acc[fb][m] = c;
+            }
+        // next chunk's rows into the registers just consumed; the ids of the one after
+        nid_cur = nid_nxt;
+        if (k0 + KW < U) {
+            fetch(nid_cur);
+            nid_nxt = k0 + 2 * KW + n < U ? col_to_row[u0 + k0 + 2 * KW + n] : -1;
+        }
+    }
+
+    // StoreDense: acc[fb][m][r] = Y[r0 + 4q + r][d0 + 64 fb + 4n + m]: 16 lanes write 256 contiguous bytes of a row
+#pragma unroll
+    for (int fb = 0; fb < NB; ++fb) {
+        const int32_t col = fb * 64 + 4 * n;
+        if (col >= Dp) continue;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int64_t row = r0 + 4 * q + r;
+            if (row < n_rows)
+                store4(Y, y_dt, row * ldy + d0 + col,
+                       make_float4(acc[fb][0][r], acc[fb][1][r], acc[fb][2][r], acc[fb][3][r]), y_vec);
+        }
+    }
+}
+
+template <bool HAS_W, int NB>
+void launch_tile_f32(const tcg_meta *m, const float *X, int64_t ldx, int32_t D, const float *w, void *Y, int y_dt,
+                     int64_t ldy, int tile_mask, hipStream_t s)
+{
+    const int32_t parts = (D + NB * 64 - 1) / (NB * 64);
+    const bool y_vec = ldy % 4 == 0 && reinterpret_cast<uintptr_t>(Y) % (y_dt == TCG_F32 ? 16 : 8) == 0;
+    const dim3 grid((unsigned)(kXcds * ceil_div(m->n_win, kXcds) * parts));
+    if ((tile_mask >> kTileFew) & 1)
+        hipLaunchKernelGGL((spmm_tile_f32_kernel<HAS_W, NB, false>), grid, dim3(kWave), 0, s, m->n_rows, m->n_win,
+                           m->d_row_ptr, m->d_edge_to_col, m->d_win_unique_ptr, m->d_col_to_row, m->d_win_path, w, X,
+                           ldx, D, parts, Y, y_dt, ldy, y_vec, 0);
+    if ((tile_mask >> kTileMany) & 1) {
+        const int32_t a_stride = (int32_t)((m->max_unique_many + KW - 1) / KW * KW + 4);
+        hipLaunchKernelGGL((spmm_tile_f32_kernel<HAS_W, NB, true>), grid, dim3(kWave),
+                           (size_t)16 * a_stride * sizeof(float), s, m->n_rows, m->n_win, m->d_row_ptr,
+                           m->d_edge_to_col, m->d_win_unique_ptr, m->d_col_to_row, m->d_win_path, w, X, ldx, D, parts,
+                           Y, y_dt, ldy, y_vec, a_stride);
+    }
+}
+
+template <bool HAS_W>
+void launch_tile_f32_s(const tcg_meta *m, const float *X, int64_t ldx, int32_t D, const float *w, void *Y,
+                       int y_dt, int64_t ldy, int tile_mask, hipStream_t s)
+{
+    if (D <= 64) launch_tile_f32<HAS_W, 1>(m, X, ldx, D, w, Y, y_dt, ldy, tile_mask, s);
+    else if (D <= 128) launch_tile_f32<HAS_W, 2>(m, X, ldx, D, w, Y, y_dt, ldy, tile_mask, s);
+    else launch_tile_f32<HAS_W, 4>(m, X, ldx, D, w, Y, y_dt, ldy, tile_mask, s);
+}
+
 template <int DT, bool HAS_W, int NS, int HB>
 void launch_wave(const tcg_meta *m, const void *X, int64_t ldx, int32_t D, const float *w, void *Y, int y_dt,
                  int64_t ldy, int tile_mask, hipStream_t s)
@@ -607,10 +861,21 @@ bool tile_path_supports(tcg_dtype x_dt, int32_t D, int64_t ldx, const void *X)
            (reinterpret_cast<uintptr_t>(X) & 15) == 0;
 }
 
+bool spmm_tile_supports(tcg_dtype x_dt, int32_t D, int64_t ldx, const void *X, int32_t win_h)
+{
+    if (x_dt == TCG_F32)       // the kernel that splits fp32 operands into bf16 triples
+        return win_h == 16 && D % 4 == 0 && D <= 1024 && ldx % 4 == 0 && (reinterpret_cast<uintptr_t>(X) & 15) == 0;
+    return (win_h == 16 || win_h == 32) && tile_path_supports(x_dt, D, ldx, X);
+}
+
 int spmm_tile_launch(tcg_meta *m, const void *d_X, tcg_dtype x_dt, int32_t D, int64_t ldx, const float *d_w,
                      void *d_Y, tcg_dtype y_dt, int64_t ldy, int tile_mask, hipStream_t s)
 {
-    if (x_dt == TCG_BF16) {
+    if (x_dt == TCG_F32) {
+        const float *X = static_cast<const float *>(d_X);
+        if (d_w) launch_tile_f32_s<true>(m, X, ldx, D, d_w, d_Y, (int)y_dt, ldy, tile_mask, s);
+        else launch_tile_f32_s<false>(m, X, ldx, D, d_w, d_Y, (int)y_dt, ldy, tile_mask, s);
+    } else if (x_dt == TCG_BF16) {
         if (d_w) launch_wave_s<TCG_BF16, true>(m, d_X, ldx, D, d_w, d_Y, (int)y_dt, ldy, tile_mask, s);
         else launch_wave_s<TCG_BF16, false>(m, d_X, ldx, D, d_w, d_Y, (int)y_dt, ldy, tile_mask, s);
     } else {

@@ -224,6 +224,81 @@ def test_spmm_16bit_features(x_dtype, policy):
         run_spmm_case(c["csr"], X, x_dtype, None, policy, TOL_F32)   # unit weights are exact in 16 bits
 
 
+@pytest.mark.parametrize("policy", [tcg.POLICY_TILE, tcg.POLICY_AUTO])
+def test_spmm_fp32_features_on_the_tile_path(policy):
+    # gfx950 has no MFMA with fp32 inputs: the tile kernel splits every fp32 operand exactly into three bf16
+    # values and accumulates the six leading products in fp32, so the fp32 tolerance applies.
+    for cfg, n, D, permute in ((5, 64 * 60, 256, False), (5, 64 * 30, 64, True), (3, 4000, 32, True),
+                               (4, 3000, 128, True), (5, 64 * 10, 72, False), (5, 64 * 12, 300, False)):
+        c = W.make_config(cfg, n=n, d=D, permute=permute)
+        w = np.random.default_rng(3).uniform(0.5, 1.5, c["csr"].nnz).astype(np.float32)
+        st = run_spmm_case(c["csr"], c["X"], "f32", w, policy, TOL_F32)
+        if policy == tcg.POLICY_TILE:
+            assert st["nnz_tile"] == c["csr"].nnz
+        if policy == tcg.POLICY_AUTO and cfg == 5 and not permute:
+            assert st["n_tile_windows"] > 0.9 * (n // 16)
+        run_spmm_case(c["csr"], c["X"], "f32", None, policy, TOL_F32)
+
+
+@pytest.mark.parametrize("D", [4, 12, 36, 68, 132, 200, 260, 516, 1024])
+def test_spmm_fp32_tile_path_feature_widths(D):
+    # One, two and four 64-feature blocks per wavefront, several feature parts, a ragged last block, padded
+    # rows, outputs that cannot take 16-byte stores, and a 16-bit result.
+    c = W.make_config(5, n=64 * 12, d=D, permute=False)
+    g, X = c["csr"], c["X"]
+    w = np.random.default_rng(D).standard_normal(g.nnz).astype(np.float32)
+    run_spmm_case(g, X, "f32", w, tcg.POLICY_TILE, TOL_F32)
+    run_spmm_case(g, X, "f32", None, tcg.POLICY_TILE, TOL_F32, pad=4)
+    rp, ci = upload_csr(g)
+    meta = tcg.sgt_build(rp, ci, 16, 8)
+    tcg.sgt_set_policy(meta, tcg.POLICY_TILE)
+    Xd = upload_x(X, "f32")
+    ref = oracle.spmm(g.row_ptr, g.col_idx, X, None)
+    for y_dtype, tol in ((torch.float32, TOL_F32), (torch.bfloat16, 2.0 ** -8)):
+        big = torch.full((g.n_rows, D + 3), float("nan"), dtype=y_dtype, device=dev())
+        Y = big[:, 1:D + 1]                                   # odd leading dimension, shifted start
+        tcg.spmm(meta, Xd, None, Y=Y)
+        torch.cuda.synchronize()
+        assert norm_err(Y.to(torch.float32).cpu().numpy(), ref) <= tol
+        assert torch.isnan(big[:, 0]).all() and torch.isnan(big[:, D + 1:]).all()   # nothing outside Y
+    meta.free()
+
+
+def test_spmm_fp32_tile_path_windows_with_many_edges():
+    # 2 dense blocks per window: 512 edges, kept in LDS; 20: the whole condensed adjacency of the window in
+    # LDS; 48: 768 condensed columns, which only a forced policy sends here (edges re-read per chunk).
+    for blocks, D in ((2, 40), (20, 136), (48, 40)):
+        g = W.dense_block_windows(1024, blocks, seed=5)
+        X = W.features_normal(1024, D, 6)
+        w = np.random.default_rng(blocks).standard_normal(g.nnz).astype(np.float32)
+        run_spmm_case(g, X, "f32", None, tcg.POLICY_TILE, TOL_F32)
+        run_spmm_case(g, X, "f32", w, tcg.POLICY_TILE, TOL_F32)
+
+
+def test_spmm_fp32_tile_path_is_as_accurate_as_fp32_arithmetic():
+    # The split into bf16 triples is exact and only products below 2^-23 of |w x| are dropped, so the error of an
+    # output stays at the level of fp32 rounding relative to sum |w||x| of its row -- also for values whose
+    # magnitudes differ by many binades, where a dropped or misplaced term of the split (2^-16 of a product)
+    # would show at once.  The gather path (plain fp32 FMAs) is held to the same bound.
+    c = W.make_config(5, n=64 * 60, d=256, permute=False)
+    g = c["csr"]
+    rng = np.random.default_rng(1)
+    Xw = (rng.standard_normal((g.n_cols, 256)) * np.exp2(rng.integers(-20, 21, (g.n_cols, 256)))).astype(np.float32)
+    ww = (rng.standard_normal(g.nnz) * np.exp2(rng.integers(-10, 11, g.nnz))).astype(np.float32)
+    rp, ci = upload_csr(g)
+    meta = tcg.sgt_build(rp, ci, 16, 8)
+    for X, w in ((Xw, ww), (Xw, None), (c["X"], rng.uniform(0.5, 1.5, g.nnz).astype(np.float32))):
+        ref = oracle.spmm(g.row_ptr, g.col_idx, X, w)
+        mag = oracle.spmm(g.row_ptr, g.col_idx, np.abs(X), None if w is None else np.abs(w))
+        for policy in (tcg.POLICY_GATHER, tcg.POLICY_TILE):
+            tcg.sgt_set_policy(meta, policy)
+            Y = tcg.spmm(meta, upload_x(X, "f32"), None if w is None else torch.from_numpy(w).to(dev()))
+            torch.cuda.synchronize()
+            rel = np.abs(Y.cpu().numpy().astype(np.float64) - ref) / np.maximum(mag, 1e-300)
+            assert rel.max() <= 2.0 ** -19, (policy, rel.max())
+    meta.free()
+
+
 def test_spmm_integer_inputs_are_bit_exact_on_every_path():
     # Unit edge values and small-integer features: every product and fp32 partial sum is exact,
     # so any path must reproduce the oracle bit for bit whatever its summation order.
@@ -233,7 +308,7 @@ def test_spmm_integer_inputs_are_bit_exact_on_every_path():
     rp, ci = upload_csr(g)
     meta = tcg.sgt_build(rp, ci, 16, 8)
     for x_dtype, policy in (("f32", tcg.POLICY_GATHER), ("bf16", tcg.POLICY_GATHER), ("bf16", tcg.POLICY_TILE),
-                            ("f16", tcg.POLICY_TILE), ("bf16", tcg.POLICY_AUTO)):
+                            ("f16", tcg.POLICY_TILE), ("bf16", tcg.POLICY_AUTO), ("f32", tcg.POLICY_TILE)):
         tcg.sgt_set_policy(meta, policy)
         Y = tcg.spmm(meta, upload_x(X, x_dtype))
         torch.cuda.synchronize()
@@ -250,6 +325,7 @@ def test_spmm_rectangular_matrix():
         X = W.features_normal(n_cols, 64, 2)
         w = rng.standard_normal(g.nnz).astype(np.float32)
         run_spmm_case(g, X, "f32", w, tcg.POLICY_AUTO, TOL_F32)
+        run_spmm_case(g, X, "f32", w, tcg.POLICY_TILE, TOL_F32)
         run_spmm_case(g, W.round_to_bf16(X), "bf16", None, tcg.POLICY_TILE, TOL_F32)
 
 
