@@ -112,11 +112,15 @@ TCG_API int tcg_sgt_export(const tcg_meta *meta, int32_t *win_partition, int32_t
  * Chooses which windows run on the condensed-tile (MFMA) path.  TCG_POLICY_AUTO (the state
  * after tcg_sgt_build) sends a window there when window_h == 16, it has at most 512 unique
  * columns and its neighbour reuse nnz_w / U_w is at least `min_reuse` (<= 0 selects the library
- * default, 2).  The flag says where a window may go; a call takes the tile path only when its X is
- * bf16 or f16 (fp32 features always use the gather path), and under TCG_POLICY_AUTO tcg_spmm
- * additionally gathers narrow features: windows of at most 512 entries use the tile kernels from
- * D >= 64, windows with more entries from D >= 128 (measured crossovers).  TCG_POLICY_TILE sends
- * every non-empty window to the tile kernels at any width.
+ * default, 2).  The flag says where a window may go; a call takes the tile path only when its
+ * operands can be read in 16-byte pieces (else it gathers), and under TCG_POLICY_AUTO narrow
+ * features are gathered as well: tcg_spmm sends windows of at most 512 entries to the tile kernels
+ * from D >= 64 and windows with more entries from D >= 128, tcg_sddmm uses them at every width for
+ * bf16/f16 and from D >= 64 for fp32 (measured crossovers).  bf16/f16 features feed the MFMA units
+ * directly (products of rounded edge values: the 1e-2 tolerance class); fp32 features are split
+ * exactly into three bf16 values each and the six leading partial products are accumulated in fp32,
+ * which keeps fp32 accuracy (D a multiple of 4, at most 1024 for tcg_spmm and 256 for tcg_sddmm).
+ * TCG_POLICY_TILE sends every non-empty window to the tile kernels at any width they support.
  * Blocks until the stream has finished.  Returns TCG_EINVAL for TCG_POLICY_TILE when
  * window_h != 16.
  */

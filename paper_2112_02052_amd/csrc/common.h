@@ -182,6 +182,7 @@ int row_softmax_impl(const tcg_meta *m, const float *d_in, float *d_out, hipStre
 // spmm_tile.hip: can the condensed-tile kernels take this operand?
 bool tile_path_supports(tcg_dtype x_dt, int32_t D, int64_t ldx, const void *X);
 bool spmm_tile_supports(tcg_dtype x_dt, int32_t D, int64_t ldx, const void *X, int32_t win_h);
+bool sddmm_tile_supports(tcg_dtype x_dt, int32_t D, int64_t ld, const void *ptr);
 
 inline int dtype_size(tcg_dtype t) { return t == TCG_F32 ? 4 : 2; }
 

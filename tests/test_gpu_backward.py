@@ -56,7 +56,8 @@ def test_edge_gather_and_softmax_backward():
 
 
 @pytest.mark.parametrize("x_dtype,policy,tol", [("f32", tcg.POLICY_AUTO, TOL_F32), ("bf16", tcg.POLICY_GATHER, TOL_F32),
-                                                ("bf16", tcg.POLICY_TILE, TOL_F32), ("f16", tcg.POLICY_TILE, TOL_F32)])
+                                                ("bf16", tcg.POLICY_TILE, TOL_F32), ("f16", tcg.POLICY_TILE, TOL_F32),
+                                                ("f32", tcg.POLICY_TILE, TOL_F32)])
 def test_sddmm_pq(x_dtype, policy, tol):
     rnd = {"f32": lambda a: a, "bf16": W.round_to_bf16, "f16": lambda a: a.astype(np.float16).astype(np.float32)}[x_dtype]
     for g, D in ((asymmetric_graph(900, 2000, 3), 64), (asymmetric_graph(2000, 900, 4), 40),

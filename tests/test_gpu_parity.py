@@ -469,6 +469,43 @@ def test_sddmm_16bit_features(x_dtype, policy):
         run_sddmm_case(c["csr"], rnd(c["X"]), x_dtype, policy, TOL_F32)   # exact products, fp32 sums on both paths
 
 
+@pytest.mark.parametrize("policy", [tcg.POLICY_TILE, tcg.POLICY_AUTO])
+def test_sddmm_fp32_features_on_the_tile_path(policy):
+    # fp32 operands split exactly into bf16 triples, six MFMAs per K step: the fp32 tolerance applies.  Widths
+    # with a ragged last K step, windows of both classes (<= 512 edges / more), rows beyond the last window.
+    for cfg, n, D, permute in ((5, 64 * 60, 256, False), (5, 64 * 30, 64, True), (3, 4000, 32, True),
+                               (5, 64 * 10, 72, False), (4, 3000, 128, True), (5, 64 * 12, 200, False),
+                               (5, 64 * 12 , 4, False)):
+        c = W.make_config(cfg, n=n, d=D, permute=permute)
+        run_sddmm_case(c["csr"], c["X"], "f32", policy, TOL_F32)
+    for blocks, D in ((2, 40), (20, 136), (48, 40)):
+        g = W.dense_block_windows(1024, blocks, seed=5)
+        run_sddmm_case(g, W.features_normal(1024, D, 6), "f32", policy, TOL_F32)
+    g = hub_graph(1000)
+    run_sddmm_case(g, W.features_normal(g.n_cols, 96, 1), "f32", policy, TOL_F32)
+
+
+def test_sddmm_fp32_tile_path_is_as_accurate_as_fp32_arithmetic():
+    # As for SpMM: every score must be within fp32 rounding of sum |x_i||x_j| over the features, also when the
+    # magnitudes of the features differ by many binades (a wrong or missing term of the split is 2^-16 of a
+    # product).  The gather path is held to the same bound.
+    c = W.make_config(5, n=64 * 60, d=256, permute=False)
+    g = c["csr"]
+    rng = np.random.default_rng(2)
+    X = (rng.standard_normal((g.n_cols, 256)) * np.exp2(rng.integers(-12, 13, (g.n_cols, 256)))).astype(np.float32)
+    ref = oracle.sddmm(g.row_ptr, g.col_idx, X)
+    mag = oracle.sddmm(g.row_ptr, g.col_idx, np.abs(X))
+    rp, ci = upload_csr(g)
+    meta = tcg.sgt_build(rp, ci, 16, 8)
+    for policy in (tcg.POLICY_GATHER, tcg.POLICY_TILE):
+        tcg.sgt_set_policy(meta, policy)
+        out = tcg.sddmm(meta, upload_x(X, "f32"))
+        torch.cuda.synchronize()
+        rel = np.abs(out.cpu().numpy().astype(np.float64) - ref) / np.maximum(mag, 1e-300)
+        assert rel.max() <= 2.0 ** -19, (policy, rel.max())
+    meta.free()
+
+
 def test_sddmm_integer_and_one_hot_inputs_are_exact():
     g = hub_graph(2000)
     rng = np.random.default_rng(0)
@@ -477,7 +514,7 @@ def test_sddmm_integer_and_one_hot_inputs_are_exact():
     rp, ci = upload_csr(g)
     meta = tcg.sgt_build(rp, ci, 16, 16)
     for x_dtype, policy in (("f32", tcg.POLICY_GATHER), ("bf16", tcg.POLICY_GATHER), ("bf16", tcg.POLICY_TILE),
-                            ("f16", tcg.POLICY_TILE)):
+                            ("f16", tcg.POLICY_TILE), ("f32", tcg.POLICY_TILE)):
         tcg.sgt_set_policy(meta, policy)
         out = tcg.sddmm(meta, upload_x(X, x_dtype))
         torch.cuda.synchronize()
