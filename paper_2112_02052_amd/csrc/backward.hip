@@ -102,69 +102,122 @@ __device__ __forceinline__ float wave_sum(float v)
     return v;
 }
 
-// dv[e] = p[e] * (dp[e] - sum over the row of p * dp).  Rows of at most kSegLen entries: one
-// wavefront per row; longer rows: one workgroup per row (the gather plan's list of split rows).
+// dv[e] = p[e] * (dp[e] - sum over the row of p * dp).  Rows of at most kSegLen entries: kBwdGroup lanes
+// per row with the row's entries in registers (four rows per wavefront); longer rows: one workgroup per
+// row (the gather plan's list of split rows).
+constexpr int kBwdGroup = 16;
+
 __global__ __launch_bounds__(kThreads) void softmax_bwd_kernel(int32_t n_rows, const int32_t *__restrict__ row_ptr,
                                                                const float *p, const float *dp, float *dv)
 {
-    const int lane = threadIdx.x & (kWave - 1);
-    const int64_t row = (int64_t)blockIdx.x * (kThreads / kWave) + (threadIdx.x >> 6);
-    if (row >= n_rows) return;
-    const int32_t b = row_ptr[row], e = row_ptr[row + 1];
-    if (b == e || e - b > kSegLen) return;
+    constexpr int G = kBwdGroup, SLOTS = kSegLen / G;
+    const int gl = threadIdx.x % G;
+    const int64_t row = ((int64_t)blockIdx.x * kThreads + threadIdx.x) / G;
+    int32_t b = 0, e = 0;
+    if (row < n_rows) {
+        b = row_ptr[row];
+        e = row_ptr[row + 1];
+        if (e - b > kSegLen) e = b;             // a long row: not here
+    }
+    float pv[SLOTS], gv[SLOTS];
     float dot = 0.f;
-    for (int32_t k = b + lane; k < e; k += kWave) dot = fmaf(p[k], dp[k], dot);
-    dot = wave_sum(dot);
-    for (int32_t k = b + lane; k < e; k += kWave) dv[k] = p[k] * (dp[k] - dot);
+#pragma unroll
+    for (int i = 0; i < SLOTS; ++i) {
+        const int32_t k = b + gl + G * i;
+        pv[i] = k < e ? p[k] : 0.f;
+        gv[i] = k < e ? dp[k] : 0.f;
+        dot = fmaf(pv[i], gv[i], dot);
+    }
+#pragma unroll
+    for (int off = 1; off < G; off <<= 1) dot += __shfl_xor(dot, off, kWave);
+#pragma unroll
+    for (int i = 0; i < SLOTS; ++i) {
+        const int32_t k = b + gl + G * i;
+        if (k < e) dv[k] = pv[i] * (gv[i] - dot);
+    }
 }
 
-// Long rows: one workgroup per row, 256 of its threads for rows up to kLongRowWide entries and all 1024
-// beyond; four values per thread in flight.
+// Long rows (the gather plan's list of split rows), in two kernels over that list.  Up to kMidRow entries:
+// one 256-thread workgroup per row, p and dp of the row in registers (eight values each per thread).
+// Beyond: 1024-thread workgroups walk the list and take two passes over such a row, four values per
+// thread in flight.
+constexpr int kMidRow = 8 * kThreads;
 constexpr int kLongThreads = 1024;
-constexpr int kLongRowWide = 4096;
+constexpr int kLongGridMax = 1024;
 
-__global__ __launch_bounds__(kLongThreads) void softmax_bwd_long_kernel(const int32_t *__restrict__ long_row,
-                                                                        const int32_t *__restrict__ row_ptr,
-                                                                        const float *p, const float *dp, float *dv)
+__global__ __launch_bounds__(kThreads) void softmax_bwd_mid_kernel(const int32_t *__restrict__ long_row,
+                                                                   const int32_t *__restrict__ row_ptr, const float *p,
+                                                                   const float *dp, float *dv)
 {
-    __shared__ float s_red[kLongThreads / kWave];
+    __shared__ float s_red[kThreads / kWave];
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
     const int32_t row = long_row[blockIdx.x];
     const int32_t b = row_ptr[row], e = row_ptr[row + 1];
-    const int nthr = e - b > kLongRowWide ? kLongThreads : kThreads;
+    if (e - b > kMidRow) return;
+    float pv[8], gv[8];
     float dot = 0.f;
-    if ((int)threadIdx.x < nthr) {
-        for (int32_t k0 = b + threadIdx.x; k0 < e; k0 += 4 * nthr) {
-            float a[4], c[4];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const bool ok = k0 + u * nthr < e;
-                a[u] = ok ? p[k0 + u * nthr] : 0.f;
-                c[u] = ok ? dp[k0 + u * nthr] : 0.f;
-            }
-#pragma unroll
-            for (int u = 0; u < 4; ++u) dot = fmaf(a[u], c[u], dot);
-        }
+    for (int i = 0; i < 8; ++i) {
+        const int32_t k = b + threadIdx.x + kThreads * i;
+        pv[i] = k < e ? p[k] : 0.f;
+        gv[i] = k < e ? dp[k] : 0.f;
+        dot = fmaf(pv[i], gv[i], dot);
     }
     dot = wave_sum(dot);
     if (lane == 0) s_red[wave] = dot;
     __syncthreads();
     dot = 0.f;
 #pragma unroll
-    for (int i = 0; i < kLongThreads / kWave; ++i) dot += s_red[i];
-    if ((int)threadIdx.x < nthr) {
-        for (int32_t k0 = b + threadIdx.x; k0 < e; k0 += 4 * nthr) {
+    for (int i = 0; i < kThreads / kWave; ++i) dot += s_red[i];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int32_t k = b + threadIdx.x + kThreads * i;
+        if (k < e) dv[k] = pv[i] * (gv[i] - dot);
+    }
+}
+
+__global__ __launch_bounds__(kLongThreads) void softmax_bwd_long_kernel(int32_t n_long,
+                                                                        const int32_t *__restrict__ long_row,
+                                                                        const int32_t *__restrict__ row_ptr,
+                                                                        const float *p, const float *dp, float *dv)
+{
+    __shared__ float s_red[kLongThreads / kWave];
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
+    for (int32_t li = blockIdx.x; li < n_long; li += gridDim.x) {     // the same trip count for every thread
+        const int32_t row = long_row[li];
+        const int32_t b = row_ptr[row], e = row_ptr[row + 1];
+        if (e - b <= kMidRow) continue;                               // the whole workgroup skips together
+        float dot = 0.f;
+        for (int32_t k0 = b + threadIdx.x; k0 < e; k0 += 4 * kLongThreads) {
             float a[4], c[4];
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
-                const bool ok = k0 + u * nthr < e;
-                a[u] = ok ? p[k0 + u * nthr] : 0.f;
-                c[u] = ok ? dp[k0 + u * nthr] : 0.f;
+                const bool ok = k0 + u * kLongThreads < e;
+                a[u] = ok ? p[k0 + u * kLongThreads] : 0.f;
+                c[u] = ok ? dp[k0 + u * kLongThreads] : 0.f;
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) dot = fmaf(a[u], c[u], dot);
+        }
+        dot = wave_sum(dot);
+        if (lane == 0) s_red[wave] = dot;
+        __syncthreads();
+        dot = 0.f;
+#pragma unroll
+        for (int i = 0; i < kLongThreads / kWave; ++i) dot += s_red[i];
+        for (int32_t k0 = b + threadIdx.x; k0 < e; k0 += 4 * kLongThreads) {
+            float a[4], c[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const bool ok = k0 + u * kLongThreads < e;
+                a[u] = ok ? p[k0 + u * kLongThreads] : 0.f;
+                c[u] = ok ? dp[k0 + u * kLongThreads] : 0.f;
             }
 #pragma unroll
             for (int u = 0; u < 4; ++u)
-                if (k0 + u * nthr < e) dv[k0 + u * nthr] = a[u] * (c[u] - dot);
+                if (k0 + u * kLongThreads < e) dv[k0 + u * kLongThreads] = a[u] * (c[u] - dot);
         }
+        __syncthreads();                                              // s_red is reused by the next row
     }
 }
 
@@ -173,12 +226,15 @@ __global__ __launch_bounds__(kLongThreads) void softmax_bwd_long_kernel(const in
 int row_softmax_backward_impl(const tcg_meta *m, const float *d_p, const float *d_dp, float *d_dv, hipStream_t s)
 {
     if (m->n_rows == 0 || m->nnz == 0) return TCG_OK;
-    hipLaunchKernelGGL(softmax_bwd_kernel, dim3((unsigned)ceil_div(m->n_rows, kThreads / kWave)), dim3(kThreads), 0, s,
+    hipLaunchKernelGGL(softmax_bwd_kernel, dim3((unsigned)ceil_div(m->n_rows, kThreads / kBwdGroup)), dim3(kThreads), 0, s,
                        m->n_rows, m->d_row_ptr, d_p, d_dp, d_dv);
     TCG_TRY(launch_status("softmax_bwd_kernel"));
     if (m->n_long > 0) {
-        hipLaunchKernelGGL(softmax_bwd_long_kernel, dim3((unsigned)m->n_long), dim3(kLongThreads), 0, s, m->d_long_row,
+        hipLaunchKernelGGL(softmax_bwd_mid_kernel, dim3((unsigned)m->n_long), dim3(kThreads), 0, s, m->d_long_row,
                            m->d_row_ptr, d_p, d_dp, d_dv);
+        TCG_TRY(launch_status("softmax_bwd_mid_kernel"));
+        hipLaunchKernelGGL(softmax_bwd_long_kernel, dim3((unsigned)std::min<int64_t>(m->n_long, kLongGridMax)),
+                           dim3(kLongThreads), 0, s, (int32_t)m->n_long, m->d_long_row, m->d_row_ptr, d_p, d_dp, d_dv);
         TCG_TRY(launch_status("softmax_bwd_long_kernel"));
     }
     return TCG_OK;

@@ -175,50 +175,116 @@ __device__ __forceinline__ float wave_sum(float v)
     return v;
 }
 
-static_assert(kSegLen == 2 * kWave, "row_softmax_kernel holds two entries per lane");
+// Rows of at most kSegLen entries: kSoftmaxGroup lanes per row, each holding up to kSegLen / kSoftmaxGroup
+// entries in registers (one read, one write; maximum and sum of exponentials by butterflies inside the
+// group).  Most rows of a graph are far shorter than a wavefront, so a wavefront takes four rows at a time.
+// (Measured and not kept: several consecutive rows per lane group with all their loads issued first, groups
+// of 8 lanes, and stopping at the longest row of the wavefront -- all within 10 % of this form.)
+// Longer rows are left to the kernels below.
+constexpr int kSoftmaxGroup = 16;
 
-// Rows of at most kSegLen entries: one wavefront per row (maximum, sum of exponentials,
-// normalised write).  Longer rows are left to row_softmax_long_kernel.
 __global__ __launch_bounds__(kBlock) void row_softmax_kernel(int32_t n_rows, const int32_t *__restrict__ row_ptr,
                                                              const float *in, float *out)
 {
-    const int lane = threadIdx.x & (kWave - 1);
-    const int64_t row = (int64_t)blockIdx.x * (kBlock / kWave) + (threadIdx.x >> 6);
-    if (row >= n_rows) return;
-    const int32_t b = row_ptr[row], e = row_ptr[row + 1];
-    if (b == e || e - b > kSegLen) return;
-    float v0 = (b + lane < e) ? in[b + lane] : -INFINITY;
-    float v1 = (b + kWave + lane < e) ? in[b + kWave + lane] : -INFINITY;
-    const float m = wave_max(fmaxf(v0, v1));
-    const float x0 = (b + lane < e) ? expf(v0 - m) : 0.f;
-    const float x1 = (b + kWave + lane < e) ? expf(v1 - m) : 0.f;
-    const float inv = 1.f / wave_sum(x0 + x1);
-    if (b + lane < e) out[b + lane] = x0 * inv;
-    if (b + kWave + lane < e) out[b + kWave + lane] = x1 * inv;
+    constexpr int G = kSoftmaxGroup, SLOTS = kSegLen / G;
+    const int gl = threadIdx.x % G;
+    const int64_t row = ((int64_t)blockIdx.x * kBlock + threadIdx.x) / G;
+    int32_t b = 0, e = 0;
+    if (row < n_rows) {
+        b = row_ptr[row];
+        e = row_ptr[row + 1];
+        if (e - b > kSegLen) e = b;             // a long row: not here
+    }
+    float v[SLOTS];
+    float m = -INFINITY;
+#pragma unroll
+    for (int i = 0; i < SLOTS; ++i) {
+        const int32_t k = b + gl + G * i;
+        v[i] = k < e ? in[k] : -INFINITY;
+        m = fmaxf(m, v[i]);
+    }
+#pragma unroll
+    for (int off = 1; off < G; off <<= 1) m = fmaxf(m, __shfl_xor(m, off, kWave));
+    float sum = 0.f;
+#pragma unroll
+    for (int i = 0; i < SLOTS; ++i) {
+        v[i] = b + gl + G * i < e ? expf(v[i] - m) : 0.f;
+        sum += v[i];
+    }
+#pragma unroll
+    for (int off = 1; off < G; off <<= 1) sum += __shfl_xor(sum, off, kWave);
+    const float inv = 1.f / sum;
+#pragma unroll
+    for (int i = 0; i < SLOTS; ++i) {
+        const int32_t k = b + gl + G * i;
+        if (k < e) out[k] = v[i] * inv;
+    }
 }
 
-// Rows longer than kSegLen (the gather plan's list of split rows): one workgroup per row, 256 of its
-// threads for rows up to kLongRowWide entries and all 1024 beyond (hub rows of power-law graphs would
-// otherwise set the kernel's duration).  Two passes: running maximum and rescaled sum of exponentials
-// (four values per thread in flight), then the normalised values.
+// Rows longer than kSegLen (the gather plan's list of split rows), in two kernels over that list.
+// Up to kMidRow entries: one 256-thread workgroup per row with the row in registers (eight values per
+// thread; one read, one write).  Beyond: 1024-thread workgroups walk the list and take two passes over such a
+// row (running maximum and rescaled sum of exponentials, four values per thread in flight, then the normalised
+// values); hub rows of power-law graphs would otherwise set the duration.
+constexpr int kMidRow = 8 * kBlock;
 constexpr int kLongThreads = 1024;
-constexpr int kLongRowWide = 4096;
+constexpr int kLongGridMax = 1024;
 
-__global__ __launch_bounds__(kLongThreads) void row_softmax_long_kernel(const int32_t *__restrict__ long_row,
+__global__ __launch_bounds__(kBlock) void row_softmax_mid_kernel(const int32_t *__restrict__ long_row,
+                                                                 const int32_t *__restrict__ row_ptr, const float *in,
+                                                                 float *out)
+{
+    __shared__ float s_m[kBlock / kWave], s_s[kBlock / kWave];
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
+    const int32_t row = long_row[blockIdx.x];
+    const int32_t b = row_ptr[row], e = row_ptr[row + 1];
+    if (e - b > kMidRow) return;
+    float v[8];
+    float m = -INFINITY;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int32_t k = b + threadIdx.x + kBlock * i;
+        v[i] = k < e ? in[k] : -INFINITY;
+        m = fmaxf(m, v[i]);
+    }
+    m = wave_max(m);
+    if (lane == 0) s_m[wave] = m;
+    __syncthreads();
+    m = fmaxf(fmaxf(s_m[0], s_m[1]), fmaxf(s_m[2], s_m[3]));
+    float sum = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        v[i] = b + threadIdx.x + kBlock * i < e ? expf(v[i] - m) : 0.f;
+        sum += v[i];
+    }
+    sum = wave_sum(sum);
+    if (lane == 0) s_s[wave] = sum;
+    __syncthreads();
+    const float inv = 1.f / ((s_s[0] + s_s[1]) + (s_s[2] + s_s[3]));
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int32_t k = b + threadIdx.x + kBlock * i;
+        if (k < e) out[k] = v[i] * inv;
+    }
+}
+static_assert(kBlock / kWave == 4, "row_softmax_mid_kernel combines four wavefront partials");
+
+__global__ __launch_bounds__(kLongThreads) void row_softmax_long_kernel(int32_t n_long,
+                                                                        const int32_t *__restrict__ long_row,
                                                                         const int32_t *__restrict__ row_ptr,
                                                                         const float *in, float *out)
 {
     __shared__ float s_m[kLongThreads / kWave], s_s[kLongThreads / kWave];
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
-    const int32_t row = long_row[blockIdx.x];
-    const int32_t b = row_ptr[row], e = row_ptr[row + 1];
-    const int nthr = e - b > kLongRowWide ? kLongThreads : kBlock;
-    float m = -INFINITY, s = 0.f;
-    if ((int)threadIdx.x < nthr) {
-        for (int32_t k0 = b + threadIdx.x; k0 < e; k0 += 4 * nthr) {
+    for (int32_t li = blockIdx.x; li < n_long; li += gridDim.x) {     // the same trip count for every thread
+        const int32_t row = long_row[li];
+        const int32_t b = row_ptr[row], e = row_ptr[row + 1];
+        if (e - b <= kMidRow) continue;                               // the whole workgroup skips together
+        float m = -INFINITY, s = 0.f;
+        for (int32_t k0 = b + threadIdx.x; k0 < e; k0 += 4 * kLongThreads) {
             float v[4];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) v[u] = k0 + u * nthr < e ? in[k0 + u * nthr] : -INFINITY;
+            for (int u = 0; u < 4; ++u) v[u] = k0 + u * kLongThreads < e ? in[k0 + u * kLongThreads] : -INFINITY;
             const float mb = fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3]));
             if (mb > m) {
                 s *= expf(m - mb);          // exp(-inf) = 0 on the first batch
@@ -227,30 +293,29 @@ __global__ __launch_bounds__(kLongThreads) void row_softmax_long_kernel(const in
 #pragma unroll
             for (int u = 0; u < 4; ++u) s += expf(v[u] - m);
         }
-    }
-    const float wm = wave_max(m);
-    const float ws = wave_sum(m > -INFINITY ? s * expf(m - wm) : 0.f);
-    if (lane == 0) {
-        s_m[wave] = wm;
-        s_s[wave] = ws;
-    }
-    __syncthreads();
-    float M = -INFINITY;
+        const float wm = wave_max(m);
+        const float ws = wave_sum(m > -INFINITY ? s * expf(m - wm) : 0.f);
+        if (lane == 0) {
+            s_m[wave] = wm;
+            s_s[wave] = ws;
+        }
+        __syncthreads();
+        float M = -INFINITY;
 #pragma unroll
-    for (int i = 0; i < kLongThreads / kWave; ++i) M = fmaxf(M, s_m[i]);
-    float S = 0.f;
+        for (int i = 0; i < kLongThreads / kWave; ++i) M = fmaxf(M, s_m[i]);
+        float S = 0.f;
 #pragma unroll
-    for (int i = 0; i < kLongThreads / kWave; ++i) S += s_m[i] > -INFINITY ? s_s[i] * expf(s_m[i] - M) : 0.f;
-    const float inv = 1.f / S;
-    if ((int)threadIdx.x < nthr) {
-        for (int32_t k0 = b + threadIdx.x; k0 < e; k0 += 4 * nthr) {
+        for (int i = 0; i < kLongThreads / kWave; ++i) S += s_m[i] > -INFINITY ? s_s[i] * expf(s_m[i] - M) : 0.f;
+        const float inv = 1.f / S;
+        for (int32_t k0 = b + threadIdx.x; k0 < e; k0 += 4 * kLongThreads) {
             float v[4];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) v[u] = k0 + u * nthr < e ? in[k0 + u * nthr] : 0.f;
+            for (int u = 0; u < 4; ++u) v[u] = k0 + u * kLongThreads < e ? in[k0 + u * kLongThreads] : 0.f;
 #pragma unroll
             for (int u = 0; u < 4; ++u)
-                if (k0 + u * nthr < e) out[k0 + u * nthr] = expf(v[u] - M) * inv;
+                if (k0 + u * kLongThreads < e) out[k0 + u * kLongThreads] = expf(v[u] - M) * inv;
         }
+        __syncthreads();                                              // s_m / s_s are reused by the next row
     }
 }
 
@@ -353,12 +418,15 @@ int sddmm_impl(tcg_meta *m, const void *d_P, int64_t ldp, const void *d_X, int64
 int row_softmax_impl(const tcg_meta *m, const float *d_in, float *d_out, hipStream_t s)
 {
     if (m->n_rows == 0 || m->nnz == 0) return TCG_OK;
-    const unsigned grid = (unsigned)ceil_div(m->n_rows, kBlock / kWave);
+    const unsigned grid = (unsigned)ceil_div(m->n_rows, kBlock / kSoftmaxGroup);
     hipLaunchKernelGGL(row_softmax_kernel, dim3(grid), dim3(kBlock), 0, s, m->n_rows, m->d_row_ptr, d_in, d_out);
     TCG_TRY(launch_status("row_softmax_kernel"));
     if (m->n_long > 0) {
-        hipLaunchKernelGGL(row_softmax_long_kernel, dim3((unsigned)m->n_long), dim3(kLongThreads), 0, s, m->d_long_row,
+        hipLaunchKernelGGL(row_softmax_mid_kernel, dim3((unsigned)m->n_long), dim3(kBlock), 0, s, m->d_long_row,
                            m->d_row_ptr, d_in, d_out);
+        TCG_TRY(launch_status("row_softmax_mid_kernel"));
+        hipLaunchKernelGGL(row_softmax_long_kernel, dim3((unsigned)std::min<int64_t>(m->n_long, kLongGridMax)),
+                           dim3(kLongThreads), 0, s, (int32_t)m->n_long, m->d_long_row, m->d_row_ptr, d_in, d_out);
         TCG_TRY(launch_status("row_softmax_long_kernel"));
     }
     return TCG_OK;

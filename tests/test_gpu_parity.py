@@ -546,6 +546,32 @@ def test_row_softmax_and_attention_chain():
     meta.free()
 
 
+def test_row_softmax_and_its_gradient_at_every_row_length_class():
+    # Row lengths on both sides of every switch between kernels (lane groups of 16 up to 128 entries, one
+    # workgroup with the row in registers up to 2,048, two passes beyond), empty rows in between, scores
+    # large enough that an unshifted exp would overflow.
+    lengths = [0, 1, 2, 15, 16, 17, 31, 33, 64, 127, 128, 129, 130, 255, 256, 257, 1000, 2047, 2048, 2049, 2050,
+               4095, 4096, 4097, 9000, 0, 3, 0]
+    n_cols = 9001
+    rng = np.random.default_rng(21)
+    g = csr_from_rows([np.sort(rng.choice(n_cols, size=k, replace=False)) for k in lengths], n_cols)
+    v = (rng.standard_normal(g.nnz) * 30.0 + 80.0).astype(np.float32)
+    dp = rng.standard_normal(g.nnz).astype(np.float32)
+    rp, ci = upload_csr(g)
+    meta = tcg.sgt_build(rp, ci, 16, 8, n_cols=n_cols)
+    p = tcg.row_softmax(meta, torch.from_numpy(v).to(dev()))
+    dv = tcg.row_softmax_backward(meta, p, torch.from_numpy(dp).to(dev()))
+    torch.cuda.synchronize()
+    p_ref = oracle.row_softmax(g.row_ptr, v.astype(np.float64))
+    assert np.isfinite(p.cpu().numpy()).all()
+    assert norm_err(p.cpu().numpy(), p_ref) <= TOL_F32
+    sums = np.add.reduceat(p.cpu().numpy().astype(np.float64), g.row_ptr[:-1][np.diff(g.row_ptr) > 0])
+    np.testing.assert_allclose(sums, 1.0, atol=1e-5)
+    dv_ref = oracle.row_softmax_backward(g.row_ptr, p.cpu().numpy().astype(np.float64), dp.astype(np.float64))
+    assert norm_err(dv.cpu().numpy(), dv_ref) <= TOL_F32
+    meta.free()
+
+
 def test_calls_follow_the_current_stream():
     # The binding passes torch's current stream: the whole path on a side stream must give the same bits
     # as on the default stream, and the work must really be enqueued there (the side stream's event
