@@ -215,7 +215,16 @@ class GCNConv(torch.nn.Module):
 
     def forward(self, X, graph, edge_values=None):
         if self.linear.in_features > self.linear.out_features:
-            H = spmm(graph, self.linear(X), edge_values)
+            out = self.linear.out_features
+            pad = (-out) % 4
+            if pad and graph.nnz >= (1 << 20):
+                # A handful of classes on a large graph: aggregate rows padded with zero columns to whole
+                # 16-byte pieces (the vector kernels; 10 fp32 columns would go piece by piece) and drop the
+                # padding afterwards.  On small graphs the extra launches cost more than they save.
+                W = torch.nn.functional.pad(self.linear.weight, (0, 0, 0, pad))
+                H = spmm(graph, _NodeLinear.apply(X, W), edge_values)[:, :out]
+            else:
+                H = spmm(graph, self.linear(X), edge_values)
         else:
             H = self.linear(spmm(graph, X, edge_values))
         return H if self.bias is None else H + self.bias
