@@ -89,6 +89,25 @@ def test_config5_full_size_bf16(permute):
     meta.free()
 
 
+def test_config5_full_size_fp32_features_on_the_tile_path():
+    # The clustered graph in its original order with fp32 features: the default policy sends the windows to the
+    # tile kernels, which split fp32 operands into bf16 triples -- fp32 tolerance at full size, with edge values.
+    c = W.make_config(5, permute=False)
+    g = c["csr"]
+    X = W.features_normal(g.n_cols, 256, 9)                      # full fp32 mantissas (the workload's X is bf16-exact)
+    rp, ci = upload_csr(g)
+    meta = tcg.sgt_build(rp, ci, 16, 8)
+    assert tcg.sgt_plan_stats(meta)["n_tile_windows"] > 0.95 * meta.n_windows
+    Xd = upload_x(X, "f32")
+    w = np.random.default_rng(0).standard_normal(g.nnz).astype(np.float32)
+    e = tcg.sddmm(meta, Xd)
+    Y = tcg.spmm(meta, Xd, torch.from_numpy(w).to(dev()))
+    torch.cuda.synchronize()
+    assert norm_err(e.cpu().numpy(), oracle.sddmm(g.row_ptr, g.col_idx, X)) <= TOL_F32
+    assert norm_err(Y.cpu().numpy(), oracle.spmm(g.row_ptr, g.col_idx, X, w)) <= TOL_F32
+    meta.free()
+
+
 def test_config5_full_size_with_row_clustering():
     # Workload 5 as given (communities hidden by the random relabelling), clustered and relabelled on the
     # GPU as `bench.py --workload 5 --reorder 2` does: the permutation is bit-exact against the oracle at
