@@ -112,7 +112,9 @@ TCG_API int tcg_sgt_export(const tcg_meta *meta, int32_t *win_partition, int32_t
  * Chooses which windows run on the condensed-tile (MFMA) path.  TCG_POLICY_AUTO (the state
  * after tcg_sgt_build) sends a window there when window_h == 16, it has at most 512 unique
  * columns and its neighbour reuse nnz_w / U_w is at least `min_reuse` (<= 0 selects the library
- * default, 2).  The flag says where a window may go; a call takes the tile path only when its
+ * default, 2); when such windows hold less than 2 % of the stored entries, none is sent there (a
+ * launch that visits every window would cost more than it saves).  The flag says where a window
+ * may go; a call takes the tile path only when its
  * operands can be read in 16-byte pieces (else it gathers), and under TCG_POLICY_AUTO narrow
  * features are gathered as well: tcg_spmm sends windows of at most 512 entries to the tile kernels
  * from D >= 64 and windows with more entries from D >= 128, tcg_sddmm uses them at every width for

@@ -809,6 +809,13 @@ int choose_paths(tcg_meta *m, tcg_policy policy, float min_reuse, hipStream_t s)
     m->nnz_tile = (int64_t)h[2];
     m->n_tile_many = (int64_t)h[3];
     m->max_unique_many = (int64_t)h[4];
+    // A handful of qualifying windows is not worth a kernel launch that visits every window (18 us on a
+    // million-node graph): under the automatic policy the tile path is used from 2 % of the stored entries on.
+    if (policy == TCG_POLICY_AUTO && m->n_tile_win > 0 && m->nnz_tile * 50 < m->nnz) {
+        TCG_HIP(hipMemsetAsync(m->d_win_path, 0, (size_t)m->n_win, s));
+        TCG_HIP(hipStreamSynchronize(s));
+        m->n_tile_win = m->nnz_tile = m->n_tile_many = m->max_unique_many = 0;
+    }
     return TCG_OK;
 }
 

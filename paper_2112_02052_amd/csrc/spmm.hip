@@ -253,16 +253,70 @@ __global__ __launch_bounds__(kBlock) void spmm_gather_generic_kernel(
     }
 }
 
-// Adds the per-segment partials of every long row, in segment order.
+// Adds the per-segment partials of every long row: one workgroup per row.  When D is a multiple of 4 (and
+// at most 4 * kBlock) a thread takes four columns, so D / 4 threads cover a partial row and the kBlock /
+// (D / 4) thread groups each add every such-and-such partial (four loads in flight); the groups' sums
+// meet in LDS and are added in group order.  The order of the additions is fixed by the sizes alone, so
+// results repeat from run to run.  A hub row of a power-law graph has more than a thousand partials:
+// adding them one after the other in a single thread per column set the duration of the whole kernel.
 __global__ __launch_bounds__(kBlock) void spmm_reduce_long_kernel(
     int64_t n_long, const int32_t *__restrict__ long_row, const int32_t *__restrict__ long_slot_ptr,
     const float *__restrict__ partial, int64_t partial_ld, int32_t D, void *__restrict__ Y, int y_dt,
     int64_t ldy, const uint8_t *__restrict__ win_path, int32_t win_h, int tile_mask)
 {
+    __shared__ float4 s_part[kBlock];
     const int64_t li = blockIdx.x;
     const int32_t row = long_row[li];
     if (win_path != nullptr && ((tile_mask >> win_path[row / win_h]) & 1)) return;
     const int32_t s0 = long_slot_ptr[li], s1 = long_slot_ptr[li + 1];
+    const int32_t c4 = D / 4;                                  // threads per partial row
+    if (D % 4 == 0 && c4 <= kBlock) {
+        const int32_t nsg = kBlock / c4;                       // groups of threads, each on its own partials
+        const int32_t c = threadIdx.x % c4, sg = threadIdx.x / c4;
+        float4 a[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) a[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (sg < nsg) {
+            const float *base = partial + 4 * c;
+            int32_t s = s0 + sg;
+            for (; s + 3 * nsg < s1; s += 4 * nsg) {
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const float4 v = *reinterpret_cast<const float4 *>(base + (int64_t)(s + u * nsg) * partial_ld);
+                    a[u].x += v.x;
+                    a[u].y += v.y;
+                    a[u].z += v.z;
+                    a[u].w += v.w;
+                }
+            }
+            for (; s < s1; s += nsg) {
+                const float4 v = *reinterpret_cast<const float4 *>(base + (int64_t)s * partial_ld);
+                a[0].x += v.x;
+                a[0].y += v.y;
+                a[0].z += v.z;
+                a[0].w += v.w;
+            }
+        }
+        s_part[threadIdx.x] = make_float4((a[0].x + a[1].x) + (a[2].x + a[3].x), (a[0].y + a[1].y) + (a[2].y + a[3].y),
+                                          (a[0].z + a[1].z) + (a[2].z + a[3].z), (a[0].w + a[1].w) + (a[2].w + a[3].w));
+        __syncthreads();
+        if (sg == 0) {
+            float4 t = s_part[c];
+            for (int32_t g = 1; g < nsg; ++g) {
+                const float4 v = s_part[g * c4 + c];
+                t.x += v.x;
+                t.y += v.y;
+                t.z += v.z;
+                t.w += v.w;
+            }
+            const int64_t o = (int64_t)row * ldy + 4 * c;
+            store_elem(Y, o, y_dt, t.x);
+            store_elem(Y, o + 1, y_dt, t.y);
+            store_elem(Y, o + 2, y_dt, t.z);
+            store_elem(Y, o + 3, y_dt, t.w);
+        }
+        return;
+    }
     for (int32_t d = threadIdx.x; d < D; d += kBlock) {
         float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
         int32_t s = s0;

@@ -389,6 +389,26 @@ def test_rows_that_cannot_be_read_in_16_byte_pieces(x_dtype, D):
     meta.free()
 
 
+def test_auto_policy_ignores_a_negligible_tile_share():
+    # A graph without neighbour sharing in which k windows are replaced by dense 16 x 16 blocks: while these hold
+    # less than 2 % of the stored entries the automatic policy sends no window to the tile kernels (a launch
+    # over all windows would cost more than it saves); above that it does.  Results are right either way.
+    base = W.make_config(5, n=64 * 40, d=8, permute=True)["csr"]
+    X = W.round_to_bf16(W.features_normal(base.n_cols, 128, 4))
+    for k, expect_tiles in ((1, False), (12, True)):
+        rows = [base.col_idx[base.row_ptr[i]:base.row_ptr[i + 1]] for i in range(base.n_rows)]
+        for wdw in range(k):
+            for r in range(16):
+                rows[wdw * 16 + r] = np.arange(100 * wdw, 100 * wdw + 16, dtype=np.int32)
+        g = csr_from_rows(rows, base.n_cols)
+        assert (256 * k * 50 < g.nnz) == (not expect_tiles)
+        st = run_spmm_case(g, X, "bf16", None, tcg.POLICY_AUTO, TOL_F32)
+        assert (st["n_tile_windows"] >= k) if expect_tiles else (st["n_tile_windows"] == 0 and st["nnz_tile"] == 0)
+        run_sddmm_case(g, X, "bf16", tcg.POLICY_AUTO, TOL_F32)
+        st = run_spmm_case(g, X, "bf16", None, tcg.POLICY_TILE, TOL_F32)
+        assert st["nnz_tile"] == g.nnz                              # a forced policy is taken literally
+
+
 @pytest.mark.parametrize("D", [24, 72, 136, 264])
 def test_spmm_tile_path_with_32_row_windows(D):
     # Windows of 32 rows: two MFMA row blocks per wavefront.  Clustered graph (windows share neighbours),
