@@ -228,6 +228,27 @@ def main():
         steady["sddmm_%s_gedges" % f] = nnz / ms / 1e6
         steady["sddmm_%s_frac_hbm" % f] = b_sd / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS
 
+    # The operations of a step (without the translation) as one HIP graph launch against the same calls issued
+    # one by one: what a training loop gains from capturing them on the launch-bound workloads.
+    def all_ops():
+        for op in ops:
+            run_op(meta, op, Xd[feat])
+
+    steady["ops_eager_ms"] = timed_loop(all_ops, reps)
+    try:
+        graph = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                all_ops()
+        torch.cuda.synchronize()
+        steady["ops_graph_replay_ms"] = timed_loop(graph.replay, reps)
+        del graph
+    except Exception as exc:                                   # a graph is a convenience here, not the product
+        steady["ops_graph_replay_ms"] = None
+        print("graph capture skipped: %s" % exc, file=sys.stderr)
+
     # Workloads whose X and Y fit in the last-level cache: the same calls rotating over enough copies of X
     # and Y that every call finds them cold (about 1 GB in total, beyond L2 and the 256 MB memory-side cache).
     copy_bytes = N * D * (sx[feat] + 4)

@@ -592,6 +592,55 @@ def test_row_softmax_and_its_gradient_at_every_row_length_class():
     meta.free()
 
 
+def test_attention_chain_replays_from_a_hip_graph():
+    # SDDMM -> row softmax -> SpMM (and the fused call) captured once into a HIP graph and replayed with fresh
+    # inputs: after the first eager call has sized the library's scratch, the calls neither allocate nor
+    # synchronise, so a launch-bound layer can be replayed as one graph launch.  Every replay is checked
+    # against the eager result bit for bit, with eager work and synchronisations between the replays.
+    c = W.make_config(3, n=20000)
+    g = c["csr"]
+    rp, ci = upload_csr(g)
+    meta = tcg.sgt_build(rp, ci, 16, 8)
+    rng = np.random.default_rng(8)
+    inputs = [torch.from_numpy(rng.standard_normal(c["X"].shape).astype(np.float32)).to(dev()) for _ in range(3)]
+    Xs = inputs[0].clone()
+    e = torch.empty(g.nnz, device=dev())
+    p = torch.empty(g.nnz, device=dev())
+    Y = torch.empty_like(Xs)
+    Yf = torch.empty_like(Xs)
+
+    def chain():
+        tcg.sddmm(meta, Xs, out=e)
+        tcg.row_softmax(meta, e, out=p)
+        tcg.spmm(meta, Xs, p, Y=Y)
+        tcg.attention(meta, Xs, Y=Yf)
+
+    eager = []
+    for X in inputs:                                         # eager reference (also sizes the scratch buffers)
+        Xs.copy_(X)
+        chain()
+        torch.cuda.synchronize()
+        eager.append((Y.clone(), Yf.clone(), p.clone()))
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            chain()
+    torch.cuda.synchronize()
+    for rnd in range(2):
+        for X, (Y_ref, Yf_ref, p_ref) in zip(inputs, eager):
+            Xs.copy_(X)
+            Y.fill_(float("nan"))
+            Yf.fill_(float("nan"))
+            graph.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(Y, Y_ref) and torch.equal(Yf, Yf_ref) and torch.equal(p, p_ref), rnd
+            tcg.spmm(meta, X)                                # unrelated eager work between the replays
+            torch.cuda.synchronize()
+    meta.free()
+
+
 def test_calls_follow_the_current_stream():
     # The binding passes torch's current stream: the whole path on a side stream must give the same bits
     # as on the default stream, and the work must really be enqueued there (the side stream's event
