@@ -661,6 +661,26 @@ __global__ __launch_bounds__(kPartThreads) void cat_scatter_kernel(
     out_dst[p] = in_dst[sgi];
 }
 
+// Ordering of the split rows' segments inside the bands: key = the leading kSegSortBits bits of a segment's
+// start column (three passes of the radix sort; a finer order buys nothing).
+constexpr int kSegSortBits = 12;
+__global__ void seg_start_col_kernel(int64_t n, const int32_t *seg_ebeg, const int32_t *ci, int shift, int32_t *keys)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) keys[i] = ci[seg_ebeg[i]] >> shift;
+}
+
+__global__ void seg_permute_kernel(int64_t n, const int32_t *order, const int32_t *in_row, const int32_t *in_ebeg,
+                                   const int32_t *in_dst, int32_t *out_row, int32_t *out_ebeg, int32_t *out_dst)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const int32_t k = order[i];
+    out_row[i] = in_row[k];
+    out_ebeg[i] = in_ebeg[k];
+    out_dst[i] = in_dst[k];
+}
+
 // lane_tab[kLaneTabStride * l] = {band l start, count, band (kBands-1-l) start, count, tail start,
 // count} (see plan_segment()).  block_off == nullptr: no ordering, the whole list is the tail.
 __global__ void lane_table_kernel(int64_t n_seg, const int32_t *block_off, int64_t n_blocks, int32_t *lane_tab)
@@ -1039,6 +1059,34 @@ int sgt_build_impl(tcg_meta *m, int validate, hipStream_t s)
                                n_pblocks, row_o, ebeg_o, dst_o, m->d_seg_row, m->d_seg_ebeg, m->d_seg_dst);
             hipLaunchKernelGGL(lane_table_kernel, dim3(1), dim3(64), 0, s, m->n_seg, block_cnt, n_pblocks, m->d_lane_tab);
             TCG_TRY(launch_status("segment ordering kernels"));
+            // Inside the bands: by start column (the bands are ranges of start columns, so one stable sort of all
+            // split-row segments keeps them in place).  Segments that run one after the other on a die then
+            // read neighbouring -- on skewed graphs largely the same -- X rows.
+            const int64_t ns = m->n_slots;
+            if (ns > 1 && radix_sort_scratch_bytes(ns) > 0) {
+                const size_t arr = ((size_t)ns * 4 + 255) & ~(size_t)255;
+                PoolBuf sb;
+                sb.s = s;
+                TCG_TRY(pool_alloc(&sb.p, 7 * arr + radix_sort_scratch_bytes(ns)));
+                char *base = static_cast<char *>(sb.p);
+                int32_t *keys = reinterpret_cast<int32_t *>(base), *keys_o = reinterpret_cast<int32_t *>(base + arr),
+                        *order = reinterpret_cast<int32_t *>(base + 2 * arr), *t_row = reinterpret_cast<int32_t *>(base + 3 * arr),
+                        *t_ebeg = reinterpret_cast<int32_t *>(base + 4 * arr), *t_dst = reinterpret_cast<int32_t *>(base + 5 * arr);
+                void *sort_scratch = base + 7 * arr;
+                int bits = 1;
+                while (bits < 31 && ((int64_t)1 << bits) < (int64_t)m->n_cols) ++bits;
+                const int shift = bits > kSegSortBits ? bits - kSegSortBits : 0;   // the leading bits are enough
+                const unsigned g = (unsigned)ceil_div(ns, 256);
+                hipLaunchKernelGGL(seg_start_col_kernel, dim3(g), dim3(256), 0, s, ns, m->d_seg_ebeg, m->d_col_idx, shift,
+                                   keys);
+                TCG_TRY(radix_sort_pairs(keys, nullptr, ns, bits - shift, keys_o, order, sort_scratch, s));
+                hipLaunchKernelGGL(seg_permute_kernel, dim3(g), dim3(256), 0, s, ns, order, m->d_seg_row, m->d_seg_ebeg,
+                                   m->d_seg_dst, t_row, t_ebeg, t_dst);
+                TCG_HIP(hipMemcpyAsync(m->d_seg_row, t_row, (size_t)ns * 4, hipMemcpyDeviceToDevice, s));
+                TCG_HIP(hipMemcpyAsync(m->d_seg_ebeg, t_ebeg, (size_t)ns * 4, hipMemcpyDeviceToDevice, s));
+                TCG_HIP(hipMemcpyAsync(m->d_seg_dst, t_dst, (size_t)ns * 4, hipMemcpyDeviceToDevice, s));
+                TCG_TRY(launch_status("segment sort kernels"));
+            }                                   // sb waits for the stream and returns the buffer
         }
     }
     if (!ordered) {
