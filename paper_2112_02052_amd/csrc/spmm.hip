@@ -257,7 +257,7 @@ __global__ __launch_bounds__(kBlock) void spmm_gather_generic_kernel(
 // at most 4 * kBlock) a thread takes four columns, so D / 4 threads cover a partial row and the kBlock /
 // (D / 4) thread groups each add every such-and-such partial (four loads in flight); the groups' sums
 // meet in LDS and are added in group order.  The order of the additions is fixed by the sizes alone, so
-// results repeat from run to run.  A hub row of a power-law graph has more than a thousand partials:
+// results repeat from run to run.  A hub row of a power-law graph has hundreds of partials:
 // adding them one after the other in a single thread per column set the duration of the whole kernel.
 __global__ __launch_bounds__(kBlock) void spmm_reduce_long_kernel(
     int64_t n_long, const int32_t *__restrict__ long_row, const int32_t *__restrict__ long_slot_ptr,
