@@ -102,48 +102,82 @@ __device__ __forceinline__ float wave_sum(float v)
     return v;
 }
 
-// dv[e] = p[e] * (dp[e] - sum over the row of p * dp).  Rows of at most kSegLen entries: kBwdGroup lanes
-// per row with the row's entries in registers (four rows per wavefront); longer rows: one workgroup per
-// row (the gather plan's list of split rows).
-constexpr int kBwdGroup = 16;
+// dv[e] = p[e] * (dp[e] - sum over the row of p * dp).  Rows of at most kSegLen entries are taken from the
+// tail of the gather plan's segment list (single-segment rows; rows without entries are not in it, and on
+// graphs without neighbour sharing it is ordered by row length): a workgroup looks at the lengths of its 64
+// rows and runs the variant that fits the longest -- G lanes per row, S entries of p and of dp per lane in
+// registers, (G, S) = (4, 2) up to 8 entries, (8, 2) up to 16, (16, 2) up to 32, (16, 8) up to 128.  Longer
+// rows: the kernels below.
+constexpr int kTailRows = 64;          // rows per workgroup
 
-__global__ __launch_bounds__(kThreads) void softmax_bwd_kernel(int32_t n_rows, const int32_t *__restrict__ row_ptr,
-                                                               const float *p, const float *dp, float *dv)
+template <int G, int S>
+__device__ __forceinline__ void softmax_bwd_rows(const int32_t *s_b, const int32_t *s_e, const float *p, const float *dp,
+                                                 float *dv)
 {
-    constexpr int G = kBwdGroup, SLOTS = kSegLen / G;
+    constexpr int ROWS = kThreads / G;               // rows per pass of the workgroup
     const int gl = threadIdx.x % G;
-    const int64_t row = ((int64_t)blockIdx.x * kThreads + threadIdx.x) / G;
-    int32_t b = 0, e = 0;
-    if (row < n_rows) {
-        b = row_ptr[row];
-        e = row_ptr[row + 1];
-        if (e - b > kSegLen) e = b;             // a long row: not here
-    }
-    float pv[SLOTS], gv[SLOTS];
-    float dot = 0.f;
 #pragma unroll
-    for (int i = 0; i < SLOTS; ++i) {
-        const int32_t k = b + gl + G * i;
-        pv[i] = k < e ? p[k] : 0.f;
-        gv[i] = k < e ? dp[k] : 0.f;
-        dot = fmaf(pv[i], gv[i], dot);
-    }
+    for (int pass = 0; pass < kTailRows / ROWS; ++pass) {
+        const int r = pass * ROWS + threadIdx.x / G;
+        const int32_t b = s_b[r], e = s_e[r];
+        float pv[S], gv[S];
+        float dot = 0.f;
 #pragma unroll
-    for (int off = 1; off < G; off <<= 1) dot += __shfl_xor(dot, off, kWave);
+        for (int i = 0; i < S; ++i) {
+            const int32_t k = b + gl + G * i;
+            pv[i] = k < e ? p[k] : 0.f;
+            gv[i] = k < e ? dp[k] : 0.f;
+            dot = fmaf(pv[i], gv[i], dot);
+        }
 #pragma unroll
-    for (int i = 0; i < SLOTS; ++i) {
-        const int32_t k = b + gl + G * i;
-        if (k < e) dv[k] = pv[i] * (gv[i] - dot);
+        for (int off = 1; off < G; off <<= 1) dot += __shfl_xor(dot, off, kWave);
+#pragma unroll
+        for (int i = 0; i < S; ++i) {
+            const int32_t k = b + gl + G * i;
+            if (k < e) dv[k] = pv[i] * (gv[i] - dot);
+        }
     }
+}
+
+__global__ __launch_bounds__(kThreads) void softmax_bwd_kernel(int32_t tail_start, int32_t tail_count,
+                                                               const int32_t *__restrict__ seg_row,
+                                                               const int32_t *__restrict__ seg_dst,
+                                                               const int32_t *__restrict__ row_ptr, const float *p,
+                                                               const float *dp, float *dv)
+{
+    __shared__ int32_t s_b[kTailRows], s_e[kTailRows];
+    __shared__ int s_max;
+    if (threadIdx.x == 0) s_max = 0;
+    __syncthreads();
+    if (threadIdx.x < kTailRows) {
+        const int64_t i = (int64_t)blockIdx.x * kTailRows + threadIdx.x;
+        int32_t b = 0, e = 0;
+        if (i < tail_count && seg_dst[tail_start + i] < 0) {          // a piece of a split row: not here
+            const int32_t row = seg_row[tail_start + i];
+            b = row_ptr[row];
+            e = row_ptr[row + 1];
+        }
+        s_b[threadIdx.x] = b;
+        s_e[threadIdx.x] = e;
+        if (e > b) atomicMax(&s_max, e - b);
+    }
+    __syncthreads();
+    const int longest = s_max;
+    if (longest == 0) return;
+    if (longest <= 8) softmax_bwd_rows<4, 2>(s_b, s_e, p, dp, dv);
+    else if (longest <= 16) softmax_bwd_rows<8, 2>(s_b, s_e, p, dp, dv);
+    else if (longest <= 32) softmax_bwd_rows<16, 2>(s_b, s_e, p, dp, dv);
+    else softmax_bwd_rows<16, kSegLen / 16>(s_b, s_e, p, dp, dv);
 }
 
 // Long rows (the gather plan's list of split rows), in two kernels over that list.  Up to kMidRow entries:
 // one 256-thread workgroup per row, p and dp of the row in registers (eight values each per thread).
-// Beyond: 1024-thread workgroups walk the list and take two passes over such a row, four values per
+// Beyond: 1024-thread workgroups share the list out; a row of up to 8,192 entries still sits in registers, a
+// longer one takes two passes, four values per
 // thread in flight.
 constexpr int kMidRow = 8 * kThreads;
 constexpr int kLongThreads = 1024;
-constexpr int kLongGridMax = 1024;
+constexpr int kLongGridMax = 512;
 
 __global__ __launch_bounds__(kThreads) void softmax_bwd_mid_kernel(const int32_t *__restrict__ long_row,
                                                                    const int32_t *__restrict__ row_ptr, const float *p,
@@ -182,11 +216,52 @@ __global__ __launch_bounds__(kLongThreads) void softmax_bwd_long_kernel(int32_t 
                                                                         const float *p, const float *dp, float *dv)
 {
     __shared__ float s_red[kLongThreads / kWave];
+    __shared__ int32_t s_rows[kLongThreads];
+    __shared__ int s_n;
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
-    for (int32_t li = blockIdx.x; li < n_long; li += gridDim.x) {     // the same trip count for every thread
-        const int32_t row = long_row[li];
+    // The workgroup's share of the list is looked at by all threads at once and its rows beyond kMidRow entries
+    // are collected in LDS (in an order that may vary; the rows are independent, the results do not).
+    const int32_t chunk = (n_long + (int32_t)gridDim.x - 1) / (int32_t)gridDim.x;       // <= kLongThreads
+    if (threadIdx.x == 0) s_n = 0;
+    __syncthreads();
+    {
+        // strided, so that the long rows of a hub-heavy id range spread over the workgroups
+        const int64_t li = (int64_t)threadIdx.x * gridDim.x + blockIdx.x;
+        if ((int32_t)threadIdx.x < chunk && li < n_long) {
+            const int32_t row = long_row[li];
+            if (row_ptr[row + 1] - row_ptr[row] > kMidRow) s_rows[atomicAdd(&s_n, 1)] = row;
+        }
+    }
+    __syncthreads();
+    const int n_mine = s_n;
+    for (int i = 0; i < n_mine; ++i) {
+        const int32_t row = s_rows[i];
         const int32_t b = row_ptr[row], e = row_ptr[row + 1];
-        if (e - b <= kMidRow) continue;                               // the whole workgroup skips together
+        if (e - b <= 8 * kLongThreads) {
+            // up to 8,192 entries: p and dp of the row fit in the workgroup's registers
+            float pv[8], gv[8];
+            float d = 0.f;
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int32_t k = b + threadIdx.x + u * kLongThreads;
+                pv[u] = k < e ? p[k] : 0.f;
+                gv[u] = k < e ? dp[k] : 0.f;
+                d = fmaf(pv[u], gv[u], d);
+            }
+            d = wave_sum(d);
+            if (lane == 0) s_red[wave] = d;
+            __syncthreads();
+            d = 0.f;
+#pragma unroll
+            for (int j = 0; j < kLongThreads / kWave; ++j) d += s_red[j];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int32_t k = b + threadIdx.x + u * kLongThreads;
+                if (k < e) dv[k] = pv[u] * (gv[u] - d);
+            }
+            __syncthreads();                                          // s_red is reused by the next row
+            continue;
+        }
         float dot = 0.f;
         for (int32_t k0 = b + threadIdx.x; k0 < e; k0 += 4 * kLongThreads) {
             float a[4], c[4];
@@ -226,15 +301,20 @@ __global__ __launch_bounds__(kLongThreads) void softmax_bwd_long_kernel(int32_t 
 int row_softmax_backward_impl(const tcg_meta *m, const float *d_p, const float *d_dp, float *d_dv, hipStream_t s)
 {
     if (m->n_rows == 0 || m->nnz == 0) return TCG_OK;
-    hipLaunchKernelGGL(softmax_bwd_kernel, dim3((unsigned)ceil_div(m->n_rows, kThreads / kBwdGroup)), dim3(kThreads), 0, s,
-                       m->n_rows, m->d_row_ptr, d_p, d_dp, d_dv);
-    TCG_TRY(launch_status("softmax_bwd_kernel"));
+    const int32_t tail_start = m->h_lane_tab[4], tail_count = m->h_lane_tab[5];
+    if (tail_count > 0) {
+        hipLaunchKernelGGL(softmax_bwd_kernel, dim3((unsigned)ceil_div(tail_count, kTailRows)), dim3(kThreads), 0, s,
+                           tail_start, tail_count, m->d_seg_row, m->d_seg_dst, m->d_row_ptr, d_p, d_dp, d_dv);
+        TCG_TRY(launch_status("softmax_bwd_kernel"));
+    }
     if (m->n_long > 0) {
         hipLaunchKernelGGL(softmax_bwd_mid_kernel, dim3((unsigned)m->n_long), dim3(kThreads), 0, s, m->d_long_row,
                            m->d_row_ptr, d_p, d_dp, d_dv);
         TCG_TRY(launch_status("softmax_bwd_mid_kernel"));
-        hipLaunchKernelGGL(softmax_bwd_long_kernel, dim3((unsigned)std::min<int64_t>(m->n_long, kLongGridMax)),
-                           dim3(kLongThreads), 0, s, (int32_t)m->n_long, m->d_long_row, m->d_row_ptr, d_p, d_dp, d_dv);
+        const int64_t long_grid = std::max<int64_t>(std::min<int64_t>(m->n_long, kLongGridMax),
+                                                    ceil_div(m->n_long, kLongThreads));
+        hipLaunchKernelGGL(softmax_bwd_long_kernel, dim3((unsigned)long_grid), dim3(kLongThreads), 0, s,
+                           (int32_t)m->n_long, m->d_long_row, m->d_row_ptr, d_p, d_dp, d_dv);
         TCG_TRY(launch_status("softmax_bwd_long_kernel"));
     }
     return TCG_OK;

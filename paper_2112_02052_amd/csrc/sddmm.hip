@@ -175,60 +175,90 @@ __device__ __forceinline__ float wave_sum(float v)
     return v;
 }
 
-// Rows of at most kSegLen entries: kSoftmaxGroup lanes per row, each holding up to kSegLen / kSoftmaxGroup
-// entries in registers (one read, one write; maximum and sum of exponentials by butterflies inside the
-// group).  Most rows of a graph are far shorter than a wavefront, so a wavefront takes four rows at a time.
-// (Measured and not kept: several consecutive rows per lane group with all their loads issued first, groups
-// of 8 lanes, and stopping at the longest row of the wavefront -- all within 10 % of this form.)
-// Longer rows are left to the kernels below.
-constexpr int kSoftmaxGroup = 16;
+// Rows of at most kSegLen entries.  They are taken from the tail of the gather plan's segment list (the
+// single-segment rows), not from the row index: rows without entries are not in that list at all -- on a
+// power-law graph that is close to half of the rows -- and on graphs whose windows share few neighbours the
+// list is ordered by row length, so a workgroup's 64 rows are alike.  The workgroup looks at its rows' lengths
+// first and then runs the variant that fits the longest of them: G lanes per row with S entries per lane
+// in registers, (G, S) = (4, 2) up to 8 entries, (8, 2) up to 16, (16, 2) up to 32, (16, 8) up to 128; maximum
+// and sum of exponentials by butterflies inside the lane group; one read, one write.
+constexpr int kTailRows = 64;          // rows per workgroup
 
-__global__ __launch_bounds__(kBlock) void row_softmax_kernel(int32_t n_rows, const int32_t *__restrict__ row_ptr,
-                                                             const float *in, float *out)
+template <int G, int S>
+__device__ __forceinline__ void softmax_rows(const int32_t *s_b, const int32_t *s_e, const float *in, float *out)
 {
-    constexpr int G = kSoftmaxGroup, SLOTS = kSegLen / G;
+    constexpr int ROWS = kBlock / G;                 // rows per pass of the workgroup
     const int gl = threadIdx.x % G;
-    const int64_t row = ((int64_t)blockIdx.x * kBlock + threadIdx.x) / G;
-    int32_t b = 0, e = 0;
-    if (row < n_rows) {
-        b = row_ptr[row];
-        e = row_ptr[row + 1];
-        if (e - b > kSegLen) e = b;             // a long row: not here
+#pragma unroll
+    for (int pass = 0; pass < kTailRows / ROWS; ++pass) {
+        const int r = pass * ROWS + threadIdx.x / G;
+        const int32_t b = s_b[r], e = s_e[r];
+        float v[S];
+        float m = -INFINITY;
+#pragma unroll
+        for (int i = 0; i < S; ++i) {
+            const int32_t k = b + gl + G * i;
+            v[i] = k < e ? in[k] : -INFINITY;
+            m = fmaxf(m, v[i]);
+        }
+#pragma unroll
+        for (int off = 1; off < G; off <<= 1) m = fmaxf(m, __shfl_xor(m, off, kWave));
+        float sum = 0.f;
+#pragma unroll
+        for (int i = 0; i < S; ++i) {
+            v[i] = b + gl + G * i < e ? expf(v[i] - m) : 0.f;
+            sum += v[i];
+        }
+#pragma unroll
+        for (int off = 1; off < G; off <<= 1) sum += __shfl_xor(sum, off, kWave);
+        const float inv = 1.f / sum;
+#pragma unroll
+        for (int i = 0; i < S; ++i) {
+            const int32_t k = b + gl + G * i;
+            if (k < e) out[k] = v[i] * inv;
+        }
     }
-    float v[SLOTS];
-    float m = -INFINITY;
-#pragma unroll
-    for (int i = 0; i < SLOTS; ++i) {
-        const int32_t k = b + gl + G * i;
-        v[i] = k < e ? in[k] : -INFINITY;
-        m = fmaxf(m, v[i]);
+}
+
+__global__ __launch_bounds__(kBlock) void row_softmax_kernel(int32_t tail_start, int32_t tail_count,
+                                                             const int32_t *__restrict__ seg_row,
+                                                             const int32_t *__restrict__ seg_dst,
+                                                             const int32_t *__restrict__ row_ptr, const float *in,
+                                                             float *out)
+{
+    __shared__ int32_t s_b[kTailRows], s_e[kTailRows];
+    __shared__ int s_max;
+    if (threadIdx.x == 0) s_max = 0;
+    __syncthreads();
+    if (threadIdx.x < kTailRows) {
+        const int64_t i = (int64_t)blockIdx.x * kTailRows + threadIdx.x;
+        int32_t b = 0, e = 0;
+        if (i < tail_count && seg_dst[tail_start + i] < 0) {          // a piece of a split row: not here
+            const int32_t row = seg_row[tail_start + i];
+            b = row_ptr[row];
+            e = row_ptr[row + 1];
+        }
+        s_b[threadIdx.x] = b;
+        s_e[threadIdx.x] = e;
+        if (e > b) atomicMax(&s_max, e - b);
     }
-#pragma unroll
-    for (int off = 1; off < G; off <<= 1) m = fmaxf(m, __shfl_xor(m, off, kWave));
-    float sum = 0.f;
-#pragma unroll
-    for (int i = 0; i < SLOTS; ++i) {
-        v[i] = b + gl + G * i < e ? expf(v[i] - m) : 0.f;
-        sum += v[i];
-    }
-#pragma unroll
-    for (int off = 1; off < G; off <<= 1) sum += __shfl_xor(sum, off, kWave);
-    const float inv = 1.f / sum;
-#pragma unroll
-    for (int i = 0; i < SLOTS; ++i) {
-        const int32_t k = b + gl + G * i;
-        if (k < e) out[k] = v[i] * inv;
-    }
+    __syncthreads();
+    const int longest = s_max;
+    if (longest == 0) return;
+    if (longest <= 8) softmax_rows<4, 2>(s_b, s_e, in, out);
+    else if (longest <= 16) softmax_rows<8, 2>(s_b, s_e, in, out);
+    else if (longest <= 32) softmax_rows<16, 2>(s_b, s_e, in, out);
+    else softmax_rows<16, kSegLen / 16>(s_b, s_e, in, out);
 }
 
 // Rows longer than kSegLen (the gather plan's list of split rows), in two kernels over that list.
 // Up to kMidRow entries: one 256-thread workgroup per row with the row in registers (eight values per
-// thread; one read, one write).  Beyond: 1024-thread workgroups walk the list and take two passes over such a
-// row (running maximum and rescaled sum of exponentials, four values per thread in flight, then the normalised
+// thread; one read, one write).  Beyond: 1024-thread workgroups share the list out; a row of up to 8,192 entries
+// still sits in registers, a longer one takes two passes (running maximum and rescaled sum of exponentials, four values per thread in flight, then the normalised
 // values); hub rows of power-law graphs would otherwise set the duration.
 constexpr int kMidRow = 8 * kBlock;
 constexpr int kLongThreads = 1024;
-constexpr int kLongGridMax = 1024;
+constexpr int kLongGridMax = 512;
 
 __global__ __launch_bounds__(kBlock) void row_softmax_mid_kernel(const int32_t *__restrict__ long_row,
                                                                  const int32_t *__restrict__ row_ptr, const float *in,
@@ -275,11 +305,66 @@ __global__ __launch_bounds__(kLongThreads) void row_softmax_long_kernel(int32_t 
                                                                         const float *in, float *out)
 {
     __shared__ float s_m[kLongThreads / kWave], s_s[kLongThreads / kWave];
+    __shared__ int32_t s_rows[kLongThreads];
+    __shared__ int s_n;
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
-    for (int32_t li = blockIdx.x; li < n_long; li += gridDim.x) {     // the same trip count for every thread
-        const int32_t row = long_row[li];
+    // The workgroup's share of the list is looked at by all threads at once (one entry each) and its rows
+    // beyond kMidRow entries are collected in LDS: walking the list entry by entry would pay two dependent
+    // loads for every row that only has to be skipped.  The order of the collected rows varies from run to
+    // run; the rows are independent, so the results do not.
+    const int32_t chunk = (n_long + (int32_t)gridDim.x - 1) / (int32_t)gridDim.x;       // <= kLongThreads
+    if (threadIdx.x == 0) s_n = 0;
+    __syncthreads();
+    {
+        // strided, so that the long rows of a hub-heavy id range spread over the workgroups
+        const int64_t li = (int64_t)threadIdx.x * gridDim.x + blockIdx.x;
+        if ((int32_t)threadIdx.x < chunk && li < n_long) {
+            const int32_t row = long_row[li];
+            if (row_ptr[row + 1] - row_ptr[row] > kMidRow) s_rows[atomicAdd(&s_n, 1)] = row;
+        }
+    }
+    __syncthreads();
+    const int n_mine = s_n;
+    for (int i = 0; i < n_mine; ++i) {
+        const int32_t row = s_rows[i];
         const int32_t b = row_ptr[row], e = row_ptr[row + 1];
-        if (e - b <= kMidRow) continue;                               // the whole workgroup skips together
+        if (e - b <= 8 * kLongThreads) {
+            // up to 8,192 entries: the row fits in the workgroup's registers (one read, one write)
+            float v[8];
+            float mx = -INFINITY;
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int32_t k = b + threadIdx.x + u * kLongThreads;
+                v[u] = k < e ? in[k] : -INFINITY;
+                mx = fmaxf(mx, v[u]);
+            }
+            mx = wave_max(mx);
+            if (lane == 0) s_m[wave] = mx;
+            __syncthreads();
+            float M = -INFINITY;
+#pragma unroll
+            for (int j = 0; j < kLongThreads / kWave; ++j) M = fmaxf(M, s_m[j]);
+            float sum = 0.f;
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                v[u] = b + threadIdx.x + u * kLongThreads < e ? expf(v[u] - M) : 0.f;
+                sum += v[u];
+            }
+            sum = wave_sum(sum);
+            if (lane == 0) s_s[wave] = sum;
+            __syncthreads();
+            float S = 0.f;
+#pragma unroll
+            for (int j = 0; j < kLongThreads / kWave; ++j) S += s_s[j];
+            const float inv = 1.f / S;
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int32_t k = b + threadIdx.x + u * kLongThreads;
+                if (k < e) out[k] = v[u] * inv;
+            }
+            __syncthreads();                                          // s_m / s_s are reused by the next row
+            continue;
+        }
         float m = -INFINITY, s = 0.f;
         for (int32_t k0 = b + threadIdx.x; k0 < e; k0 += 4 * kLongThreads) {
             float v[4];
@@ -418,15 +503,20 @@ int sddmm_impl(tcg_meta *m, const void *d_P, int64_t ldp, const void *d_X, int64
 int row_softmax_impl(const tcg_meta *m, const float *d_in, float *d_out, hipStream_t s)
 {
     if (m->n_rows == 0 || m->nnz == 0) return TCG_OK;
-    const unsigned grid = (unsigned)ceil_div(m->n_rows, kBlock / kSoftmaxGroup);
-    hipLaunchKernelGGL(row_softmax_kernel, dim3(grid), dim3(kBlock), 0, s, m->n_rows, m->d_row_ptr, d_in, d_out);
-    TCG_TRY(launch_status("row_softmax_kernel"));
+    const int32_t tail_start = m->h_lane_tab[4], tail_count = m->h_lane_tab[5];
+    if (tail_count > 0) {
+        hipLaunchKernelGGL(row_softmax_kernel, dim3((unsigned)ceil_div(tail_count, kTailRows)), dim3(kBlock), 0, s,
+                           tail_start, tail_count, m->d_seg_row, m->d_seg_dst, m->d_row_ptr, d_in, d_out);
+        TCG_TRY(launch_status("row_softmax_kernel"));
+    }
     if (m->n_long > 0) {
         hipLaunchKernelGGL(row_softmax_mid_kernel, dim3((unsigned)m->n_long), dim3(kBlock), 0, s, m->d_long_row,
                            m->d_row_ptr, d_in, d_out);
         TCG_TRY(launch_status("row_softmax_mid_kernel"));
-        hipLaunchKernelGGL(row_softmax_long_kernel, dim3((unsigned)std::min<int64_t>(m->n_long, kLongGridMax)),
-                           dim3(kLongThreads), 0, s, (int32_t)m->n_long, m->d_long_row, m->d_row_ptr, d_in, d_out);
+        const int64_t long_grid = std::max<int64_t>(std::min<int64_t>(m->n_long, kLongGridMax),
+                                                    ceil_div(m->n_long, kLongThreads));
+        hipLaunchKernelGGL(row_softmax_long_kernel, dim3((unsigned)long_grid), dim3(kLongThreads), 0, s,
+                           (int32_t)m->n_long, m->d_long_row, m->d_row_ptr, d_in, d_out);
         TCG_TRY(launch_status("row_softmax_long_kernel"));
     }
     return TCG_OK;

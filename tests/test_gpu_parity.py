@@ -567,11 +567,11 @@ def test_row_softmax_and_attention_chain():
 
 
 def test_row_softmax_and_its_gradient_at_every_row_length_class():
-    # Row lengths on both sides of every switch between kernels (lane groups of 16 up to 128 entries, one
-    # workgroup with the row in registers up to 2,048, two passes beyond), empty rows in between, scores
-    # large enough that an unshifted exp would overflow.
+    # Row lengths on both sides of every switch between kernels and variants (lane groups of 4, 8 and 16 up to 128
+    # entries, one workgroup with the row in registers up to 2,048 and up to 8,192, two passes beyond), empty rows
+    # in between, scores large enough that an unshifted exp would overflow.
     lengths = [0, 1, 2, 15, 16, 17, 31, 33, 64, 127, 128, 129, 130, 255, 256, 257, 1000, 2047, 2048, 2049, 2050,
-               4095, 4096, 4097, 9000, 0, 3, 0]
+               4095, 4096, 4097, 8191, 8192, 8193, 9000, 0, 3, 0, 5, 7, 8, 9, 12, 24, 32, 40]
     n_cols = 9001
     rng = np.random.default_rng(21)
     g = csr_from_rows([np.sort(rng.choice(n_cols, size=k, replace=False)) for k in lengths], n_cols)
@@ -590,6 +590,20 @@ def test_row_softmax_and_its_gradient_at_every_row_length_class():
     dv_ref = oracle.row_softmax_backward(g.row_ptr, p.cpu().numpy().astype(np.float64), dp.astype(np.float64))
     assert norm_err(dv.cpu().numpy(), dv_ref) <= TOL_F32
     meta.free()
+    # graphs whose rows all stay below 8, 16 and 32 entries: the variants with 4, 8 and 16 lanes per row
+    for cap in (8, 16, 32):
+        g = csr_from_rows([np.sort(rng.choice(500, size=int(k), replace=False)) for k in rng.integers(0, cap + 1, 300)], 500)
+        v = (rng.standard_normal(g.nnz) * 30.0 + 80.0).astype(np.float32)
+        dp = rng.standard_normal(g.nnz).astype(np.float32)
+        rp, ci = upload_csr(g)
+        meta = tcg.sgt_build(rp, ci, 16, 8, n_cols=500)
+        p = tcg.row_softmax(meta, torch.from_numpy(v).to(dev()))
+        dv = tcg.row_softmax_backward(meta, p, torch.from_numpy(dp).to(dev()))
+        torch.cuda.synchronize()
+        assert norm_err(p.cpu().numpy(), oracle.row_softmax(g.row_ptr, v.astype(np.float64))) <= TOL_F32, cap
+        dv_ref = oracle.row_softmax_backward(g.row_ptr, p.cpu().numpy().astype(np.float64), dp.astype(np.float64))
+        assert norm_err(dv.cpu().numpy(), dv_ref) <= TOL_F32, cap
+        meta.free()
 
 
 def test_attention_chain_replays_from_a_hip_graph():
