@@ -277,7 +277,7 @@ __device__ __forceinline__ void split8(const f32x4 &u, const f32x4 &v, uint4 &h,
 constexpr int kScoreStrideF = 17;          // floats per row of a 16-column score tile
 
 template <int KSTEPS, bool MANY>
-__global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(KSTEPS >= 8 ? 2 : 4))) void sddmm_tile_f32_kernel(
+__global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(KSTEPS >= 8 || MANY ? 2 : 4))) void sddmm_tile_f32_kernel(
     int32_t n_rows, int64_t n_win, const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ edge_to_col,
     const int32_t *__restrict__ win_unique_ptr, const int32_t *__restrict__ col_to_row,
     const uint8_t *__restrict__ win_path, const float *__restrict__ P, int64_t ldp, const float *__restrict__ X,
