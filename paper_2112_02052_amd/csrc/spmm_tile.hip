@@ -345,7 +345,7 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(3))) void
     }
 }
 
-// ---- neighbour rows straight into the MFMA operand registers (16-row windows of class kTileFew) --------
+// ---- neighbour rows straight into the MFMA operand registers (16-row windows, both tile classes) ---------
 // The B operand of v_mfma_f32_16x16x16 wants, per lane (n = lane % 16, q = lane / 16), the four values
 // B[4q .. 4q+3][n]: four NEIGHBOURS, one feature.  Memory has the features of a neighbour contiguous, which
 // is why the kernel above stages the rows in LDS and reads them back transposed.  But nothing says that
@@ -356,7 +356,9 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(3))) void
 // accumulators a lane ends up with 4 CONSECUTIVE features of its four output rows, one 16-byte store per
 // row with 16 lanes writing 256 contiguous bytes -- no LDS staging on the way in, none on the way out,
 // no barrier.  A second set of pieces, 64 features further on, fills a block of 128 features.  LDS
-// only holds the 16 x 16 slice of the condensed adjacency (the A operand) and the row pointers.
+// only holds the A operand and the row pointers: for a window of class kTileFew the window's edges (as row /
+// condensed-column codes) and the 16 x 16 slice of the condensed adjacency rebuilt from them per chunk,
+// for class kTileMany (FULL_A) the whole 16 x U_w adjacency, built once.
 // NFB: blocks of 128 features per wavefront (a wider D is split over n_dparts wavefronts).
 template <int DT, bool HAS_W, int NFB, bool FULL_A>
 __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(4))) void spmm_tile_direct_kernel(
