@@ -118,7 +118,8 @@ TCG_API int tcg_sgt_export(const tcg_meta *meta, int32_t *win_partition, int32_t
  * operands can be read in 16-byte pieces (else it gathers), and under TCG_POLICY_AUTO narrow
  * features are gathered as well: tcg_spmm sends windows of at most 512 entries to the tile kernels
  * from D >= 64 and windows with more entries from D >= 128, tcg_sddmm uses them at every width for
- * bf16/f16 and from D >= 64 for fp32 (measured crossovers).  bf16/f16 features feed the MFMA units
+ * bf16/f16 and, for fp32, from D >= 64 when the tile-path windows hold at least 3 entries per distinct
+ * column on average (measured crossovers).  bf16/f16 features feed the MFMA units
  * directly (products of rounded edge values: the 1e-2 tolerance class); fp32 features are split
  * exactly into three bf16 values each and the six leading partial products are accumulated in fp32,
  * which keeps fp32 accuracy (D a multiple of 4, at most 1024 for tcg_spmm and 256 for tcg_sddmm).

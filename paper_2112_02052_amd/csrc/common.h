@@ -23,6 +23,9 @@ constexpr uint8_t kTileFew = 1, kTileMany = 2;
 constexpr int kTileFewEdges = 512;
 // SpMM sends a class to the MFMA kernels only from this feature width on (measured crossovers).
 constexpr int kTileMinWidthFew = 64, kTileMinWidthMany = 128;
+// fp32 features on the tile path cost six MFMAs per product: SDDMM takes it from this mean reuse (stored
+// entries per distinct column over the tile-path windows) on; measured crossover 2.5 - 3.5.
+constexpr float kTileMinReuseF32Sddmm = 3.0f;
 
 // Records the text of a failing HIP call for tcg_strerror (thread local).
 void set_hip_error(hipError_t e, const char *what);
@@ -228,4 +231,5 @@ struct tcg_meta {
     uint8_t *d_win_path = nullptr;        // [n_win] 1 = condensed-tile path
     int64_t n_tile_win = 0, nnz_tile = 0;   // windows on the tile path (both classes) and their edges
     int64_t n_tile_many = 0, max_unique_many = 0;   // class kTileMany: count, widest window
+    int64_t unique_tile = 0;                        // distinct columns summed over the tile-path windows
 };

@@ -468,7 +468,8 @@ int sddmm_impl(tcg_meta *m, const void *d_P, int64_t ldp, const void *d_X, int64
     if (m->n_rows == 0 || m->nnz == 0) return TCG_OK;
     // fp32 rows take the tile path (six MFMAs per product) only where it was measured to pay; a forced policy
     // is taken literally
-    const bool wide_enough = x_dt != TCG_F32 || D >= kTileMinWidthFew || m->policy == TCG_POLICY_TILE;
+    const bool wide_enough = x_dt != TCG_F32 || m->policy == TCG_POLICY_TILE ||
+                             (D >= kTileMinWidthFew && (float)m->nnz_tile >= kTileMinReuseF32Sddmm * (float)m->unique_tile);
     const bool use_tiles = m->n_tile_win > 0 && m->win_h == 16 && wide_enough &&
                            sddmm_tile_supports(x_dt, D, ldx, d_X) && sddmm_tile_supports(x_dt, D, ldp, d_P);
     const uint8_t *win_path = use_tiles ? m->d_win_path : nullptr;

@@ -716,7 +716,7 @@ __global__ __launch_bounds__(256) void choose_path_kernel(int32_t n_rows, int32_
                                                           uint8_t *win_path, unsigned long long *counts)
 {
     const int64_t w = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    unsigned long long tiles = 0, tile_win = 0, tile_nnz = 0, tile_many = 0;
+    unsigned long long tiles = 0, tile_win = 0, tile_nnz = 0, tile_many = 0, tile_unique = 0;
     if (w < n_win) {
         int32_t lo, hi;
         window_edge_range(rp, n_rows, win_h, w, &lo, &hi);
@@ -737,6 +737,7 @@ __global__ __launch_bounds__(256) void choose_path_kernel(int32_t n_rows, int32_
         if (tile) {
             tile_win = 1;
             tile_nnz = (unsigned long long)nnz_w;
+            tile_unique = (unsigned long long)uw;
         }
         if (many) {
             tile_many = 1;
@@ -747,11 +748,13 @@ __global__ __launch_bounds__(256) void choose_path_kernel(int32_t n_rows, int32_
     tile_win = wave_sum_u64(tile_win);
     tile_nnz = wave_sum_u64(tile_nnz);
     tile_many = wave_sum_u64(tile_many);
+    tile_unique = wave_sum_u64(tile_unique);
     if ((threadIdx.x & (kWave - 1)) == 0) {
         if (tiles) atomicAdd(&counts[0], tiles);
         if (tile_win) atomicAdd(&counts[1], tile_win);
         if (tile_nnz) atomicAdd(&counts[2], tile_nnz);
         if (tile_many) atomicAdd(&counts[3], tile_many);
+        if (tile_unique) atomicAdd(&counts[5], tile_unique);
     }
 }
 
@@ -810,16 +813,17 @@ int choose_paths(tcg_meta *m, tcg_policy policy, float min_reuse, hipStream_t s)
 {
     if (policy == TCG_POLICY_TILE && m->win_h != 16 && m->win_h != 32) return TCG_EINVAL;
     if (min_reuse <= 0.f) min_reuse = kDefaultMinReuse;
-    // [0] tiles, [1] tile-path windows, [2] their edges, [3] windows of class kTileMany, [4] their widest
+    // [0] tiles, [1] tile-path windows, [2] their edges, [3] windows of class kTileMany, [4] their widest,
+    // [5] distinct columns summed over the tile-path windows
     unsigned long long *counts = m->d_counters;
-    TCG_HIP(hipMemsetAsync(counts, 0, 5 * sizeof(unsigned long long), s));
+    TCG_HIP(hipMemsetAsync(counts, 0, 6 * sizeof(unsigned long long), s));
     if (m->n_win > 0) {
         hipLaunchKernelGGL(choose_path_kernel, dim3((unsigned)ceil_div(m->n_win, 256)), dim3(256), 0, s,
                            m->n_rows, m->win_h, m->tile_w, m->n_win, m->d_row_ptr, m->d_win_unique_ptr,
                            (int)policy, min_reuse, m->d_win_partition, m->d_win_path, counts);
         TCG_TRY(launch_status("choose_path_kernel"));
     }
-    unsigned long long h[5];
+    unsigned long long h[6];
     TCG_HIP(hipMemcpyAsync(h, counts, sizeof(h), hipMemcpyDeviceToHost, s));
     TCG_HIP(hipStreamSynchronize(s));
     m->policy = policy;
@@ -829,12 +833,13 @@ int choose_paths(tcg_meta *m, tcg_policy policy, float min_reuse, hipStream_t s)
     m->nnz_tile = (int64_t)h[2];
     m->n_tile_many = (int64_t)h[3];
     m->max_unique_many = (int64_t)h[4];
+    m->unique_tile = (int64_t)h[5];
     // A handful of qualifying windows is not worth a kernel launch that visits every window (18 us on a
     // million-node graph): under the automatic policy the tile path is used from 2 % of the stored entries on.
     if (policy == TCG_POLICY_AUTO && m->n_tile_win > 0 && m->nnz_tile * 50 < m->nnz) {
         TCG_HIP(hipMemsetAsync(m->d_win_path, 0, (size_t)m->n_win, s));
         TCG_HIP(hipStreamSynchronize(s));
-        m->n_tile_win = m->nnz_tile = m->n_tile_many = m->max_unique_many = 0;
+        m->n_tile_win = m->nnz_tile = m->n_tile_many = m->max_unique_many = m->unique_tile = 0;
     }
     return TCG_OK;
 }
