@@ -106,8 +106,7 @@ __device__ __forceinline__ float wave_sum(float v)
 // tail of the gather plan's segment list (single-segment rows; rows without entries are not in it, and on
 // graphs without neighbour sharing it is ordered by row length): a workgroup looks at the lengths of its 64
 // rows and runs the variant that fits the longest -- G lanes per row, S entries of p and of dp per lane in
-// registers, (G, S) = (4, 2) up to 8 entries, (8, 2) up to 16, (16, 2) up to 32, (16, 8) up to 128.  Longer
-// rows: the kernels below.
+// registers, (G, S) = (4, 2) up to 8 entries, (8, 2) up to 16, (16, 2) up to 32, (16, 8) up to 128.
 constexpr int kTailRows = 64;          // rows per workgroup
 
 template <int G, int S>
@@ -139,18 +138,91 @@ __device__ __forceinline__ void softmax_bwd_rows(const int32_t *s_b, const int32
     }
 }
 
-__global__ __launch_bounds__(kThreads) void softmax_bwd_kernel(int32_t tail_start, int32_t tail_count,
+// A row of the gather plan's list of split rows (more than kSegLen entries), by one 256-thread workgroup: up to
+// 8 * 256 entries p and dp of the row sit in registers; a longer row takes two passes, eight values of each
+// operand per thread in flight.  (More registers per thread would halve the resident wavefronts of the whole
+// kernel, which the short rows need more than the long ones need the saved second read.)
+__device__ __forceinline__ void softmax_bwd_long_row(int32_t b, int32_t e, const float *p, const float *dp, float *dv,
+                                                     float *s_red)
+{
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
+    if (e - b <= 8 * kThreads) {
+        float pv[8], gv[8];
+        float dot = 0.f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int32_t k = b + threadIdx.x + kThreads * i;
+            pv[i] = k < e ? p[k] : 0.f;
+            gv[i] = k < e ? dp[k] : 0.f;
+            dot = fmaf(pv[i], gv[i], dot);
+        }
+        dot = wave_sum(dot);
+        if (lane == 0) s_red[wave] = dot;
+        __syncthreads();
+        dot = 0.f;
+#pragma unroll
+        for (int i = 0; i < kThreads / kWave; ++i) dot += s_red[i];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int32_t k = b + threadIdx.x + kThreads * i;
+            if (k < e) dv[k] = pv[i] * (gv[i] - dot);
+        }
+        return;
+    }
+    float dot = 0.f;
+    for (int32_t k0 = b + threadIdx.x; k0 < e; k0 += 8 * kThreads) {
+        float a[8], c[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const bool ok = k0 + u * kThreads < e;
+            a[u] = ok ? p[k0 + u * kThreads] : 0.f;
+            c[u] = ok ? dp[k0 + u * kThreads] : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) dot = fmaf(a[u], c[u], dot);
+    }
+    dot = wave_sum(dot);
+    if (lane == 0) s_red[wave] = dot;
+    __syncthreads();
+    dot = 0.f;
+#pragma unroll
+    for (int i = 0; i < kThreads / kWave; ++i) dot += s_red[i];
+    for (int32_t k0 = b + threadIdx.x; k0 < e; k0 += 8 * kThreads) {
+        float a[8], c[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const bool ok = k0 + u * kThreads < e;
+            a[u] = ok ? p[k0 + u * kThreads] : 0.f;
+            c[u] = ok ? dp[k0 + u * kThreads] : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            if (k0 + u * kThreads < e) dv[k0 + u * kThreads] = a[u] * (c[u] - dot);
+    }
+}
+
+// One launch for all rows: workgroups 0 .. n_long - 1 take one split row each (dispatched first, so the long
+// rows start at once and the short ones fill in around them), the workgroups behind them 64 single-segment rows
+// each.
+__global__ __launch_bounds__(kThreads) void softmax_bwd_kernel(int32_t n_long, const int32_t *__restrict__ long_row,
+                                                               int32_t tail_start, int32_t tail_count,
                                                                const int32_t *__restrict__ seg_row,
                                                                const int32_t *__restrict__ seg_dst,
                                                                const int32_t *__restrict__ row_ptr, const float *p,
                                                                const float *dp, float *dv)
 {
     __shared__ int32_t s_b[kTailRows], s_e[kTailRows];
+    __shared__ float s_red[kThreads / kWave];
     __shared__ int s_max;
+    if ((int32_t)blockIdx.x < n_long) {
+        const int32_t row = long_row[blockIdx.x];
+        softmax_bwd_long_row(row_ptr[row], row_ptr[row + 1], p, dp, dv, s_red);
+        return;
+    }
     if (threadIdx.x == 0) s_max = 0;
     __syncthreads();
     if (threadIdx.x < kTailRows) {
-        const int64_t i = (int64_t)blockIdx.x * kTailRows + threadIdx.x;
+        const int64_t i = (int64_t)(blockIdx.x - n_long) * kTailRows + threadIdx.x;
         int32_t b = 0, e = 0;
         if (i < tail_count && seg_dst[tail_start + i] < 0) {          // a piece of a split row: not here
             const int32_t row = seg_row[tail_start + i];
@@ -170,152 +242,18 @@ __global__ __launch_bounds__(kThreads) void softmax_bwd_kernel(int32_t tail_star
     else softmax_bwd_rows<16, kSegLen / 16>(s_b, s_e, p, dp, dv);
 }
 
-// Long rows (the gather plan's list of split rows), in two kernels over that list.  Up to kMidRow entries:
-// one 256-thread workgroup per row, p and dp of the row in registers (eight values each per thread).
-// Beyond: 1024-thread workgroups share the list out; a row of up to 8,192 entries still sits in registers, a
-// longer one takes two passes, four values per
-// thread in flight.
-constexpr int kMidRow = 8 * kThreads;
-constexpr int kLongThreads = 1024;
-constexpr int kLongGridMax = 512;
-
-__global__ __launch_bounds__(kThreads) void softmax_bwd_mid_kernel(const int32_t *__restrict__ long_row,
-                                                                   const int32_t *__restrict__ row_ptr, const float *p,
-                                                                   const float *dp, float *dv)
-{
-    __shared__ float s_red[kThreads / kWave];
-    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
-    const int32_t row = long_row[blockIdx.x];
-    const int32_t b = row_ptr[row], e = row_ptr[row + 1];
-    if (e - b > kMidRow) return;
-    float pv[8], gv[8];
-    float dot = 0.f;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        const int32_t k = b + threadIdx.x + kThreads * i;
-        pv[i] = k < e ? p[k] : 0.f;
-        gv[i] = k < e ? dp[k] : 0.f;
-        dot = fmaf(pv[i], gv[i], dot);
-    }
-    dot = wave_sum(dot);
-    if (lane == 0) s_red[wave] = dot;
-    __syncthreads();
-    dot = 0.f;
-#pragma unroll
-    for (int i = 0; i < kThreads / kWave; ++i) dot += s_red[i];
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        const int32_t k = b + threadIdx.x + kThreads * i;
-        if (k < e) dv[k] = pv[i] * (gv[i] - dot);
-    }
-}
-
-__global__ __launch_bounds__(kLongThreads) void softmax_bwd_long_kernel(int32_t n_long,
-                                                                        const int32_t *__restrict__ long_row,
-                                                                        const int32_t *__restrict__ row_ptr,
-                                                                        const float *p, const float *dp, float *dv)
-{
-    __shared__ float s_red[kLongThreads / kWave];
-    __shared__ int32_t s_rows[kLongThreads];
-    __shared__ int s_n;
-    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
-    // The workgroup's share of the list is looked at by all threads at once and its rows beyond kMidRow entries
-    // are collected in LDS (in an order that may vary; the rows are independent, the results do not).
-    const int32_t chunk = (n_long + (int32_t)gridDim.x - 1) / (int32_t)gridDim.x;       // <= kLongThreads
-    if (threadIdx.x == 0) s_n = 0;
-    __syncthreads();
-    {
-        // strided, so that the long rows of a hub-heavy id range spread over the workgroups
-        const int64_t li = (int64_t)threadIdx.x * gridDim.x + blockIdx.x;
-        if ((int32_t)threadIdx.x < chunk && li < n_long) {
-            const int32_t row = long_row[li];
-            if (row_ptr[row + 1] - row_ptr[row] > kMidRow) s_rows[atomicAdd(&s_n, 1)] = row;
-        }
-    }
-    __syncthreads();
-    const int n_mine = s_n;
-    for (int i = 0; i < n_mine; ++i) {
-        const int32_t row = s_rows[i];
-        const int32_t b = row_ptr[row], e = row_ptr[row + 1];
-        if (e - b <= 8 * kLongThreads) {
-            // up to 8,192 entries: p and dp of the row fit in the workgroup's registers
-            float pv[8], gv[8];
-            float d = 0.f;
-#pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const int32_t k = b + threadIdx.x + u * kLongThreads;
-                pv[u] = k < e ? p[k] : 0.f;
-                gv[u] = k < e ? dp[k] : 0.f;
-                d = fmaf(pv[u], gv[u], d);
-            }
-            d = wave_sum(d);
-            if (lane == 0) s_red[wave] = d;
-            __syncthreads();
-            d = 0.f;
-#pragma unroll
-            for (int j = 0; j < kLongThreads / kWave; ++j) d += s_red[j];
-#pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const int32_t k = b + threadIdx.x + u * kLongThreads;
-                if (k < e) dv[k] = pv[u] * (gv[u] - d);
-            }
-            __syncthreads();                                          // s_red is reused by the next row
-            continue;
-        }
-        float dot = 0.f;
-        for (int32_t k0 = b + threadIdx.x; k0 < e; k0 += 4 * kLongThreads) {
-            float a[4], c[4];
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const bool ok = k0 + u * kLongThreads < e;
-                a[u] = ok ? p[k0 + u * kLongThreads] : 0.f;
-                c[u] = ok ? dp[k0 + u * kLongThreads] : 0.f;
-            }
-#pragma unroll
-            for (int u = 0; u < 4; ++u) dot = fmaf(a[u], c[u], dot);
-        }
-        dot = wave_sum(dot);
-        if (lane == 0) s_red[wave] = dot;
-        __syncthreads();
-        dot = 0.f;
-#pragma unroll
-        for (int i = 0; i < kLongThreads / kWave; ++i) dot += s_red[i];
-        for (int32_t k0 = b + threadIdx.x; k0 < e; k0 += 4 * kLongThreads) {
-            float a[4], c[4];
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const bool ok = k0 + u * kLongThreads < e;
-                a[u] = ok ? p[k0 + u * kLongThreads] : 0.f;
-                c[u] = ok ? dp[k0 + u * kLongThreads] : 0.f;
-            }
-#pragma unroll
-            for (int u = 0; u < 4; ++u)
-                if (k0 + u * kLongThreads < e) dv[k0 + u * kLongThreads] = a[u] * (c[u] - dot);
-        }
-        __syncthreads();                                              // s_red is reused by the next row
-    }
-}
-
 }  // namespace
 
 int row_softmax_backward_impl(const tcg_meta *m, const float *d_p, const float *d_dp, float *d_dv, hipStream_t s)
 {
     if (m->n_rows == 0 || m->nnz == 0) return TCG_OK;
     const int32_t tail_start = m->h_lane_tab[4], tail_count = m->h_lane_tab[5];
-    if (tail_count > 0) {
-        hipLaunchKernelGGL(softmax_bwd_kernel, dim3((unsigned)ceil_div(tail_count, kTailRows)), dim3(kThreads), 0, s,
-                           tail_start, tail_count, m->d_seg_row, m->d_seg_dst, m->d_row_ptr, d_p, d_dp, d_dv);
+    const int64_t grid = m->n_long + ceil_div(tail_count, kTailRows);
+    if (grid > 0) {
+        hipLaunchKernelGGL(softmax_bwd_kernel, dim3((unsigned)grid), dim3(kThreads), 0, s, (int32_t)m->n_long,
+                           m->d_long_row, tail_start, tail_count, m->d_seg_row, m->d_seg_dst, m->d_row_ptr, d_p, d_dp,
+                           d_dv);
         TCG_TRY(launch_status("softmax_bwd_kernel"));
-    }
-    if (m->n_long > 0) {
-        hipLaunchKernelGGL(softmax_bwd_mid_kernel, dim3((unsigned)m->n_long), dim3(kThreads), 0, s, m->d_long_row,
-                           m->d_row_ptr, d_p, d_dp, d_dv);
-        TCG_TRY(launch_status("softmax_bwd_mid_kernel"));
-        const int64_t long_grid = std::max<int64_t>(std::min<int64_t>(m->n_long, kLongGridMax),
-                                                    ceil_div(m->n_long, kLongThreads));
-        hipLaunchKernelGGL(softmax_bwd_long_kernel, dim3((unsigned)long_grid), dim3(kLongThreads), 0, s,
-                           (int32_t)m->n_long, m->d_long_row, m->d_row_ptr, d_p, d_dp, d_dv);
-        TCG_TRY(launch_status("softmax_bwd_long_kernel"));
     }
     return TCG_OK;
 }

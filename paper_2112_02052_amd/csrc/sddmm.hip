@@ -220,18 +220,115 @@ __device__ __forceinline__ void softmax_rows(const int32_t *s_b, const int32_t *
     }
 }
 
-__global__ __launch_bounds__(kBlock) void row_softmax_kernel(int32_t tail_start, int32_t tail_count,
+// A row of the gather plan's list of split rows (more than kSegLen entries), by one 256-thread workgroup:
+// up to R * 256 entries the row sits in registers (R values per thread; one read, one write).
+template <int R>
+__device__ __forceinline__ void softmax_row_in_registers(int32_t b, int32_t e, const float *in, float *out, float *s_m,
+                                                         float *s_s)
+{
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
+    float v[R];
+    float m = -INFINITY;
+#pragma unroll
+    for (int i = 0; i < R; ++i) {
+        const int32_t k = b + threadIdx.x + kBlock * i;
+        v[i] = k < e ? in[k] : -INFINITY;
+        m = fmaxf(m, v[i]);
+    }
+    m = wave_max(m);
+    if (lane == 0) s_m[wave] = m;
+    __syncthreads();
+    m = fmaxf(fmaxf(s_m[0], s_m[1]), fmaxf(s_m[2], s_m[3]));
+    float sum = 0.f;
+#pragma unroll
+    for (int i = 0; i < R; ++i) {
+        v[i] = b + threadIdx.x + kBlock * i < e ? expf(v[i] - m) : 0.f;
+        sum += v[i];
+    }
+    sum = wave_sum(sum);
+    if (lane == 0) s_s[wave] = sum;
+    __syncthreads();
+    const float inv = 1.f / ((s_s[0] + s_s[1]) + (s_s[2] + s_s[3]));
+#pragma unroll
+    for (int i = 0; i < R; ++i) {
+        const int32_t k = b + threadIdx.x + kBlock * i;
+        if (k < e) out[k] = v[i] * inv;
+    }
+}
+static_assert(kBlock / kWave == 4, "the row kernels combine four wavefront partials");
+
+// Longer rows: two passes (running maximum and rescaled sum of exponentials, eight values per thread in
+// flight, then the normalised values).
+constexpr int kTwoPassUnroll = 8;
+__device__ __forceinline__ void softmax_row_two_pass(int32_t b, int32_t e, const float *in, float *out, float *s_m,
+                                                     float *s_s)
+{
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
+    float m = -INFINITY, s = 0.f;
+    for (int32_t k0 = b + threadIdx.x; k0 < e; k0 += kTwoPassUnroll * kBlock) {
+        float v[kTwoPassUnroll];
+#pragma unroll
+        for (int u = 0; u < kTwoPassUnroll; ++u) v[u] = k0 + u * kBlock < e ? in[k0 + u * kBlock] : -INFINITY;
+        float mb = v[0];
+#pragma unroll
+        for (int u = 1; u < kTwoPassUnroll; ++u) mb = fmaxf(mb, v[u]);
+        if (mb > m) {
+            s *= expf(m - mb);          // exp(-inf) = 0 on the first batch
+            m = mb;
+        }
+#pragma unroll
+        for (int u = 0; u < kTwoPassUnroll; ++u) s += expf(v[u] - m);
+    }
+    const float wm = wave_max(m);
+    const float ws = wave_sum(m > -INFINITY ? s * expf(m - wm) : 0.f);
+    if (lane == 0) {
+        s_m[wave] = wm;
+        s_s[wave] = ws;
+    }
+    __syncthreads();
+    float M = -INFINITY;
+#pragma unroll
+    for (int i = 0; i < kBlock / kWave; ++i) M = fmaxf(M, s_m[i]);
+    float S = 0.f;
+#pragma unroll
+    for (int i = 0; i < kBlock / kWave; ++i) S += s_m[i] > -INFINITY ? s_s[i] * expf(s_m[i] - M) : 0.f;
+    const float inv = 1.f / S;
+    for (int32_t k0 = b + threadIdx.x; k0 < e; k0 += kTwoPassUnroll * kBlock) {
+        float v[kTwoPassUnroll];
+#pragma unroll
+        for (int u = 0; u < kTwoPassUnroll; ++u) v[u] = k0 + u * kBlock < e ? in[k0 + u * kBlock] : 0.f;
+#pragma unroll
+        for (int u = 0; u < kTwoPassUnroll; ++u)
+            if (k0 + u * kBlock < e) out[k0 + u * kBlock] = expf(v[u] - M) * inv;
+    }
+}
+
+// One launch for all rows.  Workgroups 0 .. n_long - 1 take one split row each (they are dispatched first, so the
+// long rows start at once and the many short ones fill in around them; three launches one after the other left
+// most of the chip idle in each); the workgroups behind them take 64 single-segment rows each.
+__global__ __launch_bounds__(kBlock) void row_softmax_kernel(int32_t n_long, const int32_t *__restrict__ long_row,
+                                                             int32_t tail_start, int32_t tail_count,
                                                              const int32_t *__restrict__ seg_row,
                                                              const int32_t *__restrict__ seg_dst,
                                                              const int32_t *__restrict__ row_ptr, const float *in,
                                                              float *out)
 {
     __shared__ int32_t s_b[kTailRows], s_e[kTailRows];
+    __shared__ float s_m[kBlock / kWave], s_s[kBlock / kWave];
     __shared__ int s_max;
+    if ((int32_t)blockIdx.x < n_long) {
+        const int32_t row = long_row[blockIdx.x];
+        const int32_t b = row_ptr[row], e = row_ptr[row + 1];
+        // (a register variant for rows of up to 8,192 entries would halve the resident wavefronts of the whole
+        // kernel, which the short rows need more than the long ones need the saved second read)
+        if (e - b <= 8 * kBlock) softmax_row_in_registers<8>(b, e, in, out, s_m, s_s);
+        else softmax_row_two_pass(b, e, in, out, s_m, s_s);
+        return;
+    }
     if (threadIdx.x == 0) s_max = 0;
     __syncthreads();
     if (threadIdx.x < kTailRows) {
-        const int64_t i = (int64_t)blockIdx.x * kTailRows + threadIdx.x;
+        const int64_t i = (int64_t)(blockIdx.x - n_long) * kTailRows + threadIdx.x;
         int32_t b = 0, e = 0;
         if (i < tail_count && seg_dst[tail_start + i] < 0) {          // a piece of a split row: not here
             const int32_t row = seg_row[tail_start + i];
@@ -249,159 +346,6 @@ __global__ __launch_bounds__(kBlock) void row_softmax_kernel(int32_t tail_start,
     else if (longest <= 16) softmax_rows<8, 2>(s_b, s_e, in, out);
     else if (longest <= 32) softmax_rows<16, 2>(s_b, s_e, in, out);
     else softmax_rows<16, kSegLen / 16>(s_b, s_e, in, out);
-}
-
-// Rows longer than kSegLen (the gather plan's list of split rows), in two kernels over that list.
-// Up to kMidRow entries: one 256-thread workgroup per row with the row in registers (eight values per
-// thread; one read, one write).  Beyond: 1024-thread workgroups share the list out; a row of up to 8,192 entries
-// still sits in registers, a longer one takes two passes (running maximum and rescaled sum of exponentials, four values per thread in flight, then the normalised
-// values); hub rows of power-law graphs would otherwise set the duration.
-constexpr int kMidRow = 8 * kBlock;
-constexpr int kLongThreads = 1024;
-constexpr int kLongGridMax = 512;
-
-__global__ __launch_bounds__(kBlock) void row_softmax_mid_kernel(const int32_t *__restrict__ long_row,
-                                                                 const int32_t *__restrict__ row_ptr, const float *in,
-                                                                 float *out)
-{
-    __shared__ float s_m[kBlock / kWave], s_s[kBlock / kWave];
-    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
-    const int32_t row = long_row[blockIdx.x];
-    const int32_t b = row_ptr[row], e = row_ptr[row + 1];
-    if (e - b > kMidRow) return;
-    float v[8];
-    float m = -INFINITY;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        const int32_t k = b + threadIdx.x + kBlock * i;
-        v[i] = k < e ? in[k] : -INFINITY;
-        m = fmaxf(m, v[i]);
-    }
-    m = wave_max(m);
-    if (lane == 0) s_m[wave] = m;
-    __syncthreads();
-    m = fmaxf(fmaxf(s_m[0], s_m[1]), fmaxf(s_m[2], s_m[3]));
-    float sum = 0.f;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        v[i] = b + threadIdx.x + kBlock * i < e ? expf(v[i] - m) : 0.f;
-        sum += v[i];
-    }
-    sum = wave_sum(sum);
-    if (lane == 0) s_s[wave] = sum;
-    __syncthreads();
-    const float inv = 1.f / ((s_s[0] + s_s[1]) + (s_s[2] + s_s[3]));
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        const int32_t k = b + threadIdx.x + kBlock * i;
-        if (k < e) out[k] = v[i] * inv;
-    }
-}
-static_assert(kBlock / kWave == 4, "row_softmax_mid_kernel combines four wavefront partials");
-
-__global__ __launch_bounds__(kLongThreads) void row_softmax_long_kernel(int32_t n_long,
-                                                                        const int32_t *__restrict__ long_row,
-                                                                        const int32_t *__restrict__ row_ptr,
-                                                                        const float *in, float *out)
-{
-    __shared__ float s_m[kLongThreads / kWave], s_s[kLongThreads / kWave];
-    __shared__ int32_t s_rows[kLongThreads];
-    __shared__ int s_n;
-    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
-    // The workgroup's share of the list is looked at by all threads at once (one entry each) and its rows
-    // beyond kMidRow entries are collected in LDS: walking the list entry by entry would pay two dependent
-    // loads for every row that only has to be skipped.  The order of the collected rows varies from run to
-    // run; the rows are independent, so the results do not.
-    const int32_t chunk = (n_long + (int32_t)gridDim.x - 1) / (int32_t)gridDim.x;       // <= kLongThreads
-    if (threadIdx.x == 0) s_n = 0;
-    __syncthreads();
-    {
-        // strided, so that the long rows of a hub-heavy id range spread over the workgroups
-        const int64_t li = (int64_t)threadIdx.x * gridDim.x + blockIdx.x;
-        if ((int32_t)threadIdx.x < chunk && li < n_long) {
-            const int32_t row = long_row[li];
-            if (row_ptr[row + 1] - row_ptr[row] > kMidRow) s_rows[atomicAdd(&s_n, 1)] = row;
-        }
-    }
-    __syncthreads();
-    const int n_mine = s_n;
-    for (int i = 0; i < n_mine; ++i) {
-        const int32_t row = s_rows[i];
-        const int32_t b = row_ptr[row], e = row_ptr[row + 1];
-        if (e - b <= 8 * kLongThreads) {
-            // up to 8,192 entries: the row fits in the workgroup's registers (one read, one write)
-            float v[8];
-            float mx = -INFINITY;
-#pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const int32_t k = b + threadIdx.x + u * kLongThreads;
-                v[u] = k < e ? in[k] : -INFINITY;
-                mx = fmaxf(mx, v[u]);
-            }
-            mx = wave_max(mx);
-            if (lane == 0) s_m[wave] = mx;
-            __syncthreads();
-            float M = -INFINITY;
-#pragma unroll
-            for (int j = 0; j < kLongThreads / kWave; ++j) M = fmaxf(M, s_m[j]);
-            float sum = 0.f;
-#pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                v[u] = b + threadIdx.x + u * kLongThreads < e ? expf(v[u] - M) : 0.f;
-                sum += v[u];
-            }
-            sum = wave_sum(sum);
-            if (lane == 0) s_s[wave] = sum;
-            __syncthreads();
-            float S = 0.f;
-#pragma unroll
-            for (int j = 0; j < kLongThreads / kWave; ++j) S += s_s[j];
-            const float inv = 1.f / S;
-#pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const int32_t k = b + threadIdx.x + u * kLongThreads;
-                if (k < e) out[k] = v[u] * inv;
-            }
-            __syncthreads();                                          // s_m / s_s are reused by the next row
-            continue;
-        }
-        float m = -INFINITY, s = 0.f;
-        for (int32_t k0 = b + threadIdx.x; k0 < e; k0 += 4 * kLongThreads) {
-            float v[4];
-#pragma unroll
-            for (int u = 0; u < 4; ++u) v[u] = k0 + u * kLongThreads < e ? in[k0 + u * kLongThreads] : -INFINITY;
-            const float mb = fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3]));
-            if (mb > m) {
-                s *= expf(m - mb);          // exp(-inf) = 0 on the first batch
-                m = mb;
-            }
-#pragma unroll
-            for (int u = 0; u < 4; ++u) s += expf(v[u] - m);
-        }
-        const float wm = wave_max(m);
-        const float ws = wave_sum(m > -INFINITY ? s * expf(m - wm) : 0.f);
-        if (lane == 0) {
-            s_m[wave] = wm;
-            s_s[wave] = ws;
-        }
-        __syncthreads();
-        float M = -INFINITY;
-#pragma unroll
-        for (int i = 0; i < kLongThreads / kWave; ++i) M = fmaxf(M, s_m[i]);
-        float S = 0.f;
-#pragma unroll
-        for (int i = 0; i < kLongThreads / kWave; ++i) S += s_m[i] > -INFINITY ? s_s[i] * expf(s_m[i] - M) : 0.f;
-        const float inv = 1.f / S;
-        for (int32_t k0 = b + threadIdx.x; k0 < e; k0 += 4 * kLongThreads) {
-            float v[4];
-#pragma unroll
-            for (int u = 0; u < 4; ++u) v[u] = k0 + u * kLongThreads < e ? in[k0 + u * kLongThreads] : 0.f;
-#pragma unroll
-            for (int u = 0; u < 4; ++u)
-                if (k0 + u * kLongThreads < e) out[k0 + u * kLongThreads] = expf(v[u] - M) * inv;
-        }
-        __syncthreads();                                              // s_m / s_s are reused by the next row
-    }
 }
 
 template <int DT, int G, int NCH, int PB = 16>
@@ -505,20 +449,12 @@ int row_softmax_impl(const tcg_meta *m, const float *d_in, float *d_out, hipStre
 {
     if (m->n_rows == 0 || m->nnz == 0) return TCG_OK;
     const int32_t tail_start = m->h_lane_tab[4], tail_count = m->h_lane_tab[5];
-    if (tail_count > 0) {
-        hipLaunchKernelGGL(row_softmax_kernel, dim3((unsigned)ceil_div(tail_count, kTailRows)), dim3(kBlock), 0, s,
-                           tail_start, tail_count, m->d_seg_row, m->d_seg_dst, m->d_row_ptr, d_in, d_out);
+    const int64_t grid = m->n_long + ceil_div(tail_count, kTailRows);
+    if (grid > 0) {
+        hipLaunchKernelGGL(row_softmax_kernel, dim3((unsigned)grid), dim3(kBlock), 0, s, (int32_t)m->n_long,
+                           m->d_long_row, tail_start, tail_count, m->d_seg_row, m->d_seg_dst, m->d_row_ptr, d_in,
+                           d_out);
         TCG_TRY(launch_status("row_softmax_kernel"));
-    }
-    if (m->n_long > 0) {
-        hipLaunchKernelGGL(row_softmax_mid_kernel, dim3((unsigned)m->n_long), dim3(kBlock), 0, s, m->d_long_row,
-                           m->d_row_ptr, d_in, d_out);
-        TCG_TRY(launch_status("row_softmax_mid_kernel"));
-        const int64_t long_grid = std::max<int64_t>(std::min<int64_t>(m->n_long, kLongGridMax),
-                                                    ceil_div(m->n_long, kLongThreads));
-        hipLaunchKernelGGL(row_softmax_long_kernel, dim3((unsigned)long_grid), dim3(kLongThreads), 0, s,
-                           (int32_t)m->n_long, m->d_long_row, m->d_row_ptr, d_in, d_out);
-        TCG_TRY(launch_status("row_softmax_long_kernel"));
     }
     return TCG_OK;
 }
