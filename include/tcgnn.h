@@ -48,7 +48,9 @@ typedef enum {
                         or a column index outside [0, n_cols)                                  */
     TCG_ERANGE = -3, /* a size does not fit the int32 index space                               */
     TCG_ENOMEM = -4, /* host or device allocation failed                                        */
-    TCG_EHIP = -5    /* a HIP runtime call or kernel launch failed                              */
+    TCG_EHIP = -5,   /* a HIP runtime call or kernel launch failed                              */
+    TCG_ESCRATCH = -6 /* a scratch buffer is too small and may not be (re)allocated in this call: a
+                        plan's buffer while the stream is being captured (tcg_strerror says more) */
 } tcg_status;
 
 /* Which kernel family a row window is executed by (see tcg_sgt_set_policy). */
@@ -147,10 +149,24 @@ TCG_API int tcg_sgt_plan_stats(const tcg_meta *meta, int64_t *n_tile_windows, in
  * D >= 1; ldx, ldy >= D.  Any D works; rows whose byte length and stride are multiples of 16
  * (and a 16-byte aligned base) take the vectorised kernels.  X and Y must not overlap.
  * The partial sums of rows split over several segments go to a scratch buffer reserved by
- * tcg_sgt_build for D <= 128; the first call with a wider D reallocates (and keeps) it.
+ * tcg_sgt_build for D <= 128; the first call with a wider D waits for the stream and reallocates (and
+ * keeps) it -- while the stream is being captured into a HIP graph that is refused with TCG_ESCRATCH:
+ * call tcg_sgt_reserve beforehand.  Apart from that the call neither allocates nor synchronises.
+ * Non-finite features: on the row-gather path a NaN or infinity in X[j] reaches exactly the rows with
+ * an entry in column j.  On the condensed-tile path it reaches every row of every window whose column
+ * list contains j (0 x inf inside the matrix unit; inf - inf in the exact split of fp32 features), and
+ * an entry (i, j) stored more than 256 times with unit values is rounded to bf16 there.
+ * TCG_POLICY_GATHER gives the strict behaviour for all windows.
  */
 TCG_API int tcg_spmm(tcg_meta *meta, const void *d_X, tcg_dtype x_dt, int32_t D, int64_t ldx,
              const float *d_w, void *d_Y, tcg_dtype y_dt, int64_t ldy, void *stream);
+
+/*
+ * Grows the plan's partial-sum scratch for feature widths up to max_D now, so that later tcg_spmm /
+ * tcg_attention calls with D <= max_D never allocate (needed before capturing them with D > 128).
+ * May wait for the stream.
+ */
+TCG_API int tcg_sgt_reserve(tcg_meta *meta, int32_t max_D, void *stream);
 
 /*
  * Edge feature computation -- Equation 2 and Algorithm 3 of the paper:

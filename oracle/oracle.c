@@ -55,8 +55,8 @@ static int cmp_i32(const void *a, const void *b)
  *     number of rows (the last window may hold fewer than win_h rows);
  *   - Sort is ascending by column id; Deduplication keeps one copy of each id;
  *   - edgeToCol[e] is the 0-based position of edgeList[e] in the window's sorted, deduplicated
- *     list (the listing's "eArrClean[eid]" read as a lookup id -> position), as section 4.1
- *     describes ("column-id from eArrClean");
+ *     list: the listing's last assignment indexes the cleaned array by a node id, which is read
+ *     as a lookup id -> position, the condensed column id that section 4.1 describes;
  *   - winPartition[w] = ceil(|eArrClean| / tile_w), zero for a window without edges.
  * Besides the listing's two outputs, the sorted unique lists themselves are returned
  * back to back (col_to_row, the text's colToRow) with their offsets (win_unique_ptr).

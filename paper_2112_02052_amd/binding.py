@@ -15,7 +15,8 @@ POLICY_AUTO, POLICY_GATHER, POLICY_TILE = 0, 1, 2
 EXPORTED = ["tcg_sgt_build", "tcg_sgt_sizes", "tcg_sgt_export", "tcg_sgt_set_policy",
             "tcg_sgt_plan_stats", "tcg_spmm", "tcg_sddmm", "tcg_row_softmax", "tcg_sgt_free",
             "tcg_strerror", "tcg_release_cached_memory", "tcg_sddmm_pq", "tcg_row_softmax_backward",
-            "tcg_csr_transpose", "tcg_edge_gather", "tcg_attention", "tcg_reorder_rows", "tcg_csr_permute"]
+            "tcg_csr_transpose", "tcg_edge_gather", "tcg_attention", "tcg_reorder_rows", "tcg_csr_permute",
+            "tcg_sgt_reserve"]
 
 _DTYPES = {torch.float32: TCG_F32, torch.bfloat16: TCG_BF16, torch.float16: TCG_F16}
 
@@ -53,6 +54,8 @@ def load_library():
     lib.tcg_spmm.restype = ctypes.c_int
     lib.tcg_spmm.argtypes = [_vp, _vp, ctypes.c_int, ctypes.c_int32, ctypes.c_int64, _vp, _vp, ctypes.c_int,
                              ctypes.c_int64, _vp]
+    lib.tcg_sgt_reserve.restype = ctypes.c_int
+    lib.tcg_sgt_reserve.argtypes = [_vp, ctypes.c_int32, _vp]
     lib.tcg_sddmm.restype = ctypes.c_int
     lib.tcg_sddmm.argtypes = [_vp, _vp, ctypes.c_int, ctypes.c_int32, ctypes.c_int64, _vp, _vp]
     lib.tcg_row_softmax.restype = ctypes.c_int
@@ -154,6 +157,12 @@ def sgt_export(meta):
 
 def sgt_set_policy(meta, policy, min_reuse=0.0):
     _check(load_library().tcg_sgt_set_policy(meta._h, int(policy), float(min_reuse), _stream()))
+
+
+def sgt_reserve(meta, max_D):
+    """tcg_sgt_reserve: size the plan's scratch for feature widths up to max_D now (needed before capturing
+    calls with D > 128 into a HIP graph)."""
+    _check(load_library().tcg_sgt_reserve(meta._h, int(max_D), _stream()))
 
 
 def sgt_plan_stats(meta):

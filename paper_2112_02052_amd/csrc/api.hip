@@ -11,6 +11,10 @@ namespace tcg {
 static thread_local char g_hip_msg[256] = "";
 static thread_local char g_msg[320] = "";
 
+static thread_local char g_detail[320] = "";
+
+void set_message(const char *text) { snprintf(g_detail, sizeof(g_detail), "%s", text); }
+
 void set_hip_error(hipError_t e, const char *what)
 {
     snprintf(g_hip_msg, sizeof(g_hip_msg), "%s: %s", what, hipGetErrorString(e));
@@ -123,6 +127,12 @@ int tcg_spmm(tcg_meta *meta, const void *d_X, tcg_dtype x_dt, int32_t D, int64_t
     return spmm_impl(meta, d_X, x_dt, D, ldx, d_w, d_Y, y_dt, ldy, static_cast<hipStream_t>(stream));
 }
 
+int tcg_sgt_reserve(tcg_meta *meta, int32_t max_D, void *stream)
+{
+    if (!meta || max_D < 1) return TCG_EINVAL;
+    return reserve_partial(meta, max_D, static_cast<hipStream_t>(stream));
+}
+
 int tcg_sddmm(tcg_meta *meta, const void *d_X, tcg_dtype x_dt, int32_t D, int64_t ldx, float *d_out,
               void *stream)
 {
@@ -217,6 +227,9 @@ const char *tcg_strerror(int status)
     case TCG_ECSR: return "malformed CSR (row_ptr not monotone from 0 to nnz, or a column index out of range)";
     case TCG_ERANGE: return "size exceeds the int32 index space";
     case TCG_ENOMEM: return "out of memory";
+    case TCG_ESCRATCH:
+        snprintf(g_msg, sizeof(g_msg), "scratch buffer too small: %s", g_detail[0] ? g_detail : "(no detail recorded)");
+        return g_msg;
     case TCG_EHIP:
         snprintf(g_msg, sizeof(g_msg), "HIP error: %s", g_hip_msg[0] ? g_hip_msg : "(no detail recorded)");
         return g_msg;

@@ -209,23 +209,7 @@ int attention_impl(tcg_meta *m, const void *d_X, tcg_dtype x_dt, int32_t D, int6
     if (!vec_ok) return TCG_EINVAL;
 
     // Scratch: fp32 accumulators of split rows (shared with tcg_spmm) and their (max, denominator).
-    const int64_t need = m->n_slots * (int64_t)D;
-    if (need > m->partial_elems) {
-        if (m->partial_owned) {
-            TCG_HIP(hipStreamSynchronize(s));
-            pool_free(m->d_partial);
-        }
-        m->d_partial = nullptr;
-        m->partial_elems = 0;
-        m->partial_owned = false;
-        TCG_TRY(dev_alloc(&m->d_partial, need));
-        m->partial_elems = need;
-        m->partial_owned = true;
-    }
-    if (m->n_slots > 0 && m->d_partial_ml == nullptr) {
-        TCG_TRY(dev_alloc(&m->d_partial_ml, 2 * m->n_slots));
-        m->owned[m->n_owned++] = m->d_partial_ml;
-    }
+    TCG_TRY(reserve_partial(m, D, s));
 
     Args a{m, d_X, ldx, D, d_scores, d_Y, (int)y_dt, ldy, m->d_partial_ml, s};
     const int32_t n_chunks = (int32_t)((int64_t)D * es / 16);

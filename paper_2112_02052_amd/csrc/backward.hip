@@ -103,8 +103,8 @@ __device__ __forceinline__ float wave_sum(float v)
 }
 
 // dv[e] = p[e] * (dp[e] - sum over the row of p * dp).  Rows of at most kSegLen entries are taken from the
-// tail of the gather plan's segment list (single-segment rows; rows without entries are not in it, and on
-// graphs without neighbour sharing it is ordered by row length): a workgroup looks at the lengths of its 64
+// tail of the gather plan's segment list (single-segment rows; rows without entries have an empty segment
+// there and are skipped; on graphs without neighbour sharing the list is ordered by row length): a workgroup looks at the lengths of its 64
 // rows and runs the variant that fits the longest -- G lanes per row, S entries of p and of dp per lane in
 // registers, (G, S) = (4, 2) up to 8 entries, (8, 2) up to 16, (16, 2) up to 32, (16, 8) up to 128.
 constexpr int kTailRows = 64;          // rows per workgroup

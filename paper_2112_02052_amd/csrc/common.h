@@ -29,6 +29,8 @@ constexpr float kTileMinReuseF32Sddmm = 3.0f;
 
 // Records the text of a failing HIP call for tcg_strerror (thread local).
 void set_hip_error(hipError_t e, const char *what);
+// Records the detail text that tcg_strerror appends to TCG_ESCRATCH (thread local).
+void set_message(const char *text);
 
 #define TCG_HIP(call)                                   \
     do {                                                \
@@ -153,6 +155,9 @@ int choose_paths(tcg_meta *m, tcg_policy policy, float min_reuse, hipStream_t s)
 // spmm.hip / sddmm.hip / softmax.hip
 int spmm_impl(tcg_meta *m, const void *d_X, tcg_dtype x_dt, int32_t D, int64_t ldx, const float *d_w,
               void *d_Y, tcg_dtype y_dt, int64_t ldy, hipStream_t s);
+// Makes the plan's partial-sum scratch large enough for feature width D (allocates; an error while the
+// stream is being captured).
+int reserve_partial(tcg_meta *m, int32_t D, hipStream_t s);
 int sddmm_impl(tcg_meta *m, const void *d_P, int64_t ldp, const void *d_X, int64_t ldx, tcg_dtype x_dt, int32_t D,
                float *d_out, hipStream_t s);
 

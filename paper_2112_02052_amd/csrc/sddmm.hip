@@ -176,9 +176,9 @@ __device__ __forceinline__ float wave_sum(float v)
 }
 
 // Rows of at most kSegLen entries.  They are taken from the tail of the gather plan's segment list (the
-// single-segment rows), not from the row index: rows without entries are not in that list at all -- on a
-// power-law graph that is close to half of the rows -- and on graphs whose windows share few neighbours the
-// list is ordered by row length, so a workgroup's 64 rows are alike.  The workgroup looks at its rows' lengths
+// single-segment rows), not from the row index: on graphs whose windows share few neighbours that list is
+// ordered by row length, so a workgroup's 64 rows are alike.  Rows without entries are in the list too (one
+// empty segment each, which the aggregation uses to write their zeros); they are skipped here.  The workgroup looks at its rows' lengths
 // first and then runs the variant that fits the longest of them: G lanes per row with S entries per lane
 // in registers, (G, S) = (4, 2) up to 8 entries, (8, 2) up to 16, (16, 2) up to 32, (16, 8) up to 128; maximum
 // and sum of exponentials by butterflies inside the lane group; one read, one write.

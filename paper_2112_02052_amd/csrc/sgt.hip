@@ -954,6 +954,7 @@ int sgt_build_impl(tcg_meta *m, int validate, hipStream_t s)
     plan.want((m->n_long + 1) * 4);
     plan.want(kLaneTabStride * kXcds * 4);
     plan.want(m->n_slots * kPartialInitD * 4);   // partial sums of split rows for D <= kPartialInitD
+    plan.want(m->n_slots * 2 * 4);               // (maximum, denominator) per split-row segment
     TCG_TRY(plan.commit());
     m->owned[m->n_owned++] = plan.base;
     m->d_seg_row = plan.take<int32_t>(m->n_seg);
@@ -965,6 +966,7 @@ int sgt_build_impl(tcg_meta *m, int validate, hipStream_t s)
     m->d_partial = plan.take<float>(m->n_slots * kPartialInitD);
     m->partial_elems = m->n_slots * kPartialInitD;
     m->partial_owned = false;
+    m->d_partial_ml = plan.take<float>(m->n_slots * 2);
 
     // Per-window translation, one launch per size class.
     if (h_cls[0] > 0)

@@ -18,6 +18,7 @@
 #include "common.h"
 #include "devutil.h"
 
+
 namespace tcg {
 
 // spmm_tile.hip
@@ -333,6 +334,7 @@ __global__ __launch_bounds__(kBlock) void spmm_reduce_long_kernel(
 
 struct GatherArgs {
     const tcg_meta *m;
+    float *partial;     // partial sums of split rows
     const void *X;
     int64_t ldx;
     int32_t D;
@@ -356,7 +358,7 @@ void launch_gather(const GatherArgs &a, int32_t n_chunks)
     hipLaunchKernelGGL((spmm_gather_kernel<DT, G, NCH, HAS_W, UNROLL>), dim3(grid), dim3(kBlock), 0, a.s,
                        m->d_lane_tab, m->d_seg_row, m->d_seg_ebeg, m->d_seg_dst, m->d_row_ptr, m->d_col_idx, a.w,
                        static_cast<const char *>(a.X), a.ldx * Elem<DT>::BYTES, n_chunks, a.D, a.Y, a.y_dt,
-                       a.ldy, m->d_partial, (int64_t)a.D, a.win_path, m->win_h, a.tile_mask, y_vec);
+                       a.ldy, a.partial, (int64_t)a.D, a.win_path, m->win_h, a.tile_mask, y_vec);
 }
 
 template <int DT, bool HAS_W>
@@ -388,7 +390,7 @@ void launch_small(const GatherArgs &a, int32_t n_pieces)
     hipLaunchKernelGGL((spmm_gather_small_kernel<DT, PB, G, NCH, HAS_W, UNROLL>), dim3(grid), dim3(kBlock), 0, a.s,
                        m->d_lane_tab, m->d_seg_row, m->d_seg_ebeg, m->d_seg_dst, m->d_row_ptr, m->d_col_idx, a.w,
                        static_cast<const char *>(a.X), a.ldx * Elem<DT>::BYTES, n_pieces, a.Y, a.y_dt, a.ldy,
-                       m->d_partial, (int64_t)a.D, a.win_path, m->win_h, a.tile_mask);
+                       a.partial, (int64_t)a.D, a.win_path, m->win_h, a.tile_mask);
 }
 
 template <int DT, int PB, bool HAS_W>
@@ -417,25 +419,38 @@ bool dispatch_elem_w(const GatherArgs &a)
 
 }  // namespace
 
+int reserve_partial(tcg_meta *m, int32_t D, hipStream_t s)
+{
+    const int64_t need = m->n_slots * (int64_t)D;
+    if (need <= m->partial_elems) return TCG_OK;
+    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(s, &cap) == hipSuccess && cap != hipStreamCaptureStatusNone) {
+        set_message("the partial-sum scratch of this plan is too small for this feature width and cannot be "
+                    "regrown while the stream is being captured: call tcg_sgt_reserve first");
+        return TCG_ESCRATCH;
+    }
+    if (m->partial_owned) {
+        TCG_HIP(hipStreamSynchronize(s));
+        pool_free(m->d_partial);
+    }
+    m->d_partial = nullptr;
+    m->partial_elems = 0;
+    m->partial_owned = false;
+    TCG_TRY(dev_alloc(&m->d_partial, need));
+    m->partial_elems = need;
+    m->partial_owned = true;
+    return TCG_OK;
+}
+
 int spmm_impl(tcg_meta *m, const void *d_X, tcg_dtype x_dt, int32_t D, int64_t ldx, const float *d_w,
               void *d_Y, tcg_dtype y_dt, int64_t ldy, hipStream_t s)
 {
     if (m->n_rows == 0) return TCG_OK;
 
-    // Scratch for the partial sums of rows that span several segments.
-    const int64_t need = m->n_slots * (int64_t)D;
-    if (need > m->partial_elems) {
-        if (m->partial_owned) {
-            TCG_HIP(hipStreamSynchronize(s));
-            pool_free(m->d_partial);
-        }
-        m->d_partial = nullptr;
-        m->partial_elems = 0;
-        m->partial_owned = false;
-        TCG_TRY(dev_alloc(&m->d_partial, need));
-        m->partial_elems = need;
-        m->partial_owned = true;
-    }
+    // Scratch for the partial sums of rows that span several segments: the plan's buffer (regrown for a
+    // wider D than it was reserved for).
+    TCG_TRY(reserve_partial(m, D, s));
+    float *partial = m->d_partial;
 
     // Which classes of tile-path windows really go to the MFMA kernels depends on the feature width, which
     // the plan does not know: measured on MI355X (the calibration tool's sweeps), narrow rows are gathered
@@ -457,7 +472,7 @@ int spmm_impl(tcg_meta *m, const void *d_X, tcg_dtype x_dt, int32_t D, int64_t l
     if (use_tiles) TCG_TRY(spmm_tile_launch(m, d_X, x_dt, D, ldx, d_w, d_Y, y_dt, ldy, tile_mask, s));
     if (few && many && m->nnz_tile == m->nnz && m->n_tile_win == m->n_win) return TCG_OK;  // nothing left
 
-    GatherArgs a{m, d_X, ldx, D, d_w, d_Y, (int)y_dt, ldy, win_path, tile_mask, s};
+    GatherArgs a{m, partial, d_X, ldx, D, d_w, d_Y, (int)y_dt, ldy, win_path, tile_mask, s};
     const int es = dtype_size(x_dt);
     const bool vec_ok = ((int64_t)D * es) % 16 == 0 && (ldx * es) % 16 == 0 && ldx * es < (1ll << 32) &&
                         (reinterpret_cast<uintptr_t>(d_X) & 15) == 0;
@@ -478,18 +493,18 @@ int spmm_impl(tcg_meta *m, const void *d_X, tcg_dtype x_dt, int32_t D, int64_t l
         if (d_w)
             hipLaunchKernelGGL(spmm_gather_generic_kernel<true>, dim3(grid), dim3(kBlock), 0, s, m->d_lane_tab,
                                m->d_seg_row, m->d_seg_ebeg, m->d_seg_dst, m->d_row_ptr, m->d_col_idx, d_w, d_X,
-                               (int)x_dt, ldx, D, d_Y, (int)y_dt, ldy, m->d_partial, (int64_t)D, win_path,
+                               (int)x_dt, ldx, D, d_Y, (int)y_dt, ldy, partial, (int64_t)D, win_path,
                                m->win_h, tile_mask);
         else
             hipLaunchKernelGGL(spmm_gather_generic_kernel<false>, dim3(grid), dim3(kBlock), 0, s, m->d_lane_tab,
                                m->d_seg_row, m->d_seg_ebeg, m->d_seg_dst, m->d_row_ptr, m->d_col_idx, d_w, d_X,
-                               (int)x_dt, ldx, D, d_Y, (int)y_dt, ldy, m->d_partial, (int64_t)D, win_path,
+                               (int)x_dt, ldx, D, d_Y, (int)y_dt, ldy, partial, (int64_t)D, win_path,
                                m->win_h, tile_mask);
     }
     TCG_TRY(launch_status("spmm_gather_kernel"));
     if (m->n_long > 0) {
         hipLaunchKernelGGL(spmm_reduce_long_kernel, dim3((unsigned)m->n_long), dim3(kBlock), 0, s, m->n_long,
-                           m->d_long_row, m->d_long_slot_ptr, m->d_partial, (int64_t)D, D, d_Y, (int)y_dt, ldy,
+                           m->d_long_row, m->d_long_slot_ptr, partial, (int64_t)D, D, d_Y, (int)y_dt, ldy,
                            win_path, m->win_h, tile_mask);
         TCG_TRY(launch_status("spmm_reduce_long_kernel"));
     }

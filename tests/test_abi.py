@@ -24,7 +24,7 @@ def test_every_declared_symbol_is_exported():
 
 def test_status_texts_and_argument_checks_without_gpu():
     lib = tcg.load_library()
-    for code in (0, -1, -2, -3, -4, -5, -99):
+    for code in (0, -1, -2, -3, -4, -5, -6, -99):
         assert len(lib.tcg_strerror(code)) > 0
     # Null handles / null outputs are rejected before any HIP call is made.
     assert lib.tcg_sgt_build(4, 4, 0, None, None, 16, 8, 1, None, None) == -1
@@ -35,7 +35,23 @@ def test_status_texts_and_argument_checks_without_gpu():
     assert lib.tcg_sddmm(None, None, 0, 16, 16, None, None) == -1
     assert lib.tcg_row_softmax(None, None, None, None) == -1
     assert lib.tcg_sgt_set_policy(None, 0, 0.0, None) == -1
+    assert lib.tcg_sgt_reserve(None, 16, None) == -1
     lib.tcg_sgt_free(None)
+
+
+def test_sizes_beyond_the_int32_index_space_are_refused_before_any_gpu_work():
+    # nnz (and the row count) must fit int32: TCG_ERANGE comes back from the argument checks, before any HIP
+    # call is made and before a pointer is touched (the pointers here are never dereferenced).
+    lib = tcg.load_library()
+    fake = ctypes.c_void_p(256)
+    h = ctypes.c_void_p()
+    for n_rows, nnz in ((4, 2 ** 31 - 1), (4, 2 ** 31), (4, 2 ** 40), (2 ** 31 - 2, 8)):
+        assert lib.tcg_sgt_build(n_rows, 4, nnz, fake, fake, 16, 8, 0, None, ctypes.byref(h)) == -3
+        assert h.value is None
+    assert lib.tcg_csr_transpose(4, 4, 2 ** 31, fake, fake, fake, fake, fake, None) == -3
+    assert lib.tcg_reorder_rows(4, 2 ** 31, fake, fake, 0, 0, fake, None) == -3
+    assert lib.tcg_csr_permute(4, 2 ** 31, fake, fake, fake, fake, fake, None, None) == -3
+    assert b"int32" in lib.tcg_strerror(-3)
 
 
 def test_sources_have_no_oracle_dependency():

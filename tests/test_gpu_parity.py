@@ -655,6 +655,79 @@ def test_attention_chain_replays_from_a_hip_graph():
     meta.free()
 
 
+def test_reserved_scratch_lets_wide_features_be_captured_without_a_warm_up():
+    # The plan reserves partial-sum scratch for D <= 128.  A wider first call regrows it, which a stream under
+    # capture cannot do: the call then reports TCG_ESCRATCH and leaves the capture intact; after
+    # tcg_sgt_reserve the same call is captured and replays to the oracle's result.
+    import ctypes
+    g = hub_graph(2500, seed=9)
+    rp, ci = upload_csr(g)
+    D = 256
+    X = W.features_uniform(g.n_cols, D, 4)
+    Xd = upload_x(X, "f32")
+    Y = torch.empty((g.n_rows, D), device=dev())
+    Y_ref = oracle.spmm(g.row_ptr, g.col_idx, X, None)
+    lib = tcg.load_library()
+    for reserve_first in (False, True):
+        meta = tcg.sgt_build(rp, ci, 16, 8)
+        assert tcg.sgt_plan_stats(meta)["n_long_rows"] > 0
+        if reserve_first:
+            tcg.sgt_reserve(meta, D)
+        graph = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        status = None
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                status = lib.tcg_spmm(meta._h, ctypes.c_void_p(Xd.data_ptr()), 0, D, D, None,
+                                      ctypes.c_void_p(Y.data_ptr()), 0, D, ctypes.c_void_p(side.cuda_stream))
+                Xd.add_(0.0)                                   # the capture is still alive after a refusal
+        torch.cuda.synchronize()
+        if not reserve_first:
+            assert status == -6 and b"tcg_sgt_reserve" in lib.tcg_strerror(status)
+        else:
+            assert status == 0
+            for _ in range(2):
+                Y.fill_(float("nan"))
+                graph.replay()
+                torch.cuda.synchronize()
+                assert norm_err(Y.cpu().numpy(), Y_ref) <= TOL_F32
+                tcg.sddmm(meta, Xd)                            # eager work between the replays
+                torch.cuda.synchronize()
+        del graph
+        meta.free()
+
+
+@pytest.mark.parametrize("x_dtype", ["f32", "bf16"])
+def test_non_finite_features_reach_the_rows_the_header_says(x_dtype):
+    # One infinite feature row X[j].  Gather path: exactly the rows with an entry in column j become
+    # non-finite (Equation 1 applied to the stored entries).  Condensed-tile path: every row of every
+    # window whose column list contains j (0 x inf inside the matrix unit); all other rows stay exact.
+    c = W.make_config(5, n=64 * 30, d=128, permute=False)
+    g = c["csr"]
+    X = W.round_to_bf16(c["X"]) if x_dtype == "bf16" else c["X"].copy()
+    j = 777
+    X[j, :] = np.inf
+    rp, ci = upload_csr(g)
+    Xd = torch.from_numpy(X).to(dev()).to(TORCH_DT[x_dtype])
+    rows_with_j = np.zeros(g.n_rows, dtype=bool)
+    for i in range(g.n_rows):
+        rows_with_j[i] = j in g.col_idx[g.row_ptr[i]:g.row_ptr[i + 1]]
+    win_with_j = rows_with_j.reshape(-1, 16).any(axis=1).repeat(16)
+    Xz = X.copy()
+    Xz[j, :] = 0.0
+    Y_clean = oracle.spmm(g.row_ptr, g.col_idx, Xz, None)
+    for policy, bad in ((tcg.POLICY_GATHER, rows_with_j), (tcg.POLICY_TILE, win_with_j)):
+        meta = tcg.sgt_build(rp, ci, 16, 8)
+        tcg.sgt_set_policy(meta, policy)
+        Y = tcg.spmm(meta, Xd).cpu().numpy()
+        finite = np.isfinite(Y).all(axis=1)
+        assert np.array_equal(~finite, bad), policy
+        tol = TOL_F32 if (x_dtype == "f32" or policy == tcg.POLICY_GATHER) else TOL_MFMA
+        assert norm_err(Y[finite], Y_clean[finite]) <= tol
+        meta.free()
+
+
 def test_calls_follow_the_current_stream():
     # The binding passes torch's current stream: the whole path on a side stream must give the same bits
     # as on the default stream, and the work must really be enqueued there (the side stream's event
