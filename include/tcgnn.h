@@ -49,8 +49,9 @@ typedef enum {
     TCG_ERANGE = -3, /* a size does not fit the int32 index space                               */
     TCG_ENOMEM = -4, /* host or device allocation failed                                        */
     TCG_EHIP = -5,   /* a HIP runtime call or kernel launch failed                              */
-    TCG_ESCRATCH = -6 /* a scratch buffer is too small and may not be (re)allocated in this call: a
-                        plan's buffer while the stream is being captured (tcg_strerror says more) */
+    TCG_ESCRATCH = -6 /* a scratch buffer is too small and may not be (re)allocated in this call: the
+                        static buffer of tcg_spmm_noalloc, or a plan's buffer while the stream is
+                        being captured (tcg_strerror says which and by how much)                */
 } tcg_status;
 
 /* Which kernel family a row window is executed by (see tcg_sgt_set_policy). */
@@ -160,6 +161,20 @@ TCG_API int tcg_sgt_plan_stats(const tcg_meta *meta, int64_t *n_tile_windows, in
  */
 TCG_API int tcg_spmm(tcg_meta *meta, const void *d_X, tcg_dtype x_dt, int32_t D, int64_t ldx,
              const float *d_w, void *d_Y, tcg_dtype y_dt, int64_t ldy, void *stream);
+
+/*
+ * tcg_spmm for callers that cannot allocate device memory (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc).  Same arguments, same kernels and bit-identical results; the
+ * partial sums of split rows go to a 64 MiB device array that is part of the library's code object
+ * (one copy per GPU, held until the process ends) instead of the plan's buffer.  The call allocates
+ * nothing and does not synchronise.  Limit: (number of segments of split rows) x D x 4 bytes <= 64 MiB;
+ * beyond it the call does nothing and returns TCG_ESCRATCH (tcg_strerror gives both sizes).  All calls
+ * on one GPU share the array: calls that overlap in time on one GPU (different streams or threads) race,
+ * also with different plans.  Nothing in it needs clearing between calls (every partial row is
+ * written in full before it is read).
+ */
+TCG_API int tcg_spmm_noalloc(tcg_meta *meta, const void *d_X, tcg_dtype x_dt, int32_t D, int64_t ldx,
+                     const float *d_w, void *d_Y, tcg_dtype y_dt, int64_t ldy, void *stream);
 
 /*
  * Grows the plan's partial-sum scratch for feature widths up to max_D now, so that later tcg_spmm /

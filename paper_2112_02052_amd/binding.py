@@ -16,7 +16,7 @@ EXPORTED = ["tcg_sgt_build", "tcg_sgt_sizes", "tcg_sgt_export", "tcg_sgt_set_pol
             "tcg_sgt_plan_stats", "tcg_spmm", "tcg_sddmm", "tcg_row_softmax", "tcg_sgt_free",
             "tcg_strerror", "tcg_release_cached_memory", "tcg_sddmm_pq", "tcg_row_softmax_backward",
             "tcg_csr_transpose", "tcg_edge_gather", "tcg_attention", "tcg_reorder_rows", "tcg_csr_permute",
-            "tcg_sgt_reserve"]
+            "tcg_sgt_reserve", "tcg_spmm_noalloc"]
 
 _DTYPES = {torch.float32: TCG_F32, torch.bfloat16: TCG_BF16, torch.float16: TCG_F16}
 
@@ -56,6 +56,8 @@ def load_library():
                              ctypes.c_int64, _vp]
     lib.tcg_sgt_reserve.restype = ctypes.c_int
     lib.tcg_sgt_reserve.argtypes = [_vp, ctypes.c_int32, _vp]
+    lib.tcg_spmm_noalloc.restype = ctypes.c_int
+    lib.tcg_spmm_noalloc.argtypes = lib.tcg_spmm.argtypes
     lib.tcg_sddmm.restype = ctypes.c_int
     lib.tcg_sddmm.argtypes = [_vp, _vp, ctypes.c_int, ctypes.c_int32, ctypes.c_int64, _vp, _vp]
     lib.tcg_row_softmax.restype = ctypes.c_int
@@ -180,7 +182,13 @@ def _features(meta, X, rows_needed):
     return X
 
 
-def spmm(meta, X, w=None, Y=None, y_dtype=torch.float32):
+def spmm_noalloc(meta, X, w, Y):
+    """tcg_spmm_noalloc: tcg_spmm with the split rows' partial sums in the library's static device array;
+    the caller passes every buffer, the call allocates nothing."""
+    return spmm(meta, X, w, Y, _entry="tcg_spmm_noalloc")
+
+
+def spmm(meta, X, w=None, Y=None, y_dtype=torch.float32, _entry="tcg_spmm"):
     """tcg_spmm: Y = (w (.) A) X.  Returns Y (allocated here unless given)."""
     X = _features(meta, X, meta.n_cols)
     D = X.shape[1]
@@ -193,9 +201,9 @@ def spmm(meta, X, w=None, Y=None, y_dtype=torch.float32):
     _need_cuda(Y)
     if Y.dim() != 2 or Y.shape != (meta.n_rows, D) or Y.stride(1) != 1 or Y.dtype not in _DTYPES:
         raise ValueError("Y must be [n_rows, D] with unit stride along features")
-    _check(load_library().tcg_spmm(meta._h, _ptr(X), _DTYPES[X.dtype], D, X.stride(0), _ptr(w), _ptr(Y),
-                                   _DTYPES[Y.dtype], Y.stride(0) if meta.n_rows > 1 else max(D, Y.stride(0)),
-                                   _stream()))
+    _check(getattr(load_library(), _entry)(meta._h, _ptr(X), _DTYPES[X.dtype], D, X.stride(0), _ptr(w), _ptr(Y),
+                                           _DTYPES[Y.dtype], Y.stride(0) if meta.n_rows > 1 else max(D, Y.stride(0)),
+                                           _stream()))
     return Y
 
 

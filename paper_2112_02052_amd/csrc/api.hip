@@ -50,6 +50,12 @@ int tcg_sgt_build(int32_t n_rows, int32_t n_cols, int64_t nnz, const int32_t *d_
         set_hip_error(hipGetLastError(), "hipGetDevice");
         return TCG_EHIP;
     }
+    // Set-up for tcg_spmm_noalloc: this device's address of the static scratch array is looked up here,
+    // so that the call itself has nothing left to resolve.
+    if (int st = static_scratch(nullptr, nullptr); st != TCG_OK) {
+        delete m;
+        return st;
+    }
     m->n_rows = n_rows;
     m->n_cols = n_cols;
     m->nnz = nnz;
@@ -124,7 +130,17 @@ int tcg_spmm(tcg_meta *meta, const void *d_X, tcg_dtype x_dt, int32_t D, int64_t
     if ((!d_X && meta->nnz > 0) || (!d_Y && meta->n_rows > 0)) return TCG_EINVAL;
     if ((reinterpret_cast<uintptr_t>(d_X) % dtype_size(x_dt)) || (reinterpret_cast<uintptr_t>(d_Y) % dtype_size(y_dt)))
         return TCG_EINVAL;
-    return spmm_impl(meta, d_X, x_dt, D, ldx, d_w, d_Y, y_dt, ldy, static_cast<hipStream_t>(stream));
+    return spmm_impl(meta, d_X, x_dt, D, ldx, d_w, d_Y, y_dt, ldy, false, static_cast<hipStream_t>(stream));
+}
+
+int tcg_spmm_noalloc(tcg_meta *meta, const void *d_X, tcg_dtype x_dt, int32_t D, int64_t ldx, const float *d_w,
+                     void *d_Y, tcg_dtype y_dt, int64_t ldy, void *stream)
+{
+    if (!meta || D < 1 || ldx < D || ldy < D || !dtype_ok(x_dt) || !dtype_ok(y_dt)) return TCG_EINVAL;
+    if ((!d_X && meta->nnz > 0) || (!d_Y && meta->n_rows > 0)) return TCG_EINVAL;
+    if ((reinterpret_cast<uintptr_t>(d_X) % dtype_size(x_dt)) || (reinterpret_cast<uintptr_t>(d_Y) % dtype_size(y_dt)))
+        return TCG_EINVAL;
+    return spmm_impl(meta, d_X, x_dt, D, ldx, d_w, d_Y, y_dt, ldy, true, static_cast<hipStream_t>(stream));
 }
 
 int tcg_sgt_reserve(tcg_meta *meta, int32_t max_D, void *stream)

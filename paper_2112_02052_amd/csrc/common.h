@@ -154,10 +154,12 @@ int choose_paths(tcg_meta *m, tcg_policy policy, float min_reuse, hipStream_t s)
 
 // spmm.hip / sddmm.hip / softmax.hip
 int spmm_impl(tcg_meta *m, const void *d_X, tcg_dtype x_dt, int32_t D, int64_t ldx, const float *d_w,
-              void *d_Y, tcg_dtype y_dt, int64_t ldy, hipStream_t s);
+              void *d_Y, tcg_dtype y_dt, int64_t ldy, bool no_alloc, hipStream_t s);
 // Makes the plan's partial-sum scratch large enough for feature width D (allocates; an error while the
 // stream is being captured).
 int reserve_partial(tcg_meta *m, int32_t D, hipStream_t s);
+// The library's static scratch array on the current device (resolved once per device).
+int static_scratch(float **ptr, int64_t *capacity_elems);
 int sddmm_impl(tcg_meta *m, const void *d_P, int64_t ldp, const void *d_X, int64_t ldx, tcg_dtype x_dt, int32_t D,
                float *d_out, hipStream_t s);
 

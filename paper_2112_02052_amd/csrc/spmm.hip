@@ -18,6 +18,9 @@
 #include "common.h"
 #include "devutil.h"
 
+#include <stdio.h>
+
+#include <mutex>
 
 namespace tcg {
 
@@ -334,7 +337,7 @@ __global__ __launch_bounds__(kBlock) void spmm_reduce_long_kernel(
 
 struct GatherArgs {
     const tcg_meta *m;
-    float *partial;     // partial sums of split rows
+    float *partial;     // partial sums of split rows: the plan's buffer or the library's static one
     const void *X;
     int64_t ldx;
     int32_t D;
@@ -419,6 +422,32 @@ bool dispatch_elem_w(const GatherArgs &a)
 
 }  // namespace
 
+// Scratch of tcg_spmm_noalloc: the partial sums of split rows, for callers that must not allocate.  Every
+// GPU the library runs on holds its own copy of the array until the process ends.  In host code the
+// array's name is only a handle for hipGetSymbolAddress; kernels get the address that call returned.
+constexpr size_t kStaticScratchBytes = (size_t)64 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mu;
+static void *g_scratch_ptr[kMaxDevices] = {nullptr};
+
+int static_scratch(float **ptr, int64_t *capacity_elems)
+{
+    int dev = 0;
+    TCG_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return TCG_EINVAL;
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        TCG_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));      // this device's copy of the array
+        g_scratch_ptr[dev] = p;
+    }
+    if (ptr) *ptr = static_cast<float *>(g_scratch_ptr[dev]);
+    if (capacity_elems) *capacity_elems = (int64_t)(kStaticScratchBytes / sizeof(float));
+    return TCG_OK;
+}
+
 int reserve_partial(tcg_meta *m, int32_t D, hipStream_t s)
 {
     const int64_t need = m->n_slots * (int64_t)D;
@@ -443,14 +472,29 @@ int reserve_partial(tcg_meta *m, int32_t D, hipStream_t s)
 }
 
 int spmm_impl(tcg_meta *m, const void *d_X, tcg_dtype x_dt, int32_t D, int64_t ldx, const float *d_w,
-              void *d_Y, tcg_dtype y_dt, int64_t ldy, hipStream_t s)
+              void *d_Y, tcg_dtype y_dt, int64_t ldy, bool no_alloc, hipStream_t s)
 {
     if (m->n_rows == 0) return TCG_OK;
 
-    // Scratch for the partial sums of rows that span several segments: the plan's buffer (regrown for a
-    // wider D than it was reserved for).
-    TCG_TRY(reserve_partial(m, D, s));
-    float *partial = m->d_partial;
+    // Scratch for the partial sums of rows that span several segments: the plan's own buffer (regrown for
+    // a wider D than it was reserved for), or the library's static array for callers that cannot allocate.
+    const int64_t need = m->n_slots * (int64_t)D;
+    float *partial = nullptr;
+    if (no_alloc) {
+        int64_t cap = 0;
+        TCG_TRY(static_scratch(&partial, &cap));
+        if (need > cap) {
+            char msg[200];
+            snprintf(msg, sizeof(msg), "tcg_spmm_noalloc: %lld split-row segments x D = %d need %lld bytes of scratch, "
+                     "the static buffer holds %lld", (long long)m->n_slots, (int)D, (long long)(need * 4),
+                     (long long)kStaticScratchBytes);
+            set_message(msg);
+            return TCG_ESCRATCH;
+        }
+    } else {
+        TCG_TRY(reserve_partial(m, D, s));
+        partial = m->d_partial;
+    }
 
     // Which classes of tile-path windows really go to the MFMA kernels depends on the feature width, which
     // the plan does not know: measured on MI355X (the calibration tool's sweeps), narrow rows are gathered
