@@ -6,7 +6,7 @@ PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG_DIR, "csrc")
 INCLUDE = os.path.join(os.path.dirname(PKG_DIR), "include")
 LIB_PATH = os.path.join(PKG_DIR, "libtcgnn.so")
-SOURCES = ["api.hip", "pool.hip", "sgt.hip", "spmm.hip", "spmm_tile.hip", "sddmm.hip", "sddmm_tile.hip", "backward.hip", "attn.hip", "reorder.hip"]
+SOURCES = ["api.hip", "pool.hip", "sgt.hip", "spmm.hip", "spmm_tile.hip", "sddmm.hip", "sddmm_tile.hip", "backward.hip", "attn.hip", "reorder.hip", "radix.hip"]
 
 HIPCC_FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared", "-fvisibility=hidden",

@@ -94,11 +94,23 @@ int tcg_sgt_export(const tcg_meta *meta, int32_t *win_partition, int32_t *win_un
     struct Item { void *dst; const void *src; int64_t count; };
     const Item items[] = {{win_partition, meta->d_win_partition, meta->n_win},
                           {win_unique_ptr, meta->d_win_unique_ptr, meta->n_win + 1},
-                          {edge_to_col, meta->d_edge_to_col, meta->nnz},
-                          {col_to_row, meta->d_col_to_row, meta->total_unique}};
+                          {edge_to_col, meta->d_edge_to_col, meta->nnz}};
     for (const Item &it : items)
         if (it.dst && it.count > 0)
             TCG_HIP(hipMemcpyAsync(it.dst, it.src, (size_t)it.count * sizeof(int32_t), kind, s));
+    // The library keeps every window's list at the window's edge offset; the exported form is packed.
+    PoolBuf staging;
+    staging.s = s;
+    if (col_to_row && meta->total_unique > 0) {
+        int32_t *packed = col_to_row;
+        if (!dst_on_device) {
+            TCG_TRY(pool_alloc(&staging.p, (size_t)meta->total_unique * sizeof(int32_t)));
+            packed = static_cast<int32_t *>(staging.p);
+        }
+        TCG_TRY(export_col_to_row(meta, packed, s));
+        if (!dst_on_device)
+            TCG_HIP(hipMemcpyAsync(col_to_row, packed, (size_t)meta->total_unique * sizeof(int32_t), kind, s));
+    }
     if (!dst_on_device) TCG_HIP(hipStreamSynchronize(s));
     return TCG_OK;
 }

@@ -4,9 +4,8 @@
 //                       dw[e] = < dY[row(e)], X[col(e)] >   tcg_sddmm_pq(P = dY, Q = X)
 //   out[e] = <x_i,x_j>: dX = (g (.) A) X + (g (.) A)^T X    two tcg_spmm calls (g = d out)
 //   p = row_softmax(v): dv[e] = p[e] (dp[e] - sum_row p dp)  tcg_row_softmax_backward
-// This file holds the CSR transpose (a stable least-significant-digit radix sort of the entries by
-// column, 4 bits per pass, so the result is unique and deterministic), the edge-value permutation
-// and the softmax gradient.
+// This file holds the CSR transpose (a stable radix sort of the entries by column, radix.hip, so the
+// result is unique and deterministic), the edge-value permutation and the softmax gradient.
 #include "common.h"
 
 namespace tcg {
@@ -14,50 +13,6 @@ namespace tcg {
 namespace {
 
 constexpr int kThreads = 256;
-constexpr int kDigits = 16;   // 4-bit radix
-
-// Pass 1 of a radix step: per-workgroup digit counts, block_cnt[digit * n_blocks + block].
-__global__ __launch_bounds__(kThreads) void radix_count_kernel(const int32_t *__restrict__ keys, int64_t n,
-                                                               int shift, int32_t *__restrict__ block_cnt,
-                                                               int64_t n_blocks)
-{
-    __shared__ int s_cnt[kDigits];
-    if (threadIdx.x < kDigits) s_cnt[threadIdx.x] = 0;
-    __syncthreads();
-    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-    if (i < n) atomicAdd(&s_cnt[(keys[i] >> shift) & (kDigits - 1)], 1);
-    __syncthreads();
-    if (threadIdx.x < kDigits) block_cnt[(int64_t)threadIdx.x * n_blocks + blockIdx.x] = s_cnt[threadIdx.x];
-}
-
-// Pass 2: stable scatter.  block_off = exclusive scan of block_cnt (digit-major); inside a workgroup
-// the rank of an element among the elements with its digit comes from wavefront ballots.
-// vals_in == nullptr stands for the identity (first pass).
-__global__ __launch_bounds__(kThreads) void radix_scatter_kernel(
-    const int32_t *__restrict__ keys_in, const int32_t *__restrict__ vals_in, int64_t n, int shift,
-    const int32_t *__restrict__ block_off, int64_t n_blocks, int32_t *__restrict__ keys_out,
-    int32_t *__restrict__ vals_out)
-{
-    __shared__ int s_wave_cnt[kThreads / kWave][kDigits];
-    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
-    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-    const int32_t key = i < n ? keys_in[i] : 0;
-    const int digit = i < n ? (key >> shift) & (kDigits - 1) : -1;
-    int rank_in_wave = 0;
-#pragma unroll
-    for (int d = 0; d < kDigits; ++d) {
-        const unsigned long long mask = __ballot(digit == d);
-        if (lane == 0) s_wave_cnt[wave][d] = __popcll(mask);
-        if (digit == d) rank_in_wave = __popcll(mask & ((1ull << lane) - 1ull));
-    }
-    __syncthreads();
-    if (digit < 0) return;
-    int32_t p = block_off[(int64_t)digit * n_blocks + blockIdx.x] + rank_in_wave;
-    for (int w2 = 0; w2 < wave; ++w2) p += s_wave_cnt[w2][digit];
-    keys_out[p] = key;
-    vals_out[p] = vals_in ? vals_in[i] : (int32_t)i;
-}
-
 // After the sort: keys are the columns in ascending order, perm the input positions.  Writes the row
 // pointers of the transpose (first position of every column, empty columns included) and the
 // transposed column indices (= input row of the entry, found by bisection in the input row_ptr).
@@ -265,50 +220,6 @@ int edge_gather_impl(int64_t n, const int32_t *d_perm, const float *d_in, float 
     return launch_status("edge_gather_kernel");
 }
 
-size_t radix_sort_scratch_bytes(int64_t n)
-{
-    const int64_t n_blocks = ceil_div(n, kThreads);
-    const int64_t cnt_elems = (int64_t)kDigits * n_blocks + 1;
-    if (cnt_elems >= (int64_t)INT32_MAX) return 0;
-    const size_t arr = ((size_t)n * 4 + 255) & ~(size_t)255;
-    const size_t cnt_bytes = ((size_t)cnt_elems * 4 + 255) & ~(size_t)255;
-    return 2 * arr + cnt_bytes + (size_t)scan_workspace_elems(cnt_elems) * 4;
-}
-
-int radix_sort_pairs(const int32_t *d_keys_in, const int32_t *d_vals_in, int64_t n, int bits, int32_t *d_keys_out,
-                     int32_t *d_vals_out, void *d_scratch, hipStream_t s)
-{
-    if (n == 0) return TCG_OK;
-    const int passes = (bits + 3) / 4;
-    const int64_t n_blocks = ceil_div(n, kThreads);
-    const int64_t cnt_elems = (int64_t)kDigits * n_blocks + 1;
-    const size_t arr = ((size_t)n * 4 + 255) & ~(size_t)255;
-    const size_t cnt_bytes = ((size_t)cnt_elems * 4 + 255) & ~(size_t)255;
-    char *base = static_cast<char *>(d_scratch);
-    int32_t *keys_b = reinterpret_cast<int32_t *>(base);
-    int32_t *vals_b = reinterpret_cast<int32_t *>(base + arr);
-    int32_t *block_cnt = reinterpret_cast<int32_t *>(base + 2 * arr);
-    int32_t *scan_work = reinterpret_cast<int32_t *>(base + 2 * arr + cnt_bytes);
-
-    const int32_t *kin = d_keys_in;
-    const int32_t *vin = d_vals_in;
-    for (int pass = 0; pass < passes; ++pass) {
-        // Choose the outputs so that the last pass lands in the caller's arrays.
-        const bool to_out = ((passes - 1 - pass) % 2) == 0;
-        int32_t *kout = to_out ? d_keys_out : keys_b;
-        int32_t *vout = to_out ? d_vals_out : vals_b;
-        hipLaunchKernelGGL(radix_count_kernel, dim3((unsigned)n_blocks), dim3(kThreads), 0, s, kin, n, 4 * pass,
-                           block_cnt, n_blocks);
-        TCG_TRY(exclusive_scan_i32(block_cnt, block_cnt, cnt_elems - 1, scan_work, s));
-        hipLaunchKernelGGL(radix_scatter_kernel, dim3((unsigned)n_blocks), dim3(kThreads), 0, s, kin, vin, n, 4 * pass,
-                           block_cnt, n_blocks, kout, vout);
-        TCG_TRY(launch_status("radix kernels"));
-        kin = kout;
-        vin = vout;
-    }
-    return TCG_OK;
-}
-
 int csr_transpose_impl(int32_t n_rows, int32_t n_cols, int64_t nnz, const int32_t *d_row_ptr,
                        const int32_t *d_col_idx, int32_t *d_out_row_ptr, int32_t *d_out_col_idx, int32_t *d_perm,
                        hipStream_t s)
@@ -330,7 +241,7 @@ int csr_transpose_impl(int32_t n_rows, int32_t n_cols, int64_t nnz, const int32_
     TCG_TRY(pool_alloc(&buf.p, arr + radix_sort_scratch_bytes(nnz)));
     char *base = static_cast<char *>(buf.p);
     int32_t *keys_sorted = reinterpret_cast<int32_t *>(base);
-    TCG_TRY(radix_sort_pairs(d_col_idx, nullptr, nnz, bits, keys_sorted, d_perm, base + arr, s));
+    TCG_TRY(radix_sort_pairs(d_col_idx, nullptr, nnz, nullptr, bits, keys_sorted, d_perm, base + arr, s));
     const int32_t *kin = keys_sorted;
     hipLaunchKernelGGL(transpose_finish_kernel, dim3((unsigned)n_blocks), dim3(kThreads), 0, s, n_rows, n_cols, nnz,
                        d_row_ptr, kin, d_perm, d_out_row_ptr, d_out_col_idx);

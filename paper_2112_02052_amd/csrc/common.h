@@ -151,6 +151,8 @@ namespace tcg {
 // sgt.hip
 int sgt_build_impl(tcg_meta *m, int validate, hipStream_t s);
 int choose_paths(tcg_meta *m, tcg_policy policy, float min_reuse, hipStream_t s);
+// Writes the per-window unique lists back to back (the exported col_to_row) into d_packed[total_unique].
+int export_col_to_row(const tcg_meta *m, int32_t *d_packed, hipStream_t s);
 
 // spmm.hip / sddmm.hip / softmax.hip
 int spmm_impl(tcg_meta *m, const void *d_X, tcg_dtype x_dt, int32_t D, int64_t ldx, const float *d_w,
@@ -173,13 +175,14 @@ int csr_transpose_impl(int32_t n_rows, int32_t n_cols, int64_t nnz, const int32_
                        const int32_t *d_col_idx, int32_t *d_out_row_ptr, int32_t *d_out_col_idx, int32_t *d_perm,
                        hipStream_t s);
 int edge_gather_impl(int64_t n, const int32_t *d_perm, const float *d_in, float *d_out, hipStream_t s);
-// Stable least-significant-digit radix sort (4 bits per pass) of n (key, value) pairs by key, keys in
-// [0, 2^bits).  d_vals_in == nullptr stands for the values 0 .. n-1.  The outputs must not overlap the
-// inputs.  d_scratch: device memory of radix_sort_scratch_bytes(n) bytes (0 = n too large).
-// Asynchronous on s.
-size_t radix_sort_scratch_bytes(int64_t n);
-int radix_sort_pairs(const int32_t *d_keys_in, const int32_t *d_vals_in, int64_t n, int bits, int32_t *d_keys_out,
-                     int32_t *d_vals_out, void *d_scratch, hipStream_t s);
+// radix.hip: stable least-significant-digit radix sort (8 bits per pass) of (key, value) pairs by key, keys in
+// [0, 2^bits) (never negative).  d_vals_in == nullptr stands for the values 0 .. n-1.  The number of pairs is
+// n_max, or, when d_n is given, the smaller of n_max and the int32 at d_n (device memory; buffers and grids
+// are sized by n_max).  The outputs must not overlap the inputs.  d_scratch: device memory of
+// radix_sort_scratch_bytes(n_max) bytes (0 = n_max too large).  Asynchronous on s.
+size_t radix_sort_scratch_bytes(int64_t n_max);
+int radix_sort_pairs(const int32_t *d_keys_in, const int32_t *d_vals_in, int64_t n_max, const int32_t *d_n, int bits,
+                     int32_t *d_keys_out, int32_t *d_vals_out, void *d_scratch, hipStream_t s);
 
 // reorder.hip
 int reorder_rows_impl(int32_t n, int64_t nnz, const int32_t *d_row_ptr, const int32_t *d_col_idx, uint64_t seed,
@@ -211,7 +214,7 @@ struct tcg_meta {
     int32_t *d_win_partition = nullptr;   // [n_win]
     int32_t *d_win_unique_ptr = nullptr;  // [n_win + 1]
     int32_t *d_edge_to_col = nullptr;     // [nnz]
-    int32_t *d_col_to_row = nullptr;      // [total_unique]
+    int32_t *d_col_to_row = nullptr;      // [nnz] window w's list at offset row_ptr[w * win_h], U_w entries
 
     // Gather plan: every row is cut into segments of at most kSegLen edges.
     int64_t n_seg = 0, n_long = 0, n_slots = 0;
@@ -220,7 +223,7 @@ struct tcg_meta {
     int32_t *d_seg_dst = nullptr;         // [n_seg] partial-sum slot, or -1: write the row directly
     int32_t *d_long_row = nullptr;        // [n_long] rows with more than one segment
     int32_t *d_long_slot_ptr = nullptr;   // [n_long + 1] their slot ranges
-    int32_t *d_lane_tab = nullptr;        // [kXcds x kLaneTabStride] see plan_segment()
+    int32_t *d_lane_tab = nullptr;        // [kXcds x kLaneTabStride] see plan_segment() (inside the build's result block)
     int32_t h_lane_tab[6 * 8] = {0};      // host copy (sizes the gather grids, see plan_grid())
     float *d_partial = nullptr;           // [n_slots x D] scratch; reserved for D <= kPartialInitD, regrown on demand
     int64_t partial_elems = 0;

@@ -271,9 +271,9 @@ int reorder_rows_impl(int32_t n, int64_t nnz, const int32_t *d_row_ptr, const in
     TCG_TRY(launch_status("refine_kernel"));
     // nodes by (label, parent, id): stable sort by parent, then stable sort by label
     const int bits = bits_for(n);
-    TCG_TRY(radix_sort_pairs(parent, nullptr, n, bits, keys, order1, sort_scratch, s));
+    TCG_TRY(radix_sort_pairs(parent, nullptr, n, nullptr, bits, keys, order1, sort_scratch, s));
     hipLaunchKernelGGL(gather_i32_kernel, dim3(blocks_for(n)), dim3(256), 0, s, (int64_t)n, order1, label, keys2);
-    TCG_TRY(radix_sort_pairs(keys2, order1, n, bits, keys, d_perm, sort_scratch, s));
+    TCG_TRY(radix_sort_pairs(keys2, order1, n, nullptr, bits, keys, d_perm, sort_scratch, s));
     TCG_HIP(hipStreamSynchronize(s));        // the scratch goes back to the pool on return
     return TCG_OK;
 }

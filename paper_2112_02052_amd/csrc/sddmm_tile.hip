@@ -80,6 +80,7 @@ __global__ __launch_bounds__(kTileBlock) void sddmm_tile_kernel(
     __syncthreads();
     const int32_t lo = s_rp[0], hi = s_rp[16];
     const int32_t u0 = win_unique_ptr[win];
+    const int32_t cb = row_ptr[r0];             // the window's list sits at its edge offset
     const int32_t U = win_unique_ptr[win + 1] - u0;
     const int32_t row_bytes = D * 2;
     const int n = lane & 15;                    // tile row (A) / tile column (B) of this lane
@@ -99,7 +100,7 @@ __global__ __launch_bounds__(kTileBlock) void sddmm_tile_kernel(
     for (int32_t c0 = 0; c0 < U; c0 += kCols) {
         for (int t = wave; t < kCols / 16 && c0 + t * 16 < U; t += kWaves) {
             const int32_t col = c0 + t * 16 + n;
-            const int64_t node = col < U ? col_to_row[u0 + col] : -1;
+            const int64_t node = col < U ? col_to_row[cb + col] : -1;
             uint4 b[KSTEPS];
 #pragma unroll
             for (int kk = 0; kk < KSTEPS; ++kk) {
@@ -159,10 +160,11 @@ __global__ __launch_bounds__(kWave) void sddmm_tile_wave_kernel(
         s_rp[lane] = row_ptr[r < n_rows ? r : n_rows];
     }
     const int32_t u0 = win_unique_ptr[win];
+    const int32_t cb = row_ptr[r0];             // the window's list sits at its edge offset
     const int32_t U = win_unique_ptr[win + 1] - u0;
     const int32_t row_bytes = D * 2;
-    int32_t nid = n < U ? col_to_row[u0 + n] : -1;              // neighbour of tile column 0
-    int32_t nid_nxt = 16 + n < U ? col_to_row[u0 + 16 + n] : -1;
+    int32_t nid = n < U ? col_to_row[cb + n] : -1;              // neighbour of tile column 0
+    int32_t nid_nxt = 16 + n < U ? col_to_row[cb + 16 + n] : -1;
 
     uint4 a[KSTEPS];
     {
@@ -212,7 +214,7 @@ __global__ __launch_bounds__(kWave) void sddmm_tile_wave_kernel(
         nid = nid_nxt;
         if (c0 + 16 < U) {
             fetch(nid);
-            nid_nxt = c0 + 32 + n < U ? col_to_row[u0 + c0 + 32 + n] : -1;
+            nid_nxt = c0 + 32 + n < U ? col_to_row[cb + c0 + 32 + n] : -1;
         }
 #pragma unroll
         for (int r = 0; r < 4; ++r) s_e[(4 * kg + r) * kScoreStride + n] = acc[r];
@@ -301,9 +303,10 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(KSTEPS >=
         s_rp[lane] = row_ptr[r < n_rows ? r : n_rows];
     }
     const int32_t u0 = win_unique_ptr[win];
+    const int32_t cb = row_ptr[r0];             // the window's list sits at its edge offset
     const int32_t U = win_unique_ptr[win + 1] - u0;
-    int32_t nid = n < U ? col_to_row[u0 + n] : -1;              // neighbour of tile column 0
-    int32_t nid_nxt = 16 + n < U ? col_to_row[u0 + 16 + n] : -1;
+    int32_t nid = n < U ? col_to_row[cb + n] : -1;              // neighbour of tile column 0
+    int32_t nid_nxt = 16 + n < U ? col_to_row[cb + 16 + n] : -1;
 
     // features kk * 32 + 8 kg .. + 7 of a row, as two 16-byte pieces (D is a multiple of 4)
     auto load8 = [&](const float *row, int kk, f32x4 &u, f32x4 &v) {
@@ -383,7 +386,7 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(KSTEPS >=
         nid = nid_nxt;
         if (c0 + 16 < U) {
             fetch(nid);
-            nid_nxt = c0 + 32 + n < U ? col_to_row[u0 + c0 + 32 + n] : -1;
+            nid_nxt = c0 + 32 + n < U ? col_to_row[cb + c0 + 32 + n] : -1;
         }
         const int32_t cb = MANY ? c0 % kBatch : 0;              // where this tile column sits in the parked batch
 #pragma unroll

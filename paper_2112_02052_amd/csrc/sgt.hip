@@ -2,21 +2,22 @@
 // execution plan derived from it.
 //
 // The paper notes that row windows are independent, so each window is translated by one
-// workgroup.  Four size classes, all producing the same canonical result (ascending unique
-// column list, rank of every edge's column in it):
-//   tiny   (<= 128 edges)    bitonic network in LDS, one wavefront
-//   small  (<= 1024 edges)   same, 256 threads
-//   medium (<= 4096 edges)   same, 256 threads, 32 KB of LDS
-//   large  (>  4096 edges)   a bitmap over the column space in device scratch: set a bit per
-//                            edge, prefix-popcount the words, rank = prefix + popcount below.
-//                            Hub windows of power-law graphs land here; the cost is
-//                            O(n_cols / 32 + nnz_w) per window.
-// Every window first writes its unique list at its own edge offset of a temporary array (the
-// list is never longer than the window's edge range); once all U_w are known a prefix sum gives
-// win_unique_ptr and the lists are packed into col_to_row.
+// workgroup.  Size classes by the number of stored entries, all producing the same canonical result
+// (ascending unique column list, rank of every edge's column in it):
+//   up to 1024 entries   (five classes: 64, 128, 256, 512, 1024) a bitonic sorting network held in
+//                        registers, 64 to 256 threads; the keys carry the entry's position, so ranks are
+//                        scattered straight to edge_to_col
+//   above               a bitmap over the column space -- in LDS when it fits (up to about 1.16 M
+//                        columns), else in device scratch (then a class of up to 4096 entries is still
+//                        sorted): set a bit per edge, prefix-popcount the words, rank = prefix + popcount
+//                        below.  Hub windows of power-law graphs land here; the cost is
+//                        O(n_cols / 32 + nnz_w) per window.
+// Every window writes its unique list at its own edge offset of col_to_row (the list is never longer than
+// the window's edge range) and it stays there: the kernels that use it find it through row_ptr, and only
+// the export packs the lists back to back.
 //
-// Host side: three stream synchronisations per build (class / plan sizes, U, final counters) and a
-// handful of arena allocations; everything else is enqueued back to back.
+// Host side: one stream synchronisation per build (see sgt_build_impl) and three arena allocations;
+// everything else is enqueued back to back.
 #include "common.h"
 
 #include <limits.h>
@@ -26,10 +27,6 @@
 namespace tcg {
 
 namespace {
-
-constexpr int kTinyCap = 128;
-constexpr int kSmallCap = 1024;
-constexpr int kMediumCap = 4096;   // 2 x 16 KB of static LDS
 
 __device__ __forceinline__ int wave_inclusive_scan(int v)
 {
@@ -167,108 +164,263 @@ __device__ __forceinline__ void window_edge_range(const int32_t *rp, int32_t n_r
     *hi = rp[r1];
 }
 
-// ---- window classification -----------------------------------------------------------------------
-// Appends every non-empty window to the list of its size class (order inside a list is irrelevant:
-// a window's result depends on the window only); empty windows get U_w = 0 here.
-// counts[0..3] = tiny, small, medium, large.
-__global__ __launch_bounds__(256) void classify_windows_kernel(int32_t n_rows, int32_t win_h, int64_t n_win,
-                                                               const int32_t *rp, int32_t *lists, int *counts,
-                                                               int32_t *win_unique, int32_t medium_cap)
+// ---- size classes and the per-build block of small results ---------------------------------------
+// A window's class follows its number of stored entries: five classes of the register sorting network
+// (<= 64, 128, 256, 512, 1024 entries), a sixth one (<= 4096) that only exists when the LDS bitmap does
+// not fit the column space, and the bitmap class.
+constexpr int kClsMedium = 5, kClsLarge = 6, kClasses = 7;
+constexpr int kSortCap = 1024;            // largest window of the five ordinary sort classes
+constexpr int kMediumCap = 4096;
+
+__device__ __forceinline__ int window_class(int32_t cnt, int32_t large_from)
 {
-    const int64_t w = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (cnt <= 64) return 0;
+    if (cnt <= 128) return 1;
+    if (cnt <= 256) return 2;
+    if (cnt <= 512) return 3;
+    if (cnt <= kSortCap) return 4;
+    return cnt <= large_from ? kClsMedium : kClsLarge;
+}
+
+// Everything the host needs from a build sits in one device block that is copied once, at the end.
+struct BuildInfo {
+    int32_t cls_count[8];                       // windows per size class
+    int32_t ticket;                             // work counter of the bitmap-class kernel
+    int32_t n_seg, n_long, n_slots;             // gather plan sizes
+    int32_t sort_tail;                          // single-segment rows ordered by length class
+    int32_t flag;                               // CSR validation
+    int32_t total_unique;
+    int32_t pad;
+    int32_t lane_tab[kLaneTabStride * kXcds];   // see plan_segment()
+    unsigned long long counters[8];             // choose_path_kernel totals
+};
+
+// ---- gather plan, step 1: per-row-block counts; window classification ----------------------------
+// Rows are handled in blocks of kRowBlock (four rounds of 256 threads; row = block * kRowBlock + round * 256
+// + thread).  Every row is cut into segments of at most kSegLen entries.  Per block: the number of split
+// rows (more than one segment), the number of their segments, and the number of single-segment rows in
+// each length class.  The same launch appends every non-empty window to the list of its size class
+// (order inside a list is irrelevant: a window's result depends on the window only).
+constexpr int kRowBlock = 1024;
+constexpr int kTailClasses = 8;
+constexpr int kPlanSums = 2 + kTailClasses;
+
+// Length classes of single-segment rows follow the number of gather iterations a row needs (longest
+// first), so that the lane groups of a wavefront get rows of similar length.
+__device__ __forceinline__ int length_class(int32_t deg)
+{
+    return deg > 96 ? 0 : deg > 64 ? 1 : deg > 48 ? 2 : deg > 32 ? 3 : deg > 24 ? 4 : deg > 16 ? 5 : deg > 8 ? 6 : 7;
+}
+
+__global__ __launch_bounds__(256) void prep_kernel(int32_t n_rows, int32_t win_h, int64_t n_win,
+                                                   const int32_t *__restrict__ rp, int64_t nb_rows,
+                                                   int32_t *__restrict__ block_sums, int32_t *__restrict__ lists,
+                                                   int32_t *cls_count, int32_t *__restrict__ win_unique,
+                                                   int32_t large_from)
+{
     const int lane = threadIdx.x & (kWave - 1);
+    if ((int64_t)blockIdx.x < nb_rows) {
+        __shared__ int s_sum[kPlanSums];
+        if (threadIdx.x < kPlanSums) s_sum[threadIdx.x] = 0;
+        __syncthreads();
+        int n_long = 0, n_slot = 0;
+#pragma unroll
+        for (int round = 0; round < kRowBlock / 256; ++round) {
+            const int64_t r = (int64_t)blockIdx.x * kRowBlock + round * 256 + threadIdx.x;
+            int cls = -1;
+            if (r < n_rows) {
+                const int32_t deg = rp[r + 1] - rp[r];
+                if (deg > kSegLen) {
+                    ++n_long;
+                    n_slot += (deg + kSegLen - 1) / kSegLen;
+                } else {
+                    cls = length_class(deg);
+                }
+            }
+#pragma unroll
+            for (int c = 0; c < kTailClasses; ++c) {
+                const unsigned long long mask = __ballot(cls == c);
+                if (lane == 0 && mask) atomicAdd(&s_sum[2 + c], __popcll(mask));
+            }
+        }
+#pragma unroll
+        for (int off = 1; off < kWave; off <<= 1) {
+            n_long += __shfl_xor(n_long, off, kWave);
+            n_slot += __shfl_xor(n_slot, off, kWave);
+        }
+        if (lane == 0 && n_long) {
+            atomicAdd(&s_sum[0], n_long);
+            atomicAdd(&s_sum[1], n_slot);
+        }
+        __syncthreads();
+        if (threadIdx.x < kPlanSums) block_sums[(int64_t)threadIdx.x * nb_rows + blockIdx.x] = s_sum[threadIdx.x];
+        return;
+    }
+    const int64_t w = ((int64_t)blockIdx.x - nb_rows) * 256 + threadIdx.x;
     int cls = -1;
     if (w < n_win) {
         int32_t lo, hi;
         window_edge_range(rp, n_rows, win_h, w, &lo, &hi);
         const int32_t cnt = hi - lo;
         if (cnt == 0) win_unique[w] = 0;
-        else cls = cnt <= kTinyCap ? 0 : cnt <= kSmallCap ? 1 : cnt <= medium_cap ? 2 : 3;
+        else cls = window_class(cnt, large_from);
     }
     // One atomic per wavefront and class instead of one per window.
 #pragma unroll
-    for (int c = 0; c < 4; ++c) {
+    for (int c = 0; c < kClasses; ++c) {
         const unsigned long long mask = __ballot(cls == c);
         if (mask == 0) continue;
         const int leader = __ffsll((long long)mask) - 1;
         int base = 0;
-        if (lane == leader) base = atomicAdd(&counts[c], __popcll(mask));
+        if (lane == leader) base = atomicAdd(&cls_count[c], __popcll(mask));
         base = __shfl(base, leader, kWave);
         if (cls == c) lists[(int64_t)c * n_win + base + __popcll(mask & ((1ull << lane) - 1ull))] = (int32_t)w;
     }
 }
 
-// Tiny, small and medium classes: one workgroup per listed window.
-template <int THREADS, int CAP>
-__global__ __launch_bounds__(THREADS) void sgt_window_lds_kernel(
-    int32_t n_rows, int32_t win_h, const int32_t *__restrict__ win_list, const int32_t *__restrict__ rp,
-    const int32_t *__restrict__ ci, int32_t *__restrict__ edge_to_col, int32_t *__restrict__ tmp_clean,
-    int32_t *__restrict__ win_unique)
+// ---- ordinary windows: sorting network in registers ---------------------------------------------
+// One workgroup of THREADS threads per window of at most N = THREADS * KPT entries; the workgroups walk
+// their class list with a grid stride (the list's length is only known on the device).  Every entry
+// becomes one key (column << pos_bits) | position-in-window, so the sorted keys carry the edge each
+// column came from: no lookup by binary search afterwards, the rank is scattered straight to
+// edge_to_col.  Thread t holds the KPT network slots t * KPT .. t * KPT + KPT - 1 in registers.  A
+// compare-exchange at distance j stays inside a thread for j < KPT, is a lane exchange inside the
+// wavefront for j < 64 * KPT, and only goes through LDS (one round trip) beyond that -- three of the 55
+// stages of a 1024-entry window.  K is uint32_t when column and position fit 31 bits, uint64_t otherwise.
+template <typename K>
+__device__ __forceinline__ K lane_xor(K v, int mask)
 {
-    __shared__ int32_t s_key[CAP];
-    __shared__ int32_t s_rank[CAP];
-    __shared__ int s_tmp[(THREADS + kWave - 1) / kWave + 1];
+    if constexpr (sizeof(K) == 4) {
+        return (K)__shfl_xor((int)v, mask, kWave);
+    } else {
+        const int lo = __shfl_xor((int)(uint32_t)v, mask, kWave);
+        const int hi = __shfl_xor((int)(uint32_t)(v >> 32), mask, kWave);
+        return ((K)(uint32_t)hi << 32) | (uint32_t)lo;
+    }
+}
 
-    const int64_t w = win_list[blockIdx.x];
-    int32_t lo, hi;
-    window_edge_range(rp, n_rows, win_h, w, &lo, &hi);
-    const int cnt = hi - lo;          // 1 <= cnt <= CAP by classification
-    int n_pad = 2;
-    while (n_pad < cnt) n_pad <<= 1;
+template <typename K>
+__device__ __forceinline__ K lane_up1(K v)
+{
+    if constexpr (sizeof(K) == 4) {
+        return (K)__shfl_up((int)v, 1, kWave);
+    } else {
+        const int lo = __shfl_up((int)(uint32_t)v, 1, kWave);
+        const int hi = __shfl_up((int)(uint32_t)(v >> 32), 1, kWave);
+        return ((K)(uint32_t)hi << 32) | (uint32_t)lo;
+    }
+}
 
-    for (int i = threadIdx.x; i < n_pad; i += THREADS) s_key[i] = i < cnt ? ci[lo + i] : INT_MAX;
-    __syncthreads();
+template <int THREADS, int KPT, typename K>
+__global__ __launch_bounds__(THREADS) void sgt_window_sort_kernel(
+    int32_t n_rows, int32_t win_h, const int32_t *__restrict__ win_list, const int32_t *__restrict__ list_len,
+    const int32_t *__restrict__ rp, const int32_t *__restrict__ ci, int pos_bits,
+    int32_t *__restrict__ edge_to_col, int32_t *__restrict__ col_to_row, int32_t *__restrict__ win_unique)
+{
+    constexpr int N = THREADS * KPT;
+    constexpr int WAVES = THREADS / kWave;
+    __shared__ K s_x[WAVES > 1 ? N : 1];
+    __shared__ K s_last[WAVES];
+    __shared__ int s_tmp[WAVES + 1];
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
+    const int32_t n_items = *list_len;
+    const K pos_mask = ((K)1 << pos_bits) - 1;
 
-    // Bitonic sorting network, ascending.
-    for (int k = 2; k <= n_pad; k <<= 1) {
-        for (int j = k >> 1; j > 0; j >>= 1) {
-            for (int t = threadIdx.x; t < (n_pad >> 1); t += THREADS) {
-                int a = ((t & ~(j - 1)) << 1) | (t & (j - 1));
-                int b = a | j;
-                int32_t ka = s_key[a], kb = s_key[b];
-                bool up = (a & k) == 0;
-                if ((ka > kb) == up) {
-                    s_key[a] = kb;
-                    s_key[b] = ka;
+    for (int64_t item = blockIdx.x; item < n_items; item += gridDim.x) {
+        const int64_t w = win_list[item];
+        int32_t lo, hi;
+        window_edge_range(rp, n_rows, win_h, w, &lo, &hi);
+        const int cnt = hi - lo;          // 1 <= cnt <= N by classification
+
+        // Coalesced loads: entry r * THREADS + t goes to slot t * KPT + r (any assignment will do, the
+        // key remembers where the entry came from); empty slots get the largest key and sort last.
+        K key[KPT];
+#pragma unroll
+        for (int r = 0; r < KPT; ++r) {
+            const int e = r * THREADS + tid;
+            key[r] = e < cnt ? (((K)(uint32_t)ci[lo + e] << pos_bits) | (K)e) : ~(K)0;
+        }
+
+#pragma unroll
+        for (int k = 2; k <= N; k <<= 1) {
+#pragma unroll
+            for (int j = k >> 1; j > 0; j >>= 1) {
+                if (j < KPT) {
+#pragma unroll
+                    for (int a = 0; a < KPT; ++a) {
+                        if (a & j) continue;
+                        const int b = a | j;
+                        const bool asc = ((tid * KPT + a) & k) == 0;
+                        const K x = key[a], y = key[b];
+                        const bool sw = (x > y) == asc;
+                        key[a] = sw ? y : x;
+                        key[b] = sw ? x : y;
+                    }
+                } else if (j < KPT * kWave) {
+                    const int lm = j / KPT;
+                    const bool lower = (lane & lm) == 0;
+#pragma unroll
+                    for (int r = 0; r < KPT; ++r) {
+                        const K other = lane_xor(key[r], lm);
+                        const bool asc = ((tid * KPT + r) & k) == 0;
+                        const K mn = key[r] < other ? key[r] : other;
+                        const K mx = key[r] < other ? other : key[r];
+                        key[r] = (lower == asc) ? mn : mx;
+                    }
+                } else {
+                    const int pt = tid ^ (j / KPT);
+                    const bool lower = (tid & (j / KPT)) == 0;
+#pragma unroll
+                    for (int r = 0; r < KPT; ++r) s_x[r * THREADS + tid] = key[r];
+                    __syncthreads();
+#pragma unroll
+                    for (int r = 0; r < KPT; ++r) {
+                        const K other = s_x[r * THREADS + pt];
+                        const bool asc = ((tid * KPT + r) & k) == 0;
+                        const K mn = key[r] < other ? key[r] : other;
+                        const K mx = key[r] < other ? other : key[r];
+                        key[r] = (lower == asc) ? mn : mx;
+                    }
+                    __syncthreads();
                 }
             }
-            __syncthreads();
         }
-    }
 
-    // Head flags of the sorted run and their prefix count: rank of position i = #heads in [0, i] - 1.
-    const int ipt = n_pad >= THREADS ? n_pad / THREADS : 1;
-    const int i0 = threadIdx.x * ipt;
-    int local = 0;
-    for (int k = 0; k < ipt; ++k) {
-        int i = i0 + k;
-        if (i < cnt && (i == 0 || s_key[i] != s_key[i - 1])) ++local;
-    }
-    int total;
-    int run = block_exclusive_scan(local, s_tmp, &total);
-    for (int k = 0; k < ipt; ++k) {
-        int i = i0 + k;
-        if (i < cnt) {
-            bool head = (i == 0 || s_key[i] != s_key[i - 1]);
-            if (head) {
-                tmp_clean[lo + run] = s_key[i];
+        // Slot i now holds the i-th smallest key; slots cnt .. N-1 hold the filler.  A slot is the head
+        // of a run of equal columns when the slot before it has another column.
+        K prev = lane_up1(key[KPT - 1]);
+        if (WAVES > 1) {
+            if (lane == kWave - 1) s_last[wave] = key[KPT - 1];
+            __syncthreads();
+            if (lane == 0 && wave > 0) prev = s_last[wave - 1];
+        }
+        bool head[KPT];
+        int local = 0;
+#pragma unroll
+        for (int r = 0; r < KPT; ++r) {
+            const int i = tid * KPT + r;
+            const K before = r == 0 ? prev : key[r - 1];
+            head[r] = i < cnt && (i == 0 || (key[r] >> pos_bits) != (before >> pos_bits));
+            local += head[r] ? 1 : 0;
+        }
+        int run, total;
+        if (WAVES > 1) {
+            run = block_exclusive_scan(local, s_tmp, &total);
+        } else {
+            const int incl = wave_inclusive_scan(local);
+            run = incl - local;
+            total = __shfl(incl, kWave - 1, kWave);
+        }
+#pragma unroll
+        for (int r = 0; r < KPT; ++r) {
+            const int i = tid * KPT + r;
+            if (head[r]) {
+                col_to_row[lo + run] = (int32_t)(key[r] >> pos_bits);
                 ++run;
             }
-            s_rank[i] = run - 1;
+            if (i < cnt) edge_to_col[lo + (int32_t)(key[r] & pos_mask)] = run - 1;
         }
-    }
-    if (threadIdx.x == 0) win_unique[w] = total;
-    __syncthreads();
-
-    // Every edge looks its column up in the sorted run (first position not below it).
-    for (int e = threadIdx.x; e < cnt; e += THREADS) {
-        int32_t c = ci[lo + e];
-        int l = 0, h = cnt;
-        while (l < h) {
-            int mid = (l + h) >> 1;
-            if (s_key[mid] < c) l = mid + 1; else h = mid;
-        }
-        edge_to_col[lo + e] = s_rank[l];
+        if (tid == 0) win_unique[w] = total;
     }
 }
 
@@ -369,13 +521,19 @@ __global__ __launch_bounds__(kBitmapThreads) void sgt_window_bitmap_kernel(
     }
 }
 
-// Large class when the column space fits: the same bitmap, but in LDS (gfx950 gives a workgroup up to
-// 160 KB): one bit per column plus the running count in front of every group of kPfGroup words.
-// Setting the bits and looking the ranks up are LDS operations instead of L2 atomics and gathers, and
-// no device scratch has to be cleared.  Needs lds_bitmap_bytes(n_words) <= kLdsBitmapMax.
+// Bitmap class when the column space fits in LDS (gfx950 gives a workgroup up to 160 KB): one bit per
+// column plus the running count in front of every group of kPfGroup words.  Setting the bits and looking
+// the ranks up are LDS operations instead of L2 atomics and gathers, and no device scratch has to be
+// cleared.  Needs lds_bitmap_bytes(n_words) <= kLdsBitmapMax.  One workgroup fills a compute unit's LDS, so
+// the kernel is launched with one workgroup per compute unit and the workgroups draw windows from a
+// counter until the class list is used up (hub windows differ in size by two orders of magnitude; the
+// counter keeps everybody busy).  The edge loops keep kEdgeUnroll column loads per thread in flight: a
+// hub window of a power-law graph has 10^5 entries, and one load per thread and round trip would make it
+// the critical path of the whole translation.
 constexpr int kPfGroup = 8;
-constexpr int kLdsBitmapFrom = 1024;
+constexpr int kLdsBitmapFrom = kSortCap;
 constexpr size_t kLdsBitmapMax = 160 * 1024 - 256;
+constexpr int kLdsEdgeUnroll = 16;
 inline size_t lds_bitmap_bytes(int64_t n_words)
 {
     return (size_t)(n_words + (n_words + kPfGroup - 1) / kPfGroup + 1) * 4;
@@ -383,321 +541,318 @@ inline size_t lds_bitmap_bytes(int64_t n_words)
 
 __global__ __launch_bounds__(kBitmapThreads) void sgt_window_lds_bitmap_kernel(
     int32_t n_rows, int32_t win_h, int32_t n_words, const int32_t *__restrict__ large_list,
-    const int32_t *__restrict__ rp, const int32_t *__restrict__ ci, int32_t *__restrict__ edge_to_col,
-    int32_t *__restrict__ tmp_clean, int32_t *__restrict__ win_unique)
+    const int32_t *__restrict__ list_len, int32_t *ticket, const int32_t *__restrict__ rp,
+    const int32_t *__restrict__ ci, int32_t *__restrict__ edge_to_col, int32_t *__restrict__ col_to_row,
+    int32_t *__restrict__ win_unique)
 {
     extern __shared__ uint32_t s_words[];          // bitmap, then the group prefixes
     __shared__ int s_tmp[kBitmapWaves + 1];
+    __shared__ int s_item;
     uint32_t *bm = s_words;
     int32_t *gpf = reinterpret_cast<int32_t *>(s_words + n_words);
-    const int64_t w = large_list[blockIdx.x];
-    int32_t lo, hi;
-    window_edge_range(rp, n_rows, win_h, w, &lo, &hi);
+    const int32_t n_items = *list_len;
+    constexpr int64_t kStep = (int64_t)kBitmapThreads * kLdsEdgeUnroll;
 
-    // The first batch of columns is requested before the bitmap is cleared (its latency hides under the
-    // clearing) and kept for step 4: windows of up to kBitmapThreads * kEdgeUnroll entries read their
-    // columns once.
-    uint32_t c_first[kEdgeUnroll];
-#pragma unroll
-    for (int u = 0; u < kEdgeUnroll; ++u) {
-        const int64_t e = (int64_t)lo + threadIdx.x + (int64_t)u * kBitmapThreads;
-        c_first[u] = e < hi ? (uint32_t)ci[e] : 0xFFFFFFFFu;
-    }
-    for (int32_t k = threadIdx.x; k < n_words; k += kBitmapThreads) bm[k] = 0u;
-    __syncthreads();
+    for (;;) {
+        if (threadIdx.x == 0) s_item = atomicAdd(ticket, 1);
+        __syncthreads();
+        const int32_t item = s_item;
+        if (item >= n_items) break;                // the same value in every thread: all leave together
+        const int64_t w = large_list[item];
+        int32_t lo, hi;
+        window_edge_range(rp, n_rows, win_h, w, &lo, &hi);
 
-    // 1. one bit per edge
+        // The first batch of columns is requested before the bitmap is cleared (its latency hides under
+        // the clearing) and kept for step 4: windows of up to kStep entries read their columns once.
+        uint32_t c_first[kLdsEdgeUnroll];
 #pragma unroll
-    for (int u = 0; u < kEdgeUnroll; ++u)
-        if (c_first[u] != 0xFFFFFFFFu) atomicOr(&bm[c_first[u] >> 5], 1u << (c_first[u] & 31));
-    for (int64_t e0 = (int64_t)lo + (int64_t)kBitmapThreads * kEdgeUnroll + threadIdx.x; e0 < hi;
-         e0 += (int64_t)kBitmapThreads * kEdgeUnroll) {
-        uint32_t c[kEdgeUnroll];
-#pragma unroll
-        for (int u = 0; u < kEdgeUnroll; ++u) {
-            int64_t e = e0 + (int64_t)u * kBitmapThreads;
-            c[u] = e < hi ? (uint32_t)ci[e] : 0xFFFFFFFFu;
+        for (int u = 0; u < kLdsEdgeUnroll; ++u) {
+            const int64_t e = (int64_t)lo + threadIdx.x + (int64_t)u * kBitmapThreads;
+            c_first[u] = e < hi ? (uint32_t)ci[e] : 0xFFFFFFFFu;
         }
+        for (int32_t k = threadIdx.x; k < n_words; k += kBitmapThreads) bm[k] = 0u;
+        __syncthreads();
+
+        // 1. one bit per edge
 #pragma unroll
-        for (int u = 0; u < kEdgeUnroll; ++u)
-            if (c[u] != 0xFFFFFFFFu) atomicOr(&bm[c[u] >> 5], 1u << (c[u] & 31));
-    }
-    __syncthreads();
-
-    // 2. every thread owns a contiguous run of R words (R odd: the lanes of a wavefront then read
-    //    different banks) and counts its bits; one workgroup-wide scan gives the count in front of
-    //    every run.  (A scan per 64 words instead costs a chain of cross-lane steps per row.)
-    const int32_t R = ((n_words + kBitmapThreads - 1) / kBitmapThreads) | 1;
-    const int32_t kb = min((int32_t)threadIdx.x * R, n_words), ke = min(kb + R, n_words);
-    int cnt = 0;
-    for (int32_t k = kb; k < ke; ++k) cnt += __popc(bm[k]);
-    int total;
-    int pos = block_exclusive_scan(cnt, s_tmp, &total);
-
-    // 3. the count in front of every group of words, and the unique list (bit positions ascending)
-    for (int32_t k = kb; k < ke; ++k) {
-        uint32_t bits = bm[k];
-        if ((k % kPfGroup) == 0) gpf[k / kPfGroup] = pos;
-        while (bits) {
-            const int b = __ffs(bits) - 1;
-            bits &= bits - 1;
-            tmp_clean[lo + pos] = k * 32 + b;
-            ++pos;
+        for (int u = 0; u < kLdsEdgeUnroll; ++u)
+            if (c_first[u] != 0xFFFFFFFFu) atomicOr(&bm[c_first[u] >> 5], 1u << (c_first[u] & 31));
+        for (int64_t e0 = (int64_t)lo + kStep + threadIdx.x; e0 < hi; e0 += kStep) {
+            uint32_t c[kLdsEdgeUnroll];
+#pragma unroll
+            for (int u = 0; u < kLdsEdgeUnroll; ++u) {
+                const int64_t e = e0 + (int64_t)u * kBitmapThreads;
+                c[u] = e < hi ? (uint32_t)ci[e] : 0xFFFFFFFFu;
+            }
+#pragma unroll
+            for (int u = 0; u < kLdsEdgeUnroll; ++u)
+                if (c[u] != 0xFFFFFFFFu) atomicOr(&bm[c[u] >> 5], 1u << (c[u] & 31));
         }
-    }
-    if (threadIdx.x == 0) win_unique[w] = total;
-    __syncthreads();
+        __syncthreads();
 
-    // 4. rank of every edge's column: group prefix + the words of the group in front of it + the bits below
-    auto rank_of = [&](uint32_t c) {
-        const int32_t wi = (int32_t)(c >> 5);
-        const int32_t g0 = wi / kPfGroup * kPfGroup;
-        int r = gpf[wi / kPfGroup] + __popc(bm[wi] & ((1u << (c & 31)) - 1u));
-#pragma unroll
-        for (int j = 0; j < kPfGroup - 1; ++j)
-            if (g0 + j < wi) r += __popc(bm[g0 + j]);
-        return r;
-    };
-#pragma unroll
-    for (int u = 0; u < kEdgeUnroll; ++u)
-        if (c_first[u] != 0xFFFFFFFFu)
-            edge_to_col[(int64_t)lo + threadIdx.x + (int64_t)u * kBitmapThreads] = rank_of(c_first[u]);
-    for (int64_t e0 = (int64_t)lo + (int64_t)kBitmapThreads * kEdgeUnroll + threadIdx.x; e0 < hi;
-         e0 += (int64_t)kBitmapThreads * kEdgeUnroll) {
-        uint32_t c[kEdgeUnroll];
-#pragma unroll
-        for (int u = 0; u < kEdgeUnroll; ++u) {
-            int64_t e = e0 + (int64_t)u * kBitmapThreads;
-            c[u] = e < hi ? (uint32_t)ci[e] : 0u;
+        // 2. every thread owns a contiguous run of R words (R odd: the lanes of a wavefront then read
+        //    different banks) and counts its bits; one workgroup-wide scan gives the count in front of
+        //    every run.  (A scan per 64 words instead costs a chain of cross-lane steps per row.)
+        const int32_t R = ((n_words + kBitmapThreads - 1) / kBitmapThreads) | 1;
+        const int32_t kb = min((int32_t)threadIdx.x * R, n_words), ke = min(kb + R, n_words);
+        int cnt = 0;
+        for (int32_t k = kb; k < ke; ++k) cnt += __popc(bm[k]);
+        int total;
+        int pos = block_exclusive_scan(cnt, s_tmp, &total);
+
+        // 3. the count in front of every group of words, and the unique list (bit positions ascending)
+        for (int32_t k = kb; k < ke; ++k) {
+            uint32_t bits = bm[k];
+            if ((k % kPfGroup) == 0) gpf[k / kPfGroup] = pos;
+            while (bits) {
+                const int b = __ffs(bits) - 1;
+                bits &= bits - 1;
+                col_to_row[lo + pos] = k * 32 + b;
+                ++pos;
+            }
         }
+        if (threadIdx.x == 0) win_unique[w] = total;
+        __syncthreads();
+
+        // 4. rank of every edge's column: group prefix + the words of the group in front of it + the bits below
+        auto rank_of = [&](uint32_t c) {
+            const int32_t wi = (int32_t)(c >> 5);
+            const int32_t g0 = wi / kPfGroup * kPfGroup;
+            int r = gpf[wi / kPfGroup] + __popc(bm[wi] & ((1u << (c & 31)) - 1u));
 #pragma unroll
-        for (int u = 0; u < kEdgeUnroll; ++u) {
-            int64_t e = e0 + (int64_t)u * kBitmapThreads;
-            if (e < hi) edge_to_col[e] = rank_of(c[u]);
+            for (int j = 0; j < kPfGroup - 1; ++j)
+                if (g0 + j < wi) r += __popc(bm[g0 + j]);
+            return r;
+        };
+#pragma unroll
+        for (int u = 0; u < kLdsEdgeUnroll; ++u)
+            if (c_first[u] != 0xFFFFFFFFu)
+                edge_to_col[(int64_t)lo + threadIdx.x + (int64_t)u * kBitmapThreads] = rank_of(c_first[u]);
+        for (int64_t e0 = (int64_t)lo + kStep + threadIdx.x; e0 < hi; e0 += kStep) {
+            uint32_t c[kLdsEdgeUnroll];
+#pragma unroll
+            for (int u = 0; u < kLdsEdgeUnroll; ++u) {
+                const int64_t e = e0 + (int64_t)u * kBitmapThreads;
+                c[u] = e < hi ? (uint32_t)ci[e] : 0xFFFFFFFFu;
+            }
+#pragma unroll
+            for (int u = 0; u < kLdsEdgeUnroll; ++u) {
+                const int64_t e = e0 + (int64_t)u * kBitmapThreads;
+                if (c[u] != 0xFFFFFFFFu) edge_to_col[e] = rank_of(c[u]);
+            }
+        }
+        __syncthreads();                           // the bitmap and s_item are reused by the next window
+    }
+}
+
+// ---- gather plan, step 2: offsets -----------------------------------------------------------------
+// One workgroup turns the per-block counts into offsets, decides (from U, now known) whether the
+// single-segment rows are ordered by length, and writes the plan sizes and the die table.
+// Order of the finished segment list: first the segments of split rows (n_slots of them, sorted by
+// start column in a later step, cut into 2 * kXcds bands of equal length), then the single-segment rows:
+// by length class and row when the windows share few neighbours (4 U > 3 nnz), else by row alone, which
+// keeps the rows of a window next to each other (that matters when they share neighbours).
+template <typename Load, typename Store>
+__device__ __forceinline__ int block_scan_sequence(int64_t n, Load load, Store store, int *tmp)
+{
+    int carry = 0;
+    for (int64_t base = 0; base < n; base += (int64_t)blockDim.x * 4) {
+        const int64_t i0 = base + (int64_t)threadIdx.x * 4;
+        int v[4];
+        int sum = 0;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            v[k] = (i0 + k < n) ? load(i0 + k) : 0;
+            sum += v[k];
+        }
+        int total;
+        int run = carry + block_exclusive_scan(sum, tmp, &total);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            if (i0 + k < n) store(i0 + k, run);
+            run += v[k];
+        }
+        carry += total;
+    }
+    return carry;
+}
+
+constexpr int kBands = 2 * kXcds;
+
+__global__ __launch_bounds__(1024) void plan_scan_kernel(int64_t nb, const int32_t *__restrict__ block_sums,
+                                                         int64_t nnz, int64_t n_win,
+                                                         const int32_t *__restrict__ win_unique_ptr,
+                                                         int32_t *__restrict__ long_off, int32_t *__restrict__ slot_off,
+                                                         int32_t *__restrict__ tail_off, BuildInfo *info,
+                                                         int32_t *__restrict__ long_slot_ptr)
+{
+    __shared__ int tmp[1024 / kWave + 1];
+    const int64_t U = win_unique_ptr[n_win];
+    const int sort_tail = 4 * U > 3 * (nnz > 0 ? nnz : 1) ? 1 : 0;
+    const int n_long = block_scan_sequence(nb, [&](int64_t i) { return block_sums[i]; },
+                                           [&](int64_t i, int v) { long_off[i] = v; }, tmp);
+    const int n_slots = block_scan_sequence(nb, [&](int64_t i) { return block_sums[nb + i]; },
+                                            [&](int64_t i, int v) { slot_off[i] = v; }, tmp);
+    int n_single;
+    if (sort_tail) {
+        // class-major: all blocks of class 0, then all blocks of class 1, ...
+        n_single = block_scan_sequence((int64_t)kTailClasses * nb, [&](int64_t i) { return block_sums[2 * nb + i]; },
+                                       [&](int64_t i, int v) { tail_off[i] = v; }, tmp);
+    } else {
+        n_single = block_scan_sequence(nb,
+                                       [&](int64_t i) {
+                                           int t = 0;
+#pragma unroll
+                                           for (int c = 0; c < kTailClasses; ++c) t += block_sums[(2 + c) * nb + i];
+                                           return t;
+                                       },
+                                       [&](int64_t i, int v) { tail_off[i] = v; }, tmp);
+    }
+    if (threadIdx.x == 0) {
+        info->n_seg = n_slots + n_single;
+        info->n_long = n_long;
+        info->n_slots = n_slots;
+        info->sort_tail = sort_tail;
+        info->total_unique = (int32_t)U;
+        long_slot_ptr[n_long] = n_slots;
+        // Die l walks bands l and 2 * kXcds - 1 - l of the split rows' segments (sorted by start column, so
+        // a band is a range of columns: its X rows stay in that die's L2, and pairing a band of popular
+        // columns with a band of rare ones spreads the L2 misses evenly), then its share of the tail.
+        for (int l = 0; l < kXcds; ++l) {
+            const int b2 = kBands - 1 - l;
+            int32_t *t = info->lane_tab + kLaneTabStride * l;
+            t[0] = (int32_t)((int64_t)n_slots * l / kBands);
+            t[1] = (int32_t)((int64_t)n_slots * (l + 1) / kBands) - t[0];
+            t[2] = (int32_t)((int64_t)n_slots * b2 / kBands);
+            t[3] = (int32_t)((int64_t)n_slots * (b2 + 1) / kBands) - t[2];
+            t[4] = n_slots;
+            t[5] = n_single;
         }
     }
 }
 
-// Packs the per-window lists into col_to_row.  One wavefront per window; windows of the large
-// class are copied by sgt_pack_large_kernel with many workgroups each.
-__global__ __launch_bounds__(kWave) void sgt_pack_kernel(int32_t n_rows, int32_t win_h,
-                                                         const int32_t *__restrict__ rp,
-                                                         const int32_t *__restrict__ tmp_clean,
-                                                         const int32_t *__restrict__ win_unique_ptr,
-                                                         int32_t *__restrict__ col_to_row, int32_t medium_cap)
+// ---- gather plan, step 3: the segment list -----------------------------------------------------------
+// Single-segment rows go straight to their final place (stable inside a length class: block offset + the
+// rows of the same class in front of this one inside the block, counted with wavefront ballots).  Split
+// rows get their entry in long_row / long_slot_ptr; their segments ("slots", numbered in row order) are
+// written with the start column as sort key by all threads of the workgroup together -- a hub row has
+// hundreds of segments.
+constexpr int kSegSortBits = 12;       // the leading bits of a start column are the sort key
+
+__global__ __launch_bounds__(256) void seg_fill_kernel(
+    int32_t n_rows, const int32_t *__restrict__ rp, const int32_t *__restrict__ ci, const BuildInfo *info,
+    int64_t nb, const int32_t *__restrict__ long_off, const int32_t *__restrict__ slot_off,
+    const int32_t *__restrict__ tail_off, int key_shift, int32_t *__restrict__ seg_row,
+    int32_t *__restrict__ seg_ebeg, int32_t *__restrict__ seg_dst, int32_t *__restrict__ long_row,
+    int32_t *__restrict__ long_slot_ptr, int32_t *__restrict__ slot_row, int32_t *__restrict__ slot_ebeg,
+    int32_t *__restrict__ slot_key)
+{
+    __shared__ int s_tmp[256 / kWave + 1];
+    __shared__ int s_wave_cnt[256 / kWave][kTailClasses];
+    __shared__ int s_tail_base[kTailClasses];      // final position of the block's next row of each class
+    __shared__ int32_t s_lrow[256], s_le0[256], s_lslot[257];
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
+    const int sort_tail = info->sort_tail;
+    const int32_t n_slots = info->n_slots;
+    if (threadIdx.x < kTailClasses)
+        s_tail_base[threadIdx.x] = n_slots + (sort_tail ? tail_off[(int64_t)threadIdx.x * nb + blockIdx.x]
+                                                        : tail_off[blockIdx.x]);
+    int32_t long_base = long_off[blockIdx.x], slot_base = slot_off[blockIdx.x];
+    __syncthreads();
+
+    for (int round = 0; round < kRowBlock / 256; ++round) {
+        const int64_t r = (int64_t)blockIdx.x * kRowBlock + round * 256 + threadIdx.x;
+        int32_t e0 = 0, deg = 0;
+        if (r < n_rows) {
+            e0 = rp[r];
+            deg = rp[r + 1] - e0;
+        }
+        const bool is_long = deg > kSegLen;
+        const int segs = is_long ? (deg + kSegLen - 1) / kSegLen : 0;
+        int n_lrows, n_lsegs;
+        const int lrank = block_exclusive_scan(is_long ? 1 : 0, s_tmp, &n_lrows);
+        const int srank = block_exclusive_scan(segs, s_tmp, &n_lsegs);
+        if (is_long) {
+            long_row[long_base + lrank] = (int32_t)r;
+            long_slot_ptr[long_base + lrank] = slot_base + srank;
+            s_lrow[lrank] = (int32_t)r;
+            s_le0[lrank] = e0;
+            s_lslot[lrank] = srank;
+        }
+        if (threadIdx.x == 0) s_lslot[n_lrows] = n_lsegs;
+
+        const int cls = (r < n_rows && !is_long) ? (sort_tail ? length_class(deg) : 0) : -1;
+        int rank_in_wave = 0;
+#pragma unroll
+        for (int c = 0; c < kTailClasses; ++c) {
+            const unsigned long long mask = __ballot(cls == c);
+            if (lane == 0) s_wave_cnt[wave][c] = __popcll(mask);
+            if (cls == c) rank_in_wave = __popcll(mask & ((1ull << lane) - 1ull));
+        }
+        __syncthreads();
+        if (cls >= 0) {
+            int32_t p = s_tail_base[cls] + rank_in_wave;
+            for (int w2 = 0; w2 < wave; ++w2) p += s_wave_cnt[w2][cls];
+            seg_row[p] = (int32_t)r;
+            seg_ebeg[p] = e0;
+            seg_dst[p] = -1;
+        }
+        // the slots of this round's split rows, one per thread and step
+        for (int32_t sl = threadIdx.x; sl < n_lsegs; sl += 256) {
+            int a = 0, b = n_lrows;                    // last split row whose first slot is <= sl
+            while (b - a > 1) {
+                const int mid = (a + b) >> 1;
+                if (s_lslot[mid] <= sl) a = mid; else b = mid;
+            }
+            const int32_t eb = s_le0[a] + (sl - s_lslot[a]) * kSegLen;
+            const int32_t g = slot_base + sl;
+            slot_row[g] = s_lrow[a];
+            slot_ebeg[g] = eb;
+            slot_key[g] = ci[eb] >> key_shift;
+        }
+        __syncthreads();
+        if (threadIdx.x < kTailClasses) {
+            int t = 0;
+#pragma unroll
+            for (int w2 = 0; w2 < 256 / kWave; ++w2) t += s_wave_cnt[w2][threadIdx.x];
+            s_tail_base[threadIdx.x] += t;
+        }
+        long_base += n_lrows;
+        slot_base += n_lsegs;
+        __syncthreads();
+    }
+}
+
+// Split rows' segments in their final order: position i of the list takes slot order[i] (order == nullptr:
+// slot order).  seg_dst is the slot number, which is also where the segment's partial sum goes.
+__global__ void seg_permute_kernel(const BuildInfo *info, const int32_t *__restrict__ order,
+                                   const int32_t *__restrict__ slot_row, const int32_t *__restrict__ slot_ebeg,
+                                   int32_t *__restrict__ seg_row, int32_t *__restrict__ seg_ebeg,
+                                   int32_t *__restrict__ seg_dst)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= info->n_slots) return;
+    const int32_t k = order ? order[i] : (int32_t)i;
+    seg_row[i] = slot_row[k];
+    seg_ebeg[i] = slot_ebeg[k];
+    seg_dst[i] = k;
+}
+
+// The per-window lists are kept where the translation wrote them, each at its window's edge offset (a
+// window never has more distinct columns than entries).  The exported col_to_row is the same lists back to
+// back: one workgroup per window copies its list to win_unique_ptr[w].
+__global__ __launch_bounds__(256) void pack_unique_kernel(int32_t n_rows, int32_t win_h,
+                                                          const int32_t *__restrict__ rp,
+                                                          const int32_t *__restrict__ loose,
+                                                          const int32_t *__restrict__ win_unique_ptr,
+                                                          int32_t *__restrict__ packed)
 {
     const int64_t w = blockIdx.x;
     int32_t lo, hi;
     window_edge_range(rp, n_rows, win_h, w, &lo, &hi);
     const int32_t u0 = win_unique_ptr[w];
     const int32_t uw = win_unique_ptr[w + 1] - u0;
-    if (hi - lo <= medium_cap)
-        for (int k = threadIdx.x; k < uw; k += kWave) col_to_row[u0 + k] = tmp_clean[lo + k];
-}
-
-constexpr int kPackSplit = 16;   // workgroups per large window
-
-__global__ __launch_bounds__(256) void sgt_pack_large_kernel(int32_t n_rows, int32_t win_h,
-                                                             const int32_t *__restrict__ large_list,
-                                                             const int32_t *__restrict__ rp,
-                                                             const int32_t *__restrict__ tmp_clean,
-                                                             const int32_t *__restrict__ win_unique_ptr,
-                                                             int32_t *__restrict__ col_to_row)
-{
-    const int64_t w = large_list[blockIdx.x];
-    int32_t lo, hi;
-    window_edge_range(rp, n_rows, win_h, w, &lo, &hi);
-    const int32_t u0 = win_unique_ptr[w];
-    const int32_t uw = win_unique_ptr[w + 1] - u0;
-    const int32_t chunk = (uw + kPackSplit - 1) / kPackSplit;
-    const int32_t k0 = blockIdx.y * chunk;
-    const int32_t k1 = min(k0 + chunk, uw);
-    for (int32_t k = k0 + threadIdx.x; k < k1; k += 256) col_to_row[u0 + k] = tmp_clean[lo + k];
-}
-
-// ---- gather plan ------------------------------------------------------------------------------
-
-__global__ void seg_count_kernel(int32_t n_rows, const int32_t *rp, int32_t *seg_cnt, int32_t *long_flag,
-                                 int32_t *slot_cnt)
-{
-    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= n_rows) return;
-    int32_t deg = rp[i + 1] - rp[i];
-    int32_t segs = deg <= kSegLen ? 1 : (deg + kSegLen - 1) / kSegLen;
-    seg_cnt[i] = segs;
-    long_flag[i] = segs > 1;
-    slot_cnt[i] = segs > 1 ? segs : 0;
-}
-
-__global__ void seg_fill_kernel(int32_t n_rows, const int32_t *rp, const int32_t *seg_off,
-                                const int32_t *long_off, const int32_t *slot_off, int32_t *seg_row,
-                                int32_t *seg_ebeg, int32_t *seg_dst, int32_t *long_row,
-                                int32_t *long_slot_ptr, int64_t n_long)
-{
-    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= n_rows) return;
-    int32_t s0 = seg_off[i], segs = seg_off[i + 1] - s0;
-    int32_t e0 = rp[i];
-    bool is_long = segs > 1;
-    int32_t slot0 = slot_off[i];
-    for (int32_t k = 0; k < segs; ++k) {
-        seg_row[s0 + k] = (int32_t)i;
-        seg_ebeg[s0 + k] = e0 + k * kSegLen;
-        seg_dst[s0 + k] = is_long ? slot0 + k : -1;
-    }
-    if (is_long) {
-        int32_t li = long_off[i];
-        long_row[li] = (int32_t)i;
-        long_slot_ptr[li] = slot0;
-        if (li == n_long - 1) long_slot_ptr[n_long] = slot0 + segs;
-    }
-}
-
-// ---- column bands: XCD-aware ordering of the segment list ---------------------------------------
-// Each accelerator die has its own L2.  Segments of split (long) rows cover a narrow range of the
-// row's columns, so sending all segments whose columns fall in the same band to the same die makes
-// that die's L2 hold only its bands' X rows: the hot rows are cached once per chip instead of once per
-// die.  The 2 * kXcds bands are chosen from a histogram of the split rows' segment start columns so
-// that every band gets about the same number of segments; die l takes bands l and 2 * kXcds - 1 - l,
-// which pairs a band of frequently used columns with a band of rarely used ones (on skewed graphs the
-// popular columns are a narrow id range), so that the L2 misses -- and with them the traffic on each
-// die's link to memory -- are spread evenly over the dies.  Single-segment rows are not banded; runs of
-// them are dealt out to the dies round-robin.  Any grouping is correct: the order of the segment
-// list only changes where a segment runs.
-constexpr int kBands = 2 * kXcds;
-constexpr int kHistBins = 8192;    // 32 KB of LDS per workgroup in band_hist_kernel
-
-__device__ __forceinline__ int column_bin(int32_t c, int32_t n_cols)
-{
-    return (int)(((int64_t)c * kHistBins) / (n_cols > 0 ? n_cols : 1));
-}
-
-// Histogram of the split rows' segment start columns.  Start columns of hub rows pile up in a few
-// bins, so every workgroup first counts in LDS and then adds its non-zero bins to the global array.
-__global__ __launch_bounds__(256) void band_hist_kernel(int64_t n_seg, const int32_t *seg_dst,
-                                                        const int32_t *seg_ebeg, const int32_t *ci,
-                                                        int32_t n_cols, int32_t *hist)
-{
-    __shared__ int32_t s_hist[kHistBins];
-    for (int b = threadIdx.x; b < kHistBins; b += blockDim.x) s_hist[b] = 0;
-    __syncthreads();
-    for (int64_t sgi = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; sgi < n_seg;
-         sgi += (int64_t)gridDim.x * blockDim.x)
-        if (seg_dst[sgi] >= 0) atomicAdd(&s_hist[column_bin(ci[seg_ebeg[sgi]], n_cols)], 1);
-    __syncthreads();
-    for (int b = threadIdx.x; b < kHistBins; b += blockDim.x)
-        if (s_hist[b]) atomicAdd(&hist[b], s_hist[b]);
-}
-
-// Category of a segment in the final order: 0 .. kBands-1 = column band of a split row's segment;
-// kBands + c = single-segment row of length class c.  With sort_tail the classes follow the number of
-// gather iterations a row needs (longest first), so that the lane groups of a wavefront get rows of
-// similar length; without it every single-segment row is class 0 and the tail stays in row order,
-// which keeps the rows of a window next to each other (that matters when they share neighbours).
-constexpr int kTailClasses = 8;
-constexpr int kCats = kBands + kTailClasses;
-constexpr int kPartThreads = 256;
-
-__device__ __forceinline__ int segment_category(int64_t sgi, const int32_t *seg_row, const int32_t *seg_dst,
-                                                const int32_t *seg_ebeg, const int32_t *rp, const int32_t *ci,
-                                                int32_t n_cols, const int32_t *hist_excl, int sort_tail)
-{
-    if (seg_dst[sgi] >= 0) {
-        const int64_t total = hist_excl[kHistBins];
-        const int64_t before = hist_excl[column_bin(ci[seg_ebeg[sgi]], n_cols)];
-        int b = (int)((before * kBands) / (total > 0 ? total : 1));
-        return b > kBands - 1 ? kBands - 1 : b;
-    }
-    if (!sort_tail) return kBands;
-    const int32_t r = seg_row[sgi];
-    const int32_t deg = rp[r + 1] - rp[r];
-    const int cls = deg > 96 ? 0 : deg > 64 ? 1 : deg > 48 ? 2 : deg > 32 ? 3 : deg > 24 ? 4 : deg > 16 ? 5 : deg > 8 ? 6 : 7;
-    return kBands + cls;
-}
-
-// Pass 1 of the stable partition: category of every segment and per-workgroup category counts
-// (block_cnt[cat * n_blocks + block]).
-__global__ __launch_bounds__(kPartThreads) void cat_count_kernel(
-    int64_t n_seg, const int32_t *seg_row, const int32_t *seg_dst, const int32_t *seg_ebeg, const int32_t *rp,
-    const int32_t *ci, int32_t n_cols, const int32_t *hist_excl, int sort_tail, uint8_t *seg_cat,
-    int32_t *block_cnt, int64_t n_blocks)
-{
-    __shared__ int s_cnt[kCats];
-    if (threadIdx.x < kCats) s_cnt[threadIdx.x] = 0;
-    __syncthreads();
-    const int64_t sgi = (int64_t)blockIdx.x * kPartThreads + threadIdx.x;
-    if (sgi < n_seg) {
-        const int c = segment_category(sgi, seg_row, seg_dst, seg_ebeg, rp, ci, n_cols, hist_excl, sort_tail);
-        seg_cat[sgi] = (uint8_t)c;
-        atomicAdd(&s_cnt[c], 1);
-    }
-    __syncthreads();
-    if (threadIdx.x < kCats) block_cnt[(int64_t)threadIdx.x * n_blocks + blockIdx.x] = s_cnt[threadIdx.x];
-}
-
-// Pass 2: block_off = exclusive scan of block_cnt (category-major = the final order).  Inside a
-// workgroup a segment's rank among the segments of its category is found with wavefront ballots, so
-// the partition is stable (row order is kept inside every category) and deterministic.
-__global__ __launch_bounds__(kPartThreads) void cat_scatter_kernel(
-    int64_t n_seg, const uint8_t *seg_cat, const int32_t *block_off, int64_t n_blocks, const int32_t *in_row,
-    const int32_t *in_ebeg, const int32_t *in_dst, int32_t *out_row, int32_t *out_ebeg, int32_t *out_dst)
-{
-    __shared__ int s_wave_cnt[kPartThreads / kWave][kCats];
-    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
-    const int64_t sgi = (int64_t)blockIdx.x * kPartThreads + threadIdx.x;
-    const int cat = sgi < n_seg ? (int)seg_cat[sgi] : -1;
-    int rank_in_wave = 0;
-    for (int c = 0; c < kCats; ++c) {
-        const unsigned long long mask = __ballot(cat == c);
-        if (lane == 0) s_wave_cnt[wave][c] = __popcll(mask);
-        if (cat == c) rank_in_wave = __popcll(mask & ((1ull << lane) - 1ull));
-    }
-    __syncthreads();
-    if (cat < 0) return;
-    int32_t p = block_off[(int64_t)cat * n_blocks + blockIdx.x] + rank_in_wave;
-    for (int w2 = 0; w2 < wave; ++w2) p += s_wave_cnt[w2][cat];
-    out_row[p] = in_row[sgi];
-    out_ebeg[p] = in_ebeg[sgi];
-    out_dst[p] = in_dst[sgi];
-}
-
-// Ordering of the split rows' segments inside the bands: key = the leading kSegSortBits bits of a segment's
-// start column (three passes of the radix sort; a finer order buys nothing).
-constexpr int kSegSortBits = 12;
-__global__ void seg_start_col_kernel(int64_t n, const int32_t *seg_ebeg, const int32_t *ci, int shift, int32_t *keys)
-{
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) keys[i] = ci[seg_ebeg[i]] >> shift;
-}
-
-__global__ void seg_permute_kernel(int64_t n, const int32_t *order, const int32_t *in_row, const int32_t *in_ebeg,
-                                   const int32_t *in_dst, int32_t *out_row, int32_t *out_ebeg, int32_t *out_dst)
-{
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= n) return;
-    const int32_t k = order[i];
-    out_row[i] = in_row[k];
-    out_ebeg[i] = in_ebeg[k];
-    out_dst[i] = in_dst[k];
-}
-
-// lane_tab[kLaneTabStride * l] = {band l start, count, band (kBands-1-l) start, count, tail start,
-// count} (see plan_segment()).  block_off == nullptr: no ordering, the whole list is the tail.
-__global__ void lane_table_kernel(int64_t n_seg, const int32_t *block_off, int64_t n_blocks, int32_t *lane_tab)
-{
-    if (threadIdx.x != 0 || blockIdx.x != 0) return;
-    const int32_t u_start = block_off ? block_off[(int64_t)kBands * n_blocks] : 0;
-    const int32_t u_count = (int32_t)n_seg - u_start;
-    for (int l = 0; l < kXcds; ++l) {
-        const int b2 = kBands - 1 - l;
-        int32_t *t = lane_tab + kLaneTabStride * l;
-        t[0] = block_off ? block_off[(int64_t)l * n_blocks] : 0;
-        t[1] = block_off ? block_off[(int64_t)(l + 1) * n_blocks] - t[0] : 0;
-        t[2] = block_off ? block_off[(int64_t)b2 * n_blocks] : 0;
-        t[3] = block_off ? block_off[(int64_t)(b2 + 1) * n_blocks] - t[2] : 0;
-        t[4] = u_start;
-        t[5] = u_count;
-    }
+    for (int32_t k = threadIdx.x; k < uw; k += 256) packed[u0 + k] = loose[lo + k];
 }
 
 __device__ __forceinline__ unsigned long long wave_sum_u64(unsigned long long v)
@@ -798,7 +953,8 @@ int64_t scan_workspace_elems(int64_t n) { return ceil_div(std::max<int64_t>(n, 1
 
 int exclusive_scan_i32(const int32_t *d_in, int32_t *d_out, int64_t n, int32_t *d_work, hipStream_t s)
 {
-    if (n <= kScanBlock) {
+    // Up to a few thousand elements per thread-round a single workgroup is quicker than three launches.
+    if (n <= 4 * kScanBlock) {
         hipLaunchKernelGGL(scan_single_kernel, dim3(1), dim3(1024), 0, s, d_in, d_out, n);
         return launch_status("scan_single_kernel");
     }
@@ -809,23 +965,18 @@ int exclusive_scan_i32(const int32_t *d_in, int32_t *d_out, int64_t n, int32_t *
     return launch_status("scan kernels");
 }
 
-int choose_paths(tcg_meta *m, tcg_policy policy, float min_reuse, hipStream_t s)
+static void launch_choose_path(tcg_meta *m, tcg_policy policy, float min_reuse, hipStream_t s)
 {
-    if (policy == TCG_POLICY_TILE && m->win_h != 16 && m->win_h != 32) return TCG_EINVAL;
-    if (min_reuse <= 0.f) min_reuse = kDefaultMinReuse;
-    // [0] tiles, [1] tile-path windows, [2] their edges, [3] windows of class kTileMany, [4] their widest,
-    // [5] distinct columns summed over the tile-path windows
-    unsigned long long *counts = m->d_counters;
-    TCG_HIP(hipMemsetAsync(counts, 0, 6 * sizeof(unsigned long long), s));
-    if (m->n_win > 0) {
-        hipLaunchKernelGGL(choose_path_kernel, dim3((unsigned)ceil_div(m->n_win, 256)), dim3(256), 0, s,
-                           m->n_rows, m->win_h, m->tile_w, m->n_win, m->d_row_ptr, m->d_win_unique_ptr,
-                           (int)policy, min_reuse, m->d_win_partition, m->d_win_path, counts);
-        TCG_TRY(launch_status("choose_path_kernel"));
-    }
-    unsigned long long h[6];
-    TCG_HIP(hipMemcpyAsync(h, counts, sizeof(h), hipMemcpyDeviceToHost, s));
-    TCG_HIP(hipStreamSynchronize(s));
+    if (m->n_win > 0)
+        hipLaunchKernelGGL(choose_path_kernel, dim3((unsigned)ceil_div(m->n_win, 256)), dim3(256), 0, s, m->n_rows,
+                           m->win_h, m->tile_w, m->n_win, m->d_row_ptr, m->d_win_unique_ptr, (int)policy, min_reuse,
+                           m->d_win_partition, m->d_win_path, m->d_counters);
+}
+
+// counts: [0] tiles, [1] tile-path windows, [2] their edges, [3] windows of class kTileMany, [4] their widest,
+// [5] distinct columns summed over the tile-path windows
+static int finish_choose_path(tcg_meta *m, tcg_policy policy, float min_reuse, const unsigned long long *h, hipStream_t s)
+{
     m->policy = policy;
     m->min_reuse = min_reuse;
     m->total_tiles = (int64_t)h[0];
@@ -838,286 +989,262 @@ int choose_paths(tcg_meta *m, tcg_policy policy, float min_reuse, hipStream_t s)
     // million-node graph): under the automatic policy the tile path is used from 2 % of the stored entries on.
     if (policy == TCG_POLICY_AUTO && m->n_tile_win > 0 && m->nnz_tile * 50 < m->nnz) {
         TCG_HIP(hipMemsetAsync(m->d_win_path, 0, (size_t)m->n_win, s));
-        TCG_HIP(hipStreamSynchronize(s));
         m->n_tile_win = m->nnz_tile = m->n_tile_many = m->max_unique_many = m->unique_tile = 0;
     }
     return TCG_OK;
 }
 
-__global__ void collect3_kernel(const int32_t *a, const int32_t *b, const int32_t *c, int *out)
+int choose_paths(tcg_meta *m, tcg_policy policy, float min_reuse, hipStream_t s)
 {
-    if (threadIdx.x == 0) {
-        out[0] = *a;
-        out[1] = *b;
-        out[2] = *c;
-    }
+    if (policy == TCG_POLICY_TILE && m->win_h != 16 && m->win_h != 32) return TCG_EINVAL;
+    if (min_reuse <= 0.f) min_reuse = kDefaultMinReuse;
+    TCG_HIP(hipMemsetAsync(m->d_counters, 0, 8 * sizeof(unsigned long long), s));
+    launch_choose_path(m, policy, min_reuse, s);
+    TCG_TRY(launch_status("choose_path_kernel"));
+    unsigned long long h[8];
+    TCG_HIP(hipMemcpyAsync(h, m->d_counters, sizeof(h), hipMemcpyDeviceToHost, s));
+    TCG_HIP(hipStreamSynchronize(s));
+    TCG_TRY(finish_choose_path(m, policy, min_reuse, h, s));
+    TCG_HIP(hipStreamSynchronize(s));
+    return TCG_OK;
 }
 
+int export_col_to_row(const tcg_meta *m, int32_t *d_packed, hipStream_t s)
+{
+    if (m->n_win == 0 || m->total_unique == 0) return TCG_OK;
+    hipLaunchKernelGGL(pack_unique_kernel, dim3((unsigned)m->n_win), dim3(256), 0, s, m->n_rows, m->win_h, m->d_row_ptr,
+                       m->d_col_to_row, m->d_win_unique_ptr, d_packed);
+    return launch_status("pack_unique_kernel");
+}
+
+template <int THREADS, int KPT>
+static void launch_sort_class(const tcg_meta *m, int cls, int64_t max_windows, int64_t grid_cap, bool wide_keys,
+                              const int32_t *lists, const BuildInfo *info, int32_t *win_unique, hipStream_t s)
+{
+    if (max_windows <= 0) return;
+    const unsigned grid = (unsigned)std::min<int64_t>(max_windows, grid_cap);
+    int pos_bits = 0;
+    while ((1 << pos_bits) < THREADS * KPT) ++pos_bits;
+    const int32_t *list = lists + (int64_t)cls * m->n_win;
+    if (wide_keys)
+        hipLaunchKernelGGL((sgt_window_sort_kernel<THREADS, KPT, uint64_t>), dim3(grid), dim3(THREADS), 0, s, m->n_rows,
+                           m->win_h, list, info->cls_count + cls, m->d_row_ptr, m->d_col_idx, pos_bits,
+                           m->d_edge_to_col, m->d_col_to_row, win_unique);
+    else
+        hipLaunchKernelGGL((sgt_window_sort_kernel<THREADS, KPT, uint32_t>), dim3(grid), dim3(THREADS), 0, s, m->n_rows,
+                           m->win_h, list, info->cls_count + cls, m->d_row_ptr, m->d_col_idx, pos_bits,
+                           m->d_edge_to_col, m->d_col_to_row, win_unique);
+}
+
+// Host side of a translation.  Every size the kernels need is either known from (n_rows, nnz) or read by
+// them from device memory, so everything is enqueued back to back and the host waits once, at the end,
+// for the block of small results (sizes of the plan, U, the die table, the path totals).  Buffers whose
+// exact size is only known then are sized by their bounds: a row has at least one segment and a split row
+// (more than kSegLen entries) at most deg / kSegLen + 1, and a window has no more distinct columns than
+// entries.
 int sgt_build_impl(tcg_meta *m, int validate, hipStream_t s)
 {
     const int32_t n = m->n_rows;
     const int64_t nnz = m->nnz;
     const int64_t n_win = m->n_win;
-    const int64_t scan_elems = scan_workspace_elems(std::max<int64_t>(n, n_win));
-    // Windows above medium_cap entries form the large class (bitmap over the column space).  When that
-    // bitmap fits in LDS it is cheaper than sorting from kLdsBitmapFrom entries on, so the class starts there.
-    const bool lds_bitmap = lds_bitmap_bytes(ceil_div(m->n_cols, 32)) <= kLdsBitmapMax;
-    const int32_t medium_cap = lds_bitmap ? std::min(kLdsBitmapFrom, kMediumCap) : kMediumCap;
+    const int64_t nb_rows = ceil_div(std::max<int64_t>(n, 0), kRowBlock);
+    const int64_t long_bound = nnz / (kSegLen + 1) + 1;
+    const int64_t slot_bound = nnz / kSegLen + long_bound;
+    const int64_t seg_bound = (int64_t)n + slot_bound;
+    if (seg_bound >= (int64_t)INT32_MAX) return TCG_ERANGE;
+    // Windows above large_from entries form the bitmap class.  When the bitmap over the column space fits
+    // in LDS it is cheaper than sorting from kLdsBitmapFrom entries on, so the class starts there.
+    const int64_t n_words = ceil_div(m->n_cols, 32);
+    const bool lds_bitmap = lds_bitmap_bytes(n_words) <= kLdsBitmapMax;
+    const int32_t large_from = lds_bitmap ? kLdsBitmapFrom : kMediumCap;
+    int col_bits = 1;
+    while (col_bits < 31 && ((int64_t)1 << col_bits) < (int64_t)m->n_cols) ++col_bits;
 
-    // Arena 0 (kept): the translated graph except col_to_row, the path flags, a few counters.
+    // Kept: the translated graph, the gather plan, the block of small results.
     Arena keep;
     keep.want(n_win * 4);             // win_partition
     keep.want((n_win + 1) * 4);       // win_unique_ptr
     keep.want(nnz * 4);               // edge_to_col
+    keep.want(nnz * 4);               // col_to_row (each window's list at its edge offset)
     keep.want(n_win);                 // win_path
-    keep.want(8 * 8);                 // counters
+    keep.want(sizeof(BuildInfo));
+    for (int i = 0; i < 3; ++i) keep.want(seg_bound * 4);
+    keep.want(long_bound * 4);
+    keep.want((long_bound + 1) * 4);
     TCG_TRY(keep.commit());
     m->owned[m->n_owned++] = keep.base;
     m->d_win_partition = keep.take<int32_t>(n_win);
     m->d_win_unique_ptr = keep.take<int32_t>(n_win + 1);
     m->d_edge_to_col = keep.take<int32_t>(nnz);
+    m->d_col_to_row = keep.take<int32_t>(nnz);
     m->d_win_path = keep.take<uint8_t>(n_win);
-    m->d_counters = keep.take<unsigned long long>(8);
+    BuildInfo *info = keep.take<BuildInfo>(1);
+    m->d_seg_row = keep.take<int32_t>(seg_bound);
+    m->d_seg_ebeg = keep.take<int32_t>(seg_bound);
+    m->d_seg_dst = keep.take<int32_t>(seg_bound);
+    m->d_long_row = keep.take<int32_t>(long_bound);
+    m->d_long_slot_ptr = keep.take<int32_t>(long_bound + 1);
+    m->d_lane_tab = info->lane_tab;
+    m->d_counters = info->counters;
 
     // Temporaries of the build.
+    const size_t sort_bytes = radix_sort_scratch_bytes(slot_bound);
+    const int64_t scan_elems = scan_workspace_elems(n_win);
     Arena tmp;
-    tmp.want(nnz * 4);                // tmp_clean
-    tmp.want((n_win + 1) * 4);        // win_unique
-    tmp.want(4 * n_win * 4);          // class lists
-    for (int i = 0; i < 3; ++i) tmp.want(((int64_t)n + 1) * 4);   // segment counts / offsets
-    tmp.want(scan_elems * 4);         // scan workspace
-    tmp.want(16 * 4);                 // class counts + validation flag
+    tmp.want((n_win + 1) * 4);                      // win_unique
+    tmp.want((int64_t)kClasses * n_win * 4);        // class lists
+    tmp.want((int64_t)kPlanSums * nb_rows * 4);     // per-row-block counts
+    tmp.want((nb_rows + 1) * 4);                    // long_off
+    tmp.want((nb_rows + 1) * 4);                    // slot_off
+    tmp.want((int64_t)kTailClasses * nb_rows * 4);  // tail_off
+    tmp.want(scan_elems * 4);
+    for (int i = 0; i < 5; ++i) tmp.want(slot_bound * 4);   // slot_row, slot_ebeg, slot_key, sorted keys, order
+    tmp.want(sort_bytes);
     TCG_TRY(tmp.commit());
     ScopedFree tmp_guard{tmp.base, s};
-    int32_t *tmp_clean = tmp.take<int32_t>(nnz);
     int32_t *win_unique = tmp.take<int32_t>(n_win + 1);
-    int32_t *lists = tmp.take<int32_t>(4 * n_win);
-    int32_t *seg_off = tmp.take<int32_t>((int64_t)n + 1);
-    int32_t *long_off = tmp.take<int32_t>((int64_t)n + 1);
-    int32_t *slot_off = tmp.take<int32_t>((int64_t)n + 1);
+    int32_t *lists = tmp.take<int32_t>((int64_t)kClasses * n_win);
+    int32_t *block_sums = tmp.take<int32_t>((int64_t)kPlanSums * nb_rows);
+    int32_t *long_off = tmp.take<int32_t>(nb_rows + 1);
+    int32_t *slot_off = tmp.take<int32_t>(nb_rows + 1);
+    int32_t *tail_off = tmp.take<int32_t>((int64_t)kTailClasses * nb_rows);
     int32_t *scan_work = tmp.take<int32_t>(scan_elems);
-    int *small_ints = tmp.take<int>(16);   // [0..3] class counts, [4..6] plan totals, [8] validation flag
-    TCG_HIP(hipMemsetAsync(small_ints, 0, 16 * sizeof(int), s));
+    int32_t *slot_row = tmp.take<int32_t>(slot_bound);
+    int32_t *slot_ebeg = tmp.take<int32_t>(slot_bound);
+    int32_t *slot_key = tmp.take<int32_t>(slot_bound);
+    int32_t *key_sorted = tmp.take<int32_t>(slot_bound);
+    int32_t *order = tmp.take<int32_t>(slot_bound);
+    void *sort_scratch = tmp.take<char>((int64_t)sort_bytes);
+
+    TCG_HIP(hipMemsetAsync(info, 0, sizeof(BuildInfo), s));
 
     if (validate) {
-        int *flag = small_ints + 8;
+        // Both checks run before anything follows row_ptr into col_idx (the column check walks 0 .. nnz-1).
         hipLaunchKernelGGL(validate_csr_kernel, dim3((unsigned)std::min<int64_t>(ceil_div((int64_t)n + 1, 256), 4096)),
-                           dim3(256), 0, s, n, nnz, m->d_row_ptr, flag);
-        TCG_TRY(launch_status("validate_csr_kernel"));
-        int h = 0;
-        TCG_HIP(hipMemcpyAsync(&h, flag, sizeof(int), hipMemcpyDeviceToHost, s));
-        TCG_HIP(hipStreamSynchronize(s));
-        if (h) return TCG_ECSR;  // do not touch col_idx through a broken row_ptr
-        if (nnz > 0) {
+                           dim3(256), 0, s, n, nnz, m->d_row_ptr, &info->flag);
+        if (nnz > 0)
             hipLaunchKernelGGL(validate_cols_kernel, dim3((unsigned)std::min<int64_t>(ceil_div(nnz, 256), 8192)),
-                               dim3(256), 0, s, m->n_cols, nnz, m->d_col_idx, flag);
-            TCG_TRY(launch_status("validate_cols_kernel"));
-            TCG_HIP(hipMemcpyAsync(&h, flag, sizeof(int), hipMemcpyDeviceToHost, s));
-            TCG_HIP(hipStreamSynchronize(s));
-            if (h) return TCG_ECSR;
-        }
+                               dim3(256), 0, s, m->n_cols, nnz, m->d_col_idx, &info->flag);
+        TCG_TRY(launch_status("validate kernels"));
+        int h = 0;
+        TCG_HIP(hipMemcpyAsync(&h, &info->flag, sizeof(int), hipMemcpyDeviceToHost, s));
+        TCG_HIP(hipStreamSynchronize(s));
+        if (h) return TCG_ECSR;
     }
 
-    // Window classes and segment counts (both depend on row_ptr only).
-    if (n_win > 0) {
-        hipLaunchKernelGGL(classify_windows_kernel, dim3((unsigned)ceil_div(n_win, 256)), dim3(256), 0, s, n,
-                           m->win_h, n_win, m->d_row_ptr, lists, small_ints, win_unique, medium_cap);
-        TCG_TRY(launch_status("classify_windows_kernel"));
+    // Per-row-block counts of the gather plan and the window classes (both depend on row_ptr only).
+    if (nb_rows + ceil_div(n_win, 256) > 0) {
+        hipLaunchKernelGGL(prep_kernel, dim3((unsigned)(nb_rows + ceil_div(n_win, 256))), dim3(256), 0, s, n, m->win_h,
+                           n_win, m->d_row_ptr, nb_rows, block_sums, lists, info->cls_count, win_unique, large_from);
+        TCG_TRY(launch_status("prep_kernel"));
     }
-    if (n > 0) {
-        hipLaunchKernelGGL(seg_count_kernel, dim3((unsigned)ceil_div(n, 256)), dim3(256), 0, s, n, m->d_row_ptr,
-                           seg_off, long_off, slot_off);
-        TCG_TRY(launch_status("seg_count_kernel"));
+
+    // Per-window translation, one launch per size class.  A class with at least `lo` entries per window has at
+    // most nnz / lo windows; the kernels read the real count on the device.
+    {
+        const bool wide = col_bits + 10 > 31;              // column and position do not fit 31 bits: 64-bit keys
+        auto most = [&](int64_t least_entries) { return std::min<int64_t>(n_win, nnz / least_entries); };
+        launch_sort_class<64, 1>(m, 0, most(1), 8192, col_bits + 6 > 31, lists, info, win_unique, s);
+        launch_sort_class<64, 2>(m, 1, most(65), 8192, col_bits + 7 > 31, lists, info, win_unique, s);
+        launch_sort_class<64, 4>(m, 2, most(129), 8192, col_bits + 8 > 31, lists, info, win_unique, s);
+        launch_sort_class<128, 4>(m, 3, most(257), 4096, col_bits + 9 > 31, lists, info, win_unique, s);
+        launch_sort_class<256, 4>(m, 4, most(513), 2048, wide, lists, info, win_unique, s);
+        if (!lds_bitmap)
+            launch_sort_class<1024, 4>(m, kClsMedium, most(kSortCap + 1), 512, col_bits + 12 > 31, lists, info,
+                                       win_unique, s);
+        TCG_TRY(launch_status("sgt_window_sort_kernel"));
     }
-    TCG_TRY(exclusive_scan_i32(seg_off, seg_off, n, scan_work, s));
-    TCG_TRY(exclusive_scan_i32(long_off, long_off, n, scan_work, s));
-    TCG_TRY(exclusive_scan_i32(slot_off, slot_off, n, scan_work, s));
-    // One copy for everything the host needs here (every separate small copy costs tens of microseconds):
-    // the three totals are collected next to the class counts first.
-    hipLaunchKernelGGL(collect3_kernel, dim3(1), dim3(64), 0, s, seg_off + n, long_off + n, slot_off + n,
-                       small_ints + 4);
-    int h_small[7] = {0, 0, 0, 0, 0, 0, 0};
-    TCG_HIP(hipMemcpyAsync(h_small, small_ints, sizeof(h_small), hipMemcpyDeviceToHost, s));
-    TCG_HIP(hipStreamSynchronize(s));                                           // sync 1
-    const int h_cls[4] = {h_small[0], h_small[1], h_small[2], h_small[3]};
-    const int32_t h_plan[3] = {h_small[4], h_small[5], h_small[6]};
-    m->n_seg = h_plan[0];
-    m->n_long = h_plan[1];
-    m->n_slots = h_plan[2];
-
-    // Arena 1 (kept): the gather plan.
-    Arena plan;
-    plan.want(m->n_seg * 4);
-    plan.want(m->n_seg * 4);
-    plan.want(m->n_seg * 4);
-    plan.want(m->n_long * 4);
-    plan.want((m->n_long + 1) * 4);
-    plan.want(kLaneTabStride * kXcds * 4);
-    plan.want(m->n_slots * kPartialInitD * 4);   // partial sums of split rows for D <= kPartialInitD
-    plan.want(m->n_slots * 2 * 4);               // (maximum, denominator) per split-row segment
-    TCG_TRY(plan.commit());
-    m->owned[m->n_owned++] = plan.base;
-    m->d_seg_row = plan.take<int32_t>(m->n_seg);
-    m->d_seg_ebeg = plan.take<int32_t>(m->n_seg);
-    m->d_seg_dst = plan.take<int32_t>(m->n_seg);
-    m->d_long_row = plan.take<int32_t>(m->n_long);
-    m->d_long_slot_ptr = plan.take<int32_t>(m->n_long + 1);
-    m->d_lane_tab = plan.take<int32_t>(kLaneTabStride * kXcds);
-    m->d_partial = plan.take<float>(m->n_slots * kPartialInitD);
-    m->partial_elems = m->n_slots * kPartialInitD;
-    m->partial_owned = false;
-    m->d_partial_ml = plan.take<float>(m->n_slots * 2);
-
-    // Per-window translation, one launch per size class.
-    if (h_cls[0] > 0)
-        hipLaunchKernelGGL((sgt_window_lds_kernel<kWave, kTinyCap>), dim3((unsigned)h_cls[0]), dim3(kWave), 0, s, n,
-                           m->win_h, lists, m->d_row_ptr, m->d_col_idx, m->d_edge_to_col, tmp_clean, win_unique);
-    if (h_cls[1] > 0)
-        hipLaunchKernelGGL((sgt_window_lds_kernel<256, kSmallCap>), dim3((unsigned)h_cls[1]), dim3(256), 0, s, n,
-                           m->win_h, lists + n_win, m->d_row_ptr, m->d_col_idx, m->d_edge_to_col, tmp_clean,
-                           win_unique);
-    if (h_cls[2] > 0)
-        hipLaunchKernelGGL((sgt_window_lds_kernel<256, kMediumCap>), dim3((unsigned)h_cls[2]), dim3(256), 0, s, n,
-                           m->win_h, lists + 2 * n_win, m->d_row_ptr, m->d_col_idx, m->d_edge_to_col, tmp_clean,
-                           win_unique);
-    TCG_TRY(launch_status("sgt_window_lds_kernel"));
     ScopedFree bitmap_guard{nullptr, s};
-    const int64_t n_words_all = ceil_div(m->n_cols, 32);
-    if (h_cls[3] > 0 && lds_bitmap_bytes(n_words_all) <= kLdsBitmapMax) {
-        const size_t lds = lds_bitmap_bytes(n_words_all);
+    const int64_t large_most = std::min<int64_t>(n_win, nnz / ((int64_t)large_from + 1));
+    if (large_most > 0 && lds_bitmap) {
+        const size_t lds = lds_bitmap_bytes(n_words);
         static bool raised = false;       // more than 64 KB of dynamic LDS has to be asked for once
         if (!raised) {
             TCG_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(sgt_window_lds_bitmap_kernel),
                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBitmapMax));
             raised = true;
         }
-        hipLaunchKernelGGL(sgt_window_lds_bitmap_kernel, dim3((unsigned)h_cls[3]), dim3(kBitmapThreads), lds, s, n,
-                           m->win_h, (int32_t)n_words_all, lists + 3 * n_win, m->d_row_ptr, m->d_col_idx,
-                           m->d_edge_to_col, tmp_clean, win_unique);
+        static int n_cu = 0;              // one workgroup per compute unit
+        if (n_cu <= 0 && (hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, m->device) != hipSuccess ||
+                          n_cu <= 0))
+            n_cu = 256;
+        const unsigned grid = (unsigned)std::min<int64_t>(large_most, n_cu);
+        hipLaunchKernelGGL(sgt_window_lds_bitmap_kernel, dim3(grid), dim3(kBitmapThreads), lds, s, n, m->win_h,
+                           (int32_t)n_words, lists + (int64_t)kClsLarge * n_win, info->cls_count + kClsLarge, &info->ticket,
+                           m->d_row_ptr, m->d_col_idx, m->d_edge_to_col, m->d_col_to_row, win_unique);
         TCG_TRY(launch_status("sgt_window_lds_bitmap_kernel"));
-    } else if (h_cls[3] > 0) {
-        const int64_t n_large = h_cls[3];
-        const int64_t n_words = n_words_all;
-        const int64_t budget_words = (int64_t)(128ll << 20) / 4;  // 128 MiB per scratch array
-        const int64_t batch = std::max<int64_t>(1, std::min<int64_t>(n_large, budget_words / n_words));
-        uint32_t *bitmap = nullptr;
-        TCG_TRY(dev_alloc(&bitmap, 2 * batch * n_words));
-        bitmap_guard.p = bitmap;
-        int32_t *prefix = reinterpret_cast<int32_t *>(bitmap + batch * n_words);
-        for (int64_t b0 = 0; b0 < n_large; b0 += batch) {
-            const int64_t nb = std::min<int64_t>(batch, n_large - b0);
-            TCG_HIP(hipMemsetAsync(bitmap, 0, (size_t)(nb * n_words) * sizeof(uint32_t), s));
-            hipLaunchKernelGGL(sgt_window_bitmap_kernel, dim3((unsigned)nb), dim3(kBitmapThreads), 0, s, n,
-                               m->win_h, n_words, lists + 3 * n_win + b0, m->d_row_ptr, m->d_col_idx, bitmap,
-                               prefix, m->d_edge_to_col, tmp_clean, win_unique);
-            TCG_TRY(launch_status("sgt_window_bitmap_kernel"));
+    } else if (large_most > 0) {
+        // Column space too wide for LDS: the bitmap lives in device scratch, sized by the number of windows
+        // in the class, which the host has to fetch first (the one extra wait of this rare path).
+        int32_t n_large = 0;
+        TCG_HIP(hipMemcpyAsync(&n_large, info->cls_count + kClsLarge, sizeof(int32_t), hipMemcpyDeviceToHost, s));
+        TCG_HIP(hipStreamSynchronize(s));
+        if (n_large > 0) {
+            const int64_t budget_words = (int64_t)(128ll << 20) / 4;  // 128 MiB per scratch array
+            const int64_t batch = std::max<int64_t>(1, std::min<int64_t>(n_large, budget_words / n_words));
+            uint32_t *bitmap = nullptr;
+            TCG_TRY(dev_alloc(&bitmap, 2 * batch * n_words));
+            bitmap_guard.p = bitmap;
+            int32_t *prefix = reinterpret_cast<int32_t *>(bitmap + batch * n_words);
+            for (int64_t b0 = 0; b0 < n_large; b0 += batch) {
+                const int64_t nb = std::min<int64_t>(batch, n_large - b0);
+                TCG_HIP(hipMemsetAsync(bitmap, 0, (size_t)(nb * n_words) * sizeof(uint32_t), s));
+                hipLaunchKernelGGL(sgt_window_bitmap_kernel, dim3((unsigned)nb), dim3(kBitmapThreads), 0, s, n,
+                                   m->win_h, n_words, lists + (int64_t)kClsLarge * n_win + b0, m->d_row_ptr, m->d_col_idx,
+                                   bitmap, prefix, m->d_edge_to_col, m->d_col_to_row, win_unique);
+                TCG_TRY(launch_status("sgt_window_bitmap_kernel"));
+            }
         }
     }
 
     TCG_TRY(exclusive_scan_i32(win_unique, m->d_win_unique_ptr, n_win, scan_work, s));
-    int32_t total_unique = 0;
-    TCG_HIP(hipMemcpyAsync(&total_unique, m->d_win_unique_ptr + n_win, sizeof(int32_t), hipMemcpyDeviceToHost, s));
-    TCG_HIP(hipStreamSynchronize(s));                                           // sync 2
-    m->total_unique = total_unique;
 
-    // Segment list: row order first, then a stable partition into column bands (split rows) and the
-    // tail of single-segment rows.  When the windows share few neighbours (U close to nnz) the tail is
-    // ordered by row length as well; otherwise it keeps the row order.
-    const int64_t n_pblocks = ceil_div(std::max<int64_t>(m->n_seg, 1), kPartThreads);
-    const int sort_tail = (double)m->total_unique > 0.75 * (double)std::max<int64_t>(nnz, 1) ? 1 : 0;
-    const bool ordered = (m->n_slots > 0 || sort_tail) && (int64_t)kCats * n_pblocks + 1 < (int64_t)INT32_MAX;
-    Arena ptmp;
-    const int64_t cnt_elems = (int64_t)kCats * n_pblocks + 1;
-    const int64_t pscan_elems = scan_workspace_elems(std::max<int64_t>(cnt_elems, kHistBins));
-    if (ordered) {
-        for (int i = 0; i < 3; ++i) ptmp.want(m->n_seg * 4);
-        ptmp.want(m->n_seg);
-        ptmp.want(cnt_elems * 4);
-        ptmp.want((kHistBins + 1) * 4);
-        ptmp.want(pscan_elems * 4);
-        TCG_TRY(ptmp.commit());
+    // Gather plan: offsets, then the segment list in its final order (see plan_scan_kernel).
+    hipLaunchKernelGGL(plan_scan_kernel, dim3(1), dim3(1024), 0, s, nb_rows, block_sums, nnz, n_win,
+                       m->d_win_unique_ptr, long_off, slot_off, tail_off, info, m->d_long_slot_ptr);
+    if (nb_rows > 0) {
+        const int key_shift = col_bits > kSegSortBits ? col_bits - kSegSortBits : 0;   // the leading bits are enough
+        hipLaunchKernelGGL(seg_fill_kernel, dim3((unsigned)nb_rows), dim3(256), 0, s, n, m->d_row_ptr, m->d_col_idx, info,
+                           nb_rows, long_off, slot_off, tail_off, key_shift, m->d_seg_row, m->d_seg_ebeg, m->d_seg_dst,
+                           m->d_long_row, m->d_long_slot_ptr, slot_row, slot_ebeg, slot_key);
+        TCG_TRY(launch_status("plan kernels"));
+        // Split rows' segments by start column: segments that run one after the other on a die then read
+        // neighbouring -- on skewed graphs largely the same -- X rows.
+        const bool sorted = sort_bytes > 0 && slot_bound > 1;
+        if (sorted)
+            TCG_TRY(radix_sort_pairs(slot_key, nullptr, slot_bound, &info->n_slots, col_bits - key_shift, key_sorted, order,
+                                     sort_scratch, s));
+        hipLaunchKernelGGL(seg_permute_kernel, dim3((unsigned)ceil_div(slot_bound, 256)), dim3(256), 0, s, info,
+                           sorted ? order : (const int32_t *)nullptr, slot_row, slot_ebeg, m->d_seg_row, m->d_seg_ebeg,
+                           m->d_seg_dst);
     }
-    ScopedFree ptmp_guard{ptmp.base, s};
-    if (n > 0) {
-        int32_t *row_o = m->d_seg_row, *ebeg_o = m->d_seg_ebeg, *dst_o = m->d_seg_dst;
-        if (ordered) {
-            row_o = ptmp.take<int32_t>(m->n_seg);
-            ebeg_o = ptmp.take<int32_t>(m->n_seg);
-            dst_o = ptmp.take<int32_t>(m->n_seg);
-        }
-        hipLaunchKernelGGL(seg_fill_kernel, dim3((unsigned)ceil_div(n, 256)), dim3(256), 0, s, n, m->d_row_ptr,
-                           seg_off, long_off, slot_off, row_o, ebeg_o, dst_o, m->d_long_row, m->d_long_slot_ptr,
-                           m->n_long);
-        TCG_TRY(launch_status("seg_fill_kernel"));
-        if (ordered) {
-            uint8_t *seg_cat = ptmp.take<uint8_t>(m->n_seg);
-            int32_t *block_cnt = ptmp.take<int32_t>(cnt_elems);
-            int32_t *hist = ptmp.take<int32_t>(kHistBins + 1);
-            int32_t *pscan = ptmp.take<int32_t>(pscan_elems);
-            const unsigned sgrid = (unsigned)n_pblocks;
-            TCG_HIP(hipMemsetAsync(hist, 0, (kHistBins + 1) * sizeof(int32_t), s));
-            hipLaunchKernelGGL(band_hist_kernel, dim3(std::min<unsigned>(sgrid, 512u)), dim3(256), 0, s, m->n_seg, dst_o,
-                               ebeg_o, m->d_col_idx, m->n_cols, hist);
-            TCG_TRY(exclusive_scan_i32(hist, hist, kHistBins, pscan, s));
-            hipLaunchKernelGGL(cat_count_kernel, dim3(sgrid), dim3(kPartThreads), 0, s, m->n_seg, row_o, dst_o, ebeg_o,
-                               m->d_row_ptr, m->d_col_idx, m->n_cols, hist, sort_tail, seg_cat, block_cnt, n_pblocks);
-            TCG_TRY(exclusive_scan_i32(block_cnt, block_cnt, cnt_elems - 1, pscan, s));
-            hipLaunchKernelGGL(cat_scatter_kernel, dim3(sgrid), dim3(kPartThreads), 0, s, m->n_seg, seg_cat, block_cnt,
-                               n_pblocks, row_o, ebeg_o, dst_o, m->d_seg_row, m->d_seg_ebeg, m->d_seg_dst);
-            hipLaunchKernelGGL(lane_table_kernel, dim3(1), dim3(64), 0, s, m->n_seg, block_cnt, n_pblocks, m->d_lane_tab);
-            TCG_TRY(launch_status("segment ordering kernels"));
-            // Inside the bands: by start column (the bands are ranges of start columns, so one stable sort of all
-            // split-row segments keeps them in place).  Segments that run one after the other on a die then
-            // read neighbouring -- on skewed graphs largely the same -- X rows.
-            const int64_t ns = m->n_slots;
-            if (ns > 1 && radix_sort_scratch_bytes(ns) > 0) {
-                const size_t arr = ((size_t)ns * 4 + 255) & ~(size_t)255;
-                PoolBuf sb;
-                sb.s = s;
-                TCG_TRY(pool_alloc(&sb.p, 7 * arr + radix_sort_scratch_bytes(ns)));
-                char *base = static_cast<char *>(sb.p);
-                int32_t *keys = reinterpret_cast<int32_t *>(base), *keys_o = reinterpret_cast<int32_t *>(base + arr),
-                        *order = reinterpret_cast<int32_t *>(base + 2 * arr), *t_row = reinterpret_cast<int32_t *>(base + 3 * arr),
-                        *t_ebeg = reinterpret_cast<int32_t *>(base + 4 * arr), *t_dst = reinterpret_cast<int32_t *>(base + 5 * arr);
-                void *sort_scratch = base + 7 * arr;
-                int bits = 1;
-                while (bits < 31 && ((int64_t)1 << bits) < (int64_t)m->n_cols) ++bits;
-                const int shift = bits > kSegSortBits ? bits - kSegSortBits : 0;   // the leading bits are enough
-                const unsigned g = (unsigned)ceil_div(ns, 256);
-                hipLaunchKernelGGL(seg_start_col_kernel, dim3(g), dim3(256), 0, s, ns, m->d_seg_ebeg, m->d_col_idx, shift,
-                                   keys);
-                TCG_TRY(radix_sort_pairs(keys, nullptr, ns, bits - shift, keys_o, order, sort_scratch, s));
-                hipLaunchKernelGGL(seg_permute_kernel, dim3(g), dim3(256), 0, s, ns, order, m->d_seg_row, m->d_seg_ebeg,
-                                   m->d_seg_dst, t_row, t_ebeg, t_dst);
-                TCG_HIP(hipMemcpyAsync(m->d_seg_row, t_row, (size_t)ns * 4, hipMemcpyDeviceToDevice, s));
-                TCG_HIP(hipMemcpyAsync(m->d_seg_ebeg, t_ebeg, (size_t)ns * 4, hipMemcpyDeviceToDevice, s));
-                TCG_HIP(hipMemcpyAsync(m->d_seg_dst, t_dst, (size_t)ns * 4, hipMemcpyDeviceToDevice, s));
-                TCG_TRY(launch_status("segment sort kernels"));
-            }                                   // sb waits for the stream and returns the buffer
-        }
-    }
-    if (!ordered) {
-        hipLaunchKernelGGL(lane_table_kernel, dim3(1), dim3(64), 0, s, m->n_seg, (const int32_t *)nullptr, (int64_t)0,
-                           m->d_lane_tab);
-        TCG_TRY(launch_status("lane_table_kernel"));
-    }
-    TCG_HIP(hipMemcpyAsync(m->h_lane_tab, m->d_lane_tab, sizeof(m->h_lane_tab), hipMemcpyDeviceToHost, s));
+    launch_choose_path(m, TCG_POLICY_AUTO, kDefaultMinReuse, s);
+    TCG_TRY(launch_status("plan and path kernels"));
 
-    TCG_TRY(dev_alloc(&m->d_col_to_row, m->total_unique));
-    m->owned[m->n_owned++] = m->d_col_to_row;
-    if (n_win > 0) {
-        hipLaunchKernelGGL(sgt_pack_kernel, dim3((unsigned)n_win), dim3(kWave), 0, s, n, m->win_h, m->d_row_ptr,
-                           tmp_clean, m->d_win_unique_ptr, m->d_col_to_row, medium_cap);
-        TCG_TRY(launch_status("sgt_pack_kernel"));
-        if (h_cls[3] > 0) {
-            hipLaunchKernelGGL(sgt_pack_large_kernel, dim3((unsigned)h_cls[3], kPackSplit), dim3(256), 0, s, n,
-                               m->win_h, lists + 3 * n_win, m->d_row_ptr, tmp_clean, m->d_win_unique_ptr,
-                               m->d_col_to_row);
-            TCG_TRY(launch_status("sgt_pack_large_kernel"));
-        }
+    BuildInfo h;
+    TCG_HIP(hipMemcpyAsync(&h, info, sizeof(BuildInfo), hipMemcpyDeviceToHost, s));
+    TCG_HIP(hipStreamSynchronize(s));                       // the one wait of a build
+    m->n_seg = h.n_seg;
+    m->n_long = h.n_long;
+    m->n_slots = h.n_slots;
+    m->total_unique = h.total_unique;
+    for (int i = 0; i < kLaneTabStride * kXcds; ++i) m->h_lane_tab[i] = h.lane_tab[i];
+    TCG_TRY(finish_choose_path(m, TCG_POLICY_AUTO, kDefaultMinReuse, h.counters, s));
+
+    // Scratch of the split rows (sized exactly, now that n_slots is known): fp32 partial sums for feature widths
+    // up to kPartialInitD and the (maximum, denominator) pairs of the fused attention.
+    {
+        Arena part;
+        part.want(m->n_slots * kPartialInitD * 4);
+        part.want(m->n_slots * 2 * 4);
+        TCG_TRY(part.commit());
+        m->owned[m->n_owned++] = part.base;
+        m->d_partial = part.take<float>(m->n_slots * kPartialInitD);
+        m->partial_elems = m->n_slots * kPartialInitD;
+        m->partial_owned = false;
+        m->d_partial_ml = part.take<float>(m->n_slots * 2);
     }
-    TCG_TRY(choose_paths(m, TCG_POLICY_AUTO, 0.f, s));                          // sync 3
-    return TCG_OK;   // temporaries are freed by the guards; the stream is idle here
+    return TCG_OK;   // temporaries are freed by the guards; the stream is idle here (or drains a last fill)
 }
 
 }  // namespace tcg

@@ -158,11 +158,12 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(3))) void
     }
     wave_lds_order();
     const int32_t u0 = win_unique_ptr[win];
+    const int32_t cb = row_ptr[r0];             // the window's list sits at its edge offset
     const int32_t U = win_unique_ptr[win + 1] - u0;
     // ids of the neighbours of chunks 0 and 1 (lane k < 16 holds row k of the chunk)
     const int kk = lane & 15;
-    int32_t nid_cur = kk < U ? col_to_row[u0 + kk] : -1;
-    int32_t nid_nxt = KW + kk < U ? col_to_row[u0 + KW + kk] : -1;
+    int32_t nid_cur = kk < U ? col_to_row[cb + kk] : -1;
+    int32_t nid_nxt = KW + kk < U ? col_to_row[cb + KW + kk] : -1;
     const int32_t lo = s_rp[0], hi = s_rp[H];
     if (skip_small && hi - lo <= kTileFewEdges) return;        // taken by the direct kernel
     const int32_t n_slices = (Dp + 15) / 16;
@@ -257,7 +258,7 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(3))) void
         nid_cur = nid_nxt;
         if (k0 + KW < U) {
             fetch(nid_cur);
-            nid_nxt = k0 + 2 * KW + kk < U ? col_to_row[u0 + k0 + 2 * KW + kk] : -1;
+            nid_nxt = k0 + 2 * KW + kk < U ? col_to_row[cb + k0 + 2 * KW + kk] : -1;
         }
         if constexpr (!FULL_A) {
             // InitSparse
@@ -393,10 +394,11 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(4))) void
     }
     wave_lds_order();
     const int32_t u0 = win_unique_ptr[win];
+    const int32_t cb = row_ptr[r0];             // the window's list sits at its edge offset
     const int32_t U = win_unique_ptr[win + 1] - u0;
     // ids of the neighbours of chunks 0 and 1 (lane k < 16 holds row k of the chunk)
-    int32_t nid_cur = n < U ? col_to_row[u0 + n] : -1;
-    int32_t nid_nxt = KW + n < U ? col_to_row[u0 + KW + n] : -1;
+    int32_t nid_cur = n < U ? col_to_row[cb + n] : -1;
+    int32_t nid_nxt = KW + n < U ? col_to_row[cb + KW + n] : -1;
     const int32_t lo = s_rp[0], hi = s_rp[16];
     if (!FULL_A && hi - lo > kTileFewEdges) return;    // only a forced policy puts such a window into this class
 
@@ -517,7 +519,7 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(4))) void
         nid_cur = nid_nxt;
         if (k0 + KW < U) {
             fetch(nid_cur);
-            nid_nxt = k0 + 2 * KW + n < U ? col_to_row[u0 + k0 + 2 * KW + n] : -1;
+            nid_nxt = k0 + 2 * KW + n < U ? col_to_row[cb + k0 + 2 * KW + n] : -1;
         }
     }
 
@@ -596,10 +598,11 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(NB >= 4 ?
     }
     wave_lds_order();
     const int32_t u0 = win_unique_ptr[win];
+    const int32_t cb = row_ptr[r0];             // the window's list sits at its edge offset
     const int32_t U = win_unique_ptr[win + 1] - u0;
     // ids of the neighbours of chunks 0 and 1 (lane k < 16 holds row k of the chunk)
-    int32_t nid_cur = n < U ? col_to_row[u0 + n] : -1;
-    int32_t nid_nxt = KW + n < U ? col_to_row[u0 + KW + n] : -1;
+    int32_t nid_cur = n < U ? col_to_row[cb + n] : -1;
+    int32_t nid_nxt = KW + n < U ? col_to_row[cb + KW + n] : -1;
     const int32_t lo = s_rp[0], hi = s_rp[16];
     // only a forced policy puts a window with more edges into class kTileFew: its edges are then read from
     // global memory for every chunk
@@ -746,7 +749,7 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(NB >= 4 ?
         nid_cur = nid_nxt;
         if (k0 + KW < U) {
             fetch(nid_cur);
-            nid_nxt = k0 + 2 * KW + n < U ? col_to_row[u0 + k0 + 2 * KW + n] : -1;
+            nid_nxt = k0 + 2 * KW + n < U ? col_to_row[cb + k0 + 2 * KW + n] : -1;
         }
     }
 
