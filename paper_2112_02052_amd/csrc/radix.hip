@@ -144,7 +144,7 @@ __global__ __launch_bounds__(kThreads) void radix_scatter_kernel(
 }
 
 constexpr int kKeysSmall = 4, kKeysLarge = 16;       // keys per thread: tiles of 1024 / 4096 keys
-constexpr int64_t kLargeFrom = 1 << 21;
+constexpr int64_t kLargeFrom = 1 << 16;
 
 inline int keys_per_thread(int64_t n_max) { return n_max >= kLargeFrom ? kKeysLarge : kKeysSmall; }
 

@@ -7,7 +7,7 @@
 //   up to 1024 entries   (five classes: 64, 128, 256, 512, 1024) a bitonic sorting network held in
 //                        registers, 64 to 256 threads; the keys carry the entry's position, so ranks are
 //                        scattered straight to edge_to_col
-//   above               a bitmap over the column space -- in LDS when it fits (up to about 1.16 M
+//   above               a bitmap over the column space -- in LDS when it fits (up to about 1.12 M
 //                        columns), else in device scratch (then a class of up to 4096 entries is still
 //                        sorted): set a bit per edge, prefix-popcount the words, rank = prefix + popcount
 //                        below.  Hub windows of power-law graphs land here; the cost is
@@ -23,6 +23,7 @@
 #include <limits.h>
 
 #include <algorithm>
+#include <mutex>
 
 namespace tcg {
 
@@ -165,21 +166,22 @@ __device__ __forceinline__ void window_edge_range(const int32_t *rp, int32_t n_r
 }
 
 // ---- size classes and the per-build block of small results ---------------------------------------
-// A window's class follows its number of stored entries: five classes of the register sorting network
-// (<= 64, 128, 256, 512, 1024 entries), a sixth one (<= 4096) that only exists when the LDS bitmap does
-// not fit the column space, and the bitmap class.
-constexpr int kClsMedium = 5, kClsLarge = 6, kClasses = 7;
-constexpr int kSortCap = 1024;            // largest window of the five ordinary sort classes
-constexpr int kMediumCap = 4096;
+// A window's class follows its number of stored entries: seven classes of the register sorting network
+// (<= 64, 128, ..., 4096 entries) and the bitmap class above.
+constexpr int kClsLarge = 7, kClasses = 8;
+constexpr int kSortCap = 4096;            // largest window that is sorted
+constexpr int kLdsBitmapFrom = 1024;      // ... when the bitmap class works in LDS
 
-__device__ __forceinline__ int window_class(int32_t cnt, int32_t large_from)
+__device__ __forceinline__ int window_class(int32_t cnt, int32_t sort_cap)
 {
+    if (cnt > sort_cap) return kClsLarge;
     if (cnt <= 64) return 0;
     if (cnt <= 128) return 1;
     if (cnt <= 256) return 2;
     if (cnt <= 512) return 3;
-    if (cnt <= kSortCap) return 4;
-    return cnt <= large_from ? kClsMedium : kClsLarge;
+    if (cnt <= 1024) return 4;
+    if (cnt <= 2048) return 5;
+    return 6;
 }
 
 // Everything the host needs from a build sits in one device block that is copied once, at the end.
@@ -215,8 +217,7 @@ __device__ __forceinline__ int length_class(int32_t deg)
 __global__ __launch_bounds__(256) void prep_kernel(int32_t n_rows, int32_t win_h, int64_t n_win,
                                                    const int32_t *__restrict__ rp, int64_t nb_rows,
                                                    int32_t *__restrict__ block_sums, int32_t *__restrict__ lists,
-                                                   int32_t *cls_count, int32_t *__restrict__ win_unique,
-                                                   int32_t large_from)
+                                                   int32_t *cls_count, int32_t *__restrict__ win_unique, int32_t sort_cap)
 {
     const int lane = threadIdx.x & (kWave - 1);
     if ((int64_t)blockIdx.x < nb_rows) {
@@ -263,18 +264,33 @@ __global__ __launch_bounds__(256) void prep_kernel(int32_t n_rows, int32_t win_h
         window_edge_range(rp, n_rows, win_h, w, &lo, &hi);
         const int32_t cnt = hi - lo;
         if (cnt == 0) win_unique[w] = 0;
-        else cls = window_class(cnt, large_from);
+        else cls = window_class(cnt, sort_cap);
     }
-    // One atomic per wavefront and class instead of one per window.
+    // One atomic per workgroup and class instead of one per window: the wavefronts count their windows of
+    // every class with ballots, one thread per class draws the workgroup's range of the list (all classes in
+    // one round trip), and every window takes its place inside it.
+    __shared__ int s_wave_cnt[256 / kWave][kClasses];
+    __shared__ int s_base[kClasses];
+    const int wave = threadIdx.x >> 6;
+    int rank_in_wave = 0;
 #pragma unroll
     for (int c = 0; c < kClasses; ++c) {
         const unsigned long long mask = __ballot(cls == c);
-        if (mask == 0) continue;
-        const int leader = __ffsll((long long)mask) - 1;
-        int base = 0;
-        if (lane == leader) base = atomicAdd(&cls_count[c], __popcll(mask));
-        base = __shfl(base, leader, kWave);
-        if (cls == c) lists[(int64_t)c * n_win + base + __popcll(mask & ((1ull << lane) - 1ull))] = (int32_t)w;
+        if (lane == 0) s_wave_cnt[wave][c] = __popcll(mask);
+        if (cls == c) rank_in_wave = __popcll(mask & ((1ull << lane) - 1ull));
+    }
+    __syncthreads();
+    if (threadIdx.x < kClasses) {
+        int t = 0;
+#pragma unroll
+        for (int w2 = 0; w2 < 256 / kWave; ++w2) t += s_wave_cnt[w2][threadIdx.x];
+        s_base[threadIdx.x] = t ? atomicAdd(&cls_count[threadIdx.x], t) : 0;
+    }
+    __syncthreads();
+    if (cls >= 0) {
+        int p = s_base[cls] + rank_in_wave;
+        for (int w2 = 0; w2 < wave; ++w2) p += s_wave_cnt[w2][cls];
+        lists[(int64_t)cls * n_win + p] = (int32_t)w;
     }
 }
 
@@ -312,9 +328,9 @@ __device__ __forceinline__ K lane_up1(K v)
 }
 
 template <int THREADS, int KPT, typename K>
-__global__ __launch_bounds__(THREADS) void sgt_window_sort_kernel(
-    int32_t n_rows, int32_t win_h, const int32_t *__restrict__ win_list, const int32_t *__restrict__ list_len,
-    const int32_t *__restrict__ rp, const int32_t *__restrict__ ci, int pos_bits,
+__device__ __forceinline__ void sort_windows(
+    int64_t first, int64_t stride, int32_t n_rows, int32_t win_h, const int32_t *__restrict__ win_list,
+    const int32_t *__restrict__ list_len, const int32_t *__restrict__ rp, const int32_t *__restrict__ ci,
     int32_t *__restrict__ edge_to_col, int32_t *__restrict__ col_to_row, int32_t *__restrict__ win_unique)
 {
     constexpr int N = THREADS * KPT;
@@ -324,9 +340,11 @@ __global__ __launch_bounds__(THREADS) void sgt_window_sort_kernel(
     __shared__ int s_tmp[WAVES + 1];
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
     const int32_t n_items = *list_len;
+    int pos_bits = 0;
+    while ((1 << pos_bits) < N) ++pos_bits;
     const K pos_mask = ((K)1 << pos_bits) - 1;
 
-    for (int64_t item = blockIdx.x; item < n_items; item += gridDim.x) {
+    for (int64_t item = first; item < n_items; item += stride) {
         const int64_t w = win_list[item];
         int32_t lo, hi;
         window_edge_range(rp, n_rows, win_h, w, &lo, &hi);
@@ -422,6 +440,36 @@ __global__ __launch_bounds__(THREADS) void sgt_window_sort_kernel(
         }
         if (tid == 0) win_unique[w] = total;
     }
+}
+
+template <int THREADS, int KPT, typename K>
+__global__ __launch_bounds__(THREADS) void sgt_window_sort_kernel(
+    int32_t n_rows, int32_t win_h, const int32_t *__restrict__ win_list, const int32_t *__restrict__ list_len,
+    const int32_t *__restrict__ rp, const int32_t *__restrict__ ci, int32_t *__restrict__ edge_to_col,
+    int32_t *__restrict__ col_to_row, int32_t *__restrict__ win_unique)
+{
+    sort_windows<THREADS, KPT, K>(blockIdx.x, gridDim.x, n_rows, win_h, win_list, list_len, rp, ci, edge_to_col,
+                                  col_to_row, win_unique);
+}
+
+// The three one-wavefront classes (up to 64, 128, 256 entries) in one launch: workgroups 0 .. g0-1 walk the
+// first class list, the next g1 the second, the rest the third (lists n_win apart, counts one apart).
+template <typename K>
+__global__ __launch_bounds__(kWave) void sgt_window_sort_small_kernel(
+    int32_t n_rows, int32_t win_h, int64_t n_win, const int32_t *__restrict__ lists,
+    const int32_t *__restrict__ cls_count, int32_t g0, int32_t g1, const int32_t *__restrict__ rp,
+    const int32_t *__restrict__ ci, int32_t *__restrict__ edge_to_col, int32_t *__restrict__ col_to_row,
+    int32_t *__restrict__ win_unique)
+{
+    const int32_t b = blockIdx.x, g2 = gridDim.x - g0 - g1;
+    if (b < g0)
+        sort_windows<kWave, 1, K>(b, g0, n_rows, win_h, lists, cls_count, rp, ci, edge_to_col, col_to_row, win_unique);
+    else if (b < g0 + g1)
+        sort_windows<kWave, 2, K>(b - g0, g1, n_rows, win_h, lists + n_win, cls_count + 1, rp, ci, edge_to_col,
+                                  col_to_row, win_unique);
+    else
+        sort_windows<kWave, 4, K>(b - g0 - g1, g2, n_rows, win_h, lists + 2 * n_win, cls_count + 2, rp, ci, edge_to_col,
+                                  col_to_row, win_unique);
 }
 
 // Large class: bitmap over the column space, one workgroup per window.  `bitmap` must be zero on
@@ -525,13 +573,15 @@ __global__ __launch_bounds__(kBitmapThreads) void sgt_window_bitmap_kernel(
 // column plus the running count in front of every group of kPfGroup words.  Setting the bits and looking
 // the ranks up are LDS operations instead of L2 atomics and gathers, and no device scratch has to be
 // cleared.  Needs lds_bitmap_bytes(n_words) <= kLdsBitmapMax.  One workgroup fills a compute unit's LDS, so
-// the kernel is launched with one workgroup per compute unit and the workgroups draw windows from a
-// counter until the class list is used up (hub windows differ in size by two orders of magnitude; the
-// counter keeps everybody busy).  The edge loops keep kEdgeUnroll column loads per thread in flight: a
-// hub window of a power-law graph has 10^5 entries, and one load per thread and round trip would make it
-// the critical path of the whole translation.
+// the kernel is launched with one workgroup per compute unit and the workgroups draw windows from a counter
+// until the class list is used up (hub windows differ in size by two orders of magnitude; the counter keeps
+// everybody busy).  The loop is software-pipelined against the chain of dependent round trips that opens a
+// window (counter -> list -> row_ptr -> columns): the counter is drawn at the start of the window before,
+// the window's id and range are fetched by one thread in two separate phases of that window, and its first
+// batch of columns is requested before the ranks of the current window are written.  The edge loops keep
+// kLdsEdgeUnroll column loads per thread in flight: a hub window of a power-law graph has 10^5 entries, and
+// one load per thread and round trip would make it the critical path of the whole translation.
 constexpr int kPfGroup = 8;
-constexpr int kLdsBitmapFrom = kSortCap;
 constexpr size_t kLdsBitmapMax = 160 * 1024 - 256;
 constexpr int kLdsEdgeUnroll = 16;
 inline size_t lds_bitmap_bytes(int64_t n_words)
@@ -547,31 +597,42 @@ __global__ __launch_bounds__(kBitmapThreads) void sgt_window_lds_bitmap_kernel(
 {
     extern __shared__ uint32_t s_words[];          // bitmap, then the group prefixes
     __shared__ int s_tmp[kBitmapWaves + 1];
-    __shared__ int s_item;
+    __shared__ int32_t s_next[4];                  // next window: list position, window id, edge range
     uint32_t *bm = s_words;
     int32_t *gpf = reinterpret_cast<int32_t *>(s_words + n_words);
     const int32_t n_items = *list_len;
     constexpr int64_t kStep = (int64_t)kBitmapThreads * kLdsEdgeUnroll;
+    // every thread owns a contiguous run of R words (R odd: the lanes of a wavefront then read different
+    // banks), so that the owners' bit counts are in column order
+    const int32_t R = ((n_words + kBitmapThreads - 1) / kBitmapThreads) | 1;
+    const int32_t kb = min((int32_t)threadIdx.x * R, n_words), ke = min(kb + R, n_words);
 
-    for (;;) {
-        if (threadIdx.x == 0) s_item = atomicAdd(ticket, 1);
-        __syncthreads();
-        const int32_t item = s_item;
-        if (item >= n_items) break;                // the same value in every thread: all leave together
-        const int64_t w = large_list[item];
-        int32_t lo, hi;
-        window_edge_range(rp, n_rows, win_h, w, &lo, &hi);
-
-        // The first batch of columns is requested before the bitmap is cleared (its latency hides under
-        // the clearing) and kept for step 4: windows of up to kStep entries read their columns once.
-        uint32_t c_first[kLdsEdgeUnroll];
-#pragma unroll
-        for (int u = 0; u < kLdsEdgeUnroll; ++u) {
-            const int64_t e = (int64_t)lo + threadIdx.x + (int64_t)u * kBitmapThreads;
-            c_first[u] = e < hi ? (uint32_t)ci[e] : 0xFFFFFFFFu;
+    if (threadIdx.x == 0) {
+        const int32_t it = atomicAdd(ticket, 1);
+        int32_t w = 0, lo = 0, hi = 0;
+        if (it < n_items) {
+            w = large_list[it];
+            window_edge_range(rp, n_rows, win_h, w, &lo, &hi);
         }
+        s_next[0] = it;
+        s_next[1] = w;
+        s_next[2] = lo;
+        s_next[3] = hi;
+    }
+    __syncthreads();
+    int32_t item = s_next[0], w = s_next[1], lo = s_next[2], hi = s_next[3];
+    uint32_t c_first[kLdsEdgeUnroll];
+#pragma unroll
+    for (int u = 0; u < kLdsEdgeUnroll; ++u) {
+        const int64_t e = (int64_t)lo + threadIdx.x + (int64_t)u * kBitmapThreads;
+        c_first[u] = e < hi ? (uint32_t)ci[e] : 0xFFFFFFFFu;
+    }
+
+    while (item < n_items) {                       // the same value in every thread: all leave together
+        int32_t next_item = 0, next_w = 0;
+        if (threadIdx.x == 0) next_item = atomicAdd(ticket, 1);
         for (int32_t k = threadIdx.x; k < n_words; k += kBitmapThreads) bm[k] = 0u;
-        __syncthreads();
+        __syncthreads();                           // also: everybody has read s_next
 
         // 1. one bit per edge
 #pragma unroll
@@ -588,31 +649,40 @@ __global__ __launch_bounds__(kBitmapThreads) void sgt_window_lds_bitmap_kernel(
             for (int u = 0; u < kLdsEdgeUnroll; ++u)
                 if (c[u] != 0xFFFFFFFFu) atomicOr(&bm[c[u] >> 5], 1u << (c[u] & 31));
         }
+        if (threadIdx.x == 0 && next_item < n_items) next_w = large_list[next_item];   // used two phases on
         __syncthreads();
 
-        // 2. every thread owns a contiguous run of R words (R odd: the lanes of a wavefront then read
-        //    different banks) and counts its bits; one workgroup-wide scan gives the count in front of
-        //    every run.  (A scan per 64 words instead costs a chain of cross-lane steps per row.)
-        const int32_t R = ((n_words + kBitmapThreads - 1) / kBitmapThreads) | 1;
-        const int32_t kb = min((int32_t)threadIdx.x * R, n_words), ke = min(kb + R, n_words);
+        // 2. bits in the words this thread owns; one workgroup-wide scan gives the count in front of them.
+        //    (A scan per 64 words instead costs a chain of cross-lane steps per row.)
         int cnt = 0;
         for (int32_t k = kb; k < ke; ++k) cnt += __popc(bm[k]);
         int total;
         int pos = block_exclusive_scan(cnt, s_tmp, &total);
+        int32_t next_lo = 0, next_hi = 0;
+        if (threadIdx.x == 0 && next_item < n_items) window_edge_range(rp, n_rows, win_h, next_w, &next_lo, &next_hi);
 
-        // 3. the count in front of every group of words, and the unique list (bit positions ascending)
+        // 3. the count in front of every group of words
         for (int32_t k = kb; k < ke; ++k) {
-            uint32_t bits = bm[k];
             if ((k % kPfGroup) == 0) gpf[k / kPfGroup] = pos;
-            while (bits) {
-                const int b = __ffs(bits) - 1;
-                bits &= bits - 1;
-                col_to_row[lo + pos] = k * 32 + b;
-                ++pos;
-            }
+            pos += __popc(bm[k]);
         }
-        if (threadIdx.x == 0) win_unique[w] = total;
+        if (threadIdx.x == 0) {
+            win_unique[w] = total;
+            s_next[0] = next_item;
+            s_next[1] = next_w;
+            s_next[2] = next_lo;
+            s_next[3] = next_hi;
+        }
         __syncthreads();
+
+        // The next window's first batch of columns is requested now; it arrives while the ranks are written.
+        const int32_t n_item = s_next[0], n_w = s_next[1], n_lo = s_next[2], n_hi = s_next[3];
+        uint32_t c_next[kLdsEdgeUnroll];
+#pragma unroll
+        for (int u = 0; u < kLdsEdgeUnroll; ++u) {
+            const int64_t e = (int64_t)n_lo + threadIdx.x + (int64_t)u * kBitmapThreads;
+            c_next[u] = e < n_hi ? (uint32_t)ci[e] : 0xFFFFFFFFu;
+        }
 
         // 4. rank of every edge's column: group prefix + the words of the group in front of it + the bits below
         auto rank_of = [&](uint32_t c) {
@@ -624,10 +694,18 @@ __global__ __launch_bounds__(kBitmapThreads) void sgt_window_lds_bitmap_kernel(
                 if (g0 + j < wi) r += __popc(bm[g0 + j]);
             return r;
         };
+        // The rank of an edge's column is also that column's place in the window's unique list, so the list is
+        // written from here: every entry of a column stores the same value at the same place, and the entries
+        // of a sorted row have rising, mostly neighbouring ranks, so these stores coalesce.  (Walking the
+        // bitmap and writing each word's columns from the thread that owns the word serialises a hub window's
+        // 10^5 stores in a few wavefronts.)
 #pragma unroll
         for (int u = 0; u < kLdsEdgeUnroll; ++u)
-            if (c_first[u] != 0xFFFFFFFFu)
-                edge_to_col[(int64_t)lo + threadIdx.x + (int64_t)u * kBitmapThreads] = rank_of(c_first[u]);
+            if (c_first[u] != 0xFFFFFFFFu) {
+                const int r = rank_of(c_first[u]);
+                edge_to_col[(int64_t)lo + threadIdx.x + (int64_t)u * kBitmapThreads] = r;
+                col_to_row[lo + r] = (int32_t)c_first[u];
+            }
         for (int64_t e0 = (int64_t)lo + kStep + threadIdx.x; e0 < hi; e0 += kStep) {
             uint32_t c[kLdsEdgeUnroll];
 #pragma unroll
@@ -638,10 +716,20 @@ __global__ __launch_bounds__(kBitmapThreads) void sgt_window_lds_bitmap_kernel(
 #pragma unroll
             for (int u = 0; u < kLdsEdgeUnroll; ++u) {
                 const int64_t e = e0 + (int64_t)u * kBitmapThreads;
-                if (c[u] != 0xFFFFFFFFu) edge_to_col[e] = rank_of(c[u]);
+                if (c[u] != 0xFFFFFFFFu) {
+                    const int r = rank_of(c[u]);
+                    edge_to_col[e] = r;
+                    col_to_row[lo + r] = (int32_t)c[u];
+                }
             }
         }
-        __syncthreads();                           // the bitmap and s_item are reused by the next window
+        item = n_item;
+        w = n_w;
+        lo = n_lo;
+        hi = n_hi;
+#pragma unroll
+        for (int u = 0; u < kLdsEdgeUnroll; ++u) c_first[u] = c_next[u];
+        __syncthreads();                           // ranks are read before the bitmap is cleared again
     }
 }
 
@@ -679,20 +767,53 @@ __device__ __forceinline__ int block_scan_sequence(int64_t n, Load load, Store s
 
 constexpr int kBands = 2 * kXcds;
 
-__global__ __launch_bounds__(1024) void plan_scan_kernel(int64_t nb, const int32_t *__restrict__ block_sums,
+// phase 0 (needs row_ptr only): offsets of the split rows and their segments, the bands of the die table.
+// phase 1 (needs U): offsets of the single-segment rows, the rest of the result block.
+__global__ __launch_bounds__(1024) void plan_scan_kernel(int phase, int64_t nb, const int32_t *__restrict__ block_sums,
                                                          int64_t nnz, int64_t n_win,
                                                          const int32_t *__restrict__ win_unique_ptr,
                                                          int32_t *__restrict__ long_off, int32_t *__restrict__ slot_off,
                                                          int32_t *__restrict__ tail_off, BuildInfo *info,
-                                                         int32_t *__restrict__ long_slot_ptr)
+                                                         int32_t *__restrict__ long_slot_ptr,
+                                                         const int32_t *__restrict__ win_unique,
+                                                         int32_t *__restrict__ win_unique_ptr_out)
 {
     __shared__ int tmp[1024 / kWave + 1];
-    const int64_t U = win_unique_ptr[n_win];
+    if (phase == 0) {
+        const int n_long = block_scan_sequence(nb, [&](int64_t i) { return block_sums[i]; },
+                                               [&](int64_t i, int v) { long_off[i] = v; }, tmp);
+        const int n_slots = block_scan_sequence(nb, [&](int64_t i) { return block_sums[nb + i]; },
+                                                [&](int64_t i, int v) { slot_off[i] = v; }, tmp);
+        if (threadIdx.x == 0) {
+            info->n_long = n_long;
+            info->n_slots = n_slots;
+            long_slot_ptr[n_long] = n_slots;
+            // Die l walks bands l and 2 * kXcds - 1 - l of the split rows' segments (sorted by start column, so
+            // a band is a range of columns: its X rows stay in that die's L2, and pairing a band of popular
+            // columns with a band of rare ones spreads the L2 misses evenly), then its share of the tail.
+            for (int l = 0; l < kXcds; ++l) {
+                const int b2 = kBands - 1 - l;
+                int32_t *t = info->lane_tab + kLaneTabStride * l;
+                t[0] = (int32_t)((int64_t)n_slots * l / kBands);
+                t[1] = (int32_t)((int64_t)n_slots * (l + 1) / kBands) - t[0];
+                t[2] = (int32_t)((int64_t)n_slots * b2 / kBands);
+                t[3] = (int32_t)((int64_t)n_slots * (b2 + 1) / kBands) - t[2];
+                t[4] = n_slots;
+            }
+        }
+        return;
+    }
+    // U: the exclusive scan of the windows' unique counts happens here unless it was done beforehand
+    // (win_unique == nullptr; graphs with so many windows that one workgroup would be slow).
+    int64_t U;
+    if (win_unique) {
+        U = block_scan_sequence(n_win, [&](int64_t i) { return win_unique[i]; },
+                                [&](int64_t i, int v) { win_unique_ptr_out[i] = v; }, tmp);
+        if (threadIdx.x == 0) win_unique_ptr_out[n_win] = (int32_t)U;
+    } else {
+        U = win_unique_ptr[n_win];
+    }
     const int sort_tail = 4 * U > 3 * (nnz > 0 ? nnz : 1) ? 1 : 0;
-    const int n_long = block_scan_sequence(nb, [&](int64_t i) { return block_sums[i]; },
-                                           [&](int64_t i, int v) { long_off[i] = v; }, tmp);
-    const int n_slots = block_scan_sequence(nb, [&](int64_t i) { return block_sums[nb + i]; },
-                                            [&](int64_t i, int v) { slot_off[i] = v; }, tmp);
     int n_single;
     if (sort_tail) {
         // class-major: all blocks of class 0, then all blocks of class 1, ...
@@ -709,117 +830,200 @@ __global__ __launch_bounds__(1024) void plan_scan_kernel(int64_t nb, const int32
                                        [&](int64_t i, int v) { tail_off[i] = v; }, tmp);
     }
     if (threadIdx.x == 0) {
-        info->n_seg = n_slots + n_single;
-        info->n_long = n_long;
-        info->n_slots = n_slots;
+        info->n_seg = info->n_slots + n_single;
         info->sort_tail = sort_tail;
         info->total_unique = (int32_t)U;
-        long_slot_ptr[n_long] = n_slots;
-        // Die l walks bands l and 2 * kXcds - 1 - l of the split rows' segments (sorted by start column, so
-        // a band is a range of columns: its X rows stay in that die's L2, and pairing a band of popular
-        // columns with a band of rare ones spreads the L2 misses evenly), then its share of the tail.
-        for (int l = 0; l < kXcds; ++l) {
-            const int b2 = kBands - 1 - l;
-            int32_t *t = info->lane_tab + kLaneTabStride * l;
-            t[0] = (int32_t)((int64_t)n_slots * l / kBands);
-            t[1] = (int32_t)((int64_t)n_slots * (l + 1) / kBands) - t[0];
-            t[2] = (int32_t)((int64_t)n_slots * b2 / kBands);
-            t[3] = (int32_t)((int64_t)n_slots * (b2 + 1) / kBands) - t[2];
-            t[4] = n_slots;
-            t[5] = n_single;
-        }
+        for (int l = 0; l < kXcds; ++l) info->lane_tab[kLaneTabStride * l + 5] = n_single;
     }
 }
 
 // ---- gather plan, step 3: the segment list -----------------------------------------------------------
-// Single-segment rows go straight to their final place (stable inside a length class: block offset + the
-// rows of the same class in front of this one inside the block, counted with wavefront ballots).  Split
-// rows get their entry in long_row / long_slot_ptr; their segments ("slots", numbered in row order) are
-// written with the start column as sort key by all threads of the workgroup together -- a hub row has
-// hundreds of segments.
-constexpr int kSegSortBits = 12;       // the leading bits of a start column are the sort key
+// A thread takes four consecutive rows of its workgroup's block.  Single-segment rows go straight to their
+// final place (stable inside a length class: block offset + the rows of the same class in front of this one
+// inside the block).  Split rows get their entry in long_row / long_slot_ptr; their segments ("slots",
+// numbered in row order) are written with the start column as sort key by all threads of the workgroup
+// together -- a hub row has hundreds of segments.  One workgroup-wide scan carries all the counts: split
+// rows, their segments, and the eight class counts packed two to a word (a block has 1024 rows).
+// Sort key of a split row's segment: its start column at a relative resolution of 1/8 (the column itself
+// below 16, else 8 steps per power of two) -- monotone in the column, at most 8 bits, so one pass of the
+// radix sort orders the segments.  Skewed graphs keep their popular columns at small ids, where this key
+// is fine-grained; equal steps in the column id would put a third of all segments into the first bucket.
+constexpr int kSegKeyBits = 8;
+__device__ __forceinline__ int32_t seg_sort_key(uint32_t c)
+{
+    if (c < 16u) return (int32_t)c;
+    const int e = 31 - __clz(c);
+    return 16 + (e - 4) * 8 + (int32_t)((c >> (e - 3)) & 7u);
+}
+constexpr int kFillVals = 2 + kTailClasses / 2;
 
+struct FillCounts {
+    int v[kFillVals];
+};
+
+__device__ __forceinline__ FillCounts block_exclusive_scan_counts(const FillCounts &in, int (*tmp)[kFillVals],
+                                                                  FillCounts *total)
+{
+    const int lane = threadIdx.x & (kWave - 1), wid = threadIdx.x >> 6;
+    constexpr int NW = 256 / kWave;
+    FillCounts incl = in;
+#pragma unroll
+    for (int off = 1; off < kWave; off <<= 1) {
+#pragma unroll
+        for (int k = 0; k < kFillVals; ++k) {
+            const int t = __shfl_up(incl.v[k], off, kWave);
+            if (lane >= off) incl.v[k] += t;
+        }
+    }
+    if (lane == kWave - 1)
+#pragma unroll
+        for (int k = 0; k < kFillVals; ++k) tmp[wid][k] = incl.v[k];
+    __syncthreads();
+    FillCounts res;
+#pragma unroll
+    for (int k = 0; k < kFillVals; ++k) {
+        int before = 0, all = 0;
+#pragma unroll
+        for (int w2 = 0; w2 < NW; ++w2) {
+            const int t = tmp[w2][k];
+            if (w2 < wid) before += t;
+            all += t;
+        }
+        res.v[k] = before + incl.v[k] - in.v[k];
+        total->v[k] = all;
+    }
+    return res;
+}
+
+// phase 0: split rows and their slots (needs row_ptr only); phase 1: single-segment rows (needs sort_tail).
 __global__ __launch_bounds__(256) void seg_fill_kernel(
-    int32_t n_rows, const int32_t *__restrict__ rp, const int32_t *__restrict__ ci, const BuildInfo *info,
+    int phase, int32_t n_rows, const int32_t *__restrict__ rp, const int32_t *__restrict__ ci, const BuildInfo *info,
     int64_t nb, const int32_t *__restrict__ long_off, const int32_t *__restrict__ slot_off,
-    const int32_t *__restrict__ tail_off, int key_shift, int32_t *__restrict__ seg_row,
+    const int32_t *__restrict__ tail_off, int32_t *__restrict__ seg_row,
     int32_t *__restrict__ seg_ebeg, int32_t *__restrict__ seg_dst, int32_t *__restrict__ long_row,
     int32_t *__restrict__ long_slot_ptr, int32_t *__restrict__ slot_row, int32_t *__restrict__ slot_ebeg,
     int32_t *__restrict__ slot_key)
 {
-    __shared__ int s_tmp[256 / kWave + 1];
-    __shared__ int s_wave_cnt[256 / kWave][kTailClasses];
-    __shared__ int s_tail_base[kTailClasses];      // final position of the block's next row of each class
-    __shared__ int32_t s_lrow[256], s_le0[256], s_lslot[257];
-    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
-    const int sort_tail = info->sort_tail;
+    constexpr int RPT = kRowBlock / 256;           // rows per thread
+    __shared__ int s_tmp[256 / kWave][kFillVals];
+    __shared__ int32_t s_lrow[kRowBlock], s_le0[kRowBlock], s_lslot[kRowBlock + 1];
+    const int sort_tail = phase == 1 ? info->sort_tail : 0;
     const int32_t n_slots = info->n_slots;
-    if (threadIdx.x < kTailClasses)
-        s_tail_base[threadIdx.x] = n_slots + (sort_tail ? tail_off[(int64_t)threadIdx.x * nb + blockIdx.x]
-                                                        : tail_off[blockIdx.x]);
-    int32_t long_base = long_off[blockIdx.x], slot_base = slot_off[blockIdx.x];
-    __syncthreads();
+    const int32_t long_base = long_off[blockIdx.x], slot_base = slot_off[blockIdx.x];
 
-    for (int round = 0; round < kRowBlock / 256; ++round) {
-        const int64_t r = (int64_t)blockIdx.x * kRowBlock + round * 256 + threadIdx.x;
-        int32_t e0 = 0, deg = 0;
-        if (r < n_rows) {
-            e0 = rp[r];
-            deg = rp[r + 1] - e0;
+    const int64_t r0 = (int64_t)blockIdx.x * kRowBlock + (int64_t)threadIdx.x * RPT;
+    int32_t e0[RPT], deg[RPT];
+    int cls[RPT];
+    FillCounts mine;
+#pragma unroll
+    for (int k = 0; k < kFillVals; ++k) mine.v[k] = 0;
+#pragma unroll
+    for (int k = 0; k < RPT; ++k) {
+        e0[k] = 0;
+        deg[k] = 0;
+        cls[k] = -1;
+        if (r0 + k < n_rows) {
+            e0[k] = rp[r0 + k];
+            deg[k] = rp[r0 + k + 1] - e0[k];
+            if (deg[k] > kSegLen) {
+                mine.v[0] += 1;
+                mine.v[1] += (deg[k] + kSegLen - 1) / kSegLen;
+            } else {
+                cls[k] = sort_tail ? length_class(deg[k]) : 0;
+#pragma unroll
+                for (int c = 0; c < kTailClasses; ++c)
+                    if (cls[k] == c) mine.v[2 + c / 2] += 1 << (16 * (c & 1));
+            }
         }
-        const bool is_long = deg > kSegLen;
-        const int segs = is_long ? (deg + kSegLen - 1) / kSegLen : 0;
-        int n_lrows, n_lsegs;
-        const int lrank = block_exclusive_scan(is_long ? 1 : 0, s_tmp, &n_lrows);
-        const int srank = block_exclusive_scan(segs, s_tmp, &n_lsegs);
-        if (is_long) {
-            long_row[long_base + lrank] = (int32_t)r;
-            long_slot_ptr[long_base + lrank] = slot_base + srank;
-            s_lrow[lrank] = (int32_t)r;
-            s_le0[lrank] = e0;
-            s_lslot[lrank] = srank;
-        }
-        if (threadIdx.x == 0) s_lslot[n_lrows] = n_lsegs;
+    }
+    FillCounts total;
+    const FillCounts before = block_exclusive_scan_counts(mine, s_tmp, &total);
 
-        const int cls = (r < n_rows && !is_long) ? (sort_tail ? length_class(deg) : 0) : -1;
-        int rank_in_wave = 0;
+    // Single-segment rows are put in (class, row) order in LDS first, so that the workgroup writes its piece
+    // of every class as one contiguous run.
+    __shared__ int32_t s_trow[kRowBlock], s_te0[kRowBlock];
+    __shared__ int s_cstart[kTailClasses + 1];
+    int cstart[kTailClasses];
+    {
+        int run = 0;
 #pragma unroll
         for (int c = 0; c < kTailClasses; ++c) {
-            const unsigned long long mask = __ballot(cls == c);
-            if (lane == 0) s_wave_cnt[wave][c] = __popcll(mask);
-            if (cls == c) rank_in_wave = __popcll(mask & ((1ull << lane) - 1ull));
+            cstart[c] = run;
+            run += (total.v[2 + c / 2] >> (16 * (c & 1))) & 0xFFFF;
         }
-        __syncthreads();
-        if (cls >= 0) {
-            int32_t p = s_tail_base[cls] + rank_in_wave;
-            for (int w2 = 0; w2 < wave; ++w2) p += s_wave_cnt[w2][cls];
-            seg_row[p] = (int32_t)r;
-            seg_ebeg[p] = e0;
-            seg_dst[p] = -1;
+        if (threadIdx.x == 0) {
+#pragma unroll
+            for (int c = 0; c < kTailClasses; ++c) s_cstart[c] = cstart[c];
+            s_cstart[kTailClasses] = run;
         }
-        // the slots of this round's split rows, one per thread and step
-        for (int32_t sl = threadIdx.x; sl < n_lsegs; sl += 256) {
-            int a = 0, b = n_lrows;                    // last split row whose first slot is <= sl
+    }
+    int lrank = before.v[0], srank = before.v[1];
+    int seen[kTailClasses];
+#pragma unroll
+    for (int c = 0; c < kTailClasses; ++c) seen[c] = cstart[c] + ((before.v[2 + c / 2] >> (16 * (c & 1))) & 0xFFFF);
+#pragma unroll
+    for (int k = 0; k < RPT; ++k) {
+        if (r0 + k >= n_rows) continue;
+        if (cls[k] < 0) {
+            if (phase != 0) continue;
+            long_row[long_base + lrank] = (int32_t)(r0 + k);
+            long_slot_ptr[long_base + lrank] = slot_base + srank;
+            s_lrow[lrank] = (int32_t)(r0 + k);
+            s_le0[lrank] = e0[k];
+            s_lslot[lrank] = srank;
+            ++lrank;
+            srank += (deg[k] + kSegLen - 1) / kSegLen;
+        } else if (phase == 1) {
+            int lp = 0;
+#pragma unroll
+            for (int c = 0; c < kTailClasses; ++c)
+                if (cls[k] == c) lp = seen[c]++;
+            s_trow[lp] = (int32_t)(r0 + k);
+            s_te0[lp] = e0[k];
+        }
+    }
+    const int n_lrows = total.v[0], n_lsegs = total.v[1];
+    if (threadIdx.x == 0) s_lslot[n_lrows] = n_lsegs;
+    __syncthreads();
+    for (int i = threadIdx.x; phase == 1 && i < s_cstart[kTailClasses]; i += 256) {
+        int c = 0;
+#pragma unroll
+        for (int c2 = 1; c2 < kTailClasses; ++c2)
+            if (i >= s_cstart[c2]) c = c2;
+        const int64_t tb = sort_tail ? tail_off[(int64_t)c * nb + blockIdx.x] : tail_off[blockIdx.x];
+        const int64_t p = (int64_t)n_slots + tb + (i - s_cstart[c]);
+        seg_row[p] = s_trow[i];
+        seg_ebeg[p] = s_te0[i];
+        seg_dst[p] = -1;
+    }
+    // the slots of the block's split rows: four per thread and step, their start columns gathered together (the
+    // block that holds the hub rows of a power-law graph has thousands of slots)
+    for (int32_t s0 = threadIdx.x; phase == 0 && s0 < n_lsegs; s0 += 4 * 256) {
+        int32_t eb[4], row[4];
+        uint32_t col[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int32_t sl = s0 + u * 256;
+            eb[u] = -1;
+            if (sl >= n_lsegs) continue;
+            int a = 0, b = n_lrows;                // last split row whose first slot is <= sl
             while (b - a > 1) {
                 const int mid = (a + b) >> 1;
                 if (s_lslot[mid] <= sl) a = mid; else b = mid;
             }
-            const int32_t eb = s_le0[a] + (sl - s_lslot[a]) * kSegLen;
-            const int32_t g = slot_base + sl;
-            slot_row[g] = s_lrow[a];
-            slot_ebeg[g] = eb;
-            slot_key[g] = ci[eb] >> key_shift;
+            eb[u] = s_le0[a] + (sl - s_lslot[a]) * kSegLen;
+            row[u] = s_lrow[a];
         }
-        __syncthreads();
-        if (threadIdx.x < kTailClasses) {
-            int t = 0;
 #pragma unroll
-            for (int w2 = 0; w2 < 256 / kWave; ++w2) t += s_wave_cnt[w2][threadIdx.x];
-            s_tail_base[threadIdx.x] += t;
+        for (int u = 0; u < 4; ++u) col[u] = eb[u] >= 0 ? (uint32_t)ci[eb[u]] : 0u;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            if (eb[u] < 0) continue;
+            const int32_t g = slot_base + s0 + u * 256;
+            slot_row[g] = row[u];
+            slot_ebeg[g] = eb[u];
+            slot_key[g] = seg_sort_key(col[u]);
         }
-        long_base += n_lrows;
-        slot_base += n_lsegs;
-        __syncthreads();
     }
 }
 
@@ -954,7 +1158,7 @@ int64_t scan_workspace_elems(int64_t n) { return ceil_div(std::max<int64_t>(n, 1
 int exclusive_scan_i32(const int32_t *d_in, int32_t *d_out, int64_t n, int32_t *d_work, hipStream_t s)
 {
     // Up to a few thousand elements per thread-round a single workgroup is quicker than three launches.
-    if (n <= 4 * kScanBlock) {
+    if (n <= 8 * kScanBlock) {
         hipLaunchKernelGGL(scan_single_kernel, dim3(1), dim3(1024), 0, s, d_in, d_out, n);
         return launch_status("scan_single_kernel");
     }
@@ -1023,18 +1227,70 @@ static void launch_sort_class(const tcg_meta *m, int cls, int64_t max_windows, i
 {
     if (max_windows <= 0) return;
     const unsigned grid = (unsigned)std::min<int64_t>(max_windows, grid_cap);
-    int pos_bits = 0;
-    while ((1 << pos_bits) < THREADS * KPT) ++pos_bits;
     const int32_t *list = lists + (int64_t)cls * m->n_win;
     if (wide_keys)
         hipLaunchKernelGGL((sgt_window_sort_kernel<THREADS, KPT, uint64_t>), dim3(grid), dim3(THREADS), 0, s, m->n_rows,
-                           m->win_h, list, info->cls_count + cls, m->d_row_ptr, m->d_col_idx, pos_bits,
-                           m->d_edge_to_col, m->d_col_to_row, win_unique);
+                           m->win_h, list, info->cls_count + cls, m->d_row_ptr, m->d_col_idx, m->d_edge_to_col,
+                           m->d_col_to_row, win_unique);
     else
         hipLaunchKernelGGL((sgt_window_sort_kernel<THREADS, KPT, uint32_t>), dim3(grid), dim3(THREADS), 0, s, m->n_rows,
-                           m->win_h, list, info->cls_count + cls, m->d_row_ptr, m->d_col_idx, pos_bits,
+                           m->win_h, list, info->cls_count + cls, m->d_row_ptr, m->d_col_idx, m->d_edge_to_col,
+                           m->d_col_to_row, win_unique);
+}
+
+static void launch_sort_small(const tcg_meta *m, int64_t most0, int64_t most1, int64_t most2, bool wide_keys,
+                              const int32_t *lists, const BuildInfo *info, int32_t *win_unique, hipStream_t s)
+{
+    if (most0 <= 0) return;
+    const int32_t g0 = (int32_t)std::min<int64_t>(most0, 12288), g1 = (int32_t)std::min<int64_t>(std::max<int64_t>(most1, 1), 4096),
+                  g2 = (int32_t)std::min<int64_t>(std::max<int64_t>(most2, 1), 4096);
+    if (wide_keys)
+        hipLaunchKernelGGL(sgt_window_sort_small_kernel<uint64_t>, dim3((unsigned)(g0 + g1 + g2)), dim3(kWave), 0, s,
+                           m->n_rows, m->win_h, m->n_win, lists, info->cls_count, g0, g1, m->d_row_ptr, m->d_col_idx,
+                           m->d_edge_to_col, m->d_col_to_row, win_unique);
+    else
+        hipLaunchKernelGGL(sgt_window_sort_small_kernel<uint32_t>, dim3((unsigned)(g0 + g1 + g2)), dim3(kWave), 0, s,
+                           m->n_rows, m->win_h, m->n_win, lists, info->cls_count, g0, g1, m->d_row_ptr, m->d_col_idx,
                            m->d_edge_to_col, m->d_col_to_row, win_unique);
 }
+
+// Two more streams per device.  After the first kernel a translation has three independent branches: the
+// bitmap-class kernel (its hub windows make it the longest kernel, while it needs one workgroup per compute
+// unit only), the sorted classes, and the part of the gather plan that depends on row_ptr alone (a chain of
+// small launches).  They run side by side and meet again before U is formed.  Default priority, created once.
+struct SideStream {
+    hipStream_t stream = nullptr, plan_stream = nullptr;
+    hipEvent_t fork = nullptr, join = nullptr, plan_join = nullptr;
+};
+static std::mutex g_side_mu;
+static SideStream g_side[64];
+
+static int side_stream(int device, SideStream **out)
+{
+    if (device < 0 || device >= 64) return TCG_EINVAL;
+    std::lock_guard<std::mutex> lock(g_side_mu);
+    SideStream &sd = g_side[device];
+    if (!sd.stream) {
+        TCG_HIP(hipStreamCreateWithFlags(&sd.stream, hipStreamNonBlocking));
+        TCG_HIP(hipStreamCreateWithFlags(&sd.plan_stream, hipStreamNonBlocking));
+        TCG_HIP(hipEventCreateWithFlags(&sd.fork, hipEventDisableTiming));
+        TCG_HIP(hipEventCreateWithFlags(&sd.join, hipEventDisableTiming));
+        TCG_HIP(hipEventCreateWithFlags(&sd.plan_join, hipEventDisableTiming));
+    }
+    *out = &sd;
+    return TCG_OK;
+}
+
+// Waits for the side stream when the scope ends (a no-op on the normal path, where the main stream has
+// already waited for it; it matters when an error return leaves its kernel in flight).
+struct SideGuard {
+    hipStream_t s = nullptr, s2 = nullptr;
+    ~SideGuard()
+    {
+        if (s) (void)hipStreamSynchronize(s);
+        if (s2) (void)hipStreamSynchronize(s2);
+    }
+};
 
 // Host side of a translation.  Every size the kernels need is either known from (n_rows, nnz) or read by
 // them from device memory, so everything is enqueued back to back and the host waits once, at the end,
@@ -1052,11 +1308,12 @@ int sgt_build_impl(tcg_meta *m, int validate, hipStream_t s)
     const int64_t slot_bound = nnz / kSegLen + long_bound;
     const int64_t seg_bound = (int64_t)n + slot_bound;
     if (seg_bound >= (int64_t)INT32_MAX) return TCG_ERANGE;
-    // Windows above large_from entries form the bitmap class.  When the bitmap over the column space fits
-    // in LDS it is cheaper than sorting from kLdsBitmapFrom entries on, so the class starts there.
+    // Windows above kSortCap entries form the bitmap class: in LDS when the bitmap over the column space fits.
     const int64_t n_words = ceil_div(m->n_cols, 32);
     const bool lds_bitmap = lds_bitmap_bytes(n_words) <= kLdsBitmapMax;
-    const int32_t large_from = lds_bitmap ? kLdsBitmapFrom : kMediumCap;
+    // The LDS bitmap is quicker than sorting from about a thousand entries on; the bitmap in device memory
+    // only beyond the largest sorted class.
+    const int32_t sort_cap = lds_bitmap ? kLdsBitmapFrom : kSortCap;
     int col_bits = 1;
     while (col_bits < 31 && ((int64_t)1 << col_bits) < (int64_t)m->n_cols) ++col_bits;
 
@@ -1135,27 +1392,27 @@ int sgt_build_impl(tcg_meta *m, int validate, hipStream_t s)
     // Per-row-block counts of the gather plan and the window classes (both depend on row_ptr only).
     if (nb_rows + ceil_div(n_win, 256) > 0) {
         hipLaunchKernelGGL(prep_kernel, dim3((unsigned)(nb_rows + ceil_div(n_win, 256))), dim3(256), 0, s, n, m->win_h,
-                           n_win, m->d_row_ptr, nb_rows, block_sums, lists, info->cls_count, win_unique, large_from);
+                           n_win, m->d_row_ptr, nb_rows, block_sums, lists, info->cls_count, win_unique, sort_cap);
         TCG_TRY(launch_status("prep_kernel"));
     }
 
-    // Per-window translation, one launch per size class.  A class with at least `lo` entries per window has at
-    // most nnz / lo windows; the kernels read the real count on the device.
-    {
-        const bool wide = col_bits + 10 > 31;              // column and position do not fit 31 bits: 64-bit keys
-        auto most = [&](int64_t least_entries) { return std::min<int64_t>(n_win, nnz / least_entries); };
-        launch_sort_class<64, 1>(m, 0, most(1), 8192, col_bits + 6 > 31, lists, info, win_unique, s);
-        launch_sort_class<64, 2>(m, 1, most(65), 8192, col_bits + 7 > 31, lists, info, win_unique, s);
-        launch_sort_class<64, 4>(m, 2, most(129), 8192, col_bits + 8 > 31, lists, info, win_unique, s);
-        launch_sort_class<128, 4>(m, 3, most(257), 4096, col_bits + 9 > 31, lists, info, win_unique, s);
-        launch_sort_class<256, 4>(m, 4, most(513), 2048, wide, lists, info, win_unique, s);
-        if (!lds_bitmap)
-            launch_sort_class<1024, 4>(m, kClsMedium, most(kSortCap + 1), 512, col_bits + 12 > 31, lists, info,
-                                       win_unique, s);
-        TCG_TRY(launch_status("sgt_window_sort_kernel"));
-    }
+    // Fork: the caller's stream keeps the sorted classes; the bitmap class and the first part of the gather plan
+    // go to the library's two side streams (see SideStream).
     ScopedFree bitmap_guard{nullptr, s};
-    const int64_t large_most = std::min<int64_t>(n_win, nnz / ((int64_t)large_from + 1));
+    SideGuard side_guard;
+    SideStream *side = nullptr;
+    TCG_TRY(side_stream(m->device, &side));
+    {
+        std::lock_guard<std::mutex> lock(g_side_mu);
+        TCG_HIP(hipEventRecord(side->fork, s));
+        TCG_HIP(hipStreamWaitEvent(side->stream, side->fork, 0));
+        TCG_HIP(hipStreamWaitEvent(side->plan_stream, side->fork, 0));
+    }
+    side_guard.s = side->stream;
+    side_guard.s2 = side->plan_stream;
+
+    // Branch 1: the bitmap class (its hub windows take longest, so it starts first).
+    const int64_t large_most = std::min<int64_t>(n_win, nnz / ((int64_t)sort_cap + 1));
     if (large_most > 0 && lds_bitmap) {
         const size_t lds = lds_bitmap_bytes(n_words);
         static bool raised = false;       // more than 64 KB of dynamic LDS has to be asked for once
@@ -1169,16 +1426,17 @@ int sgt_build_impl(tcg_meta *m, int validate, hipStream_t s)
                           n_cu <= 0))
             n_cu = 256;
         const unsigned grid = (unsigned)std::min<int64_t>(large_most, n_cu);
-        hipLaunchKernelGGL(sgt_window_lds_bitmap_kernel, dim3(grid), dim3(kBitmapThreads), lds, s, n, m->win_h,
+        hipLaunchKernelGGL(sgt_window_lds_bitmap_kernel, dim3(grid), dim3(kBitmapThreads), lds, side->stream, n, m->win_h,
                            (int32_t)n_words, lists + (int64_t)kClsLarge * n_win, info->cls_count + kClsLarge, &info->ticket,
                            m->d_row_ptr, m->d_col_idx, m->d_edge_to_col, m->d_col_to_row, win_unique);
         TCG_TRY(launch_status("sgt_window_lds_bitmap_kernel"));
     } else if (large_most > 0) {
         // Column space too wide for LDS: the bitmap lives in device scratch, sized by the number of windows
         // in the class, which the host has to fetch first (the one extra wait of this rare path).
+        hipStream_t bs = side->stream;
         int32_t n_large = 0;
-        TCG_HIP(hipMemcpyAsync(&n_large, info->cls_count + kClsLarge, sizeof(int32_t), hipMemcpyDeviceToHost, s));
-        TCG_HIP(hipStreamSynchronize(s));
+        TCG_HIP(hipMemcpyAsync(&n_large, info->cls_count + kClsLarge, sizeof(int32_t), hipMemcpyDeviceToHost, bs));
+        TCG_HIP(hipStreamSynchronize(bs));
         if (n_large > 0) {
             const int64_t budget_words = (int64_t)(128ll << 20) / 4;  // 128 MiB per scratch array
             const int64_t batch = std::max<int64_t>(1, std::min<int64_t>(n_large, budget_words / n_words));
@@ -1188,8 +1446,8 @@ int sgt_build_impl(tcg_meta *m, int validate, hipStream_t s)
             int32_t *prefix = reinterpret_cast<int32_t *>(bitmap + batch * n_words);
             for (int64_t b0 = 0; b0 < n_large; b0 += batch) {
                 const int64_t nb = std::min<int64_t>(batch, n_large - b0);
-                TCG_HIP(hipMemsetAsync(bitmap, 0, (size_t)(nb * n_words) * sizeof(uint32_t), s));
-                hipLaunchKernelGGL(sgt_window_bitmap_kernel, dim3((unsigned)nb), dim3(kBitmapThreads), 0, s, n,
+                TCG_HIP(hipMemsetAsync(bitmap, 0, (size_t)(nb * n_words) * sizeof(uint32_t), bs));
+                hipLaunchKernelGGL(sgt_window_bitmap_kernel, dim3((unsigned)nb), dim3(kBitmapThreads), 0, bs, n,
                                    m->win_h, n_words, lists + (int64_t)kClsLarge * n_win + b0, m->d_row_ptr, m->d_col_idx,
                                    bitmap, prefix, m->d_edge_to_col, m->d_col_to_row, win_unique);
                 TCG_TRY(launch_status("sgt_window_bitmap_kernel"));
@@ -1197,27 +1455,63 @@ int sgt_build_impl(tcg_meta *m, int validate, hipStream_t s)
         }
     }
 
-    TCG_TRY(exclusive_scan_i32(win_unique, m->d_win_unique_ptr, n_win, scan_work, s));
-
-    // Gather plan: offsets, then the segment list in its final order (see plan_scan_kernel).
-    hipLaunchKernelGGL(plan_scan_kernel, dim3(1), dim3(1024), 0, s, nb_rows, block_sums, nnz, n_win,
-                       m->d_win_unique_ptr, long_off, slot_off, tail_off, info, m->d_long_slot_ptr);
-    if (nb_rows > 0) {
-        const int key_shift = col_bits > kSegSortBits ? col_bits - kSegSortBits : 0;   // the leading bits are enough
-        hipLaunchKernelGGL(seg_fill_kernel, dim3((unsigned)nb_rows), dim3(256), 0, s, n, m->d_row_ptr, m->d_col_idx, info,
-                           nb_rows, long_off, slot_off, tail_off, key_shift, m->d_seg_row, m->d_seg_ebeg, m->d_seg_dst,
-                           m->d_long_row, m->d_long_slot_ptr, slot_row, slot_ebeg, slot_key);
+    // Branch 2: the gather plan as far as it needs row_ptr only -- split rows, their segments sorted by start
+    // column (segments that run one after the other on a die then read neighbouring -- on skewed graphs largely
+    // the same -- X rows).
+    {
+        hipStream_t ps = side->plan_stream;
+        hipLaunchKernelGGL(plan_scan_kernel, dim3(1), dim3(1024), 0, ps, 0, nb_rows, block_sums, nnz, n_win,
+                           m->d_win_unique_ptr, long_off, slot_off, tail_off, info, m->d_long_slot_ptr,
+                           (const int32_t *)nullptr, (int32_t *)nullptr);
+        if (nb_rows > 0) {
+            hipLaunchKernelGGL(seg_fill_kernel, dim3((unsigned)nb_rows), dim3(256), 0, ps, 0, n, m->d_row_ptr, m->d_col_idx,
+                               info, nb_rows, long_off, slot_off, tail_off, m->d_seg_row, m->d_seg_ebeg, m->d_seg_dst,
+                               m->d_long_row, m->d_long_slot_ptr, slot_row, slot_ebeg, slot_key);
+            TCG_TRY(launch_status("plan kernels"));
+            const bool sorted = sort_bytes > 0 && slot_bound > 1;
+            if (sorted)
+                TCG_TRY(radix_sort_pairs(slot_key, nullptr, slot_bound, &info->n_slots, kSegKeyBits, key_sorted, order,
+                                         sort_scratch, ps));
+            hipLaunchKernelGGL(seg_permute_kernel, dim3((unsigned)ceil_div(slot_bound, 256)), dim3(256), 0, ps, info,
+                               sorted ? order : (const int32_t *)nullptr, slot_row, slot_ebeg, m->d_seg_row, m->d_seg_ebeg,
+                               m->d_seg_dst);
+        }
         TCG_TRY(launch_status("plan kernels"));
-        // Split rows' segments by start column: segments that run one after the other on a die then read
-        // neighbouring -- on skewed graphs largely the same -- X rows.
-        const bool sorted = sort_bytes > 0 && slot_bound > 1;
-        if (sorted)
-            TCG_TRY(radix_sort_pairs(slot_key, nullptr, slot_bound, &info->n_slots, col_bits - key_shift, key_sorted, order,
-                                     sort_scratch, s));
-        hipLaunchKernelGGL(seg_permute_kernel, dim3((unsigned)ceil_div(slot_bound, 256)), dim3(256), 0, s, info,
-                           sorted ? order : (const int32_t *)nullptr, slot_row, slot_ebeg, m->d_seg_row, m->d_seg_ebeg,
-                           m->d_seg_dst);
     }
+
+    // Branch 3: the sorted classes, one launch each beyond the three smallest (a column and a position inside
+    // the window must fit 32 bits for 32-bit sort keys, else 64-bit ones).  A class with at least `lo` entries
+    // per window has at most nnz / lo windows; the kernels read the real count on the device.
+    {
+        auto most = [&](int64_t least_entries) { return std::min<int64_t>(n_win, nnz / least_entries); };
+        launch_sort_small(m, most(1), most(65), most(129), col_bits + 8 > 32, lists, info, win_unique, s);
+        launch_sort_class<128, 4>(m, 3, most(257), 4096, col_bits + 9 > 32, lists, info, win_unique, s);
+        launch_sort_class<256, 4>(m, 4, most(513), 2048, col_bits + 10 > 32, lists, info, win_unique, s);
+        if (sort_cap > 1024) launch_sort_class<512, 4>(m, 5, most(1025), 1024, col_bits + 11 > 32, lists, info, win_unique, s);
+        if (sort_cap > 2048) launch_sort_class<1024, 4>(m, 6, most(2049), 512, col_bits + 12 > 32, lists, info, win_unique, s);
+        TCG_TRY(launch_status("sgt_window_sort_kernel"));
+    }
+
+    // Join.
+    {
+        std::lock_guard<std::mutex> lock(g_side_mu);
+        TCG_HIP(hipEventRecord(side->join, side->stream));
+        TCG_HIP(hipEventRecord(side->plan_join, side->plan_stream));
+        TCG_HIP(hipStreamWaitEvent(s, side->join, 0));
+        TCG_HIP(hipStreamWaitEvent(s, side->plan_join, 0));
+    }
+
+    // With every window translated: U, and the part of the plan that depends on it (the order of the
+    // single-segment rows).
+    const bool scan_inside = n_win <= (1 << 14);        // one workgroup scans this many counts in a few microseconds
+    if (!scan_inside) TCG_TRY(exclusive_scan_i32(win_unique, m->d_win_unique_ptr, n_win, scan_work, s));
+    hipLaunchKernelGGL(plan_scan_kernel, dim3(1), dim3(1024), 0, s, 1, nb_rows, block_sums, nnz, n_win,
+                       m->d_win_unique_ptr, long_off, slot_off, tail_off, info, m->d_long_slot_ptr,
+                       scan_inside ? win_unique : (const int32_t *)nullptr, m->d_win_unique_ptr);
+    if (nb_rows > 0)
+        hipLaunchKernelGGL(seg_fill_kernel, dim3((unsigned)nb_rows), dim3(256), 0, s, 1, n, m->d_row_ptr, m->d_col_idx,
+                           info, nb_rows, long_off, slot_off, tail_off, m->d_seg_row, m->d_seg_ebeg,
+                           m->d_seg_dst, m->d_long_row, m->d_long_slot_ptr, slot_row, slot_ebeg, slot_key);
     launch_choose_path(m, TCG_POLICY_AUTO, kDefaultMinReuse, s);
     TCG_TRY(launch_status("plan and path kernels"));
 

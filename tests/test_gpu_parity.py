@@ -72,10 +72,10 @@ def test_sgt_all_size_classes_and_unsorted_rows():
 
 def test_sgt_large_windows_in_both_bitmap_variants():
     # Windows above 4096 entries use a bitmap over the column space: in LDS when the column space fits
-    # (up to about 1.16 M columns), in device memory beyond.  Both with columns up to the last one, rows
+    # (up to about 1.12 M columns), in device memory beyond.  Both with columns up to the last one, rows
     # in shuffled order, repeated entries, and a window that is nearly full.
     rng = np.random.default_rng(21)
-    for n_cols in (70000, 1160000 - 7, 1400003):
+    for n_cols in (70000, 1120000 - 7, 1400003):
         rows = []
         for i in range(48):
             k = 400 if i < 16 else (3 if i < 32 else 700)
