@@ -100,6 +100,19 @@ TCG_API int tcg_sgt_sizes(const tcg_meta *meta, int64_t *n_windows, int64_t *tot
                   int64_t *total_tiles, int64_t *nnz);
 
 /*
+ * How many tiles a window-by-window tiled kernel visits with and without the translation -- the quantity of
+ * the paper's SGT-effectiveness study (section 5.2, the figure on the reduction of traversed blocks) -- for any
+ * tile width (the paper: 8 for the aggregation, 16 for the edge features; section 4.3 recounts the blocks
+ * for the second width from the same translated graph):
+ *   tiles_translated    sum over windows of ceil(U_w / tile_w)
+ *   tiles_untranslated  sum over windows of the number of tile_w-wide column blocks of the original matrix,
+ *                       aligned at multiples of tile_w, that hold at least one stored entry of the window
+ * Either output may be NULL.  Blocks until the stream has finished.
+ */
+TCG_API int tcg_sgt_tile_stats(tcg_meta *meta, int32_t tile_w, int64_t *tiles_translated,
+                       int64_t *tiles_untranslated, void *stream);
+
+/*
  * Copies the canonical metadata into caller-owned buffers (any of them may be NULL to skip):
  *   win_partition   int32[n_windows]
  *   win_unique_ptr  int32[n_windows + 1]   offsets of each window's list inside col_to_row

@@ -65,6 +65,16 @@ def _load():
                                         ctypes.c_int64, ctypes.c_int32, _f64p]
         lib.oracle_row_softmax_backward.restype = None
         lib.oracle_row_softmax_backward.argtypes = [ctypes.c_int32, _i32p, _f64p, _f64p, _f64p]
+        lib.oracle_tile_counts.restype = ctypes.c_int
+        lib.oracle_tile_counts.argtypes = [ctypes.c_int32, _i32p, _i32p, ctypes.c_int32, ctypes.c_int32, _i64p, _i64p]
+        lib.oracle_sgt_parallel.restype = ctypes.c_int64
+        lib.oracle_sgt_parallel.argtypes = lib.oracle_sgt.argtypes
+        lib.oracle_spmm_f32acc.restype = None
+        lib.oracle_spmm_f32acc.argtypes = [ctypes.c_int32, _i32p, _i32p, _f32p, _f32p, ctypes.c_int32,
+                                           ctypes.c_int64, _f32p, ctypes.c_int64]
+        lib.oracle_sddmm_f32acc.restype = None
+        lib.oracle_sddmm_f32acc.argtypes = [ctypes.c_int32, _i32p, _i32p, _f32p, ctypes.c_int32,
+                                            ctypes.c_int64, _f32p]
         _lib = lib
     return _lib
 
@@ -85,10 +95,11 @@ def num_threads():
     return int(_load().oracle_num_threads())
 
 
-def sgt(row_ptr, col_idx, win_h, tile_w):
+def sgt(row_ptr, col_idx, win_h, tile_w, parallel=False):
     """Sparse Graph Translation (Algorithm 1).  Returns a dict with
     win_partition [n_win] int32, win_unique_ptr [n_win+1] int64, edge_to_col [nnz] int32,
-    col_to_row [U] int32."""
+    col_to_row [U] int32.  parallel=True runs the windows on all host cores (the variant the
+    benchmark times; same results)."""
     rp, ci = _csr(row_ptr, col_idx)
     n_rows = rp.size - 1
     if win_h < 1 or tile_w < 1:
@@ -98,13 +109,51 @@ def sgt(row_ptr, col_idx, win_h, tile_w):
     win_unique_ptr = np.zeros(n_win + 1, dtype=np.int64)
     edge_to_col = np.zeros(ci.size, dtype=np.int32)
     col_to_row = np.zeros(max(ci.size, 1), dtype=np.int32)
-    total = _load().oracle_sgt(n_rows, _p(rp, _i32p), _p(ci, _i32p), win_h, tile_w,
+    fn = _load().oracle_sgt_parallel if parallel else _load().oracle_sgt
+    total = fn(n_rows, _p(rp, _i32p), _p(ci, _i32p), win_h, tile_w,
                                _p(win_partition, _i32p), _p(win_unique_ptr, _i64p),
                                _p(edge_to_col, _i32p), _p(col_to_row, _i32p))
     if total < 0:
         raise ValueError("oracle_sgt rejected its arguments")
     return dict(win_partition=win_partition, win_unique_ptr=win_unique_ptr,
                 edge_to_col=edge_to_col, col_to_row=col_to_row[:total].copy())
+
+
+def tile_counts(row_ptr, col_idx, win_h, tile_w):
+    """(translated, untranslated) tile counts: sum over windows of ceil(U_w / tile_w), and of the number of
+    aligned tile_w-wide column blocks of the original matrix that hold an entry of the window."""
+    rp, ci = _csr(row_ptr, col_idx)
+    t, u = ctypes.c_int64(), ctypes.c_int64()
+    if _load().oracle_tile_counts(rp.size - 1, _p(rp, _i32p), _p(ci, _i32p), win_h, tile_w, ctypes.byref(t),
+                                  ctypes.byref(u)) != 0:
+        raise ValueError("oracle_tile_counts rejected its arguments")
+    return t.value, u.value
+
+
+def spmm_f32acc(row_ptr, col_idx, X, w=None):
+    """Equation 1 with float accumulation (timed CPU baseline, not the parity oracle)."""
+    rp, ci = _csr(row_ptr, col_idx)
+    n_rows = rp.size - 1
+    X = _features(X, int(ci.max()) + 1 if ci.size else 0)
+    D = X.shape[1]
+    wp = None
+    if w is not None:
+        w = np.ascontiguousarray(w, dtype=np.float32)
+        wp = _p(w, _f32p)
+    Y = np.zeros((n_rows, D), dtype=np.float32)
+    _load().oracle_spmm_f32acc(n_rows, _p(rp, _i32p), _p(ci, _i32p), wp, _p(X, _f32p), D, D, _p(Y, _f32p), D)
+    return Y
+
+
+def sddmm_f32acc(row_ptr, col_idx, X):
+    """Equation 2 with float accumulation (timed CPU baseline, not the parity oracle)."""
+    rp, ci = _csr(row_ptr, col_idx)
+    n_rows = rp.size - 1
+    X = _features(X, max(n_rows, int(ci.max()) + 1 if ci.size else 0))
+    out = np.zeros(ci.size, dtype=np.float32)
+    _load().oracle_sddmm_f32acc(n_rows, _p(rp, _i32p), _p(ci, _i32p), _p(X, _f32p), X.shape[1], X.shape[1],
+                                _p(out, _f32p))
+    return out
 
 
 def _features(X, n_need):

@@ -21,6 +21,12 @@
  *   oracle_sddmm_tiled   -- must reproduce oracle_spmm / oracle_sddmm (Algorithms 2 and 3 run
  *                           from the translated metadata alone).
  *
+ *   oracle_tile_counts   -- brute force from the dense matrix, closed forms (identity, dense blocks).
+ *   oracle_sgt_parallel, oracle_spmm_f32acc, oracle_sddmm_f32acc
+ *                        -- the variants that the benchmark times as CPU baselines (windows in parallel;
+ *                           float accumulation).  Not used for parity; pinned to the functions above
+ *                           (bit-equal metadata; floats within 1e-5 of the double results).
+ *
  * Arithmetic: all floating-point accumulation is in double, in CSR order; outputs are double.
  * Rows are independent, so the row loops are split over OpenMP threads; that does not change
  * any result.
@@ -331,5 +337,133 @@ void oracle_row_softmax_backward(int32_t n_rows, const int32_t *row_ptr, const d
         double dot = 0.0;
         for (int64_t k = row_ptr[i]; k < row_ptr[i + 1]; ++k) dot += p[k] * dp[k];
         for (int64_t k = row_ptr[i]; k < row_ptr[i + 1]; ++k) dv[k] = p[k] * (dp[k] - dot);
+    }
+}
+
+/*
+ * Number of tiles a window-by-window tiled kernel has to visit with and without the translation
+ * (the quantity behind the paper's SGT-effectiveness figure, section 5.2): per row window,
+ *   translated    ceil(U_w / tile_w)                      -- the window's columns condensed first
+ *   untranslated  the number of tile_w-wide column blocks of the original matrix, aligned at multiples
+ *                 of tile_w, that hold at least one stored entry of the window.
+ * Returns 0, or -1 on a malformed argument.
+ */
+int oracle_tile_counts(int32_t n_rows, const int32_t *row_ptr, const int32_t *col_idx, int32_t win_h,
+                       int32_t tile_w, int64_t *translated, int64_t *untranslated)
+{
+    if (n_rows < 0 || win_h < 1 || tile_w < 1) return -1;
+    int64_t n_win = ((int64_t)n_rows + win_h - 1) / win_h;
+    int64_t t_sum = 0, u_sum = 0;
+    for (int64_t w = 0; w < n_win; ++w) {
+        int64_t r0 = w * win_h, r1 = r0 + win_h;
+        if (r1 > n_rows) r1 = n_rows;
+        int64_t b = row_ptr[r0], e = row_ptr[r1], cnt = e - b;
+        if (cnt == 0) continue;
+        int32_t *arr = (int32_t *)malloc(sizeof(int32_t) * (size_t)cnt);
+        memcpy(arr, col_idx + b, (size_t)cnt * sizeof(int32_t));
+        qsort(arr, (size_t)cnt, sizeof(int32_t), cmp_i32);
+        int64_t uniq = 0, blocks = 0;
+        for (int64_t k = 0; k < cnt; ++k) {
+            if (k == 0 || arr[k] != arr[k - 1]) ++uniq;
+            if (k == 0 || arr[k] / tile_w != arr[k - 1] / tile_w) ++blocks;
+        }
+        free(arr);
+        t_sum += (uniq + tile_w - 1) / tile_w;
+        u_sum += blocks;
+    }
+    *translated = t_sum;
+    *untranslated = u_sum;
+    return 0;
+}
+
+/* ------------------------------------------------------------------------------------------------
+ * CPU baselines timed by the benchmark (not used for parity).
+ * ------------------------------------------------------------------------------------------------ */
+
+/*
+ * Algorithm 1 with the windows spread over the host's cores (the paper notes that windows are
+ * independent, section 4.1): every window is sorted, deduplicated and ranked at its own edge offset of a
+ * scratch array, then the lists are packed.  Same outputs as oracle_sgt, bit for bit.
+ */
+int64_t oracle_sgt_parallel(int32_t n_rows, const int32_t *row_ptr, const int32_t *col_idx,
+                            int32_t win_h, int32_t tile_w,
+                            int32_t *win_partition, int64_t *win_unique_ptr,
+                            int32_t *edge_to_col, int32_t *col_to_row)
+{
+    if (n_rows < 0 || win_h < 1 || tile_w < 1) return -1;
+    int64_t n_win = ((int64_t)n_rows + win_h - 1) / win_h;
+    int64_t nnz = row_ptr[n_rows];
+    int32_t *scratch = (int32_t *)malloc(sizeof(int32_t) * (size_t)(nnz > 0 ? nnz : 1));
+    int64_t *uniq_w = (int64_t *)malloc(sizeof(int64_t) * (size_t)(n_win > 0 ? n_win : 1));
+    if (!scratch || !uniq_w) {
+        free(scratch);
+        free(uniq_w);
+        return -1;
+    }
+#pragma omp parallel for schedule(dynamic, 16)
+    for (int64_t w = 0; w < n_win; ++w) {
+        int64_t r0 = w * win_h, r1 = r0 + win_h;
+        if (r1 > n_rows) r1 = n_rows;
+        int64_t win_start = row_ptr[r0], win_end = row_ptr[r1], cnt = win_end - win_start;
+        int32_t *arr = scratch + win_start;
+        memcpy(arr, col_idx + win_start, (size_t)cnt * sizeof(int32_t));
+        qsort(arr, (size_t)cnt, sizeof(int32_t), cmp_i32);
+        int64_t uniq = 0;
+        for (int64_t k = 0; k < cnt; ++k)
+            if (k == 0 || arr[k] != arr[k - 1]) arr[uniq++] = arr[k];
+        uniq_w[w] = uniq;
+        win_partition[w] = (int32_t)((uniq + tile_w - 1) / tile_w);
+        for (int64_t e = win_start; e < win_end; ++e) {
+            int32_t id = col_idx[e];
+            int64_t lo = 0, hi = uniq;
+            while (lo < hi) {
+                int64_t mid = (lo + hi) / 2;
+                if (arr[mid] < id) lo = mid + 1; else hi = mid;
+            }
+            edge_to_col[e] = (int32_t)lo;
+        }
+    }
+    win_unique_ptr[0] = 0;
+    for (int64_t w = 0; w < n_win; ++w) win_unique_ptr[w + 1] = win_unique_ptr[w] + uniq_w[w];
+#pragma omp parallel for schedule(dynamic, 64)
+    for (int64_t w = 0; w < n_win; ++w) {
+        int64_t r0 = w * win_h;
+        memcpy(col_to_row + win_unique_ptr[w], scratch + row_ptr[r0], (size_t)uniq_w[w] * sizeof(int32_t));
+    }
+    int64_t total = win_unique_ptr[n_win];
+    free(scratch);
+    free(uniq_w);
+    return total;
+}
+
+/* Equation 1 with float accumulation (what a plain CPU kernel would do); Y float. */
+void oracle_spmm_f32acc(int32_t n_rows, const int32_t *row_ptr, const int32_t *col_idx, const float *w,
+                        const float *X, int32_t D, int64_t ldx, float *Y, int64_t ldy)
+{
+#pragma omp parallel for schedule(dynamic, 256)
+    for (int32_t i = 0; i < n_rows; ++i) {
+        float *y = Y + (int64_t)i * ldy;
+        for (int32_t d = 0; d < D; ++d) y[d] = 0.0f;
+        for (int64_t e = row_ptr[i]; e < row_ptr[i + 1]; ++e) {
+            const float *x = X + (int64_t)col_idx[e] * ldx;
+            float we = w ? w[e] : 1.0f;
+            for (int32_t d = 0; d < D; ++d) y[d] += we * x[d];
+        }
+    }
+}
+
+/* Equation 2 with float accumulation; out float. */
+void oracle_sddmm_f32acc(int32_t n_rows, const int32_t *row_ptr, const int32_t *col_idx,
+                         const float *X, int32_t D, int64_t ldx, float *out)
+{
+#pragma omp parallel for schedule(dynamic, 256)
+    for (int32_t i = 0; i < n_rows; ++i) {
+        const float *xi = X + (int64_t)i * ldx;
+        for (int64_t e = row_ptr[i]; e < row_ptr[i + 1]; ++e) {
+            const float *xj = X + (int64_t)col_idx[e] * ldx;
+            float acc = 0.0f;
+            for (int32_t d = 0; d < D; ++d) acc += xi[d] * xj[d];
+            out[e] = acc;
+        }
     }
 }

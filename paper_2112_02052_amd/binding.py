@@ -16,7 +16,7 @@ EXPORTED = ["tcg_sgt_build", "tcg_sgt_sizes", "tcg_sgt_export", "tcg_sgt_set_pol
             "tcg_sgt_plan_stats", "tcg_spmm", "tcg_sddmm", "tcg_row_softmax", "tcg_sgt_free",
             "tcg_strerror", "tcg_release_cached_memory", "tcg_sddmm_pq", "tcg_row_softmax_backward",
             "tcg_csr_transpose", "tcg_edge_gather", "tcg_attention", "tcg_reorder_rows", "tcg_csr_permute",
-            "tcg_sgt_reserve", "tcg_spmm_noalloc"]
+            "tcg_sgt_reserve", "tcg_spmm_noalloc", "tcg_sgt_tile_stats"]
 
 _DTYPES = {torch.float32: TCG_F32, torch.bfloat16: TCG_BF16, torch.float16: TCG_F16}
 
@@ -54,6 +54,8 @@ def load_library():
     lib.tcg_spmm.restype = ctypes.c_int
     lib.tcg_spmm.argtypes = [_vp, _vp, ctypes.c_int, ctypes.c_int32, ctypes.c_int64, _vp, _vp, ctypes.c_int,
                              ctypes.c_int64, _vp]
+    lib.tcg_sgt_tile_stats.restype = ctypes.c_int
+    lib.tcg_sgt_tile_stats.argtypes = [_vp, ctypes.c_int32, _i64p, _i64p, _vp]
     lib.tcg_sgt_reserve.restype = ctypes.c_int
     lib.tcg_sgt_reserve.argtypes = [_vp, ctypes.c_int32, _vp]
     lib.tcg_spmm_noalloc.restype = ctypes.c_int
@@ -159,6 +161,13 @@ def sgt_export(meta):
 
 def sgt_set_policy(meta, policy, min_reuse=0.0):
     _check(load_library().tcg_sgt_set_policy(meta._h, int(policy), float(min_reuse), _stream()))
+
+
+def sgt_tile_stats(meta, tile_w):
+    """tcg_sgt_tile_stats: (tiles with the translation, tiles without it) for tiles of tile_w columns."""
+    t, u = ctypes.c_int64(), ctypes.c_int64()
+    _check(load_library().tcg_sgt_tile_stats(meta._h, int(tile_w), t, u, _stream()))
+    return t.value, u.value
 
 
 def sgt_reserve(meta, max_D):

@@ -115,6 +115,13 @@ int tcg_sgt_export(const tcg_meta *meta, int32_t *win_partition, int32_t *win_un
     return TCG_OK;
 }
 
+int tcg_sgt_tile_stats(tcg_meta *meta, int32_t tile_w, int64_t *tiles_translated, int64_t *tiles_untranslated,
+                       void *stream)
+{
+    if (!meta || tile_w < 1) return TCG_EINVAL;
+    return tile_stats(meta, tile_w, tiles_translated, tiles_untranslated, static_cast<hipStream_t>(stream));
+}
+
 int tcg_sgt_set_policy(tcg_meta *meta, tcg_policy policy, float min_reuse, void *stream)
 {
     if (!meta) return TCG_EINVAL;

@@ -153,6 +153,7 @@ int sgt_build_impl(tcg_meta *m, int validate, hipStream_t s);
 int choose_paths(tcg_meta *m, tcg_policy policy, float min_reuse, hipStream_t s);
 // Writes the per-window unique lists back to back (the exported col_to_row) into d_packed[total_unique].
 int export_col_to_row(const tcg_meta *m, int32_t *d_packed, hipStream_t s);
+int tile_stats(const tcg_meta *m, int32_t tile_w, int64_t *translated, int64_t *untranslated, hipStream_t s);
 
 // spmm.hip / sddmm.hip / softmax.hip
 int spmm_impl(tcg_meta *m, const void *d_X, tcg_dtype x_dt, int32_t D, int64_t ldx, const float *d_w,

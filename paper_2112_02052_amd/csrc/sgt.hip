@@ -1213,6 +1213,53 @@ int choose_paths(tcg_meta *m, tcg_policy policy, float min_reuse, hipStream_t s)
     return TCG_OK;
 }
 
+// Tile counts for a tile width: per window ceil(U_w / tile_w), and the number of aligned tile_w-wide column
+// blocks of the original matrix that hold an entry of the window (heads of runs of equal column / tile_w in
+// the window's ascending list).  One workgroup per window, grid stride; totals by one atomic per workgroup.
+__global__ __launch_bounds__(256) void tile_stats_kernel(int32_t n_rows, int32_t win_h, int64_t n_win, int32_t tile_w,
+                                                         const int32_t *__restrict__ rp,
+                                                         const int32_t *__restrict__ win_unique_ptr,
+                                                         const int32_t *__restrict__ col_to_row,
+                                                         unsigned long long *out)
+{
+    __shared__ unsigned long long s_red[256 / kWave];
+    unsigned long long blocks = 0, tiles = 0;
+    for (int64_t w = blockIdx.x; w < n_win; w += gridDim.x) {
+        int32_t lo, hi;
+        window_edge_range(rp, n_rows, win_h, w, &lo, &hi);
+        const int32_t uw = win_unique_ptr[w + 1] - win_unique_ptr[w];
+        if (threadIdx.x == 0) tiles += (unsigned long long)(((int64_t)uw + tile_w - 1) / tile_w);
+        for (int32_t k = threadIdx.x; k < uw; k += 256)
+            if (k == 0 || col_to_row[lo + k] / tile_w != col_to_row[lo + k - 1] / tile_w) ++blocks;
+    }
+    blocks = wave_sum_u64(blocks);
+    if ((threadIdx.x & (kWave - 1)) == 0) s_red[threadIdx.x >> 6] = blocks;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        unsigned long long t = 0;
+        for (int i = 0; i < 256 / kWave; ++i) t += s_red[i];
+        if (tiles) atomicAdd(&out[0], tiles);
+        if (t) atomicAdd(&out[1], t);
+    }
+}
+
+int tile_stats(const tcg_meta *m, int32_t tile_w, int64_t *translated, int64_t *untranslated, hipStream_t s)
+{
+    unsigned long long *out = m->d_counters + 6;        // the two spare slots of the counter block
+    TCG_HIP(hipMemsetAsync(out, 0, 2 * sizeof(unsigned long long), s));
+    if (m->n_win > 0) {
+        hipLaunchKernelGGL(tile_stats_kernel, dim3((unsigned)std::min<int64_t>(m->n_win, 4096)), dim3(256), 0, s, m->n_rows,
+                           m->win_h, m->n_win, tile_w, m->d_row_ptr, m->d_win_unique_ptr, m->d_col_to_row, out);
+        TCG_TRY(launch_status("tile_stats_kernel"));
+    }
+    unsigned long long h[2] = {0, 0};
+    TCG_HIP(hipMemcpyAsync(h, out, sizeof(h), hipMemcpyDeviceToHost, s));
+    TCG_HIP(hipStreamSynchronize(s));
+    if (translated) *translated = (int64_t)h[0];
+    if (untranslated) *untranslated = (int64_t)h[1];
+    return TCG_OK;
+}
+
 int export_col_to_row(const tcg_meta *m, int32_t *d_packed, hipStream_t s)
 {
     if (m->n_win == 0 || m->total_unique == 0) return TCG_OK;

@@ -36,6 +36,7 @@ def test_status_texts_and_argument_checks_without_gpu():
     assert lib.tcg_row_softmax(None, None, None, None) == -1
     assert lib.tcg_sgt_set_policy(None, 0, 0.0, None) == -1
     assert lib.tcg_sgt_reserve(None, 16, None) == -1
+    assert lib.tcg_sgt_tile_stats(None, 8, None, None, None) == -1
     assert lib.tcg_spmm_noalloc(None, None, 0, 16, 16, None, None, 0, 16, None) == -1
     lib.tcg_sgt_free(None)
 

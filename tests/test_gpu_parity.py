@@ -90,6 +90,19 @@ def test_sgt_large_windows_in_both_bitmap_variants():
         meta.free()
 
 
+@pytest.mark.parametrize("cfg,n,H", [(1, 2048, 16), (3, 30000, 16), (4, 50000, 16), (5, 64 * 100, 16), (2, 1003, 12)])
+def test_sgt_tile_counts_with_and_without_the_translation(cfg, n, H):
+    # Section 5.2's quantity for the paper's two tile widths (8: aggregation, 16: edge features) and two
+    # others, from one translated graph; bit-exact against the oracle's count from the CSR.
+    g = W.make_config(cfg, n=n, d=4)["csr"]
+    rp, ci = upload_csr(g)
+    meta = tcg.sgt_build(rp, ci, H, 8)
+    for tile_w in (8, 16, 1, 5):
+        assert tcg.sgt_tile_stats(meta, tile_w) == oracle.tile_counts(g.row_ptr, g.col_idx, H, tile_w), tile_w
+    assert tcg.sgt_tile_stats(meta, 8)[0] == meta.total_tiles
+    meta.free()
+
+
 def test_sgt_empty_and_degenerate():
     for g in (CSR(0, 0, np.zeros(1, np.int32), np.zeros(0, np.int32)),
               CSR(37, 37, np.zeros(38, np.int32), np.zeros(0, np.int32)),
