@@ -57,84 +57,107 @@ __device__ __forceinline__ float wave_sum(float v)
     return v;
 }
 
-// dv[e] = p[e] * (dp[e] - sum over the row of p * dp).  Rows of at most kSegLen entries are taken from the
-// tail of the gather plan's segment list (single-segment rows; rows without entries have an empty segment
-// there and are skipped; on graphs without neighbour sharing the list is ordered by row length): a workgroup looks at the lengths of its 64
-// rows and runs the variant that fits the longest -- G lanes per row, S entries of p and of dp per lane in
-// registers, (G, S) = (4, 2) up to 8 entries, (8, 2) up to 16, (16, 2) up to 32, (16, 8) up to 128.
-constexpr int kTailRows = 64;          // rows per workgroup
+// dv[e] = p[e] * (dp[e] - sum over the row of p * dp), laid out like the row softmax (sddmm.hip): work is dealt
+// out per wavefront without LDS or barriers -- 16 single-segment rows per wavefront from the tail of the gather
+// plan's segment list (first edge in seg_ebeg, length in seg_dst), G lanes per row with S entries of p and of dp
+// per lane in registers, (G, S) = (4, 2) up to 8 entries, (8, 2) up to 16, (16, 2) up to 32, (16, 8) up to 128;
+// one wavefront per split row of up to kGiantRow entries; one workgroup per longer row, two passes with the
+// next batch requested before the current one is worked on.
+constexpr int kTailRowsPerWave = 16;             // lanes 0 .. 15 look the rows up (more rows per wavefront cost
+                                                 // registers, and with them resident wavefronts: measured slower)
 
 template <int G, int S>
-__device__ __forceinline__ void softmax_bwd_rows(const int32_t *s_b, const int32_t *s_e, const float *p, const float *dp,
-                                                 float *dv)
+__device__ __forceinline__ void softmax_bwd_tail_rows(int32_t b_l, int32_t len_l, const float *p, const float *dp,
+                                                      float *dv)
 {
-    constexpr int ROWS = kThreads / G;               // rows per pass of the workgroup
-    const int gl = threadIdx.x % G;
+    constexpr int RPP = kWave / G;                   // rows per pass of the wavefront
+    constexpr int PASSES = kTailRowsPerWave / RPP;
+    // The values of several passes are requested before the first result is stored (dv may be dp, so the compiler
+    // keeps loads behind earlier stores): all passes, or two at a time where that would take too many registers.
+    constexpr int BATCH = PASSES * S > 16 ? 16 / S : PASSES;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int gl = lane % G;
 #pragma unroll
-    for (int pass = 0; pass < kTailRows / ROWS; ++pass) {
-        const int r = pass * ROWS + threadIdx.x / G;
-        const int32_t b = s_b[r], e = s_e[r];
-        float pv[S], gv[S];
-        float dot = 0.f;
+    for (int p0 = 0; p0 < PASSES; p0 += BATCH) {
+        float pv[BATCH][S], gv[BATCH][S];
+        int32_t b[BATCH], e[BATCH];
 #pragma unroll
-        for (int i = 0; i < S; ++i) {
-            const int32_t k = b + gl + G * i;
-            pv[i] = k < e ? p[k] : 0.f;
-            gv[i] = k < e ? dp[k] : 0.f;
-            dot = fmaf(pv[i], gv[i], dot);
+        for (int q = 0; q < BATCH; ++q) {
+            const int r = (p0 + q) * RPP + lane / G;
+            b[q] = __shfl(b_l, r, kWave);
+            e[q] = b[q] + __shfl(len_l, r, kWave);
+#pragma unroll
+            for (int i = 0; i < S; ++i) {
+                const int32_t k = b[q] + gl + G * i;
+                pv[q][i] = k < e[q] ? p[k] : 0.f;
+                gv[q][i] = k < e[q] ? dp[k] : 0.f;
+            }
         }
 #pragma unroll
-        for (int off = 1; off < G; off <<= 1) dot += __shfl_xor(dot, off, kWave);
+        for (int q = 0; q < BATCH; ++q) {
+            float dot = 0.f;
 #pragma unroll
-        for (int i = 0; i < S; ++i) {
-            const int32_t k = b + gl + G * i;
-            if (k < e) dv[k] = pv[i] * (gv[i] - dot);
+            for (int i = 0; i < S; ++i) dot = fmaf(pv[q][i], gv[q][i], dot);
+#pragma unroll
+            for (int off = 1; off < G; off <<= 1) dot += __shfl_xor(dot, off, kWave);
+#pragma unroll
+            for (int i = 0; i < S; ++i) {
+                const int32_t k = b[q] + gl + G * i;
+                if (k < e[q]) dv[k] = pv[q][i] * (gv[q][i] - dot);
+            }
         }
     }
 }
 
-// A row of the gather plan's list of split rows (more than kSegLen entries), by one 256-thread workgroup: up to
-// 8 * 256 entries p and dp of the row sit in registers; a longer row takes two passes, eight values of each
-// operand per thread in flight.  (More registers per thread would halve the resident wavefronts of the whole
-// kernel, which the short rows need more than the long ones need the saved second read.)
-__device__ __forceinline__ void softmax_bwd_long_row(int32_t b, int32_t e, const float *p, const float *dp, float *dv,
-                                                     float *s_red)
+template <int R>
+__device__ __forceinline__ void softmax_bwd_row_wave(int32_t b, int32_t e, const float *p, const float *dp, float *dv)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    float pv[R], gv[R];
+    float dot = 0.f;
+#pragma unroll
+    for (int i = 0; i < R; ++i) {
+        const int32_t k = b + lane + kWave * i;
+        pv[i] = k < e ? p[k] : 0.f;
+        gv[i] = k < e ? dp[k] : 0.f;
+        dot = fmaf(pv[i], gv[i], dot);
+    }
+    dot = wave_sum(dot);
+#pragma unroll
+    for (int i = 0; i < R; ++i) {
+        const int32_t k = b + lane + kWave * i;
+        if (k < e) dv[k] = pv[i] * (gv[i] - dot);
+    }
+}
+
+// One of the few longer rows by a workgroup: two passes over batches of kBwdUnroll values of each operand per
+// thread, the next batch requested before the current one is worked on.
+constexpr int kBwdUnroll = 6;
+__device__ __forceinline__ void softmax_bwd_giant_row(int32_t b, int32_t e, const float *p, const float *dp, float *dv,
+                                                      float *s_red)
 {
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
-    if (e - b <= 8 * kThreads) {
-        float pv[8], gv[8];
-        float dot = 0.f;
+    constexpr int32_t kStep = kBwdUnroll * kThreads;
+    auto load = [&](int32_t k0, float (&a)[kBwdUnroll], float (&c)[kBwdUnroll]) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int32_t k = b + threadIdx.x + kThreads * i;
-            pv[i] = k < e ? p[k] : 0.f;
-            gv[i] = k < e ? dp[k] : 0.f;
-            dot = fmaf(pv[i], gv[i], dot);
-        }
-        dot = wave_sum(dot);
-        if (lane == 0) s_red[wave] = dot;
-        __syncthreads();
-        dot = 0.f;
-#pragma unroll
-        for (int i = 0; i < kThreads / kWave; ++i) dot += s_red[i];
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int32_t k = b + threadIdx.x + kThreads * i;
-            if (k < e) dv[k] = pv[i] * (gv[i] - dot);
-        }
-        return;
-    }
-    float dot = 0.f;
-    for (int32_t k0 = b + threadIdx.x; k0 < e; k0 += 8 * kThreads) {
-        float a[8], c[8];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
+        for (int u = 0; u < kBwdUnroll; ++u) {
             const bool ok = k0 + u * kThreads < e;
             a[u] = ok ? p[k0 + u * kThreads] : 0.f;
             c[u] = ok ? dp[k0 + u * kThreads] : 0.f;
         }
+    };
+    float a[kBwdUnroll], c[kBwdUnroll], an[kBwdUnroll], cn[kBwdUnroll];
+    float dot = 0.f;
+    load(b + threadIdx.x, a, c);
+    for (int32_t k0 = b + threadIdx.x; k0 < e; k0 += kStep) {
+        load(k0 + kStep, an, cn);                  // past the end: nothing is read
 #pragma unroll
-        for (int u = 0; u < 8; ++u) dot = fmaf(a[u], c[u], dot);
+        for (int u = 0; u < kBwdUnroll; ++u) dot = fmaf(a[u], c[u], dot);
+#pragma unroll
+        for (int u = 0; u < kBwdUnroll; ++u) {
+            a[u] = an[u];
+            c[u] = cn[u];
+        }
     }
     dot = wave_sum(dot);
     if (lane == 0) s_red[wave] = dot;
@@ -142,59 +165,102 @@ __device__ __forceinline__ void softmax_bwd_long_row(int32_t b, int32_t e, const
     dot = 0.f;
 #pragma unroll
     for (int i = 0; i < kThreads / kWave; ++i) dot += s_red[i];
-    for (int32_t k0 = b + threadIdx.x; k0 < e; k0 += 8 * kThreads) {
-        float a[8], c[8];
+    load(b + threadIdx.x, a, c);
+    for (int32_t k0 = b + threadIdx.x; k0 < e; k0 += kStep) {
+        load(k0 + kStep, an, cn);                  // requested before this batch's stores
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            const bool ok = k0 + u * kThreads < e;
-            a[u] = ok ? p[k0 + u * kThreads] : 0.f;
-            c[u] = ok ? dp[k0 + u * kThreads] : 0.f;
-        }
-#pragma unroll
-        for (int u = 0; u < 8; ++u)
+        for (int u = 0; u < kBwdUnroll; ++u)
             if (k0 + u * kThreads < e) dv[k0 + u * kThreads] = a[u] * (c[u] - dot);
+#pragma unroll
+        for (int u = 0; u < kBwdUnroll; ++u) {
+            a[u] = an[u];
+            c[u] = cn[u];
+        }
     }
 }
 
-// One launch for all rows: workgroups 0 .. n_long - 1 take one split row each (dispatched first, so the long
-// rows start at once and the short ones fill in around them), the workgroups behind them 64 single-segment rows
-// each.
-__global__ __launch_bounds__(kThreads) void softmax_bwd_kernel(int32_t n_long, const int32_t *__restrict__ long_row,
-                                                               int32_t tail_start, int32_t tail_count,
-                                                               const int32_t *__restrict__ seg_row,
-                                                               const int32_t *__restrict__ seg_dst,
-                                                               const int32_t *__restrict__ row_ptr, const float *p,
-                                                               const float *dp, float *dv)
+// A split row of 1025 .. kGiantRow entries by one wavefront, 16 values of each operand per lane at a time: the sum
+// over both halves first, then each half again for the results (both operands of the whole row in registers
+// would cost the kernel half of its resident wavefronts).
+__device__ __forceinline__ void softmax_bwd_row_wave_halves(int32_t b, int32_t e, const float *p, const float *dp,
+                                                            float *dv)
 {
-    __shared__ int32_t s_b[kTailRows], s_e[kTailRows];
-    __shared__ float s_red[kThreads / kWave];
-    __shared__ int s_max;
-    if ((int32_t)blockIdx.x < n_long) {
-        const int32_t row = long_row[blockIdx.x];
-        softmax_bwd_long_row(row_ptr[row], row_ptr[row + 1], p, dp, dv, s_red);
+    constexpr int R = 16;
+    const int lane = threadIdx.x & (kWave - 1);
+    float dot = 0.f;
+#pragma unroll 1
+    for (int h = 0; h < 2; ++h) {
+        float a[R], c[R];
+#pragma unroll
+        for (int i = 0; i < R; ++i) {
+            const int32_t k = b + h * kWave * R + lane + kWave * i;
+            a[i] = k < e ? p[k] : 0.f;
+            c[i] = k < e ? dp[k] : 0.f;
+        }
+#pragma unroll
+        for (int i = 0; i < R; ++i) dot = fmaf(a[i], c[i], dot);
+    }
+    dot = wave_sum(dot);
+#pragma unroll 1
+    for (int h = 0; h < 2; ++h) {
+        float a[R], c[R];
+#pragma unroll
+        for (int i = 0; i < R; ++i) {
+            const int32_t k = b + h * kWave * R + lane + kWave * i;
+            a[i] = k < e ? p[k] : 0.f;
+            c[i] = k < e ? dp[k] : 0.f;
+        }
+#pragma unroll
+        for (int i = 0; i < R; ++i) {
+            const int32_t k = b + h * kWave * R + lane + kWave * i;
+            if (k < e) dv[k] = a[i] * (c[i] - dot);
+        }
+    }
+}
+
+constexpr int kWavesPerBlock = kThreads / kWave;
+__global__ __launch_bounds__(kThreads) void softmax_bwd_kernel(
+    int32_t n_giant, const int32_t *__restrict__ giant, int32_t n_long, const int32_t *__restrict__ long_ebeg,
+    const int32_t *__restrict__ long_len, int32_t tail_start, int32_t tail_count,
+    const int32_t *__restrict__ seg_ebeg, const int32_t *__restrict__ seg_dst, const float *p, const float *dp,
+    float *dv)
+{
+    __shared__ float s_red[kWavesPerBlock];
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
+    int32_t blk = blockIdx.x;
+    if (blk < n_giant) {
+        const int32_t li = giant[blk];
+        const int32_t b = long_ebeg[li];
+        softmax_bwd_giant_row(b, b + long_len[li], p, dp, dv, s_red);
         return;
     }
-    if (threadIdx.x == 0) s_max = 0;
-    __syncthreads();
-    if (threadIdx.x < kTailRows) {
-        const int64_t i = (int64_t)(blockIdx.x - n_long) * kTailRows + threadIdx.x;
-        int32_t b = 0, e = 0;
-        if (i < tail_count && seg_dst[tail_start + i] < 0) {          // a piece of a split row: not here
-            const int32_t row = seg_row[tail_start + i];
-            b = row_ptr[row];
-            e = row_ptr[row + 1];
-        }
-        s_b[threadIdx.x] = b;
-        s_e[threadIdx.x] = e;
-        if (e > b) atomicMax(&s_max, e - b);
+    blk -= n_giant;
+    const int32_t n_long_blocks = (n_long + kWavesPerBlock - 1) / kWavesPerBlock;
+    if (blk < n_long_blocks) {
+        const int32_t li = blk * kWavesPerBlock + wave;
+        if (li >= n_long) return;
+        const int32_t b = long_ebeg[li], len = long_len[li];
+        if (len <= 8 * kWave) softmax_bwd_row_wave<8>(b, b + len, p, dp, dv);
+        else if (len <= 16 * kWave) softmax_bwd_row_wave<16>(b, b + len, p, dp, dv);
+        else if (len <= kGiantRow) softmax_bwd_row_wave_halves(b, b + len, p, dp, dv);
+        return;                                     // longer: one of the giant rows
     }
-    __syncthreads();
-    const int longest = s_max;
+    blk -= n_long_blocks;
+    const int64_t i = ((int64_t)blk * kWavesPerBlock + wave) * kTailRowsPerWave + lane;
+    int32_t b = 0, len = 0;
+    if (lane < kTailRowsPerWave && i < tail_count) {
+        b = seg_ebeg[tail_start + i];
+        len = -1 - seg_dst[tail_start + i];                           // single-segment rows carry their length
+    }
+    int longest = len;
+#pragma unroll
+    for (int off = 1; off < kTailRowsPerWave; off <<= 1) longest = max(longest, __shfl_xor(longest, off, kWave));
+    longest = __shfl(longest, 0, kWave);
     if (longest == 0) return;
-    if (longest <= 8) softmax_bwd_rows<4, 2>(s_b, s_e, p, dp, dv);
-    else if (longest <= 16) softmax_bwd_rows<8, 2>(s_b, s_e, p, dp, dv);
-    else if (longest <= 32) softmax_bwd_rows<16, 2>(s_b, s_e, p, dp, dv);
-    else softmax_bwd_rows<16, kSegLen / 16>(s_b, s_e, p, dp, dv);
+    if (longest <= 8) softmax_bwd_tail_rows<4, 2>(b, len, p, dp, dv);
+    else if (longest <= 16) softmax_bwd_tail_rows<8, 2>(b, len, p, dp, dv);
+    else if (longest <= 32) softmax_bwd_tail_rows<16, 2>(b, len, p, dp, dv);
+    else softmax_bwd_tail_rows<16, kSegLen / 16>(b, len, p, dp, dv);
 }
 
 }  // namespace
@@ -203,11 +269,12 @@ int row_softmax_backward_impl(const tcg_meta *m, const float *d_p, const float *
 {
     if (m->n_rows == 0 || m->nnz == 0) return TCG_OK;
     const int32_t tail_start = m->h_lane_tab[4], tail_count = m->h_lane_tab[5];
-    const int64_t grid = m->n_long + ceil_div(tail_count, kTailRows);
+    const int64_t grid = m->n_giant + ceil_div(m->n_long, kWavesPerBlock) +
+                         ceil_div(tail_count, kWavesPerBlock * kTailRowsPerWave);
     if (grid > 0) {
-        hipLaunchKernelGGL(softmax_bwd_kernel, dim3((unsigned)grid), dim3(kThreads), 0, s, (int32_t)m->n_long,
-                           m->d_long_row, tail_start, tail_count, m->d_seg_row, m->d_seg_dst, m->d_row_ptr, d_p, d_dp,
-                           d_dv);
+        hipLaunchKernelGGL(softmax_bwd_kernel, dim3((unsigned)grid), dim3(kThreads), 0, s, (int32_t)m->n_giant, m->d_giant,
+                           (int32_t)m->n_long, m->d_long_ebeg, m->d_long_len, tail_start, tail_count, m->d_seg_ebeg,
+                           m->d_seg_dst, d_p, d_dp, d_dv);
         TCG_TRY(launch_status("softmax_bwd_kernel"));
     }
     return TCG_OK;

@@ -12,6 +12,8 @@ namespace tcg {
 
 constexpr int kWave = 64;            // gfx950 wavefront width
 constexpr int kSegLen = 128;         // max edges of one row segment on the gather path
+constexpr int kGiantRow = 2048;      // rows with more entries are listed apart in the plan (row-wise kernels give them a
+                                     // workgroup each; up to this length a row fits one wavefront's registers)
 constexpr float kDefaultMinReuse = 2.0f;
 constexpr int kXcds = 8;              // accelerator dies of an MI355X; workgroup i is dispatched to die i % 8
 constexpr int kPartialInitD = 128;   // the build reserves partial-sum scratch for feature widths up to this
@@ -221,9 +223,14 @@ struct tcg_meta {
     int64_t n_seg = 0, n_long = 0, n_slots = 0;
     int32_t *d_seg_row = nullptr;         // [n_seg] row of the segment
     int32_t *d_seg_ebeg = nullptr;        // [n_seg] first edge
-    int32_t *d_seg_dst = nullptr;         // [n_seg] partial-sum slot, or -1: write the row directly
+    int32_t *d_seg_dst = nullptr;         // [n_seg] partial-sum slot, or below zero: write the row directly
+                                          //         (-1 - the row's length: a single-segment row)
     int32_t *d_long_row = nullptr;        // [n_long] rows with more than one segment
     int32_t *d_long_slot_ptr = nullptr;   // [n_long + 1] their slot ranges
+    int32_t *d_long_ebeg = nullptr;       // [n_long] their first edge
+    int32_t *d_long_len = nullptr;        // [n_long] their number of entries
+    int32_t *d_giant = nullptr;           // [n_giant] positions (in the four arrays above) of the rows beyond kGiantRow
+    int64_t n_giant = 0;
     int32_t *d_lane_tab = nullptr;        // [kXcds x kLaneTabStride] see plan_segment() (inside the build's result block)
     int32_t h_lane_tab[6 * 8] = {0};      // host copy (sizes the gather grids, see plan_grid())
     float *d_partial = nullptr;           // [n_slots x D] scratch; reserved for D <= kPartialInitD, regrown on demand

@@ -175,109 +175,132 @@ __device__ __forceinline__ float wave_sum(float v)
     return v;
 }
 
-// Rows of at most kSegLen entries.  They are taken from the tail of the gather plan's segment list (the
-// single-segment rows), not from the row index: on graphs whose windows share few neighbours that list is
-// ordered by row length, so a workgroup's 64 rows are alike.  Rows without entries are in the list too (one
-// empty segment each, which the aggregation uses to write their zeros); they are skipped here.  The workgroup looks at its rows' lengths
-// first and then runs the variant that fits the longest of them: G lanes per row with S entries per lane
-// in registers, (G, S) = (4, 2) up to 8 entries, (8, 2) up to 16, (16, 2) up to 32, (16, 8) up to 128; maximum
-// and sum of exponentials by butterflies inside the lane group; one read, one write.
-constexpr int kTailRows = 64;          // rows per workgroup
+// ---- row softmax ----------------------------------------------------------------------------------
+// The kernel is bound by memory latency, not bandwidth: a row is a short chain of dependent round trips (where
+// is the row -> its values -> the result), so it is laid out for as many independent chains in flight as
+// possible and as few links per chain as possible.  Work is dealt out per wavefront, without LDS or barriers:
+//   single-segment rows (at most kSegLen entries)  16 consecutive entries of the tail of the gather plan's
+//       segment list per wavefront.  A tail entry carries the row's first edge (seg_ebeg) and its length
+//       (seg_dst = -1 - length), so one round trip yields both; on graphs whose windows share few neighbours the
+//       tail is ordered by row length, so the 16 rows are alike, and the wavefront runs the variant that fits
+//       the longest: G lanes per row with S entries per lane in registers, (G, S) = (4, 2) up to 8 entries,
+//       (8, 2) up to 16, (16, 2) up to 32, (16, 8) up to 128.  Rows without entries are in the list too (the
+//       aggregation writes their zeros) and cost nothing here.
+//   split rows of up to kGiantRow entries           one wavefront each, the row in registers (8, 16 or 32
+//       values per lane), first edge and length from the plan's long-row table.
+//   the few longer rows                            one workgroup each from the plan's list of them, two passes
+//       with the next batch of values requested before the current one is worked on.
+// All values a wavefront needs are requested before its first result is stored (input and output may be the
+// same array, so the compiler keeps loads behind earlier stores).
+constexpr int kTailRowsPerWave = 16;             // lanes 0 .. 15 look the rows up (more rows per wavefront cost
+                                                 // registers, and with them resident wavefronts: measured slower)
 
 template <int G, int S>
-__device__ __forceinline__ void softmax_rows(const int32_t *s_b, const int32_t *s_e, const float *in, float *out)
+__device__ __forceinline__ void softmax_tail_rows(int32_t b_l, int32_t len_l, const float *in, float *out)
 {
-    constexpr int ROWS = kBlock / G;                 // rows per pass of the workgroup
-    const int gl = threadIdx.x % G;
+    constexpr int RPP = kWave / G;                   // rows per pass of the wavefront
+    constexpr int PASSES = kTailRowsPerWave / RPP;
+    constexpr int BATCH = PASSES * S > 32 ? 32 / S : PASSES;      // passes whose values are in registers together
+    const int lane = threadIdx.x & (kWave - 1);
+    const int gl = lane % G;
 #pragma unroll
-    for (int pass = 0; pass < kTailRows / ROWS; ++pass) {
-        const int r = pass * ROWS + threadIdx.x / G;
-        const int32_t b = s_b[r], e = s_e[r];
-        float v[S];
-        float m = -INFINITY;
+    for (int p0 = 0; p0 < PASSES; p0 += BATCH) {
+        float v[BATCH][S];
+        int32_t b[BATCH], e[BATCH];
 #pragma unroll
-        for (int i = 0; i < S; ++i) {
-            const int32_t k = b + gl + G * i;
-            v[i] = k < e ? in[k] : -INFINITY;
-            m = fmaxf(m, v[i]);
+        for (int q = 0; q < BATCH; ++q) {
+            const int r = (p0 + q) * RPP + lane / G;
+            b[q] = __shfl(b_l, r, kWave);
+            e[q] = b[q] + __shfl(len_l, r, kWave);
+#pragma unroll
+            for (int i = 0; i < S; ++i) {
+                const int32_t k = b[q] + gl + G * i;
+                v[q][i] = k < e[q] ? in[k] : -INFINITY;
+            }
         }
 #pragma unroll
-        for (int off = 1; off < G; off <<= 1) m = fmaxf(m, __shfl_xor(m, off, kWave));
-        float sum = 0.f;
+        for (int q = 0; q < BATCH; ++q) {
+            float m = -INFINITY;
 #pragma unroll
-        for (int i = 0; i < S; ++i) {
-            v[i] = b + gl + G * i < e ? expf(v[i] - m) : 0.f;
-            sum += v[i];
-        }
+            for (int i = 0; i < S; ++i) m = fmaxf(m, v[q][i]);
 #pragma unroll
-        for (int off = 1; off < G; off <<= 1) sum += __shfl_xor(sum, off, kWave);
-        const float inv = 1.f / sum;
+            for (int off = 1; off < G; off <<= 1) m = fmaxf(m, __shfl_xor(m, off, kWave));
+            float sum = 0.f;
 #pragma unroll
-        for (int i = 0; i < S; ++i) {
-            const int32_t k = b + gl + G * i;
-            if (k < e) out[k] = v[i] * inv;
+            for (int i = 0; i < S; ++i) {
+                v[q][i] = b[q] + gl + G * i < e[q] ? expf(v[q][i] - m) : 0.f;
+                sum += v[q][i];
+            }
+#pragma unroll
+            for (int off = 1; off < G; off <<= 1) sum += __shfl_xor(sum, off, kWave);
+            const float inv = 1.f / sum;
+#pragma unroll
+            for (int i = 0; i < S; ++i) {
+                const int32_t k = b[q] + gl + G * i;
+                if (k < e[q]) out[k] = v[q][i] * inv;
+            }
         }
     }
 }
 
-// A row of the gather plan's list of split rows (more than kSegLen entries), by one 256-thread workgroup:
-// up to R * 256 entries the row sits in registers (R values per thread; one read, one write).
 template <int R>
-__device__ __forceinline__ void softmax_row_in_registers(int32_t b, int32_t e, const float *in, float *out, float *s_m,
-                                                         float *s_s)
+__device__ __forceinline__ void softmax_row_wave(int32_t b, int32_t e, const float *in, float *out)
 {
-    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & (kWave - 1);
     float v[R];
     float m = -INFINITY;
 #pragma unroll
     for (int i = 0; i < R; ++i) {
-        const int32_t k = b + threadIdx.x + kBlock * i;
+        const int32_t k = b + lane + kWave * i;
         v[i] = k < e ? in[k] : -INFINITY;
         m = fmaxf(m, v[i]);
     }
     m = wave_max(m);
-    if (lane == 0) s_m[wave] = m;
-    __syncthreads();
-    m = fmaxf(fmaxf(s_m[0], s_m[1]), fmaxf(s_m[2], s_m[3]));
     float sum = 0.f;
 #pragma unroll
     for (int i = 0; i < R; ++i) {
-        v[i] = b + threadIdx.x + kBlock * i < e ? expf(v[i] - m) : 0.f;
+        v[i] = b + lane + kWave * i < e ? expf(v[i] - m) : 0.f;
         sum += v[i];
     }
-    sum = wave_sum(sum);
-    if (lane == 0) s_s[wave] = sum;
-    __syncthreads();
-    const float inv = 1.f / ((s_s[0] + s_s[1]) + (s_s[2] + s_s[3]));
+    const float inv = 1.f / wave_sum(sum);
 #pragma unroll
     for (int i = 0; i < R; ++i) {
-        const int32_t k = b + threadIdx.x + kBlock * i;
+        const int32_t k = b + lane + kWave * i;
         if (k < e) out[k] = v[i] * inv;
     }
 }
-static_assert(kBlock / kWave == 4, "the row kernels combine four wavefront partials");
 
-// Longer rows: two passes (running maximum and rescaled sum of exponentials, eight values per thread in
-// flight, then the normalised values).
-constexpr int kTwoPassUnroll = 8;
+// One of the few longer rows by a workgroup: two passes (running maximum and rescaled sum of exponentials, then
+// the normalised values), each over batches of kTwoPassUnroll values per thread with the next batch requested
+// before the current one is worked on.  (Cutting these rows into chunks for several workgroups, with a second
+// launch to combine them, was measured: 62 us against 54 us on the 1M-node graph -- the extra launch costs more
+// than the hub row's tail.)
+constexpr int kTwoPassUnroll = 12;
 __device__ __forceinline__ void softmax_row_two_pass(int32_t b, int32_t e, const float *in, float *out, float *s_m,
                                                      float *s_s)
 {
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
+    constexpr int32_t kStep = kTwoPassUnroll * kBlock;
+    auto load = [&](int32_t k0, float (&v)[kTwoPassUnroll], float fill) {
+#pragma unroll
+        for (int u = 0; u < kTwoPassUnroll; ++u) v[u] = k0 + u * kBlock < e ? in[k0 + u * kBlock] : fill;
+    };
     float m = -INFINITY, s = 0.f;
-    for (int32_t k0 = b + threadIdx.x; k0 < e; k0 += kTwoPassUnroll * kBlock) {
-        float v[kTwoPassUnroll];
+    float cur[kTwoPassUnroll], nxt[kTwoPassUnroll];
+    load(b + threadIdx.x, cur, -INFINITY);
+    for (int32_t k0 = b + threadIdx.x; k0 < e; k0 += kStep) {
+        load(k0 + kStep, nxt, -INFINITY);          // past the end: nothing is read
+        float mb = cur[0];
 #pragma unroll
-        for (int u = 0; u < kTwoPassUnroll; ++u) v[u] = k0 + u * kBlock < e ? in[k0 + u * kBlock] : -INFINITY;
-        float mb = v[0];
-#pragma unroll
-        for (int u = 1; u < kTwoPassUnroll; ++u) mb = fmaxf(mb, v[u]);
+        for (int u = 1; u < kTwoPassUnroll; ++u) mb = fmaxf(mb, cur[u]);
         if (mb > m) {
             s *= expf(m - mb);          // exp(-inf) = 0 on the first batch
             m = mb;
         }
 #pragma unroll
-        for (int u = 0; u < kTwoPassUnroll; ++u) s += expf(v[u] - m);
+        for (int u = 0; u < kTwoPassUnroll; ++u) s += expf(cur[u] - m);
+#pragma unroll
+        for (int u = 0; u < kTwoPassUnroll; ++u) cur[u] = nxt[u];
     }
     const float wm = wave_max(m);
     const float ws = wave_sum(m > -INFINITY ? s * expf(m - wm) : 0.f);
@@ -293,59 +316,62 @@ __device__ __forceinline__ void softmax_row_two_pass(int32_t b, int32_t e, const
 #pragma unroll
     for (int i = 0; i < kBlock / kWave; ++i) S += s_m[i] > -INFINITY ? s_s[i] * expf(s_m[i] - M) : 0.f;
     const float inv = 1.f / S;
-    for (int32_t k0 = b + threadIdx.x; k0 < e; k0 += kTwoPassUnroll * kBlock) {
-        float v[kTwoPassUnroll];
-#pragma unroll
-        for (int u = 0; u < kTwoPassUnroll; ++u) v[u] = k0 + u * kBlock < e ? in[k0 + u * kBlock] : 0.f;
+    load(b + threadIdx.x, cur, 0.f);
+    for (int32_t k0 = b + threadIdx.x; k0 < e; k0 += kStep) {
+        load(k0 + kStep, nxt, 0.f);                // requested before this batch's stores
 #pragma unroll
         for (int u = 0; u < kTwoPassUnroll; ++u)
-            if (k0 + u * kBlock < e) out[k0 + u * kBlock] = expf(v[u] - M) * inv;
+            if (k0 + u * kBlock < e) out[k0 + u * kBlock] = expf(cur[u] - M) * inv;
+#pragma unroll
+        for (int u = 0; u < kTwoPassUnroll; ++u) cur[u] = nxt[u];
     }
 }
 
-// One launch for all rows.  Workgroups 0 .. n_long - 1 take one split row each (they are dispatched first, so the
-// long rows start at once and the many short ones fill in around them; three launches one after the other left
-// most of the chip idle in each); the workgroups behind them take 64 single-segment rows each.
-__global__ __launch_bounds__(kBlock) void row_softmax_kernel(int32_t n_long, const int32_t *__restrict__ long_row,
-                                                             int32_t tail_start, int32_t tail_count,
-                                                             const int32_t *__restrict__ seg_row,
-                                                             const int32_t *__restrict__ seg_dst,
-                                                             const int32_t *__restrict__ row_ptr, const float *in,
-                                                             float *out)
+// One launch, three kinds of workgroups in the order in which they should start: the giant rows first (they run
+// longest), then the other split rows (four per workgroup, one per wavefront), then the single-segment rows (64
+// per workgroup, 16 per wavefront).
+constexpr int kWavesPerBlock = kBlock / kWave;
+__global__ __launch_bounds__(kBlock) void row_softmax_kernel(
+    int32_t n_giant, const int32_t *__restrict__ giant, int32_t n_long, const int32_t *__restrict__ long_ebeg,
+    const int32_t *__restrict__ long_len, int32_t tail_start, int32_t tail_count,
+    const int32_t *__restrict__ seg_ebeg, const int32_t *__restrict__ seg_dst, const float *in, float *out)
 {
-    __shared__ int32_t s_b[kTailRows], s_e[kTailRows];
-    __shared__ float s_m[kBlock / kWave], s_s[kBlock / kWave];
-    __shared__ int s_max;
-    if ((int32_t)blockIdx.x < n_long) {
-        const int32_t row = long_row[blockIdx.x];
-        const int32_t b = row_ptr[row], e = row_ptr[row + 1];
-        // (a register variant for rows of up to 8,192 entries would halve the resident wavefronts of the whole
-        // kernel, which the short rows need more than the long ones need the saved second read)
-        if (e - b <= 8 * kBlock) softmax_row_in_registers<8>(b, e, in, out, s_m, s_s);
-        else softmax_row_two_pass(b, e, in, out, s_m, s_s);
+    __shared__ float s_m[kWavesPerBlock], s_s[kWavesPerBlock];
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
+    int32_t blk = blockIdx.x;
+    if (blk < n_giant) {
+        const int32_t li = giant[blk];
+        const int32_t b = long_ebeg[li];
+        softmax_row_two_pass(b, b + long_len[li], in, out, s_m, s_s);
         return;
     }
-    if (threadIdx.x == 0) s_max = 0;
-    __syncthreads();
-    if (threadIdx.x < kTailRows) {
-        const int64_t i = (int64_t)(blockIdx.x - n_long) * kTailRows + threadIdx.x;
-        int32_t b = 0, e = 0;
-        if (i < tail_count && seg_dst[tail_start + i] < 0) {          // a piece of a split row: not here
-            const int32_t row = seg_row[tail_start + i];
-            b = row_ptr[row];
-            e = row_ptr[row + 1];
-        }
-        s_b[threadIdx.x] = b;
-        s_e[threadIdx.x] = e;
-        if (e > b) atomicMax(&s_max, e - b);
+    blk -= n_giant;
+    const int32_t n_long_blocks = (n_long + kWavesPerBlock - 1) / kWavesPerBlock;
+    if (blk < n_long_blocks) {
+        const int32_t li = blk * kWavesPerBlock + wave;
+        if (li >= n_long) return;
+        const int32_t b = long_ebeg[li], len = long_len[li];
+        if (len <= 8 * kWave) softmax_row_wave<8>(b, b + len, in, out);
+        else if (len <= 16 * kWave) softmax_row_wave<16>(b, b + len, in, out);
+        else if (len <= kGiantRow) softmax_row_wave<kGiantRow / kWave>(b, b + len, in, out);
+        return;                                     // longer: one of the giant rows
     }
-    __syncthreads();
-    const int longest = s_max;
+    blk -= n_long_blocks;
+    const int64_t i = ((int64_t)blk * kWavesPerBlock + wave) * kTailRowsPerWave + lane;
+    int32_t b = 0, len = 0;
+    if (lane < kTailRowsPerWave && i < tail_count) {
+        b = seg_ebeg[tail_start + i];
+        len = -1 - seg_dst[tail_start + i];                           // single-segment rows carry their length
+    }
+    int longest = len;
+#pragma unroll
+    for (int off = 1; off < kTailRowsPerWave; off <<= 1) longest = max(longest, __shfl_xor(longest, off, kWave));
+    longest = __shfl(longest, 0, kWave);
     if (longest == 0) return;
-    if (longest <= 8) softmax_rows<4, 2>(s_b, s_e, in, out);
-    else if (longest <= 16) softmax_rows<8, 2>(s_b, s_e, in, out);
-    else if (longest <= 32) softmax_rows<16, 2>(s_b, s_e, in, out);
-    else softmax_rows<16, kSegLen / 16>(s_b, s_e, in, out);
+    if (longest <= 8) softmax_tail_rows<4, 2>(b, len, in, out);
+    else if (longest <= 16) softmax_tail_rows<8, 2>(b, len, in, out);
+    else if (longest <= 32) softmax_tail_rows<16, 2>(b, len, in, out);
+    else softmax_tail_rows<16, kSegLen / 16>(b, len, in, out);
 }
 
 template <int DT, int G, int NCH, int PB = 16>
@@ -449,11 +475,12 @@ int row_softmax_impl(const tcg_meta *m, const float *d_in, float *d_out, hipStre
 {
     if (m->n_rows == 0 || m->nnz == 0) return TCG_OK;
     const int32_t tail_start = m->h_lane_tab[4], tail_count = m->h_lane_tab[5];
-    const int64_t grid = m->n_long + ceil_div(tail_count, kTailRows);
+    const int64_t grid = m->n_giant + ceil_div(m->n_long, kWavesPerBlock) +
+                         ceil_div(tail_count, kWavesPerBlock * kTailRowsPerWave);
     if (grid > 0) {
-        hipLaunchKernelGGL(row_softmax_kernel, dim3((unsigned)grid), dim3(kBlock), 0, s, (int32_t)m->n_long,
-                           m->d_long_row, tail_start, tail_count, m->d_seg_row, m->d_seg_dst, m->d_row_ptr, d_in,
-                           d_out);
+        hipLaunchKernelGGL(row_softmax_kernel, dim3((unsigned)grid), dim3(kBlock), 0, s, (int32_t)m->n_giant, m->d_giant,
+                           (int32_t)m->n_long, m->d_long_ebeg, m->d_long_len, tail_start, tail_count, m->d_seg_ebeg,
+                           m->d_seg_dst, d_in, d_out);
         TCG_TRY(launch_status("row_softmax_kernel"));
     }
     return TCG_OK;

@@ -192,7 +192,7 @@ struct BuildInfo {
     int32_t sort_tail;                          // single-segment rows ordered by length class
     int32_t flag;                               // CSR validation
     int32_t total_unique;
-    int32_t pad;
+    int32_t n_giant;                            // split rows with more than kGiantRow entries
     int32_t lane_tab[kLaneTabStride * kXcds];   // see plan_segment()
     unsigned long long counters[8];             // choose_path_kernel totals
 };
@@ -897,11 +897,12 @@ __device__ __forceinline__ FillCounts block_exclusive_scan_counts(const FillCoun
 
 // phase 0: split rows and their slots (needs row_ptr only); phase 1: single-segment rows (needs sort_tail).
 __global__ __launch_bounds__(256) void seg_fill_kernel(
-    int phase, int32_t n_rows, const int32_t *__restrict__ rp, const int32_t *__restrict__ ci, const BuildInfo *info,
+    int phase, int32_t n_rows, const int32_t *__restrict__ rp, const int32_t *__restrict__ ci, BuildInfo *info,
     int64_t nb, const int32_t *__restrict__ long_off, const int32_t *__restrict__ slot_off,
     const int32_t *__restrict__ tail_off, int32_t *__restrict__ seg_row,
     int32_t *__restrict__ seg_ebeg, int32_t *__restrict__ seg_dst, int32_t *__restrict__ long_row,
-    int32_t *__restrict__ long_slot_ptr, int32_t *__restrict__ slot_row, int32_t *__restrict__ slot_ebeg,
+    int32_t *__restrict__ long_slot_ptr, int32_t *__restrict__ long_ebeg, int32_t *__restrict__ long_len,
+    int32_t *__restrict__ giant, int32_t *__restrict__ slot_row, int32_t *__restrict__ slot_ebeg,
     int32_t *__restrict__ slot_key)
 {
     constexpr int RPT = kRowBlock / 256;           // rows per thread
@@ -941,7 +942,7 @@ __global__ __launch_bounds__(256) void seg_fill_kernel(
 
     // Single-segment rows are put in (class, row) order in LDS first, so that the workgroup writes its piece
     // of every class as one contiguous run.
-    __shared__ int32_t s_trow[kRowBlock], s_te0[kRowBlock];
+    __shared__ int32_t s_trow[kRowBlock], s_te0[kRowBlock], s_tdeg[kRowBlock];
     __shared__ int s_cstart[kTailClasses + 1];
     int cstart[kTailClasses];
     {
@@ -968,6 +969,10 @@ __global__ __launch_bounds__(256) void seg_fill_kernel(
             if (phase != 0) continue;
             long_row[long_base + lrank] = (int32_t)(r0 + k);
             long_slot_ptr[long_base + lrank] = slot_base + srank;
+            long_ebeg[long_base + lrank] = e0[k];
+            long_len[long_base + lrank] = deg[k];
+            // the few very long rows are listed apart (in any order: the list only says who works on a row)
+            if (deg[k] > kGiantRow) giant[atomicAdd(&info->n_giant, 1)] = long_base + lrank;
             s_lrow[lrank] = (int32_t)(r0 + k);
             s_le0[lrank] = e0[k];
             s_lslot[lrank] = srank;
@@ -980,6 +985,7 @@ __global__ __launch_bounds__(256) void seg_fill_kernel(
                 if (cls[k] == c) lp = seen[c]++;
             s_trow[lp] = (int32_t)(r0 + k);
             s_te0[lp] = e0[k];
+            s_tdeg[lp] = deg[k];
         }
     }
     const int n_lrows = total.v[0], n_lsegs = total.v[1];
@@ -994,7 +1000,7 @@ __global__ __launch_bounds__(256) void seg_fill_kernel(
         const int64_t p = (int64_t)n_slots + tb + (i - s_cstart[c]);
         seg_row[p] = s_trow[i];
         seg_ebeg[p] = s_te0[i];
-        seg_dst[p] = -1;
+        seg_dst[p] = -1 - s_tdeg[i];     // below zero: written straight to the result; carries the row's length
     }
     // the slots of the block's split rows: four per thread and step, their start columns gathered together (the
     // block that holds the hub rows of a power-law graph has thousands of slots)
@@ -1375,6 +1381,10 @@ int sgt_build_impl(tcg_meta *m, int validate, hipStream_t s)
     for (int i = 0; i < 3; ++i) keep.want(seg_bound * 4);
     keep.want(long_bound * 4);
     keep.want((long_bound + 1) * 4);
+    keep.want(long_bound * 4);
+    keep.want(long_bound * 4);
+    const int64_t giant_bound = nnz / (kGiantRow + 1) + 1;
+    keep.want(giant_bound * 4);
     TCG_TRY(keep.commit());
     m->owned[m->n_owned++] = keep.base;
     m->d_win_partition = keep.take<int32_t>(n_win);
@@ -1388,6 +1398,9 @@ int sgt_build_impl(tcg_meta *m, int validate, hipStream_t s)
     m->d_seg_dst = keep.take<int32_t>(seg_bound);
     m->d_long_row = keep.take<int32_t>(long_bound);
     m->d_long_slot_ptr = keep.take<int32_t>(long_bound + 1);
+    m->d_long_ebeg = keep.take<int32_t>(long_bound);
+    m->d_long_len = keep.take<int32_t>(long_bound);
+    m->d_giant = keep.take<int32_t>(giant_bound);
     m->d_lane_tab = info->lane_tab;
     m->d_counters = info->counters;
 
@@ -1513,7 +1526,8 @@ int sgt_build_impl(tcg_meta *m, int validate, hipStream_t s)
         if (nb_rows > 0) {
             hipLaunchKernelGGL(seg_fill_kernel, dim3((unsigned)nb_rows), dim3(256), 0, ps, 0, n, m->d_row_ptr, m->d_col_idx,
                                info, nb_rows, long_off, slot_off, tail_off, m->d_seg_row, m->d_seg_ebeg, m->d_seg_dst,
-                               m->d_long_row, m->d_long_slot_ptr, slot_row, slot_ebeg, slot_key);
+                               m->d_long_row, m->d_long_slot_ptr, m->d_long_ebeg, m->d_long_len, m->d_giant, slot_row, slot_ebeg,
+                               slot_key);
             TCG_TRY(launch_status("plan kernels"));
             const bool sorted = sort_bytes > 0 && slot_bound > 1;
             if (sorted)
@@ -1558,7 +1572,8 @@ int sgt_build_impl(tcg_meta *m, int validate, hipStream_t s)
     if (nb_rows > 0)
         hipLaunchKernelGGL(seg_fill_kernel, dim3((unsigned)nb_rows), dim3(256), 0, s, 1, n, m->d_row_ptr, m->d_col_idx,
                            info, nb_rows, long_off, slot_off, tail_off, m->d_seg_row, m->d_seg_ebeg,
-                           m->d_seg_dst, m->d_long_row, m->d_long_slot_ptr, slot_row, slot_ebeg, slot_key);
+                           m->d_seg_dst, m->d_long_row, m->d_long_slot_ptr, m->d_long_ebeg, m->d_long_len, m->d_giant, slot_row, slot_ebeg,
+                               slot_key);
     launch_choose_path(m, TCG_POLICY_AUTO, kDefaultMinReuse, s);
     TCG_TRY(launch_status("plan and path kernels"));
 
@@ -1567,6 +1582,7 @@ int sgt_build_impl(tcg_meta *m, int validate, hipStream_t s)
     TCG_HIP(hipStreamSynchronize(s));                       // the one wait of a build
     m->n_seg = h.n_seg;
     m->n_long = h.n_long;
+    m->n_giant = h.n_giant;
     m->n_slots = h.n_slots;
     m->total_unique = h.total_unique;
     for (int i = 0; i < kLaneTabStride * kXcds; ++i) m->h_lane_tab[i] = h.lane_tab[i];
