@@ -166,8 +166,12 @@ class Run:
         pl = perm.long()
         _, t_x = once_ms(lambda: self.Xd[self.feat][pl])
         u_before = tcg.sgt_build(rp, ci, self.H, self.TW, validate=False)
+        # the same three steps as one library call (clustering + relabelling + translation)
+        (m1, _, _), t_one = once_ms(lambda: tcg.sgt_build_clustered(rp, ci, self.H, self.TW, seed=0, refine=rounds))
+        m1.free()
         self.reorder_info = {"refine_rounds": rounds, "reorder_rows_ms": t_perm, "csr_permute_ms": t_csr,
-                             "permute_X_ms": t_x, "window_unique_before": u_before.total_unique}
+                             "permute_X_ms": t_x, "sgt_build_clustered_ms": t_one,
+                             "window_unique_before": u_before.total_unique}
         u_before.free()
         self.rp, self.ci, self.perm = rp2, ci2, perm
         self.Xd = {k: v[pl].contiguous() for k, v in self.Xd.items()}

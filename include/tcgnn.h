@@ -236,6 +236,25 @@ TCG_API int tcg_attention(tcg_meta *meta, const void *d_X, tcg_dtype x_dt, int32
                   float *d_scores, void *d_Y, tcg_dtype y_dt, int64_t ldy, void *stream);
 
 /*
+ * The fused aggregation with cosine-style scores, as the attention layer of the paper's AGNN model uses them
+ * (the evaluation section names the model, 4 layers of 32 hidden features; the paper leaves its normalisation
+ * open -- this is the published AGNN propagation):
+ *   c_e = d_rnorm[i] * d_rnorm[j] * < X[i], X[j] >      for the stored entry e = (i, j)
+ *   Y[i] = sum over the stored entries e of row i of  softmax_i(beta * c)_e * X[j]
+ * With d_rnorm[v] = 1 / |X[v]| (tcg_row_rnorm) c_e is the cosine of the two feature rows; X itself, not a
+ * normalised copy, is gathered once per entry for score and aggregation alike.  d_scores: NULL, or device
+ * float[nnz] that receives c (without beta) in CSR order.  d_rnorm: device float[max(n_rows, n_cols)].
+ * Same operand requirements as tcg_attention.
+ */
+TCG_API int tcg_attention_cos(tcg_meta *meta, const void *d_X, tcg_dtype x_dt, int32_t D, int64_t ldx,
+                      const float *d_rnorm, float beta, float *d_scores, void *d_Y, tcg_dtype y_dt, int64_t ldy,
+                      void *stream);
+
+/* d_out[i] = 1 / max(|X[i]|_2, eps) for the n rows of X (row-major, leading dimension ldx, type x_dt); eps > 0. */
+TCG_API int tcg_row_rnorm(int64_t n, const void *d_X, tcg_dtype x_dt, int32_t D, int64_t ldx, float eps,
+                  float *d_out, void *stream);
+
+/*
  * Gradient of tcg_row_softmax:  d_dv[e] = d_p[e] * (d_dp[e] - sum over the row of d_p * d_dp), where d_p is
  * the softmax output and d_dp the gradient with respect to it.  In-place (d_dv == d_dp) is allowed.
  */
@@ -288,6 +307,24 @@ TCG_API int tcg_reorder_rows(int32_t n, int64_t nnz, const int32_t *d_row_ptr, c
 TCG_API int tcg_csr_permute(int32_t n, int64_t nnz, const int32_t *d_row_ptr, const int32_t *d_col_idx,
                     const int32_t *d_perm, int32_t *d_out_row_ptr, int32_t *d_out_col_idx,
                     int32_t *d_edge_perm, void *stream);
+
+/*
+ * Row clustering, relabelling and translation in one call, for graphs whose labelling scatters the members of
+ * a community (the paper's related-work section calls row reordering orthogonal and complementary to SGT):
+ * tcg_reorder_rows -> tcg_csr_permute -> tcg_sgt_build on a square n x n pattern.
+ *   d_perm          device int32[n]      out: new -> old, the relabelling
+ *   d_out_row_ptr   device int32[n + 1]  out: the relabelled pattern; BORROWED by the metadata object like the
+ *   d_out_col_idx   device int32[nnz]         CSR arrays of tcg_sgt_build (keep them alive until tcg_sgt_free)
+ *   d_edge_perm     device int32[nnz] or NULL  out: entry k of the relabelled pattern is entry d_edge_perm[k] of
+ *                                              the input (edge values follow with tcg_edge_gather)
+ * The metadata object describes the relabelled graph: features go in as X'[i] = X[d_perm[i]], results come out
+ * as Y'[i] = Y[d_perm[i]], edge outputs in the relabelled entry order.  Returns TCG_ECSR for a malformed pattern.
+ * Blocks until the stream has finished.
+ */
+TCG_API int tcg_sgt_build_clustered(int32_t n, int64_t nnz, const int32_t *d_row_ptr, const int32_t *d_col_idx,
+                            int32_t window_h, int32_t tile_w, uint64_t seed, int32_t refine, void *stream,
+                            int32_t *d_perm, int32_t *d_out_row_ptr, int32_t *d_out_col_idx,
+                            int32_t *d_edge_perm, tcg_meta **out);
 
 /* Releases the metadata object and every device buffer it owns (NULL is a no-op).  The caller
  * must make sure no kernel using it is still running (its buffers go back to the library's cache

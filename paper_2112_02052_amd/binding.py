@@ -16,7 +16,8 @@ EXPORTED = ["tcg_sgt_build", "tcg_sgt_sizes", "tcg_sgt_export", "tcg_sgt_set_pol
             "tcg_sgt_plan_stats", "tcg_spmm", "tcg_sddmm", "tcg_row_softmax", "tcg_sgt_free",
             "tcg_strerror", "tcg_release_cached_memory", "tcg_sddmm_pq", "tcg_row_softmax_backward",
             "tcg_csr_transpose", "tcg_edge_gather", "tcg_attention", "tcg_reorder_rows", "tcg_csr_permute",
-            "tcg_sgt_reserve", "tcg_spmm_noalloc", "tcg_sgt_tile_stats"]
+            "tcg_sgt_reserve", "tcg_spmm_noalloc", "tcg_sgt_tile_stats", "tcg_attention_cos", "tcg_row_rnorm",
+            "tcg_sgt_build_clustered"]
 
 _DTYPES = {torch.float32: TCG_F32, torch.bfloat16: TCG_BF16, torch.float16: TCG_F16}
 
@@ -81,6 +82,14 @@ def load_library():
     lib.tcg_attention.restype = ctypes.c_int
     lib.tcg_attention.argtypes = [_vp, _vp, ctypes.c_int, ctypes.c_int32, ctypes.c_int64, _vp, _vp, ctypes.c_int,
                                   ctypes.c_int64, _vp]
+    lib.tcg_attention_cos.restype = ctypes.c_int
+    lib.tcg_attention_cos.argtypes = [_vp, _vp, ctypes.c_int, ctypes.c_int32, ctypes.c_int64, _vp, ctypes.c_float, _vp, _vp,
+                                      ctypes.c_int, ctypes.c_int64, _vp]
+    lib.tcg_row_rnorm.restype = ctypes.c_int
+    lib.tcg_row_rnorm.argtypes = [ctypes.c_int64, _vp, ctypes.c_int, ctypes.c_int32, ctypes.c_int64, ctypes.c_float, _vp, _vp]
+    lib.tcg_sgt_build_clustered.restype = ctypes.c_int
+    lib.tcg_sgt_build_clustered.argtypes = [ctypes.c_int32, ctypes.c_int64, _vp, _vp, ctypes.c_int32, ctypes.c_int32,
+                                            ctypes.c_uint64, ctypes.c_int32, _vp, _vp, _vp, _vp, _vp, ctypes.POINTER(_vp)]
     lib.tcg_release_cached_memory.restype = None
     lib.tcg_release_cached_memory.argtypes = []
     lib.tcg_strerror.restype = ctypes.c_char_p
@@ -353,3 +362,53 @@ def attention(meta, X, Y=None, scores=None, y_dtype=torch.float32):
                                         _DTYPES[Y.dtype], Y.stride(0) if meta.n_rows > 1 else max(D, Y.stride(0)),
                                         _stream()))
     return Y
+
+
+def row_rnorm(X, eps=1e-12, out=None):
+    """tcg_row_rnorm: out[i] = 1 / max(|X[i]|, eps), fp32."""
+    _need_cuda(X)
+    if X.dim() != 2 or X.dtype not in _DTYPES or X.stride(1) != 1:
+        raise ValueError("X must be a 2-D fp32/bf16/fp16 tensor with unit stride along features")
+    if out is None:
+        out = torch.empty(X.shape[0], dtype=torch.float32, device=X.device)
+    _check(load_library().tcg_row_rnorm(X.shape[0], _ptr(X), _DTYPES[X.dtype], X.shape[1], X.stride(0), float(eps), _ptr(out),
+                                        _stream()))
+    return out
+
+
+def attention_cos(meta, X, rnorm, beta, Y=None, scores=None, y_dtype=torch.float32):
+    """tcg_attention_cos: Y[i] = sum_e softmax_i(beta * c)_e x_j with c_e = rnorm_i rnorm_j <x_i, x_j>; `scores`
+    (optional fp32 [nnz]) receives c."""
+    X = _features(meta, X, max(meta.n_rows, meta.n_cols))
+    D = X.shape[1]
+    _need_cuda(rnorm)
+    if rnorm.dtype != torch.float32 or rnorm.numel() < max(meta.n_rows, meta.n_cols) or not rnorm.is_contiguous():
+        raise ValueError("rnorm must be a contiguous fp32 tensor with one value per node")
+    if Y is None:
+        Y = torch.empty((meta.n_rows, D), dtype=y_dtype, device=X.device)
+    _need_cuda(Y, scores)
+    if Y.dim() != 2 or Y.shape != (meta.n_rows, D) or Y.stride(1) != 1 or Y.dtype not in _DTYPES:
+        raise ValueError("Y must be [n_rows, D] with unit stride along features")
+    if scores is not None and (scores.dtype != torch.float32 or scores.numel() != meta.nnz or not scores.is_contiguous()):
+        raise ValueError("scores must be a contiguous fp32 tensor with one value per stored entry")
+    _check(load_library().tcg_attention_cos(meta._h, _ptr(X), _DTYPES[X.dtype], D, X.stride(0), _ptr(rnorm), float(beta),
+                                            _ptr(scores), _ptr(Y), _DTYPES[Y.dtype],
+                                            Y.stride(0) if meta.n_rows > 1 else max(D, Y.stride(0)), _stream()))
+    return Y
+
+
+def sgt_build_clustered(row_ptr, col_idx, window_h=16, tile_w=8, seed=0, refine=2, want_edge_perm=True):
+    """tcg_sgt_build_clustered: (meta of the relabelled graph, perm [new -> old], edge_perm or None).  The meta's
+    row_ptr / col_idx are the relabelled pattern."""
+    row_ptr, col_idx = _square_csr(row_ptr, col_idx)
+    n, nnz = row_ptr.numel() - 1, col_idx.numel()
+    dev = row_ptr.device
+    perm = torch.empty(n, dtype=torch.int32, device=dev)
+    rp2 = torch.empty(n + 1, dtype=torch.int32, device=dev)
+    ci2 = torch.empty(nnz, dtype=torch.int32, device=dev)
+    ep = torch.empty(nnz, dtype=torch.int32, device=dev) if want_edge_perm else None
+    h = ctypes.c_void_p()
+    _check(load_library().tcg_sgt_build_clustered(n, nnz, _ptr(row_ptr), _ptr(col_idx), int(window_h), int(tile_w),
+                                                  int(seed) & (2 ** 64 - 1), int(refine), _stream(), _ptr(perm), _ptr(rp2),
+                                                  _ptr(ci2), _ptr(ep), ctypes.byref(h)))
+    return Meta(h, rp2, ci2, n, n, int(window_h), int(tile_w)), perm, ep

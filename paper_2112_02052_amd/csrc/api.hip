@@ -74,6 +74,23 @@ int tcg_sgt_build(int32_t n_rows, int32_t n_cols, int64_t nnz, const int32_t *d_
     return TCG_OK;
 }
 
+int tcg_sgt_build_clustered(int32_t n, int64_t nnz, const int32_t *d_row_ptr, const int32_t *d_col_idx,
+                            int32_t window_h, int32_t tile_w, uint64_t seed, int32_t refine, void *stream,
+                            int32_t *d_perm, int32_t *d_out_row_ptr, int32_t *d_out_col_idx, int32_t *d_edge_perm,
+                            tcg_meta **out)
+{
+    if (!out || !d_row_ptr || !d_out_row_ptr || n < 0 || nnz < 0 || refine < 0 || window_h < 1 || tile_w < 1)
+        return TCG_EINVAL;
+    if (n > 0 && !d_perm) return TCG_EINVAL;
+    if (nnz > 0 && (!d_col_idx || !d_out_col_idx)) return TCG_EINVAL;
+    if (nnz >= (int64_t)INT32_MAX || (int64_t)n + 1 >= (int64_t)INT32_MAX) return TCG_ERANGE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    // the clustering validates the pattern (TCG_ECSR), so the translation need not do it again
+    TCG_TRY(reorder_rows_impl(n, nnz, d_row_ptr, d_col_idx, seed, refine, d_perm, s));
+    TCG_TRY(csr_permute_impl(n, nnz, d_row_ptr, d_col_idx, d_perm, d_out_row_ptr, d_out_col_idx, d_edge_perm, s));
+    return tcg_sgt_build(n, n, nnz, d_out_row_ptr, d_out_col_idx, window_h, tile_w, 0, stream, out);
+}
+
 int tcg_sgt_sizes(const tcg_meta *meta, int64_t *n_windows, int64_t *total_unique, int64_t *total_tiles,
                   int64_t *nnz)
 {
@@ -193,7 +210,25 @@ int tcg_attention(tcg_meta *meta, const void *d_X, tcg_dtype x_dt, int32_t D, in
     if (!meta || D < 1 || ldx < D || ldy < D || !dtype_ok(x_dt) || !dtype_ok(y_dt)) return TCG_EINVAL;
     if ((!d_X && meta->nnz > 0) || (!d_Y && meta->n_rows > 0)) return TCG_EINVAL;
     if ((reinterpret_cast<uintptr_t>(d_Y) % dtype_size(y_dt))) return TCG_EINVAL;
-    return attention_impl(meta, d_X, x_dt, D, ldx, d_scores, d_Y, y_dt, ldy, static_cast<hipStream_t>(stream));
+    return attention_impl(meta, d_X, x_dt, D, ldx, nullptr, 1.f, d_scores, d_Y, y_dt, ldy, static_cast<hipStream_t>(stream));
+}
+
+int tcg_attention_cos(tcg_meta *meta, const void *d_X, tcg_dtype x_dt, int32_t D, int64_t ldx, const float *d_rnorm,
+                      float beta, float *d_scores, void *d_Y, tcg_dtype y_dt, int64_t ldy, void *stream)
+{
+    if (!meta || D < 1 || ldx < D || ldy < D || !dtype_ok(x_dt) || !dtype_ok(y_dt)) return TCG_EINVAL;
+    if ((!d_X && meta->nnz > 0) || (!d_Y && meta->n_rows > 0) || (!d_rnorm && meta->n_rows > 0)) return TCG_EINVAL;
+    if ((reinterpret_cast<uintptr_t>(d_Y) % dtype_size(y_dt))) return TCG_EINVAL;
+    return attention_impl(meta, d_X, x_dt, D, ldx, d_rnorm, beta, d_scores, d_Y, y_dt, ldy,
+                          static_cast<hipStream_t>(stream));
+}
+
+int tcg_row_rnorm(int64_t n, const void *d_X, tcg_dtype x_dt, int32_t D, int64_t ldx, float eps, float *d_out, void *stream)
+{
+    if (n < 0 || D < 1 || ldx < D || !dtype_ok(x_dt) || !(eps > 0.f)) return TCG_EINVAL;
+    if (n > 0 && (!d_X || !d_out)) return TCG_EINVAL;
+    if (reinterpret_cast<uintptr_t>(d_X) % dtype_size(x_dt)) return TCG_EINVAL;
+    return row_rnorm_impl(n, d_X, x_dt, D, ldx, eps, d_out, static_cast<hipStream_t>(stream));
 }
 
 int tcg_row_softmax_backward(const tcg_meta *meta, const float *d_p, const float *d_dp, float *d_dv, void *stream)

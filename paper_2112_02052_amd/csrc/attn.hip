@@ -1,5 +1,8 @@
 // Fused attention-style aggregation: Y[i] = sum_e softmax_i(<x_i, x_j>)_e * x_j, i.e. the chain
 // SDDMM (Equation 2) -> row softmax -> SpMM (Equation 1) of the paper's AGNN workload in one pass.
+// With per-node factors r and a scale beta the score of an edge becomes beta * r_i * r_j * <x_i, x_j>: with
+// r = 1 / |x| that is the cosine attention of the AGNN layer, computed while x_j itself (not its normalised
+// copy) is gathered once for score and aggregation alike.
 //
 // Run as three library calls the chain gathers every neighbour row twice (once for the score, once
 // for the aggregation) and moves the scores through HBM three times.  Here a group of G lanes walks a
@@ -18,12 +21,13 @@ namespace {
 
 constexpr int kBlock = 256;
 
-template <int DT, int G, int NCH, int UNROLL>
+template <int DT, int G, int NCH, int UNROLL, bool HAS_R>
 __global__ __launch_bounds__(kBlock) void attn_fused_kernel(
     const int32_t *__restrict__ lane_tab, const int32_t *__restrict__ seg_row, const int32_t *__restrict__ seg_ebeg,
     const int32_t *__restrict__ seg_dst, const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ col_idx,
-    const char *__restrict__ X, int64_t ldx_bytes, int32_t n_chunks, int32_t D, float *__restrict__ scores,
-    void *__restrict__ Y, int y_dt, int64_t ldy, float *__restrict__ partial, float *__restrict__ partial_ml)
+    const char *__restrict__ X, int64_t ldx_bytes, int32_t n_chunks, int32_t D, const float *__restrict__ rnorm,
+    float beta, float *__restrict__ scores, void *__restrict__ Y, int y_dt, int64_t ldy, float *__restrict__ partial,
+    float *__restrict__ partial_ml)
 {
     constexpr int VEC = Elem<DT>::VEC;
     const int lane = threadIdx.x % G;
@@ -47,6 +51,7 @@ __global__ __launch_bounds__(kBlock) void attn_fused_kernel(
         }
     }
     float m_run = -INFINITY, l_run = 0.f;
+    const float r_i = HAS_R ? rnorm[row] : 1.f;
 
     if (eb < ee) {
         const int32_t last = ee - 1;
@@ -59,10 +64,11 @@ __global__ __launch_bounds__(kBlock) void attn_fused_kernel(
 #pragma unroll
             for (int u = 0; u < UNROLL; ++u) cnext[u] = col_idx[min(e + UNROLL + u, last)];
             float v[UNROLL][NCH][VEC];
-            float p[UNROLL];
+            float p[UNROLL], rj[UNROLL];
 #pragma unroll
             for (int u = 0; u < UNROLL; ++u) {
                 const char *xr = X + (uint64_t)(uint32_t)cn[u] * ldx32;
+                rj[u] = HAS_R ? rnorm[cn[u]] : 1.f;         // the same address in every lane of the group
                 float a = 0.f;
 #pragma unroll
                 for (int c = 0; c < NCH; ++c) {
@@ -78,21 +84,36 @@ __global__ __launch_bounds__(kBlock) void attn_fused_kernel(
 #pragma unroll
             for (int u = 0; u < UNROLL; ++u) cn[u] = cnext[u];
 
-            // Scores of the UNROLL edges, known to every lane of the group.
+            // Scores of the UNROLL edges, known to every lane of the group: the stored score is
+            // r_i * r_j * <x_i, x_j>, the softmax runs over beta times that.
             float s[UNROLL];
             const float r = group_reduce<G, UNROLL>(p, lane);
             if constexpr (G >= UNROLL) {
-                if (scores != nullptr && lane < UNROLL && e + lane < ee) scores[e + lane] = r;
 #pragma unroll
                 for (int u = 0; u < UNROLL; ++u) s[u] = __shfl(r, u, G);
             } else {
 #pragma unroll
                 for (int u = 0; u < UNROLL; ++u) s[u] = p[u];
-                if (scores != nullptr && lane == 0) {
+            }
+            if constexpr (HAS_R) {
+#pragma unroll
+                for (int u = 0; u < UNROLL; ++u) s[u] *= r_i * rj[u];
+            }
+            if (scores != nullptr) {
+                if constexpr (G >= UNROLL) {        // lane u stores the score of edge u: one coalesced store
+                    float mine = s[0];
+#pragma unroll
+                    for (int u = 1; u < UNROLL; ++u) mine = lane == u ? s[u] : mine;
+                    if (lane < UNROLL && e + lane < ee) scores[e + lane] = mine;
+                } else if (lane == 0) {
 #pragma unroll
                     for (int u = 0; u < UNROLL; ++u)
                         if (e + u < ee) scores[e + u] = s[u];
                 }
+            }
+            if constexpr (HAS_R) {
+#pragma unroll
+                for (int u = 0; u < UNROLL; ++u) s[u] *= beta;
             }
             // Online softmax update (edge e itself is always valid, so the new maximum is finite).
             float m_new = m_run;
@@ -164,6 +185,8 @@ struct Args {
     const void *X;
     int64_t ldx;
     int32_t D;
+    const float *rnorm;
+    float beta;
     float *scores;
     void *Y;
     int y_dt;
@@ -178,10 +201,16 @@ void launch(const Args &a, int32_t n_chunks)
     constexpr int UNROLL = NCH == 1 ? 8 : (NCH == 2 ? 4 : 2);
     const tcg_meta *m = a.m;
     const unsigned grid = (unsigned)plan_grid(m->h_lane_tab, kBlock / G);
-    hipLaunchKernelGGL((attn_fused_kernel<DT, G, NCH, UNROLL>), dim3(grid), dim3(kBlock), 0, a.s, m->d_lane_tab,
-                       m->d_seg_row, m->d_seg_ebeg, m->d_seg_dst, m->d_row_ptr, m->d_col_idx,
-                       static_cast<const char *>(a.X), a.ldx * Elem<DT>::BYTES, n_chunks, a.D, a.scores, a.Y, a.y_dt, a.ldy,
-                       m->d_partial, a.partial_ml);
+    if (a.rnorm)
+        hipLaunchKernelGGL((attn_fused_kernel<DT, G, NCH, UNROLL, true>), dim3(grid), dim3(kBlock), 0, a.s, m->d_lane_tab,
+                           m->d_seg_row, m->d_seg_ebeg, m->d_seg_dst, m->d_row_ptr, m->d_col_idx,
+                           static_cast<const char *>(a.X), a.ldx * Elem<DT>::BYTES, n_chunks, a.D, a.rnorm, a.beta,
+                           a.scores, a.Y, a.y_dt, a.ldy, m->d_partial, a.partial_ml);
+    else
+        hipLaunchKernelGGL((attn_fused_kernel<DT, G, NCH, UNROLL, false>), dim3(grid), dim3(kBlock), 0, a.s, m->d_lane_tab,
+                           m->d_seg_row, m->d_seg_ebeg, m->d_seg_dst, m->d_row_ptr, m->d_col_idx,
+                           static_cast<const char *>(a.X), a.ldx * Elem<DT>::BYTES, n_chunks, a.D, a.rnorm, a.beta,
+                           a.scores, a.Y, a.y_dt, a.ldy, m->d_partial, a.partial_ml);
 }
 
 template <int DT>
@@ -199,8 +228,34 @@ bool dispatch(const Args &a, int32_t n_chunks)
 
 }  // namespace
 
-int attention_impl(tcg_meta *m, const void *d_X, tcg_dtype x_dt, int32_t D, int64_t ldx, float *d_scores, void *d_Y,
-                   tcg_dtype y_dt, int64_t ldy, hipStream_t s)
+// out[i] = 1 / max(|x_i|, eps): 16 lanes per row.
+__global__ __launch_bounds__(256) void row_rnorm_kernel(int64_t n, const void *__restrict__ X, int x_dt, int32_t D,
+                                                        int64_t ldx, float eps, float *__restrict__ out)
+{
+    const int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) / 16;
+    const int gl = threadIdx.x % 16;
+    float a = 0.f;
+    if (i < n)
+        for (int32_t d = gl; d < D; d += 16) {
+            const float v = load_elem(X, i * ldx + d, x_dt);
+            a = fmaf(v, v, a);
+        }
+#pragma unroll
+    for (int off = 1; off < 16; off <<= 1) a += __shfl_xor(a, off, kWave);
+    if (i < n && gl == 0) out[i] = 1.f / fmaxf(sqrtf(a), eps);
+}
+
+int row_rnorm_impl(int64_t n, const void *d_X, tcg_dtype x_dt, int32_t D, int64_t ldx, float eps, float *d_out,
+                   hipStream_t s)
+{
+    if (n == 0) return TCG_OK;
+    hipLaunchKernelGGL(row_rnorm_kernel, dim3((unsigned)ceil_div(n * 16, 256)), dim3(256), 0, s, n, d_X, (int)x_dt, D, ldx,
+                       eps, d_out);
+    return launch_status("row_rnorm_kernel");
+}
+
+int attention_impl(tcg_meta *m, const void *d_X, tcg_dtype x_dt, int32_t D, int64_t ldx, const float *d_rnorm, float beta,
+                   float *d_scores, void *d_Y, tcg_dtype y_dt, int64_t ldy, hipStream_t s)
 {
     if (m->n_rows == 0) return TCG_OK;
     const int es = dtype_size(x_dt);
@@ -211,7 +266,7 @@ int attention_impl(tcg_meta *m, const void *d_X, tcg_dtype x_dt, int32_t D, int6
     // Scratch: fp32 accumulators of split rows (shared with tcg_spmm) and their (max, denominator).
     TCG_TRY(reserve_partial(m, D, s));
 
-    Args a{m, d_X, ldx, D, d_scores, d_Y, (int)y_dt, ldy, m->d_partial_ml, s};
+    Args a{m, d_X, ldx, D, d_rnorm, beta, d_scores, d_Y, (int)y_dt, ldy, m->d_partial_ml, s};
     const int32_t n_chunks = (int32_t)((int64_t)D * es / 16);
     bool ok;
     if (x_dt == TCG_F32) ok = dispatch<TCG_F32>(a, n_chunks);

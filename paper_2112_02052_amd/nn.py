@@ -135,6 +135,49 @@ class _SelfAttention(torch.autograd.Function):
         return None, dX.to(Xc.dtype)
 
 
+class _CosAttention(torch.autograd.Function):
+    """Y_i = sum_e softmax_i(beta cos(x_i, x_j))_e x_j -- the AGNN propagation -- through the fused kernel
+    forward (inverse row norms from one small kernel, X gathered once per edge) and the library's building
+    blocks backward.  With r = 1 / max(|x|, eps), xn = r x, c_e = <xn_i, xn_j>, p = row softmax of beta c:
+        dp = sddmm_pq(dY, X),  ds = row_softmax_backward(p, dp),  dbeta = sum_e ds_e c_e,  dc = beta ds
+        dXn = (dc . A) Xn + (dc . A)^T Xn,   dX = (p . A)^T dY + r (dXn - xn <dXn, xn>)
+    (for a row shorter than eps the projection term vanishes with xn, as in the clamped normalisation)."""
+
+    EPS = 1e-12
+
+    @staticmethod
+    def forward(ctx, graph, X, beta):
+        Xc = _f32c(X) if X.dtype == torch.float32 else X.contiguous()
+        r = _b.row_rnorm(Xc, _CosAttention.EPS)
+        c = torch.empty(graph.nnz, dtype=torch.float32, device=X.device)
+        Y = _b.attention_cos(graph.meta, Xc, r, float(beta), scores=c)
+        ctx.graph = graph
+        ctx.save_for_backward(Xc, r, c, beta)
+        return Y
+
+    @staticmethod
+    def backward(ctx, dY):
+        graph = ctx.graph
+        Xc, r, c, beta = ctx.saved_tensors
+        meta_t, perm = graph.transposed()
+        dY = dY.contiguous().to(Xc.dtype)
+        p = _b.row_softmax(graph.meta, c * beta)
+        dp = _b.sddmm_pq(graph.meta, dY, Xc)
+        ds = _b.row_softmax_backward(graph.meta, p, dp)
+        dbeta = (ds * c).sum() if ctx.needs_input_grad[2] else None
+        dX = None
+        if ctx.needs_input_grad[1]:
+            dc = ds * beta
+            Xn = (Xc.to(torch.float32) * r[:, None]).to(Xc.dtype)
+            dXn = _b.spmm(graph.meta, Xn, dc)
+            dXn += _b.spmm(meta_t, Xn, _b.edge_gather(perm, dc))
+            Xn32 = Xn.to(torch.float32)
+            dX = _b.spmm(meta_t, dY, _b.edge_gather(perm, p))
+            dX += (dXn - Xn32 * (dXn * Xn32).sum(dim=1, keepdim=True)) * r[:, None]
+            dX = dX.to(Xc.dtype)
+        return None, dX, dbeta
+
+
 def _tall_tn(A, B, chunk=4096):
     """A^T B for tall A [N, p] and B [N, q]: the reduction over the N nodes is cut into chunks that run as
     one batched GEMM and are then added, which gives the BLAS library parallel work when p and q are
@@ -203,6 +246,17 @@ def self_attention(graph, X):
     return _SelfAttention.apply(graph, X)
 
 
+def _fused_attention_ok(X):
+    """The fused attention kernels read rows in 16-byte pieces of at most 2 KB."""
+    row_bytes = X.shape[1] * X.element_size()
+    return row_bytes % 16 == 0 and row_bytes <= 2048 and (X.stride(0) * X.element_size()) % 16 == 0
+
+
+def cos_attention(graph, X, beta):
+    """Differentiable Y_i = sum_e softmax_i(beta cos(x_i, x_j))_e x_j (fused forward); beta: 0-d tensor."""
+    return _CosAttention.apply(graph, X, beta)
+
+
 class GCNConv(torch.nn.Module):
     """Graph convolution: neighbour aggregation with fixed edge values (the symmetric normalisation
     1/sqrt(deg_i deg_j) in the GCN model) and a linear update.  The update is applied on whichever side
@@ -243,6 +297,8 @@ class AGNNConv(torch.nn.Module):
             self.register_buffer("beta", beta)
 
     def forward(self, X, graph):
+        if _fused_attention_ok(X):
+            return _CosAttention.apply(graph, X, self.beta)
         Xn = torch.nn.functional.normalize(X, p=2.0, dim=1)
         p = row_softmax(graph, self.beta * sddmm(graph, Xn))
         return spmm(graph, X, p)

@@ -158,3 +158,32 @@ def test_fused_attention_matches_the_three_call_chain(x_dtype):
         torch.cuda.synchronize()
         assert norm_err(Y.cpu().numpy(), Y3.cpu().numpy().astype(np.float64)) <= (1e-4 if x_dtype == "f32" else TOL_MFMA)
         meta.free()
+
+
+@pytest.mark.parametrize("x_dtype", ["f32", "bf16"])
+def test_cosine_attention_matches_the_chain_on_normalised_rows(x_dtype):
+    # tcg_row_rnorm + tcg_attention_cos against the oracle's chain: c_e = <x_i, x_j> / (|x_i| |x_j|) (the oracle's
+    # SDDMM scaled in double), row softmax of beta * c, aggregation of the unnormalised rows.  Hub rows (split
+    # segments merged under the online softmax), empty rows and one all-zero feature row included.
+    c = W.make_config(3, n=20000, d=32)
+    g = c["csr"]
+    X = W.round_to_bf16(c["X"]) if x_dtype == "bf16" else c["X"].copy()
+    X[17, :] = 0.0
+    beta = 1.7
+    rp, ci = upload_csr(g)
+    Xd = upload_x(X, x_dtype)
+    meta = tcg.sgt_build(rp, ci, 16, 8)
+    r = tcg.row_rnorm(Xd)
+    nrm = np.sqrt((X.astype(np.float64) ** 2).sum(axis=1))
+    r_ref = 1.0 / np.maximum(nrm, 1e-12)
+    assert norm_err(r.cpu().numpy()[nrm > 0], r_ref[nrm > 0]) <= TOL_F32
+    cs = torch.empty(g.nnz, device=dev())
+    Y = tcg.attention_cos(meta, Xd, r, beta, scores=cs)
+    torch.cuda.synchronize()
+    rows = np.repeat(np.arange(g.n_rows), np.diff(g.row_ptr))
+    c_ref = oracle.sddmm(g.row_ptr, g.col_idx, X) * r_ref[rows] * r_ref[g.col_idx]
+    p_ref = oracle.row_softmax(g.row_ptr, beta * c_ref)
+    Y_ref = oracle.spmm(g.row_ptr, g.col_idx, X, p_ref.astype(np.float32))
+    assert norm_err(cs.cpu().numpy(), c_ref) <= TOL_F32
+    assert norm_err(Y.cpu().numpy(), Y_ref) <= 1e-4            # the chain's end-to-end bound (exp of an fp32 score)
+    meta.free()

@@ -10,7 +10,8 @@ import oracle.reorder as R
 import paper_2112_02052_amd as tcg
 import workloads as W
 
-from gpu_util import TOL_F32, dev, norm_err, upload_csr, upload_x
+from gpu_util import TOL_F32, TOL_MFMA, check_sgt, dev, norm_err, upload_csr, upload_x
+from workloads.graphs import CSR
 from test_gpu_parity import csr_from_rows, hub_graph
 
 pytestmark = pytest.mark.gpu
@@ -121,3 +122,36 @@ def test_aggregation_commutes_with_the_relabelling_and_windows_condense():
     assert norm_err(Yw.cpu().numpy(), oracle.spmm(g.row_ptr, g.col_idx, X, w)[perm.cpu().numpy()]) <= TOL_F32
     meta0.free()
     meta1.free()
+
+
+def test_clustered_build_gives_the_oracle_results_on_the_original_labelling():
+    # tcg_sgt_build_clustered = reorder + permute + translate.  Its permutation and relabelled pattern are the
+    # oracle's bit for bit; SpMM / SDDMM run on the relabelled graph and, taken back to the original labelling,
+    # equal the oracle's results on the original graph; and the windows condense (the point of the exercise).
+    c = W.make_config(5, n=64 * 150, d=64)
+    g = c["csr"]
+    X = W.round_to_bf16(c["X"])
+    rp, ci = upload_csr(g)
+    meta, perm, ep = tcg.sgt_build_clustered(rp, ci, 16, 8, seed=0, refine=2)
+    perm_ref = R.reorder_rows(g.row_ptr, g.col_idx, seed=0, refine=2)[0]
+    assert np.array_equal(perm.cpu().numpy(), perm_ref)
+    rp2_ref, ci2_ref, ep_ref = R.csr_permute(g.row_ptr, g.col_idx, perm_ref)
+    assert np.array_equal(meta.row_ptr.cpu().numpy(), rp2_ref) and np.array_equal(meta.col_idx.cpu().numpy(), ci2_ref)
+    assert np.array_equal(ep.cpu().numpy(), ep_ref)
+    check_sgt(meta, CSR(g.n_rows, g.n_cols, rp2_ref, ci2_ref), 16, 8)
+    plain = tcg.sgt_build(rp, ci, 16, 8)
+    assert meta.total_unique < 0.5 * plain.total_unique
+    assert tcg.sgt_plan_stats(meta)["n_tile_windows"] > 0.9 * meta.n_windows
+    plain.free()
+    pl = perm.long()
+    Xd = upload_x(X, "bf16")
+    Yp = tcg.spmm(meta, Xd[pl].contiguous())
+    Ep = tcg.sddmm(meta, Xd[pl].contiguous())
+    torch.cuda.synchronize()
+    Y = torch.empty_like(Yp)
+    Y[pl] = Yp
+    E = torch.empty_like(Ep)
+    E[ep.long()] = Ep
+    assert norm_err(Y.cpu().numpy(), oracle.spmm(g.row_ptr, g.col_idx, X, None)) <= TOL_MFMA
+    assert norm_err(E.cpu().numpy(), oracle.sddmm(g.row_ptr, g.col_idx, X)) <= TOL_MFMA
+    meta.free()
