@@ -159,19 +159,79 @@ __global__ __launch_bounds__(kBlock) void attn_fused_kernel(
     }
 }
 
-// Merges the per-segment (accumulator, maximum, denominator) of every split row, in segment order.
+// Merges the per-segment (accumulator, maximum, denominator) of every split row: one workgroup per row.  The
+// row's maximum and denominator come from a workgroup-wide reduction over its segments; for the accumulators a
+// thread takes four columns, so D / 4 threads cover a partial row and the 256 / (D / 4) thread groups each add
+// every such-and-such segment, their sums meeting in LDS in group order.  The order of all additions is fixed
+// by the sizes alone, so results repeat from run to run.  (One thread per column walking all segments one after
+// the other made this kernel as long as the fused kernel itself: a hub row has hundreds of segments.)
+__device__ __forceinline__ float block_reduce(float v, float *s_red, bool is_max)
+{
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
+#pragma unroll
+    for (int off = 1; off < kWave; off <<= 1) {
+        const float t = __shfl_xor(v, off, kWave);
+        v = is_max ? fmaxf(v, t) : v + t;
+    }
+    __syncthreads();                         // s_red may still be read from the previous reduction
+    if (lane == 0) s_red[wave] = v;
+    __syncthreads();
+    float r = s_red[0];
+#pragma unroll
+    for (int i = 1; i < kBlock / kWave; ++i) r = is_max ? fmaxf(r, s_red[i]) : r + s_red[i];
+    return r;
+}
+
 __global__ __launch_bounds__(kBlock) void attn_merge_long_kernel(
     const int32_t *__restrict__ long_row, const int32_t *__restrict__ long_slot_ptr, const float *__restrict__ partial,
     const float *__restrict__ partial_ml, int32_t D, void *__restrict__ Y, int y_dt, int64_t ldy)
 {
+    __shared__ float s_red[kBlock / kWave];
+    __shared__ float4 s_part[kBlock];
     const int64_t li = blockIdx.x;
     const int32_t row = long_row[li];
     const int32_t s0 = long_slot_ptr[li], s1 = long_slot_ptr[li + 1];
     float m = -INFINITY;
-    for (int32_t sgi = s0; sgi < s1; ++sgi) m = fmaxf(m, partial_ml[2 * (int64_t)sgi]);
+    for (int32_t sgi = s0 + threadIdx.x; sgi < s1; sgi += kBlock) m = fmaxf(m, partial_ml[2 * (int64_t)sgi]);
+    m = block_reduce(m, s_red, true);
     float l = 0.f;
-    for (int32_t sgi = s0; sgi < s1; ++sgi) l += partial_ml[2 * (int64_t)sgi + 1] * expf(partial_ml[2 * (int64_t)sgi] - m);
+    for (int32_t sgi = s0 + threadIdx.x; sgi < s1; sgi += kBlock)
+        l += partial_ml[2 * (int64_t)sgi + 1] * expf(partial_ml[2 * (int64_t)sgi] - m);
+    l = block_reduce(l, s_red, false);
     const float inv = l > 0.f ? 1.f / l : 0.f;
+    const int32_t c4 = D / 4;
+    if (D % 4 == 0 && c4 <= kBlock) {
+        const int32_t nsg = kBlock / c4;
+        const int32_t c = threadIdx.x % c4, sg = threadIdx.x / c4;
+        float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (sg < nsg)
+            for (int32_t sgi = s0 + sg; sgi < s1; sgi += nsg) {
+                const float w = expf(partial_ml[2 * (int64_t)sgi] - m);
+                const float4 v = *reinterpret_cast<const float4 *>(partial + (int64_t)sgi * D + 4 * c);
+                a.x = fmaf(v.x, w, a.x);
+                a.y = fmaf(v.y, w, a.y);
+                a.z = fmaf(v.z, w, a.z);
+                a.w = fmaf(v.w, w, a.w);
+            }
+        s_part[threadIdx.x] = a;
+        __syncthreads();
+        if (sg == 0) {
+            float4 t = s_part[c];
+            for (int32_t g = 1; g < nsg; ++g) {
+                const float4 v = s_part[g * c4 + c];
+                t.x += v.x;
+                t.y += v.y;
+                t.z += v.z;
+                t.w += v.w;
+            }
+            const int64_t o = (int64_t)row * ldy + 4 * c;
+            store_elem(Y, o, y_dt, t.x * inv);
+            store_elem(Y, o + 1, y_dt, t.y * inv);
+            store_elem(Y, o + 2, y_dt, t.z * inv);
+            store_elem(Y, o + 3, y_dt, t.w * inv);
+        }
+        return;
+    }
     for (int32_t d = threadIdx.x; d < D; d += kBlock) {
         float y = 0.f;
         for (int32_t sgi = s0; sgi < s1; ++sgi)
