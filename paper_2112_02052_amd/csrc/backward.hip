@@ -130,52 +130,84 @@ __device__ __forceinline__ void softmax_bwd_row_wave(int32_t b, int32_t e, const
     }
 }
 
-// One of the few longer rows by a workgroup: two passes over batches of kBwdUnroll values of each operand per
-// thread, the next batch requested before the current one is worked on.
-constexpr int kBwdUnroll = 6;
-__device__ __forceinline__ void softmax_bwd_giant_row(int32_t b, int32_t e, const float *p, const float *dp, float *dv,
-                                                      float *s_red)
+// The few longer rows: pieces of kGiantChunk entries from the plan's list, one workgroup per piece with both
+// operands of the piece in registers, in two launches -- the first leaves every piece's sum of p * dp, in the
+// second the workgroup of a piece adds the sums of its row's pieces in a fixed order and writes its results.
+constexpr int kPieceVals = kGiantChunk / kThreads;
+constexpr int kWavesPerBlock = kThreads / kWave;
+
+struct RowPiece {
+    int32_t b, e;            // the piece's entries
+    int32_t first, count;    // the pieces of its row in the list
+};
+
+__device__ __forceinline__ RowPiece giant_piece(int32_t k, const int32_t *gchunk_li, const int32_t *gchunk_c,
+                                             const int32_t *long_ebeg, const int32_t *long_len)
+{
+    const int32_t li = gchunk_li[k], c = gchunk_c[k];
+    const int32_t rb = long_ebeg[li], len = long_len[li];
+    RowPiece pc;
+    pc.b = rb + c * kGiantChunk;
+    pc.e = min(rb + len, pc.b + kGiantChunk);
+    pc.first = k - c;
+    pc.count = (len + kGiantChunk - 1) / kGiantChunk;
+    return pc;
+}
+
+// Workgroup-wide sum in a fixed order; every thread of the workgroup calls it.
+__device__ __forceinline__ float block_sum(float v, float *s_red)
 {
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
-    constexpr int32_t kStep = kBwdUnroll * kThreads;
-    auto load = [&](int32_t k0, float (&a)[kBwdUnroll], float (&c)[kBwdUnroll]) {
-#pragma unroll
-        for (int u = 0; u < kBwdUnroll; ++u) {
-            const bool ok = k0 + u * kThreads < e;
-            a[u] = ok ? p[k0 + u * kThreads] : 0.f;
-            c[u] = ok ? dp[k0 + u * kThreads] : 0.f;
-        }
-    };
-    float a[kBwdUnroll], c[kBwdUnroll], an[kBwdUnroll], cn[kBwdUnroll];
-    float dot = 0.f;
-    load(b + threadIdx.x, a, c);
-    for (int32_t k0 = b + threadIdx.x; k0 < e; k0 += kStep) {
-        load(k0 + kStep, an, cn);                  // past the end: nothing is read
-#pragma unroll
-        for (int u = 0; u < kBwdUnroll; ++u) dot = fmaf(a[u], c[u], dot);
-#pragma unroll
-        for (int u = 0; u < kBwdUnroll; ++u) {
-            a[u] = an[u];
-            c[u] = cn[u];
-        }
-    }
-    dot = wave_sum(dot);
-    if (lane == 0) s_red[wave] = dot;
+    v = wave_sum(v);
+    if (lane == 0) s_red[wave] = v;
     __syncthreads();
-    dot = 0.f;
+    float r = s_red[0];
 #pragma unroll
-    for (int i = 0; i < kThreads / kWave; ++i) dot += s_red[i];
-    load(b + threadIdx.x, a, c);
-    for (int32_t k0 = b + threadIdx.x; k0 < e; k0 += kStep) {
-        load(k0 + kStep, an, cn);                  // requested before this batch's stores
+    for (int i = 1; i < kWavesPerBlock; ++i) r += s_red[i];
+    return r;
+}
+
+__global__ __launch_bounds__(kThreads) void softmax_bwd_piece_sums_kernel(const int32_t *__restrict__ gchunk_li,
+                                                                          const int32_t *__restrict__ gchunk_c,
+                                                                          const int32_t *__restrict__ long_ebeg,
+                                                                          const int32_t *__restrict__ long_len,
+                                                                          const float *__restrict__ p,
+                                                                          const float *__restrict__ dp,
+                                                                          float *__restrict__ sums)
+{
+    __shared__ float s_red[kWavesPerBlock];
+    const RowPiece pc = giant_piece((int32_t)blockIdx.x, gchunk_li, gchunk_c, long_ebeg, long_len);
+    float a[kPieceVals], c[kPieceVals];
 #pragma unroll
-        for (int u = 0; u < kBwdUnroll; ++u)
-            if (k0 + u * kThreads < e) dv[k0 + u * kThreads] = a[u] * (c[u] - dot);
+    for (int u = 0; u < kPieceVals; ++u) {
+        const int32_t k = pc.b + threadIdx.x + u * kThreads;
+        a[u] = k < pc.e ? p[k] : 0.f;
+        c[u] = k < pc.e ? dp[k] : 0.f;
+    }
+    float dot = 0.f;
 #pragma unroll
-        for (int u = 0; u < kBwdUnroll; ++u) {
-            a[u] = an[u];
-            c[u] = cn[u];
-        }
+    for (int u = 0; u < kPieceVals; ++u) dot = fmaf(a[u], c[u], dot);
+    dot = block_sum(dot, s_red);
+    if (threadIdx.x == 0) sums[blockIdx.x] = dot;
+}
+
+__device__ __forceinline__ void softmax_bwd_piece(const RowPiece &pc, const float *sums, const float *p, const float *dp,
+                                                  float *dv, float *s_red)
+{
+    float a[kPieceVals], c[kPieceVals];
+#pragma unroll
+    for (int u = 0; u < kPieceVals; ++u) {
+        const int32_t k = pc.b + threadIdx.x + u * kThreads;
+        a[u] = k < pc.e ? p[k] : 0.f;
+        c[u] = k < pc.e ? dp[k] : 0.f;
+    }
+    float part = 0.f;
+    for (int32_t i = threadIdx.x; i < pc.count; i += kThreads) part += sums[pc.first + i];
+    const float dot = block_sum(part, s_red);
+#pragma unroll
+    for (int u = 0; u < kPieceVals; ++u) {
+        const int32_t k = pc.b + threadIdx.x + u * kThreads;
+        if (k < pc.e) dv[k] = a[u] * (c[u] - dot);
     }
 }
 
@@ -218,9 +250,9 @@ __device__ __forceinline__ void softmax_bwd_row_wave_halves(int32_t b, int32_t e
     }
 }
 
-constexpr int kWavesPerBlock = kThreads / kWave;
 __global__ __launch_bounds__(kThreads) void softmax_bwd_kernel(
-    int32_t n_giant, const int32_t *__restrict__ giant, int32_t n_long, const int32_t *__restrict__ long_ebeg,
+    int32_t n_gchunks, const int32_t *__restrict__ gchunk_li, const int32_t *__restrict__ gchunk_c,
+    const float *__restrict__ sums, int32_t n_long, const int32_t *__restrict__ long_ebeg,
     const int32_t *__restrict__ long_len, int32_t tail_start, int32_t tail_count,
     const int32_t *__restrict__ seg_ebeg, const int32_t *__restrict__ seg_dst, const float *p, const float *dp,
     float *dv)
@@ -228,13 +260,11 @@ __global__ __launch_bounds__(kThreads) void softmax_bwd_kernel(
     __shared__ float s_red[kWavesPerBlock];
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
     int32_t blk = blockIdx.x;
-    if (blk < n_giant) {
-        const int32_t li = giant[blk];
-        const int32_t b = long_ebeg[li];
-        softmax_bwd_giant_row(b, b + long_len[li], p, dp, dv, s_red);
+    if (blk < n_gchunks) {
+        softmax_bwd_piece(giant_piece(blk, gchunk_li, gchunk_c, long_ebeg, long_len), sums, p, dp, dv, s_red);
         return;
     }
-    blk -= n_giant;
+    blk -= n_gchunks;
     const int32_t n_long_blocks = (n_long + kWavesPerBlock - 1) / kWavesPerBlock;
     if (blk < n_long_blocks) {
         const int32_t li = blk * kWavesPerBlock + wave;
@@ -243,7 +273,7 @@ __global__ __launch_bounds__(kThreads) void softmax_bwd_kernel(
         if (len <= 8 * kWave) softmax_bwd_row_wave<8>(b, b + len, p, dp, dv);
         else if (len <= 16 * kWave) softmax_bwd_row_wave<16>(b, b + len, p, dp, dv);
         else if (len <= kGiantRow) softmax_bwd_row_wave_halves(b, b + len, p, dp, dv);
-        return;                                     // longer: one of the giant rows
+        return;                                     // longer: handled in pieces
     }
     blk -= n_long_blocks;
     const int64_t i = ((int64_t)blk * kWavesPerBlock + wave) * kTailRowsPerWave + lane;
@@ -269,12 +299,16 @@ int row_softmax_backward_impl(const tcg_meta *m, const float *d_p, const float *
 {
     if (m->n_rows == 0 || m->nnz == 0) return TCG_OK;
     const int32_t tail_start = m->h_lane_tab[4], tail_count = m->h_lane_tab[5];
-    const int64_t grid = m->n_giant + ceil_div(m->n_long, kWavesPerBlock) +
+    const int64_t grid = m->n_gchunks + ceil_div(m->n_long, kWavesPerBlock) +
                          ceil_div(tail_count, kWavesPerBlock * kTailRowsPerWave);
+    float *sums = m->d_partial_ml;                       // one sum per piece; pieces <= slots
+    if (m->n_gchunks > 0)
+        hipLaunchKernelGGL(softmax_bwd_piece_sums_kernel, dim3((unsigned)m->n_gchunks), dim3(kThreads), 0, s,
+                           m->d_gchunk_li, m->d_gchunk_c, m->d_long_ebeg, m->d_long_len, d_p, d_dp, sums);
     if (grid > 0) {
-        hipLaunchKernelGGL(softmax_bwd_kernel, dim3((unsigned)grid), dim3(kThreads), 0, s, (int32_t)m->n_giant, m->d_giant,
-                           (int32_t)m->n_long, m->d_long_ebeg, m->d_long_len, tail_start, tail_count, m->d_seg_ebeg,
-                           m->d_seg_dst, d_p, d_dp, d_dv);
+        hipLaunchKernelGGL(softmax_bwd_kernel, dim3((unsigned)grid), dim3(kThreads), 0, s, (int32_t)m->n_gchunks,
+                           m->d_gchunk_li, m->d_gchunk_c, sums, (int32_t)m->n_long, m->d_long_ebeg, m->d_long_len,
+                           tail_start, tail_count, m->d_seg_ebeg, m->d_seg_dst, d_p, d_dp, d_dv);
         TCG_TRY(launch_status("softmax_bwd_kernel"));
     }
     return TCG_OK;

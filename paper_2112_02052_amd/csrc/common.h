@@ -12,8 +12,9 @@ namespace tcg {
 
 constexpr int kWave = 64;            // gfx950 wavefront width
 constexpr int kSegLen = 128;         // max edges of one row segment on the gather path
-constexpr int kGiantRow = 2048;      // rows with more entries are listed apart in the plan (row-wise kernels give them a
-                                     // workgroup each; up to this length a row fits one wavefront's registers)
+constexpr int kGiantRow = 2048;      // up to this length a row fits one wavefront's registers; longer rows are listed
+constexpr int kGiantChunk = 4096;    // apart in the plan, in pieces of this many entries (one workgroup per piece in
+                                     // the row-wise kernels)
 constexpr float kDefaultMinReuse = 2.0f;
 constexpr int kXcds = 8;              // accelerator dies of an MI355X; workgroup i is dispatched to die i % 8
 constexpr int kPartialInitD = 128;   // the build reserves partial-sum scratch for feature widths up to this
@@ -231,13 +232,15 @@ struct tcg_meta {
     int32_t *d_long_slot_ptr = nullptr;   // [n_long + 1] their slot ranges
     int32_t *d_long_ebeg = nullptr;       // [n_long] their first edge
     int32_t *d_long_len = nullptr;        // [n_long] their number of entries
-    int32_t *d_giant = nullptr;           // [n_giant] positions (in the four arrays above) of the rows beyond kGiantRow
-    int64_t n_giant = 0;
+    int32_t *d_gchunk_li = nullptr;       // [n_gchunks] the kGiantChunk-entry pieces of the rows beyond kGiantRow: position
+    int32_t *d_gchunk_c = nullptr;        //             of the row in the four arrays above, and number of the piece
+    int64_t n_gchunks = 0;                //             in its row (a row's pieces are consecutive)
     int32_t *d_lane_tab = nullptr;        // [kXcds x kLaneTabStride] see plan_segment() (inside the build's result block)
     int32_t h_lane_tab[6 * 8] = {0};      // host copy (sizes the gather grids, see plan_grid())
     float *d_partial = nullptr;           // [n_slots x D] scratch; reserved for D <= kPartialInitD, regrown on demand
     int64_t partial_elems = 0;
-    float *d_partial_ml = nullptr;        // [n_slots x 2] (maximum, denominator) per split-row segment (tcg_attention)
+    float *d_partial_ml = nullptr;        // [n_slots x 2] (maximum, denominator) per split-row segment (tcg_attention);
+                                          //               per piece of a very long row in the row softmax and its gradient
     bool partial_owned = false;          // true once regrown by tcg_spmm for a wider D (separate allocation)
 
     // Device allocations owned by this object (the pointers above and below are carved from them).

@@ -188,8 +188,7 @@ __device__ __forceinline__ float wave_sum(float v)
 //       aggregation writes their zeros) and cost nothing here.
 //   split rows of up to kGiantRow entries           one wavefront each, the row in registers (8, 16 or 32
 //       values per lane), first edge and length from the plan's long-row table.
-//   the few longer rows                            one workgroup each from the plan's list of them, two passes
-//       with the next batch of values requested before the current one is worked on.
+//   the few longer rows                            in pieces of kGiantChunk entries, see softmax_piece().
 // All values a wavefront needs are requested before its first result is stored (input and output may be the
 // same array, so the compiler keeps loads behind earlier stores).
 constexpr int kTailRowsPerWave = 16;             // lanes 0 .. 15 look the rows up (more rows per wavefront cost
@@ -270,82 +269,128 @@ __device__ __forceinline__ void softmax_row_wave(int32_t b, int32_t e, const flo
     }
 }
 
-// One of the few longer rows by a workgroup: two passes (running maximum and rescaled sum of exponentials, then
-// the normalised values), each over batches of kTwoPassUnroll values per thread with the next batch requested
-// before the current one is worked on.  (Cutting these rows into chunks for several workgroups, with a second
-// launch to combine them, was measured: 62 us against 54 us on the 1M-node graph -- the extra launch costs more
-// than the hub row's tail.)
-constexpr int kTwoPassUnroll = 12;
-__device__ __forceinline__ void softmax_row_two_pass(int32_t b, int32_t e, const float *in, float *out, float *s_m,
-                                                     float *s_s)
+// The few longer rows are cut into pieces of kGiantChunk entries (the plan lists them), one workgroup per piece
+// with the piece in registers, in two launches: the first leaves the (maximum, sum of exponentials) of every piece,
+// in the second the workgroup of a piece merges the figures of its row's pieces in a fixed order and writes the
+// normalised values.  A hub row of tens of thousands of entries is then spread over the chip instead of being a
+// chain of round trips in one workgroup that outlasts the rest of the kernel (one workgroup per row, two passes:
+// 54 us on the 1M-node graph, 30 of them the longest row's; a second launch *after* the main one to combine the
+// pieces: 62 us).
+constexpr int kPieceVals = kGiantChunk / kBlock;
+constexpr int kWavesPerBlock = kBlock / kWave;
+
+struct RowPiece {
+    int32_t b, e;            // the piece's entries
+    int32_t first, count;    // the pieces of its row in the list
+};
+
+__device__ __forceinline__ RowPiece giant_piece(int32_t k, const int32_t *gchunk_li, const int32_t *gchunk_c,
+                                             const int32_t *long_ebeg, const int32_t *long_len)
+{
+    const int32_t li = gchunk_li[k], c = gchunk_c[k];
+    const int32_t rb = long_ebeg[li], len = long_len[li];
+    RowPiece p;
+    p.b = rb + c * kGiantChunk;
+    p.e = min(rb + len, p.b + kGiantChunk);
+    p.first = k - c;
+    p.count = (len + kGiantChunk - 1) / kGiantChunk;
+    return p;
+}
+
+// Workgroup-wide maximum / sum in a fixed order.  Every thread of the workgroup calls them.
+__device__ __forceinline__ float block_max(float v, float *s_red)
 {
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
-    constexpr int32_t kStep = kTwoPassUnroll * kBlock;
-    auto load = [&](int32_t k0, float (&v)[kTwoPassUnroll], float fill) {
-#pragma unroll
-        for (int u = 0; u < kTwoPassUnroll; ++u) v[u] = k0 + u * kBlock < e ? in[k0 + u * kBlock] : fill;
-    };
-    float m = -INFINITY, s = 0.f;
-    float cur[kTwoPassUnroll], nxt[kTwoPassUnroll];
-    load(b + threadIdx.x, cur, -INFINITY);
-    for (int32_t k0 = b + threadIdx.x; k0 < e; k0 += kStep) {
-        load(k0 + kStep, nxt, -INFINITY);          // past the end: nothing is read
-        float mb = cur[0];
-#pragma unroll
-        for (int u = 1; u < kTwoPassUnroll; ++u) mb = fmaxf(mb, cur[u]);
-        if (mb > m) {
-            s *= expf(m - mb);          // exp(-inf) = 0 on the first batch
-            m = mb;
-        }
-#pragma unroll
-        for (int u = 0; u < kTwoPassUnroll; ++u) s += expf(cur[u] - m);
-#pragma unroll
-        for (int u = 0; u < kTwoPassUnroll; ++u) cur[u] = nxt[u];
-    }
-    const float wm = wave_max(m);
-    const float ws = wave_sum(m > -INFINITY ? s * expf(m - wm) : 0.f);
-    if (lane == 0) {
-        s_m[wave] = wm;
-        s_s[wave] = ws;
-    }
+    v = wave_max(v);
+    __syncthreads();                                   // s_red may still be read from an earlier call
+    if (lane == 0) s_red[wave] = v;
     __syncthreads();
-    float M = -INFINITY;
+    float r = s_red[0];
 #pragma unroll
-    for (int i = 0; i < kBlock / kWave; ++i) M = fmaxf(M, s_m[i]);
-    float S = 0.f;
+    for (int i = 1; i < kWavesPerBlock; ++i) r = fmaxf(r, s_red[i]);
+    return r;
+}
+
+__device__ __forceinline__ float block_sum(float v, float *s_red)
+{
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
+    v = wave_sum(v);
+    __syncthreads();
+    if (lane == 0) s_red[wave] = v;
+    __syncthreads();
+    float r = s_red[0];
 #pragma unroll
-    for (int i = 0; i < kBlock / kWave; ++i) S += s_m[i] > -INFINITY ? s_s[i] * expf(s_m[i] - M) : 0.f;
-    const float inv = 1.f / S;
-    load(b + threadIdx.x, cur, 0.f);
-    for (int32_t k0 = b + threadIdx.x; k0 < e; k0 += kStep) {
-        load(k0 + kStep, nxt, 0.f);                // requested before this batch's stores
+    for (int i = 1; i < kWavesPerBlock; ++i) r += s_red[i];
+    return r;
+}
+
+__global__ __launch_bounds__(kBlock) void softmax_piece_stats_kernel(const int32_t *__restrict__ gchunk_li,
+                                                                     const int32_t *__restrict__ gchunk_c,
+                                                                     const int32_t *__restrict__ long_ebeg,
+                                                                     const int32_t *__restrict__ long_len,
+                                                                     const float *__restrict__ in,
+                                                                     float2 *__restrict__ stats)
+{
+    __shared__ float s_red[kWavesPerBlock];
+    const RowPiece p = giant_piece((int32_t)blockIdx.x, gchunk_li, gchunk_c, long_ebeg, long_len);
+    float v[kPieceVals];
+    float m = -INFINITY;
 #pragma unroll
-        for (int u = 0; u < kTwoPassUnroll; ++u)
-            if (k0 + u * kBlock < e) out[k0 + u * kBlock] = expf(cur[u] - M) * inv;
+    for (int u = 0; u < kPieceVals; ++u) {
+        const int32_t k = p.b + threadIdx.x + u * kBlock;
+        v[u] = k < p.e ? in[k] : -INFINITY;
+        m = fmaxf(m, v[u]);
+    }
+    const float M = block_max(m, s_red);
+    float sum = 0.f;
 #pragma unroll
-        for (int u = 0; u < kTwoPassUnroll; ++u) cur[u] = nxt[u];
+    for (int u = 0; u < kPieceVals; ++u) sum += v[u] > -INFINITY ? expf(v[u] - M) : 0.f;
+    const float S = block_sum(sum, s_red);
+    if (threadIdx.x == 0) stats[blockIdx.x] = make_float2(M, S);
+}
+
+__device__ __forceinline__ void softmax_piece(const RowPiece &p, const float2 *stats, const float *in, float *out,
+                                              float *s_red)
+{
+    float v[kPieceVals];
+#pragma unroll
+    for (int u = 0; u < kPieceVals; ++u) {
+        const int32_t k = p.b + threadIdx.x + u * kBlock;
+        v[u] = k < p.e ? in[k] : -INFINITY;
+    }
+    float m = -INFINITY;
+    for (int32_t i = threadIdx.x; i < p.count; i += kBlock) m = fmaxf(m, stats[p.first + i].x);
+    const float M = block_max(m, s_red);
+    float sum = 0.f;
+    for (int32_t i = threadIdx.x; i < p.count; i += kBlock) {
+        const float2 t = stats[p.first + i];
+        sum += t.x > -INFINITY ? t.y * expf(t.x - M) : 0.f;
+    }
+    const float inv = 1.f / block_sum(sum, s_red);
+#pragma unroll
+    for (int u = 0; u < kPieceVals; ++u) {
+        const int32_t k = p.b + threadIdx.x + u * kBlock;
+        if (k < p.e) out[k] = expf(v[u] - M) * inv;
     }
 }
 
-// One launch, three kinds of workgroups in the order in which they should start: the giant rows first (they run
-// longest), then the other split rows (four per workgroup, one per wavefront), then the single-segment rows (64
-// per workgroup, 16 per wavefront).
-constexpr int kWavesPerBlock = kBlock / kWave;
+// One launch, three kinds of workgroups in the order in which they should start: the pieces of the very long rows,
+// then the other split rows (four per workgroup, one per wavefront), then the single-segment rows (64 per
+// workgroup, 16 per wavefront).
 __global__ __launch_bounds__(kBlock) void row_softmax_kernel(
-    int32_t n_giant, const int32_t *__restrict__ giant, int32_t n_long, const int32_t *__restrict__ long_ebeg,
+    int32_t n_gchunks, const int32_t *__restrict__ gchunk_li, const int32_t *__restrict__ gchunk_c,
+    const float2 *__restrict__ stats, int32_t n_long, const int32_t *__restrict__ long_ebeg,
     const int32_t *__restrict__ long_len, int32_t tail_start, int32_t tail_count,
     const int32_t *__restrict__ seg_ebeg, const int32_t *__restrict__ seg_dst, const float *in, float *out)
 {
-    __shared__ float s_m[kWavesPerBlock], s_s[kWavesPerBlock];
+    __shared__ float s_red[kWavesPerBlock];
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
     int32_t blk = blockIdx.x;
-    if (blk < n_giant) {
-        const int32_t li = giant[blk];
-        const int32_t b = long_ebeg[li];
-        softmax_row_two_pass(b, b + long_len[li], in, out, s_m, s_s);
+    if (blk < n_gchunks) {
+        softmax_piece(giant_piece(blk, gchunk_li, gchunk_c, long_ebeg, long_len), stats, in, out, s_red);
         return;
     }
-    blk -= n_giant;
+    blk -= n_gchunks;
     const int32_t n_long_blocks = (n_long + kWavesPerBlock - 1) / kWavesPerBlock;
     if (blk < n_long_blocks) {
         const int32_t li = blk * kWavesPerBlock + wave;
@@ -354,7 +399,7 @@ __global__ __launch_bounds__(kBlock) void row_softmax_kernel(
         if (len <= 8 * kWave) softmax_row_wave<8>(b, b + len, in, out);
         else if (len <= 16 * kWave) softmax_row_wave<16>(b, b + len, in, out);
         else if (len <= kGiantRow) softmax_row_wave<kGiantRow / kWave>(b, b + len, in, out);
-        return;                                     // longer: one of the giant rows
+        return;                                     // longer: handled in pieces
     }
     blk -= n_long_blocks;
     const int64_t i = ((int64_t)blk * kWavesPerBlock + wave) * kTailRowsPerWave + lane;
@@ -475,12 +520,16 @@ int row_softmax_impl(const tcg_meta *m, const float *d_in, float *d_out, hipStre
 {
     if (m->n_rows == 0 || m->nnz == 0) return TCG_OK;
     const int32_t tail_start = m->h_lane_tab[4], tail_count = m->h_lane_tab[5];
-    const int64_t grid = m->n_giant + ceil_div(m->n_long, kWavesPerBlock) +
+    const int64_t grid = m->n_gchunks + ceil_div(m->n_long, kWavesPerBlock) +
                          ceil_div(tail_count, kWavesPerBlock * kTailRowsPerWave);
+    float2 *stats = reinterpret_cast<float2 *>(m->d_partial_ml);        // one pair per piece; pieces <= slots
+    if (m->n_gchunks > 0)
+        hipLaunchKernelGGL(softmax_piece_stats_kernel, dim3((unsigned)m->n_gchunks), dim3(kBlock), 0, s, m->d_gchunk_li,
+                           m->d_gchunk_c, m->d_long_ebeg, m->d_long_len, d_in, stats);
     if (grid > 0) {
-        hipLaunchKernelGGL(row_softmax_kernel, dim3((unsigned)grid), dim3(kBlock), 0, s, (int32_t)m->n_giant, m->d_giant,
-                           (int32_t)m->n_long, m->d_long_ebeg, m->d_long_len, tail_start, tail_count, m->d_seg_ebeg,
-                           m->d_seg_dst, d_in, d_out);
+        hipLaunchKernelGGL(row_softmax_kernel, dim3((unsigned)grid), dim3(kBlock), 0, s, (int32_t)m->n_gchunks,
+                           m->d_gchunk_li, m->d_gchunk_c, stats, (int32_t)m->n_long, m->d_long_ebeg, m->d_long_len,
+                           tail_start, tail_count, m->d_seg_ebeg, m->d_seg_dst, d_in, d_out);
         TCG_TRY(launch_status("row_softmax_kernel"));
     }
     return TCG_OK;

@@ -192,7 +192,7 @@ struct BuildInfo {
     int32_t sort_tail;                          // single-segment rows ordered by length class
     int32_t flag;                               // CSR validation
     int32_t total_unique;
-    int32_t n_giant;                            // split rows with more than kGiantRow entries
+    int32_t n_gchunks;                          // kGiantChunk-entry pieces of the rows beyond kGiantRow entries
     int32_t lane_tab[kLaneTabStride * kXcds];   // see plan_segment()
     unsigned long long counters[8];             // choose_path_kernel totals
 };
@@ -902,8 +902,8 @@ __global__ __launch_bounds__(256) void seg_fill_kernel(
     const int32_t *__restrict__ tail_off, int32_t *__restrict__ seg_row,
     int32_t *__restrict__ seg_ebeg, int32_t *__restrict__ seg_dst, int32_t *__restrict__ long_row,
     int32_t *__restrict__ long_slot_ptr, int32_t *__restrict__ long_ebeg, int32_t *__restrict__ long_len,
-    int32_t *__restrict__ giant, int32_t *__restrict__ slot_row, int32_t *__restrict__ slot_ebeg,
-    int32_t *__restrict__ slot_key)
+    int32_t *__restrict__ gchunk_li, int32_t *__restrict__ gchunk_c, int32_t *__restrict__ slot_row,
+    int32_t *__restrict__ slot_ebeg, int32_t *__restrict__ slot_key)
 {
     constexpr int RPT = kRowBlock / 256;           // rows per thread
     __shared__ int s_tmp[256 / kWave][kFillVals];
@@ -971,8 +971,16 @@ __global__ __launch_bounds__(256) void seg_fill_kernel(
             long_slot_ptr[long_base + lrank] = slot_base + srank;
             long_ebeg[long_base + lrank] = e0[k];
             long_len[long_base + lrank] = deg[k];
-            // the few very long rows are listed apart (in any order: the list only says who works on a row)
-            if (deg[k] > kGiantRow) giant[atomicAdd(&info->n_giant, 1)] = long_base + lrank;
+            // the few very long rows are listed apart, cut into pieces of kGiantChunk entries (the pieces of a row
+            // are consecutive; the rows come in any order: the list only says who works on what)
+            if (deg[k] > kGiantRow) {
+                const int32_t pieces = (deg[k] + kGiantChunk - 1) / kGiantChunk;
+                const int32_t at = atomicAdd(&info->n_gchunks, pieces);
+                for (int32_t c = 0; c < pieces; ++c) {
+                    gchunk_li[at + c] = long_base + lrank;
+                    gchunk_c[at + c] = c;
+                }
+            }
             s_lrow[lrank] = (int32_t)(r0 + k);
             s_le0[lrank] = e0[k];
             s_lslot[lrank] = srank;
@@ -1383,8 +1391,9 @@ int sgt_build_impl(tcg_meta *m, int validate, hipStream_t s)
     keep.want((long_bound + 1) * 4);
     keep.want(long_bound * 4);
     keep.want(long_bound * 4);
-    const int64_t giant_bound = nnz / (kGiantRow + 1) + 1;
-    keep.want(giant_bound * 4);
+    const int64_t gchunk_bound = nnz / kGiantChunk + nnz / (kGiantRow + 1) + 1;
+    keep.want(gchunk_bound * 4);
+    keep.want(gchunk_bound * 4);
     TCG_TRY(keep.commit());
     m->owned[m->n_owned++] = keep.base;
     m->d_win_partition = keep.take<int32_t>(n_win);
@@ -1400,7 +1409,8 @@ int sgt_build_impl(tcg_meta *m, int validate, hipStream_t s)
     m->d_long_slot_ptr = keep.take<int32_t>(long_bound + 1);
     m->d_long_ebeg = keep.take<int32_t>(long_bound);
     m->d_long_len = keep.take<int32_t>(long_bound);
-    m->d_giant = keep.take<int32_t>(giant_bound);
+    m->d_gchunk_li = keep.take<int32_t>(gchunk_bound);
+    m->d_gchunk_c = keep.take<int32_t>(gchunk_bound);
     m->d_lane_tab = info->lane_tab;
     m->d_counters = info->counters;
 
@@ -1526,7 +1536,7 @@ int sgt_build_impl(tcg_meta *m, int validate, hipStream_t s)
         if (nb_rows > 0) {
             hipLaunchKernelGGL(seg_fill_kernel, dim3((unsigned)nb_rows), dim3(256), 0, ps, 0, n, m->d_row_ptr, m->d_col_idx,
                                info, nb_rows, long_off, slot_off, tail_off, m->d_seg_row, m->d_seg_ebeg, m->d_seg_dst,
-                               m->d_long_row, m->d_long_slot_ptr, m->d_long_ebeg, m->d_long_len, m->d_giant, slot_row, slot_ebeg,
+                               m->d_long_row, m->d_long_slot_ptr, m->d_long_ebeg, m->d_long_len, m->d_gchunk_li, m->d_gchunk_c, slot_row, slot_ebeg,
                                slot_key);
             TCG_TRY(launch_status("plan kernels"));
             const bool sorted = sort_bytes > 0 && slot_bound > 1;
@@ -1572,7 +1582,7 @@ int sgt_build_impl(tcg_meta *m, int validate, hipStream_t s)
     if (nb_rows > 0)
         hipLaunchKernelGGL(seg_fill_kernel, dim3((unsigned)nb_rows), dim3(256), 0, s, 1, n, m->d_row_ptr, m->d_col_idx,
                            info, nb_rows, long_off, slot_off, tail_off, m->d_seg_row, m->d_seg_ebeg,
-                           m->d_seg_dst, m->d_long_row, m->d_long_slot_ptr, m->d_long_ebeg, m->d_long_len, m->d_giant, slot_row, slot_ebeg,
+                           m->d_seg_dst, m->d_long_row, m->d_long_slot_ptr, m->d_long_ebeg, m->d_long_len, m->d_gchunk_li, m->d_gchunk_c, slot_row, slot_ebeg,
                                slot_key);
     launch_choose_path(m, TCG_POLICY_AUTO, kDefaultMinReuse, s);
     TCG_TRY(launch_status("plan and path kernels"));
@@ -1582,7 +1592,7 @@ int sgt_build_impl(tcg_meta *m, int validate, hipStream_t s)
     TCG_HIP(hipStreamSynchronize(s));                       // the one wait of a build
     m->n_seg = h.n_seg;
     m->n_long = h.n_long;
-    m->n_giant = h.n_giant;
+    m->n_gchunks = h.n_gchunks;
     m->n_slots = h.n_slots;
     m->total_unique = h.total_unique;
     for (int i = 0; i < kLaneTabStride * kXcds; ++i) m->h_lane_tab[i] = h.lane_tab[i];

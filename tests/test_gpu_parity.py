@@ -581,11 +581,12 @@ def test_row_softmax_and_attention_chain():
 
 def test_row_softmax_and_its_gradient_at_every_row_length_class():
     # Row lengths on both sides of every switch between kernels and variants (lane groups of 4, 8 and 16 up to 128
-    # entries, one workgroup with the row in registers up to 2,048 and up to 8,192, two passes beyond), empty rows
-    # in between, scores large enough that an unshifted exp would overflow.
-    lengths = [0, 1, 2, 15, 16, 17, 31, 33, 64, 127, 128, 129, 130, 255, 256, 257, 1000, 2047, 2048, 2049, 2050,
-               4095, 4096, 4097, 8191, 8192, 8193, 9000, 0, 3, 0, 5, 7, 8, 9, 12, 24, 32, 40]
-    n_cols = 9001
+    # entries, one wavefront with the row in registers up to 512, 1,024 and 2,048, pieces of 4,096 entries spread
+    # over workgroups beyond), empty rows in between, scores large enough that an unshifted exp would overflow.
+    lengths = [0, 1, 2, 15, 16, 17, 31, 33, 64, 127, 128, 129, 130, 255, 256, 257, 511, 512, 513, 1000, 1024, 1025,
+               2047, 2048, 2049, 2050, 4095, 4096, 4097, 8191, 8192, 8193, 9000, 0, 3, 0, 5, 7, 8, 9, 12, 24, 32, 40,
+               20000]
+    n_cols = 20001
     rng = np.random.default_rng(21)
     g = csr_from_rows([np.sort(rng.choice(n_cols, size=k, replace=False)) for k in lengths], n_cols)
     v = (rng.standard_normal(g.nnz) * 30.0 + 80.0).astype(np.float32)
@@ -602,6 +603,20 @@ def test_row_softmax_and_its_gradient_at_every_row_length_class():
     np.testing.assert_allclose(sums, 1.0, atol=1e-5)
     dv_ref = oracle.row_softmax_backward(g.row_ptr, p.cpu().numpy().astype(np.float64), dp.astype(np.float64))
     assert norm_err(dv.cpu().numpy(), dv_ref) <= TOL_F32
+    # in place, and a very long row one of whose pieces holds nothing but -inf (masked scores): zeros there
+    v2 = v.copy()
+    b = int(g.row_ptr[len(lengths) - 1])
+    v2[b + 4096:b + 8192] = -np.inf
+    q = torch.from_numpy(v2).to(dev())
+    q2 = tcg.row_softmax(meta, q, out=q)
+    torch.cuda.synchronize()
+    q_ref = oracle.row_softmax(g.row_ptr, v2.astype(np.float64))
+    assert np.isfinite(q2.cpu().numpy()).all() and (q2.cpu().numpy()[b + 4096:b + 8192] == 0).all()
+    assert norm_err(q2.cpu().numpy(), q_ref) <= TOL_F32
+    d2 = torch.from_numpy(dp).to(dev())
+    d2 = tcg.row_softmax_backward(meta, p, d2, out=d2)
+    torch.cuda.synchronize()
+    assert torch.equal(d2, dv)
     meta.free()
     # graphs whose rows all stay below 8, 16 and 32 entries: the variants with 4, 8 and 16 lanes per row
     for cap in (8, 16, 32):
