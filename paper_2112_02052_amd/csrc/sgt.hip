@@ -11,7 +11,8 @@
 //                        columns), else in device scratch (then a class of up to 4096 entries is still
 //                        sorted): set a bit per edge, prefix-popcount the words, rank = prefix + popcount
 //                        below.  Hub windows of power-law graphs land here; the cost is
-//                        O(n_cols / 32 + nnz_w) per window.
+//                        O(n_cols / 32 + nnz_w) per window, and in LDS a window of more than kHubEntries
+//                        entries is shared by up to kHubMaxParts workgroups.
 // Every window writes its unique list at its own edge offset of col_to_row (the list is never longer than
 // the window's edge range) and it stays there: the kernels that use it find it through row_ptr, and only
 // the export packs the lists back to back.
@@ -171,6 +172,8 @@ __device__ __forceinline__ void window_edge_range(const int32_t *rp, int32_t n_r
 constexpr int kClsLarge = 7, kClasses = 8;
 constexpr int kSortCap = 4096;            // largest window that is sorted
 constexpr int kLdsBitmapFrom = 1024;      // ... when the bitmap class works in LDS
+constexpr int kHubEntries = 16384;        // LDS bitmap class: a window with more entries is listed in several parts,
+constexpr int kHubMaxParts = 8;           // one per kHubEntries entries up to this many (see the kernel)
 
 __device__ __forceinline__ int window_class(int32_t cnt, int32_t sort_cap)
 {
@@ -217,7 +220,8 @@ __device__ __forceinline__ int length_class(int32_t deg)
 __global__ __launch_bounds__(256) void prep_kernel(int32_t n_rows, int32_t win_h, int64_t n_win,
                                                    const int32_t *__restrict__ rp, int64_t nb_rows,
                                                    int32_t *__restrict__ block_sums, int32_t *__restrict__ lists,
-                                                   int32_t *cls_count, int32_t *__restrict__ win_unique, int32_t sort_cap)
+                                                   int32_t *cls_count, int32_t *__restrict__ win_unique, int32_t sort_cap,
+                                                   int32_t *__restrict__ large_part, int32_t hub_entries)
 {
     const int lane = threadIdx.x & (kWave - 1);
     if ((int64_t)blockIdx.x < nb_rows) {
@@ -259,12 +263,24 @@ __global__ __launch_bounds__(256) void prep_kernel(int32_t n_rows, int32_t win_h
     }
     const int64_t w = ((int64_t)blockIdx.x - nb_rows) * 256 + threadIdx.x;
     int cls = -1;
+    int32_t cnt = 0;
     if (w < n_win) {
         int32_t lo, hi;
         window_edge_range(rp, n_rows, win_h, w, &lo, &hi);
-        const int32_t cnt = hi - lo;
+        cnt = hi - lo;
         if (cnt == 0) win_unique[w] = 0;
         else cls = window_class(cnt, sort_cap);
+    }
+    // The bitmap class is small and its list has one item per part of a window (large_part: part number, and the
+    // number of parts from bit 8 up): its windows draw their places themselves.
+    if (cls == kClsLarge) {
+        const int parts = cnt > hub_entries ? min(kHubMaxParts, (cnt + hub_entries - 1) / hub_entries) : 1;
+        const int at = atomicAdd(&cls_count[kClsLarge], parts);
+        for (int j = 0; j < parts; ++j) {
+            lists[(int64_t)kClsLarge * n_win + at + j] = (int32_t)w;
+            large_part[at + j] = j | (parts << 8);
+        }
+        cls = -1;
     }
     // One atomic per workgroup and class instead of one per window: the wavefronts count their windows of
     // every class with ballots, one thread per class draws the workgroup's range of the list (all classes in
@@ -274,13 +290,13 @@ __global__ __launch_bounds__(256) void prep_kernel(int32_t n_rows, int32_t win_h
     const int wave = threadIdx.x >> 6;
     int rank_in_wave = 0;
 #pragma unroll
-    for (int c = 0; c < kClasses; ++c) {
+    for (int c = 0; c < kClsLarge; ++c) {
         const unsigned long long mask = __ballot(cls == c);
         if (lane == 0) s_wave_cnt[wave][c] = __popcll(mask);
         if (cls == c) rank_in_wave = __popcll(mask & ((1ull << lane) - 1ull));
     }
     __syncthreads();
-    if (threadIdx.x < kClasses) {
+    if (threadIdx.x < kClsLarge) {
         int t = 0;
 #pragma unroll
         for (int w2 = 0; w2 < 256 / kWave; ++w2) t += s_wave_cnt[w2][threadIdx.x];
@@ -591,13 +607,14 @@ inline size_t lds_bitmap_bytes(int64_t n_words)
 
 __global__ __launch_bounds__(kBitmapThreads) void sgt_window_lds_bitmap_kernel(
     int32_t n_rows, int32_t win_h, int32_t n_words, const int32_t *__restrict__ large_list,
-    const int32_t *__restrict__ list_len, int32_t *ticket, const int32_t *__restrict__ rp,
+    const int32_t *__restrict__ large_part, const int32_t *__restrict__ list_len, int32_t *ticket,
+    const int32_t *__restrict__ rp,
     const int32_t *__restrict__ ci, int32_t *__restrict__ edge_to_col, int32_t *__restrict__ col_to_row,
     int32_t *__restrict__ win_unique)
 {
     extern __shared__ uint32_t s_words[];          // bitmap, then the group prefixes
     __shared__ int s_tmp[kBitmapWaves + 1];
-    __shared__ int32_t s_next[4];                  // next window: list position, window id, edge range
+    __shared__ int32_t s_next[5];                  // next item: list position, window id, edge range, part
     uint32_t *bm = s_words;
     int32_t *gpf = reinterpret_cast<int32_t *>(s_words + n_words);
     const int32_t n_items = *list_len;
@@ -609,18 +626,20 @@ __global__ __launch_bounds__(kBitmapThreads) void sgt_window_lds_bitmap_kernel(
 
     if (threadIdx.x == 0) {
         const int32_t it = atomicAdd(ticket, 1);
-        int32_t w = 0, lo = 0, hi = 0;
+        int32_t w = 0, lo = 0, hi = 0, pp = 1 << 8;
         if (it < n_items) {
             w = large_list[it];
+            pp = large_part[it];
             window_edge_range(rp, n_rows, win_h, w, &lo, &hi);
         }
         s_next[0] = it;
         s_next[1] = w;
         s_next[2] = lo;
         s_next[3] = hi;
+        s_next[4] = pp;
     }
     __syncthreads();
-    int32_t item = s_next[0], w = s_next[1], lo = s_next[2], hi = s_next[3];
+    int32_t item = s_next[0], w = s_next[1], lo = s_next[2], hi = s_next[3], pp = s_next[4];
     uint32_t c_first[kLdsEdgeUnroll];
 #pragma unroll
     for (int u = 0; u < kLdsEdgeUnroll; ++u) {
@@ -629,7 +648,7 @@ __global__ __launch_bounds__(kBitmapThreads) void sgt_window_lds_bitmap_kernel(
     }
 
     while (item < n_items) {                       // the same value in every thread: all leave together
-        int32_t next_item = 0, next_w = 0;
+        int32_t next_item = 0, next_w = 0, next_pp = 1 << 8;
         if (threadIdx.x == 0) next_item = atomicAdd(ticket, 1);
         for (int32_t k = threadIdx.x; k < n_words; k += kBitmapThreads) bm[k] = 0u;
         __syncthreads();                           // also: everybody has read s_next
@@ -649,7 +668,10 @@ __global__ __launch_bounds__(kBitmapThreads) void sgt_window_lds_bitmap_kernel(
             for (int u = 0; u < kLdsEdgeUnroll; ++u)
                 if (c[u] != 0xFFFFFFFFu) atomicOr(&bm[c[u] >> 5], 1u << (c[u] & 31));
         }
-        if (threadIdx.x == 0 && next_item < n_items) next_w = large_list[next_item];   // used two phases on
+        if (threadIdx.x == 0 && next_item < n_items) {                                 // used two phases on
+            next_w = large_list[next_item];
+            next_pp = large_part[next_item];
+        }
         __syncthreads();
 
         // 2. bits in the words this thread owns; one workgroup-wide scan gives the count in front of them.
@@ -672,11 +694,12 @@ __global__ __launch_bounds__(kBitmapThreads) void sgt_window_lds_bitmap_kernel(
             s_next[1] = next_w;
             s_next[2] = next_lo;
             s_next[3] = next_hi;
+            s_next[4] = next_pp;
         }
         __syncthreads();
 
         // The next window's first batch of columns is requested now; it arrives while the ranks are written.
-        const int32_t n_item = s_next[0], n_w = s_next[1], n_lo = s_next[2], n_hi = s_next[3];
+        const int32_t n_item = s_next[0], n_w = s_next[1], n_lo = s_next[2], n_hi = s_next[3], n_pp = s_next[4];
         uint32_t c_next[kLdsEdgeUnroll];
 #pragma unroll
         for (int u = 0; u < kLdsEdgeUnroll; ++u) {
@@ -699,19 +722,31 @@ __global__ __launch_bounds__(kBitmapThreads) void sgt_window_lds_bitmap_kernel(
         // of a sorted row have rising, mostly neighbouring ranks, so these stores coalesce.  (Walking the
         // bitmap and writing each word's columns from the thread that owns the word serialises a hub window's
         // 10^5 stores in a few wavefronts.)
+        // A window listed in several parts: every part has built the whole bitmap (the bits are the cheaper
+        // half, and every part needs all of them) and ranks its share of the entries; every column occurs in
+        // some entry, so the parts together write the whole unique list.
+        const int32_t part = pp & 255, n_parts = pp >> 8;
+        int64_t r_lo = lo, r_hi = hi;
+        if (n_parts == 1) {
 #pragma unroll
-        for (int u = 0; u < kLdsEdgeUnroll; ++u)
-            if (c_first[u] != 0xFFFFFFFFu) {
-                const int r = rank_of(c_first[u]);
-                edge_to_col[(int64_t)lo + threadIdx.x + (int64_t)u * kBitmapThreads] = r;
-                col_to_row[lo + r] = (int32_t)c_first[u];
-            }
-        for (int64_t e0 = (int64_t)lo + kStep + threadIdx.x; e0 < hi; e0 += kStep) {
+            for (int u = 0; u < kLdsEdgeUnroll; ++u)
+                if (c_first[u] != 0xFFFFFFFFu) {
+                    const int r = rank_of(c_first[u]);
+                    edge_to_col[(int64_t)lo + threadIdx.x + (int64_t)u * kBitmapThreads] = r;
+                    col_to_row[lo + r] = (int32_t)c_first[u];
+                }
+            r_lo = (int64_t)lo + kStep;
+        } else {
+            const int64_t len = (int64_t)hi - lo;
+            r_lo = lo + len * part / n_parts;
+            r_hi = lo + len * (part + 1) / n_parts;
+        }
+        for (int64_t e0 = r_lo + threadIdx.x; e0 < r_hi; e0 += kStep) {
             uint32_t c[kLdsEdgeUnroll];
 #pragma unroll
             for (int u = 0; u < kLdsEdgeUnroll; ++u) {
                 const int64_t e = e0 + (int64_t)u * kBitmapThreads;
-                c[u] = e < hi ? (uint32_t)ci[e] : 0xFFFFFFFFu;
+                c[u] = e < r_hi ? (uint32_t)ci[e] : 0xFFFFFFFFu;
             }
 #pragma unroll
             for (int u = 0; u < kLdsEdgeUnroll; ++u) {
@@ -727,10 +762,111 @@ __global__ __launch_bounds__(kBitmapThreads) void sgt_window_lds_bitmap_kernel(
         w = n_w;
         lo = n_lo;
         hi = n_hi;
+        pp = n_pp;
 #pragma unroll
         for (int u = 0; u < kLdsEdgeUnroll; ++u) c_first[u] = c_next[u];
         __syncthreads();                           // ranks are read before the bitmap is cleared again
     }
+}
+
+// ---- per-window path choice ------------------------------------------------------------------------
+__device__ __forceinline__ unsigned long long wave_sum_u64(unsigned long long v)
+{
+#pragma unroll
+    for (int off = 1; off < kWave; off <<= 1) v += __shfl_xor(v, off, kWave);
+    return v;
+}
+
+// Per window: win_partition = ceil(U_w / tile_w) (Algorithm 1), the path flag under the given policy,
+// and the totals (tiles, tile-path windows, their edges) with one atomic per wavefront.
+struct PathArgs {
+    int32_t n_rows, win_h, tile_w;
+    int policy;
+    float min_reuse;
+    const int32_t *rp;
+    int32_t *win_partition;
+    uint8_t *win_path;
+    unsigned long long *counts;
+};
+
+struct PathTotals {
+    unsigned long long tiles = 0, tile_win = 0, tile_nnz = 0, tile_many = 0, tile_unique = 0;
+};
+
+__device__ __forceinline__ void choose_window(const PathArgs &a, int64_t w, int32_t uw, PathTotals &t)
+{
+    int32_t lo, hi;
+    window_edge_range(a.rp, a.n_rows, a.win_h, w, &lo, &hi);
+    const int32_t nnz_w = hi - lo;
+    const unsigned long long tiles = (unsigned long long)(((int64_t)uw + a.tile_w - 1) / a.tile_w);
+    a.win_partition[w] = (int32_t)tiles;
+    bool tile = false;
+    if (a.policy == TCG_POLICY_TILE) tile = uw > 0;
+    else if (a.policy == TCG_POLICY_AUTO)
+        // Windows with shared neighbours, but not hub windows: the tile kernels keep a window's
+        // condensed columns (or its whole condensed adjacency) in LDS, which needs compact windows.
+        tile = (a.win_h == 16 || a.win_h == 32) && uw > 0 && uw <= kTileMaxUnique &&
+               (float)nnz_w >= a.min_reuse * (float)uw;
+    // windows of 32 rows: class kTileFew only (twice the edges of a 16-row window fit in registers)
+    if (a.win_h == 32 && a.policy == TCG_POLICY_AUTO && nnz_w > 2 * kTileFewEdges) tile = false;
+    const bool many = tile && a.win_h == 16 && nnz_w > kTileFewEdges && uw <= kTileMaxUnique;
+    a.win_path[w] = tile ? (many ? kTileMany : kTileFew) : 0;
+    t.tiles += tiles;
+    if (tile) {
+        t.tile_win += 1;
+        t.tile_nnz += (unsigned long long)nnz_w;
+        t.tile_unique += (unsigned long long)uw;
+    }
+    if (many) {
+        t.tile_many += 1;
+        atomicMax(&a.counts[4], (unsigned long long)uw);
+    }
+}
+
+// Every lane of the wavefront calls it.
+__device__ __forceinline__ void flush_path_totals(const PathArgs &a, const PathTotals &t)
+{
+    const unsigned long long tiles = wave_sum_u64(t.tiles), tile_win = wave_sum_u64(t.tile_win),
+                             tile_nnz = wave_sum_u64(t.tile_nnz), tile_many = wave_sum_u64(t.tile_many),
+                             tile_unique = wave_sum_u64(t.tile_unique);
+    if ((threadIdx.x & (kWave - 1)) == 0) {
+        if (tiles) atomicAdd(&a.counts[0], tiles);
+        if (tile_win) atomicAdd(&a.counts[1], tile_win);
+        if (tile_nnz) atomicAdd(&a.counts[2], tile_nnz);
+        if (tile_many) atomicAdd(&a.counts[3], tile_many);
+        if (tile_unique) atomicAdd(&a.counts[5], tile_unique);
+    }
+}
+
+__global__ __launch_bounds__(256) void choose_path_kernel(PathArgs a, int64_t n_win, const int32_t *win_unique_ptr)
+{
+    const int64_t w = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    PathTotals t;
+    if (w < n_win) choose_window(a, w, win_unique_ptr[w + 1] - win_unique_ptr[w], t);
+    flush_path_totals(a, t);
+}
+
+// First step of the scan of the windows' unique counts (sums of blocks of kScanBlock windows) and, in the same
+// pass over the counts, the path choice of every window.
+__global__ __launch_bounds__(kScanThreads) void unique_sums_choose_kernel(const int32_t *__restrict__ win_unique,
+                                                                          int64_t n_win, int32_t *__restrict__ block_sums,
+                                                                          PathArgs a)
+{
+    __shared__ int tmp[kScanThreads / kWave + 1];
+    const int64_t i0 = (int64_t)blockIdx.x * kScanBlock + (int64_t)threadIdx.x * kScanItems;
+    int sum = 0;
+    PathTotals t;
+#pragma unroll 4
+    for (int k = 0; k < kScanItems; ++k)
+        if (i0 + k < n_win) {
+            const int32_t uw = win_unique[i0 + k];
+            sum += uw;
+            choose_window(a, i0 + k, uw, t);
+        }
+    flush_path_totals(a, t);
+    int total;
+    (void)block_exclusive_scan(sum, tmp, &total);
+    if (threadIdx.x == 0) block_sums[blockIdx.x] = total;
 }
 
 // ---- gather plan, step 2: offsets -----------------------------------------------------------------
@@ -776,7 +912,9 @@ __global__ __launch_bounds__(1024) void plan_scan_kernel(int phase, int64_t nb, 
                                                          int32_t *__restrict__ tail_off, BuildInfo *info,
                                                          int32_t *__restrict__ long_slot_ptr,
                                                          const int32_t *__restrict__ win_unique,
-                                                         int32_t *__restrict__ win_unique_ptr_out)
+                                                         int32_t *__restrict__ win_unique_ptr_out,
+                                                         int32_t *__restrict__ unique_block_sums, int64_t n_unique_blocks,
+                                                         PathArgs pa)
 {
     __shared__ int tmp[1024 / kWave + 1];
     if (phase == 0) {
@@ -803,15 +941,22 @@ __global__ __launch_bounds__(1024) void plan_scan_kernel(int phase, int64_t nb, 
         }
         return;
     }
-    // U: the exclusive scan of the windows' unique counts happens here unless it was done beforehand
-    // (win_unique == nullptr; graphs with so many windows that one workgroup would be slow).
+    // U: with few windows the exclusive scan of their unique counts and their path choice happen here; with
+    // many (one workgroup would be slow) unique_sums_choose_kernel has been over the counts, this kernel scans
+    // its block sums in place, and scan_apply_kernel finishes.
     int64_t U;
     if (win_unique) {
         U = block_scan_sequence(n_win, [&](int64_t i) { return win_unique[i]; },
                                 [&](int64_t i, int v) { win_unique_ptr_out[i] = v; }, tmp);
         if (threadIdx.x == 0) win_unique_ptr_out[n_win] = (int32_t)U;
+        PathTotals t;
+        for (int64_t w0 = 0; w0 < n_win; w0 += 1024)
+            if (w0 + threadIdx.x < n_win) choose_window(pa, w0 + threadIdx.x, win_unique[w0 + threadIdx.x], t);
+        flush_path_totals(pa, t);
     } else {
-        U = win_unique_ptr[n_win];
+        U = block_scan_sequence(n_unique_blocks, [&](int64_t i) { return unique_block_sums[i]; },
+                                [&](int64_t i, int v) { unique_block_sums[i] = v; }, tmp);
+        if (threadIdx.x == 0) unique_block_sums[n_unique_blocks] = (int32_t)U;
     }
     const int sort_tail = 4 * U > 3 * (nnz > 0 ? nnz : 1) ? 1 : 0;
     int n_single;
@@ -1073,64 +1218,6 @@ __global__ __launch_bounds__(256) void pack_unique_kernel(int32_t n_rows, int32_
     for (int32_t k = threadIdx.x; k < uw; k += 256) packed[u0 + k] = loose[lo + k];
 }
 
-__device__ __forceinline__ unsigned long long wave_sum_u64(unsigned long long v)
-{
-#pragma unroll
-    for (int off = 1; off < kWave; off <<= 1) v += __shfl_xor(v, off, kWave);
-    return v;
-}
-
-// Per window: win_partition = ceil(U_w / tile_w) (Algorithm 1), the path flag under the given policy,
-// and the totals (tiles, tile-path windows, their edges) with one atomic per wavefront.
-__global__ __launch_bounds__(256) void choose_path_kernel(int32_t n_rows, int32_t win_h, int32_t tile_w,
-                                                          int64_t n_win, const int32_t *rp,
-                                                          const int32_t *win_unique_ptr, int policy,
-                                                          float min_reuse, int32_t *win_partition,
-                                                          uint8_t *win_path, unsigned long long *counts)
-{
-    const int64_t w = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    unsigned long long tiles = 0, tile_win = 0, tile_nnz = 0, tile_many = 0, tile_unique = 0;
-    if (w < n_win) {
-        int32_t lo, hi;
-        window_edge_range(rp, n_rows, win_h, w, &lo, &hi);
-        const int32_t uw = win_unique_ptr[w + 1] - win_unique_ptr[w];
-        const int32_t nnz_w = hi - lo;
-        tiles = (unsigned long long)(((int64_t)uw + tile_w - 1) / tile_w);
-        win_partition[w] = (int32_t)tiles;
-        bool tile = false;
-        if (policy == TCG_POLICY_TILE) tile = uw > 0;
-        else if (policy == TCG_POLICY_AUTO)
-            // Windows with shared neighbours, but not hub windows: the tile kernels keep a window's
-            // condensed columns (or its whole condensed adjacency) in LDS, which needs compact windows.
-            tile = (win_h == 16 || win_h == 32) && uw > 0 && uw <= kTileMaxUnique && (float)nnz_w >= min_reuse * (float)uw;
-        // windows of 32 rows: class kTileFew only (twice the edges of a 16-row window fit in registers)
-        if (win_h == 32 && policy == TCG_POLICY_AUTO && nnz_w > 2 * kTileFewEdges) tile = false;
-        const bool many = tile && win_h == 16 && nnz_w > kTileFewEdges && uw <= kTileMaxUnique;
-        win_path[w] = tile ? (many ? kTileMany : kTileFew) : 0;
-        if (tile) {
-            tile_win = 1;
-            tile_nnz = (unsigned long long)nnz_w;
-            tile_unique = (unsigned long long)uw;
-        }
-        if (many) {
-            tile_many = 1;
-            atomicMax(&counts[4], (unsigned long long)uw);
-        }
-    }
-    tiles = wave_sum_u64(tiles);
-    tile_win = wave_sum_u64(tile_win);
-    tile_nnz = wave_sum_u64(tile_nnz);
-    tile_many = wave_sum_u64(tile_many);
-    tile_unique = wave_sum_u64(tile_unique);
-    if ((threadIdx.x & (kWave - 1)) == 0) {
-        if (tiles) atomicAdd(&counts[0], tiles);
-        if (tile_win) atomicAdd(&counts[1], tile_win);
-        if (tile_nnz) atomicAdd(&counts[2], tile_nnz);
-        if (tile_many) atomicAdd(&counts[3], tile_many);
-        if (tile_unique) atomicAdd(&counts[5], tile_unique);
-    }
-}
-
 // One device allocation carved into 256-byte aligned pieces.
 struct Arena {
     char *base = nullptr;
@@ -1183,12 +1270,17 @@ int exclusive_scan_i32(const int32_t *d_in, int32_t *d_out, int64_t n, int32_t *
     return launch_status("scan kernels");
 }
 
+static PathArgs path_args(const tcg_meta *m, tcg_policy policy, float min_reuse)
+{
+    return PathArgs{m->n_rows,     m->win_h,          m->tile_w,     (int)policy, min_reuse,
+                    m->d_row_ptr,  m->d_win_partition, m->d_win_path, m->d_counters};
+}
+
 static void launch_choose_path(tcg_meta *m, tcg_policy policy, float min_reuse, hipStream_t s)
 {
     if (m->n_win > 0)
-        hipLaunchKernelGGL(choose_path_kernel, dim3((unsigned)ceil_div(m->n_win, 256)), dim3(256), 0, s, m->n_rows,
-                           m->win_h, m->tile_w, m->n_win, m->d_row_ptr, m->d_win_unique_ptr, (int)policy, min_reuse,
-                           m->d_win_partition, m->d_win_path, m->d_counters);
+        hipLaunchKernelGGL(choose_path_kernel, dim3((unsigned)ceil_div(m->n_win, 256)), dim3(256), 0, s,
+                           path_args(m, policy, min_reuse), m->n_win, m->d_win_unique_ptr);
 }
 
 // counts: [0] tiles, [1] tile-path windows, [2] their edges, [3] windows of class kTileMany, [4] their widest,
@@ -1419,7 +1511,9 @@ int sgt_build_impl(tcg_meta *m, int validate, hipStream_t s)
     const int64_t scan_elems = scan_workspace_elems(n_win);
     Arena tmp;
     tmp.want((n_win + 1) * 4);                      // win_unique
-    tmp.want((int64_t)kClasses * n_win * 4);        // class lists
+    const int64_t hub_extra = (int64_t)(kHubMaxParts - 1) * (nnz / kHubEntries + 1);   // items beyond one per window
+    tmp.want(((int64_t)kClasses * n_win + hub_extra) * 4);        // class lists (the bitmap class last)
+    tmp.want((n_win + hub_extra) * 4);                            // parts of the bitmap class's items
     tmp.want((int64_t)kPlanSums * nb_rows * 4);     // per-row-block counts
     tmp.want((nb_rows + 1) * 4);                    // long_off
     tmp.want((nb_rows + 1) * 4);                    // slot_off
@@ -1430,7 +1524,8 @@ int sgt_build_impl(tcg_meta *m, int validate, hipStream_t s)
     TCG_TRY(tmp.commit());
     ScopedFree tmp_guard{tmp.base, s};
     int32_t *win_unique = tmp.take<int32_t>(n_win + 1);
-    int32_t *lists = tmp.take<int32_t>((int64_t)kClasses * n_win);
+    int32_t *lists = tmp.take<int32_t>((int64_t)kClasses * n_win + hub_extra);
+    int32_t *large_part = tmp.take<int32_t>(n_win + hub_extra);
     int32_t *block_sums = tmp.take<int32_t>((int64_t)kPlanSums * nb_rows);
     int32_t *long_off = tmp.take<int32_t>(nb_rows + 1);
     int32_t *slot_off = tmp.take<int32_t>(nb_rows + 1);
@@ -1462,7 +1557,8 @@ int sgt_build_impl(tcg_meta *m, int validate, hipStream_t s)
     // Per-row-block counts of the gather plan and the window classes (both depend on row_ptr only).
     if (nb_rows + ceil_div(n_win, 256) > 0) {
         hipLaunchKernelGGL(prep_kernel, dim3((unsigned)(nb_rows + ceil_div(n_win, 256))), dim3(256), 0, s, n, m->win_h,
-                           n_win, m->d_row_ptr, nb_rows, block_sums, lists, info->cls_count, win_unique, sort_cap);
+                           n_win, m->d_row_ptr, nb_rows, block_sums, lists, info->cls_count, win_unique, sort_cap, large_part,
+                           lds_bitmap ? kHubEntries : INT_MAX);
         TCG_TRY(launch_status("prep_kernel"));
     }
 
@@ -1495,9 +1591,10 @@ int sgt_build_impl(tcg_meta *m, int validate, hipStream_t s)
         if (n_cu <= 0 && (hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, m->device) != hipSuccess ||
                           n_cu <= 0))
             n_cu = 256;
-        const unsigned grid = (unsigned)std::min<int64_t>(large_most, n_cu);
+        const unsigned grid = (unsigned)std::min<int64_t>(large_most + hub_extra, n_cu);
         hipLaunchKernelGGL(sgt_window_lds_bitmap_kernel, dim3(grid), dim3(kBitmapThreads), lds, side->stream, n, m->win_h,
-                           (int32_t)n_words, lists + (int64_t)kClsLarge * n_win, info->cls_count + kClsLarge, &info->ticket,
+                           (int32_t)n_words, lists + (int64_t)kClsLarge * n_win, large_part, info->cls_count + kClsLarge,
+                           &info->ticket,
                            m->d_row_ptr, m->d_col_idx, m->d_edge_to_col, m->d_col_to_row, win_unique);
         TCG_TRY(launch_status("sgt_window_lds_bitmap_kernel"));
     } else if (large_most > 0) {
@@ -1525,14 +1622,29 @@ int sgt_build_impl(tcg_meta *m, int validate, hipStream_t s)
         }
     }
 
-    // Branch 2: the gather plan as far as it needs row_ptr only -- split rows, their segments sorted by start
+    // Branch 2 (enqueued before the third, whose kernels are short: the host takes a few microseconds per launch,
+    // and these kernels are on the critical path): the sorted classes, one launch each beyond the three smallest (a column and a position inside
+    // the window must fit 32 bits for 32-bit sort keys, else 64-bit ones).  A class with at least `lo` entries
+    // per window has at most nnz / lo windows; the kernels read the real count on the device.
+    {
+        auto most = [&](int64_t least_entries) { return std::min<int64_t>(n_win, nnz / least_entries); };
+        launch_sort_small(m, most(1), most(65), most(129), col_bits + 8 > 32, lists, info, win_unique, s);
+        launch_sort_class<128, 4>(m, 3, most(257), 4096, col_bits + 9 > 32, lists, info, win_unique, s);
+        launch_sort_class<256, 4>(m, 4, most(513), 2048, col_bits + 10 > 32, lists, info, win_unique, s);
+        if (sort_cap > 1024) launch_sort_class<512, 4>(m, 5, most(1025), 1024, col_bits + 11 > 32, lists, info, win_unique, s);
+        if (sort_cap > 2048) launch_sort_class<1024, 4>(m, 6, most(2049), 512, col_bits + 12 > 32, lists, info, win_unique, s);
+        TCG_TRY(launch_status("sgt_window_sort_kernel"));
+    }
+
+    // Branch 3: the gather plan as far as it needs row_ptr only -- split rows, their segments sorted by start
     // column (segments that run one after the other on a die then read neighbouring -- on skewed graphs largely
     // the same -- X rows).
     {
         hipStream_t ps = side->plan_stream;
         hipLaunchKernelGGL(plan_scan_kernel, dim3(1), dim3(1024), 0, ps, 0, nb_rows, block_sums, nnz, n_win,
                            m->d_win_unique_ptr, long_off, slot_off, tail_off, info, m->d_long_slot_ptr,
-                           (const int32_t *)nullptr, (int32_t *)nullptr);
+                           (const int32_t *)nullptr, (int32_t *)nullptr, (int32_t *)nullptr, (int64_t)0,
+                           path_args(m, TCG_POLICY_AUTO, kDefaultMinReuse));
         if (nb_rows > 0) {
             hipLaunchKernelGGL(seg_fill_kernel, dim3((unsigned)nb_rows), dim3(256), 0, ps, 0, n, m->d_row_ptr, m->d_col_idx,
                                info, nb_rows, long_off, slot_off, tail_off, m->d_seg_row, m->d_seg_ebeg, m->d_seg_dst,
@@ -1550,19 +1662,6 @@ int sgt_build_impl(tcg_meta *m, int validate, hipStream_t s)
         TCG_TRY(launch_status("plan kernels"));
     }
 
-    // Branch 3: the sorted classes, one launch each beyond the three smallest (a column and a position inside
-    // the window must fit 32 bits for 32-bit sort keys, else 64-bit ones).  A class with at least `lo` entries
-    // per window has at most nnz / lo windows; the kernels read the real count on the device.
-    {
-        auto most = [&](int64_t least_entries) { return std::min<int64_t>(n_win, nnz / least_entries); };
-        launch_sort_small(m, most(1), most(65), most(129), col_bits + 8 > 32, lists, info, win_unique, s);
-        launch_sort_class<128, 4>(m, 3, most(257), 4096, col_bits + 9 > 32, lists, info, win_unique, s);
-        launch_sort_class<256, 4>(m, 4, most(513), 2048, col_bits + 10 > 32, lists, info, win_unique, s);
-        if (sort_cap > 1024) launch_sort_class<512, 4>(m, 5, most(1025), 1024, col_bits + 11 > 32, lists, info, win_unique, s);
-        if (sort_cap > 2048) launch_sort_class<1024, 4>(m, 6, most(2049), 512, col_bits + 12 > 32, lists, info, win_unique, s);
-        TCG_TRY(launch_status("sgt_window_sort_kernel"));
-    }
-
     // Join.
     {
         std::lock_guard<std::mutex> lock(g_side_mu);
@@ -1575,16 +1674,23 @@ int sgt_build_impl(tcg_meta *m, int validate, hipStream_t s)
     // With every window translated: U, and the part of the plan that depends on it (the order of the
     // single-segment rows).
     const bool scan_inside = n_win <= (1 << 14);        // one workgroup scans this many counts in a few microseconds
-    if (!scan_inside) TCG_TRY(exclusive_scan_i32(win_unique, m->d_win_unique_ptr, n_win, scan_work, s));
+    const int64_t n_ublocks = ceil_div(n_win, kScanBlock);
+    const PathArgs pa = path_args(m, TCG_POLICY_AUTO, kDefaultMinReuse);
+    if (!scan_inside)
+        hipLaunchKernelGGL(unique_sums_choose_kernel, dim3((unsigned)n_ublocks), dim3(kScanThreads), 0, s, win_unique,
+                           n_win, scan_work, pa);
     hipLaunchKernelGGL(plan_scan_kernel, dim3(1), dim3(1024), 0, s, 1, nb_rows, block_sums, nnz, n_win,
                        m->d_win_unique_ptr, long_off, slot_off, tail_off, info, m->d_long_slot_ptr,
-                       scan_inside ? win_unique : (const int32_t *)nullptr, m->d_win_unique_ptr);
+                       scan_inside ? win_unique : (const int32_t *)nullptr, m->d_win_unique_ptr, scan_work, n_ublocks,
+                       pa);
+    if (!scan_inside)
+        hipLaunchKernelGGL(scan_apply_kernel, dim3((unsigned)n_ublocks), dim3(kScanThreads), 0, s, win_unique,
+                           m->d_win_unique_ptr, n_win, scan_work, n_ublocks);
     if (nb_rows > 0)
         hipLaunchKernelGGL(seg_fill_kernel, dim3((unsigned)nb_rows), dim3(256), 0, s, 1, n, m->d_row_ptr, m->d_col_idx,
                            info, nb_rows, long_off, slot_off, tail_off, m->d_seg_row, m->d_seg_ebeg,
                            m->d_seg_dst, m->d_long_row, m->d_long_slot_ptr, m->d_long_ebeg, m->d_long_len, m->d_gchunk_li, m->d_gchunk_c, slot_row, slot_ebeg,
                                slot_key);
-    launch_choose_path(m, TCG_POLICY_AUTO, kDefaultMinReuse, s);
     TCG_TRY(launch_status("plan and path kernels"));
 
     BuildInfo h;

@@ -90,6 +90,27 @@ def test_sgt_large_windows_in_both_bitmap_variants():
         meta.free()
 
 
+def test_sgt_hub_windows_translated_in_parts():
+    # A window of the LDS-bitmap class with more than 16,384 entries is listed in 2 .. 8 parts (each part ranks
+    # its share of the entries): windows in 2, 3 and 8 parts (the last beyond 8 x 16,384 entries) next to ordinary
+    # ones, unsorted rows with repeated entries, the first and the last column present.
+    rng = np.random.default_rng(33)
+    n_cols = 300000
+    per_row = [1200] * 16 + [5] * 16 + [2900] * 16 + [40] * 16 + [9000] * 16 + [700] * 16
+    rows = [rng.integers(0, n_cols, size=k) for k in per_row]
+    rows[0][:2] = (0, n_cols - 1)
+    rows[64][:4] = (n_cols - 1, 0, 7, 7)
+    g = csr_from_rows(rows, n_cols)
+    rp, ci = upload_csr(g)
+    meta = tcg.sgt_build(rp, ci, 16, 8, n_cols=n_cols)
+    check_sgt(meta, g, 16, 8)
+    meta.free()
+    # 12 rows per window: parts whose shares do not divide evenly
+    meta = tcg.sgt_build(rp, ci, 12, 16, n_cols=n_cols)
+    check_sgt(meta, g, 12, 16)
+    meta.free()
+
+
 @pytest.mark.parametrize("cfg,n,H", [(1, 2048, 16), (3, 30000, 16), (4, 50000, 16), (5, 64 * 100, 16), (2, 1003, 12)])
 def test_sgt_tile_counts_with_and_without_the_translation(cfg, n, H):
     # Section 5.2's quantity for the paper's two tile widths (8: aggregation, 16: edge features) and two
