@@ -1335,8 +1335,22 @@ __global__ __launch_bounds__(256) void tile_stats_kernel(int32_t n_rows, int32_t
         window_edge_range(rp, n_rows, win_h, w, &lo, &hi);
         const int32_t uw = win_unique_ptr[w + 1] - win_unique_ptr[w];
         if (threadIdx.x == 0) tiles += (unsigned long long)(((int64_t)uw + tile_w - 1) / tile_w);
-        for (int32_t k = threadIdx.x; k < uw; k += 256)
-            if (k == 0 || col_to_row[lo + k] / tile_w != col_to_row[lo + k - 1] / tile_w) ++blocks;
+        // eight entries per thread in flight: a hub window has 10^5 distinct columns
+        constexpr int kUnroll = 8;
+        for (int32_t k0 = threadIdx.x; k0 < uw; k0 += 256 * kUnroll) {
+            int32_t cur[kUnroll], prev[kUnroll];
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) {
+                const int32_t k = k0 + u * 256;
+                cur[u] = k < uw ? col_to_row[lo + k] : 0;
+                prev[u] = k < uw && k > 0 ? col_to_row[lo + k - 1] : 0;
+            }
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) {
+                const int32_t k = k0 + u * 256;
+                if (k < uw && (k == 0 || cur[u] / tile_w != prev[u] / tile_w)) ++blocks;
+            }
+        }
     }
     blocks = wave_sum_u64(blocks);
     if ((threadIdx.x & (kWave - 1)) == 0) s_red[threadIdx.x >> 6] = blocks;

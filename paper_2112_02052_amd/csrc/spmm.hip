@@ -460,14 +460,13 @@ int reserve_partial(tcg_meta *m, int32_t D, hipStream_t s)
                     "regrown while the stream is being captured: call tcg_sgt_reserve first");
         return TCG_ESCRATCH;
     }
+    float *fresh = nullptr;
+    TCG_TRY(dev_alloc(&fresh, need));        // on failure the plan keeps the scratch it has
     if (m->partial_owned) {
         TCG_HIP(hipStreamSynchronize(s));
         pool_free(m->d_partial);
     }
-    m->d_partial = nullptr;
-    m->partial_elems = 0;
-    m->partial_owned = false;
-    TCG_TRY(dev_alloc(&m->d_partial, need));
+    m->d_partial = fresh;
     m->partial_elems = need;
     m->partial_owned = true;
     return TCG_OK;

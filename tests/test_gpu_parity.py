@@ -142,6 +142,27 @@ def test_sgt_empty_and_degenerate():
         meta.free()
 
 
+def test_out_of_device_memory_is_an_error_code_and_leaves_the_plan_usable():
+    # Scratch for an absurd feature width (1,600 split-row segments x 2^31 - 1 columns x 4 bytes = 13 TB) cannot be
+    # allocated: TCG_ENOMEM, and the plan, its scratch and the library keep working.
+    rng = np.random.default_rng(2)
+    rows = [np.sort(rng.choice(250000, size=k, replace=False)) for k in (200000, 3, 0, 900)] + [[i] for i in range(60)]
+    g = csr_from_rows(rows, 250000)
+    rp, ci = upload_csr(g)
+    meta = tcg.sgt_build(rp, ci, 16, 8, n_cols=g.n_cols)
+    X = rng.standard_normal((g.n_cols, 16)).astype(np.float32)
+    Xd = torch.from_numpy(X).to(dev())
+    Y0 = tcg.spmm(meta, Xd)
+    with pytest.raises(tcg.TcgError) as ei:
+        tcg.sgt_reserve(meta, 2 ** 31 - 1)
+    assert ei.value.status == -4
+    Y1 = tcg.spmm(meta, Xd)
+    torch.cuda.synchronize()
+    assert torch.equal(Y0, Y1)
+    assert norm_err(Y1.cpu().numpy(), oracle.spmm(g.row_ptr, g.col_idx, X, None)) <= TOL_F32
+    meta.free()
+
+
 def test_sgt_rejects_malformed_csr():
     rp = torch.tensor([0, 2, 1, 3], dtype=torch.int32, device=dev())
     ci = torch.tensor([0, 1, 2], dtype=torch.int32, device=dev())
