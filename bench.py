@@ -17,6 +17,8 @@ The printed JSON line reports
                      `frac_compulsory` with every X row once
   cpu_baseline       the CPU oracle's SpMM timed on the host cores, same inputs (plus the float-accumulating
                      variants and the window-parallel translation, each with its core count)
+  d_sweep            SpMM / SDDMM on the headline graph for feature widths 16 .. 256 in both feature types (the
+                     paper's embedding-dimension study, section 5.4)
   configs            with no --workload: a few steps of every other workload x feature type (ms as median
                      and minimum, GFLOP/s, Gedges/s, byte counts, tile share, tile counts with and without the
                      translation, largest normalised error against the oracle on the full outputs)
@@ -505,6 +507,28 @@ def main():
                      "csr_gather_bytes": b["spmm_csr_gather"]},
         "generate_s": run.gen_s,
     }
+    # Throughput against the feature width on the same graph (the paper's embedding-dimension study, section 5.4):
+    # D = 16 .. 256 in both feature types, a few calls each on the reused translation; timing only (uniform
+    # features from a seeded generator on the device).
+    if not args.no_configs and args.model is None and not args.backward:
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(0)
+        tdt = {"f32": torch.float32, "bf16": torch.bfloat16}
+        sweep = []
+        for d in (16, 32, 64, 128, 256):
+            x32 = torch.rand((g.n_cols, d), generator=gen, device=dev) * 2.0 - 1.0
+            y = torch.empty((N, d), dtype=torch.float32, device=dev)
+            for f in feats:
+                x = x32.to(tdt[f])
+                sp = run.timed(lambda: tcg.spmm(meta, x, run.P if run.spmm_op == "spmm_w" else run.w_given, Y=y), 6)
+                sd = run.timed(lambda: tcg.sddmm(meta, x, out=run.E), 6)
+                b_alg = algorithmic_bytes_spmm(N, nnz, meta.total_unique, meta.n_windows, d, SX[f], 4, run.weighted)
+                sweep.append({"D": d, "features": f, "spmm_ms": sp["median"], "sddmm_ms": sd["median"],
+                              "spmm_gflops": 2.0 * nnz * d / sp["median"] / 1e6,
+                              "sddmm_gedges": nnz / sd["median"] / 1e6,
+                              "spmm_frac_hbm_algorithmic": b_alg / (sp["median"] * 1e-3) / 1e9 / HBM_PEAK_GBS})
+            del x32, y
+        out["d_sweep"] = sweep
     if run.reorder_info is not None:
         run.reorder_info["window_unique_after"] = meta.total_unique
         out["reorder"] = run.reorder_info
