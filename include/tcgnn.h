@@ -16,7 +16,8 @@
  *     enqueued on it and the call returns without waiting, except tcg_sgt_build and
  *     tcg_sgt_set_policy, which wait for the stream because sizes must reach the host, and
  *     tcg_sgt_export to host memory.
- *   - Indices are int32; nnz and the sum of window-unique columns must be below 2^31.
+ *   - Indices are int32; nnz (and with it the sum of window-unique columns) must be below 2^31 - 2^16
+ *     (TCG_ERANGE otherwise, decided before any device work).
  *   - The caller owns every array it passes in.  The CSR arrays are BORROWED by the metadata
  *     object: they must stay alive and unchanged until tcg_sgt_free().
  *   - A tcg_meta may be used by one call at a time (calls on one stream are ordered and fine;

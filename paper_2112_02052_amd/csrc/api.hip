@@ -42,7 +42,7 @@ int tcg_sgt_build(int32_t n_rows, int32_t n_cols, int64_t nnz, const int32_t *d_
     if (!out || !d_row_ptr || n_rows < 0 || n_cols < 0 || nnz < 0 || window_h < 1 || tile_w < 1)
         return TCG_EINVAL;
     if (nnz > 0 && !d_col_idx) return TCG_EINVAL;
-    if (nnz >= (int64_t)INT32_MAX || (int64_t)n_rows + 1 >= (int64_t)INT32_MAX) return TCG_ERANGE;
+    if (nnz >= kIndexLimit || (int64_t)n_rows + 1 >= (int64_t)INT32_MAX) return TCG_ERANGE;
     tcg_meta *m = new (std::nothrow) tcg_meta();
     if (!m) return TCG_ENOMEM;
     if (hipGetDevice(&m->device) != hipSuccess) {
@@ -83,7 +83,7 @@ int tcg_sgt_build_clustered(int32_t n, int64_t nnz, const int32_t *d_row_ptr, co
         return TCG_EINVAL;
     if (n > 0 && !d_perm) return TCG_EINVAL;
     if (nnz > 0 && (!d_col_idx || !d_out_col_idx)) return TCG_EINVAL;
-    if (nnz >= (int64_t)INT32_MAX || (int64_t)n + 1 >= (int64_t)INT32_MAX) return TCG_ERANGE;
+    if (nnz >= kIndexLimit || (int64_t)n + 1 >= (int64_t)INT32_MAX) return TCG_ERANGE;
     hipStream_t s = static_cast<hipStream_t>(stream);
     // the clustering validates the pattern (TCG_ECSR), so the translation need not do it again
     TCG_TRY(reorder_rows_impl(n, nnz, d_row_ptr, d_col_idx, seed, refine, d_perm, s));
@@ -244,7 +244,7 @@ int tcg_csr_transpose(int32_t n_rows, int32_t n_cols, int64_t nnz, const int32_t
 {
     if (n_rows < 0 || n_cols < 0 || nnz < 0 || !d_row_ptr || !d_out_row_ptr) return TCG_EINVAL;
     if (nnz > 0 && (!d_col_idx || !d_out_col_idx || !d_perm)) return TCG_EINVAL;
-    if (nnz >= (int64_t)INT32_MAX || (int64_t)n_cols + 1 >= (int64_t)INT32_MAX) return TCG_ERANGE;
+    if (nnz >= kIndexLimit || (int64_t)n_cols + 1 >= (int64_t)INT32_MAX) return TCG_ERANGE;
     return csr_transpose_impl(n_rows, n_cols, nnz, d_row_ptr, d_col_idx, d_out_row_ptr, d_out_col_idx, d_perm,
                               static_cast<hipStream_t>(stream));
 }
@@ -255,7 +255,7 @@ int tcg_reorder_rows(int32_t n, int64_t nnz, const int32_t *d_row_ptr, const int
     if (n < 0 || nnz < 0 || refine < 0 || !d_row_ptr) return TCG_EINVAL;
     if (n > 0 && !d_perm) return TCG_EINVAL;
     if (nnz > 0 && !d_col_idx) return TCG_EINVAL;
-    if (nnz >= (int64_t)INT32_MAX || (int64_t)n + 1 >= (int64_t)INT32_MAX) return TCG_ERANGE;
+    if (nnz >= kIndexLimit || (int64_t)n + 1 >= (int64_t)INT32_MAX) return TCG_ERANGE;
     return reorder_rows_impl(n, nnz, d_row_ptr, d_col_idx, seed, refine, d_perm, static_cast<hipStream_t>(stream));
 }
 
@@ -266,7 +266,7 @@ int tcg_csr_permute(int32_t n, int64_t nnz, const int32_t *d_row_ptr, const int3
     if (n < 0 || nnz < 0 || !d_row_ptr || !d_out_row_ptr) return TCG_EINVAL;
     if (n > 0 && !d_perm) return TCG_EINVAL;
     if (nnz > 0 && (!d_col_idx || !d_out_col_idx)) return TCG_EINVAL;
-    if (nnz >= (int64_t)INT32_MAX || (int64_t)n + 1 >= (int64_t)INT32_MAX) return TCG_ERANGE;
+    if (nnz >= kIndexLimit || (int64_t)n + 1 >= (int64_t)INT32_MAX) return TCG_ERANGE;
     return csr_permute_impl(n, nnz, d_row_ptr, d_col_idx, d_perm, d_out_row_ptr, d_out_col_idx, d_edge_perm,
                             static_cast<hipStream_t>(stream));
 }

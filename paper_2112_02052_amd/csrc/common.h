@@ -15,6 +15,9 @@ constexpr int kSegLen = 128;         // max edges of one row segment on the gath
 constexpr int kGiantRow = 2048;      // up to this length a row fits one wavefront's registers; longer rows are listed
 constexpr int kGiantChunk = 4096;    // apart in the plan, in pieces of this many entries (one workgroup per piece in
                                      // the row-wise kernels)
+// Largest nnz the library takes: the kernels form entry positions up to a few thousand past the end of a row
+// (look-ahead of the unrolled loops) before comparing them with it, and those must still fit int32.
+constexpr int64_t kIndexLimit = (int64_t)INT32_MAX - (1 << 16);
 constexpr float kDefaultMinReuse = 2.0f;
 constexpr int kXcds = 8;              // accelerator dies of an MI355X; workgroup i is dispatched to die i % 8
 constexpr int kPartialInitD = 128;   // the build reserves partial-sum scratch for feature widths up to this

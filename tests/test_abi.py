@@ -47,7 +47,7 @@ def test_sizes_beyond_the_int32_index_space_are_refused_before_any_gpu_work():
     lib = tcg.load_library()
     fake = ctypes.c_void_p(256)
     h = ctypes.c_void_p()
-    for n_rows, nnz in ((4, 2 ** 31 - 1), (4, 2 ** 31), (4, 2 ** 40), (2 ** 31 - 2, 8)):
+    for n_rows, nnz in ((4, 2 ** 31 - 2 ** 16 - 1), (4, 2 ** 31 - 1), (4, 2 ** 31), (4, 2 ** 40), (2 ** 31 - 2, 8)):
         assert lib.tcg_sgt_build(n_rows, 4, nnz, fake, fake, 16, 8, 0, None, ctypes.byref(h)) == -3
         assert h.value is None
     assert lib.tcg_csr_transpose(4, 4, 2 ** 31, fake, fake, fake, fake, fake, None) == -3
