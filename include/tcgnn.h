@@ -85,7 +85,10 @@ typedef enum {
  *   validate        non-zero: check the CSR on the device first (TCG_ECSR on failure);
  *                   zero: the caller guarantees a well-formed CSR
  *   out             receives the metadata object; untouched on error
- * Blocks until the stream has finished the build.
+ * Blocks until the stream has finished the build.  Part of the work runs on two streams of the library's own
+ * (default priority, ordered against `stream` by events), and sizes travel to the host: `stream` must not be
+ * under HIP graph capture.  Builds that run at the same time on one device share those two streams and are
+ * ordered against each other there.
  */
 TCG_API int tcg_sgt_build(int32_t n_rows, int32_t n_cols, int64_t nnz,
                   const int32_t *d_row_ptr, const int32_t *d_col_idx,
@@ -219,7 +222,8 @@ TCG_API int tcg_sddmm_pq(tcg_meta *meta, const void *d_P, int64_t ldp, const voi
  * Row-wise softmax over the stored entries of each row (the normalisation of the
  * attention-style workload; not part of the paper's method):
  *   d_out[e] = exp(d_in[e] - m_i) / sum_{e' in row i} exp(d_in[e'] - m_i),  m_i = row maximum.
- * In-place (d_out == d_in) is allowed.
+ * In-place (d_out == d_in) is allowed.  Rows of more than 2,048 entries are worked on in pieces whose partial
+ * results pass through the metadata object's scratch (one call at a time per object, see the conventions above).
  */
 TCG_API int tcg_row_softmax(const tcg_meta *meta, const float *d_in, float *d_out, void *stream);
 
