@@ -90,6 +90,36 @@ def test_sgt_large_windows_in_both_bitmap_variants():
         meta.free()
 
 
+def test_more_windows_than_one_workgroup_scans():
+    # Above 16,384 windows the unique counts are scanned, and the windows' paths chosen, by a multi-workgroup pass
+    # instead of the single workgroup that serves smaller graphs: a clustered graph of 19,200 windows whose windows
+    # go to the MFMA tile path (translation, plan statistics, SpMM and SDDMM), and one-row windows on a power-law
+    # graph.
+    c = W.make_config(5, n=64 * 4800, permute=False, d=64)
+    g, X = c["csr"], c["X"]
+    rp, ci = upload_csr(g)
+    meta = tcg.sgt_build(rp, ci, 16, 8)
+    assert meta.n_windows == 19200
+    ref = check_sgt(meta, g, 16, 8)
+    uw = np.diff(ref["win_unique_ptr"])
+    nnz_w = np.add.reduceat(np.diff(g.row_ptr), np.arange(0, g.n_rows, 16))
+    expect = int(np.sum((uw > 0) & (uw <= 512) & (nnz_w >= 2.0 * uw)))
+    assert tcg.sgt_plan_stats(meta)["n_tile_windows"] == expect and expect > 0.95 * meta.n_windows
+    Xd = upload_x(X, "bf16")
+    e = tcg.sddmm(meta, Xd)
+    Y = tcg.spmm(meta, Xd)
+    torch.cuda.synchronize()
+    assert norm_err(e.cpu().numpy(), oracle.sddmm(g.row_ptr, g.col_idx, X)) <= TOL_F32
+    assert norm_err(Y.cpu().numpy(), oracle.spmm(g.row_ptr, g.col_idx, X)) <= TOL_F32
+    meta.free()
+    g = W.make_config(3, n=30000, d=4)["csr"]
+    rp, ci = upload_csr(g)
+    meta = tcg.sgt_build(rp, ci, 1, 8)
+    assert meta.n_windows == 30000
+    check_sgt(meta, g, 1, 8)
+    meta.free()
+
+
 def test_sgt_hub_windows_translated_in_parts():
     # A window of the LDS-bitmap class with more than 16,384 entries is listed in 2 .. 8 parts (each part ranks
     # its share of the entries): windows in 2, 3 and 8 parts (the last beyond 8 x 16,384 entries) next to ordinary
