@@ -985,10 +985,10 @@ __global__ __launch_bounds__(1024) void plan_scan_kernel(int phase, int64_t nb, 
 // ---- gather plan, step 3: the segment list -----------------------------------------------------------
 // A thread takes four consecutive rows of its workgroup's block.  Single-segment rows go straight to their
 // final place (stable inside a length class: block offset + the rows of the same class in front of this one
-// inside the block).  Split rows get their entry in the table of split rows (long_row, long_slot_ptr, long_ebeg,
-// long_len); their segments ("slots", numbered in row order) are written from that table by slot_fill_kernel.
-// One workgroup-wide scan carries all the counts: split rows, their segments, and the eight class counts
-// packed two to a word (a block has 1024 rows).
+// inside the block).  Split rows get their entry in long_row / long_slot_ptr; their segments ("slots",
+// numbered in row order) are written with the start column as sort key by all threads of the workgroup
+// together -- a hub row has hundreds of segments.  One workgroup-wide scan carries all the counts: split
+// rows, their segments, and the eight class counts packed two to a word (a block has 1024 rows).
 // Sort key of a split row's segment: its start column at a relative resolution of 1/8 (the column itself
 // below 16, else 8 steps per power of two) -- monotone in the column, at most 8 bits, so one pass of the
 // radix sort orders the segments.  Skewed graphs keep their popular columns at small ids, where this key
@@ -1047,10 +1047,12 @@ __global__ __launch_bounds__(256) void seg_fill_kernel(
     const int32_t *__restrict__ tail_off, int32_t *__restrict__ seg_row,
     int32_t *__restrict__ seg_ebeg, int32_t *__restrict__ seg_dst, int32_t *__restrict__ long_row,
     int32_t *__restrict__ long_slot_ptr, int32_t *__restrict__ long_ebeg, int32_t *__restrict__ long_len,
-    int32_t *__restrict__ gchunk_li, int32_t *__restrict__ gchunk_c)
+    int32_t *__restrict__ gchunk_li, int32_t *__restrict__ gchunk_c, int32_t *__restrict__ slot_row,
+    int32_t *__restrict__ slot_ebeg, int32_t *__restrict__ slot_key)
 {
     constexpr int RPT = kRowBlock / 256;           // rows per thread
     __shared__ int s_tmp[256 / kWave][kFillVals];
+    __shared__ int32_t s_lrow[kRowBlock], s_le0[kRowBlock], s_lslot[kRowBlock + 1];
     const int sort_tail = phase == 1 ? info->sort_tail : 0;
     const int32_t n_slots = info->n_slots;
     const int32_t long_base = long_off[blockIdx.x], slot_base = slot_off[blockIdx.x];
@@ -1124,6 +1126,9 @@ __global__ __launch_bounds__(256) void seg_fill_kernel(
                     gchunk_c[at + c] = c;
                 }
             }
+            s_lrow[lrank] = (int32_t)(r0 + k);
+            s_le0[lrank] = e0[k];
+            s_lslot[lrank] = srank;
             ++lrank;
             srank += (deg[k] + kSegLen - 1) / kSegLen;
         } else if (phase == 1) {
@@ -1136,6 +1141,8 @@ __global__ __launch_bounds__(256) void seg_fill_kernel(
             s_tdeg[lp] = deg[k];
         }
     }
+    const int n_lrows = total.v[0], n_lsegs = total.v[1];
+    if (threadIdx.x == 0) s_lslot[n_lrows] = n_lsegs;
     __syncthreads();
     for (int i = threadIdx.x; phase == 1 && i < s_cstart[kTailClasses]; i += 256) {
         int c = 0;
@@ -1148,28 +1155,35 @@ __global__ __launch_bounds__(256) void seg_fill_kernel(
         seg_ebeg[p] = s_te0[i];
         seg_dst[p] = -1 - s_tdeg[i];     // below zero: written straight to the result; carries the row's length
     }
-}
-
-// The segments ("slots") of the split rows, numbered in row order: one thread per slot finds its row in the table of
-// split rows (long_slot_ptr is ascending) and writes the slot's row, first edge and sort key.  A flat launch over
-// all slots: the row block that holds the hub rows of a power-law graph has tens of thousands of them.
-__global__ __launch_bounds__(256) void slot_fill_kernel(const BuildInfo *info, const int32_t *__restrict__ long_row,
-                                                        const int32_t *__restrict__ long_slot_ptr,
-                                                        const int32_t *__restrict__ long_ebeg,
-                                                        const int32_t *__restrict__ ci, int32_t *__restrict__ slot_row,
-                                                        int32_t *__restrict__ slot_ebeg, int32_t *__restrict__ slot_key)
-{
-    const int64_t sl = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (sl >= info->n_slots) return;
-    int32_t a = 0, b = info->n_long;               // last split row whose first slot is <= sl
-    while (b - a > 1) {
-        const int32_t mid = (a + b) >> 1;
-        if (long_slot_ptr[mid] <= sl) a = mid; else b = mid;
+    // the slots of the block's split rows: four per thread and step, their start columns gathered together (the
+    // block that holds the hub rows of a power-law graph has thousands of slots)
+    for (int32_t s0 = threadIdx.x; phase == 0 && s0 < n_lsegs; s0 += 4 * 256) {
+        int32_t eb[4], row[4];
+        uint32_t col[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int32_t sl = s0 + u * 256;
+            eb[u] = -1;
+            if (sl >= n_lsegs) continue;
+            int a = 0, b = n_lrows;                // last split row whose first slot is <= sl
+            while (b - a > 1) {
+                const int mid = (a + b) >> 1;
+                if (s_lslot[mid] <= sl) a = mid; else b = mid;
+            }
+            eb[u] = s_le0[a] + (sl - s_lslot[a]) * kSegLen;
+            row[u] = s_lrow[a];
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) col[u] = eb[u] >= 0 ? (uint32_t)ci[eb[u]] : 0u;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            if (eb[u] < 0) continue;
+            const int32_t g = slot_base + s0 + u * 256;
+            slot_row[g] = row[u];
+            slot_ebeg[g] = eb[u];
+            slot_key[g] = seg_sort_key(col[u]);
+        }
     }
-    const int32_t eb = long_ebeg[a] + ((int32_t)sl - long_slot_ptr[a]) * kSegLen;
-    slot_row[sl] = long_row[a];
-    slot_ebeg[sl] = eb;
-    slot_key[sl] = seg_sort_key((uint32_t)ci[eb]);
 }
 
 // Split rows' segments in their final order: position i of the list takes slot order[i] (order == nullptr:
@@ -1650,12 +1664,8 @@ int sgt_build_impl(tcg_meta *m, int validate, hipStream_t s)
         if (nb_rows > 0) {
             hipLaunchKernelGGL(seg_fill_kernel, dim3((unsigned)nb_rows), dim3(256), 0, ps, 0, n, m->d_row_ptr, m->d_col_idx,
                                info, nb_rows, long_off, slot_off, tail_off, m->d_seg_row, m->d_seg_ebeg, m->d_seg_dst,
-                               m->d_long_row, m->d_long_slot_ptr, m->d_long_ebeg, m->d_long_len, m->d_gchunk_li,
-                               m->d_gchunk_c);
-            if (slot_bound > 0 && nnz > 0)
-                hipLaunchKernelGGL(slot_fill_kernel, dim3((unsigned)ceil_div(slot_bound, 256)), dim3(256), 0, ps, info,
-                                   m->d_long_row, m->d_long_slot_ptr, m->d_long_ebeg, m->d_col_idx, slot_row, slot_ebeg,
-                                   slot_key);
+                               m->d_long_row, m->d_long_slot_ptr, m->d_long_ebeg, m->d_long_len, m->d_gchunk_li, m->d_gchunk_c, slot_row, slot_ebeg,
+                               slot_key);
             TCG_TRY(launch_status("plan kernels"));
             const bool sorted = sort_bytes > 0 && slot_bound > 1;
             if (sorted)
@@ -1695,8 +1705,8 @@ int sgt_build_impl(tcg_meta *m, int validate, hipStream_t s)
     if (nb_rows > 0)
         hipLaunchKernelGGL(seg_fill_kernel, dim3((unsigned)nb_rows), dim3(256), 0, s, 1, n, m->d_row_ptr, m->d_col_idx,
                            info, nb_rows, long_off, slot_off, tail_off, m->d_seg_row, m->d_seg_ebeg,
-                           m->d_seg_dst, m->d_long_row, m->d_long_slot_ptr, m->d_long_ebeg, m->d_long_len, m->d_gchunk_li,
-                           m->d_gchunk_c);
+                           m->d_seg_dst, m->d_long_row, m->d_long_slot_ptr, m->d_long_ebeg, m->d_long_len, m->d_gchunk_li, m->d_gchunk_c, slot_row, slot_ebeg,
+                               slot_key);
     TCG_TRY(launch_status("plan and path kernels"));
 
     BuildInfo h;
