@@ -193,6 +193,45 @@ def test_out_of_device_memory_is_an_error_code_and_leaves_the_plan_usable():
     meta.free()
 
 
+def test_builds_and_calls_from_two_host_threads():
+    # Two host threads, each with its own stream, translate different graphs and run the aggregation at the same
+    # time (the translations share the library's two side streams and its allocator): every result is checked
+    # against the oracle, and the translations bit for bit.
+    import threading
+    cases = [(W.make_config(3, n=20000, d=32), 16), (W.make_config(4, n=30000, d=64), 16),
+             (W.make_config(2, n=6000, d=16), 12), (W.make_config(5, n=64 * 150, d=64, permute=False), 16)]
+    refs = [(oracle.sgt(c["csr"].row_ptr, c["csr"].col_idx, H, 8),
+             oracle.spmm(c["csr"].row_ptr, c["csr"].col_idx, np.asarray(c["X"], dtype=np.float32), None)) for c, H in cases]
+    errors = []
+
+    def work(tid):
+        try:
+            stream = torch.cuda.Stream()
+            with torch.cuda.stream(stream):
+                for rep in range(4):
+                    for k in range(tid, len(cases), 2):
+                        (c, H), (sref, yref) = cases[k], refs[k]
+                        g = c["csr"]
+                        rp, ci = upload_csr(g)
+                        meta = tcg.sgt_build(rp, ci, H, 8)
+                        got = {n: v.cpu().numpy() for n, v in tcg.sgt_export(meta).items()}
+                        for n in ("win_partition", "edge_to_col", "col_to_row"):
+                            assert np.array_equal(got[n], sref[n]), (k, n)
+                        Y = tcg.spmm(meta, upload_x(np.asarray(c["X"], dtype=np.float32), "f32"))
+                        stream.synchronize()
+                        assert norm_err(Y.cpu().numpy(), yref) <= TOL_F32, k
+                        meta.free()
+        except BaseException as exc:        # reported by the main thread
+            errors.append((tid, repr(exc)))
+
+    threads = [threading.Thread(target=work, args=(t,)) for t in range(2)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not errors, errors
+
+
 def test_sgt_rejects_malformed_csr():
     rp = torch.tensor([0, 2, 1, 3], dtype=torch.int32, device=dev())
     ci = torch.tensor([0, 1, 2], dtype=torch.int32, device=dev())
