@@ -1421,6 +1421,47 @@ static void launch_sort_small(const tcg_meta *m, int64_t most0, int64_t most1, i
                            m->d_edge_to_col, m->d_col_to_row, win_unique);
 }
 
+// Pinned host slots for the result block of a build (allocated once; builds running at the same time take
+// different slots).
+constexpr int kHostSlots = 16;
+static std::mutex g_slot_mu;
+static BuildInfo *g_slot_base = nullptr;
+static unsigned g_slot_busy = 0;
+static bool g_slot_failed = false;
+struct HostSlot {
+    BuildInfo *info = nullptr;
+    int index = -1;
+    HostSlot()
+    {
+        std::lock_guard<std::mutex> lock(g_slot_mu);
+        if (!g_slot_base && !g_slot_failed) {
+            void *p = nullptr;
+            if (hipHostMalloc(&p, sizeof(BuildInfo) * kHostSlots, hipHostMallocDefault) == hipSuccess)
+                g_slot_base = static_cast<BuildInfo *>(p);
+            else {
+                (void)hipGetLastError();
+                g_slot_failed = true;
+            }
+        }
+        if (!g_slot_base) return;
+        for (int i = 0; i < kHostSlots; ++i)
+            if (!((g_slot_busy >> i) & 1u)) {
+                g_slot_busy |= 1u << i;
+                index = i;
+                info = g_slot_base + i;
+                return;
+            }
+    }
+    ~HostSlot()
+    {
+        if (index < 0) return;
+        std::lock_guard<std::mutex> lock(g_slot_mu);
+        g_slot_busy &= ~(1u << index);
+    }
+    HostSlot(const HostSlot &) = delete;
+    HostSlot &operator=(const HostSlot &) = delete;
+};
+
 // Two more streams per device.  After the first kernel a translation has three independent branches: the
 // bitmap-class kernel (its hub windows make it the longest kernel, while it needs one workgroup per compute
 // unit only), the sorted classes, and the part of the gather plan that depends on row_ptr alone (a chain of
@@ -1709,9 +1750,14 @@ int sgt_build_impl(tcg_meta *m, int validate, hipStream_t s)
                                slot_key);
     TCG_TRY(launch_status("plan and path kernels"));
 
-    BuildInfo h;
-    TCG_HIP(hipMemcpyAsync(&h, info, sizeof(BuildInfo), hipMemcpyDeviceToHost, s));
+    // The result block comes back through pinned host memory (a copy to pageable memory is staged by the
+    // runtime and takes longer); a build that finds all slots taken copies to its stack instead.
+    BuildInfo h_stack;
+    HostSlot slot;
+    BuildInfo *hp = slot.info ? slot.info : &h_stack;
+    TCG_HIP(hipMemcpyAsync(hp, info, sizeof(BuildInfo), hipMemcpyDeviceToHost, s));
     TCG_HIP(hipStreamSynchronize(s));                       // the one wait of a build
+    const BuildInfo &h = *hp;
     m->n_seg = h.n_seg;
     m->n_long = h.n_long;
     m->n_gchunks = h.n_gchunks;
