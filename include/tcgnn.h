@@ -85,8 +85,9 @@ typedef enum {
  *   validate        non-zero: check the CSR on the device first (TCG_ECSR on failure);
  *                   zero: the caller guarantees a well-formed CSR
  *   out             receives the metadata object; untouched on error
- * Blocks until the stream has finished the build.  Part of the work runs on two streams of the library's own
- * (default priority, ordered against `stream` by events), and sizes travel to the host: `stream` must not be
+ * Blocks until the stream has finished the build.  For graphs of 2^20 stored entries and more, part of the work
+ * runs on two streams of the library's own (default priority, ordered against `stream` by events), and in every
+ * case sizes travel to the host: `stream` must not be
  * under HIP graph capture.  Builds that run at the same time on one device share those two streams and are
  * ordered against each other there.
  */

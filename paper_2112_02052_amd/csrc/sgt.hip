@@ -173,7 +173,8 @@ constexpr int kClsLarge = 7, kClasses = 8;
 constexpr int kSortCap = 4096;            // largest window that is sorted
 constexpr int kLdsBitmapFrom = 1024;      // ... when the bitmap class works in LDS
 constexpr int kHubEntries = 16384;        // LDS bitmap class: a window with more entries is listed in several parts,
-constexpr int kHubMaxParts = 8;           // one per kHubEntries entries up to this many (see the kernel)
+constexpr int kHubMaxParts = 8;
+constexpr int64_t kForkMinEntries = 1 << 20;       // a translation of fewer entries runs on one stream           // one per kHubEntries entries up to this many (see the kernel)
 
 __device__ __forceinline__ int window_class(int32_t cnt, int32_t sort_cap)
 {
@@ -1622,15 +1623,20 @@ int sgt_build_impl(tcg_meta *m, int validate, hipStream_t s)
     ScopedFree bitmap_guard{nullptr, s};
     SideGuard side_guard;
     SideStream *side = nullptr;
-    TCG_TRY(side_stream(m->device, &side));
-    {
+    // Small graphs stay on the caller's stream: their kernels are over before the next one is enqueued, so there
+    // is nothing to overlap, and the hand-over between streams costs 10-20 us (measured: 2,048 nodes 118 -> 100 us,
+    // 20,000 nodes 114 -> 100 us per build; 100,000 nodes with hub windows 160 -> 180 us the other way round).
+    const bool forked = nnz >= kForkMinEntries;
+    hipStream_t bitmap_stream = s, plan_stream = s;
+    if (forked) {
+        TCG_TRY(side_stream(m->device, &side));
         std::lock_guard<std::mutex> lock(g_side_mu);
         TCG_HIP(hipEventRecord(side->fork, s));
         TCG_HIP(hipStreamWaitEvent(side->stream, side->fork, 0));
         TCG_HIP(hipStreamWaitEvent(side->plan_stream, side->fork, 0));
+        side_guard.s = bitmap_stream = side->stream;
+        side_guard.s2 = plan_stream = side->plan_stream;
     }
-    side_guard.s = side->stream;
-    side_guard.s2 = side->plan_stream;
 
     // Branch 1: the bitmap class (its hub windows take longest, so it starts first).
     const int64_t large_most = std::min<int64_t>(n_win, nnz / ((int64_t)sort_cap + 1));
@@ -1647,7 +1653,7 @@ int sgt_build_impl(tcg_meta *m, int validate, hipStream_t s)
                           n_cu <= 0))
             n_cu = 256;
         const unsigned grid = (unsigned)std::min<int64_t>(large_most + hub_extra, n_cu);
-        hipLaunchKernelGGL(sgt_window_lds_bitmap_kernel, dim3(grid), dim3(kBitmapThreads), lds, side->stream, n, m->win_h,
+        hipLaunchKernelGGL(sgt_window_lds_bitmap_kernel, dim3(grid), dim3(kBitmapThreads), lds, bitmap_stream, n, m->win_h,
                            (int32_t)n_words, lists + (int64_t)kClsLarge * n_win, large_part, info->cls_count + kClsLarge,
                            &info->ticket,
                            m->d_row_ptr, m->d_col_idx, m->d_edge_to_col, m->d_col_to_row, win_unique);
@@ -1655,7 +1661,7 @@ int sgt_build_impl(tcg_meta *m, int validate, hipStream_t s)
     } else if (large_most > 0) {
         // Column space too wide for LDS: the bitmap lives in device scratch, sized by the number of windows
         // in the class, which the host has to fetch first (the one extra wait of this rare path).
-        hipStream_t bs = side->stream;
+        hipStream_t bs = bitmap_stream;
         int32_t n_large = 0;
         TCG_HIP(hipMemcpyAsync(&n_large, info->cls_count + kClsLarge, sizeof(int32_t), hipMemcpyDeviceToHost, bs));
         TCG_HIP(hipStreamSynchronize(bs));
@@ -1695,7 +1701,7 @@ int sgt_build_impl(tcg_meta *m, int validate, hipStream_t s)
     // column (segments that run one after the other on a die then read neighbouring -- on skewed graphs largely
     // the same -- X rows).
     {
-        hipStream_t ps = side->plan_stream;
+        hipStream_t ps = plan_stream;
         // (256 threads: a workgroup of 1024 waits a long time for sixteen free wavefront slots on one compute unit
         // while the sort kernels' small workgroups keep taking them)
         hipLaunchKernelGGL(plan_scan_kernel, dim3(1), dim3(256), 0, ps, 0, nb_rows, block_sums, nnz, n_win,
@@ -1721,11 +1727,13 @@ int sgt_build_impl(tcg_meta *m, int validate, hipStream_t s)
 
     // Join.
     {
-        std::lock_guard<std::mutex> lock(g_side_mu);
-        TCG_HIP(hipEventRecord(side->join, side->stream));
-        TCG_HIP(hipEventRecord(side->plan_join, side->plan_stream));
-        TCG_HIP(hipStreamWaitEvent(s, side->join, 0));
-        TCG_HIP(hipStreamWaitEvent(s, side->plan_join, 0));
+        if (forked) {
+            std::lock_guard<std::mutex> lock(g_side_mu);
+            TCG_HIP(hipEventRecord(side->join, side->stream));
+            TCG_HIP(hipEventRecord(side->plan_join, side->plan_stream));
+            TCG_HIP(hipStreamWaitEvent(s, side->join, 0));
+            TCG_HIP(hipStreamWaitEvent(s, side->plan_join, 0));
+        }
     }
 
     // With every window translated: U, and the part of the plan that depends on it (the order of the
