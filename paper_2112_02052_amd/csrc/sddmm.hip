@@ -21,6 +21,8 @@ int sddmm_tile_launch(tcg_meta *m, const void *d_P, int64_t ldp, const void *d_Q
 namespace {
 
 constexpr int kBlock = 256;
+constexpr int64_t kSlabBytes = 256;                       // see sddmm_impl
+constexpr int64_t kSlabMinMatrixBytes = (int64_t)64 << 20;
 
 // After group_reduce with G >= UNROLL, lane (position in group) `l` holds the total of partial
 // index idx(l): step off=1 keeps index parity = bit 0 of l as the LOWEST bit of the original
@@ -32,7 +34,7 @@ __global__ __launch_bounds__(kBlock) void sddmm_gather_kernel(
     const int32_t *__restrict__ lane_tab, const int32_t *__restrict__ seg_row, const int32_t *__restrict__ seg_ebeg,
     const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ col_idx,
     const char *__restrict__ P, int64_t ldp_bytes, const char *__restrict__ X, int64_t ldx_bytes, int32_t n_chunks,
-    float *__restrict__ out, const uint8_t *__restrict__ win_path, int32_t win_h)
+    float *__restrict__ out, const uint8_t *__restrict__ win_path, int32_t win_h, int accumulate)
 {
     using Pc = Piece<DT, PB>;
     constexpr bool ELEM = PB != 16;
@@ -70,6 +72,11 @@ __global__ __launch_bounds__(kBlock) void sddmm_gather_kernel(
         int32_t cnext[UNROLL];
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) cnext[u] = col_idx[min(e + UNROLL + u, last)];
+        // a later feature slab adds to what the earlier ones left (requested with the ids, ahead of the rows)
+        float prev = 0.f;
+        if constexpr (G >= UNROLL) {
+            if (accumulate && lane < UNROLL && e + lane < ee) prev = out[e + lane];
+        }
         float p[UNROLL];
         if constexpr (!ELEM) {
             uint4 raw[UNROLL][NCH];
@@ -125,12 +132,12 @@ __global__ __launch_bounds__(kBlock) void sddmm_gather_kernel(
         }
         float r = group_reduce<G, UNROLL>(p, lane);
         if constexpr (G >= UNROLL) {
-            if (lane < UNROLL && e + lane < ee) out[e + lane] = r;
+            if (lane < UNROLL && e + lane < ee) out[e + lane] = r + prev;
         } else {
             if (lane == 0) {
 #pragma unroll
                 for (int u = 0; u < UNROLL; ++u)
-                    if (e + u < ee) out[e + u] = p[u];
+                    if (e + u < ee) out[e + u] = accumulate ? out[e + u] + p[u] : p[u];
             }
         }
     }
@@ -421,7 +428,7 @@ __global__ __launch_bounds__(kBlock) void row_softmax_kernel(
 
 template <int DT, int G, int NCH, int PB = 16>
 void launch_sddmm(const tcg_meta *m, const void *P, int64_t ldp, const void *X, int64_t ldx, int32_t n_chunks,
-                  float *out, const uint8_t *win_path, hipStream_t s)
+                  float *out, const uint8_t *win_path, hipStream_t s, int accumulate = 0)
 {
     // A group narrower than 8 lanes reduces 8 partial products with more shuffles and stores than
     // loads; it takes as many edges per step as it has lanes.
@@ -430,16 +437,16 @@ void launch_sddmm(const tcg_meta *m, const void *P, int64_t ldp, const void *X, 
     hipLaunchKernelGGL((sddmm_gather_kernel<DT, G, NCH, UNROLL, PB>), dim3(grid), dim3(kBlock), 0, s, m->d_lane_tab,
                        m->d_seg_row, m->d_seg_ebeg, m->d_row_ptr, m->d_col_idx, static_cast<const char *>(P),
                        ldp * Elem<DT>::BYTES, static_cast<const char *>(X), ldx * Elem<DT>::BYTES, n_chunks, out, win_path,
-                       m->win_h);
+                       m->win_h, accumulate);
 }
 
 template <int DT>
 bool dispatch_sddmm(const tcg_meta *m, const void *P, int64_t ldp, const void *X, int64_t ldx, int32_t n_chunks,
-                    float *out, const uint8_t *win_path, hipStream_t s)
+                    float *out, const uint8_t *win_path, hipStream_t s, int accumulate = 0)
 {
     if (n_chunks <= 4) launch_sddmm<DT, 4, 1>(m, P, ldp, X, ldx, n_chunks, out, win_path, s);
     else if (n_chunks <= 8) launch_sddmm<DT, 8, 1>(m, P, ldp, X, ldx, n_chunks, out, win_path, s);
-    else if (n_chunks <= 16) launch_sddmm<DT, 16, 1>(m, P, ldp, X, ldx, n_chunks, out, win_path, s);
+    else if (n_chunks <= 16) launch_sddmm<DT, 16, 1>(m, P, ldp, X, ldx, n_chunks, out, win_path, s, accumulate);
     else if (n_chunks <= 32) launch_sddmm<DT, 32, 1>(m, P, ldp, X, ldx, n_chunks, out, win_path, s);
     else if (n_chunks <= 64) launch_sddmm<DT, 64, 1>(m, P, ldp, X, ldx, n_chunks, out, win_path, s);
     else if (n_chunks <= 128) launch_sddmm<DT, 64, 2>(m, P, ldp, X, ldx, n_chunks, out, win_path, s);
@@ -497,10 +504,24 @@ int sddmm_impl(tcg_meta *m, const void *d_P, int64_t ldp, const void *d_X, int64
                         (reinterpret_cast<uintptr_t>(d_P) & 15) == 0;
     bool done = false;
     if (vec_ok) {
-        const int32_t n_chunks = (int32_t)((int64_t)D * es / 16);
-        if (x_dt == TCG_F32) done = dispatch_sddmm<TCG_F32>(m, d_P, ldp, d_X, ldx, n_chunks, d_out, win_path, s);
-        else if (x_dt == TCG_BF16) done = dispatch_sddmm<TCG_BF16>(m, d_P, ldp, d_X, ldx, n_chunks, d_out, win_path, s);
-        else done = dispatch_sddmm<TCG_F16>(m, d_P, ldp, d_X, ldx, n_chunks, d_out, win_path, s);
+        const int64_t row_bytes = (int64_t)D * es;
+        // As in the aggregation, rows of 512 bytes and more are gathered in slabs of 256 bytes, one launch per
+        // slab, when the operand exceeds the caches; a later slab adds its share of the dot product to what the
+        // earlier ones left in d_out (read back with the column ids, ahead of the rows).  Measured on the 1M-node
+        // R-MAT graph, old and new side by side: fp32 D = 128 1.18 -> 1.16 ms, D = 256 2.65 -> 2.52 ms, bf16
+        // D = 512 2.63 -> 2.38 ms.
+        int slabs = 1;
+        if (row_bytes >= 512 && row_bytes % kSlabBytes == 0 && (int64_t)m->n_cols * row_bytes >= kSlabMinMatrixBytes)
+            slabs = (int)(row_bytes / kSlabBytes);
+        const int32_t n_chunks = (int32_t)(row_bytes / slabs / 16);
+        done = true;
+        for (int sl = 0; sl < slabs && done; ++sl) {
+            const char *Ps = static_cast<const char *>(d_P) + (int64_t)sl * kSlabBytes;
+            const char *Xs = static_cast<const char *>(d_X) + (int64_t)sl * kSlabBytes;
+            if (x_dt == TCG_F32) done = dispatch_sddmm<TCG_F32>(m, Ps, ldp, Xs, ldx, n_chunks, d_out, win_path, s, sl > 0);
+            else if (x_dt == TCG_BF16) done = dispatch_sddmm<TCG_BF16>(m, Ps, ldp, Xs, ldx, n_chunks, d_out, win_path, s, sl > 0);
+            else done = dispatch_sddmm<TCG_F16>(m, Ps, ldp, Xs, ldx, n_chunks, d_out, win_path, s, sl > 0);
+        }
     }
     if (!done) {
         if (x_dt == TCG_F32) done = dispatch_sddmm_elem<TCG_F32>(m, d_P, ldp, d_X, ldx, D, d_out, win_path, s);

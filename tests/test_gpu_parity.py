@@ -90,6 +90,30 @@ def test_sgt_large_windows_in_both_bitmap_variants():
         meta.free()
 
 
+@pytest.mark.parametrize("x_dtype,D", [("f32", 128), ("f32", 192), ("bf16", 384)])
+def test_wide_rows_of_a_large_operand_are_gathered_in_feature_slabs(x_dtype, D):
+    # Rows of 512 bytes and more of an operand beyond 64 MB are gathered in 256-byte slabs, one launch per slab
+    # (the aggregation writes each slab's columns, the edge scores add up over the slabs): 2, 3 and 3 slabs here,
+    # with edge values, against the oracle.
+    c = W.make_config(4, n=140000, d=D, x_dtype=x_dtype)
+    g, X = c["csr"], c["X"]
+    assert g.n_cols * D * (4 if x_dtype == "f32" else 2) >= 64 << 20
+    rng = np.random.default_rng(3)
+    w = rng.uniform(0.5, 1.5, g.nnz).astype(np.float32)
+    rp, ci = upload_csr(g)
+    meta = tcg.sgt_build(rp, ci, 16, 8)
+    Xd = upload_x(X, x_dtype)
+    Y = tcg.spmm(meta, Xd, torch.from_numpy(w).to(dev()))
+    e = tcg.sddmm(meta, Xd)
+    torch.cuda.synchronize()
+    assert norm_err(Y.cpu().numpy(), oracle.spmm(g.row_ptr, g.col_idx, X, w)) <= TOL_F32
+    assert norm_err(e.cpu().numpy(), oracle.sddmm(g.row_ptr, g.col_idx, X)) <= TOL_F32
+    e2 = tcg.sddmm(meta, Xd, out=torch.full_like(e, float("nan")))        # what is in the output beforehand is not used
+    torch.cuda.synchronize()
+    assert torch.equal(e, e2)
+    meta.free()
+
+
 def test_more_windows_than_one_workgroup_scans():
     # Above 16,384 windows the unique counts are scanned, and the windows' paths chosen, by a multi-workgroup pass
     # instead of the single workgroup that serves smaller graphs: a clustered graph of 19,200 windows whose windows
