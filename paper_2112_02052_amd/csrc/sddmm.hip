@@ -132,7 +132,8 @@ __global__ __launch_bounds__(kBlock) void sddmm_gather_kernel(
         }
         float r = group_reduce<G, UNROLL>(p, lane);
         if constexpr (G >= UNROLL) {
-            if (lane < UNROLL && e + lane < ee) out[e + lane] = r + prev;
+            // streaming store: the scores are not read again by this launch and should not take the rows' place in L2
+            if (lane < UNROLL && e + lane < ee) __builtin_nontemporal_store(r + prev, &out[e + lane]);
         } else {
             if (lane == 0) {
 #pragma unroll
