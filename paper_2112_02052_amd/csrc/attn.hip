@@ -35,7 +35,8 @@ __global__ __launch_bounds__(kBlock) void attn_fused_kernel(
     if (seg < 0) return;
     const int32_t row = seg_row[seg];
     const int32_t eb = seg_ebeg[seg];
-    const int32_t ee = min(eb + kSegLen, row_ptr[row + 1]);
+    const int32_t dst = seg_dst[seg];
+    const int32_t ee = segment_end(eb, dst, row, row_ptr);
 
     float xi[NCH][VEC], acc[NCH][VEC];
     {
@@ -139,11 +140,10 @@ __global__ __launch_bounds__(kBlock) void attn_fused_kernel(
         }
     }
 
-    const int32_t dst = seg_dst[seg];
     const float inv = (dst < 0 && l_run > 0.f) ? 1.f / l_run : (dst < 0 ? 0.f : 1.f);
     if (dst >= 0 && lane == 0) {
-        partial_ml[2 * (int64_t)dst] = m_run;
-        partial_ml[2 * (int64_t)dst + 1] = l_run;
+        partial_ml[2 * (int64_t)segment_slot(dst)] = m_run;
+        partial_ml[2 * (int64_t)segment_slot(dst) + 1] = l_run;
     }
 #pragma unroll
     for (int c = 0; c < NCH; ++c) {
@@ -153,7 +153,7 @@ __global__ __launch_bounds__(kBlock) void attn_fused_kernel(
 #pragma unroll
         for (int k = 0; k < VEC; ++k) {
             const float val = acc[c][k] * inv;
-            if (dst >= 0) partial[(int64_t)dst * D + d0 + k] = val;
+            if (dst >= 0) partial[(int64_t)segment_slot(dst) * D + d0 + k] = val;
             else store_elem(Y, (int64_t)row * ldy + d0 + k, y_dt, val);
         }
     }

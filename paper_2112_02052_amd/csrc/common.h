@@ -112,6 +112,19 @@ __device__ __forceinline__ int64_t plan_segment(const int32_t *__restrict__ lane
     return i < t[5] ? (int64_t)t[4] + i : -1;
 }
 
+// seg_dst of a segment.  Below zero: a single-segment row, written straight to the result, and -1 - seg_dst is its
+// length.  Otherwise a segment of a split row: the low bits are its slot (where its partial result goes), and
+// kSegFull is set when it is not the last segment of its row, i.e. has exactly kSegLen entries.  The end of a
+// segment's entries therefore needs a look at row_ptr only for the last segment of a split row -- one round
+// trip less in the chain segment record -> column ids -> rows, which is most of a short row's time.
+constexpr int32_t kSegFull = 1 << 30;
+__device__ __forceinline__ int32_t segment_slot(int32_t dst) { return dst & (kSegFull - 1); }
+__device__ __forceinline__ int32_t segment_end(int32_t eb, int32_t dst, int32_t row, const int32_t *__restrict__ row_ptr)
+{
+    if (dst < 0) return eb - 1 - dst;
+    return (dst & kSegFull) ? eb + kSegLen : row_ptr[row + 1];
+}
+
 // Host side of the same mapping: number of workgroups to launch for `groups_per_block`.
 inline int64_t plan_grid(const int32_t *h_lane_tab, int groups_per_block)
 {
@@ -229,8 +242,8 @@ struct tcg_meta {
     int64_t n_seg = 0, n_long = 0, n_slots = 0;
     int32_t *d_seg_row = nullptr;         // [n_seg] row of the segment
     int32_t *d_seg_ebeg = nullptr;        // [n_seg] first edge
-    int32_t *d_seg_dst = nullptr;         // [n_seg] partial-sum slot, or below zero: write the row directly
-                                          //         (-1 - the row's length: a single-segment row)
+    int32_t *d_seg_dst = nullptr;         // [n_seg] see segment_end(): partial-sum slot (+ kSegFull), or below zero: write
+                                          //         the row directly (-1 - the row's length: a single-segment row)
     int32_t *d_long_row = nullptr;        // [n_long] rows with more than one segment
     int32_t *d_long_slot_ptr = nullptr;   // [n_long + 1] their slot ranges
     int32_t *d_long_ebeg = nullptr;       // [n_long] their first edge

@@ -32,7 +32,7 @@ constexpr int64_t kSlabMinMatrixBytes = (int64_t)64 << 20;
 template <int DT, int G, int NCH, int UNROLL, int PB>
 __global__ __launch_bounds__(kBlock) void sddmm_gather_kernel(
     const int32_t *__restrict__ lane_tab, const int32_t *__restrict__ seg_row, const int32_t *__restrict__ seg_ebeg,
-    const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ col_idx,
+    const int32_t *__restrict__ seg_dst, const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ col_idx,
     const char *__restrict__ P, int64_t ldp_bytes, const char *__restrict__ X, int64_t ldx_bytes, int32_t n_chunks,
     float *__restrict__ out, const uint8_t *__restrict__ win_path, int32_t win_h, int accumulate)
 {
@@ -45,7 +45,7 @@ __global__ __launch_bounds__(kBlock) void sddmm_gather_kernel(
     const int32_t row = seg_row[seg];
     if (win_path != nullptr && win_path[row / win_h]) return;
     const int32_t eb = seg_ebeg[seg];
-    const int32_t ee = min(eb + kSegLen, row_ptr[row + 1]);
+    const int32_t ee = segment_end(eb, seg_dst[seg], row, row_ptr);
 
     float xi[NCH][VEC];
     {
@@ -147,7 +147,7 @@ __global__ __launch_bounds__(kBlock) void sddmm_gather_kernel(
 // Any D / alignment: one wavefront per segment, lanes stride over the feature dimension.
 __global__ __launch_bounds__(kBlock) void sddmm_gather_generic_kernel(
     const int32_t *__restrict__ lane_tab, const int32_t *__restrict__ seg_row, const int32_t *__restrict__ seg_ebeg,
-    const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ col_idx, const void *__restrict__ P,
+    const int32_t *__restrict__ seg_dst, const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ col_idx, const void *__restrict__ P,
     int64_t ldp, const void *__restrict__ X, int x_dt, int64_t ldx, int32_t D, float *__restrict__ out,
     const uint8_t *__restrict__ win_path, int32_t win_h)
 {
@@ -157,7 +157,7 @@ __global__ __launch_bounds__(kBlock) void sddmm_gather_generic_kernel(
     const int32_t row = seg_row[seg];
     if (win_path != nullptr && win_path[row / win_h]) return;
     const int32_t eb = seg_ebeg[seg];
-    const int32_t ee = min(eb + kSegLen, row_ptr[row + 1]);
+    const int32_t ee = segment_end(eb, seg_dst[seg], row, row_ptr);
     for (int32_t e = eb; e < ee; ++e) {
         const int64_t j = col_idx[e];
         float a = 0.f;
@@ -436,7 +436,7 @@ void launch_sddmm(const tcg_meta *m, const void *P, int64_t ldp, const void *X, 
     constexpr int UNROLL = NCH == 1 ? (G < 8 ? G : 8) : (NCH == 2 ? 4 : 2);
     const unsigned grid = (unsigned)plan_grid(m->h_lane_tab, kBlock / G);
     hipLaunchKernelGGL((sddmm_gather_kernel<DT, G, NCH, UNROLL, PB>), dim3(grid), dim3(kBlock), 0, s, m->d_lane_tab,
-                       m->d_seg_row, m->d_seg_ebeg, m->d_row_ptr, m->d_col_idx, static_cast<const char *>(P),
+                       m->d_seg_row, m->d_seg_ebeg, m->d_seg_dst, m->d_row_ptr, m->d_col_idx, static_cast<const char *>(P),
                        ldp * Elem<DT>::BYTES, static_cast<const char *>(X), ldx * Elem<DT>::BYTES, n_chunks, out, win_path,
                        m->win_h, accumulate);
 }
@@ -532,7 +532,7 @@ int sddmm_impl(tcg_meta *m, const void *d_P, int64_t ldp, const void *d_X, int64
     if (!done) {
         const unsigned grid = (unsigned)plan_grid(m->h_lane_tab, kBlock / kWave);
         hipLaunchKernelGGL(sddmm_gather_generic_kernel, dim3(grid), dim3(kBlock), 0, s, m->d_lane_tab, m->d_seg_row,
-                           m->d_seg_ebeg, m->d_row_ptr, m->d_col_idx, d_P, ldp, d_X, (int)x_dt, ldx, D, d_out, win_path,
+                           m->d_seg_ebeg, m->d_seg_dst, m->d_row_ptr, m->d_col_idx, d_P, ldp, d_X, (int)x_dt, ldx, D, d_out, win_path,
                            m->win_h);
     }
     return launch_status("sddmm_gather_kernel");

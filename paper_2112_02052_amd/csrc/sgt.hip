@@ -1188,7 +1188,8 @@ __global__ __launch_bounds__(256) void seg_fill_kernel(
 }
 
 // Split rows' segments in their final order: position i of the list takes slot order[i] (order == nullptr:
-// slot order).  seg_dst is the slot number, which is also where the segment's partial sum goes.
+// slot order).  seg_dst is the slot number, which is also where the segment's partial sum goes, with kSegFull
+// set unless the segment is the last of its row (slots are numbered in row order, so the next slot tells).
 __global__ void seg_permute_kernel(const BuildInfo *info, const int32_t *__restrict__ order,
                                    const int32_t *__restrict__ slot_row, const int32_t *__restrict__ slot_ebeg,
                                    int32_t *__restrict__ seg_row, int32_t *__restrict__ seg_ebeg,
@@ -1197,9 +1198,11 @@ __global__ void seg_permute_kernel(const BuildInfo *info, const int32_t *__restr
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= info->n_slots) return;
     const int32_t k = order ? order[i] : (int32_t)i;
-    seg_row[i] = slot_row[k];
+    const int32_t row = slot_row[k];
+    const bool full = k + 1 < info->n_slots && slot_row[k + 1] == row;
+    seg_row[i] = row;
     seg_ebeg[i] = slot_ebeg[k];
-    seg_dst[i] = k;
+    seg_dst[i] = full ? (k | kSegFull) : k;
 }
 
 // The per-window lists are kept where the translation wrote them, each at its window's edge offset (a

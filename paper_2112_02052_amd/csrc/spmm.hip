@@ -50,7 +50,8 @@ __global__ __launch_bounds__(kBlock) void spmm_gather_kernel(
     const int32_t row = seg_row[seg];
     if (win_path != nullptr && ((tile_mask >> win_path[row / win_h]) & 1)) return;
     const int32_t eb = seg_ebeg[seg];
-    const int32_t ee = min(eb + kSegLen, row_ptr[row + 1]);
+    const int32_t dst = seg_dst[seg];
+    const int32_t ee = segment_end(eb, dst, row, row_ptr);
 
     float acc[NCH][VEC];
 #pragma unroll
@@ -117,17 +118,16 @@ __global__ __launch_bounds__(kBlock) void spmm_gather_kernel(
         }
     }
 
-    const int32_t dst = seg_dst[seg];
 #pragma unroll
     for (int c = 0; c < NCH; ++c) {
         int chunk = lane + c * G;
         if (chunk >= n_chunks) continue;
         int64_t d0 = (int64_t)chunk * VEC;
         if (dst >= 0) {
-            float *p = partial + (int64_t)dst * partial_ld + d0;
+            float *p = partial + (int64_t)segment_slot(dst) * partial_ld + d0;
 #pragma unroll
             for (int k = 0; k < VEC; k += 4)
-                *reinterpret_cast<float4 *>(p + k) = make_float4(acc[c][k], acc[c][k + 1], acc[c][k + 2], acc[c][k + 3]);
+                stream_store(p + k, acc[c][k], acc[c][k + 1], acc[c][k + 2], acc[c][k + 3]);   // like Y: not in L2's way
         } else if (y_vec) {
             float *p = static_cast<float *>(Y) + (int64_t)row * ldy + d0;
 #pragma unroll
@@ -159,7 +159,8 @@ __global__ __launch_bounds__(kBlock) void spmm_gather_small_kernel(
     const int32_t row = seg_row[seg];
     if (win_path != nullptr && ((tile_mask >> win_path[row / win_h]) & 1)) return;
     const int32_t eb = seg_ebeg[seg];
-    const int32_t ee = min(eb + kSegLen, row_ptr[row + 1]);
+    const int32_t dst = seg_dst[seg];
+    const int32_t ee = segment_end(eb, dst, row, row_ptr);
 
     float acc[NCH][VEC];
 #pragma unroll
@@ -217,7 +218,6 @@ __global__ __launch_bounds__(kBlock) void spmm_gather_small_kernel(
         }
     }
 
-    const int32_t dst = seg_dst[seg];
 #pragma unroll
     for (int c = 0; c < NCH; ++c) {
         const int piece = lane + c * G;
@@ -225,7 +225,7 @@ __global__ __launch_bounds__(kBlock) void spmm_gather_small_kernel(
 #pragma unroll
         for (int k = 0; k < VEC; ++k) {
             const int d = piece * VEC + k;
-            if (dst >= 0) partial[(int64_t)dst * partial_ld + d] = acc[c][k];
+            if (dst >= 0) partial[(int64_t)segment_slot(dst) * partial_ld + d] = acc[c][k];
             else store_elem(Y, (int64_t)row * ldy + d, y_dt, acc[c][k]);
         }
     }
@@ -246,15 +246,15 @@ __global__ __launch_bounds__(kBlock) void spmm_gather_generic_kernel(
     const int32_t row = seg_row[seg];
     if (win_path != nullptr && ((tile_mask >> win_path[row / win_h]) & 1)) return;
     const int32_t eb = seg_ebeg[seg];
-    const int32_t ee = min(eb + kSegLen, row_ptr[row + 1]);
     const int32_t dst = seg_dst[seg];
+    const int32_t ee = segment_end(eb, dst, row, row_ptr);
     for (int32_t d = lane; d < D; d += kWave) {
         float acc = 0.f;
         for (int32_t e = eb; e < ee; ++e) {
             float x = load_elem(X, (int64_t)col_idx[e] * ldx + d, x_dt);
             acc = HAS_W ? fmaf(w[e], x, acc) : acc + x;
         }
-        if (dst >= 0) partial[(int64_t)dst * partial_ld + d] = acc;
+        if (dst >= 0) partial[(int64_t)segment_slot(dst) * partial_ld + d] = acc;
         else store_elem(Y, (int64_t)row * ldy + d, y_dt, acc);
     }
 }
