@@ -919,3 +919,76 @@ def test_calls_follow_the_current_stream():
     assert norm_err(p1.cpu().numpy(), S) <= TOL_F32
     meta0.free()
     meta1.free()
+
+
+def _random_graph(rng):
+    """Graphs nobody would draw on purpose: random shape, a random mix of empty rows, short rows, hub rows, rows
+    of one window sharing a column set, sorted or shuffled column order, column spaces from tiny to beyond the
+    LDS bitmap."""
+    n_rows = int(rng.integers(1, 6000))
+    n_cols = int(rng.choice([rng.integers(1, 3000), rng.integers(3000, 150000), rng.integers(1200000, 2500000)]))
+    kind = int(rng.integers(0, 4))
+    shared = np.sort(rng.choice(n_cols, size=min(n_cols, int(rng.integers(1, 500))), replace=False))
+    lens = np.where(rng.random(n_rows) < 0.3, 0, rng.integers(1, 30, n_rows))
+    for _ in range(int(rng.integers(0, 5))):
+        lens[rng.integers(0, n_rows)] = int(rng.integers(150, 9000)) if rng.random() < 0.8 else int(rng.integers(9000, 60000))
+    rows = []
+    for i in range(n_rows):
+        k = min(int(lens[i]), n_cols)
+        if k == 0:
+            rows.append(np.zeros(0, np.int32))
+            continue
+        if kind == 1 or (kind == 2 and (i // 16) % 2 == 0):
+            cols = rng.choice(shared, size=min(k, len(shared)), replace=False)
+        elif kind == 3 and (i // 16) % 5 == 0:
+            cols = shared
+        else:
+            cols = rng.choice(n_cols, size=k, replace=False) if k * 4 < n_cols else rng.permutation(n_cols)[:k]
+        cols = np.asarray(cols, dtype=np.int32)
+        rows.append(np.sort(cols) if rng.random() < 0.7 else cols)
+    return csr_from_rows(rows, n_cols)
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_graphs_every_operation_against_the_oracle(seed):
+    rng = np.random.default_rng(1000 + seed)
+    g = _random_graph(rng)
+    D = int(rng.choice([4, 16, 32, 64, 72, 128, 200, 256]))
+    if max(g.n_rows, g.n_cols) * D > 1.5e8:
+        D = 16
+    x_dtype = str(rng.choice(["f32", "bf16", "f16"]))
+    H = int(rng.choice([16, 16, 32, 7]))
+    policy = [tcg.POLICY_AUTO, tcg.POLICY_GATHER, tcg.POLICY_TILE][int(rng.integers(0, 3))]
+    if H == 7:
+        policy = tcg.POLICY_AUTO
+    weighted = bool(rng.random() < 0.5)
+    case = dict(seed=seed, n_rows=g.n_rows, n_cols=g.n_cols, nnz=g.nnz, D=D, x=x_dtype, H=H, policy=int(policy), w=weighted)
+    X = W.features_normal(max(g.n_rows, g.n_cols), D, seed)
+    X = W.round_to_bf16(X) if x_dtype == "bf16" else (X.astype(np.float16).astype(np.float32) if x_dtype == "f16" else X)
+    w = rng.standard_normal(g.nnz).astype(np.float32) if weighted else None
+    rp, ci = upload_csr(g)
+    meta = tcg.sgt_build(rp, ci, H, 8, n_cols=g.n_cols)
+    check_sgt(meta, g, H, 8)
+    tcg.sgt_set_policy(meta, policy)
+    Xd = upload_x(X, x_dtype)
+    tile_possible = policy != tcg.POLICY_GATHER and x_dtype != "f32"
+    Y = torch.full((g.n_rows, D), float("nan"), device=dev())
+    tcg.spmm(meta, Xd, None if w is None else torch.from_numpy(w).to(dev()), Y=Y)
+    torch.cuda.synchronize()
+    err = norm_err(Y.cpu().numpy(), oracle.spmm(g.row_ptr, g.col_idx, X[:g.n_cols], w))
+    assert err <= (TOL_MFMA if (weighted and tile_possible) else TOL_F32), ("spmm", err, case)
+    if g.nnz:
+        e = torch.full((g.nnz,), float("nan"), device=dev())
+        tcg.sddmm(meta, Xd, out=e)
+        torch.cuda.synchronize()
+        err = norm_err(e.cpu().numpy(), oracle.sddmm(g.row_ptr, g.col_idx, X))
+        assert err <= TOL_F32, ("sddmm", err, case)
+        v = (rng.standard_normal(g.nnz) * 10).astype(np.float32)
+        p = tcg.row_softmax(meta, torch.from_numpy(v).to(dev()))
+        dp = rng.standard_normal(g.nnz).astype(np.float32)
+        dv = tcg.row_softmax_backward(meta, p, torch.from_numpy(dp).to(dev()))
+        torch.cuda.synchronize()
+        assert norm_err(p.cpu().numpy(), oracle.row_softmax(g.row_ptr, v.astype(np.float64))) <= TOL_F32, ("softmax", case)
+        dv_ref = oracle.row_softmax_backward(g.row_ptr, p.cpu().numpy().astype(np.float64), dp.astype(np.float64))
+        assert norm_err(dv.cpu().numpy(), dv_ref) <= TOL_F32, ("softmax gradient", case)
+    meta.free()
