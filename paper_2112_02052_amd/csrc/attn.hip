@@ -57,13 +57,25 @@ __global__ __launch_bounds__(kBlock) void attn_fused_kernel(
     if (eb < ee) {
         const int32_t last = ee - 1;
         const uint32_t ldx32 = (uint32_t)ldx_bytes;
+        // ids: loaded once per lane group (lane l takes entries l, l + G, ...) and handed round with shuffles
+        constexpr int PER = (UNROLL + G - 1) / G;
+        auto request = [&](int32_t e0, int32_t (&mc)[PER]) {
+#pragma unroll
+            for (int k = 0; k < PER; ++k) mc[k] = col_idx[min(e0 + lane + k * G, last)];
+        };
+        auto hand_round = [&](const int32_t (&mc)[PER], int32_t (&c)[UNROLL]) {
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) c[u] = __shfl(mc[u / G], u % G, G);
+        };
         int32_t cn[UNROLL];
-#pragma unroll
-        for (int u = 0; u < UNROLL; ++u) cn[u] = col_idx[min(eb + u, last)];
+        {
+            int32_t mc[PER];
+            request(eb, mc);
+            hand_round(mc, cn);
+        }
         for (int32_t e = eb; e < ee; e += UNROLL) {
-            int32_t cnext[UNROLL];
-#pragma unroll
-            for (int u = 0; u < UNROLL; ++u) cnext[u] = col_idx[min(e + UNROLL + u, last)];
+            int32_t mc_next[PER];
+            request(e + UNROLL, mc_next);
             float v[UNROLL][NCH][VEC];
             float p[UNROLL], rj[UNROLL];
 #pragma unroll
@@ -82,8 +94,7 @@ __global__ __launch_bounds__(kBlock) void attn_fused_kernel(
                 }
                 p[u] = a;
             }
-#pragma unroll
-            for (int u = 0; u < UNROLL; ++u) cn[u] = cnext[u];
+            hand_round(mc_next, cn);          // after the row loads have gone out
 
             // Scores of the UNROLL edges, known to every lane of the group: the stored score is
             // r_i * r_j * <x_i, x_j>, the softmax runs over beta times that.

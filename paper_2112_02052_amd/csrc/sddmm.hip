@@ -64,14 +64,27 @@ __global__ __launch_bounds__(kBlock) void sddmm_gather_kernel(
     // iteration's ids go out before this iteration's row loads, so one wait covers both.
     const int32_t last = ee - 1;
     const uint32_t ldx32 = (uint32_t)ldx_bytes;
-    int32_t cn[UNROLL];
+    // The ids of a step are loaded once per lane group (lane l takes entries l, l + G, ...) and handed round with
+    // shuffles: every lane loading all UNROLL of them costs more load instructions than narrow rows do.
+    constexpr int PER = (UNROLL + G - 1) / G;
+    auto request = [&](int32_t e0, int32_t (&mc)[PER]) {
 #pragma unroll
-    for (int u = 0; u < UNROLL; ++u) cn[u] = col_idx[min(eb + u, last)];
+        for (int k = 0; k < PER; ++k) mc[k] = col_idx[min(e0 + lane + k * G, last)];
+    };
+    auto hand_round = [&](const int32_t (&mc)[PER], int32_t (&c)[UNROLL]) {
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) c[u] = __shfl(mc[u / G], u % G, G);
+    };
+    int32_t cn[UNROLL];
+    {
+        int32_t mc[PER];
+        request(eb, mc);
+        hand_round(mc, cn);
+    }
 
     for (int32_t e = eb; e < ee; e += UNROLL) {
-        int32_t cnext[UNROLL];
-#pragma unroll
-        for (int u = 0; u < UNROLL; ++u) cnext[u] = col_idx[min(e + UNROLL + u, last)];
+        int32_t mc_next[PER];
+        request(e + UNROLL, mc_next);
         // a later feature slab adds to what the earlier ones left (requested with the ids, ahead of the rows)
         float prev = 0.f;
         if constexpr (G >= UNROLL) {
@@ -91,8 +104,7 @@ __global__ __launch_bounds__(kBlock) void sddmm_gather_kernel(
                         raw[u][c] = *reinterpret_cast<const uint4 *>(xr + (uint32_t)chunk * 16u);
                 }
             }
-#pragma unroll
-            for (int u = 0; u < UNROLL; ++u) cn[u] = cnext[u];
+            hand_round(mc_next, cn);          // after the row loads have gone out
 #pragma unroll
             for (int u = 0; u < UNROLL; ++u) {
                 float a = 0.f;
@@ -118,8 +130,7 @@ __global__ __launch_bounds__(kBlock) void sddmm_gather_kernel(
                     if (e + u < ee && chunk < n_chunks) Pc::load(xr + (int64_t)chunk * Pc::BYTES, v[u][c]);
                 }
             }
-#pragma unroll
-            for (int u = 0; u < UNROLL; ++u) cn[u] = cnext[u];
+            hand_round(mc_next, cn);          // after the row loads have gone out
 #pragma unroll
             for (int u = 0; u < UNROLL; ++u) {
                 float a = 0.f;

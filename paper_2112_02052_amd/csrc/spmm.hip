@@ -64,25 +64,39 @@ __global__ __launch_bounds__(kBlock) void spmm_gather_kernel(
         // no predicate and are issued back to back; only the row loads of a ragged tail are masked.
         const int32_t last = ee - 1;
         const uint32_t ldx32 = (uint32_t)ldx_bytes;
+        // The UNROLL ids (and edge values) of a step are loaded once per lane group -- lane l takes entries l,
+        // l + G, ... -- and handed round with shuffles: every lane loading all of them costs UNROLL load
+        // instructions per array and step, which for narrow rows is more than the rows themselves.
+        constexpr int PER = (UNROLL + G - 1) / G;
+        auto request = [&](int32_t e0, int32_t (&mc)[PER], float (&mw)[PER]) {
+#pragma unroll
+            for (int k = 0; k < PER; ++k) {
+                const int32_t en = min(e0 + lane + k * G, last);
+                mc[k] = col_idx[en];
+                mw[k] = HAS_W ? w[en] : 1.f;
+            }
+        };
+        auto hand_round = [&](const int32_t (&mc)[PER], const float (&mw)[PER], int32_t (&c)[UNROLL], float (&wv)[UNROLL]) {
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) {
+                c[u] = __shfl(mc[u / G], u % G, G);
+                wv[u] = HAS_W ? __shfl(mw[u / G], u % G, G) : 1.f;
+            }
+        };
         int32_t cn[UNROLL];
         float wn[UNROLL];
-#pragma unroll
-        for (int u = 0; u < UNROLL; ++u) {
-            const int32_t en = min(eb + u, last);
-            cn[u] = col_idx[en];
-            wn[u] = HAS_W ? w[en] : 1.f;
+        {
+            int32_t mc[PER];
+            float mw[PER];
+            request(eb, mc, mw);
+            hand_round(mc, mw, cn, wn);
         }
         for (int32_t e = eb; e < ee; e += UNROLL) {
             // Next iteration's ids go out first: they are older than the row loads below, so the
             // one wait for the rows also covers them and their latency hides under the rows'.
-            int32_t cnext[UNROLL];
-            float wnext[UNROLL];
-#pragma unroll
-            for (int u = 0; u < UNROLL; ++u) {
-                const int32_t en = min(e + UNROLL + u, last);
-                cnext[u] = col_idx[en];
-                wnext[u] = HAS_W ? w[en] : 1.f;
-            }
+            int32_t mc_next[PER];
+            float mw_next[PER];
+            request(e + UNROLL, mc_next, mw_next);
             uint4 raw[UNROLL][NCH];
             float wc[UNROLL];
 #pragma unroll
@@ -97,11 +111,7 @@ __global__ __launch_bounds__(kBlock) void spmm_gather_kernel(
                         raw[u][c] = *reinterpret_cast<const uint4 *>(xr + (uint32_t)chunk * 16u);
                 }
             }
-#pragma unroll
-            for (int u = 0; u < UNROLL; ++u) {
-                cn[u] = cnext[u];
-                wn[u] = wnext[u];
-            }
+            hand_round(mc_next, mw_next, cn, wn);      // after the row loads have gone out
 #pragma unroll
             for (int u = 0; u < UNROLL; ++u) {
 #pragma unroll
