@@ -15,7 +15,8 @@
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All kernels are
  *     enqueued on it and the call returns without waiting, except tcg_sgt_build and
  *     tcg_sgt_set_policy, which wait for the stream because sizes must reach the host, and
- *     tcg_sgt_export to host memory.
+ *     tcg_sgt_export to host memory; the calls that wait say so below and return TCG_ECAPTURE when the
+ *     stream is being captured into a HIP graph.
  *   - Indices are int32; nnz (and with it the sum of window-unique columns) must be below 2^31 - 2^16
  *     (TCG_ERANGE otherwise, decided before any device work).
  *   - The caller owns every array it passes in.  The CSR arrays are BORROWED by the metadata
@@ -50,9 +51,12 @@ typedef enum {
     TCG_ERANGE = -3, /* a size does not fit the int32 index space                               */
     TCG_ENOMEM = -4, /* host or device allocation failed                                        */
     TCG_EHIP = -5,   /* a HIP runtime call or kernel launch failed                              */
-    TCG_ESCRATCH = -6 /* a scratch buffer is too small and may not be (re)allocated in this call: the
+    TCG_ESCRATCH = -6, /* a scratch buffer is too small and may not be (re)allocated in this call: the
                         static buffer of tcg_spmm_noalloc, or a plan's buffer while the stream is
                         being captured (tcg_strerror says which and by how much)                */
+    TCG_ECAPTURE = -7 /* the call waits for the stream (sizes or data travel to the host) and the stream
+                        is being captured into a HIP graph; refused before the stream is touched, so
+                        the capture stays intact                                                */
 } tcg_status;
 
 /* Which kernel family a row window is executed by (see tcg_sgt_set_policy). */

@@ -20,6 +20,22 @@ void set_hip_error(hipError_t e, const char *what)
     snprintf(g_hip_msg, sizeof(g_hip_msg), "%s: %s", what, hipGetErrorString(e));
 }
 
+// The calls that wait for the stream cannot run while it is being captured into a graph: they say so before
+// they touch it, which leaves the capture intact.
+static int refuse_capture(void *stream, const char *name)
+{
+    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(static_cast<hipStream_t>(stream), &cap) != hipSuccess) {
+        (void)hipGetLastError();
+        return TCG_OK;
+    }
+    if (cap == hipStreamCaptureStatusNone) return TCG_OK;
+    char msg[200];
+    snprintf(msg, sizeof(msg), "%s waits for the stream, which is being captured into a HIP graph", name);
+    set_message(msg);
+    return TCG_ECAPTURE;
+}
+
 static void free_meta(tcg_meta *m)
 {
     if (!m) return;
@@ -43,6 +59,7 @@ int tcg_sgt_build(int32_t n_rows, int32_t n_cols, int64_t nnz, const int32_t *d_
         return TCG_EINVAL;
     if (nnz > 0 && !d_col_idx) return TCG_EINVAL;
     if (nnz >= kIndexLimit || (int64_t)n_rows + 1 >= (int64_t)INT32_MAX) return TCG_ERANGE;
+    TCG_TRY(refuse_capture(stream, "tcg_sgt_build"));
     tcg_meta *m = new (std::nothrow) tcg_meta();
     if (!m) return TCG_ENOMEM;
     if (hipGetDevice(&m->device) != hipSuccess) {
@@ -84,6 +101,7 @@ int tcg_sgt_build_clustered(int32_t n, int64_t nnz, const int32_t *d_row_ptr, co
     if (n > 0 && !d_perm) return TCG_EINVAL;
     if (nnz > 0 && (!d_col_idx || !d_out_col_idx)) return TCG_EINVAL;
     if (nnz >= kIndexLimit || (int64_t)n + 1 >= (int64_t)INT32_MAX) return TCG_ERANGE;
+    TCG_TRY(refuse_capture(stream, "tcg_sgt_build_clustered"));
     hipStream_t s = static_cast<hipStream_t>(stream);
     // the clustering validates the pattern (TCG_ECSR), so the translation need not do it again
     TCG_TRY(reorder_rows_impl(n, nnz, d_row_ptr, d_col_idx, seed, refine, d_perm, s));
@@ -106,6 +124,7 @@ int tcg_sgt_export(const tcg_meta *meta, int32_t *win_partition, int32_t *win_un
                    int32_t *col_to_row, int dst_on_device, void *stream)
 {
     if (!meta) return TCG_EINVAL;
+    if (!dst_on_device) TCG_TRY(refuse_capture(stream, "tcg_sgt_export to host memory"));
     hipStream_t s = static_cast<hipStream_t>(stream);
     const hipMemcpyKind kind = dst_on_device ? hipMemcpyDeviceToDevice : hipMemcpyDeviceToHost;
     struct Item { void *dst; const void *src; int64_t count; };
@@ -136,6 +155,7 @@ int tcg_sgt_tile_stats(tcg_meta *meta, int32_t tile_w, int64_t *tiles_translated
                        void *stream)
 {
     if (!meta || tile_w < 1) return TCG_EINVAL;
+    TCG_TRY(refuse_capture(stream, "tcg_sgt_tile_stats"));
     return tile_stats(meta, tile_w, tiles_translated, tiles_untranslated, static_cast<hipStream_t>(stream));
 }
 
@@ -143,6 +163,7 @@ int tcg_sgt_set_policy(tcg_meta *meta, tcg_policy policy, float min_reuse, void 
 {
     if (!meta) return TCG_EINVAL;
     if (policy != TCG_POLICY_AUTO && policy != TCG_POLICY_GATHER && policy != TCG_POLICY_TILE) return TCG_EINVAL;
+    TCG_TRY(refuse_capture(stream, "tcg_sgt_set_policy"));
     return choose_paths(meta, policy, min_reuse, static_cast<hipStream_t>(stream));
 }
 
@@ -245,6 +266,7 @@ int tcg_csr_transpose(int32_t n_rows, int32_t n_cols, int64_t nnz, const int32_t
     if (n_rows < 0 || n_cols < 0 || nnz < 0 || !d_row_ptr || !d_out_row_ptr) return TCG_EINVAL;
     if (nnz > 0 && (!d_col_idx || !d_out_col_idx || !d_perm)) return TCG_EINVAL;
     if (nnz >= kIndexLimit || (int64_t)n_cols + 1 >= (int64_t)INT32_MAX) return TCG_ERANGE;
+    TCG_TRY(refuse_capture(stream, "tcg_csr_transpose"));
     return csr_transpose_impl(n_rows, n_cols, nnz, d_row_ptr, d_col_idx, d_out_row_ptr, d_out_col_idx, d_perm,
                               static_cast<hipStream_t>(stream));
 }
@@ -256,6 +278,7 @@ int tcg_reorder_rows(int32_t n, int64_t nnz, const int32_t *d_row_ptr, const int
     if (n > 0 && !d_perm) return TCG_EINVAL;
     if (nnz > 0 && !d_col_idx) return TCG_EINVAL;
     if (nnz >= kIndexLimit || (int64_t)n + 1 >= (int64_t)INT32_MAX) return TCG_ERANGE;
+    TCG_TRY(refuse_capture(stream, "tcg_reorder_rows"));
     return reorder_rows_impl(n, nnz, d_row_ptr, d_col_idx, seed, refine, d_perm, static_cast<hipStream_t>(stream));
 }
 
@@ -267,6 +290,7 @@ int tcg_csr_permute(int32_t n, int64_t nnz, const int32_t *d_row_ptr, const int3
     if (n > 0 && !d_perm) return TCG_EINVAL;
     if (nnz > 0 && (!d_col_idx || !d_out_col_idx)) return TCG_EINVAL;
     if (nnz >= kIndexLimit || (int64_t)n + 1 >= (int64_t)INT32_MAX) return TCG_ERANGE;
+    TCG_TRY(refuse_capture(stream, "tcg_csr_permute"));
     return csr_permute_impl(n, nnz, d_row_ptr, d_col_idx, d_perm, d_out_row_ptr, d_out_col_idx, d_edge_perm,
                             static_cast<hipStream_t>(stream));
 }
@@ -302,6 +326,9 @@ const char *tcg_strerror(int status)
         return g_msg;
     case TCG_EHIP:
         snprintf(g_msg, sizeof(g_msg), "HIP error: %s", g_hip_msg[0] ? g_hip_msg : "(no detail recorded)");
+        return g_msg;
+    case TCG_ECAPTURE:
+        snprintf(g_msg, sizeof(g_msg), "not possible under stream capture: %s", g_detail[0] ? g_detail : "(no detail recorded)");
         return g_msg;
     default: return "unknown status";
     }

@@ -24,7 +24,7 @@ def test_every_declared_symbol_is_exported():
 
 def test_status_texts_and_argument_checks_without_gpu():
     lib = tcg.load_library()
-    for code in (0, -1, -2, -3, -4, -5, -6, -99):
+    for code in (0, -1, -2, -3, -4, -5, -6, -7, -99):
         assert len(lib.tcg_strerror(code)) > 0
     # Null handles / null outputs are rejected before any HIP call is made.
     assert lib.tcg_sgt_build(4, 4, 0, None, None, 16, 8, 1, None, None) == -1

@@ -256,6 +256,38 @@ def test_builds_and_calls_from_two_host_threads():
     assert not errors, errors
 
 
+def test_calls_that_wait_for_the_stream_refuse_a_stream_under_capture():
+    # Translation, policy change, tile statistics and export to the host wait for the stream; under HIP graph
+    # capture they return TCG_ECAPTURE before they touch it, so the capture goes on and the graph replays.
+    c = W.make_config(2, n=3000, d=16)
+    g, X = c["csr"], c["X"]
+    rp, ci = upload_csr(g)
+    meta = tcg.sgt_build(rp, ci, 16, 8)
+    Xd = upload_x(X, "f32")
+    Y = torch.empty((g.n_rows, 16), device=dev())
+    tcg.spmm(meta, Xd, Y=Y)
+    torch.cuda.synchronize()
+    Y_eager = Y.clone()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    refused = []
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            for call in (lambda: tcg.sgt_build(rp, ci, 16, 8), lambda: tcg.sgt_set_policy(meta, tcg.POLICY_GATHER),
+                         lambda: tcg.sgt_tile_stats(meta, 8), lambda: tcg.csr_transpose(rp, ci)):
+                with pytest.raises(tcg.TcgError) as ei:
+                    call()
+                refused.append(ei.value.status)
+            tcg.spmm(meta, Xd, Y=Y)
+    assert refused == [-7] * 4
+    Y.zero_()
+    graph.replay()
+    torch.cuda.synchronize()
+    assert torch.equal(Y, Y_eager)
+    meta.free()
+
+
 def test_sgt_rejects_malformed_csr():
     rp = torch.tensor([0, 2, 1, 3], dtype=torch.int32, device=dev())
     ci = torch.tensor([0, 1, 2], dtype=torch.int32, device=dev())
