@@ -87,7 +87,8 @@ inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 // tail of the list (the same for all lanes).  A lane walks its two bands in workgroup-sized blocks,
 // one band after the other, then takes every kXcds-th run of the unbanded tail.
 constexpr int kLaneTabStride = 6;
-constexpr int kTailRun = 128;        // segments per contiguous run of the unbanded tail
+constexpr int kTailRun = 32;         // segments per contiguous run of the unbanded tail (16 .. 64 measure alike,
+                                     // 128 and more 2-5 % slower: shorter runs spread a stretch of long rows over the dies)
 __device__ __forceinline__ int64_t plan_segment(const int32_t *__restrict__ lane_tab, int groups_per_block,
                                                 int group)
 {
