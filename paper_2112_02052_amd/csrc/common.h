@@ -11,7 +11,14 @@
 namespace tcg {
 
 constexpr int kWave = 64;            // gfx950 wavefront width
-constexpr int kSegLen = 128;         // max edges of one row segment on the gather path
+constexpr int kSegLen = 128;         // a row with more entries is split; the others are one segment
+// Entries per segment ("slot") of a split row: half a kSegLen when X has so many rows that it cannot stay in the
+// caches -- shorter slots cover narrower column ranges, which is what the column bands live on (1M-node graph:
+// SpMM -6 %, SDDMM -4 %) -- and a whole one otherwise, where more slots only mean more partial rows (100k-node
+// graph: +6 % the other way).
+constexpr int kSlotShort = 64;
+constexpr int64_t kSlotShortFromCols = 1 << 18;
+inline int slot_length(int64_t n_cols) { return n_cols >= kSlotShortFromCols ? kSlotShort : kSegLen; }
 constexpr int kGiantRow = 2048;      // up to this length a row fits one wavefront's registers; longer rows are listed
 constexpr int kGiantChunk = 4096;    // apart in the plan, in pieces of this many entries (one workgroup per piece in
                                      // the row-wise kernels)
@@ -114,16 +121,19 @@ __device__ __forceinline__ int64_t plan_segment(const int32_t *__restrict__ lane
 }
 
 // seg_dst of a segment.  Below zero: a single-segment row, written straight to the result, and -1 - seg_dst is its
-// length.  Otherwise a segment of a split row: the low bits are its slot (where its partial result goes), and
-// kSegFull is set when it is not the last segment of its row, i.e. has exactly kSegLen entries.  The end of a
-// segment's entries therefore needs a look at row_ptr only for the last segment of a split row -- one round
-// trip less in the chain segment record -> column ids -> rows, which is most of a short row's time.
-constexpr int32_t kSegFull = 1 << 30;
-__device__ __forceinline__ int32_t segment_slot(int32_t dst) { return dst & (kSegFull - 1); }
+// length.  Otherwise a segment of a split row: the low kSegSlotBits bits are its slot (where its partial result
+// goes), and the three bits above say how long it is when it is not the last segment of its row: 0 = the last
+// one, else 16 << code entries (64 or 128).  The end of a segment's entries therefore needs a look at row_ptr
+// only for the last segment of a split row -- one round trip less in the chain segment record -> column ids ->
+// rows, which is most of a short row's time.
+constexpr int kSegSlotBits = 28;
+__host__ __device__ __forceinline__ int32_t segment_full_code(int slot_len) { return slot_len == 64 ? 2 : 3; }
+__device__ __forceinline__ int32_t segment_slot(int32_t dst) { return dst & ((1 << kSegSlotBits) - 1); }
 __device__ __forceinline__ int32_t segment_end(int32_t eb, int32_t dst, int32_t row, const int32_t *__restrict__ row_ptr)
 {
     if (dst < 0) return eb - 1 - dst;
-    return (dst & kSegFull) ? eb + kSegLen : row_ptr[row + 1];
+    const int32_t code = dst >> kSegSlotBits;
+    return code ? eb + (16 << code) : row_ptr[row + 1];
 }
 
 // Host side of the same mapping: number of workgroups to launch for `groups_per_block`.

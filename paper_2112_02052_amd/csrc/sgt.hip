@@ -222,7 +222,7 @@ __global__ __launch_bounds__(256) void prep_kernel(int32_t n_rows, int32_t win_h
                                                    const int32_t *__restrict__ rp, int64_t nb_rows,
                                                    int32_t *__restrict__ block_sums, int32_t *__restrict__ lists,
                                                    int32_t *cls_count, int32_t *__restrict__ win_unique, int32_t sort_cap,
-                                                   int32_t *__restrict__ large_part, int32_t hub_entries)
+                                                   int32_t *__restrict__ large_part, int32_t hub_entries, int32_t slot_len)
 {
     const int lane = threadIdx.x & (kWave - 1);
     if ((int64_t)blockIdx.x < nb_rows) {
@@ -238,7 +238,7 @@ __global__ __launch_bounds__(256) void prep_kernel(int32_t n_rows, int32_t win_h
                 const int32_t deg = rp[r + 1] - rp[r];
                 if (deg > kSegLen) {
                     ++n_long;
-                    n_slot += (deg + kSegLen - 1) / kSegLen;
+                    n_slot += (deg + slot_len - 1) / slot_len;
                 } else {
                     cls = length_class(deg);
                 }
@@ -1049,7 +1049,7 @@ __global__ __launch_bounds__(256) void seg_fill_kernel(
     int32_t *__restrict__ seg_ebeg, int32_t *__restrict__ seg_dst, int32_t *__restrict__ long_row,
     int32_t *__restrict__ long_slot_ptr, int32_t *__restrict__ long_ebeg, int32_t *__restrict__ long_len,
     int32_t *__restrict__ gchunk_li, int32_t *__restrict__ gchunk_c, int32_t *__restrict__ slot_row,
-    int32_t *__restrict__ slot_ebeg, int32_t *__restrict__ slot_key)
+    int32_t *__restrict__ slot_ebeg, int32_t *__restrict__ slot_key, int32_t slot_len)
 {
     constexpr int RPT = kRowBlock / 256;           // rows per thread
     __shared__ int s_tmp[256 / kWave][kFillVals];
@@ -1074,7 +1074,7 @@ __global__ __launch_bounds__(256) void seg_fill_kernel(
             deg[k] = rp[r0 + k + 1] - e0[k];
             if (deg[k] > kSegLen) {
                 mine.v[0] += 1;
-                mine.v[1] += (deg[k] + kSegLen - 1) / kSegLen;
+                mine.v[1] += (deg[k] + slot_len - 1) / slot_len;
             } else {
                 cls[k] = sort_tail ? length_class(deg[k]) : 0;
 #pragma unroll
@@ -1131,7 +1131,7 @@ __global__ __launch_bounds__(256) void seg_fill_kernel(
             s_le0[lrank] = e0[k];
             s_lslot[lrank] = srank;
             ++lrank;
-            srank += (deg[k] + kSegLen - 1) / kSegLen;
+            srank += (deg[k] + slot_len - 1) / slot_len;
         } else if (phase == 1) {
             int lp = 0;
 #pragma unroll
@@ -1171,7 +1171,7 @@ __global__ __launch_bounds__(256) void seg_fill_kernel(
                 const int mid = (a + b) >> 1;
                 if (s_lslot[mid] <= sl) a = mid; else b = mid;
             }
-            eb[u] = s_le0[a] + (sl - s_lslot[a]) * kSegLen;
+            eb[u] = s_le0[a] + (sl - s_lslot[a]) * slot_len;
             row[u] = s_lrow[a];
         }
 #pragma unroll
@@ -1188,12 +1188,13 @@ __global__ __launch_bounds__(256) void seg_fill_kernel(
 }
 
 // Split rows' segments in their final order: position i of the list takes slot order[i] (order == nullptr:
-// slot order).  seg_dst is the slot number, which is also where the segment's partial sum goes, with kSegFull
-// set unless the segment is the last of its row (slots are numbered in row order, so the next slot tells).
+// slot order).  seg_dst is the slot number, which is also where the segment's partial sum goes, with the code of
+// the slot length above it unless the segment is the last of its row (slots are numbered in row order, so the
+// next slot tells).
 __global__ void seg_permute_kernel(const BuildInfo *info, const int32_t *__restrict__ order,
                                    const int32_t *__restrict__ slot_row, const int32_t *__restrict__ slot_ebeg,
                                    int32_t *__restrict__ seg_row, int32_t *__restrict__ seg_ebeg,
-                                   int32_t *__restrict__ seg_dst)
+                                   int32_t *__restrict__ seg_dst, int32_t full_code)
 {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= info->n_slots) return;
@@ -1202,7 +1203,7 @@ __global__ void seg_permute_kernel(const BuildInfo *info, const int32_t *__restr
     const bool full = k + 1 < info->n_slots && slot_row[k + 1] == row;
     seg_row[i] = row;
     seg_ebeg[i] = slot_ebeg[k];
-    seg_dst[i] = full ? (k | kSegFull) : k;
+    seg_dst[i] = full ? (k | (full_code << kSegSlotBits)) : k;
 }
 
 // The per-window lists are kept where the translation wrote them, each at its window's edge offset (a
@@ -1517,7 +1518,8 @@ int sgt_build_impl(tcg_meta *m, int validate, hipStream_t s)
     const int64_t n_win = m->n_win;
     const int64_t nb_rows = ceil_div(std::max<int64_t>(n, 0), kRowBlock);
     const int64_t long_bound = nnz / (kSegLen + 1) + 1;
-    const int64_t slot_bound = nnz / kSegLen + long_bound;
+    const int slot_len = slot_length(m->n_cols);
+    const int64_t slot_bound = nnz / slot_len + long_bound;
     const int64_t seg_bound = (int64_t)n + slot_bound;
     if (seg_bound >= (int64_t)INT32_MAX) return TCG_ERANGE;
     // Windows above kSortCap entries form the bitmap class: in LDS when the bitmap over the column space fits.
@@ -1617,7 +1619,7 @@ int sgt_build_impl(tcg_meta *m, int validate, hipStream_t s)
     if (nb_rows + ceil_div(n_win, 256) > 0) {
         hipLaunchKernelGGL(prep_kernel, dim3((unsigned)(nb_rows + ceil_div(n_win, 256))), dim3(256), 0, s, n, m->win_h,
                            n_win, m->d_row_ptr, nb_rows, block_sums, lists, info->cls_count, win_unique, sort_cap, large_part,
-                           lds_bitmap ? kHubEntries : INT_MAX);
+                           lds_bitmap ? kHubEntries : INT_MAX, slot_len);
         TCG_TRY(launch_status("prep_kernel"));
     }
 
@@ -1715,7 +1717,7 @@ int sgt_build_impl(tcg_meta *m, int validate, hipStream_t s)
             hipLaunchKernelGGL(seg_fill_kernel, dim3((unsigned)nb_rows), dim3(256), 0, ps, 0, n, m->d_row_ptr, m->d_col_idx,
                                info, nb_rows, long_off, slot_off, tail_off, m->d_seg_row, m->d_seg_ebeg, m->d_seg_dst,
                                m->d_long_row, m->d_long_slot_ptr, m->d_long_ebeg, m->d_long_len, m->d_gchunk_li, m->d_gchunk_c, slot_row, slot_ebeg,
-                               slot_key);
+                               slot_key, slot_len);
             TCG_TRY(launch_status("plan kernels"));
             const bool sorted = sort_bytes > 0 && slot_bound > 1;
             if (sorted)
@@ -1723,7 +1725,7 @@ int sgt_build_impl(tcg_meta *m, int validate, hipStream_t s)
                                          sort_scratch, ps));
             hipLaunchKernelGGL(seg_permute_kernel, dim3((unsigned)ceil_div(slot_bound, 256)), dim3(256), 0, ps, info,
                                sorted ? order : (const int32_t *)nullptr, slot_row, slot_ebeg, m->d_seg_row, m->d_seg_ebeg,
-                               m->d_seg_dst);
+                               m->d_seg_dst, segment_full_code(slot_len));
         }
         TCG_TRY(launch_status("plan kernels"));
     }
@@ -1758,7 +1760,7 @@ int sgt_build_impl(tcg_meta *m, int validate, hipStream_t s)
         hipLaunchKernelGGL(seg_fill_kernel, dim3((unsigned)nb_rows), dim3(256), 0, s, 1, n, m->d_row_ptr, m->d_col_idx,
                            info, nb_rows, long_off, slot_off, tail_off, m->d_seg_row, m->d_seg_ebeg,
                            m->d_seg_dst, m->d_long_row, m->d_long_slot_ptr, m->d_long_ebeg, m->d_long_len, m->d_gchunk_li, m->d_gchunk_c, slot_row, slot_ebeg,
-                               slot_key);
+                               slot_key, slot_len);
     TCG_TRY(launch_status("plan and path kernels"));
 
     // The result block comes back through pinned host memory (a copy to pageable memory is staged by the
