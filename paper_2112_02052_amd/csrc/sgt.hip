@@ -174,6 +174,7 @@ constexpr int kSortCap = 4096;            // largest window that is sorted
 constexpr int kLdsBitmapFrom = 1024;      // ... when the bitmap class works in LDS
 constexpr int kHubEntries = 16384;        // LDS bitmap class: a window with more entries is listed in several parts,
 constexpr int kHubMaxParts = 8;
+constexpr int kSlotSharers = 8;                     // workgroups per row block in seg_fill_kernel's first phase (large graphs)
 constexpr int64_t kForkMinEntries = 1 << 20;       // a translation of fewer entries runs on one stream           // one per kHubEntries entries up to this many (see the kernel)
 
 __device__ __forceinline__ int window_class(int32_t cnt, int32_t sort_cap)
@@ -1113,13 +1114,15 @@ __global__ __launch_bounds__(256) void seg_fill_kernel(
         if (r0 + k >= n_rows) continue;
         if (cls[k] < 0) {
             if (phase != 0) continue;
-            long_row[long_base + lrank] = (int32_t)(r0 + k);
-            long_slot_ptr[long_base + lrank] = slot_base + srank;
-            long_ebeg[long_base + lrank] = e0[k];
-            long_len[long_base + lrank] = deg[k];
+            if (blockIdx.y == 0) {
+                long_row[long_base + lrank] = (int32_t)(r0 + k);
+                long_slot_ptr[long_base + lrank] = slot_base + srank;
+                long_ebeg[long_base + lrank] = e0[k];
+                long_len[long_base + lrank] = deg[k];
+            }
             // the few very long rows are listed apart, cut into pieces of kGiantChunk entries (the pieces of a row
             // are consecutive; the rows come in any order: the list only says who works on what)
-            if (deg[k] > kGiantRow) {
+            if (blockIdx.y == 0 && deg[k] > kGiantRow) {
                 const int32_t pieces = (deg[k] + kGiantChunk - 1) / kGiantChunk;
                 const int32_t at = atomicAdd(&info->n_gchunks, pieces);
                 for (int32_t c = 0; c < pieces; ++c) {
@@ -1156,9 +1159,10 @@ __global__ __launch_bounds__(256) void seg_fill_kernel(
         seg_ebeg[p] = s_te0[i];
         seg_dst[p] = -1 - s_tdeg[i];     // below zero: written straight to the result; carries the row's length
     }
-    // the slots of the block's split rows: four per thread and step, their start columns gathered together (the
-    // block that holds the hub rows of a power-law graph has thousands of slots)
-    for (int32_t s0 = threadIdx.x; phase == 0 && s0 < n_lsegs; s0 += 4 * 256) {
+    // the slots of the block's split rows: four per thread and step, their start columns gathered together.  The
+    // block that holds the hub rows of a power-law graph has 10^5 slots, so large graphs launch the first phase
+    // with several workgroups per row block (gridDim.y), which share the block's slots in turns of 1024.
+    for (int32_t s0 = threadIdx.x + 4 * 256 * blockIdx.y; phase == 0 && s0 < n_lsegs; s0 += 4 * 256 * gridDim.y) {
         int32_t eb[4], row[4];
         uint32_t col[4];
 #pragma unroll
@@ -1714,7 +1718,7 @@ int sgt_build_impl(tcg_meta *m, int validate, hipStream_t s)
                            (const int32_t *)nullptr, (int32_t *)nullptr, (int32_t *)nullptr, (int64_t)0,
                            path_args(m, TCG_POLICY_AUTO, kDefaultMinReuse));
         if (nb_rows > 0) {
-            hipLaunchKernelGGL(seg_fill_kernel, dim3((unsigned)nb_rows), dim3(256), 0, ps, 0, n, m->d_row_ptr, m->d_col_idx,
+            hipLaunchKernelGGL(seg_fill_kernel, dim3((unsigned)nb_rows, forked ? kSlotSharers : 1), dim3(256), 0, ps, 0, n, m->d_row_ptr, m->d_col_idx,
                                info, nb_rows, long_off, slot_off, tail_off, m->d_seg_row, m->d_seg_ebeg, m->d_seg_dst,
                                m->d_long_row, m->d_long_slot_ptr, m->d_long_ebeg, m->d_long_len, m->d_gchunk_li, m->d_gchunk_c, slot_row, slot_ebeg,
                                slot_key, slot_len);
