@@ -138,13 +138,11 @@ __global__ __launch_bounds__(kBlock) void spmm_gather_kernel(
 #pragma unroll
             for (int k = 0; k < VEC; k += 4)
                 stream_store(p + k, acc[c][k], acc[c][k + 1], acc[c][k + 2], acc[c][k + 3]);   // like Y: not in L2's way
-        } else if (y_vec) {
-            float *p = static_cast<float *>(Y) + (int64_t)row * ldy + d0;
-#pragma unroll
-            for (int k = 0; k < VEC; k += 4) stream_store(p + k, acc[c][k], acc[c][k + 1], acc[c][k + 2], acc[c][k + 3]);
         } else {
 #pragma unroll
-            for (int k = 0; k < VEC; ++k) store_elem(Y, (int64_t)row * ldy + d0 + k, y_dt, acc[c][k]);
+            for (int k = 0; k < VEC; k += 4)
+                store4(Y, y_dt, (int64_t)row * ldy + d0 + k, make_float4(acc[c][k], acc[c][k + 1], acc[c][k + 2], acc[c][k + 3]),
+                       y_vec);
         }
     }
 }
@@ -278,7 +276,7 @@ __global__ __launch_bounds__(kBlock) void spmm_gather_generic_kernel(
 __global__ __launch_bounds__(kBlock) void spmm_reduce_long_kernel(
     int64_t n_long, const int32_t *__restrict__ long_row, const int32_t *__restrict__ long_slot_ptr,
     const float *__restrict__ partial, int64_t partial_ld, int32_t D, void *__restrict__ Y, int y_dt,
-    int64_t ldy, const uint8_t *__restrict__ win_path, int32_t win_h, int tile_mask)
+    int64_t ldy, const uint8_t *__restrict__ win_path, int32_t win_h, int tile_mask, int y_vec)
 {
     __shared__ float4 s_part[kBlock];
     const int64_t li = blockIdx.x;
@@ -325,11 +323,7 @@ __global__ __launch_bounds__(kBlock) void spmm_reduce_long_kernel(
                 t.z += v.z;
                 t.w += v.w;
             }
-            const int64_t o = (int64_t)row * ldy + 4 * c;
-            store_elem(Y, o, y_dt, t.x);
-            store_elem(Y, o + 1, y_dt, t.y);
-            store_elem(Y, o + 2, y_dt, t.z);
-            store_elem(Y, o + 3, y_dt, t.w);
+            store4(Y, y_dt, (int64_t)row * ldy + 4 * c, t, y_vec);
         }
         return;
     }
@@ -369,7 +363,7 @@ void launch_gather(const GatherArgs &a, int32_t n_chunks)
     const tcg_meta *m = a.m;
     const int gpb = kBlock / G;
     const unsigned grid = (unsigned)plan_grid(m->h_lane_tab, gpb);
-    const int y_vec = a.y_dt == TCG_F32 && (a.ldy & 3) == 0 && (reinterpret_cast<uintptr_t>(a.Y) & 15) == 0;
+    const int y_vec = (a.ldy & 3) == 0 && reinterpret_cast<uintptr_t>(a.Y) % (a.y_dt == TCG_F32 ? 16 : 8) == 0;
     hipLaunchKernelGGL((spmm_gather_kernel<DT, G, NCH, HAS_W, UNROLL>), dim3(grid), dim3(kBlock), 0, a.s,
                        m->d_lane_tab, m->d_seg_row, m->d_seg_ebeg, m->d_seg_dst, m->d_row_ptr, m->d_col_idx, a.w,
                        static_cast<const char *>(a.X), a.ldx * Elem<DT>::BYTES, n_chunks, a.D, a.Y, a.y_dt,
@@ -578,7 +572,8 @@ int spmm_impl(tcg_meta *m, const void *d_X, tcg_dtype x_dt, int32_t D, int64_t l
     if (m->n_long > 0) {
         hipLaunchKernelGGL(spmm_reduce_long_kernel, dim3((unsigned)m->n_long), dim3(kBlock), 0, s, m->n_long,
                            m->d_long_row, m->d_long_slot_ptr, partial, (int64_t)D, D, d_Y, (int)y_dt, ldy,
-                           win_path, m->win_h, tile_mask);
+                           win_path, m->win_h, tile_mask,
+                           (int)((ldy & 3) == 0 && reinterpret_cast<uintptr_t>(d_Y) % (y_dt == TCG_F32 ? 16 : 8) == 0));
         TCG_TRY(launch_status("spmm_reduce_long_kernel"));
     }
     return TCG_OK;

@@ -90,28 +90,6 @@ __device__ __forceinline__ f32x4 mfma16k16(const uint2 &a, const uint2 &b, f32x4
     }
 }
 
-// Four consecutive outputs of a row: one 16-byte (fp32) or 8-byte (16-bit) store when aligned, else scalars.
-__device__ __forceinline__ void store4(void *Y, int y_dt, int64_t o, const float4 &v, bool y_vec)
-{
-    if (y_dt == TCG_F32) {
-        float *y = static_cast<float *>(Y) + o;
-        if (y_vec) stream_store(y, v.x, v.y, v.z, v.w);
-        else { y[0] = v.x; y[1] = v.y; y[2] = v.z; y[3] = v.w; }
-    } else {
-        uint16_t *y = static_cast<uint16_t *>(Y) + o;
-        uint2 pk;
-        if (y_dt == TCG_BF16) {
-            pk.x = (uint32_t)f32_to_bf16_bits(v.x) | ((uint32_t)f32_to_bf16_bits(v.y) << 16);
-            pk.y = (uint32_t)f32_to_bf16_bits(v.z) | ((uint32_t)f32_to_bf16_bits(v.w) << 16);
-        } else {
-            pk.x = (uint32_t)__half_as_ushort(__float2half_rn(v.x)) | ((uint32_t)__half_as_ushort(__float2half_rn(v.y)) << 16);
-            pk.y = (uint32_t)__half_as_ushort(__float2half_rn(v.z)) | ((uint32_t)__half_as_ushort(__float2half_rn(v.w)) << 16);
-        }
-        if (y_vec) stream_store(y, pk.x, pk.y);
-        else { y[0] = (uint16_t)pk.x; y[1] = (uint16_t)(pk.x >> 16); y[2] = (uint16_t)pk.y; y[3] = (uint16_t)(pk.y >> 16); }
-    }
-}
-
 // NS: 16-column slices of D per wavefront; a window with D > 16 * NS is shared by n_dparts wavefronts.
 // FULL_A = false serves the windows of class kTileFew (at most kTileFewEdges edges, kept in registers;
 // the 16 x KW slice of the condensed adjacency is rebuilt for every chunk).  FULL_A = true serves class

@@ -619,6 +619,30 @@ def test_spmm_bf16_output():
         run_spmm_case(c["csr"], c["X"], "bf16", None, policy, 2.0 ** -8, y_dtype=torch.bfloat16)
 
 
+@pytest.mark.parametrize("x_dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("y_dtype", [torch.bfloat16, torch.float16])
+def test_spmm_gather_sixteen_bit_output(x_dtype, y_dtype):
+    """Rows with and without split segments (hubs of an R-MAT graph) written as 16-bit values: packed stores
+    when the output rows are 8-byte aligned, scalar ones for a view that starts one element later."""
+    c = W.make_config(4, n=6000, d=64)
+    g = c["csr"]
+    X = W.round_to_bf16(c["X"]) if x_dtype == "bf16" else c["X"]
+    tol = 2.0 ** -8 if y_dtype == torch.bfloat16 else 2.0 ** -10
+    stats = run_spmm_case(g, X, x_dtype, None, tcg.POLICY_GATHER, tol, y_dtype=y_dtype)
+    assert stats["n_long_rows"] > 0
+    rp, ci = upload_csr(g)
+    meta = tcg.sgt_build(rp, ci, 16, 8)
+    tcg.sgt_set_policy(meta, tcg.POLICY_GATHER)
+    big = torch.full((g.n_rows, 64 + 4), float("nan"), dtype=y_dtype, device=dev())
+    Y = big[:, 1:65]                                       # rows start 2 bytes off an 8-byte boundary
+    tcg.spmm(meta, upload_x(X, x_dtype), None, Y=Y)
+    torch.cuda.synchronize()
+    meta.free()
+    ref = oracle.spmm(g.row_ptr, g.col_idx, X, None)
+    assert norm_err(Y.to(torch.float32).cpu().numpy(), ref) <= tol
+    assert torch.isnan(big[:, 0]).all() and torch.isnan(big[:, 65:]).all()
+
+
 def test_spmm_is_deterministic():
     c = W.make_config(4, n=20000, d=64)
     rp, ci = upload_csr(c["csr"])
