@@ -45,7 +45,8 @@ __global__ __launch_bounds__(kBlock) void attn_fused_kernel(
         for (int c = 0; c < NCH; ++c) {
             const int chunk = lane + c * G;
             uint4 raw = make_uint4(0, 0, 0, 0);
-            if (chunk < n_chunks) raw = *reinterpret_cast<const uint4 *>(xr + (int64_t)chunk * 16);
+            if (chunk < n_chunks && eb < ee)           // a row without entries only has its zeros written
+                raw = *reinterpret_cast<const uint4 *>(xr + (int64_t)chunk * 16);
             unpack16<DT>(raw, xi[c]);
 #pragma unroll
             for (int k = 0; k < VEC; ++k) acc[c][k] = 0.f;

@@ -47,6 +47,7 @@ __global__ __launch_bounds__(kBlock) void sddmm_gather_kernel(
     const int32_t eb = seg_ebeg[seg];
     const int32_t ee = segment_end(eb, seg_dst[seg], row, row_ptr);
 
+    if (eb >= ee) return;                  // empty row: nothing to write, so its P row is not read either
     float xi[NCH][VEC];
     {
         const char *xr = P + (int64_t)row * ldp_bytes;
@@ -59,7 +60,6 @@ __global__ __launch_bounds__(kBlock) void sddmm_gather_kernel(
         }
     }
 
-    if (eb >= ee) return;                  // empty row: nothing to write
     // Ids are read from a clamped, valid position (no predicate, issued back to back) and the next
     // iteration's ids go out before this iteration's row loads, so one wait covers both.
     const int32_t last = ee - 1;
