@@ -150,6 +150,23 @@ __device__ __forceinline__ void store4(void *Y, int y_dt, int64_t o, const float
     }
 }
 
+// Eight consecutive 16-bit outputs of a row as one 16-byte streaming store; p is 16-byte aligned.
+__device__ __forceinline__ void store8_16bit(uint16_t *p, int y_dt, const float (&v)[8])
+{
+    uint32_t w[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        if (y_dt == TCG_BF16)
+            w[i] = (uint32_t)f32_to_bf16_bits(v[2 * i]) | ((uint32_t)f32_to_bf16_bits(v[2 * i + 1]) << 16);
+        else
+            w[i] = (uint32_t)__half_as_ushort(__float2half_rn(v[2 * i])) |
+                   ((uint32_t)__half_as_ushort(__float2half_rn(v[2 * i + 1])) << 16);
+    }
+    typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+    const u32x4_t q = {w[0], w[1], w[2], w[3]};
+    __builtin_nontemporal_store(q, reinterpret_cast<u32x4_t *>(p));
+}
+
 // Sums UNROLL per-lane partials across the G lanes of a group.  On return, lane j (j < UNROLL,
 // position inside the group) holds the total of partial j -- if G >= UNROLL; otherwise every
 // lane holds all totals in p[].  Must be executed by all lanes of the group.
