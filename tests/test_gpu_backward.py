@@ -24,6 +24,8 @@ def asymmetric_graph(n_rows, n_cols, seed, max_deg=40):
 @pytest.mark.parametrize("make", [lambda: asymmetric_graph(300, 5000, 1), lambda: asymmetric_graph(5000, 300, 2),
                                   lambda: hub_graph(3000), lambda: W.make_config(4, n=40000, d=2)["csr"],
                                   lambda: W.make_config(3, n=17, d=2)["csr"],
+                                  lambda: asymmetric_graph(8193, 700, 3, max_deg=6),      # row search: stride 2
+                                  lambda: W.make_config(3, d=2)["csr"],                   # stride 13, empty rows
                                   lambda: csr_from_rows([[], [], []], 5), lambda: csr_from_rows([[2, 2, 0]], 3)])
 def test_csr_transpose_bit_exact(make):
     g = make()
