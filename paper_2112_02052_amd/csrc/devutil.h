@@ -1,6 +1,7 @@
 // Device-side helpers: 16-byte feature chunks of fp32 / bf16 / fp16 rows unpacked to fp32,
 // and fp32 -> storage-type conversion for outputs.
 #pragma once
+#include <type_traits>
 
 #include <hip/hip_runtime.h>
 #include <hip/hip_fp16.h>
@@ -165,6 +166,58 @@ __device__ __forceinline__ void store8_16bit(uint16_t *p, int y_dt, const float 
     typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
     const u32x4_t q = {w[0], w[1], w[2], w[3]};
     __builtin_nontemporal_store(q, reinterpret_cast<u32x4_t *>(p));
+}
+
+// The value that lane SRC of the caller's group of G lanes holds (SRC < G, both known at compile time), in every
+// lane of the group.  A group of 16 is a row of the data-parallel primitives, so the broadcast is one vector
+// instruction (row_newbcast) instead of a trip through the LDS crossbar (ds_bpermute), whose issue rate the
+// gather kernels' sixteen shuffles per step were measured to strain; a group of 8 takes two broadcasts and a
+// select.  As with __shfl, the lanes of a group must be active together.
+template <int G, int SRC>
+__device__ __forceinline__ int32_t group_lane(int32_t v)
+{
+    static_assert(SRC >= 0 && SRC < G, "source lane outside the group");
+    if constexpr (G == 16) {
+        return __builtin_amdgcn_update_dpp(0, v, 0x150 + SRC, 0xf, 0xf, false);
+    } else if constexpr (G == 8) {
+        const int32_t a = __builtin_amdgcn_update_dpp(0, v, 0x150 + SRC, 0xf, 0xf, false);
+        const int32_t b = __builtin_amdgcn_update_dpp(0, v, 0x150 + SRC + 8, 0xf, 0xf, false);
+        return (threadIdx.x & 8) ? b : a;
+    } else {
+        return __shfl(v, SRC, G);
+    }
+}
+
+// f(std::integral_constant<int, 0>{}), ..., f(std::integral_constant<int, N - 1>{}): a loop whose counter is a
+// compile-time constant inside the body.
+template <int N, int I = 0, typename F>
+__device__ __forceinline__ void static_for(F &&f)
+{
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for<N, I + 1>(f);
+    }
+}
+
+// The lanes of a group loaded a block of values together, lane l holding elements l, l + G, ... of the block in
+// m[0], m[1], ...; out[u] = element S * UNROLL + u, the u-th value of step S of the block.
+template <int G, int UNROLL, int PER, int S, int U = 0>
+__device__ __forceinline__ void block_ids(const int32_t (&m)[PER], int32_t (&out)[UNROLL])
+{
+    if constexpr (U < UNROLL) {
+        constexpr int Q = S * UNROLL + U;
+        out[U] = group_lane<G, Q % G>(m[Q / G]);
+        block_ids<G, UNROLL, PER, S, U + 1>(m, out);
+    }
+}
+template <int G, int UNROLL, int PER, int S, int U = 0>
+__device__ __forceinline__ void block_ids(const float (&m)[PER], float (&out)[UNROLL])
+{
+    if constexpr (U < UNROLL) {
+        constexpr int Q = S * UNROLL + U;
+        out[U] = __int_as_float(group_lane<G, Q % G>(__float_as_int(m[Q / G])));
+        block_ids<G, UNROLL, PER, S, U + 1>(m, out);
+    }
 }
 
 // Sums UNROLL per-lane partials across the G lanes of a group.  On return, lane j (j < UNROLL,

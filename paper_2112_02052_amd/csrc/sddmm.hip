@@ -60,98 +60,102 @@ __global__ __launch_bounds__(kBlock) void sddmm_gather_kernel(
         }
     }
 
-    // Ids are read from a clamped, valid position (no predicate, issued back to back) and the next
-    // iteration's ids go out before this iteration's row loads, so one wait covers both.
+    // Ids are read from clamped, valid positions (no predicate, issued back to back), a block of IDB entries -- a
+    // whole cache line of them -- at a time and once per lane group: lane l takes entries l, l + G, ... of the block
+    // and the values are handed round inside the group (every lane loading all of its step's ids costs more load
+    // instructions than narrow rows do; asked for step by step, eight at a time, a line of ids had left the L2
+    // again before the next step wanted it).  The next block's ids go out before this block's row loads.
     const int32_t last = ee - 1;
     const uint32_t ldx32 = (uint32_t)ldx_bytes;
-    // The ids of a step are loaded once per lane group (lane l takes entries l, l + G, ...) and handed round with
-    // shuffles: every lane loading all UNROLL of them costs more load instructions than narrow rows do.
-    constexpr int PER = (UNROLL + G - 1) / G;
+    constexpr int IDB = G <= 4 ? 16 : (UNROLL * 8 < (G > 32 ? 64 : 32) ? UNROLL * 8 : (G > 32 ? 64 : 32));
+    constexpr int PER = (IDB + G - 1) / G;
+    constexpr int STEPS = IDB / UNROLL;
     auto request = [&](int32_t e0, int32_t (&mc)[PER]) {
 #pragma unroll
         for (int k = 0; k < PER; ++k) mc[k] = col_idx[min(e0 + lane + k * G, last)];
     };
-    auto hand_round = [&](const int32_t (&mc)[PER], int32_t (&c)[UNROLL]) {
-#pragma unroll
-        for (int u = 0; u < UNROLL; ++u) c[u] = __shfl(mc[u / G], u % G, G);
-    };
-    int32_t cn[UNROLL];
-    {
-        int32_t mc[PER];
-        request(eb, mc);
-        hand_round(mc, cn);
-    }
+    int32_t mc[PER];
+    request(eb, mc);
 
-    for (int32_t e = eb; e < ee; e += UNROLL) {
+    for (int32_t e0 = eb; e0 < ee; e0 += IDB) {
         int32_t mc_next[PER];
-        request(e + UNROLL, mc_next);
-        // a later feature slab adds to what the earlier ones left (requested with the ids, ahead of the rows)
-        float prev = 0.f;
-        if constexpr (G >= UNROLL) {
-            if (accumulate && lane < UNROLL && e + lane < ee) prev = out[e + lane];
-        }
-        float p[UNROLL];
-        if constexpr (!ELEM) {
-            uint4 raw[UNROLL][NCH];
+        request(e0 + IDB, mc_next);
+        static_for<STEPS>([&](auto step) {
+            constexpr int S = decltype(step)::value;
+            const int32_t e = e0 + S * UNROLL;
+            if (e < ee) {
+                int32_t cn[UNROLL];
+                block_ids<G, UNROLL, PER, S>(mc, cn);
+                // a later feature slab adds to what the earlier ones left (requested ahead of the rows)
+                float prev = 0.f;
+                if constexpr (G >= UNROLL) {
+                    if (accumulate && lane < UNROLL && e + lane < ee) prev = out[e + lane];
+                }
+                float p[UNROLL];
+                if constexpr (!ELEM) {
+                    uint4 raw[UNROLL][NCH];
 #pragma unroll
-            for (int u = 0; u < UNROLL; ++u) {
-                const char *xr = X + (uint64_t)(uint32_t)cn[u] * ldx32;
+                    for (int u = 0; u < UNROLL; ++u) {
+                        const char *xr = X + (uint64_t)(uint32_t)cn[u] * ldx32;
 #pragma unroll
-                for (int c = 0; c < NCH; ++c) {
-                    int chunk = lane + c * G;
-                    raw[u][c] = make_uint4(0, 0, 0, 0);
-                    if (e + u < ee && chunk < n_chunks)
-                        raw[u][c] = *reinterpret_cast<const uint4 *>(xr + (uint32_t)chunk * 16u);
+                        for (int c = 0; c < NCH; ++c) {
+                            int chunk = lane + c * G;
+                            raw[u][c] = make_uint4(0, 0, 0, 0);
+                            if (e + u < ee && chunk < n_chunks)
+                                raw[u][c] = *reinterpret_cast<const uint4 *>(xr + (uint32_t)chunk * 16u);
+                        }
+                    }
+#pragma unroll
+                    for (int u = 0; u < UNROLL; ++u) {
+                        float a = 0.f;
+#pragma unroll
+                        for (int c = 0; c < NCH; ++c) {
+                            float v[VEC];
+                            unpack16<DT>(raw[u][c], v);
+#pragma unroll
+                            for (int k = 0; k < VEC; ++k) a = fmaf(xi[c][k], v[k], a);
+                        }
+                        p[u] = a;
+                    }
+                } else {
+                    float v[UNROLL][NCH][VEC];
+#pragma unroll
+                    for (int u = 0; u < UNROLL; ++u) {
+                        const char *xr = X + (int64_t)cn[u] * ldx_bytes;
+#pragma unroll
+                        for (int c = 0; c < NCH; ++c) {
+                            int chunk = lane + c * G;
+#pragma unroll
+                            for (int k = 0; k < VEC; ++k) v[u][c][k] = 0.f;
+                            if (e + u < ee && chunk < n_chunks) Pc::load(xr + (int64_t)chunk * Pc::BYTES, v[u][c]);
+                        }
+                    }
+#pragma unroll
+                    for (int u = 0; u < UNROLL; ++u) {
+                        float a = 0.f;
+#pragma unroll
+                        for (int c = 0; c < NCH; ++c)
+#pragma unroll
+                            for (int k = 0; k < VEC; ++k) a = fmaf(xi[c][k], v[u][c][k], a);
+                        p[u] = a;
+                    }
+                }
+                float r = group_reduce<G, UNROLL>(p, lane);
+                if constexpr (G >= UNROLL) {
+                    // streaming store: the scores are not read again by this launch and should not take the rows'
+                    // place in L2
+                    if (lane < UNROLL && e + lane < ee) __builtin_nontemporal_store(r + prev, &out[e + lane]);
+                } else {
+                    if (lane == 0) {
+#pragma unroll
+                        for (int u = 0; u < UNROLL; ++u)
+                            if (e + u < ee) out[e + u] = accumulate ? out[e + u] + p[u] : p[u];
+                    }
                 }
             }
-            hand_round(mc_next, cn);          // after the row loads have gone out
+        });
 #pragma unroll
-            for (int u = 0; u < UNROLL; ++u) {
-                float a = 0.f;
-#pragma unroll
-                for (int c = 0; c < NCH; ++c) {
-                    float v[VEC];
-                    unpack16<DT>(raw[u][c], v);
-#pragma unroll
-                    for (int k = 0; k < VEC; ++k) a = fmaf(xi[c][k], v[k], a);
-                }
-                p[u] = a;
-            }
-        } else {
-            float v[UNROLL][NCH][VEC];
-#pragma unroll
-            for (int u = 0; u < UNROLL; ++u) {
-                const char *xr = X + (int64_t)cn[u] * ldx_bytes;
-#pragma unroll
-                for (int c = 0; c < NCH; ++c) {
-                    int chunk = lane + c * G;
-#pragma unroll
-                    for (int k = 0; k < VEC; ++k) v[u][c][k] = 0.f;
-                    if (e + u < ee && chunk < n_chunks) Pc::load(xr + (int64_t)chunk * Pc::BYTES, v[u][c]);
-                }
-            }
-            hand_round(mc_next, cn);          // after the row loads have gone out
-#pragma unroll
-            for (int u = 0; u < UNROLL; ++u) {
-                float a = 0.f;
-#pragma unroll
-                for (int c = 0; c < NCH; ++c)
-#pragma unroll
-                    for (int k = 0; k < VEC; ++k) a = fmaf(xi[c][k], v[u][c][k], a);
-                p[u] = a;
-            }
-        }
-        float r = group_reduce<G, UNROLL>(p, lane);
-        if constexpr (G >= UNROLL) {
-            // streaming store: the scores are not read again by this launch and should not take the rows' place in L2
-            if (lane < UNROLL && e + lane < ee) __builtin_nontemporal_store(r + prev, &out[e + lane]);
-        } else {
-            if (lane == 0) {
-#pragma unroll
-                for (int u = 0; u < UNROLL; ++u)
-                    if (e + u < ee) out[e + u] = accumulate ? out[e + u] + p[u] : p[u];
-            }
-        }
+        for (int k = 0; k < PER; ++k) mc[k] = mc_next[k];
     }
 }
 

@@ -64,10 +64,16 @@ __global__ __launch_bounds__(kBlock) void spmm_gather_kernel(
         // no predicate and are issued back to back; only the row loads of a ragged tail are masked.
         const int32_t last = ee - 1;
         const uint32_t ldx32 = (uint32_t)ldx_bytes;
-        // The UNROLL ids (and edge values) of a step are loaded once per lane group -- lane l takes entries l,
-        // l + G, ... -- and handed round with shuffles: every lane loading all of them costs UNROLL load
-        // instructions per array and step, which for narrow rows is more than the rows themselves.
-        constexpr int PER = (UNROLL + G - 1) / G;
+        // Ids (and edge values) are loaded a block of IDB entries at a time, once per lane group -- lane l takes
+        // entries l, l + G, ... of the block -- and handed round inside the group: every lane loading all of
+        // its step's ids costs more load instructions than narrow rows do themselves.  A block is a whole cache
+        // line of ids requested in one go: asked for eight at a time, step by step, the line had left the L2
+        // again between two steps (the gathered rows turn the cache over every few microseconds) and was fetched
+        // up to four times -- 0.3 GB read per launch for the 76 MB of either array on the 1M-node graph.
+        // (Four-lane groups keep half a line when there are edge values too: the registers of a whole one cost more.)
+        constexpr int IDB = G <= 4 ? (HAS_W ? 16 : 32) : (UNROLL * 8 < (G > 32 ? 64 : 32) ? UNROLL * 8 : (G > 32 ? 64 : 32));
+        constexpr int PER = (IDB + G - 1) / G;
+        constexpr int STEPS = IDB / UNROLL;
         auto request = [&](int32_t e0, int32_t (&mc)[PER], float (&mw)[PER]) {
 #pragma unroll
             for (int k = 0; k < PER; ++k) {
@@ -76,54 +82,55 @@ __global__ __launch_bounds__(kBlock) void spmm_gather_kernel(
                 mw[k] = HAS_W ? w[en] : 1.f;
             }
         };
-        auto hand_round = [&](const int32_t (&mc)[PER], const float (&mw)[PER], int32_t (&c)[UNROLL], float (&wv)[UNROLL]) {
-#pragma unroll
-            for (int u = 0; u < UNROLL; ++u) {
-                c[u] = __shfl(mc[u / G], u % G, G);
-                wv[u] = HAS_W ? __shfl(mw[u / G], u % G, G) : 1.f;
-            }
-        };
-        int32_t cn[UNROLL];
-        float wn[UNROLL];
-        {
-            int32_t mc[PER];
-            float mw[PER];
-            request(eb, mc, mw);
-            hand_round(mc, mw, cn, wn);
-        }
-        for (int32_t e = eb; e < ee; e += UNROLL) {
-            // Next iteration's ids go out first: they are older than the row loads below, so the
-            // one wait for the rows also covers them and their latency hides under the rows'.
+        int32_t mc[PER];
+        float mw[PER];
+        request(eb, mc, mw);
+        for (int32_t e = eb; e < ee; e += IDB) {
+            // The next block's ids go out first: they are older than the row loads below, so a wait for rows
+            // also covers them and their latency hides under the rows'.
             int32_t mc_next[PER];
             float mw_next[PER];
-            request(e + UNROLL, mc_next, mw_next);
-            uint4 raw[UNROLL][NCH];
-            float wc[UNROLL];
+            request(e + IDB, mc_next, mw_next);
+            static_for<STEPS>([&](auto step) {
+                constexpr int S = decltype(step)::value;
+                const int32_t es = e + S * UNROLL;
+                if (es < ee) {
+                    int32_t cn[UNROLL];
+                    float wc[UNROLL];
+                    block_ids<G, UNROLL, PER, S>(mc, cn);
+                    if constexpr (HAS_W) block_ids<G, UNROLL, PER, S>(mw, wc);
+                    uint4 raw[UNROLL][NCH];
 #pragma unroll
-            for (int u = 0; u < UNROLL; ++u) {
-                wc[u] = (e + u < ee) ? wn[u] : 0.f;
-                const char *xr = X + (uint64_t)(uint32_t)cn[u] * ldx32;
+                    for (int u = 0; u < UNROLL; ++u) {
+                        if (!HAS_W || es + u >= ee) wc[u] = 0.f;
+                        const char *xr = X + (uint64_t)(uint32_t)cn[u] * ldx32;
 #pragma unroll
-                for (int c = 0; c < NCH; ++c) {
-                    const int chunk = lane + c * G;
-                    raw[u][c] = make_uint4(0, 0, 0, 0);
-                    if (e + u < ee && chunk < n_chunks)
-                        raw[u][c] = *reinterpret_cast<const uint4 *>(xr + (uint32_t)chunk * 16u);
-                }
-            }
-            hand_round(mc_next, mw_next, cn, wn);      // after the row loads have gone out
+                        for (int c = 0; c < NCH; ++c) {
+                            const int chunk = lane + c * G;
+                            raw[u][c] = make_uint4(0, 0, 0, 0);
+                            if (es + u < ee && chunk < n_chunks)
+                                raw[u][c] = *reinterpret_cast<const uint4 *>(xr + (uint32_t)chunk * 16u);
+                        }
+                    }
 #pragma unroll
-            for (int u = 0; u < UNROLL; ++u) {
+                    for (int u = 0; u < UNROLL; ++u) {
 #pragma unroll
-                for (int c = 0; c < NCH; ++c) {
-                    float v[VEC];
-                    unpack16<DT>(raw[u][c], v);   // masked-off loads left zeros: they add nothing
+                        for (int c = 0; c < NCH; ++c) {
+                            float v[VEC];
+                            unpack16<DT>(raw[u][c], v);   // masked-off loads left zeros: they add nothing
 #pragma unroll
-                    for (int k = 0; k < VEC; ++k) {
-                        if (HAS_W) acc[c][k] = fmaf(wc[u], v[k], acc[c][k]);
-                        else acc[c][k] += v[k];
+                            for (int k = 0; k < VEC; ++k) {
+                                if (HAS_W) acc[c][k] = fmaf(wc[u], v[k], acc[c][k]);
+                                else acc[c][k] += v[k];
+                            }
+                        }
                     }
                 }
+            });
+#pragma unroll
+            for (int k = 0; k < PER; ++k) {
+                mc[k] = mc_next[k];
+                mw[k] = mw_next[k];
             }
         }
     }
