@@ -80,17 +80,25 @@ __global__ __launch_bounds__(kBlock) void sddmm_gather_kernel(
     for (int32_t e0 = eb; e0 < ee; e0 += IDB) {
         int32_t mc_next[PER];
         request(e0 + IDB, mc_next);
+        // The block's scores are collected in the layout of its ids (lane l: entries l, l + G, ...) and leave
+        // together at its end, as whole lines where the block covers them; what an earlier feature slab left is
+        // read the same way, ahead of the rows.  (Eight scores at a time: 32-byte stores that reached memory
+        // one by one, and a line of the earlier slab's scores read once per step.)
+        float res[PER], prev[PER];
+#pragma unroll
+        for (int k = 0; k < PER; ++k) {
+            res[k] = 0.f;
+            prev[k] = 0.f;
+            if constexpr (G >= UNROLL) {
+                if (accumulate && lane + k * G < IDB && e0 + lane + k * G < ee) prev[k] = out[e0 + lane + k * G];
+            }
+        }
         static_for<STEPS>([&](auto step) {
             constexpr int S = decltype(step)::value;
             const int32_t e = e0 + S * UNROLL;
             if (e < ee) {
                 int32_t cn[UNROLL];
                 block_ids<G, UNROLL, PER, S>(mc, cn);
-                // a later feature slab adds to what the earlier ones left (requested ahead of the rows)
-                float prev = 0.f;
-                if constexpr (G >= UNROLL) {
-                    if (accumulate && lane < UNROLL && e + lane < ee) prev = out[e + lane];
-                }
                 float p[UNROLL];
                 if constexpr (!ELEM) {
                     uint4 raw[UNROLL][NCH];
@@ -142,9 +150,11 @@ __global__ __launch_bounds__(kBlock) void sddmm_gather_kernel(
                 }
                 float r = group_reduce<G, UNROLL>(p, lane);
                 if constexpr (G >= UNROLL) {
-                    // streaming store: the scores are not read again by this launch and should not take the rows'
-                    // place in L2
-                    if (lane < UNROLL && e + lane < ee) __builtin_nontemporal_store(r + prev, &out[e + lane]);
+                    // lane j < UNROLL holds the score of entry S * UNROLL + j of the block, whose place is lane
+                    // (S * UNROLL + j) % G, element (S * UNROLL + j) / G
+                    constexpr int FIRST = (S * UNROLL) % G;
+                    const float moved = FIRST == 0 ? r : __shfl(r, lane - FIRST, G);
+                    if (lane >= FIRST && lane < FIRST + UNROLL) res[(S * UNROLL) / G] = moved;
                 } else {
                     if (lane == 0) {
 #pragma unroll
@@ -154,6 +164,13 @@ __global__ __launch_bounds__(kBlock) void sddmm_gather_kernel(
                 }
             }
         });
+        if constexpr (G >= UNROLL) {
+            // streaming stores: the scores are not read again by this launch and should not take the rows' place in L2
+#pragma unroll
+            for (int k = 0; k < PER; ++k)
+                if (lane + k * G < IDB && e0 + lane + k * G < ee)       // (a group wider than the block: its upper lanes idle)
+                    __builtin_nontemporal_store(res[k] + prev[k], &out[e0 + lane + k * G]);
+        }
 #pragma unroll
         for (int k = 0; k < PER; ++k) mc[k] = mc_next[k];
     }
