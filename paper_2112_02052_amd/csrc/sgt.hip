@@ -1054,7 +1054,12 @@ __global__ __launch_bounds__(256) void seg_fill_kernel(
 {
     constexpr int RPT = kRowBlock / 256;           // rows per thread
     __shared__ int s_tmp[256 / kWave][kFillVals];
-    __shared__ int32_t s_lrow[kRowBlock], s_le0[kRowBlock], s_lslot[kRowBlock + 1];
+    // One buffer for both phases (the first keeps the block's split rows in it, the second its single-segment rows):
+    // with 12 KB the workgroup fits beside the bitmap kernel, whose workgroups leave under 20 KB of a compute
+    // unit's LDS free for the whole of their run -- with 24 KB this kernel waited for them to end.
+    __shared__ int32_t s_rows[3 * kRowBlock + 1];
+    int32_t *const s_lrow = s_rows, *const s_le0 = s_rows + kRowBlock, *const s_lslot = s_rows + 2 * kRowBlock;
+    int32_t *const s_trow = s_rows, *const s_te0 = s_rows + kRowBlock, *const s_tdeg = s_rows + 2 * kRowBlock;
     const int sort_tail = phase == 1 ? info->sort_tail : 0;
     const int32_t n_slots = info->n_slots;
     const int32_t long_base = long_off[blockIdx.x], slot_base = slot_off[blockIdx.x];
@@ -1089,7 +1094,6 @@ __global__ __launch_bounds__(256) void seg_fill_kernel(
 
     // Single-segment rows are put in (class, row) order in LDS first, so that the workgroup writes its piece
     // of every class as one contiguous run.
-    __shared__ int32_t s_trow[kRowBlock], s_te0[kRowBlock], s_tdeg[kRowBlock];
     __shared__ int s_cstart[kTailClasses + 1];
     int cstart[kTailClasses];
     {
@@ -1146,7 +1150,7 @@ __global__ __launch_bounds__(256) void seg_fill_kernel(
         }
     }
     const int n_lrows = total.v[0], n_lsegs = total.v[1];
-    if (threadIdx.x == 0) s_lslot[n_lrows] = n_lsegs;
+    if (threadIdx.x == 0 && phase == 0) s_lslot[n_lrows] = n_lsegs;
     __syncthreads();
     for (int i = threadIdx.x; phase == 1 && i < s_cstart[kTailClasses]; i += 256) {
         int c = 0;
