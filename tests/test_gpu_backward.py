@@ -14,6 +14,18 @@ from test_gpu_parity import csr_from_rows, hub_graph
 pytestmark = pytest.mark.gpu
 
 
+def hub_and_gaps_graph():
+    """A row of 10,000 entries (several whole entry tiles of the transpose's row search lie inside it), a run of
+    6,000 rows without entries, and short rows around them."""
+    rng = np.random.default_rng(11)
+    n_cols = 20000
+    rows = [rng.choice(n_cols, size=int(rng.integers(0, 4)), replace=False) for _ in range(300)]
+    rows.append(rng.choice(n_cols, size=10000, replace=False))
+    rows += [np.zeros(0, dtype=np.int64)] * 6000
+    rows += [rng.choice(n_cols, size=int(rng.integers(1, 12)), replace=False) for _ in range(900)]
+    return csr_from_rows(rows, n_cols)
+
+
 def asymmetric_graph(n_rows, n_cols, seed, max_deg=40):
     rng = np.random.default_rng(seed)
     rows = [rng.choice(n_cols, size=int(rng.integers(0, max_deg)), replace=False) for _ in range(n_rows)]
@@ -24,8 +36,8 @@ def asymmetric_graph(n_rows, n_cols, seed, max_deg=40):
 @pytest.mark.parametrize("make", [lambda: asymmetric_graph(300, 5000, 1), lambda: asymmetric_graph(5000, 300, 2),
                                   lambda: hub_graph(3000), lambda: W.make_config(4, n=40000, d=2)["csr"],
                                   lambda: W.make_config(3, n=17, d=2)["csr"],
-                                  lambda: asymmetric_graph(8193, 700, 3, max_deg=6),      # row search: stride 2
-                                  lambda: W.make_config(3, d=2)["csr"],                   # stride 13, empty rows
+                                  lambda: asymmetric_graph(8193, 700, 3, max_deg=6),
+                                  lambda: W.make_config(3, d=2)["csr"], hub_and_gaps_graph,
                                   lambda: csr_from_rows([[], [], []], 5), lambda: csr_from_rows([[2, 2, 0]], 3)])
 def test_csr_transpose_bit_exact(make):
     g = make()
