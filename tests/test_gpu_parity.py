@@ -361,6 +361,19 @@ def test_spmm_fp32_gather(cfg, n, D):
     run_spmm_case(c["csr"], c["X"], "f32", None, tcg.POLICY_GATHER, TOL_F32)
 
 
+@pytest.mark.parametrize("D", [4, 8, 16])
+def test_spmm_narrow_result_of_split_rows(D):
+    """Split rows whose partial sums are added by the one-wavefront-per-row kernel (4, 8, 16 columns), with and
+    without edge values, fp32 and 16-bit results."""
+    g = hub_graph()
+    X = W.features_normal(g.n_cols, D, 5)
+    w = np.random.default_rng(3).standard_normal(g.nnz).astype(np.float32)
+    stats = run_spmm_case(g, X, "f32", w, tcg.POLICY_GATHER, TOL_F32)
+    assert stats["n_long_rows"] > 0
+    run_spmm_case(g, X, "f32", None, tcg.POLICY_GATHER, TOL_F32)
+    run_spmm_case(g, X, "f32", None, tcg.POLICY_GATHER, 2.0 ** -8, y_dtype=torch.bfloat16)
+
+
 def test_spmm_fp32_strided_and_other_window_heights():
     c = W.make_config(4, n=6000, d=64)
     run_spmm_case(c["csr"], c["X"], "f32", None, tcg.POLICY_AUTO, TOL_F32, pad=8)
