@@ -307,8 +307,9 @@ __global__ __launch_bounds__(kBlock) void spmm_reduce_long_kernel(
     if (win_path != nullptr && ((tile_mask >> win_path[row / win_h]) & 1)) return;
     const int32_t s0 = long_slot_ptr[li], s1 = long_slot_ptr[li + 1];
     const int32_t c4 = D / 4;                                  // threads per partial row
-    if (D % 4 == 0 && c4 <= kBlock) {
-        const int32_t nsg = kBlock / c4;                       // groups of threads, each on its own partials
+    const int32_t n_threads = blockDim.x;                      // kBlock, or half of it for rows of up to 64 columns
+    if (D % 4 == 0 && c4 <= n_threads) {
+        const int32_t nsg = n_threads / c4;                       // groups of threads, each on its own partials
         const int32_t c = threadIdx.x % c4, sg = threadIdx.x / c4;
         float4 a[4];
 #pragma unroll
@@ -350,7 +351,7 @@ __global__ __launch_bounds__(kBlock) void spmm_reduce_long_kernel(
         }
         return;
     }
-    for (int32_t d = threadIdx.x; d < D; d += kBlock) {
+    for (int32_t d = threadIdx.x; d < D; d += n_threads) {
         float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
         int32_t s = s0;
         for (; s + 4 <= s1; s += 4) {
@@ -645,7 +646,7 @@ int spmm_impl(tcg_meta *m, const void *d_X, tcg_dtype x_dt, int32_t D, int64_t l
                                0, s, m->n_long, m->d_long_row, m->d_long_slot_ptr, partial, (int64_t)D, c4_log2, d_Y,
                                (int)y_dt, ldy, win_path, m->win_h, tile_mask, y_vec);
         } else {
-            hipLaunchKernelGGL(spmm_reduce_long_kernel, dim3((unsigned)m->n_long), dim3(kBlock), 0, s, m->n_long,
+            hipLaunchKernelGGL(spmm_reduce_long_kernel, dim3((unsigned)m->n_long), dim3(D <= 64 ? kBlock / 2 : kBlock), 0, s, m->n_long,
                                m->d_long_row, m->d_long_slot_ptr, partial, (int64_t)D, D, d_Y, (int)y_dt, ldy, win_path,
                                m->win_h, tile_mask, y_vec);
         }
