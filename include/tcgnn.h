@@ -265,6 +265,17 @@ TCG_API int tcg_row_rnorm(int64_t n, const void *d_X, tcg_dtype x_dt, int32_t D,
                   float *d_out, void *stream);
 
 /*
+ * The way back through the row normalisation xn[i] = d_rnorm[i] * X[i] of the scaled-cosine scores (the attention
+ * layer of the paper's second benchmark model, evaluation section): with d_G the gradient with respect to xn,
+ *   d_dX[i] += scale * d_rnorm[i] * (d_G[i] - xn[i] * <d_G[i], xn[i]>)        for the n rows,
+ * which is scale times the derivative of x / |x| applied to d_G[i] when d_rnorm[i] = 1 / |X[i]| (tcg_row_rnorm);
+ * for a row clamped by eps there the second term fades with xn[i].  d_G and d_dX are fp32, row-major with leading
+ * dimensions ldg, ldd >= D; d_dX is accumulated into and must not overlap d_G.  Errors: TCG_EINVAL.
+ */
+TCG_API int tcg_row_unit_grad(int64_t n, const void *d_X, tcg_dtype x_dt, int32_t D, int64_t ldx, const float *d_rnorm,
+                      float scale, const float *d_G, int64_t ldg, float *d_dX, int64_t ldd, void *stream);
+
+/*
  * Gradient of tcg_row_softmax:  d_dv[e] = d_p[e] * (d_dp[e] - sum over the row of d_p * d_dp), where d_p is
  * the softmax output and d_dp the gradient with respect to it.  In-place (d_dv == d_dp) is allowed.
  */

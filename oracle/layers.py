@@ -132,6 +132,20 @@ def sddmm_grads(row_ptr, col_idx, X, ds):
     return S[rows, col_idx], dX
 
 
+def row_unit_grad(X, G, scale=1.0, eps=1e-12):
+    """The way back through the row normalisation xn_i = x_i / max(|x_i|, eps): for the gradient G with respect
+    to xn, returns scale * r_i (G_i - xn_i <G_i, xn_i>) with r_i = 1 / max(|x_i|, eps), row by row in fp64 --
+    the derivative of x / |x| applied to G_i wherever |x_i| >= eps."""
+    X = np.asarray(X, dtype=np.float64)
+    G = np.asarray(G, dtype=np.float64)
+    out = np.zeros_like(X)
+    for i in range(X.shape[0]):
+        r = 1.0 / max(float(np.sqrt(np.dot(X[i], X[i]))), eps)
+        xn = r * X[i]
+        out[i] = scale * r * (G[i] - xn * np.dot(G[i], xn))
+    return out
+
+
 def gcn_model(row_ptr, col_idx, edge_values, X, params, dOut):
     """Two-layer GCN of the paper's evaluation: log_softmax(A_w relu(A_w X W1^T + b1) W2^T + b2).
     params = (W1, b1, W2, b2); returns the output and the parameter gradients for upstream dOut."""

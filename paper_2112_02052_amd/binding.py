@@ -17,7 +17,7 @@ EXPORTED = ["tcg_sgt_build", "tcg_sgt_sizes", "tcg_sgt_export", "tcg_sgt_set_pol
             "tcg_strerror", "tcg_release_cached_memory", "tcg_sddmm_pq", "tcg_row_softmax_backward",
             "tcg_csr_transpose", "tcg_edge_gather", "tcg_attention", "tcg_reorder_rows", "tcg_csr_permute",
             "tcg_sgt_reserve", "tcg_spmm_noalloc", "tcg_sgt_tile_stats", "tcg_attention_cos", "tcg_row_rnorm",
-            "tcg_sgt_build_clustered"]
+            "tcg_sgt_build_clustered", "tcg_row_unit_grad"]
 
 _DTYPES = {torch.float32: TCG_F32, torch.bfloat16: TCG_BF16, torch.float16: TCG_F16}
 
@@ -85,6 +85,9 @@ def load_library():
     lib.tcg_attention_cos.restype = ctypes.c_int
     lib.tcg_attention_cos.argtypes = [_vp, _vp, ctypes.c_int, ctypes.c_int32, ctypes.c_int64, _vp, ctypes.c_float, _vp, _vp,
                                       ctypes.c_int, ctypes.c_int64, _vp]
+    lib.tcg_row_unit_grad.restype = ctypes.c_int
+    lib.tcg_row_unit_grad.argtypes = [ctypes.c_int64, _vp, ctypes.c_int, ctypes.c_int32, ctypes.c_int64, _vp, ctypes.c_float,
+                                      _vp, ctypes.c_int64, _vp, ctypes.c_int64, _vp]
     lib.tcg_row_rnorm.restype = ctypes.c_int
     lib.tcg_row_rnorm.argtypes = [ctypes.c_int64, _vp, ctypes.c_int, ctypes.c_int32, ctypes.c_int64, ctypes.c_float, _vp, _vp]
     lib.tcg_sgt_build_clustered.restype = ctypes.c_int
@@ -374,6 +377,23 @@ def row_rnorm(X, eps=1e-12, out=None):
     _check(load_library().tcg_row_rnorm(X.shape[0], _ptr(X), _DTYPES[X.dtype], X.shape[1], X.stride(0), float(eps), _ptr(out),
                                         _stream()))
     return out
+
+
+def row_unit_grad(X, rnorm, G, dX, scale=1.0):
+    """tcg_row_unit_grad: dX[i] += scale * rnorm[i] * (G[i] - xn[i] <G[i], xn[i]>) with xn = rnorm * X; returns dX."""
+    _need_cuda(X, rnorm, G, dX)
+    if X.dim() != 2 or X.dtype not in _DTYPES or X.stride(1) != 1:
+        raise ValueError("X must be a 2-D fp32/bf16/fp16 tensor with unit stride along features")
+    n, D = X.shape
+    for t in (G, dX):
+        if t.dtype != torch.float32 or t.shape != X.shape or t.stride(1) != 1:
+            raise ValueError("G and dX must be fp32 tensors of X's shape with unit stride along features")
+    if rnorm.dtype != torch.float32 or rnorm.numel() != n or not rnorm.is_contiguous():
+        raise ValueError("rnorm must be a contiguous fp32 tensor with one value per row")
+    _check(load_library().tcg_row_unit_grad(n, _ptr(X), _DTYPES[X.dtype], D, X.stride(0) if n > 1 else max(D, X.stride(0)),
+                                            _ptr(rnorm), float(scale), _ptr(G), G.stride(0) if n > 1 else max(D, G.stride(0)),
+                                            _ptr(dX), dX.stride(0) if n > 1 else max(D, dX.stride(0)), _stream()))
+    return dX
 
 
 def attention_cos(meta, X, rnorm, beta, Y=None, scores=None, y_dtype=torch.float32):

@@ -252,6 +252,15 @@ int tcg_row_rnorm(int64_t n, const void *d_X, tcg_dtype x_dt, int32_t D, int64_t
     return row_rnorm_impl(n, d_X, x_dt, D, ldx, eps, d_out, static_cast<hipStream_t>(stream));
 }
 
+int tcg_row_unit_grad(int64_t n, const void *d_X, tcg_dtype x_dt, int32_t D, int64_t ldx, const float *d_rnorm,
+                      float scale, const float *d_G, int64_t ldg, float *d_dX, int64_t ldd, void *stream)
+{
+    if (n < 0 || D < 1 || ldx < D || ldg < D || ldd < D || !dtype_ok(x_dt)) return TCG_EINVAL;
+    if (n > 0 && (!d_X || !d_rnorm || !d_G || !d_dX)) return TCG_EINVAL;
+    if (reinterpret_cast<uintptr_t>(d_X) % dtype_size(x_dt)) return TCG_EINVAL;
+    return row_unit_grad_impl(n, d_X, x_dt, D, ldx, d_rnorm, scale, d_G, ldg, d_dX, ldd, static_cast<hipStream_t>(stream));
+}
+
 int tcg_row_softmax_backward(const tcg_meta *meta, const float *d_p, const float *d_dp, float *d_dv, void *stream)
 {
     if (!meta) return TCG_EINVAL;

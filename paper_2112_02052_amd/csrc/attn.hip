@@ -326,6 +326,35 @@ int row_rnorm_impl(int64_t n, const void *d_X, tcg_dtype x_dt, int32_t D, int64_
     return launch_status("row_rnorm_kernel");
 }
 
+// dX[i] += scale * r_i * (G[i] - xn_i <G[i], xn_i>), xn_i = r_i x_i: 16 lanes per row, the row's dot product first.
+__global__ __launch_bounds__(256) void row_unit_grad_kernel(int64_t n, const void *__restrict__ X, int x_dt, int32_t D,
+                                                            int64_t ldx, const float *__restrict__ rnorm, float scale,
+                                                            const float *__restrict__ G, int64_t ldg,
+                                                            float *__restrict__ dX, int64_t ldd)
+{
+    const int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) / 16;
+    const int gl = threadIdx.x % 16;
+    float dot = 0.f;
+    if (i < n)
+        for (int32_t d = gl; d < D; d += 16) dot = fmaf(G[i * ldg + d], load_elem(X, i * ldx + d, x_dt), dot);
+#pragma unroll
+    for (int off = 1; off < 16; off <<= 1) dot += __shfl_xor(dot, off, kWave);
+    if (i >= n) return;
+    const float r = rnorm[i];
+    const float back = r * r * dot;                      // <G, xn> r: the factor of x in xn <G, xn>
+    for (int32_t d = gl; d < D; d += 16)
+        dX[i * ldd + d] += scale * r * (G[i * ldg + d] - back * load_elem(X, i * ldx + d, x_dt));
+}
+
+int row_unit_grad_impl(int64_t n, const void *d_X, tcg_dtype x_dt, int32_t D, int64_t ldx, const float *d_rnorm,
+                       float scale, const float *d_G, int64_t ldg, float *d_dX, int64_t ldd, hipStream_t s)
+{
+    if (n == 0) return TCG_OK;
+    hipLaunchKernelGGL(row_unit_grad_kernel, dim3((unsigned)ceil_div(n * 16, 256)), dim3(256), 0, s, n, d_X, (int)x_dt, D,
+                       ldx, d_rnorm, scale, d_G, ldg, d_dX, ldd);
+    return launch_status("row_unit_grad_kernel");
+}
+
 int attention_impl(tcg_meta *m, const void *d_X, tcg_dtype x_dt, int32_t D, int64_t ldx, const float *d_rnorm, float beta,
                    float *d_scores, void *d_Y, tcg_dtype y_dt, int64_t ldy, hipStream_t s)
 {

@@ -201,6 +201,8 @@ int attention_impl(tcg_meta *m, const void *d_X, tcg_dtype x_dt, int32_t D, int6
                    float *d_scores, void *d_Y, tcg_dtype y_dt, int64_t ldy, hipStream_t s);
 int row_rnorm_impl(int64_t n, const void *d_X, tcg_dtype x_dt, int32_t D, int64_t ldx, float eps, float *d_out,
                    hipStream_t s);
+int row_unit_grad_impl(int64_t n, const void *d_X, tcg_dtype x_dt, int32_t D, int64_t ldx, const float *d_rnorm,
+                       float scale, const float *d_G, int64_t ldg, float *d_dX, int64_t ldd, hipStream_t s);
 
 // backward.hip
 int row_softmax_backward_impl(const tcg_meta *m, const float *d_p, const float *d_dp, float *d_dv, hipStream_t s);

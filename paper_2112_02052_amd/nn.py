@@ -10,7 +10,9 @@ Gradients (A is the n_rows x n_cols pattern, e an edge (i, j), w its value):
     s_e = <X_i, X_j>      dX = (ds . A) X + (ds . A)^T X
     p = row_softmax(s)    ds_e = p_e (dp_e - sum_{e' in row} p_e' dp_e')
 The transposed products use a second SGT plan built on the transposed pattern; the permutation that the
-transposition returns carries edge values from one edge order to the other.
+transposition returns carries edge values from one edge order to the other.  When the pattern is symmetric
+(every undirected graph) the transposed pattern is the pattern itself: no second plan is built, and the two
+products of a score gradient, (ds . A) X + (ds . A)^T X, become one with the edge values ds_ij + ds_ji.
 """
 import torch
 
@@ -28,25 +30,43 @@ class TiledGraph:
         self.meta = _b.sgt_build(self.row_ptr, self.col_idx, window_h, tile_w, n_cols=n_cols, validate=validate)
         self.n_rows, self.n_cols, self.nnz = self.meta.n_rows, self.meta.n_cols, self.meta.nnz
         self._t = None
+        self.symmetric = False          # known once transposed() has run
 
     def transposed(self):
-        """(plan of A^T, perm) with edge k of A^T being edge perm[k] of A."""
+        """(plan of A^T, perm) with edge k of A^T being edge perm[k] of A.  For a symmetric pattern the plan is
+        the graph's own (self.symmetric is set) and perm pairs every edge with its reverse."""
         if self._t is None:
             rpt, cit, perm = _b.csr_transpose(self.row_ptr, self.col_idx, n_cols=self.n_cols)
-            meta_t = _b.sgt_build(rpt, cit, self.window_h, self.tile_w, n_cols=self.n_rows, validate=False)
+            self.symmetric = bool(self.n_rows == self.n_cols and torch.equal(rpt, self.row_ptr)
+                                  and torch.equal(cit, self.col_idx))
+            if self.symmetric:
+                meta_t = self.meta
+            else:
+                meta_t = _b.sgt_build(rpt, cit, self.window_h, self.tile_w, n_cols=self.n_rows, validate=False)
             self._t = (meta_t, perm)
         return self._t
 
+    def both_sides(self, X, g):
+        """(g . A) X + (g . A)^T X for edge values g: the gradient of a score s_e = <X_i, X_j> with respect to X."""
+        meta_t, perm = self.transposed()
+        g_t = _b.edge_gather(perm, g)
+        if self.symmetric:
+            return _b.spmm(self.meta, X, g_t.add_(g))
+        out = _b.spmm(self.meta, X, g)
+        out += _b.spmm(meta_t, X, g_t)
+        return out
+
     def set_policy(self, policy, min_reuse=0.0):
         _b.sgt_set_policy(self.meta, policy, min_reuse)
-        if self._t is not None:
+        if self._t is not None and self._t[0] is not self.meta:
             _b.sgt_set_policy(self._t[0], policy, min_reuse)
 
     def free(self):
-        self.meta.free()
         if self._t is not None:
-            self._t[0].free()
+            if self._t[0] is not self.meta:
+                self._t[0].free()
             self._t = None
+        self.meta.free()
 
 
 def _f32c(t):
@@ -86,11 +106,7 @@ class _SDDMM(torch.autograd.Function):
     def backward(ctx, ds):
         graph = ctx.graph
         (X,) = ctx.saved_tensors
-        meta_t, perm = graph.transposed()
-        ds = _f32c(ds)
-        Xc = X.contiguous()
-        dX = _b.spmm(graph.meta, Xc, ds)
-        dX += _b.spmm(meta_t, Xc, _b.edge_gather(perm, ds))
+        dX = graph.both_sides(X.contiguous(), _f32c(ds))
         return None, dX.to(X.dtype)
 
 
@@ -130,8 +146,7 @@ class _SelfAttention(torch.autograd.Function):
         dp = _b.sddmm_pq(graph.meta, dY, Xc)
         ds = _b.row_softmax_backward(graph.meta, p, dp)
         dX = _b.spmm(meta_t, dY, _b.edge_gather(perm, p))          # through the aggregated values
-        dX += _b.spmm(graph.meta, Xc, ds)                          # through the row side of the scores
-        dX += _b.spmm(meta_t, Xc, _b.edge_gather(perm, ds))        # through the neighbour side of the scores
+        dX += graph.both_sides(Xc, ds)                             # through both sides of the scores
         return None, dX.to(Xc.dtype)
 
 
@@ -139,9 +154,10 @@ class _CosAttention(torch.autograd.Function):
     """Y_i = sum_e softmax_i(beta cos(x_i, x_j))_e x_j -- the AGNN propagation -- through the fused kernel
     forward (inverse row norms from one small kernel, X gathered once per edge) and the library's building
     blocks backward.  With r = 1 / max(|x|, eps), xn = r x, c_e = <xn_i, xn_j>, p = row softmax of beta c:
-        dp = sddmm_pq(dY, X),  ds = row_softmax_backward(p, dp),  dbeta = sum_e ds_e c_e,  dc = beta ds
-        dXn = (dc . A) Xn + (dc . A)^T Xn,   dX = (p . A)^T dY + r (dXn - xn <dXn, xn>)
-    (for a row shorter than eps the projection term vanishes with xn, as in the clamped normalisation)."""
+        dp = sddmm_pq(dY, X),  ds = row_softmax_backward(p, dp),  dbeta = sum_e ds_e c_e,
+        dXn = (ds . A) Xn + (ds . A)^T Xn,   dX = (p . A)^T dY + beta r (dXn - xn <dXn, xn>)
+    (dc = beta ds, and everything after it is linear in dc, so beta joins r in the last step; for a row shorter than
+    eps the projection term vanishes with xn, as in the clamped normalisation)."""
 
     EPS = 1e-12
 
@@ -150,7 +166,8 @@ class _CosAttention(torch.autograd.Function):
         Xc = _f32c(X) if X.dtype == torch.float32 else X.contiguous()
         r = _b.row_rnorm(Xc, _CosAttention.EPS)
         c = torch.empty(graph.nnz, dtype=torch.float32, device=X.device)
-        Y = _b.attention_cos(graph.meta, Xc, r, float(beta), scores=c)
+        ctx.beta_value = float(beta)          # read once: the kernels take it as a plain number
+        Y = _b.attention_cos(graph.meta, Xc, r, ctx.beta_value, scores=c)
         ctx.graph = graph
         ctx.save_for_backward(Xc, r, c, beta)
         return Y
@@ -164,16 +181,13 @@ class _CosAttention(torch.autograd.Function):
         p = _b.row_softmax(graph.meta, c * beta)
         dp = _b.sddmm_pq(graph.meta, dY, Xc)
         ds = _b.row_softmax_backward(graph.meta, p, dp)
-        dbeta = (ds * c).sum() if ctx.needs_input_grad[2] else None
+        dbeta = torch.dot(ds, c) if ctx.needs_input_grad[2] else None
         dX = None
         if ctx.needs_input_grad[1]:
-            dc = ds * beta
             Xn = (Xc.to(torch.float32) * r[:, None]).to(Xc.dtype)
-            dXn = _b.spmm(graph.meta, Xn, dc)
-            dXn += _b.spmm(meta_t, Xn, _b.edge_gather(perm, dc))
-            Xn32 = Xn.to(torch.float32)
+            dXn = graph.both_sides(Xn, ds)
             dX = _b.spmm(meta_t, dY, _b.edge_gather(perm, p))
-            dX += (dXn - Xn32 * (dXn * Xn32).sum(dim=1, keepdim=True)) * r[:, None]
+            _b.row_unit_grad(Xc, r, dXn, dX, scale=ctx.beta_value)     # dX += beta r (dXn - xn <dXn, xn>)
             dX = dX.to(Xc.dtype)
         return None, dX, dbeta
 

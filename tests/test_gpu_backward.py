@@ -201,3 +201,28 @@ def test_cosine_attention_matches_the_chain_on_normalised_rows(x_dtype):
     assert norm_err(cs.cpu().numpy(), c_ref) <= TOL_F32
     assert norm_err(Y.cpu().numpy(), Y_ref) <= 1e-4            # the chain's end-to-end bound (exp of an fp32 score)
     meta.free()
+
+
+@pytest.mark.parametrize("x_dtype,D", [("f32", 32), ("f32", 50), ("bf16", 64), ("f32", 3)])
+def test_row_unit_grad(x_dtype, D):
+    """tcg_row_unit_grad against the oracle, accumulated into a non-zero dX, with a zero row (clamped norm)."""
+    import oracle.layers as L
+    rng = np.random.default_rng(5)
+    n = 1000
+    X = rng.standard_normal((n, D)).astype(np.float32)
+    X[17] = 0.0
+    if x_dtype == "bf16":
+        X = W.round_to_bf16(X)
+    G = rng.standard_normal((n, D)).astype(np.float32)
+    base = rng.standard_normal((n, D)).astype(np.float32)
+    Xd = upload_x(X, x_dtype)
+    r = tcg.row_rnorm(Xd)
+    dX = torch.from_numpy(base.copy()).to(dev())
+    tcg.row_unit_grad(Xd, r, torch.from_numpy(G).to(dev()), dX, scale=0.7)
+    torch.cuda.synchronize()
+    ref = base.astype(np.float64) + L.row_unit_grad(X, G, scale=0.7)
+    got = dX.cpu().numpy()
+    keep = np.arange(n) != 17
+    assert norm_err(got[keep], ref[keep]) <= TOL_F32
+    assert np.allclose(got[17], ref[17], rtol=1e-5)          # the clamped row: G / eps, far above the others
+

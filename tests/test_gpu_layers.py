@@ -155,6 +155,41 @@ def test_agnn_conv(cfg3):
     assert abs(layer.beta.grad.item() - dbr) <= TOL_MODEL * max(1.0, abs(dbr))   # a sum over all edges
 
 
+def test_score_gradients_on_symmetric_and_asymmetric_patterns(cfg3):
+    """The gradient of the scores with respect to X, (g . A) X + (g . A)^T X: one product with g_ij + g_ji on a
+    symmetric pattern (no second plan is built), two products and the transposed plan otherwise."""
+    g, graph, X = cfg3
+    graph.transposed()
+    assert graph.symmetric and graph.transposed()[0] is graph.meta
+    ga = asymmetric_graph(400, 400, 6, max_deg=30)
+    rp, ci = upload_csr(ga)
+    sq = tnn.TiledGraph(rp, ci)
+    sq.transposed()
+    assert not sq.symmetric and sq.transposed()[0] is not sq.meta
+    rng = np.random.default_rng(7)
+    Xa = f32(rng.standard_normal((400, 32))) * np.float32(0.3)
+    ds = f32(rng.standard_normal(ga.nnz))
+    Xd = t32(Xa, True)
+    tnn.sddmm(sq, Xd).backward(t32(ds))
+    check("asymmetric sddmm dX", Xd.grad, L.sddmm_grads(ga.row_ptr, ga.col_idx, Xa, ds)[1], TOL_LAYER)
+    dH = f32(rng.standard_normal(Xa.shape))
+    Hr, Pr, dXr = L.self_attention(ga.row_ptr, ga.col_idx, Xa, dH)
+    Xd = t32(Xa, True)
+    H = tnn.self_attention(sq, Xd)
+    H.backward(t32(dH))
+    check("asymmetric attention H", H, Hr, TOL_LAYER)
+    check("asymmetric attention dX", Xd.grad, dXr, TOL_LAYER)
+    layer = tnn.AGNNConv(init_beta=0.8).to(dev())
+    Xd = t32(Xa, True)
+    H = layer(Xd, sq)
+    H.backward(t32(dH))
+    Hr, Pr, dXr, dbr = L.agnn_conv(ga.row_ptr, ga.col_idx, Xa, 0.8, dH)
+    check("asymmetric agnn H", H, Hr, TOL_LAYER)
+    check("asymmetric agnn dX", Xd.grad, dXr, TOL_LAYER)
+    assert abs(layer.beta.grad.item() - dbr) <= TOL_MODEL * max(1.0, abs(dbr))
+    sq.free()
+
+
 def test_gcn_model_training_step():
     # the paper's GCN setting: two layers, 16 hidden features
     c = W.make_config(2, n=1500, d=64)

@@ -164,6 +164,33 @@ def test_model_gradients_by_finite_differences():
     np.testing.assert_allclose(grads[4], central(fb, np.array([betas[0]]))[0], rtol=1e-5)
 
 
+def test_row_unit_grad_against_reverse_mode_and_closed_forms():
+    """Pins of oracle.layers.row_unit_grad: the vector-Jacobian product of torch's own row normalisation, its
+    orthogonality to the row (the derivative of a unit vector has no component along it), zero for a gradient
+    along the row, plain scaling for a gradient across it, and central finite differences of x -> x / |x|."""
+    import torch
+    rng = np.random.default_rng(0)
+    X = rng.standard_normal((7, 5))
+    G = rng.standard_normal((7, 5))
+    got = L.row_unit_grad(X, G, scale=1.7)
+    Xt = torch.tensor(X, requires_grad=True)
+    torch.nn.functional.normalize(Xt, p=2.0, dim=1).backward(torch.tensor(G))
+    assert np.allclose(got, 1.7 * Xt.grad.numpy(), rtol=1e-12, atol=1e-14)
+    assert np.abs((got * X).sum(axis=1)).max() < 1e-12
+    assert np.abs(L.row_unit_grad(X, 3.0 * X)).max() < 1e-12
+    x = np.array([[3.0, 4.0, 0.0]])
+    assert np.allclose(L.row_unit_grad(x, np.array([[0.0, 0.0, 2.0]])), [[0.0, 0.0, 0.4]])        # across: G / |x|
+    h = 1e-6
+    fd = np.zeros((1, 3))
+    g = np.array([[0.3, -1.1, 0.7]])
+    for d in range(3):
+        e = np.zeros((1, 3))
+        e[0, d] = h
+        up, dn = (x + e) / np.linalg.norm(x + e), (x - e) / np.linalg.norm(x - e)
+        fd[0, d] = ((up - dn) / (2 * h) * g).sum()
+    assert np.allclose(L.row_unit_grad(x, g), fd, atol=1e-8)
+
+
 def test_isolated_nodes_and_zero_rows():
     # node 2 has no entries: its output row is zero, and in a second propagation its zero feature row
     # must neither produce NaN nor receive a gradient through the normalisation.
